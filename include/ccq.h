@@ -1,0 +1,159 @@
+/*
+ * libccq -- fused dequantize-and-multiply for Convolutional Code Quantization
+ * (CCQ, arXiv 2507.07145) on AMD MI355X (gfx950).
+ *
+ * The library computes  y = x * W_dq^T  where W_dq is never materialised in
+ * memory: the packed convolutional-code bitstream is streamed from HBM, the
+ * overlapping L-bit states are cut out of each code with bit shifts (Sec. 3.1
+ * "Bitshift Decoding", Table 1), mapped to values by the linear rule
+ * (state - zp) * scale (Alg. 2 / Alg. 3, last line of the loop) and contracted
+ * against bf16 activations with fp32 accumulation.  No codebook is stored or
+ * looked up.
+ *
+ * Supported code configurations (Table 1):
+ *   narrow  (L=6,N=4,S=3) with Code Cluster: one byte per 4 weights (2.0 bpw);
+ *           the byte q is first expanded to the 15-bit code
+ *           c = round(q * code_alpha[n] + code_beta[n])   (Alg. 3, Eq. 1)
+ *   wide    (L=4,N=3,S=2): 22 bytes per 64 weights (2.75 bpw), Alg. 2.
+ * A weight matrix uses the narrow format, the wide format, or a per-group mix
+ * (group_fmt), all rows sharing the same map.  Group size is 64 along K and
+ * scales are fp16, one per (row, group).
+ *
+ * Conventions
+ *   - Every pointer is marked HOST or DEVICE.  The caller owns all buffers; the
+ *     library never allocates, frees or synchronises.  DEVICE pointers must be
+ *     16-byte aligned.
+ *   - ccq_gemm / ccq_grouped_gemm enqueue work on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and return immediately.
+ *   - Return value: CCQ_OK or a negative ccq_status.  On error nothing has
+ *     been enqueued.
+ *   - "Canonical" order is the paper's: row n of W_q is the concatenation over
+ *     groups (k order) of the group's codes, code j covering weights N*j..N*j+N-1
+ *     of the group (Alg. 2/3: q_w = W_q[idx / p_w]); the first state of a code
+ *     sits in its most significant bits (Sec. 3.1, the 00->01->10 = 0010
+ *     example).  The kernels read a permuted "device" order of the same bytes,
+ *     produced by the ccq_pack_* host routines below; it stores exactly as many
+ *     code bytes as the canonical order.
+ */
+#ifndef CCQ_H
+#define CCQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CCQ_OK = 0,
+  CCQ_ERR_NULL = -1,        /* a required pointer is NULL                    */
+  CCQ_ERR_BAD_PARAM = -2,   /* inconsistent sizes / values                   */
+  CCQ_ERR_UNSUPPORTED = -3, /* valid CCQ, but not built into the kernels     */
+  CCQ_ERR_ALIGN = -4,       /* DEVICE pointer or leading dim not aligned     */
+  CCQ_ERR_WORKSPACE = -5,   /* workspace missing or too small                */
+  CCQ_ERR_ROUTING = -6,     /* expert offsets not monotone / out of range    */
+  CCQ_ERR_HIP = -7          /* a HIP runtime call failed                     */
+} ccq_status;
+
+/* A convolutional-code configuration, Sec. 3.1: L bits per state, N states per
+ * code, S transition bits between adjacent states; T = L + (N-1)*S code bits. */
+typedef struct {
+  int32_t L, N, S;
+  int32_t code_cluster; /* 1: the stored code is the 8-bit clustered value (Sec. 3.3) */
+  float zp;             /* weight zero-point of Alg. 2/3; a multiple of 0.5  */
+} ccq_code;
+
+/* One quantized weight matrix W[N][K] (N output channels, K input channels). */
+typedef struct {
+  int32_t K, N;
+  int32_t group;            /* weights per scale along K; must be 64         */
+  int32_t n_formats;        /* 1 or 2                                        */
+  ccq_code fmt[2];          /* fmt[0] = narrow (6,4,3)+cluster or wide; with 2 formats fmt[0] narrow, fmt[1] wide */
+  const uint8_t *group_fmt; /* HOST, K/group entries in {0,1} selecting fmt[] per group; NULL = all fmt[0] */
+  const void *codes;        /* DEVICE, packed codes in device order (ccq_pack_codes)   */
+  const void *scales;       /* DEVICE, fp16 group scales in device order (ccq_pack_scales) */
+  const float *code_alpha;  /* DEVICE, fp32[N]: Code Cluster scale s_code, >= 0        */
+  const float *code_beta;   /* DEVICE, fp32[N]: Code Cluster zero-point zp_code, an
+                               integer value with 255*alpha + beta < 2^15 (the
+                               kernels rely on it; device data is not checked)         */
+  const void *meta;         /* DEVICE, group map in device order (ccq_pack_meta); may be NULL when group_fmt is NULL */
+  int32_t scale_mode;       /* 0 = fp16 group scales (the only mode built)   */
+} ccq_weight;
+
+/* Sizes and accounting of the device layout (Eq. 5 for the bpw fields). */
+typedef struct {
+  int64_t code_bytes;       /* bytes of the packed code stream (= canonical bytes)      */
+  int64_t scale_bytes;      /* bytes of the fp16 scale array                             */
+  int64_t meta_bytes;       /* bytes ccq_pack_meta writes                                */
+  int64_t workspace_bytes;  /* workspace ccq_gemm may need for M <= M_max                */
+  int64_t row_tile_bytes;   /* code bytes of one tile of 16 output rows (all of K)       */
+  int32_t bytes_per_group[2]; /* code bytes per 64-weight group, per format (16 / 22)    */
+  int32_t groups[2];        /* number of groups along K in each format                   */
+  int32_t align;            /* required alignment of DEVICE pointers (16)                */
+  double code_bpw;          /* code bits per weight: exactly 2.0 narrow, 2.75 wide       */
+  double total_bpw;         /* + fp16 scales + per-row alpha/beta                        */
+} ccq_info;
+
+/* Validate a descriptor (DEVICE pointers may be NULL here) and report the
+ * layout sizes, the bits-per-weight accounting of Eq. 5 and the workspace
+ * ccq_gemm needs for up to M_max activation rows.  Pure host code. */
+int ccq_pack_info(const ccq_weight *w, int32_t M_max, ccq_info *out);
+
+/* Host-side permutations from canonical order to device order.
+ *   ccq_pack_codes : canonical_codes HOST uint8 [N][row bytes]  -> out HOST [code_bytes]
+ *   ccq_pack_scales: canonical fp16 bits HOST [N][K/64]         -> out HOST [scale_bytes/2]
+ *   ccq_pack_meta  : group_fmt                                  -> out HOST [meta_bytes]
+ * Byte values are copied, never altered.  The caller uploads the results. */
+int ccq_pack_codes(const ccq_weight *w, const uint8_t *canonical_codes, void *out);
+int ccq_pack_scales(const ccq_weight *w, const uint16_t *canonical_scales, void *out);
+int ccq_pack_meta(const ccq_weight *w, void *out);
+
+/* y[m][n] = sum_k x[m][k] * W_dq[n][k]   (the W2A16 GEMV / GEMM of the
+ * "Inference Performance" section; Alg. 2/3 fused into the contraction).
+ *   x DEVICE bf16 [M][ldx], y DEVICE bf16 [M][ldy] (round to nearest even),
+ *   fp32 accumulation.  ldx, ldy in elements, multiples of 8.
+ *   M = 0 is a no-op.  workspace DEVICE, workspace_bytes >= the value
+ *   ccq_pack_info reports for M_max >= M (may be NULL if that value is 0). */
+int ccq_gemm(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void *y, int64_t ldy,
+             void *workspace, int64_t workspace_bytes, void *hip_stream);
+
+/* Explicit launch shape for ccq_gemm_ex (0 = let the library choose).  */
+typedef struct {
+  int32_t rows_per_wave_tiles; /* 16-row tiles each wavefront owns: 1 or 2      */
+  int32_t waves_rows;          /* wavefronts of a workgroup along the rows       */
+  int32_t waves_k;             /* wavefronts of a workgroup along K (reduced in LDS) */
+  int32_t splits_k;            /* workgroups along K (reduced through workspace) */
+} ccq_launch;
+
+/* ccq_gemm with a caller-chosen decomposition (tuning and tests). */
+int ccq_gemm_ex(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void *y, int64_t ldy,
+                void *workspace, int64_t workspace_bytes, void *hip_stream, const ccq_launch *launch);
+
+/* Grouped GEMM for mixture-of-experts layers (the Grouped-GEMM operator of the
+ * "Inference Performance" section).  All E experts share one shape and format:
+ * `w0` describes expert 0 and expert e's DEVICE arrays start
+ * e * {codes,scales,ab}_stride bytes after expert 0's.
+ *   Output row p in [expert_offsets[e], expert_offsets[e+1]) is
+ *       y[p][:] = x[sorted_rows[p]][:] * W_dq(e)^T.
+ *   x DEVICE bf16 [T][ldx]; sorted_rows DEVICE int32 [P], values in [0,T);
+ *   expert_offsets_dev DEVICE int32 [E+1] with [0] = 0, monotone, [E] = P;
+ *   expert_offsets_host HOST copy of the same, or NULL: when given it is
+ *   validated (CCQ_ERR_ROUTING) -- device data is never read back;
+ *   y DEVICE bf16 [P][ldy].  An expert with no rows writes nothing.
+ *   The top-k combine and any activation function stay with the caller. */
+int ccq_grouped_gemm(const ccq_weight *w0, int32_t E, int64_t codes_stride, int64_t scales_stride,
+                     int64_t ab_stride, const void *x, int32_t T, int64_t ldx,
+                     const int32_t *sorted_rows, int32_t P, const int32_t *expert_offsets_dev,
+                     const int32_t *expert_offsets_host, void *y, int64_t ldy, void *workspace,
+                     int64_t workspace_bytes, void *hip_stream);
+
+/* Workspace bytes ccq_grouped_gemm needs for P output rows. */
+int64_t ccq_grouped_workspace_bytes(const ccq_weight *w0, int32_t E, int32_t P);
+
+/* Human-readable name of a status code. */
+const char *ccq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCQ_H */

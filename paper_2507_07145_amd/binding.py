@@ -1,0 +1,270 @@
+"""Thin ctypes binding of libccq.so (include/ccq.h): argument marshalling only.
+
+Every step of the fused dequantize-and-multiply runs inside the HIP library;
+PyTorch is used for device memory and streams.  The functions carry the names
+of the C entry points (pack_info, pack_codes, pack_scales, pack_meta, gemm,
+gemm_ex, grouped_gemm).  If the library has not been built this module raises
+on first use -- there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libccq.so")
+
+CCQ_OK = 0
+STATUS = {0: "CCQ_OK", -1: "CCQ_ERR_NULL", -2: "CCQ_ERR_BAD_PARAM", -3: "CCQ_ERR_UNSUPPORTED", -4: "CCQ_ERR_ALIGN",
+          -5: "CCQ_ERR_WORKSPACE", -6: "CCQ_ERR_ROUTING", -7: "CCQ_ERR_HIP"}
+
+
+class CcqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where} failed: {STATUS.get(status, status)}")
+        self.status = status
+
+
+class ccq_code(ctypes.Structure):
+    _fields_ = [("L", ctypes.c_int32), ("N", ctypes.c_int32), ("S", ctypes.c_int32), ("code_cluster", ctypes.c_int32),
+                ("zp", ctypes.c_float)]
+
+
+class ccq_weight(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_int32), ("N", ctypes.c_int32), ("group", ctypes.c_int32), ("n_formats", ctypes.c_int32),
+                ("fmt", ccq_code * 2), ("group_fmt", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("code_alpha", ctypes.c_void_p), ("code_beta", ctypes.c_void_p), ("meta", ctypes.c_void_p),
+                ("scale_mode", ctypes.c_int32)]
+
+
+class ccq_info(ctypes.Structure):
+    _fields_ = [("code_bytes", ctypes.c_int64), ("scale_bytes", ctypes.c_int64), ("meta_bytes", ctypes.c_int64),
+                ("workspace_bytes", ctypes.c_int64), ("row_tile_bytes", ctypes.c_int64), ("bytes_per_group", ctypes.c_int32 * 2),
+                ("groups", ctypes.c_int32 * 2), ("align", ctypes.c_int32), ("code_bpw", ctypes.c_double), ("total_bpw", ctypes.c_double)]
+
+
+class ccq_launch(ctypes.Structure):
+    _fields_ = [("rows_per_wave_tiles", ctypes.c_int32), ("waves_rows", ctypes.c_int32), ("waves_k", ctypes.c_int32),
+                ("splits_k", ctypes.c_int32)]
+
+
+# the two code configurations of Table 1 the kernels are built for
+NARROW = ccq_code(6, 4, 3, 1, 32.0)   # (L=6,N=4,S=3) + Code Cluster, 2.0 bpw
+WIDE = ccq_code(4, 3, 2, 0, 8.0)      # (L=4,N=3,S=2), 2.75 bpw
+
+EXPORTS = ["ccq_pack_info", "ccq_pack_codes", "ccq_pack_scales", "ccq_pack_meta", "ccq_gemm", "ccq_gemm_ex",
+           "ccq_grouped_gemm", "ccq_grouped_workspace_bytes", "ccq_status_string"]
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libccq.so; raises if it has not been built (python -m paper_2507_07145_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2507_07145_amd.build` "
+                           "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    wp = ctypes.POINTER(ccq_weight)
+    L.ccq_pack_info.restype = ctypes.c_int
+    L.ccq_pack_info.argtypes = [wp, i32, ctypes.POINTER(ccq_info)]
+    for name in ("ccq_pack_codes", "ccq_pack_scales"):
+        f = getattr(L, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [wp, vp, vp]
+    L.ccq_pack_meta.restype = ctypes.c_int
+    L.ccq_pack_meta.argtypes = [wp, vp]
+    L.ccq_gemm.restype = ctypes.c_int
+    L.ccq_gemm.argtypes = [wp, vp, i32, i64, vp, i64, vp, i64, vp]
+    L.ccq_gemm_ex.restype = ctypes.c_int
+    L.ccq_gemm_ex.argtypes = [wp, vp, i32, i64, vp, i64, vp, i64, vp, ctypes.POINTER(ccq_launch)]
+    L.ccq_grouped_gemm.restype = ctypes.c_int
+    L.ccq_grouped_gemm.argtypes = [wp, i32, i64, i64, i64, vp, i32, i64, vp, i32, vp, vp, vp, i64, vp, i64, vp]
+    L.ccq_grouped_workspace_bytes.restype = i64
+    L.ccq_grouped_workspace_bytes.argtypes = [wp, i32, i32]
+    L.ccq_status_string.restype = ctypes.c_char_p
+    L.ccq_status_string.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != CCQ_OK:
+        raise CcqError(status, where)
+
+
+def _np_ptr(a) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data) if a is not None else ctypes.c_void_p(0)
+
+
+def _t_ptr(t) -> ctypes.c_void_p:
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream_ptr(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def descriptor(K: int, N: int, fmts, group_fmt: np.ndarray | None = None) -> ccq_weight:
+    """A ccq_weight with shape/format fields set and all DEVICE pointers NULL."""
+    w = ccq_weight()
+    w.K, w.N, w.group, w.n_formats, w.scale_mode = K, N, 64, len(fmts), 0
+    for i, f in enumerate(fmts):
+        w.fmt[i] = f
+    w.group_fmt = group_fmt.ctypes.data if group_fmt is not None else None
+    return w
+
+
+def pack_info(w: ccq_weight, M_max: int = 64) -> ccq_info:
+    info = ccq_info()
+    _check(load().ccq_pack_info(ctypes.byref(w), M_max, ctypes.byref(info)), "ccq_pack_info")
+    return info
+
+
+def pack_codes(w: ccq_weight, canonical: np.ndarray) -> np.ndarray:
+    info = pack_info(w, 0)
+    src = np.ascontiguousarray(canonical, dtype=np.uint8)
+    if src.size != info.code_bytes:
+        raise ValueError(f"canonical code stream has {src.size} bytes, layout needs {info.code_bytes}")
+    out = np.empty(info.code_bytes, dtype=np.uint8)
+    _check(load().ccq_pack_codes(ctypes.byref(w), _np_ptr(src), _np_ptr(out)), "ccq_pack_codes")
+    return out
+
+
+def pack_scales(w: ccq_weight, canonical_fp16_bits: np.ndarray) -> np.ndarray:
+    info = pack_info(w, 0)
+    src = np.ascontiguousarray(canonical_fp16_bits, dtype=np.uint16)
+    if src.size * 2 != info.scale_bytes:
+        raise ValueError("scale array size does not match the layout")
+    out = np.empty(src.size, dtype=np.uint16)
+    _check(load().ccq_pack_scales(ctypes.byref(w), _np_ptr(src), _np_ptr(out)), "ccq_pack_scales")
+    return out
+
+
+def pack_meta(w: ccq_weight) -> np.ndarray:
+    info = pack_info(w, 0)
+    out = np.empty(info.meta_bytes // 4, dtype=np.int32)
+    _check(load().ccq_pack_meta(ctypes.byref(w), _np_ptr(out)), "ccq_pack_meta")
+    return out
+
+
+def bf16_tensor(bits: np.ndarray, device) -> torch.Tensor:
+    """uint16 bf16 bit patterns (numpy) -> torch bf16 tensor on `device`."""
+    return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint16).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def bf16_bits(t: torch.Tensor) -> np.ndarray:
+    """torch bf16 tensor -> uint16 bit patterns on the host."""
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class Weight:
+    """Device-resident quantized weights of one matrix, or of E same-shaped experts stacked along a leading axis."""
+
+    def __init__(self):
+        self.desc = None
+        self.info = None
+        self.E = 1
+        self.codes = self.scales = self.alpha = self.beta = self.meta = None
+        self._group_fmt = None
+
+    @classmethod
+    def from_canonical(cls, K, N, fmts, codes, scales_fp16, alpha=None, beta=None, group_fmt=None, device="cuda:0", experts: int | None = None):
+        """Permute canonical (paper order) arrays into device order with the library's pack routines and upload.
+        With `experts` = E the arrays carry a leading expert axis."""
+        self = cls()
+        self._group_fmt = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
+        w = descriptor(K, N, fmts, self._group_fmt)
+        info = pack_info(w, 64)
+        E = 1 if experts is None else int(experts)
+        codes = np.ascontiguousarray(codes, dtype=np.uint8).reshape(E, -1)
+        scales = np.ascontiguousarray(scales_fp16, dtype=np.uint16).reshape(E, -1)
+        pc = np.stack([pack_codes(w, codes[e]) for e in range(E)])
+        ps = np.stack([pack_scales(w, scales[e]) for e in range(E)])
+        self.codes = torch.from_numpy(pc).to(device)
+        self.scales = torch.from_numpy(ps.view(np.int16)).to(device)
+        needs_ab = any(f.code_cluster for f in fmts)
+        if needs_ab:
+            self.alpha = torch.from_numpy(np.ascontiguousarray(alpha, dtype=np.float32).reshape(E, N)).to(device)
+            self.beta = torch.from_numpy(np.ascontiguousarray(beta, dtype=np.float32).reshape(E, N)).to(device)
+        if group_fmt is not None:
+            self.meta = torch.from_numpy(pack_meta(w)).to(device)
+        w.codes, w.scales = self.codes.data_ptr(), self.scales.data_ptr()
+        w.code_alpha = self.alpha.data_ptr() if needs_ab else None
+        w.code_beta = self.beta.data_ptr() if needs_ab else None
+        w.meta = self.meta.data_ptr() if self.meta is not None else None
+        self.desc, self.info, self.E = w, info, E
+        return self
+
+    @property
+    def K(self):
+        return self.desc.K
+
+    @property
+    def N(self):
+        return self.desc.N
+
+    @property
+    def device(self):
+        return self.codes.device
+
+    def strides(self):
+        """(codes, scales, alpha/beta) byte strides between consecutive experts."""
+        return (self.codes.stride(0), self.scales.stride(0) * 2, self.alpha.stride(0) * 4 if self.alpha is not None else 0)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor | None:
+    return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes > 0 else None
+
+
+def gemm(w: Weight, x: torch.Tensor, out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None,
+         launch: ccq_launch | None = None) -> torch.Tensor:
+    """y = x W_dq^T through ccq_gemm (or ccq_gemm_ex when `launch` is given).  x: bf16 [M][K] on the GPU."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1 and x.is_cuda
+    M = x.shape[0]
+    y = out if out is not None else torch.empty((M, w.N), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        need = launch.splits_k * M * w.N * 4 if (launch is not None and launch.splits_k > 1) else pack_info(w.desc, max(M, 1)).workspace_bytes
+        workspace = _workspace(need, x.device)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    L = load()
+    if launch is None:
+        rc = L.ccq_gemm(ctypes.byref(w.desc), _t_ptr(x), M, x.stride(0), _t_ptr(y), y.stride(0), _t_ptr(workspace), ws_bytes, _stream_ptr(stream))
+    else:
+        rc = L.ccq_gemm_ex(ctypes.byref(w.desc), _t_ptr(x), M, x.stride(0), _t_ptr(y), y.stride(0), _t_ptr(workspace), ws_bytes,
+                           _stream_ptr(stream), ctypes.byref(launch))
+    _check(rc, "ccq_gemm")
+    return y
+
+
+def grouped_workspace_bytes(w: Weight, P: int) -> int:
+    return int(load().ccq_grouped_workspace_bytes(ctypes.byref(w.desc), w.E, P))
+
+
+def grouped_gemm(w: Weight, x: torch.Tensor, sorted_rows: torch.Tensor, expert_offsets: torch.Tensor,
+                 expert_offsets_host: np.ndarray | None = None, out: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                 stream=None) -> torch.Tensor:
+    """y[p] = x[sorted_rows[p]] W_dq(e)^T for p in expert e's range, through ccq_grouped_gemm."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1 and x.is_cuda
+    assert sorted_rows.dtype == torch.int32 and expert_offsets.dtype == torch.int32
+    P = sorted_rows.numel()
+    y = out if out is not None else torch.empty((P, w.N), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = _workspace(max(grouped_workspace_bytes(w, P), 0), x.device)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    cs, ss, abs_ = w.strides()
+    host = None
+    if expert_offsets_host is not None:
+        host = np.ascontiguousarray(expert_offsets_host, dtype=np.int32)
+    rc = load().ccq_grouped_gemm(ctypes.byref(w.desc), w.E, cs, ss, abs_, _t_ptr(x), x.shape[0], x.stride(0), _t_ptr(sorted_rows), P,
+                                 _t_ptr(expert_offsets), _np_ptr(host), _t_ptr(y), y.stride(0), _t_ptr(workspace), ws_bytes,
+                                 _stream_ptr(stream))
+    _check(rc, "ccq_grouped_gemm")
+    return y

@@ -1,0 +1,377 @@
+// Host layer of libccq: descriptor validation, layout accounting (Eq. 5 of the
+// CCQ paper), canonical -> device order permutations, argument checks and
+// dispatch to the kernel launchers.  No device code in this file.
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#include "ccq_internal.h"
+
+namespace ccq {
+
+static bool is_narrow(const ccq_code& c) { return c.L == 6 && c.N == 4 && c.S == 3 && c.code_cluster == 1; }
+static bool is_wide(const ccq_code& c) { return c.L == 4 && c.N == 3 && c.S == 2 && c.code_cluster == 0; }
+
+int make_layout(const ccq_weight* w, Layout* out) {
+  if (!w || !out) return CCQ_ERR_NULL;
+  if (w->K <= 0 || w->N <= 0 || w->n_formats < 1 || w->n_formats > 2) return CCQ_ERR_BAD_PARAM;
+  if (w->group != kGroup) return w->group > 0 ? CCQ_ERR_UNSUPPORTED : CCQ_ERR_BAD_PARAM;
+  if (w->K % kGroup != 0) return CCQ_ERR_BAD_PARAM;
+  if (w->scale_mode != 0) return CCQ_ERR_UNSUPPORTED;
+  if (w->n_formats == 1 && w->group_fmt) return CCQ_ERR_BAD_PARAM;
+  Layout L;
+  L.K = w->K;
+  L.N = w->N;
+  L.G = w->K / kGroup;
+  for (int f = 0; f < w->n_formats; ++f) {
+    const ccq_code& c = w->fmt[f];
+    if (c.L < 1 || c.N < 1 || c.S < 1 || c.S > c.L || c.L > 16) return CCQ_ERR_BAD_PARAM;
+    float twice = c.zp * 2.0f;
+    if (!(twice == std::floor(twice)) || c.zp < 0.f || c.zp > 64.f) return CCQ_ERR_BAD_PARAM;
+    if (is_narrow(c)) L.kind_of_fmt[f] = kNarrow;
+    else if (is_wide(c)) L.kind_of_fmt[f] = kWide;
+    else return CCQ_ERR_UNSUPPORTED;
+    L.zp[L.kind_of_fmt[f]] = c.zp;
+  }
+  if (w->n_formats == 2 && L.kind_of_fmt[0] == L.kind_of_fmt[1]) return CCQ_ERR_BAD_PARAM;
+  L.has_map = w->group_fmt != nullptr;
+  if (w->n_formats == 2 && !w->group_fmt) return CCQ_ERR_NULL;
+  for (int g = 0; g < L.G; ++g) {
+    int f = w->group_fmt ? w->group_fmt[g] : 0;
+    if (f < 0 || f >= w->n_formats) return CCQ_ERR_BAD_PARAM;
+    L.groups[L.kind_of_fmt[f]]++;
+  }
+  // whole k-tiles only, and whole row tiles (the kernels do not mask partial tiles)
+  if (L.groups[kNarrow] % kNarrowGroupsPerTile != 0 || L.groups[kWide] % kWideGroupsPerTile != 0) return CCQ_ERR_UNSUPPORTED;
+  if (w->N % kRowsPerTile != 0) return CCQ_ERR_UNSUPPORTED;
+  L.tiles[kNarrow] = L.groups[kNarrow] / kNarrowGroupsPerTile;
+  L.tiles[kWide] = L.groups[kWide] / kWideGroupsPerTile;
+  L.row_tile_bytes = (int64_t)L.tiles[kNarrow] * kNarrowTileBytes + (int64_t)L.tiles[kWide] * kWideTileBytes;
+  L.row_tile_scale_halfs = (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs + (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;
+  L.row_tiles = w->N / kRowsPerTile;
+  if (L.row_tile_bytes * (int64_t)L.row_tiles >= (int64_t)1 << 40) return CCQ_ERR_BAD_PARAM;
+  *out = L;
+  return CCQ_OK;
+}
+
+// ---- launch decomposition ---------------------------------------------------
+
+bool decomp_ok(const Layout& L, const Decomp& d) {
+  (void)L;
+  if (d.RT < 1 || d.RT > 2) return false;
+  if (d.WR < 1 || d.WK < 1 || d.WR * d.WK > 16) return false;
+  if (d.S < 1 || d.S > kMaxSplitsK) return false;
+  return true;
+}
+
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
+  (void)rows_total;
+  Decomp d;
+  const int nt = L.tiles[kNarrow] + L.tiles[kWide];  // k-tiles per row tile
+  const int64_t units = (int64_t)L.row_tiles * experts;  // row tiles over all experts
+  if (M <= 4) {
+    // bandwidth-bound GEMV: many wavefronts, K split inside the workgroup so
+    // that no workspace pass is needed
+    d.RT = 1;
+    const int64_t target_waves = 4096;
+    int ks = (int)std::max<int64_t>(1, std::min<int64_t>(nt, target_waves / std::max<int64_t>(1, units)));
+    if (ks <= 8) { d.WK = ks; d.S = 1; }
+    else { d.WK = 8; d.S = std::min(kMaxSplitsK, ceil_div(ks, 8)); }
+    d.WR = std::max(1, std::min(8 / d.WK, (int)std::min<int64_t>(8, L.row_tiles)));
+    if (units / d.WR >= 8192) d.RT = 2;
+  } else {
+    d.RT = L.row_tiles >= 2 ? 2 : 1;
+    d.WR = (int)std::min<int64_t>(4, std::max(1, L.row_tiles / d.RT));
+    d.WK = 1;
+    int64_t row_blocks = (int64_t)ceil_div(L.row_tiles, d.RT * d.WR) * experts;
+    int s = (int)std::max<int64_t>(1, 512 / std::max<int64_t>(1, row_blocks));
+    s = std::min(s, std::max(1, nt / 2));
+    if (M > 16) s = std::min(s, 2);
+    d.S = std::min(s, kMaxSplitsK);
+  }
+  return d;
+}
+
+}  // namespace ccq
+
+using namespace ccq;
+
+static int64_t dense_workspace_bytes(const Layout& L, int M) {
+  int64_t need = 0;
+  for (int m = 1; m <= M && m <= kMaxSkinnyM; ++m) {
+    Decomp d = choose_decomp(L, m, 1, m);
+    if (d.S > 1) need = std::max(need, (int64_t)d.S * m * L.N * 4);
+  }
+  return need;
+}
+
+extern "C" int ccq_pack_info(const ccq_weight* w, int32_t M_max, ccq_info* out) {
+  if (!w || !out) return CCQ_ERR_NULL;
+  if (M_max < 0) return CCQ_ERR_BAD_PARAM;
+  Layout L;
+  int rc = make_layout(w, &L);
+  if (rc != CCQ_OK) return rc;
+  ccq_info info;
+  std::memset(&info, 0, sizeof(info));
+  info.bytes_per_group[0] = info.bytes_per_group[1] = 0;
+  for (int f = 0; f < w->n_formats; ++f)
+    info.bytes_per_group[f] = L.kind_of_fmt[f] == kNarrow ? kNarrowGroupBytes : kWideGroupBytes;
+  for (int f = 0; f < w->n_formats; ++f) info.groups[f] = L.groups[L.kind_of_fmt[f]];
+  info.row_tile_bytes = L.row_tile_bytes;
+  info.code_bytes = L.row_tile_bytes * L.row_tiles;
+  info.scale_bytes = L.row_tile_scale_halfs * L.row_tiles * 2;
+  info.meta_bytes = (int64_t)L.G * 4;
+  info.align = 16;
+  info.workspace_bytes = dense_workspace_bytes(L, M_max);
+  // Eq. 5: stored code bits per weight; a narrow group holds 64/4 one-byte codes
+  // (g = 0 mod N: scale bits come on top), a wide group ceil(64/3) = 22 one-byte
+  // codes (g = 1 mod N: the spare bits of the last code are part of the count).
+  const double weights = (double)L.N * (double)L.K;
+  info.code_bpw = 8.0 * (double)info.code_bytes / weights;
+  const double ab_bytes = L.groups[kNarrow] > 0 ? 8.0 * (double)L.N : 0.0;
+  info.total_bpw = 8.0 * ((double)info.code_bytes + (double)info.scale_bytes + ab_bytes) / weights;
+  *out = info;
+  return CCQ_OK;
+}
+
+// packed index of every group: narrow groups first (k order), then wide
+static void packed_order(const ccq_weight* w, const Layout& L, std::vector<int>& pos_in_kind, std::vector<int>& kind) {
+  pos_in_kind.resize(L.G);
+  kind.resize(L.G);
+  int cnt[2] = {0, 0};
+  for (int g = 0; g < L.G; ++g) {
+    int k = group_kind(w, L, g);
+    kind[g] = k;
+    pos_in_kind[g] = cnt[k]++;
+  }
+}
+
+extern "C" int ccq_pack_codes(const ccq_weight* w, const uint8_t* src, void* out_v) {
+  if (!w || !src || !out_v) return CCQ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(w, &L);
+  if (rc != CCQ_OK) return rc;
+  uint8_t* out = static_cast<uint8_t*>(out_v);
+  std::vector<int> pos, kind;
+  packed_order(w, L, pos, kind);
+  std::vector<int64_t> goff(L.G);  // canonical byte offset of each group inside a row
+  int64_t row_bytes = 0;
+  for (int g = 0; g < L.G; ++g) {
+    goff[g] = row_bytes;
+    row_bytes += kind[g] == kNarrow ? kNarrowGroupBytes : kWideGroupBytes;
+  }
+  const int64_t wide_base = (int64_t)L.tiles[kNarrow] * kNarrowTileBytes;
+  for (int n = 0; n < L.N; ++n) {
+    const uint8_t* row = src + (int64_t)n * row_bytes;
+    uint8_t* tile_row = out + (int64_t)(n / kRowsPerTile) * L.row_tile_bytes;
+    const int r = n % kRowsPerTile;
+    for (int g = 0; g < L.G; ++g) {
+      const uint8_t* gb = row + goff[g];
+      if (kind[g] == kNarrow) {
+        uint8_t* tile = tile_row + (int64_t)(pos[g] / kNarrowGroupsPerTile) * kNarrowTileBytes;
+        const int j = pos[g] % kNarrowGroupsPerTile;
+        for (int kq = 0; kq < 4; ++kq)
+          for (int b = 0; b < 4; ++b) tile[(kq * 16 + r) * 16 + j * 4 + b] = gb[4 * kq + b];
+      } else {
+        uint8_t* tile = tile_row + wide_base + (int64_t)(pos[g] / kWideGroupsPerTile) * kWideTileBytes;
+        const int j = pos[g] % kWideGroupsPerTile;
+        for (int kq = 0; kq < 4; ++kq)
+          for (int t = 0; t < 3; ++t) {
+            if (kq == 3 && t == 2) continue;  // quarter 3 owns bytes 18..21 only
+            for (int b = 0; b < 2; ++b) tile[t * 1024 + (kq * 16 + r) * 16 + j * 2 + b] = gb[6 * kq + 2 * t + b];
+          }
+      }
+    }
+  }
+  return CCQ_OK;
+}
+
+extern "C" int ccq_pack_scales(const ccq_weight* w, const uint16_t* src, void* out_v) {
+  if (!w || !src || !out_v) return CCQ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(w, &L);
+  if (rc != CCQ_OK) return rc;
+  uint16_t* out = static_cast<uint16_t*>(out_v);
+  std::vector<int> pos, kind;
+  packed_order(w, L, pos, kind);
+  const int64_t wide_base = (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs;
+  for (int n = 0; n < L.N; ++n) {
+    uint16_t* tile_row = out + (int64_t)(n / kRowsPerTile) * L.row_tile_scale_halfs;
+    const int r = n % kRowsPerTile;
+    for (int g = 0; g < L.G; ++g) {
+      uint16_t v = src[(int64_t)n * L.G + g];
+      if (kind[g] == kNarrow)
+        tile_row[(int64_t)(pos[g] / 4) * kNarrowTileScaleHalfs + r * 4 + pos[g] % 4] = v;
+      else
+        tile_row[wide_base + (int64_t)(pos[g] / 8) * kWideTileScaleHalfs + r * 8 + pos[g] % 8] = v;
+    }
+  }
+  return CCQ_OK;
+}
+
+extern "C" int ccq_pack_meta(const ccq_weight* w, void* out_v) {
+  if (!w || !out_v) return CCQ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(w, &L);
+  if (rc != CCQ_OK) return rc;
+  int32_t* out = static_cast<int32_t*>(out_v);
+  std::vector<int> pos, kind;
+  packed_order(w, L, pos, kind);
+  for (int g = 0; g < L.G; ++g) out[(kind[g] == kNarrow ? 0 : L.groups[kNarrow]) + pos[g]] = g;
+  return CCQ_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_weight_ptrs(const ccq_weight* w, const Layout& L) {
+  if (!w->codes || !w->scales) return CCQ_ERR_NULL;
+  if (L.groups[kNarrow] > 0 && (!w->code_alpha || !w->code_beta)) return CCQ_ERR_NULL;
+  if (L.has_map && !w->meta) return CCQ_ERR_NULL;
+  if (!aligned16(w->codes) || !aligned16(w->scales) || !aligned16(w->code_alpha) || !aligned16(w->code_beta) || !aligned16(w->meta))
+    return CCQ_ERR_ALIGN;
+  return CCQ_OK;
+}
+
+static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
+                     int64_t workspace_bytes, void* stream, const ccq_launch* launch) {
+  if (!w) return CCQ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(w, &L);
+  if (rc != CCQ_OK) return rc;
+  if (M < 0 || workspace_bytes < 0) return CCQ_ERR_BAD_PARAM;
+  if (M == 0) return CCQ_OK;
+  if (!x || !y) return CCQ_ERR_NULL;
+  rc = check_weight_ptrs(w, L);
+  if (rc != CCQ_OK) return rc;
+  if (ldx < L.K || ldy < L.N) return CCQ_ERR_BAD_PARAM;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(workspace) || ldx % 8 != 0 || ldy % 8 != 0) return CCQ_ERR_ALIGN;
+
+  // rows are processed in passes of at most kMaxSkinnyM
+  for (int m0 = 0; m0 < M; m0 += kMaxSkinnyM) {
+    const int mc = std::min(kMaxSkinnyM, M - m0);
+    SkinnyCall c;
+    c.w = w;
+    c.L = L;
+    if (launch && (launch->rows_per_wave_tiles || launch->waves_rows || launch->waves_k || launch->splits_k)) {
+      c.d.RT = launch->rows_per_wave_tiles ? launch->rows_per_wave_tiles : 1;
+      c.d.WR = launch->waves_rows ? launch->waves_rows : 1;
+      c.d.WK = launch->waves_k ? launch->waves_k : 1;
+      c.d.S = launch->splits_k ? launch->splits_k : 1;
+      if (!decomp_ok(L, c.d)) return CCQ_ERR_BAD_PARAM;
+    } else {
+      c.d = choose_decomp(L, mc, 1, mc);
+    }
+    if (c.d.S > 1) {
+      const int64_t need = (int64_t)c.d.S * mc * L.N * 4;
+      if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
+      c.partial = static_cast<float*>(workspace);
+    }
+    c.E = 1;
+    c.x = static_cast<const uint16_t*>(x) + (int64_t)m0 * ldx;
+    c.ldx = ldx;
+    c.y = static_cast<uint16_t*>(y) + (int64_t)m0 * ldy;
+    c.ldy = ldy;
+    c.M = mc;
+    c.m_tile_hint = mc;
+    c.stream = stream;
+    rc = launch_skinny(c);
+    if (rc != CCQ_OK) return rc;
+  }
+  return CCQ_OK;
+}
+
+extern "C" int ccq_gemm(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
+                        int64_t workspace_bytes, void* hip_stream) {
+  return gemm_impl(w, x, M, ldx, y, ldy, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+extern "C" int ccq_gemm_ex(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
+                           int64_t workspace_bytes, void* hip_stream, const ccq_launch* launch) {
+  return gemm_impl(w, x, M, ldx, y, ldy, workspace, workspace_bytes, hip_stream, launch);
+}
+
+static int grouped_tile_rows(int E, int P) {
+  // rows one pass holds: twice the mean rows per expert, rounded up to 16, at most 64
+  int64_t mean2 = E > 0 ? (2 * (int64_t)P + E - 1) / E : 0;
+  int rows = (int)std::min<int64_t>(kMaxSkinnyM, std::max<int64_t>(16, ((mean2 + 15) / 16) * 16));
+  return rows;
+}
+
+extern "C" int64_t ccq_grouped_workspace_bytes(const ccq_weight* w0, int32_t E, int32_t P) {
+  Layout L;
+  if (make_layout(w0, &L) != CCQ_OK || E <= 0 || P < 0) return -1;
+  if (P == 0) return 0;
+  Decomp d = choose_decomp(L, grouped_tile_rows(E, P), E, P);
+  return d.S > 1 ? (int64_t)d.S * P * L.N * 4 : 0;
+}
+
+extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride,
+                                const void* x, int32_t T, int64_t ldx, const int32_t* sorted_rows, int32_t P,
+                                const int32_t* expert_offsets_dev, const int32_t* expert_offsets_host, void* y, int64_t ldy,
+                                void* workspace, int64_t workspace_bytes, void* hip_stream) {
+  if (!w0) return CCQ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(w0, &L);
+  if (rc != CCQ_OK) return rc;
+  if (E <= 0 || P < 0 || T < 0 || workspace_bytes < 0) return CCQ_ERR_BAD_PARAM;
+  if (expert_offsets_host) {
+    if (expert_offsets_host[0] != 0 || expert_offsets_host[E] != P) return CCQ_ERR_ROUTING;
+    for (int e = 0; e < E; ++e)
+      if (expert_offsets_host[e + 1] < expert_offsets_host[e]) return CCQ_ERR_ROUTING;
+  }
+  if (P == 0) return CCQ_OK;
+  if (T == 0) return CCQ_ERR_ROUTING;
+  if (!x || !y || !sorted_rows || !expert_offsets_dev) return CCQ_ERR_NULL;
+  rc = check_weight_ptrs(w0, L);
+  if (rc != CCQ_OK) return rc;
+  if (ldx < L.K || ldy < L.N) return CCQ_ERR_BAD_PARAM;
+  if (E > 1) {
+    const int64_t code_bytes = L.row_tile_bytes * L.row_tiles, scale_bytes = L.row_tile_scale_halfs * L.row_tiles * 2;
+    if (codes_stride < code_bytes || scales_stride < scale_bytes) return CCQ_ERR_BAD_PARAM;
+    if (L.groups[kNarrow] > 0 && ab_stride < (int64_t)L.N * 4) return CCQ_ERR_BAD_PARAM;
+    if (codes_stride % 16 || scales_stride % 16 || ab_stride % 16) return CCQ_ERR_ALIGN;
+  }
+  if (!aligned16(x) || !aligned16(y) || !aligned16(workspace) || !aligned16(sorted_rows) || !aligned16(expert_offsets_dev) ||
+      ldx % 8 != 0 || ldy % 8 != 0)
+    return CCQ_ERR_ALIGN;
+  SkinnyCall c;
+  c.w = w0;
+  c.L = L;
+  c.m_tile_hint = grouped_tile_rows(E, P);
+  c.d = choose_decomp(L, c.m_tile_hint, E, P);
+  if (c.d.S > 1) {
+    const int64_t need = (int64_t)c.d.S * P * L.N * 4;
+    if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
+    c.partial = static_cast<float*>(workspace);
+  }
+  c.E = E;
+  c.codes_stride = codes_stride;
+  c.scales_stride = scales_stride;
+  c.ab_stride = ab_stride;
+  c.x = x;
+  c.ldx = ldx;
+  c.y = y;
+  c.ldy = ldy;
+  c.M = P;
+  c.sorted_rows = sorted_rows;
+  c.expert_offsets = expert_offsets_dev;
+  c.stream = hip_stream;
+  return launch_skinny(c);
+}
+
+extern "C" const char* ccq_status_string(int status) {
+  switch (status) {
+    case CCQ_OK: return "CCQ_OK";
+    case CCQ_ERR_NULL: return "CCQ_ERR_NULL";
+    case CCQ_ERR_BAD_PARAM: return "CCQ_ERR_BAD_PARAM";
+    case CCQ_ERR_UNSUPPORTED: return "CCQ_ERR_UNSUPPORTED";
+    case CCQ_ERR_ALIGN: return "CCQ_ERR_ALIGN";
+    case CCQ_ERR_WORKSPACE: return "CCQ_ERR_WORKSPACE";
+    case CCQ_ERR_ROUTING: return "CCQ_ERR_ROUTING";
+    case CCQ_ERR_HIP: return "CCQ_ERR_HIP";
+    default: return "CCQ_ERR_UNKNOWN";
+  }
+}

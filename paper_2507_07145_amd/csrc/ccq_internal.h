@@ -1,0 +1,91 @@
+// Internal declarations shared by the host layer and the kernel launchers of
+// libccq.  Nothing here is part of the public C ABI (include/ccq.h).
+#pragma once
+#include <cstdint>
+
+#include "ccq.h"
+
+namespace ccq {
+
+// ---- device layout of the packed code stream ------------------------------
+// Output rows are cut into tiles of 16; K is cut into k-tiles.  A k-tile of the
+// narrow format spans 4 groups (256 weights), one of the wide format 8 groups
+// (512 weights).  Inside a row tile all narrow k-tiles come first (k order),
+// then all wide k-tiles.  Lane l of a wavefront owns output row (l % 16) and
+// quarter kq = l / 16 of every group.
+//
+//   narrow k-tile (1024 B): lane l reads bytes [16 l, 16 l + 16): dword j is
+//     group j of the tile, holding that group's canonical bytes 4kq..4kq+3
+//     (the codes of weights 16kq..16kq+15).
+//   wide k-tile (2816 B): three segments t = 0,1,2 of 1024, 1024, 768 bytes;
+//     lane l reads 16 bytes of segment t: halfword j is group j of the tile,
+//     holding canonical bytes 6kq+2t, 6kq+2t+1 of the group (quarter 3 has only
+//     bytes 18..21, so segment 2 has no entries for lanes 48..63).
+constexpr int kGroup = 64;
+constexpr int kRowsPerTile = 16;
+constexpr int kNarrowGroupsPerTile = 4;
+constexpr int kWideGroupsPerTile = 8;
+constexpr int kNarrowTileBytes = 1024;
+constexpr int kWideTileBytes = 2816;
+constexpr int kNarrowGroupBytes = 16;
+constexpr int kWideGroupBytes = 22;
+// fp16 scales: per row tile, per k-tile, [row 0..15][group of the tile]
+constexpr int kNarrowTileScaleHalfs = 16 * 4;
+constexpr int kWideTileScaleHalfs = 16 * 8;
+
+constexpr int kMaxSkinnyM = 64;   // rows one pass of the skinny kernel holds
+constexpr int kMaxSplitsK = 32;
+
+enum Kind : int { kNarrow = 0, kWide = 1 };
+
+// A validated view of a ccq_weight.
+struct Layout {
+  int K = 0, N = 0, G = 0;
+  int groups[2] = {0, 0};       // groups per kind
+  int tiles[2] = {0, 0};        // k-tiles per kind
+  int kind_of_fmt[2] = {0, 0};  // descriptor format index -> Kind
+  float zp[2] = {0.f, 0.f};     // zero-point per kind
+  bool has_map = false;         // group_fmt given
+  int64_t row_tile_bytes = 0;
+  int64_t row_tile_scale_halfs = 0;
+  int row_tiles = 0;
+};
+
+// Validates the shape/format part of a descriptor (no pointer checks).
+int make_layout(const ccq_weight* w, Layout* out);
+// Kind of group g.
+inline int group_kind(const ccq_weight* w, const Layout& L, int g) {
+  return L.kind_of_fmt[w->group_fmt ? w->group_fmt[g] : 0];
+}
+
+// Launch decomposition of the skinny kernel.
+struct Decomp {
+  int RT = 1;  // 16-row tiles per wavefront
+  int WR = 1;  // wavefronts along rows per workgroup
+  int WK = 1;  // wavefronts along K per workgroup
+  int S = 1;   // workgroups along K
+};
+Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total);
+bool decomp_ok(const Layout& L, const Decomp& d);
+
+// Kernel launchers (ccq_skinny.hip).  All pointers DEVICE unless noted.
+struct SkinnyCall {
+  const ccq_weight* w = nullptr;  // HOST descriptor of expert 0
+  Layout L;
+  Decomp d;
+  int E = 1;
+  int64_t codes_stride = 0, scales_stride = 0, ab_stride = 0;
+  const void* x = nullptr;
+  int64_t ldx = 0;
+  void* y = nullptr;
+  int64_t ldy = 0;
+  int M = 0;                            // rows (dense) / P total rows (grouped)
+  int m_tile_hint = 0;                  // rows one pass should hold (<= 64)
+  const int32_t* sorted_rows = nullptr; // grouped only
+  const int32_t* expert_offsets = nullptr;
+  float* partial = nullptr;             // fp32 [S][M][N] when S > 1
+  void* stream = nullptr;
+};
+int launch_skinny(const SkinnyCall& c);
+
+}  // namespace ccq

@@ -1,0 +1,554 @@
+// Skinny fused dequantize-and-multiply (M <= 64 rows per pass) and its grouped
+// (mixture-of-experts) form, for gfx950.
+//
+// One wavefront owns 16 (or 32) output rows and a range of k-tiles.  It streams
+// the packed code bytes with 128-bit loads, cuts the overlapping states out of
+// each code with shifts (Sec. 3.1 "Bitshift Decoding", Table 1 shift lists
+// [9,6,3,0] / [4,2,0]), and feeds them to the matrix cores as bf16 integers:
+// OR-ing a state s into the mantissa of bf16 128.0 (0x4300) gives exactly
+// 128 + s.  The contraction of one 64-weight group therefore yields
+//     sum_k (128 + s_k) x_k ,
+// and starting the accumulator at  -(128 + zp) * sum_k x_k  turns it into
+//     sum_k (s_k - zp) x_k ,
+// which is multiplied by the group's fp16 scale afterwards -- the linear map
+// d = (w_uint - zp) * s of Alg. 2 / Alg. 3 applied after the contraction
+// instead of per weight.  For the Code Cluster format the stored byte q is
+// first expanded to the 15-bit code c = round(q*alpha + beta) (Alg. 3) with a
+// single fused multiply-add against beta + 2^23: the sum lies in [2^23, 2^24)
+// where fp32 has unit spacing, so the hardware's round-to-nearest-even *is* the
+// rounding of Eq. 1 and c appears in the low mantissa bits.
+//
+// MFMA 16x16x32 bf16 operand layout (lane l, quarter kq = l / 16):
+//   A (activations): row m = l % 16, k-slots 8kq .. 8kq+7
+//   B (weights)    : column n = l % 16, k-slots 8kq .. 8kq+7
+//   C/D            : rows m = 4kq .. 4kq+3, column n = l % 16
+// so all four accumulator values of a lane share the output row n of W and one
+// group scale serves them.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "ccq_internal.h"
+
+namespace ccq {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+struct SkinnyArgs {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const int32_t* meta;
+  const uint16_t* x;
+  uint16_t* y;
+  float* partial;
+  const int32_t* sorted_rows;
+  const int32_t* expert_offsets;
+  int64_t ldx, ldy, codes_stride, scales_stride, ab_stride;
+  int64_t row_tile_bytes, row_tile_scale_halfs;
+  int32_t M;          // rows (dense) or total rows P (grouped)
+  int32_t N;
+  int32_t row_tiles;
+  int32_t tiles[2];   // k-tiles per kind
+  int32_t groups_narrow;
+  int32_t KC[2];      // k-tiles per wavefront per staged chunk, per kind
+  int32_t WR, WK, S;
+  float cneg[2];      // -(128 + zp) per kind
+};
+
+template <int KIND> struct Traits;
+template <> struct Traits<kNarrow> {
+  static constexpr int GPT = kNarrowGroupsPerTile, T = 2, SEGS = 1, TILE_BYTES = kNarrowTileBytes, SCALE_HALFS = kNarrowTileScaleHalfs;
+};
+template <> struct Traits<kWide> {
+  static constexpr int GPT = kWideGroupsPerTile, T = 3, SEGS = 3, TILE_BYTES = kWideTileBytes, SCALE_HALFS = kWideTileScaleHalfs;
+};
+
+template <int KIND> struct TileRegs {
+  u32x4 c[Traits<KIND>::SEGS];
+  uint32_t s[Traits<KIND>::GPT / 2];
+};
+
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
+  uint32_t d;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(orv));
+  return d;
+}
+
+__device__ __forceinline__ uint32_t dword_of(const u32x4& v, int j) {
+  return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
+}
+
+template <int KIND>
+__device__ __forceinline__ void load_tile(TileRegs<KIND>& r, const uint8_t* codes_kind, const uint16_t* scales_kind, int kt, int lane) {
+  using TR = Traits<KIND>;
+  const uint8_t* t = codes_kind + (int64_t)kt * TR::TILE_BYTES + lane * 16;
+  r.c[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
+  if constexpr (KIND == kWide) {
+    r.c[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
+    u32x4 z = {0u, 0u, 0u, 0u};
+    if (lane < 48) z = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048));
+    r.c[2] = z;
+  }
+  const uint16_t* sp = scales_kind + (int64_t)kt * TR::SCALE_HALFS + (lane & 15) * TR::GPT;
+  if constexpr (KIND == kNarrow) {
+    uint2 v = *reinterpret_cast<const uint2*>(sp);
+    r.s[0] = v.x; r.s[1] = v.y;
+  } else {
+    uint4 v = *reinterpret_cast<const uint4*>(sp);
+    r.s[0] = v.x; r.s[1] = v.y; r.s[2] = v.z; r.s[3] = v.w;
+  }
+}
+
+// Weight fragment (8 bf16 integers 128 + state) of group j, k-step t.
+template <int KIND>
+__device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, int t, float al, float be_magic, uint32_t c4300) {
+  uint4 o;
+  if constexpr (KIND == kNarrow) {
+    // two clustered bytes -> two 15-bit codes (Alg. 3), side by side in one register
+    const uint32_t d = dword_of(r.c[0], j);
+    const float fa = __builtin_fmaf((float)((d >> (16 * t)) & 0xFFu), al, be_magic);
+    const float fb = __builtin_fmaf((float)((d >> (16 * t + 8)) & 0xFFu), al, be_magic);
+    const uint32_t yy = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, fb), __builtin_bit_cast(uint32_t, fa), 0x05040100u);
+    // states by the shift list [9,6,3,0], mask 0x3F (Table 1), for both codes at once
+    o.x = and_or(yy >> 9, 0x003F003Fu, c4300);
+    o.y = and_or(yy >> 6, 0x003F003Fu, c4300);
+    o.z = and_or(yy >> 3, 0x003F003Fu, c4300);
+    o.w = and_or(yy, 0x003F003Fu, c4300);
+  } else {
+    // two 8-bit codes of (L=4,N=3,S=2); shift list [4,2,0], mask 0xF (Table 1)
+    const uint32_t d = dword_of(r.c[t], j >> 1);
+    const uint32_t p = __builtin_amdgcn_perm(0u, d, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // {0,b,0,a}
+    o.x = and_or(p >> 4, 0x000F000Fu, c4300);
+    o.y = and_or(p >> 2, 0x000F000Fu, c4300);
+    o.z = and_or(p, 0x000F000Fu, c4300);
+    o.w = c4300;  // unused k-slots (their activations are staged as zero)
+  }
+  return __builtin_bit_cast(bf16x8, o);
+}
+
+template <int KIND>
+__device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, int j) {
+  const uint32_t d = r.s[j >> 1];
+  const uint16_t h = (uint16_t)((j & 1) ? (d >> 16) : (d & 0xFFFFu));
+  return (float)__builtin_bit_cast(_Float16, h);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __builtin_bit_cast(float, bits16 << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Stage the activations of `ng` consecutive packed groups (first packed index
+// pg0 inside the kind) as A-operand fragments and compute each group's
+// accumulator start value  cneg * sum_k x[m][k].
+//   lds_x    : fragments, index ((lg*T + t)*4 + kq)*MRT + m, 16 bytes each
+//   lds_cneg : fp32, index lg*(MT*16) + m
+template <int KIND, int MT, int MR>
+__device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, const uint16_t* x, int row_base, int rows_valid, int pg0,
+                            int ng, int tid, int nthreads) {
+  using TR = Traits<KIND>;
+  constexpr int MRT = (MT == 1) ? MR : MT * 16;
+  const int nfrag = ng * TR::T * 4 * MRT;
+  const int meta_base = (KIND == kWide) ? a.groups_narrow : 0;
+  for (int f = tid; f < nfrag; f += nthreads) {
+    const int m = f % MRT;
+    const int kq = (f / MRT) & 3;
+    const int t = (f / (MRT * 4)) % TR::T;
+    const int lg = f / (MRT * 4 * TR::T);
+    uint4 o = {0u, 0u, 0u, 0u};
+    if (m < rows_valid) {
+      const int g = a.meta ? a.meta[meta_base + pg0 + lg] : (pg0 + lg);
+      const int64_t row = a.sorted_rows ? (int64_t)a.sorted_rows[row_base + m] : (int64_t)(row_base + m);
+      const uint16_t* xr = x + row * a.ldx + (int64_t)g * kGroup;
+      if constexpr (KIND == kNarrow) {
+        // the two codes of a k-step cover weights 16kq+8t+{0..3} and +{4..7}; slots
+        // interleave them: {0,4,1,5,2,6,3,7}
+        const uint4 v = *reinterpret_cast<const uint4*>(xr + 16 * kq + 8 * t);
+        o.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);
+        o.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
+        o.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
+        o.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
+      } else {
+        // codes ja = 6kq+2t and ja+1 cover weights 3ja+{0,1,2} and 3ja+3+{0,1,2};
+        // slots {a0,b0,a1,b1,a2,b2,-,-}; code 21 carries weight 63 only
+        const int ja = 6 * kq + 2 * t;
+        uint32_t h[6];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+#pragma unroll
+          for (int which = 0; which < 2; ++which) {
+            const int jj = ja + which, wi = 3 * jj + i;
+            h[2 * i + which] = (jj <= 21 && wi < kGroup) ? (uint32_t)xr[wi] : 0u;
+          }
+        }
+        o.x = h[0] | (h[1] << 16);
+        o.y = h[2] | (h[3] << 16);
+        o.z = h[4] | (h[5] << 16);
+      }
+    }
+    lds_x[f] = o;
+  }
+  __syncthreads();
+  const int ncneg = ng * MT * 16;
+  const float factor = a.cneg[KIND];
+  for (int i = tid; i < ncneg; i += nthreads) {
+    const int m = i % (MT * 16);
+    const int lg = i / (MT * 16);
+    float sum = 0.f;
+    if (m < MRT) {
+#pragma unroll 1
+      for (int tk = 0; tk < TR::T * 4; ++tk) {
+        const uint4 v = lds_x[(lg * TR::T * 4 + tk) * MRT + m];
+        sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
+               bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
+      }
+    }
+    lds_cneg[i] = factor * sum;
+  }
+  __syncthreads();
+}
+
+template <int KIND, int MT, int MR, int RT>
+__device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int lg0, const uint4* lds_x, const float* lds_cneg, const float (&al)[RT],
+                                             const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, uint32_t c4300) {
+  using TR = Traits<KIND>;
+  constexpr int MRT = (MT == 1) ? MR : MT * 16;
+  const int kq = lane >> 4, m = lane & 15;
+#pragma unroll
+  for (int j = 0; j < TR::GPT; ++j) {
+    const int lg = lg0 + j;
+    f32x4 P[RT][MT];
+    f32x4 cin[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
+#pragma unroll
+    for (int t = 0; t < TR::T; ++t) {
+      bf16x8 xf[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (MR == 16 || m < MR) v = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + mt * 16 + m];
+        xf[mt] = __builtin_bit_cast(bf16x8, v);
+      }
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], c4300);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          P[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mt], wf, t == 0 ? cin[mt] : P[rt][mt], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const float s = group_scale<KIND>(r[rt], j);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        // Only element 0 is needed when one activation row is held, but all four registers of the
+        // MFMA result stay allocated up to here: reusing the unused ones as scratch while the
+        // MFMA is still in flight gave wrong results on the device.
+        if (MR == 1) asm volatile("" : "+v"(P[rt][mt]));
+        acc[rt][mt][0] = __builtin_fmaf(s, P[rt][mt][0], acc[rt][mt][0]);
+        if (MR > 1) {
+          acc[rt][mt][1] = __builtin_fmaf(s, P[rt][mt][1], acc[rt][mt][1]);
+          acc[rt][mt][2] = __builtin_fmaf(s, P[rt][mt][2], acc[rt][mt][2]);
+          acc[rt][mt][3] = __builtin_fmaf(s, P[rt][mt][3], acc[rt][mt][3]);
+        }
+      }
+    }
+  }
+}
+
+// All k-tiles of one kind that belong to this workgroup, chunk by chunk.
+template <int KIND, int MT, int MR, int RT>
+__device__ void run_kind(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
+                         const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg, const uint16_t* x,
+                         int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads, uint32_t c4300) {
+  using TR = Traits<KIND>;
+  constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);  // tiles in flight per wavefront
+  const int tiles = a.tiles[KIND];
+  const int A = (int)(((int64_t)split * tiles) / a.S), B = (int)(((int64_t)(split + 1) * tiles) / a.S);
+  const int KC = a.KC[KIND], CH = KC * a.WK;
+  for (int c0 = A; c0 < B; c0 += CH) {
+    const int cend = min(c0 + CH, B);
+    const int k0 = min(c0 + wk * KC, cend), k1 = min(k0 + KC, cend);
+    TileRegs<KIND> buf[D][RT];
+    if (active) {
+#pragma unroll
+      for (int i = 0; i < D; ++i)
+        if (k0 + i < k1) {
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], k0 + i, lane);
+        }
+    }
+    __syncthreads();  // the previous chunk's fragments are no longer read
+    stage_chunk<KIND, MT, MR>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, (cend - c0) * TR::GPT, tid, nthreads);
+    if (active) {
+      for (int kt = k0; kt < k1; kt += D) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+          if (kt + i < k1) {
+            process_tile<KIND, MT, MR, RT>(buf[i], (kt + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+            if (kt + i + D < k1) {
+#pragma unroll
+              for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], kt + i + D, lane);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int MT, int MR, int RT, int FM>
+__global__ void __launch_bounds__(MT >= 2 ? 512 : 1024) ccq_skinny_kernel(const SkinnyArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wr = wave % a.WR, wk = wave / a.WR;
+  const int split = blockIdx.y, e = blockIdx.z;
+
+  int off0 = 0, Me = a.M;
+  if (a.expert_offsets) {
+    off0 = a.expert_offsets[e];
+    Me = a.expert_offsets[e + 1] - off0;
+  }
+  if (Me <= 0) return;
+
+  const uint8_t* codes = a.codes + (int64_t)e * a.codes_stride;
+  const uint16_t* scales = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scales) + (int64_t)e * a.scales_stride);
+  const float* alpha = a.alpha ? reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + (int64_t)e * a.ab_stride) : nullptr;
+  const float* beta = a.beta ? reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + (int64_t)e * a.ab_stride) : nullptr;
+
+  const int rtile0 = (blockIdx.x * a.WR + wr) * RT;
+  const bool active = rtile0 < a.row_tiles;
+  const uint8_t* codes_n[RT];
+  const uint8_t* codes_w[RT];
+  const uint16_t* scales_n[RT];
+  const uint16_t* scales_w[RT];
+  float al[RT], be[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int rtile = min(rtile0 + rt, a.row_tiles - 1);  // a ragged last pair re-reads the last tile; its result is not stored
+    codes_n[rt] = codes + (int64_t)rtile * a.row_tile_bytes;
+    codes_w[rt] = codes_n[rt] + (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
+    scales_n[rt] = scales + (int64_t)rtile * a.row_tile_scale_halfs;
+    scales_w[rt] = scales_n[rt] + (int64_t)a.tiles[kNarrow] * kNarrowTileScaleHalfs;
+    al[rt] = 0.f;
+    be[rt] = 8388608.f;
+    if ((FM & 1) && active) {
+      al[rt] = alpha[rtile * 16 + (lane & 15)];
+      be[rt] = beta[rtile * 16 + (lane & 15)] + 8388608.f;  // + 2^23: exact, beta is an integer below 2^15
+    }
+  }
+
+  uint4* lds_x = reinterpret_cast<uint4*>(smem);
+  // the start values follow the fragments; their offset is fixed by the larger of the two kinds' chunk sizes
+  constexpr int MRT = (MT == 1) ? MR : MT * 16;
+  int frag_cap = 0;
+  if (FM & 1) frag_cap = max(frag_cap, a.KC[kNarrow] * a.WK * Traits<kNarrow>::GPT * Traits<kNarrow>::T * 4 * MRT);
+  if (FM & 2) frag_cap = max(frag_cap, a.KC[kWide] * a.WK * Traits<kWide>::GPT * Traits<kWide>::T * 4 * MRT);
+  float* lds_cneg = reinterpret_cast<float*>(smem + (size_t)frag_cap * 16);
+  uint32_t c4300 = 0x43004300u;
+  asm volatile("" : "+v"(c4300));  // keep the constant in a vector register for v_and_or_b32
+
+  for (int m0 = 0; m0 < Me; m0 += MT * 16) {
+    const int rows_valid = min(MT * 16, Me - m0);
+    f32x4 acc[RT][MT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if constexpr ((FM & 1) != 0)
+      run_kind<kNarrow, MT, MR, RT>(a, codes_n, scales_n, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
+                                    nthreads, c4300);
+    if constexpr ((FM & 2) != 0)
+      run_kind<kWide, MT, MR, RT>(a, codes_w, scales_w, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
+                                  nthreads, c4300);
+
+    // ---- reduce the K-splits of this workgroup through LDS (fixed order) ----
+    if (a.WK > 1) {
+      __syncthreads();
+      f32x4* red = reinterpret_cast<f32x4*>(smem);
+      if (wk > 0) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) red[((((wk - 1) * a.WR + wr) * RT + rt) * MT + mt) * 64 + lane] = acc[rt][mt];
+      }
+      __syncthreads();
+      if (wk == 0) {
+        for (int k = 1; k < a.WK; ++k) {
+#pragma unroll
+          for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              const f32x4 v = red[((((k - 1) * a.WR + wr) * RT + rt) * MT + mt) * 64 + lane];
+              acc[rt][mt] += v;
+            }
+        }
+      }
+    }
+
+    // ---- store: bf16 result, or fp32 partials when K is also split over workgroups ----
+    if (wk == 0 && active) {
+      const int kq = lane >> 4;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        if (rtile0 + rt >= a.row_tiles) continue;
+        const int n = (rtile0 + rt) * 16 + (lane & 15);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int m = mt * 16 + 4 * kq + r;
+            if (m < rows_valid) {
+              const int64_t prow = (int64_t)off0 + m0 + m;
+              if (a.S > 1) a.partial[((int64_t)split * a.M + prow) * a.N + n] = acc[rt][mt][r];
+              else a.y[prow * a.ldy + n] = f32_to_bf16_rne(acc[rt][mt][r]);
+            }
+          }
+        }
+      }
+    }
+    if (m0 + MT * 16 < Me) __syncthreads();
+  }
+}
+
+// y[p][n] = bf16( sum_s partial[s][p][n] ), splits added in index order.
+__global__ void ccq_reduce_splits_kernel(const float* partial, uint16_t* y, int64_t ldy, int rows, int N, int S) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (int64_t)rows * N;
+  if (i >= total) return;
+  float sum = partial[i];
+  for (int s = 1; s < S; ++s) sum += partial[(int64_t)s * total + i];
+  const int64_t p = i / N, n = i % N;
+  y[p * ldy + n] = f32_to_bf16_rne(sum);
+}
+
+// ---------------------------------------------------------------------------
+
+typedef void (*SkinnyKernel)(const SkinnyArgs);
+
+template <int MT, int MR, int RT>
+static SkinnyKernel pick_fm(int fm) {
+  switch (fm) {
+    case 1: return ccq_skinny_kernel<MT, MR, RT, 1>;
+    case 2: return ccq_skinny_kernel<MT, MR, RT, 2>;
+    default: return ccq_skinny_kernel<MT, MR, RT, 3>;
+  }
+}
+
+template <int MT, int MR>
+static SkinnyKernel pick_rt(int rt, int fm) {
+  return rt == 1 ? pick_fm<MT, MR, 1>(fm) : pick_fm<MT, MR, 2>(fm);
+}
+
+static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm) {
+  if (mt == 1) {
+    if (mr == 1) return pick_rt<1, 1>(rt, fm);
+    if (mr == 4) return pick_rt<1, 4>(rt, fm);
+    return pick_rt<1, 16>(rt, fm);
+  }
+  if (mt == 2) return pick_rt<2, 16>(rt, fm);
+  return pick_rt<4, 16>(rt, fm);
+}
+
+int launch_skinny(const SkinnyCall& c) {
+  const Layout& L = c.L;
+  const Decomp& d = c.d;
+  const int rows = std::min(std::max(c.m_tile_hint, 1), kMaxSkinnyM);
+  int mt = (rows + 15) / 16;
+  if (mt == 3) mt = 4;
+  const int mr = mt > 1 ? 16 : (rows == 1 ? 1 : (rows <= 4 ? 4 : 16));
+  const int mrt = mt == 1 ? mr : mt * 16;
+  const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
+  if (mt >= 2 && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
+
+  SkinnyArgs a;
+  a.codes = static_cast<const uint8_t*>(c.w->codes);
+  a.scales = static_cast<const uint16_t*>(c.w->scales);
+  a.alpha = c.w->code_alpha;
+  a.beta = c.w->code_beta;
+  a.meta = static_cast<const int32_t*>(c.w->meta);
+  a.x = static_cast<const uint16_t*>(c.x);
+  a.y = static_cast<uint16_t*>(c.y);
+  a.partial = c.partial;
+  a.sorted_rows = c.sorted_rows;
+  a.expert_offsets = c.expert_offsets;
+  a.ldx = c.ldx;
+  a.ldy = c.ldy;
+  a.codes_stride = c.codes_stride;
+  a.scales_stride = c.scales_stride;
+  a.ab_stride = c.ab_stride;
+  a.row_tile_bytes = L.row_tile_bytes;
+  a.row_tile_scale_halfs = L.row_tile_scale_halfs;
+  a.M = c.M;
+  a.N = L.N;
+  a.row_tiles = L.row_tiles;
+  a.tiles[0] = L.tiles[0];
+  a.tiles[1] = L.tiles[1];
+  a.groups_narrow = L.groups[kNarrow];
+  a.WR = d.WR;
+  a.WK = d.WK;
+  a.S = d.S;
+  a.cneg[0] = -(128.f + L.zp[0]);
+  a.cneg[1] = -(128.f + L.zp[1]);
+
+  // chunk sizes: as many k-tiles per wavefront as fit a 56 KiB staging budget
+  const int64_t budget = 56 * 1024;
+  int64_t lds = 0;
+  const int per_tile[2] = {kNarrowGroupsPerTile * (2 * 4 * mrt * 16 + mt * 16 * 4), kWideGroupsPerTile * (3 * 4 * mrt * 16 + mt * 16 * 4)};
+  int64_t frag_cap = 0;
+  for (int k = 0; k < 2; ++k) {
+    a.KC[k] = 1;
+    if (L.tiles[k] == 0) continue;
+    const int wg_tiles = (L.tiles[k] + d.S - 1) / d.S;             // most k-tiles a workgroup owns
+    const int want = (wg_tiles + d.WK - 1) / d.WK;                 // per wavefront if staged at once
+    const int fit = (int)std::max<int64_t>(1, budget / ((int64_t)per_tile[k] * d.WK));
+    a.KC[k] = std::max(1, std::min(want, fit));
+    const int gpt = k == kNarrow ? kNarrowGroupsPerTile : kWideGroupsPerTile, T = k == kNarrow ? 2 : 3;
+    frag_cap = std::max<int64_t>(frag_cap, (int64_t)a.KC[k] * d.WK * gpt * T * 4 * mrt);
+    lds = std::max<int64_t>(lds, frag_cap * 16 + (int64_t)a.KC[k] * d.WK * gpt * mt * 16 * 4);
+  }
+  // both kinds use the same fragment capacity, so the start values of either fit behind it
+  for (int k = 0; k < 2; ++k) {
+    if (L.tiles[k] == 0) continue;
+    const int gpt = k == kNarrow ? kNarrowGroupsPerTile : kWideGroupsPerTile;
+    lds = std::max<int64_t>(lds, frag_cap * 16 + (int64_t)a.KC[k] * d.WK * gpt * mt * 16 * 4);
+  }
+  if (d.WK > 1) lds = std::max<int64_t>(lds, (int64_t)(d.WK - 1) * d.WR * d.RT * mt * 64 * 16);
+  if (lds > 150 * 1024) return CCQ_ERR_BAD_PARAM;
+
+  SkinnyKernel kern = pick_kernel(mt, mr, d.RT, fm);
+  hipStream_t stream = static_cast<hipStream_t>(c.stream);
+  if (lds > 48 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      (void)hipGetLastError();
+      return CCQ_ERR_HIP;
+    }
+  }
+  const int row_blocks = (L.row_tiles + d.WR * d.RT - 1) / (d.WR * d.RT);
+  dim3 grid((unsigned)row_blocks, (unsigned)d.S, (unsigned)c.E);
+  dim3 block((unsigned)(64 * d.WR * d.WK));
+  hipLaunchKernelGGL(kern, grid, block, (size_t)lds, stream, a);
+  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+  if (d.S > 1) {
+    const int64_t total = (int64_t)c.M * L.N;
+    const int threads = 256;
+    hipLaunchKernelGGL(ccq_reduce_splits_kernel, dim3((unsigned)((total + threads - 1) / threads)), dim3(threads), 0, stream, c.partial,
+                       static_cast<uint16_t*>(c.y), c.ldy, c.M, L.N, d.S);
+    if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+  }
+  return CCQ_OK;
+}
+
+}  // namespace ccq

@@ -1,0 +1,186 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI.
+
+Decoded weights are compared bit for bit (one-hot activations make ccq_gemm
+return bf16(W_dq[:, k])); GEMM outputs are compared element by element within
+the tolerance of tests/cases.py.  Sizes here finish in seconds on the oracle and
+still span several tiles, ragged splits and every launch decomposition; the
+full benchmark configurations are in test_gpu_configs.py."""
+import numpy as np
+import pytest
+import torch
+
+from cases import Case, assert_gemm_close, canon_zero, encoded_case, random_case
+from oracle import ccq_oracle as o
+from paper_2507_07145_amd import binding as b
+from paper_2507_07145_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _gemm_bits(w, x_bits, **kw):
+    y = b.gemm(w, b.bf16_tensor(x_bits, DEV), **kw)
+    torch.cuda.synchronize()
+    return b.bf16_bits(y)
+
+
+def _check_decode(case: Case, w, ks, **kw):
+    """One-hot rows e_k through the GEMM return column k of the decoded matrix, exactly."""
+    ks = list(ks)
+    got = _gemm_bits(w, synth.one_hot_bf16(ks, case.K), **kw)
+    want = o.to_bf16_bits(case.W()[:, ks].T)
+    assert np.array_equal(canon_zero(got), canon_zero(want)), f"decoded weights differ at columns {ks[:8]}..."
+
+
+@pytest.fixture(scope="module")
+def cfg1():
+    """Config 1: W 1024x1024 ~ N(0, 0.02), encoded by the oracle at 2.0 bits/weight."""
+    c = encoded_case(1024, 1024, 1)
+    return c, c.device_weight(DEV)
+
+
+def test_cfg1_decode_bit_exact(cfg1):
+    c, w = cfg1
+    rng = np.random.default_rng(0)
+    cols = np.concatenate([np.arange(0, 64), [255, 256, 511, 960, 1023], rng.integers(0, 1024, 59)])
+    for i in range(0, len(cols), 16):
+        _check_decode(c, w, cols[i:i + 16])
+    _check_decode(c, w, [7])                                     # M = 1 path
+    _check_decode(c, w, [1, 2, 1022])                            # M = 3 path (4 held rows)
+
+
+def test_cfg1_gemv_and_skinny(cfg1):
+    c, w = cfg1
+    for M in (1, 2, 3, 4, 5, 8, 15, 16, 17, 32, 33, 48, 64):
+        x = synth.activations_bf16(M, c.K, synth.rng(1, 100 + M))
+        assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"cfg1 M={M}")
+
+
+def test_more_rows_than_one_pass(cfg1):
+    c, w = cfg1
+    for M in (65, 100, 130):
+        x = synth.activations_bf16(M, c.K, synth.rng(1, 200 + M))
+        assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"cfg1 M={M}")
+
+
+@pytest.mark.parametrize("launch", [(1, 1, 1, 1), (2, 1, 1, 1), (1, 4, 1, 1), (1, 1, 4, 1), (2, 2, 2, 1), (1, 2, 1, 2), (2, 1, 2, 4),
+                                    (1, 4, 4, 1), (1, 1, 16, 1), (2, 3, 3, 3), (1, 2, 8, 1), (1, 1, 1, 5)])
+@pytest.mark.parametrize("M", [1, 4, 16, 40])
+def test_every_decomposition_gives_the_same_answer(cfg1, launch, M):
+    c, w = cfg1
+    if M > 16 and launch[1] * launch[2] > 8:
+        pytest.skip("more than 8 wavefronts per workgroup is only built for M <= 16")
+    x = synth.activations_bf16(M, c.K, synth.rng(1, 300 + M))
+    ref = o.matmul(x, c.W())
+    assert_gemm_close(_gemm_bits(w, x, launch=b.ccq_launch(*launch)), ref, f"M={M} launch={launch}")
+    _check_decode(c, w, [3, 64 + 17, 1023, 500][:min(M, 4)], launch=b.ccq_launch(*launch))
+
+
+@pytest.mark.parametrize("kinds,K,N,n_wide", [(["wide"], 1024, 256, None), (["wide"], 512, 48, None), (["narrow"], 1280, 80, None),
+                                              (["narrow", "wide"], 2048, 128, 8), (["narrow", "wide"], 4096, 64, 24)])
+def test_formats_decode_and_gemm(kinds, K, N, n_wide):
+    c = random_case(K, N, kinds, 7, stream0=10 * len(kinds) + K % 7, n_wide=n_wide)
+    w = c.device_weight(DEV)
+    ks = [0, 1, 2, 3, 17, 18, 19, 53, 54, 59, 60, 61, 62, 63, 64, K - 1]
+    _check_decode(c, w, ks)
+    if c.group_fmt is not None:                                  # every column of one wide and one narrow group
+        gw, gn = int(np.flatnonzero(c.group_fmt == 1)[0]), int(np.flatnonzero(c.group_fmt == 0)[-1])
+        for g in (gw, gn):
+            for i in range(0, 64, 16):
+                _check_decode(c, w, range(64 * g + i, 64 * g + i + 16))
+    else:
+        for i in range(0, 64, 16):
+            _check_decode(c, w, range(64 + i, 64 + i + 16))
+    for M in (1, 3, 8, 16, 33, 64):
+        x = synth.activations_bf16(M, K, synth.rng(7, 50 + M))
+        ref = o.matmul(x, c.W())
+        assert_gemm_close(_gemm_bits(w, x), ref, f"{kinds} K={K} N={N} M={M}")
+        for launch in ((2, 2, 1, 1), (1, 1, 3, 2), (1, 2, 2, 1)):
+            assert_gemm_close(_gemm_bits(w, x, launch=b.ccq_launch(*launch)), ref, f"{kinds} M={M} launch={launch}")
+
+
+def test_strided_activations_and_guard_bands():
+    """ldx > K, ldy > N: nothing outside y[:M, :N] is written."""
+    c = random_case(1024, 96, ["narrow"], 8)
+    w = c.device_weight(DEV)
+    for M in (1, 7, 64, 70):
+        xb = synth.activations_bf16(M, c.K, synth.rng(8, M))
+        xt = torch.zeros((M, c.K + 64), dtype=torch.bfloat16, device=DEV)
+        xt[:, :c.K] = b.bf16_tensor(xb, DEV)
+        big = torch.full((M + 2, c.N + 40), -7.0, dtype=torch.bfloat16, device=DEV)
+        b.gemm(w, xt[:, :c.K], out=big[1:M + 1, 8:8 + c.N])
+        torch.cuda.synchronize()
+        assert_gemm_close(b.bf16_bits(big[1:M + 1, 8:8 + c.N]), o.matmul(xb, c.W()), f"strided M={M}")
+        guard = big.clone()
+        guard[1:M + 1, 8:8 + c.N] = -7.0
+        assert bool((guard == -7.0).all()), "wrote outside the output block"
+
+
+def test_deterministic(cfg1):
+    c, w = cfg1
+    for M, launch in ((1, None), (16, None), (16, (1, 2, 2, 4)), (64, None)):
+        x = synth.activations_bf16(M, c.K, synth.rng(1, 400 + M))
+        kw = {} if launch is None else {"launch": b.ccq_launch(*launch)}
+        first = _gemm_bits(w, x, **kw)
+        for _ in range(3):
+            assert np.array_equal(_gemm_bits(w, x, **kw), first)
+
+
+def test_linearity_in_activations(cfg1):
+    """The path is linear in x: exact powers of two scale the output exactly."""
+    c, w = cfg1
+    x = synth.activations_bf16(4, c.K, synth.rng(1, 500))
+    y1 = o.bf16_bits_to_f64(_gemm_bits(w, x))
+    x4 = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(x) * np.float32(4.0))
+    y4 = o.bf16_bits_to_f64(_gemm_bits(w, x4))
+    assert np.array_equal(y4, 4.0 * y1)
+
+
+def _grouped_reference(cases, x, rows, offs):
+    return o.grouped_matmul(x, rows, offs, lambda e: cases[e].W())
+
+
+@pytest.mark.parametrize("kinds,K,N", [(["narrow"], 512, 64), (["wide"], 512, 32), (["narrow"], 1024, 160)])
+def test_grouped_small(kinds, K, N):
+    E, T = 6, 40
+    cases = [random_case(K, N, kinds, 9, stream0=10 * e) for e in range(E)]
+    w = b.Weight.from_canonical(K, N, [b.NARROW if kinds[0] == "narrow" else b.WIDE],
+                                np.stack([c.codes for c in cases]), np.stack([c.scales for c in cases]),
+                                None if kinds[0] != "narrow" else np.stack([c.alpha for c in cases]),
+                                None if kinds[0] != "narrow" else np.stack([c.beta for c in cases]), device=DEV, experts=E)
+    x = synth.activations_bf16(T, K, synth.rng(9, 99))
+    # expert 2 is empty, expert 4 has more rows than one pass holds at the chosen tile height
+    counts = [5, 1, 0, 17, 38, 16]
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    rows = synth.rng(9, 98).integers(0, T, size=int(offs[-1])).astype(np.int32)
+    P = int(offs[-1])
+    y = torch.full((P + 1, N), 3.0, dtype=torch.bfloat16, device=DEV)
+    b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs, out=y[:P])
+    torch.cuda.synchronize()
+    assert_gemm_close(b.bf16_bits(y[:P]), _grouped_reference(cases, x, rows, offs), f"grouped {kinds}")
+    assert bool((y[P] == 3.0).all())
+    # decoded weights of every expert, bit exact: one-hot tokens routed to each expert
+    ks = [0, 63, 64, K - 1]
+    xe = synth.one_hot_bf16(ks, K)
+    counts2 = [len(ks)] * E
+    offs2 = np.concatenate([[0], np.cumsum(counts2)]).astype(np.int32)
+    rows2 = np.tile(np.arange(len(ks), dtype=np.int32), E)
+    y2 = b.grouped_gemm(w, b.bf16_tensor(xe, DEV), torch.from_numpy(rows2).to(DEV), torch.from_numpy(offs2).to(DEV), offs2)
+    torch.cuda.synchronize()
+    got = b.bf16_bits(y2).reshape(E, len(ks), N)
+    for e in range(E):
+        assert np.array_equal(canon_zero(got[e]), canon_zero(o.to_bf16_bits(cases[e].W()[:, ks].T))), f"expert {e}"
+
+
+def test_grouped_all_experts_empty_and_errors():
+    c = random_case(512, 32, ["narrow"], 10)
+    w = c.device_weight(DEV)
+    x = b.bf16_tensor(synth.activations_bf16(4, 512, synth.rng(10, 1)), DEV)
+    rows = torch.zeros(0, dtype=torch.int32, device=DEV)
+    offs = torch.zeros(2, dtype=torch.int32, device=DEV)
+    y = b.grouped_gemm(w, x, rows, offs, np.zeros(2, np.int32))
+    assert y.shape == (0, 32)
+    rows = torch.zeros(4, dtype=torch.int32, device=DEV)
+    with pytest.raises(b.CcqError) as ei:
+        b.grouped_gemm(w, x, rows, offs, np.array([0, 3], np.int32))      # offsets[E] != P
+    assert ei.value.status == -6

@@ -1,0 +1,145 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads and exports every
+declared symbol, the layout accounting follows Eq. 5, the pack routines are the documented
+byte permutations, and bad arguments come back as error codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import ccq_oracle as o
+from paper_2507_07145_amd import binding as b
+from paper_2507_07145_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = b.load()
+    header = open(os.path.join(ROOT, "include", "ccq.h")).read()
+    declared = set(re.findall(r"\b(ccq_[a-z_]+)\s*\(", header))
+    assert {"ccq_pack_info", "ccq_gemm", "ccq_grouped_gemm"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(b.EXPORTS)
+    assert lib.ccq_status_string(-6) == b"CCQ_ERR_ROUTING"
+
+
+def test_pack_info_accounting_matches_eq5_and_oracle():
+    for kinds, fmt, bpw in (([b.NARROW], o.F2, 2.0), ([b.WIDE], o.F275, 2.75)):
+        w = b.descriptor(8192, 8192, kinds)
+        i = b.pack_info(w, 16)
+        assert i.code_bpw == bpw == o.bpw(8, 64, fmt.N, 0)
+        assert i.code_bytes == 8192 * o.row_bytes(8192, fmt)              # device order stores exactly the canonical bytes
+        assert i.bytes_per_group[0] == o.group_bytes(fmt) and i.scale_bytes == 8192 * 128 * 2
+        assert i.align == 16 and i.meta_bytes == 128 * 4
+    # per-group mix: 32 of 128 groups wide -> (96*16 + 32*22) bytes per row = 2.1875 bpw
+    gf = synth.group_format_map(128, 32, synth.rng(3, 0))
+    w = b.descriptor(8192, 28672, [b.NARROW, b.WIDE], gf)
+    i = b.pack_info(w, 64)
+    assert i.code_bpw == 2.1875 and list(i.groups) == [96, 32]
+    assert i.code_bytes == 28672 * o.row_bytes(8192, (o.F2, o.F275), gf) == 64225280
+    assert i.total_bpw == 8.0 * (i.code_bytes + i.scale_bytes + 8 * 28672) / (28672 * 8192)
+
+
+def _device_offset_narrow(n, pos, byte):
+    """Documented device order of a narrow k-tile (independent re-statement for the test)."""
+    tile, j, kq, b_in = pos // 4, pos % 4, byte // 4, byte % 4
+    return tile * 1024 + (kq * 16 + n % 16) * 16 + j * 4 + b_in
+
+
+def _device_offset_wide(n, pos, byte):
+    tile, j = pos // 8, pos % 8
+    kq = min(byte // 6, 3)
+    t, b_in = (byte - 6 * kq) // 2, (byte - 6 * kq) % 2
+    return tile * 2816 + t * 1024 + (kq * 16 + n % 16) * 16 + j * 2 + b_in
+
+
+def test_pack_codes_is_the_documented_permutation():
+    rng = np.random.default_rng(0)
+    K, N = 2048, 48
+    gf = synth.group_format_map(K // 64, 8, synth.rng(3, 1))
+    w = b.descriptor(K, N, [b.NARROW, b.WIDE], gf)
+    rb = o.row_bytes(K, (o.F2, o.F275), gf)
+    src = rng.integers(0, 256, size=(N, rb), dtype=np.uint8)
+    out = b.pack_codes(w, src)
+    assert np.array_equal(np.sort(out), np.sort(src.ravel()))               # a permutation: no byte altered, none duplicated
+    info = b.pack_info(w, 0)
+    n_narrow = int((gf == 0).sum())
+    pos = {0: 0, 1: 0}
+    off = 0
+    for g in range(K // 64):
+        kind = int(gf[g])
+        nb = 22 if kind else 16
+        for n in (0, 5, 16, 47):
+            base = (n // 16) * info.row_tile_bytes + (0 if kind == 0 else (n_narrow // 4) * 1024)
+            for byte in range(nb):
+                d = base + (_device_offset_wide(n, pos[1], byte) if kind else _device_offset_narrow(n, pos[0], byte))
+                assert out[d] == src[n, off + byte], (g, n, byte)
+        pos[kind] += 1
+        off += nb
+    meta = b.pack_meta(w)
+    assert list(meta[:n_narrow]) == list(np.flatnonzero(gf == 0)) and list(meta[n_narrow:]) == list(np.flatnonzero(gf == 1))
+    scales = rng.integers(0, 1 << 16, size=(N, K // 64), dtype=np.uint16)
+    ps = b.pack_scales(w, scales)
+    assert np.array_equal(np.sort(ps), np.sort(scales.ravel()))
+    tile_halfs = (n_narrow // 4) * 64 + ((K // 64 - n_narrow) // 8) * 128
+    g0 = int(np.flatnonzero(gf == 0)[5])                                    # 6th narrow group: tile 1, slot 1
+    assert ps[2 * tile_halfs + 1 * 64 + 3 * 4 + 1] == scales[35, g0]
+    g1 = int(np.flatnonzero(gf == 1)[7])                                    # 8th wide group: tile 0, slot 7
+    assert ps[0 * tile_halfs + (n_narrow // 4) * 64 + 9 * 8 + 7] == scales[9, g1]
+
+
+def test_descriptor_validation():
+    def status(fn):
+        try:
+            fn()
+            return 0
+        except b.CcqError as e:
+            return e.status
+    ok = b.descriptor(1024, 64, [b.NARROW])
+    assert status(lambda: b.pack_info(ok)) == 0
+    bad_group = b.descriptor(1024, 64, [b.NARROW]); bad_group.group = 128
+    assert status(lambda: b.pack_info(bad_group)) == -3                     # valid CCQ, not built
+    assert status(lambda: b.pack_info(b.descriptor(1000, 64, [b.NARROW]))) == -2   # K not a multiple of 64
+    assert status(lambda: b.pack_info(b.descriptor(1024, 0, [b.NARROW]))) == -2
+    assert status(lambda: b.pack_info(b.descriptor(1024, 40, [b.NARROW]))) == -3   # rows not a multiple of 16
+    assert status(lambda: b.pack_info(b.descriptor(1088, 64, [b.NARROW]))) == -3   # 17 narrow groups: partial k-tile
+    assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.ccq_code(3, 3, 2, 0, 4.0)]))) == -3   # other (L,N,S)
+    assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.ccq_code(6, 4, 3, 1, 31.25)]))) == -2  # zp not a multiple of 0.5
+    assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.ccq_code(6, 4, 7, 1, 32.0)]))) == -2   # S > L
+    assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.NARROW, b.NARROW], np.zeros(16, np.uint8)))) == -2
+    gf = np.zeros(16, np.uint8); gf[3] = 2
+    assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.NARROW, b.WIDE], gf))) == -2
+    assert b.load().ccq_pack_info(None, 1, None) == -1
+
+
+def test_gemm_argument_errors_need_no_gpu():
+    """All argument checks happen before any HIP call."""
+    lib = b.load()
+    w = b.descriptor(1024, 64, [b.NARROW])
+    vp = ctypes.c_void_p
+    assert lib.ccq_gemm(ctypes.byref(w), vp(0), 0, 1024, vp(0), 64, vp(0), 0, vp(0)) == 0            # M = 0: no-op
+    assert lib.ccq_gemm(ctypes.byref(w), vp(0), 1, 1024, vp(0), 64, vp(0), 0, vp(0)) == -1           # x, y NULL
+    assert lib.ccq_gemm(ctypes.byref(w), vp(256), 1, 1024, vp(512), 64, vp(0), 0, vp(0)) == -1       # codes NULL
+    w.codes, w.scales, w.code_alpha, w.code_beta = 4096, 8192, 12288, 16384                           # never dereferenced below
+    assert lib.ccq_gemm(ctypes.byref(w), vp(256), -1, 1024, vp(512), 64, vp(0), 0, vp(0)) == -2
+    assert lib.ccq_gemm(ctypes.byref(w), vp(256), 1, 512, vp(512), 64, vp(0), 0, vp(0)) == -2        # ldx < K
+    assert lib.ccq_gemm(ctypes.byref(w), vp(258), 1, 1024, vp(512), 64, vp(0), 0, vp(0)) == -4       # misaligned x
+    assert lib.ccq_gemm(ctypes.byref(w), vp(256), 1, 1028, vp(512), 64, vp(0), 0, vp(0)) == -4       # ldx not a multiple of 8
+    la = b.ccq_launch(1, 1, 1, 4)
+    assert lib.ccq_gemm_ex(ctypes.byref(w), vp(256), 1, 1024, vp(512), 64, vp(0), 0, vp(0), ctypes.byref(la)) == -5   # workspace missing
+    la = b.ccq_launch(3, 1, 1, 1)
+    assert lib.ccq_gemm_ex(ctypes.byref(w), vp(256), 1, 1024, vp(512), 64, vp(0), 0, vp(0), ctypes.byref(la)) == -2
+    offs = np.array([0, 2, 1, 4], dtype=np.int32)                                                    # not monotone
+    rc = lib.ccq_grouped_gemm(ctypes.byref(w), 3, 1 << 20, 1 << 16, 4096, vp(256), 4, 1024, vp(512), 4, vp(768),
+                              offs.ctypes.data_as(vp), vp(1024), 64, vp(0), 0, vp(0))
+    assert rc == -6
+
+
+def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "libccq.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        b.load()
