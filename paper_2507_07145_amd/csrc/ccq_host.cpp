@@ -83,7 +83,7 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     d.WR = std::max(1, std::min(8 / d.WK, (int)std::min<int64_t>(8, L.row_tiles)));
     if (units / d.WR >= 8192) d.RT = 2;
   } else {
-    d.RT = L.row_tiles >= 2 ? 2 : 1;
+    d.RT = (L.row_tiles >= 2 && M <= 32) ? 2 : 1;  // 33..64 held rows: one row tile per wavefront
     d.WR = (int)std::min<int64_t>(4, std::max(1, L.row_tiles / d.RT));
     d.WK = 1;
     int64_t row_blocks = (int64_t)ceil_div(L.row_tiles, d.RT * d.WR) * experts;

@@ -55,7 +55,9 @@ struct SkinnyArgs {
   int32_t tiles[2];   // k-tiles per kind
   int32_t groups_narrow;
   int32_t KC[2];      // k-tiles per wavefront per staged chunk, per kind
+  int32_t SG[2];      // groups of a k-tile staged at a time (= groups per tile unless LDS is tight; then KC = 1)
   int32_t WR, WK, S;
+  int32_t frag_cap;   // 16-byte fragments the LDS staging area holds; the start values follow it
   float cneg[2];      // -(128 + zp) per kind
 };
 
@@ -146,14 +148,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
-// Stage the activations of `ng` consecutive packed groups (first packed index
-// pg0 inside the kind) as A-operand fragments and compute each group's
-// accumulator start value  cneg * sum_k x[m][k].
+// Stage the activations of `ng` packed groups as A-operand fragments and compute
+// each group's accumulator start value  cneg * sum_k x[m][k].  Local group lg is
+// packed group  pg0 + (lg / sg) * GPT + j0 + lg % sg  of the kind: with sg = GPT,
+// j0 = 0 that is a run of whole k-tiles, otherwise groups j0..j0+sg-1 of
+// consecutive k-tiles.
 //   lds_x    : fragments, index ((lg*T + t)*4 + kq)*MRT + m, 16 bytes each
 //   lds_cneg : fp32, index lg*(MT*16) + m
 template <int KIND, int MT, int MR>
 __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, const uint16_t* x, int row_base, int rows_valid, int pg0,
-                            int ng, int tid, int nthreads) {
+                            int ng, int sg, int j0, int tid, int nthreads) {
   using TR = Traits<KIND>;
   constexpr int MRT = (MT == 1) ? MR : MT * 16;
   const int nfrag = ng * TR::T * 4 * MRT;
@@ -165,7 +169,8 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
     const int lg = f / (MRT * 4 * TR::T);
     uint4 o = {0u, 0u, 0u, 0u};
     if (m < rows_valid) {
-      const int g = a.meta ? a.meta[meta_base + pg0 + lg] : (pg0 + lg);
+      const int pg = pg0 + (lg / sg) * TR::GPT + j0 + lg % sg;
+      const int g = a.meta ? a.meta[meta_base + pg] : pg;
       const int64_t row = a.sorted_rows ? (int64_t)a.sorted_rows[row_base + m] : (int64_t)(row_base + m);
       const uint16_t* xr = x + row * a.ldx + (int64_t)g * kGroup;
       if constexpr (KIND == kNarrow) {
@@ -216,15 +221,15 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
   __syncthreads();
 }
 
-template <int KIND, int MT, int MR, int RT>
+template <int KIND, int MT, int MR, int RT, int J0, int NJ>
 __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int lg0, const uint4* lds_x, const float* lds_cneg, const float (&al)[RT],
                                              const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, uint32_t c4300) {
   using TR = Traits<KIND>;
   constexpr int MRT = (MT == 1) ? MR : MT * 16;
   const int kq = lane >> 4, m = lane & 15;
 #pragma unroll
-  for (int j = 0; j < TR::GPT; ++j) {
-    const int lg = lg0 + j;
+  for (int j = J0; j < J0 + NJ; ++j) {
+    const int lg = lg0 + (j - J0);
     f32x4 P[RT][MT];
     f32x4 cin[MT];
 #pragma unroll
@@ -266,11 +271,15 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
   }
 }
 
-// All k-tiles of one kind that belong to this workgroup, chunk by chunk.
+// All k-tiles of one kind that belong to this workgroup, chunk by chunk: the
+// activations of a chunk (KC k-tiles for each of the WK wavefronts along K) are
+// staged in LDS, then every wavefront walks its own tiles with a register ring
+// of D tiles in flight.
 template <int KIND, int MT, int MR, int RT>
-__device__ void run_kind(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
-                         const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg, const uint16_t* x,
-                         int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads, uint32_t c4300) {
+__device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
+                               const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
+                               const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
+                               uint32_t c4300) {
   using TR = Traits<KIND>;
   constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);  // tiles in flight per wavefront
   const int tiles = a.tiles[KIND];
@@ -289,13 +298,13 @@ __device__ void run_kind(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], co
         }
     }
     __syncthreads();  // the previous chunk's fragments are no longer read
-    stage_chunk<KIND, MT, MR>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, (cend - c0) * TR::GPT, tid, nthreads);
+    stage_chunk<KIND, MT, MR>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, (cend - c0) * TR::GPT, TR::GPT, 0, tid, nthreads);
     if (active) {
       for (int kt = k0; kt < k1; kt += D) {
 #pragma unroll
         for (int i = 0; i < D; ++i) {
           if (kt + i < k1) {
-            process_tile<KIND, MT, MR, RT>(buf[i], (kt + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+            process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (kt + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
             if (kt + i + D < k1) {
 #pragma unroll
               for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], kt + i + D, lane);
@@ -305,6 +314,81 @@ __device__ void run_kind(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], co
       }
     }
   }
+}
+
+// When many activation rows are held, the fragments of a whole k-tile do not fit
+// in LDS next to other workgroups: every wavefront along K then owns one k-tile
+// per step and its groups are staged SG at a time.
+template <int KIND, int MT, int MR, int RT, int SG, int J0>
+struct SubSteps {
+  static __device__ __forceinline__ void run(const SkinnyArgs& a, const TileRegs<KIND> (&r)[RT], bool has, const float (&al)[RT],
+                                             const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg, const uint16_t* x,
+                                             int row_base, int rows_valid, int c0, int ntiles, int wk, int lane, int tid, int nthreads,
+                                             uint32_t c4300) {
+    using TR = Traits<KIND>;
+    if constexpr (J0 < TR::GPT) {
+      __syncthreads();  // the previous step's fragments are no longer read
+      stage_chunk<KIND, MT, MR>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, ntiles * SG, SG, J0, tid, nthreads);
+      if (has) process_tile<KIND, MT, MR, RT, J0, SG>(r, wk * SG, lds_x, lds_cneg, al, be, acc, lane, c4300);
+      SubSteps<KIND, MT, MR, RT, SG, J0 + SG>::run(a, r, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid,
+                                                   nthreads, c4300);
+    }
+  }
+};
+
+template <int KIND, int MT, int MR, int RT, int SG>
+__device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
+                                const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
+                                const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
+                                uint32_t c4300) {
+  using TR = Traits<KIND>;
+  const int tiles = a.tiles[KIND];
+  const int A = (int)(((int64_t)split * tiles) / a.S), B = (int)(((int64_t)(split + 1) * tiles) / a.S);
+  TileRegs<KIND> cur[RT], nxt[RT];
+  if (active && A + wk < B) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(cur[rt], codes_rt[rt], scales_rt[rt], A + wk, lane);
+  }
+  for (int c0 = A; c0 < B; c0 += a.WK) {
+    const int ntiles = min(a.WK, B - c0);
+    const bool has = active && wk < ntiles;
+    const bool has_next = active && c0 + a.WK + wk < B;
+    if (has_next) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(nxt[rt], codes_rt[rt], scales_rt[rt], c0 + a.WK + wk, lane);
+    }
+    SubSteps<KIND, MT, MR, RT, SG, 0>::run(a, cur, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid, nthreads,
+                                           c4300);
+    if (has_next) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) cur[rt] = nxt[rt];
+    }
+  }
+}
+
+template <int KIND, int MT, int MR, int RT>
+__device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
+                                         const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
+                                         const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
+                                         uint32_t c4300) {
+  using TR = Traits<KIND>;
+  if constexpr (MT >= 2) {
+    const int sg = a.SG[KIND];
+    if (sg != TR::GPT) {
+      if (sg == 1)
+        run_kind_groups<KIND, MT, MR, RT, 1>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
+                                             tid, nthreads, c4300);
+      else if (sg == 2)
+        run_kind_groups<KIND, MT, MR, RT, 2>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
+                                             tid, nthreads, c4300);
+      else
+        run_kind_groups<KIND, MT, MR, RT, 4>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
+                                             tid, nthreads, c4300);
+      return;
+    }
+  }
+  run_kind_tiles<KIND, MT, MR, RT>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane, tid,
+                                   nthreads, c4300);
 }
 
 template <int MT, int MR, int RT, int FM>
@@ -350,11 +434,7 @@ __global__ void __launch_bounds__(MT >= 2 ? 512 : 1024) ccq_skinny_kernel(const 
   }
 
   uint4* lds_x = reinterpret_cast<uint4*>(smem);
-  // the start values follow the fragments; their offset is fixed by the larger of the two kinds' chunk sizes
-  constexpr int MRT = (MT == 1) ? MR : MT * 16;
-  int frag_cap = 0;
-  if (FM & 1) frag_cap = max(frag_cap, a.KC[kNarrow] * a.WK * Traits<kNarrow>::GPT * Traits<kNarrow>::T * 4 * MRT);
-  if (FM & 2) frag_cap = max(frag_cap, a.KC[kWide] * a.WK * Traits<kWide>::GPT * Traits<kWide>::T * 4 * MRT);
+  const int frag_cap = a.frag_cap;
   float* lds_cneg = reinterpret_cast<float*>(smem + (size_t)frag_cap * 16);
   uint32_t c4300 = 0x43004300u;
   asm volatile("" : "+v"(c4300));  // keep the constant in a vector register for v_and_or_b32
@@ -459,7 +539,7 @@ static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm) {
     return pick_rt<1, 16>(rt, fm);
   }
   if (mt == 2) return pick_rt<2, 16>(rt, fm);
-  return pick_rt<4, 16>(rt, fm);
+  return pick_fm<4, 16, 1>(fm);  // 64 held rows: one row tile per wavefront (two would spill registers)
 }
 
 int launch_skinny(const SkinnyCall& c) {
@@ -472,6 +552,7 @@ int launch_skinny(const SkinnyCall& c) {
   const int mrt = mt == 1 ? mr : mt * 16;
   const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
   if (mt >= 2 && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
+  if (mt == 4 && d.RT != 1) return CCQ_ERR_BAD_PARAM;
 
   SkinnyArgs a;
   a.codes = static_cast<const uint8_t*>(c.w->codes);
@@ -503,28 +584,34 @@ int launch_skinny(const SkinnyCall& c) {
   a.cneg[0] = -(128.f + L.zp[0]);
   a.cneg[1] = -(128.f + L.zp[1]);
 
-  // chunk sizes: as many k-tiles per wavefront as fit a 56 KiB staging budget
+  // chunk sizes: as many k-tiles per wavefront as fit a 56 KiB staging budget; if not even one
+  // tile per wavefront fits, the groups of a tile are staged a few at a time
   const int64_t budget = 56 * 1024;
-  int64_t lds = 0;
-  const int per_tile[2] = {kNarrowGroupsPerTile * (2 * 4 * mrt * 16 + mt * 16 * 4), kWideGroupsPerTile * (3 * 4 * mrt * 16 + mt * 16 * 4)};
-  int64_t frag_cap = 0;
+  int64_t frag_cap = 0, cneg_cap = 0;
   for (int k = 0; k < 2; ++k) {
     a.KC[k] = 1;
+    const int gpt = k == kNarrow ? kNarrowGroupsPerTile : kWideGroupsPerTile, T = k == kNarrow ? 2 : 3;
+    a.SG[k] = gpt;
     if (L.tiles[k] == 0) continue;
+    const int64_t per_group = (int64_t)T * 4 * mrt * 16 + (int64_t)mt * 16 * 4;
     const int wg_tiles = (L.tiles[k] + d.S - 1) / d.S;             // most k-tiles a workgroup owns
     const int want = (wg_tiles + d.WK - 1) / d.WK;                 // per wavefront if staged at once
-    const int fit = (int)std::max<int64_t>(1, budget / ((int64_t)per_tile[k] * d.WK));
-    a.KC[k] = std::max(1, std::min(want, fit));
-    const int gpt = k == kNarrow ? kNarrowGroupsPerTile : kWideGroupsPerTile, T = k == kNarrow ? 2 : 3;
-    frag_cap = std::max<int64_t>(frag_cap, (int64_t)a.KC[k] * d.WK * gpt * T * 4 * mrt);
-    lds = std::max<int64_t>(lds, frag_cap * 16 + (int64_t)a.KC[k] * d.WK * gpt * mt * 16 * 4);
+    const int64_t fit = budget / (per_group * gpt * d.WK);
+    int64_t groups_staged;
+    if (fit >= 1 || mt < 2) {
+      a.KC[k] = (int)std::max<int64_t>(1, std::min<int64_t>(want, fit));
+      groups_staged = (int64_t)a.KC[k] * d.WK * gpt;
+    } else {
+      int sg = gpt / 2;
+      while (sg > 1 && per_group * sg * d.WK > budget) sg /= 2;
+      a.SG[k] = sg;
+      groups_staged = (int64_t)sg * d.WK;
+    }
+    frag_cap = std::max<int64_t>(frag_cap, groups_staged * T * 4 * mrt);
+    cneg_cap = std::max<int64_t>(cneg_cap, groups_staged * mt * 16);
   }
-  // both kinds use the same fragment capacity, so the start values of either fit behind it
-  for (int k = 0; k < 2; ++k) {
-    if (L.tiles[k] == 0) continue;
-    const int gpt = k == kNarrow ? kNarrowGroupsPerTile : kWideGroupsPerTile;
-    lds = std::max<int64_t>(lds, frag_cap * 16 + (int64_t)a.KC[k] * d.WK * gpt * mt * 16 * 4);
-  }
+  a.frag_cap = (int)frag_cap;
+  int64_t lds = frag_cap * 16 + cneg_cap * 4;
   if (d.WK > 1) lds = std::max<int64_t>(lds, (int64_t)(d.WK - 1) * d.WR * d.RT * mt * 64 * 16);
   if (lds > 150 * 1024) return CCQ_ERR_BAD_PARAM;
 

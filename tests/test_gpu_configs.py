@@ -1,0 +1,114 @@
+"""GPU parity at the full sizes of the five benchmark configurations, in the launch
+configuration the library (and bench.py) picks by itself.  Where the whole output is too
+large for the oracle to finish in seconds, a seeded sample of output channels is decoded and
+multiplied by the oracle and compared element by element; decoded weights are compared bit
+for bit on sampled columns."""
+import numpy as np
+import pytest
+import torch
+
+from cases import Case, assert_gemm_close, canon_zero, encoded_case, random_case
+from oracle import ccq_oracle as o
+from paper_2507_07145_amd import binding as b
+from paper_2507_07145_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _sample_rows(N, n_tiles, rng):
+    """Whole 16-row tiles: the first, the last and a random selection."""
+    tiles = np.unique(np.concatenate([[0, N // 16 - 1], rng.choice(N // 16, size=n_tiles, replace=False)]))
+    return (tiles[:, None] * 16 + np.arange(16)[None, :]).reshape(-1)
+
+
+def _run(w, x_bits, **kw):
+    y = b.gemm(w, b.bf16_tensor(x_bits, DEV), **kw)
+    torch.cuda.synchronize()
+    return b.bf16_bits(y)
+
+
+def _check_sampled(case: Case, w, Ms, cfg, rows, decode_cols):
+    Wr = case.W(rows)
+    for M in Ms:
+        x = synth.activations_bf16(M, case.K, synth.rng(cfg, 100 + M))
+        got = _run(w, x)
+        assert_gemm_close(got[:, rows], o.matmul(x, Wr), f"config {cfg} M={M}")
+    for i in range(0, len(decode_cols), 16):
+        ks = [int(k) for k in decode_cols[i:i + 16]]
+        got = _run(w, synth.one_hot_bf16(ks, case.K))
+        assert np.array_equal(canon_zero(got[:, rows]), canon_zero(o.to_bf16_bits(Wr[:, ks].T))), f"config {cfg}: decoded columns {ks}"
+
+
+def test_config2_dense_decode_encoded_weights():
+    """K = N = 8192, N(0, 0.02) weights encoded by the oracle at 2.0 bits/weight; M in {1, 8, 16}; every output checked."""
+    c = encoded_case(8192, 8192, 2)
+    w = c.device_weight(DEV)
+    info = w.info
+    assert info.code_bpw == 2.0 and info.code_bytes == 16777216
+    rows = np.arange(8192)
+    cols = np.concatenate([[0, 63, 64, 8191], synth.rng(2, 9).integers(0, 8192, 28)])
+    _check_sampled(c, w, (1, 8, 16), 2, rows, cols)
+
+
+@pytest.mark.parametrize("variant", ["all_wide", "mixed"])
+def test_config3_hybrid_skinny(variant):
+    """K = 8192, N = 28672, M in {1, 16, 64}; either every group in the 2.75-bit format or a seeded
+    32-of-128 mix with the 2-bit format; random code bitstream, log-uniform fp16 scales."""
+    if variant == "all_wide":
+        c = random_case(8192, 28672, ["wide"], 3)
+    else:
+        c = random_case(8192, 28672, ["narrow", "wide"], 3, stream0=20, n_wide=32)
+    w = c.device_weight(DEV)
+    assert w.info.code_bpw == (2.75 if variant == "all_wide" else 2.1875)
+    rows = _sample_rows(28672, 30, synth.rng(3, 7))
+    cols = np.concatenate([[0, 63, 8191], synth.rng(3, 8).integers(0, 8192, 13)])
+    if c.group_fmt is not None:
+        gw = int(np.flatnonzero(c.group_fmt == 1)[3])
+        cols = np.concatenate([cols, 64 * gw + np.arange(48, 64)])
+    _check_sampled(c, w, (1, 16, 64), 3, rows, cols)
+
+
+@pytest.mark.parametrize("proj,K,N", [("up", 7168, 2048), ("down", 2048, 7168)])
+def test_config4_moe_grouped(proj, K, N):
+    """64 experts, 64 tokens, top-8 routing without replacement; 2.0 bits/weight random bitstream."""
+    E, T, topk = 64, 64, 8
+    G = K // 64
+    s0 = 0 if proj == "up" else 50
+    codes = synth.random_codes(E * N, K // 4, synth.rng(4, s0)).reshape(E, N, K // 4)
+    scales = synth.scales_log_uniform_fp16(E * N, G, synth.rng(4, s0 + 1)).reshape(E, N, G)
+    alpha, beta = synth.cluster_params(E * N, synth.rng(4, s0 + 2))
+    alpha, beta = alpha.reshape(E, N), beta.reshape(E, N)
+    w = b.Weight.from_canonical(K, N, [b.NARROW], codes, scales, alpha, beta, device=DEV, experts=E)
+    rows, offs = synth.routing_topk(T, E, topk, synth.rng(4, s0 + 3))
+    P = T * topk
+    assert offs[-1] == P and len(rows) == P
+    x = synth.activations_bf16(T, K, synth.rng(4, s0 + 4))
+    y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
+    torch.cuda.synchronize()
+    got = b.bf16_bits(y)
+    sel = _sample_rows(N, 6, synth.rng(4, s0 + 5))
+    ref = np.zeros((P, len(sel)))
+    for e in range(E):
+        lo, hi = int(offs[e]), int(offs[e + 1])
+        if hi > lo:
+            We = o.decode(K, len(sel), o.F2, codes[e][sel], scales[e][sel], alpha[e][sel], beta[e][sel])
+            ref[lo:hi] = o.matmul(x[rows[lo:hi]], We)
+    assert_gemm_close(got[:, sel], ref, f"config 4 {proj}")
+
+
+def test_config5_prefill():
+    """M = 2048, K = 7168, N = 18432 at 2.0 bits/weight (random bitstream)."""
+    c = random_case(7168, 18432, ["narrow"], 5)
+    w = c.device_weight(DEV)
+    M = 2048
+    x = synth.activations_bf16(M, c.K, synth.rng(5, 10))
+    got = _run(w, x)
+    rows = _sample_rows(18432, 10, synth.rng(5, 11))
+    assert_gemm_close(got[:, rows], o.matmul(x, c.W(rows)), "config 5")
+    # decoded weights through identity blocks of activations
+    ks = synth.rng(5, 12).integers(0, c.K, 64)
+    got = _run(w, synth.one_hot_bf16(np.tile(ks, M // 64), c.K))
+    want = o.to_bf16_bits(c.W(rows)[:, ks].T)
+    for rep in (0, M // 64 - 1):
+        assert np.array_equal(canon_zero(got[rep * 64:(rep + 1) * 64][:, rows]), canon_zero(want)), "config 5: decoded weights"

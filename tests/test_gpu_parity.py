@@ -70,6 +70,8 @@ def test_every_decomposition_gives_the_same_answer(cfg1, launch, M):
     c, w = cfg1
     if M > 16 and launch[1] * launch[2] > 8:
         pytest.skip("more than 8 wavefronts per workgroup is only built for M <= 16")
+    if M > 32 and launch[0] != 1:
+        pytest.skip("two row tiles per wavefront are only built for M <= 32")
     x = synth.activations_bf16(M, c.K, synth.rng(1, 300 + M))
     ref = o.matmul(x, c.W())
     assert_gemm_close(_gemm_bits(w, x, launch=b.ccq_launch(*launch)), ref, f"M={M} launch={launch}")
@@ -95,7 +97,9 @@ def test_formats_decode_and_gemm(kinds, K, N, n_wide):
         x = synth.activations_bf16(M, K, synth.rng(7, 50 + M))
         ref = o.matmul(x, c.W())
         assert_gemm_close(_gemm_bits(w, x), ref, f"{kinds} K={K} N={N} M={M}")
-        for launch in ((2, 2, 1, 1), (1, 1, 3, 2), (1, 2, 2, 1)):
+        for launch in ((2, 2, 1, 1), (1, 1, 3, 2), (1, 2, 2, 1), (1, 2, 1, 4), (2, 2, 1, 4), (1, 1, 1, 8)):
+            if M > 32 and launch[0] != 1:
+                continue
             assert_gemm_close(_gemm_bits(w, x, launch=b.ccq_launch(*launch)), ref, f"{kinds} M={M} launch={launch}")
 
 
