@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the CCQ fused dequantize-and-multiply on one MI355X.
+
+A step is one pass of the whole hot path (stream codes -> Code Cluster map -> window
+extraction -> linear value map -> contraction -> K reduction) over one batch: one ccq_gemm
+call with M = 1 on the dense decode configuration K = N = 8192 at 2.0 code bits/weight with fp16
+group-64 scales.  Inputs are resident in HBM before the timed region.  The step rotates over
+enough copies of the weights (distinct addresses) that the 256 MB Infinity Cache cannot hold
+them, so the rate is an HBM rate.  Launches are captured in a HIP graph (one replay = one pass
+over all copies) so that the host launch path is not what is timed.
+
+Prints one JSON line: the headline metric (effective HBM GB/s at M = 1), the roofline object
+for the dominant kernel (HIP events over the timed region), the oracle timed on the host cores
+(cpu_baseline), and, as additional context, the M = 2048 prefill rate in TFLOP/s.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None until measured
+TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def algorithmic_bytes(K: int, N: int, M: int, code_bytes: int, has_cluster: bool) -> int:
+    """codes + fp16 group scales + per-row alpha/beta + activations + outputs."""
+    return code_bytes + N * (K // 64) * 2 + (8 * N if has_cluster else 0) + 2 * M * K + 2 * M * N
+
+
+def make_weight_copies(K, N, copies, device):
+    """Random code bitstream (valid: every bit pattern decodes), log-uniform fp16 scales, random
+    Code Cluster parameters; packed once and cloned to `copies` distinct device buffers."""
+    import torch
+    from paper_2507_07145_amd import binding as b, synth
+    codes = synth.random_codes(N, K // 4, synth.rng(2, 0))
+    scales = synth.scales_log_uniform_fp16(N, K // 64, synth.rng(2, 1))
+    alpha, beta = synth.cluster_params(N, synth.rng(2, 2))
+    w0 = b.Weight.from_canonical(K, N, [b.NARROW], codes, scales, alpha, beta, device=device)
+    ws = [w0]
+    for _ in range(copies - 1):
+        w = b.Weight()
+        w.codes, w.scales, w.alpha, w.beta = w0.codes.clone(), w0.scales.clone(), w0.alpha.clone(), w0.beta.clone()
+        d = b.descriptor(K, N, [b.NARROW])
+        d.codes, d.scales, d.code_alpha, d.code_beta = w.codes.data_ptr(), w.scales.data_ptr(), w.alpha.data_ptr(), w.beta.data_ptr()
+        w.desc, w.info, w.E = d, w0.info, 1
+        ws.append(w)
+    return ws, (codes, scales, alpha, beta)
+
+
+def time_steps(step_fns, steps, warmup, device):
+    """Run `warmup` untimed and exactly `steps` timed steps, cycling over step_fns; one graph replay
+    covers len(step_fns) steps.  Returns (wall seconds, event seconds)."""
+    import torch
+    R = len(step_fns)
+    for i in range(warmup):
+        step_fns[i % R]()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream(device=device)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        for f in step_fns:          # one eager pass on the capture stream first
+            f()
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            for f in step_fns:
+                f()
+        graph.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        full, rest = divmod(steps, R)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(full):
+            graph.replay()
+        for i in range(rest):
+            step_fns[i]()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    return t1 - t0, e0.elapsed_time(e1) * 1e-3
+
+
+def cpu_baseline(canon, K, N, x_bits, budget_s=12.0):
+    """The oracle as it stands (decode + fp64 GEMV) on the host cores, repeated for about budget_s."""
+    from oracle import ccq_oracle as o
+    codes, scales, alpha, beta = canon
+    reps, spent = 0, 0.0
+    t_start = time.perf_counter()
+    while spent < budget_s and reps < 50:
+        W = o.decode(K, N, o.F2, codes, scales, alpha, beta)
+        o.matmul(x_bits, W)
+        reps += 1
+        spent = time.perf_counter() - t_start
+    nbytes = algorithmic_bytes(K, N, 1, codes.size, True)
+    return {"value": round(nbytes * reps / spent / 1e9, 4), "unit": "GB/s", "cores": o.num_threads(), "kind": "oracle",
+            "sample": f"whole workload (decode + fp64 GEMV of the {N}x{K} matrix, M=1), {reps} repetitions, {spent:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=6400)
+    ap.add_argument("--warmup", type=int, default=640)
+    ap.add_argument("--copies", type=int, default=32, help="weight copies the step rotates over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2507_07145_amd import binding as b, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    b.load()
+
+    K = N = 8192
+    M = 1
+    weights, canon = make_weight_copies(K, N, args.copies, dev)
+    x_bits = synth.activations_bf16(M, K, synth.rng(2, 3))
+    x = b.bf16_tensor(x_bits, dev)
+    ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in weights]
+    ws_bytes = b.pack_info(weights[0].desc, M).workspace_bytes
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    def make_step(w, y):
+        return lambda: b.gemm(w, x, out=y, workspace=ws)
+
+    steps_fns = [make_step(w, y) for w, y in zip(weights, ys)]
+    wall, ev = time_steps(steps_fns, args.steps, args.warmup, dev)
+    nbytes = algorithmic_bytes(K, N, M, weights[0].info.code_bytes, True)
+    value = nbytes * args.steps / wall / 1e9
+    per_launch_s = ev / args.steps
+    achieved = nbytes / per_launch_s / 1e9
+    out = {
+        "metric": "CCQ decode-GEMM effective HBM GB/s (M=1) and TFLOP/s (M=2048), % of roofline",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic (seeded random code bitstream, log-uniform fp16 scales, N(0,1) bf16 activations)",
+        "config": {"workload": "config 2: dense decode GEMV, M=1, K=8192, N=8192, 2.0 code bits/weight + fp16 group-64 scales",
+                   "M": M, "K": K, "N": N, "weight_copies": args.copies, "bytes_per_step": nbytes, "launch": "HIP graph replay"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                     "kernel": "ccq_skinny_kernel", "us_per_launch": round(per_launch_s * 1e6, 3)},
+    }
+
+    if not args.no_prefill:
+        Kp, Np, Mp = 7168, 18432, 2048
+        cp = synth.random_codes(Np, Kp // 4, synth.rng(5, 0))
+        sp = synth.scales_log_uniform_fp16(Np, Kp // 64, synth.rng(5, 1))
+        ap_, bp_ = synth.cluster_params(Np, synth.rng(5, 2))
+        wp = b.Weight.from_canonical(Kp, Np, [b.NARROW], cp, sp, ap_, bp_, device=dev)
+        xp = b.bf16_tensor(synth.activations_bf16(Mp, Kp, synth.rng(5, 3)), dev)
+        yp = torch.empty((Mp, Np), dtype=torch.bfloat16, device=dev)
+        wsp = torch.empty(max(b.pack_info(wp.desc, 64).workspace_bytes, 16), dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            b.gemm(wp, xp, out=yp, workspace=wsp)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5
+        e0.record()
+        for _ in range(reps):
+            b.gemm(wp, xp, out=yp, workspace=wsp)
+        e1.record()
+        torch.cuda.synchronize()
+        sec = e0.elapsed_time(e1) * 1e-3 / reps
+        tf = 2.0 * Mp * Kp * Np / sec / 1e12
+        out["prefill"] = {"workload": "config 5: M=2048, K=7168, N=18432, 2.0 code bits/weight", "ms": round(sec * 1e3, 4),
+                          "value": round(tf, 2), "unit": "TFLOP/s",
+                          "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(canon, K, N, x_bits)
+    out["context"] = {"paper": "CCQ GEMV 8192x8192 M=1 at 2.06 bpw: 0.090 ms on one NVIDIA H20 (Table 4); another machine, not a target"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
