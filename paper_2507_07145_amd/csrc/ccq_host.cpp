@@ -249,7 +249,11 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
   if (ldx < L.K || ldy < L.N) return CCQ_ERR_BAD_PARAM;
   if (!aligned16(x) || !aligned16(y) || !aligned16(workspace) || ldx % 8 != 0 || ldy % 8 != 0) return CCQ_ERR_ALIGN;
 
-  // rows are processed in passes of at most kMaxSkinnyM
+  // many rows, narrow format only: the LDS-tiled MFMA kernel
+  const bool explicit_launch = launch && (launch->rows_per_wave_tiles || launch->waves_rows || launch->waves_k || launch->splits_k);
+  if (M > kMaxSkinnyM && L.tiles[kWide] == 0 && !explicit_launch) return launch_prefill(w, L, x, M, ldx, y, ldy, stream);
+
+  // otherwise rows are processed in passes of at most kMaxSkinnyM
   for (int m0 = 0; m0 < M; m0 += kMaxSkinnyM) {
     const int mc = std::min(kMaxSkinnyM, M - m0);
     SkinnyCall c;

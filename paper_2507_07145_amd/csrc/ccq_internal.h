@@ -88,4 +88,7 @@ struct SkinnyCall {
 };
 int launch_skinny(const SkinnyCall& c);
 
+// Large-M kernel for narrow-format weights (ccq_prefill.hip).
+int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
+
 }  // namespace ccq

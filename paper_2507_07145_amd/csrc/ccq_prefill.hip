@@ -1,0 +1,268 @@
+// Prefill (large M) fused dequantize-and-multiply for the narrow format
+// (L=6,N=4,S=3 + Code Cluster), gfx950.
+//
+// This is the one place where the work is a dense contraction: a workgroup owns
+// a 256 x BN tile of the output, walks K in steps of one 64-weight group, and per
+// step
+//   - copies the 256 x 64 activation tile to LDS,
+//   - decodes the BN x 64 weight tile to bf16 in LDS: the stored byte q becomes
+//     the 15-bit code c = round(q*alpha + beta) (Alg. 3) with one FMA against
+//     beta + 2^23, the four states are cut out by the shift list [9,6,3,0] and mask
+//     0x3F (Table 1) directly into the mantissa of fp32 128.0, and one FMA applies
+//     d = (w_uint - zp) * s (Alg. 3, last line): fma(128 + state, s, -(128 + zp) s)
+//     is exact in fp32, so the value written is the correctly rounded bf16 of the
+//     exact weight,
+//   - multiplies the two tiles with MFMA 32x32x16 bf16 (fp32 accumulators).
+// LDS tiles are double buffered; rows are padded by 16 bytes so that operand
+// reads (16 bytes per lane, 32 consecutive rows) spread over all banks.
+//
+// Workgroup-to-tile map: consecutive workgroup ids walk the M blocks first; with
+// 8 M blocks (M = 2048) every XCD keeps one 256-row slab of the activations in its
+// own L2 and streams the (small) code bytes.
+#include <hip/hip_runtime.h>
+
+#include "ccq_internal.h"
+
+namespace ccq {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+struct PrefillArgs {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const uint16_t* x;
+  uint16_t* y;
+  int64_t ldx, ldy;
+  int64_t row_tile_bytes, row_tile_scale_halfs;
+  int32_t M, N, K;
+  int32_t row_tiles;
+  int32_t m_blocks;
+  float zp;
+};
+
+constexpr int kBM = 256;          // output rows (activation rows) per workgroup
+constexpr int kBK = 64;           // one group per step
+constexpr int kLdsRow = kBK + 8;  // bf16 elements per padded LDS row (144 bytes)
+
+__device__ __forceinline__ uint32_t and_or_p(uint32_t a, uint32_t mask, uint32_t orv) {
+  uint32_t d;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(orv));
+  return d;
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne_p(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 b = __builtin_convertvector(v, bf16x2);  // round to nearest even
+  return __builtin_bit_cast(uint32_t, b);
+}
+
+// RTW = 16-row weight tiles decoded per wavefront per step; BN = 64 * RTW.
+template <int RTW>
+__global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
+  constexpr int BN = 64 * RTW;
+  constexpr int NT = BN / 64;  // 32-wide MFMA column tiles per wavefront (wave tile is 128 x BN/2)
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);                          // [2][kBM][kLdsRow]
+  uint16_t* Bs = As + 2 * kBM * kLdsRow;                                     // [2][BN][kLdsRow]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
+  const int m0 = m_block * kBM, n0 = n_block * BN;
+  const int kq = lane >> 4, nl = lane & 15;
+
+  // per-thread weight rows: tiles rt = wave*RTW + i of this block, row nl, quarter kq
+  const uint8_t* code_ptr[RTW];
+  const uint16_t* scale_ptr[RTW];
+  float al[RTW], be[RTW];
+#pragma unroll
+  for (int i = 0; i < RTW; ++i) {
+    int rtile = n0 / 16 + wave * RTW + i;
+    rtile = min(rtile, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
+    code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes + lane * 16;
+    scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + nl * 4;
+    al[i] = a.alpha[rtile * 16 + nl];
+    be[i] = a.beta[rtile * 16 + nl] + 8388608.f;
+  }
+  uint32_t c43 = 0x43000000u;
+  asm volatile("" : "+v"(c43));
+  const float neg_off = -(128.f + a.zp);
+
+  // activation copy: 8 chunks of 16 bytes per thread and step
+  const uint16_t* xrow[8];
+  bool xok[8];
+  int a_lds_off[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, col = c & 7;
+    xok[i] = m0 + row < a.M;
+    xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
+    a_lds_off[i] = row * kLdsRow + col * 8;
+  }
+
+  f32x16 acc[4][NT];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nsteps = a.K / kBK;
+  u32x4 areg[8];
+  u32x4 creg[RTW];
+  uint2 sreg[RTW];
+
+  auto load_a = [&](int step) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (xok[i]) v = *reinterpret_cast<const u32x4*>(xrow[i] + (int64_t)step * kBK);
+      areg[i] = v;
+    }
+  };
+  auto load_codes = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < RTW; ++i) {
+      creg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_ptr[i] + (int64_t)kt * kNarrowTileBytes));
+      sreg[i] = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs);
+    }
+  };
+  auto store_a = [&](int buf) {
+    uint16_t* dst = As + buf * kBM * kLdsRow;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = areg[i];
+  };
+  // decode group j (0..3) of the held k-tile into LDS buffer `buf`
+  auto decode_b = [&](int buf, int j) {
+    uint16_t* dst = Bs + buf * BN * kLdsRow;
+#pragma unroll
+    for (int i = 0; i < RTW; ++i) {
+      const uint32_t d = j == 0 ? creg[i].x : (j == 1 ? creg[i].y : (j == 2 ? creg[i].z : creg[i].w));
+      const uint32_t sw = (j >> 1) ? sreg[i].y : sreg[i].x;
+      const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+      const float c0 = neg_off * s;  // exact: 8-bit times 11-bit significand
+      uint32_t o[8];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], be[i]);
+        const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code
+        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, 0x003F0000u, c43)), s, c0);
+        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, 0x003F0000u, c43)), s, c0);
+        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, 0x003F0000u, c43)), s, c0);
+        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, 0x003F0000u, c43)), s, c0);
+        o[2 * b] = pack_bf16(w0, w1);
+        o[2 * b + 1] = pack_bf16(w2, w3);
+      }
+      uint16_t* p = dst + ((wave * RTW + i) * 16 + nl) * kLdsRow + kq * 16;
+      *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
+      *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
+    }
+  };
+
+  // prologue: step 0 into buffer 0
+  load_a(0);
+  load_codes(0);
+  store_a(0);
+  decode_b(0, 0);
+  __syncthreads();
+
+  for (int step = 0; step < nsteps; ++step) {
+    const int buf = step & 1;
+    const bool more = step + 1 < nsteps;
+    if (more) {
+      load_a(step + 1);
+      if (((step + 1) & 3) == 0) load_codes((step + 1) >> 2);
+    }
+    const uint16_t* Ab = As + buf * kBM * kLdsRow + (wm * 128 + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+    const uint16_t* Bb = Bs + buf * BN * kLdsRow + (wn * (BN / 2) + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[4], bfr[NT];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * kLdsRow + kk * 16));
+#pragma unroll
+      for (int j = 0; j < NT; ++j) bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + j * 32 * kLdsRow + kk * 16));
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      store_a(buf ^ 1);
+      switch ((step + 1) & 3) {
+        case 0: decode_b(buf ^ 1, 0); break;
+        case 1: decode_b(buf ^ 1, 1); break;
+        case 2: decode_b(buf ^ 1, 2); break;
+        default: decode_b(buf ^ 1, 3); break;
+      }
+    }
+    __syncthreads();
+  }
+
+  // epilogue: D[row][col], row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const float val = acc[i][j][r];  // by value: bit-casting the element lvalue itself reads element 0
+        if (m < a.M && n < a.N) a.y[(int64_t)m * a.ldy + n] = f32_to_bf16_rne_p(val);
+      }
+    }
+  }
+}
+
+int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
+  PrefillArgs a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.row_tile_bytes = L.row_tile_bytes;
+  a.row_tile_scale_halfs = L.row_tile_scale_halfs;
+  a.M = M;
+  a.N = L.N;
+  a.K = L.K;
+  a.row_tiles = L.row_tiles;
+  a.m_blocks = (M + kBM - 1) / kBM;
+  a.zp = L.zp[kNarrow];
+  // 192-column blocks when they tile N exactly (less tail imbalance on 256 CUs), else 256
+  const bool use192 = (L.N % 192 == 0);
+  const int BN = use192 ? 192 : 256;
+  const int n_blocks = (L.N + BN - 1) / BN;
+  const size_t lds = (size_t)2 * (kBM + BN) * kLdsRow * 2;
+  const void* kern = use192 ? reinterpret_cast<const void*>(ccq_prefill_kernel<3>) : reinterpret_cast<const void*>(ccq_prefill_kernel<4>);
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  dim3 grid((unsigned)(a.m_blocks * n_blocks)), block(256);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (use192) hipLaunchKernelGGL(ccq_prefill_kernel<3>, grid, block, lds, s, a);
+  else hipLaunchKernelGGL(ccq_prefill_kernel<4>, grid, block, lds, s, a);
+  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+  return CCQ_OK;
+}
+
+}  // namespace ccq
