@@ -114,6 +114,7 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=32, help="weight copies the step rotates over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--launch", type=str, default="", help="explicit decomposition RT,WR,WK,S for tuning (default: the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -133,11 +134,12 @@ def main() -> int:
     x_bits = synth.activations_bf16(M, K, synth.rng(2, 3))
     x = b.bf16_tensor(x_bits, dev)
     ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in weights]
-    ws_bytes = b.pack_info(weights[0].desc, M).workspace_bytes
+    launch = b.ccq_launch(*[int(v) for v in args.launch.split(",")]) if args.launch else None
+    ws_bytes = b.pack_info(weights[0].desc, M).workspace_bytes if launch is None else launch.splits_k * M * N * 4
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
     def make_step(w, y):
-        return lambda: b.gemm(w, x, out=y, workspace=ws)
+        return lambda: b.gemm(w, x, out=y, workspace=ws, launch=launch)
 
     steps_fns = [make_step(w, y) for w, y in zip(weights, ys)]
     wall, ev = time_steps(steps_fns, args.steps, args.warmup, dev)

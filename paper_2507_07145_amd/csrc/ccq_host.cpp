@@ -81,9 +81,10 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     if (ks <= 8) { d.WK = ks; d.S = 1; }
     else { d.WK = 8; d.S = std::min(kMaxSplitsK, ceil_div(ks, 8)); }
     d.WR = std::max(1, std::min(8 / d.WK, (int)std::min<int64_t>(8, L.row_tiles)));
-    if (units / d.WR >= 8192) d.RT = 2;
+    if (units / d.WR >= 8192 && L.tiles[kWide] == 0) d.RT = 2;
   } else {
-    d.RT = (L.row_tiles >= 2 && M <= 32) ? 2 : 1;  // 33..64 held rows: one row tile per wavefront
+    // two row tiles per wavefront only for the narrow format with at most 32 held rows (register budget)
+    d.RT = (L.row_tiles >= 2 && M <= 32 && L.tiles[kWide] == 0) ? 2 : 1;
     d.WR = (int)std::min<int64_t>(4, std::max(1, L.row_tiles / d.RT));
     d.WK = 1;
     int64_t row_blocks = (int64_t)ceil_div(L.row_tiles, d.RT * d.WR) * experts;

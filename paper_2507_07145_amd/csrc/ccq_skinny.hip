@@ -57,7 +57,8 @@ struct SkinnyArgs {
   int32_t KC[2];      // k-tiles per wavefront per staged chunk, per kind
   int32_t SG[2];      // groups of a k-tile staged at a time (= groups per tile unless LDS is tight; then KC = 1)
   int32_t WR, WK, S;
-  int32_t frag_cap;   // 16-byte fragments the LDS staging area holds; the start values follow it
+  int32_t frag_cap;   // 16-byte fragments the LDS staging area holds (per wavefront when one row is held); the start values follow it
+  int32_t cneg_cap;   // floats of start values per wavefront (one held row only; multiple of 4)
   float cneg[2];      // -(128 + zp) per kind
 };
 
@@ -91,9 +92,9 @@ __device__ __forceinline__ void load_tile(TileRegs<KIND>& r, const uint8_t* code
   r.c[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
   if constexpr (KIND == kWide) {
     r.c[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
-    u32x4 z = {0u, 0u, 0u, 0u};
-    if (lane < 48) z = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048));
-    r.c[2] = z;
+    // the third segment has entries for 48 lanes only; lanes 48..63 re-read lane 47's entry (their k-slots
+    // are staged as zero activations, and every bit pattern decodes to a finite value)
+    r.c[2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47 ? (lane - 47) * 16 : 0)));
   }
   const uint16_t* sp = scales_kind + (int64_t)kt * TR::SCALE_HALFS + (lane & 15) * TR::GPT;
   if constexpr (KIND == kNarrow) {
@@ -155,7 +156,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // consecutive k-tiles.
 //   lds_x    : fragments, index ((lg*T + t)*4 + kq)*MRT + m, 16 bytes each
 //   lds_cneg : fp32, index lg*(MT*16) + m
-template <int KIND, int MT, int MR>
+template <int KIND, int MT, int MR, bool META>
 __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, const uint16_t* x, int row_base, int rows_valid, int pg0,
                             int ng, int sg, int j0, int tid, int nthreads) {
   using TR = Traits<KIND>;
@@ -170,7 +171,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
     uint4 o = {0u, 0u, 0u, 0u};
     if (m < rows_valid) {
       const int pg = pg0 + (lg / sg) * TR::GPT + j0 + lg % sg;
-      const int g = a.meta ? a.meta[meta_base + pg] : pg;
+      const int g = META ? a.meta[meta_base + pg] : pg;  // a group map exists only for mixed formats
       const int64_t row = a.sorted_rows ? (int64_t)a.sorted_rows[row_base + m] : (int64_t)(row_base + m);
       const uint16_t* xr = x + row * a.ldx + (int64_t)g * kGroup;
       if constexpr (KIND == kNarrow) {
@@ -202,21 +203,20 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
     lds_x[f] = o;
   }
   __syncthreads();
-  const int ncneg = ng * MT * 16;
+  // start values for the rows that are really held; rows beyond them are never stored
+  const int ncneg = ng * MRT;
   const float factor = a.cneg[KIND];
   for (int i = tid; i < ncneg; i += nthreads) {
-    const int m = i % (MT * 16);
-    const int lg = i / (MT * 16);
+    const int m = i % MRT;
+    const int lg = i / MRT;
     float sum = 0.f;
-    if (m < MRT) {
-#pragma unroll 1
-      for (int tk = 0; tk < TR::T * 4; ++tk) {
-        const uint4 v = lds_x[(lg * TR::T * 4 + tk) * MRT + m];
-        sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
-               bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
-      }
+#pragma unroll
+    for (int tk = 0; tk < TR::T * 4; ++tk) {
+      const uint4 v = lds_x[(lg * TR::T * 4 + tk) * MRT + m];
+      sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
+             bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
     }
-    lds_cneg[i] = factor * sum;
+    lds_cneg[lg * (MT * 16) + m] = factor * sum;
   }
   __syncthreads();
 }
@@ -233,13 +233,20 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
     f32x4 P[RT][MT];
     f32x4 cin[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
+    for (int mt = 0; mt < MT; ++mt) {
+      // With at most 4 held rows only accumulator rows 0..3 (lanes 0..15) are ever stored; the other
+      // lanes' rows of the product may hold anything, so they skip the read.
+      if constexpr (MR == 1) cin[mt][0] = lds_cneg[lg];  // one float per group; rows 1..3 of the tile are never stored
+      else if (MR == 16 || kq == 0) cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
+    }
 #pragma unroll
     for (int t = 0; t < TR::T; ++t) {
       bf16x8 xf[MT];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        uint4 v = {0u, 0u, 0u, 0u};
+        // Rows of the product are independent: activation lanes of rows that are not held feed rows
+        // that are never stored, so they are left as they are instead of being zeroed.
+        uint4 v;
         if (MR == 16 || m < MR) v = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + mt * 16 + m];
         xf[mt] = __builtin_bit_cast(bf16x8, v);
       }
@@ -275,7 +282,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
 // activations of a chunk (KC k-tiles for each of the WK wavefronts along K) are
 // staged in LDS, then every wavefront walks its own tiles with a register ring
 // of D tiles in flight.
-template <int KIND, int MT, int MR, int RT>
+template <int KIND, int MT, int MR, int RT, bool META>
 __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
                                const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
@@ -288,29 +295,35 @@ __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[R
   for (int c0 = A; c0 < B; c0 += CH) {
     const int cend = min(c0 + CH, B);
     const int k0 = min(c0 + wk * KC, cend), k1 = min(k0 + KC, cend);
+    // Register ring of D tiles.  All loads inside the steady loop are unconditional (a load under a
+    // branch would have to be waited for at once); only the last group of tiles is processed without
+    // prefetching, and a ragged last group re-reads its last tile.
     TileRegs<KIND> buf[D][RT];
-    if (active) {
+    const int n = k1 - k0, ngroups = (n + D - 1) / D;
+    if (active && n > 0) {
 #pragma unroll
-      for (int i = 0; i < D; ++i)
-        if (k0 + i < k1) {
+      for (int i = 0; i < D; ++i) {
 #pragma unroll
-          for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], k0 + i, lane);
-        }
+        for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], k0 + min(i, n - 1), lane);
+      }
     }
     __syncthreads();  // the previous chunk's fragments are no longer read
-    stage_chunk<KIND, MT, MR>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, (cend - c0) * TR::GPT, TR::GPT, 0, tid, nthreads);
-    if (active) {
-      for (int kt = k0; kt < k1; kt += D) {
+    stage_chunk<KIND, MT, MR, META>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, (cend - c0) * TR::GPT, TR::GPT, 0, tid, nthreads);
+    if (active && n > 0) {
+      for (int j = 0; j + 1 < ngroups; ++j) {
 #pragma unroll
         for (int i = 0; i < D; ++i) {
-          if (kt + i < k1) {
-            process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (kt + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
-            if (kt + i + D < k1) {
+          process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (k0 + j * D + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
 #pragma unroll
-              for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], kt + i + D, lane);
-            }
-          }
+          for (int rt = 0; rt < RT; ++rt)
+            load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], k0 + min((j + 1) * D + i, n - 1), lane);
         }
+      }
+      const int jl = ngroups - 1;
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        if (jl * D + i < n)
+          process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (k0 + jl * D + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
       }
     }
   }
@@ -319,7 +332,7 @@ __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[R
 // When many activation rows are held, the fragments of a whole k-tile do not fit
 // in LDS next to other workgroups: every wavefront along K then owns one k-tile
 // per step and its groups are staged SG at a time.
-template <int KIND, int MT, int MR, int RT, int SG, int J0>
+template <int KIND, int MT, int MR, int RT, int SG, int J0, bool META>
 struct SubSteps {
   static __device__ __forceinline__ void run(const SkinnyArgs& a, const TileRegs<KIND> (&r)[RT], bool has, const float (&al)[RT],
                                              const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg, const uint16_t* x,
@@ -328,15 +341,15 @@ struct SubSteps {
     using TR = Traits<KIND>;
     if constexpr (J0 < TR::GPT) {
       __syncthreads();  // the previous step's fragments are no longer read
-      stage_chunk<KIND, MT, MR>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, ntiles * SG, SG, J0, tid, nthreads);
+      stage_chunk<KIND, MT, MR, META>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, ntiles * SG, SG, J0, tid, nthreads);
       if (has) process_tile<KIND, MT, MR, RT, J0, SG>(r, wk * SG, lds_x, lds_cneg, al, be, acc, lane, c4300);
-      SubSteps<KIND, MT, MR, RT, SG, J0 + SG>::run(a, r, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid,
+      SubSteps<KIND, MT, MR, RT, SG, J0 + SG, META>::run(a, r, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid,
                                                    nthreads, c4300);
     }
   }
 };
 
-template <int KIND, int MT, int MR, int RT, int SG>
+template <int KIND, int MT, int MR, int RT, int SG, bool META>
 __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
                                 const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                 const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
@@ -357,7 +370,7 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(nxt[rt], codes_rt[rt], scales_rt[rt], c0 + a.WK + wk, lane);
     }
-    SubSteps<KIND, MT, MR, RT, SG, 0>::run(a, cur, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid, nthreads,
+    SubSteps<KIND, MT, MR, RT, SG, 0, META>::run(a, cur, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid, nthreads,
                                            c4300);
     if (has_next) {
 #pragma unroll
@@ -366,7 +379,113 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
   }
 }
 
-template <int KIND, int MT, int MR, int RT>
+// ---- one held row (M = 1): wavefront-private staging ------------------------
+// Every wavefront stages the activations of its own k-tiles in a private LDS
+// region, so no workgroup barrier is needed before the contraction and the
+// wavefronts of a workgroup drift apart instead of waiting for each other.
+//   lds_x   : fragments, index (lg*T + t)*4 + kq, 16 bytes each
+//   lds_cneg: one float per group
+template <int KIND, bool META>
+__device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, const uint16_t* xr, int pg0, int ng, int lane) {
+  using TR = Traits<KIND>;
+  const int meta_base = (KIND == kWide) ? a.groups_narrow : 0;
+  const int nfrag = ng * TR::T * 4;
+  for (int f = lane; f < nfrag; f += 64) {
+    const int kq = f & 3;
+    const int t = (f >> 2) % TR::T;
+    const int lg = f / (4 * TR::T);
+    const int pg = pg0 + lg;
+    const int g = META ? a.meta[meta_base + pg] : pg;  // a group map exists only for mixed formats
+    const uint16_t* xg = xr + (int64_t)g * kGroup;
+    uint4 o = {0u, 0u, 0u, 0u};
+    if constexpr (KIND == kNarrow) {
+      const uint4 v = *reinterpret_cast<const uint4*>(xg + 16 * kq + 8 * t);
+      o.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);
+      o.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
+      o.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
+      o.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
+    } else {
+      const int ja = 6 * kq + 2 * t;
+      uint32_t h[6];
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+          const int jj = ja + which, wi = 3 * jj + i;
+          h[2 * i + which] = (jj <= 21 && wi < kGroup) ? (uint32_t)xg[wi] : 0u;
+        }
+      }
+      o.x = h[0] | (h[1] << 16);
+      o.y = h[2] | (h[3] << 16);
+      o.z = h[4] | (h[5] << 16);
+    }
+    lds_x[f] = o;
+    if constexpr (KIND == kNarrow) {
+      // the 8 fragments of a group sit in 8 neighbouring lanes: add them up with DPP, fixed order
+      float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
+                  ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x141, 0xF, 0xF, true));  // mirror in 8 lanes
+      if ((f & 7) == 0) lds_cneg[lg] = a.cneg[KIND] * sum;
+    }
+  }
+  if constexpr (KIND == kWide) {
+    // 12 fragments per group: one lane per group adds them up from LDS (same wavefront: LDS operations stay in order)
+    __builtin_amdgcn_wave_barrier();
+    for (int lg = lane; lg < ng; lg += 64) {
+      float sum = 0.f;
+#pragma unroll
+      for (int tk = 0; tk < TR::T * 4; ++tk) {
+        const uint4 v = lds_x[lg * TR::T * 4 + tk];
+        sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
+               bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
+      }
+      lds_cneg[lg] = a.cneg[KIND] * sum;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+}
+
+template <int KIND, int RT, bool META>
+__device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
+                                 const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][1], uint4* lds_x, float* lds_cneg,
+                                 const uint16_t* xr, int split, int wk, int lane, uint32_t c4300) {
+  using TR = Traits<KIND>;
+  constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);
+  if (!active) return;
+  const int tiles = a.tiles[KIND];
+  const int A = (int)(((int64_t)split * tiles) / a.S), B = (int)(((int64_t)(split + 1) * tiles) / a.S);
+  const int k0 = A + (int)(((int64_t)(B - A) * wk) / a.WK), k1 = A + (int)(((int64_t)(B - A) * (wk + 1)) / a.WK);
+  const int CT = a.KC[KIND];  // k-tiles the private region holds
+  for (int c0 = k0; c0 < k1; c0 += CT) {
+    const int cend = min(c0 + CT, k1);
+    TileRegs<KIND> buf[D][RT];
+    const int n = cend - c0, ngroups = (n + D - 1) / D;
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], c0 + min(i, n - 1), lane);
+    }
+    stage_private<KIND, META>(lds_x, lds_cneg, a, xr, c0 * TR::GPT, n * TR::GPT, lane);
+    for (int j = 0; j + 1 < ngroups; ++j) {
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        process_tile<KIND, 1, 1, RT, 0, TR::GPT>(buf[i], (j * D + i) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], c0 + min((j + 1) * D + i, n - 1), lane);
+      }
+    }
+    const int jl = ngroups - 1;
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      if (jl * D + i < n) process_tile<KIND, 1, 1, RT, 0, TR::GPT>(buf[i], (jl * D + i) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+    }
+    __builtin_amdgcn_wave_barrier();  // the region is rewritten by the next chunk
+  }
+}
+
+template <int KIND, int MT, int MR, int RT, bool META>
 __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
                                          const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                          const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
@@ -376,26 +495,27 @@ __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&c
     const int sg = a.SG[KIND];
     if (sg != TR::GPT) {
       if (sg == 1)
-        run_kind_groups<KIND, MT, MR, RT, 1>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
+        run_kind_groups<KIND, MT, MR, RT, 1, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
                                              tid, nthreads, c4300);
       else if (sg == 2)
-        run_kind_groups<KIND, MT, MR, RT, 2>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
+        run_kind_groups<KIND, MT, MR, RT, 2, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
                                              tid, nthreads, c4300);
       else
-        run_kind_groups<KIND, MT, MR, RT, 4>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
+        run_kind_groups<KIND, MT, MR, RT, 4, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
                                              tid, nthreads, c4300);
       return;
     }
   }
-  run_kind_tiles<KIND, MT, MR, RT>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane, tid,
+  run_kind_tiles<KIND, MT, MR, RT, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane, tid,
                                    nthreads, c4300);
 }
 
 template <int MT, int MR, int RT, int FM>
-__global__ void __launch_bounds__(MT >= 2 ? 512 : 1024) ccq_skinny_kernel(const SkinnyArgs a) {
+__global__ void __launch_bounds__(MT == 4 ? 256 : (MT == 2 ? 512 : 1024)) ccq_skinny_kernel(const SkinnyArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, nthreads = blockDim.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps tile indices and base pointers in scalar registers
   const int wr = wave % a.WR, wk = wave / a.WR;
   const int split = blockIdx.y, e = blockIdx.z;
 
@@ -447,33 +567,58 @@ __global__ void __launch_bounds__(MT >= 2 ? 512 : 1024) ccq_skinny_kernel(const 
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if constexpr ((FM & 1) != 0)
-      run_kind<kNarrow, MT, MR, RT>(a, codes_n, scales_n, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
+    if constexpr (MR == 1) {
+      // one held row: private staging region of this wavefront (fragments, then start values)
+      uint4* my_x = lds_x + (size_t)wave * (a.frag_cap + a.cneg_cap / 4);
+      float* my_cneg = reinterpret_cast<float*>(my_x + a.frag_cap);
+      const uint16_t* xr = a.x + (a.sorted_rows ? (int64_t)a.sorted_rows[off0 + m0] : (int64_t)(off0 + m0)) * a.ldx;
+      if constexpr ((FM & 1) != 0) run_kind_private<kNarrow, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, c4300);
+      if constexpr ((FM & 2) != 0) run_kind_private<kWide, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, c4300);
+    } else {
+      if constexpr ((FM & 1) != 0)
+        run_kind<kNarrow, MT, MR, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
+                                      nthreads, c4300);
+      if constexpr ((FM & 2) != 0)
+        run_kind<kWide, MT, MR, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
                                     nthreads, c4300);
-    if constexpr ((FM & 2) != 0)
-      run_kind<kWide, MT, MR, RT>(a, codes_w, scales_w, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
-                                  nthreads, c4300);
+    }
 
     // ---- reduce the K-splits of this workgroup through LDS (fixed order) ----
     if (a.WK > 1) {
       __syncthreads();
-      f32x4* red = reinterpret_cast<f32x4*>(smem);
-      if (wk > 0) {
+      if constexpr (MR == 1) {
+        // one held row: only element 0 of lanes 0..15 carries a result
+        float* red = reinterpret_cast<float*>(smem);
+        if (wk > 0 && lane < 16) {
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
+          for (int rt = 0; rt < RT; ++rt) red[(((wk - 1) * a.WR + wr) * RT + rt) * 16 + lane] = acc[rt][0][0];
+        }
+        __syncthreads();
+        if (wk == 0 && lane < 16) {
+          for (int k = 1; k < a.WK; ++k) {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) red[((((wk - 1) * a.WR + wr) * RT + rt) * MT + mt) * 64 + lane] = acc[rt][mt];
-      }
-      __syncthreads();
-      if (wk == 0) {
-        for (int k = 1; k < a.WK; ++k) {
+            for (int rt = 0; rt < RT; ++rt) acc[rt][0][0] += red[(((k - 1) * a.WR + wr) * RT + rt) * 16 + lane];
+          }
+        }
+      } else {
+        f32x4* red = reinterpret_cast<f32x4*>(smem);
+        if (wk > 0) {
 #pragma unroll
           for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              const f32x4 v = red[((((k - 1) * a.WR + wr) * RT + rt) * MT + mt) * 64 + lane];
-              acc[rt][mt] += v;
-            }
+            for (int mt = 0; mt < MT; ++mt) red[((((wk - 1) * a.WR + wr) * RT + rt) * MT + mt) * 64 + lane] = acc[rt][mt];
+        }
+        __syncthreads();
+        if (wk == 0) {
+          for (int k = 1; k < a.WK; ++k) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) {
+                const f32x4 v = red[((((k - 1) * a.WR + wr) * RT + rt) * MT + mt) * 64 + lane];
+                acc[rt][mt] += v;
+              }
+          }
         }
       }
     }
@@ -488,7 +633,7 @@ __global__ void __launch_bounds__(MT >= 2 ? 512 : 1024) ccq_skinny_kernel(const 
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
+          for (int r = 0; r < (MR == 1 ? 1 : 4); ++r) {
             const int m = mt * 16 + 4 * kq + r;
             if (m < rows_valid) {
               const int64_t prow = (int64_t)off0 + m0 + m;
@@ -527,9 +672,12 @@ static SkinnyKernel pick_fm(int fm) {
   }
 }
 
+// Two row tiles per wavefront are built for the narrow format only: with the wide format the
+// register file does not hold both tiles' code registers and the compiler would spill to scratch.
 template <int MT, int MR>
 static SkinnyKernel pick_rt(int rt, int fm) {
-  return rt == 1 ? pick_fm<MT, MR, 1>(fm) : pick_fm<MT, MR, 2>(fm);
+  if (rt == 2) return ccq_skinny_kernel<MT, MR, 2, 1>;
+  return pick_fm<MT, MR, 1>(fm);
 }
 
 static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm) {
@@ -539,7 +687,7 @@ static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm) {
     return pick_rt<1, 16>(rt, fm);
   }
   if (mt == 2) return pick_rt<2, 16>(rt, fm);
-  return pick_fm<4, 16, 1>(fm);  // 64 held rows: one row tile per wavefront (two would spill registers)
+  return pick_fm<4, 16, 1>(fm);
 }
 
 int launch_skinny(const SkinnyCall& c) {
@@ -552,7 +700,8 @@ int launch_skinny(const SkinnyCall& c) {
   const int mrt = mt == 1 ? mr : mt * 16;
   const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
   if (mt >= 2 && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
-  if (mt == 4 && d.RT != 1) return CCQ_ERR_BAD_PARAM;
+  if (d.RT == 2 && (mt == 4 || fm != 1)) return CCQ_ERR_BAD_PARAM;  // two row tiles per wavefront: narrow format, at most 32 held rows
+  if (mt == 4 && d.WR * d.WK > 4) return CCQ_ERR_BAD_PARAM;            // 64 held rows: built for at most 256 threads
 
   SkinnyArgs a;
   a.codes = static_cast<const uint8_t*>(c.w->codes);
@@ -611,7 +760,26 @@ int launch_skinny(const SkinnyCall& c) {
     cneg_cap = std::max<int64_t>(cneg_cap, groups_staged * mt * 16);
   }
   a.frag_cap = (int)frag_cap;
+  a.cneg_cap = 0;
   int64_t lds = frag_cap * 16 + cneg_cap * 4;
+  if (mr == 1 && mt == 1) {
+    // one held row: every wavefront has a private region for up to KC k-tiles (about 6 KiB)
+    const int waves = d.WR * d.WK;
+    int64_t pf = 0, pc = 0;
+    for (int k = 0; k < 2; ++k) {
+      if (L.tiles[k] == 0) continue;
+      const int gpt = k == kNarrow ? kNarrowGroupsPerTile : kWideGroupsPerTile, T = k == kNarrow ? 2 : 3;
+      const int per_wave = ((L.tiles[k] + d.S - 1) / d.S + d.WK - 1) / d.WK;
+      const int fit = std::max(1, (6 * 1024) / (gpt * T * 4 * 16));
+      a.KC[k] = std::max(1, std::min(per_wave, fit));
+      a.SG[k] = gpt;
+      pf = std::max<int64_t>(pf, (int64_t)a.KC[k] * gpt * T * 4);
+      pc = std::max<int64_t>(pc, (int64_t)((a.KC[k] * gpt + 3) / 4) * 4);
+    }
+    a.frag_cap = (int)pf;
+    a.cneg_cap = (int)pc;
+    lds = (int64_t)waves * (pf * 16 + pc * 4);
+  }
   if (d.WK > 1) lds = std::max<int64_t>(lds, (int64_t)(d.WK - 1) * d.WR * d.RT * mt * 64 * 16);
   if (lds > 150 * 1024) return CCQ_ERR_BAD_PARAM;
 
