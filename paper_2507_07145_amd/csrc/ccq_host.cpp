@@ -72,7 +72,7 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
   Decomp d;
   const int nt = L.tiles[kNarrow] + L.tiles[kWide];  // k-tiles per row tile
   const int64_t units = (int64_t)L.row_tiles * experts;  // row tiles over all experts
-  if (M <= 4) {
+  if (M == 1) {
     // bandwidth-bound GEMV: many wavefronts, K split inside the workgroup so
     // that no workspace pass is needed
     d.RT = 1;
@@ -81,7 +81,6 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     if (ks <= 8) { d.WK = ks; d.S = 1; }
     else { d.WK = 8; d.S = std::min(kMaxSplitsK, ceil_div(ks, 8)); }
     d.WR = std::max(1, std::min(8 / d.WK, (int)std::min<int64_t>(8, L.row_tiles)));
-    if (units / d.WR >= 8192 && L.tiles[kWide] == 0) d.RT = 2;
   } else {
     // two row tiles per wavefront only for the narrow format with at most 32 held rows (register budget)
     d.RT = (L.row_tiles >= 2 && M <= 32 && L.tiles[kWide] == 0) ? 2 : 1;

@@ -221,41 +221,59 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
   __syncthreads();
 }
 
-template <int KIND, int MT, int MR, int RT, int J0, int NJ>
-__device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int lg0, const uint4* lds_x, const float* lds_cneg, const float (&al)[RT],
-                                             const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, uint32_t c4300) {
+// Activation fragments and accumulator start values of one group, read from LDS.
+template <int KIND, int MT, int MR>
+struct GroupOperands {
+  uint4 x[Traits<KIND>::T][MT];
+  f32x4 cin[MT];
+};
+
+// Rows of the product are independent: an activation lane of a row that is not held only feeds a row
+// of the product that is never stored.  With a single held row (MR = 1) such lanes skip the LDS read: the
+// operand registers are zeroed once per tile and only the lanes of row 0 are ever overwritten.
+template <int KIND, int MT, int MR>
+__device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>& g, int lg, const uint4* lds_x, const float* lds_cneg, int lane) {
   using TR = Traits<KIND>;
   constexpr int MRT = (MT == 1) ? MR : MT * 16;
   const int kq = lane >> 4, m = lane & 15;
 #pragma unroll
-  for (int j = J0; j < J0 + NJ; ++j) {
-    const int lg = lg0 + (j - J0);
-    f32x4 P[RT][MT];
-    f32x4 cin[MT];
+  for (int mt = 0; mt < MT; ++mt) {
+    if constexpr (MR == 1) g.cin[mt][0] = lds_cneg[lg];  // one float per group; elements 1..3 keep their value
+    else g.cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
+  }
+#pragma unroll
+  for (int t = 0; t < TR::T; ++t) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      // With at most 4 held rows only accumulator rows 0..3 (lanes 0..15) are ever stored; the other
-      // lanes' rows of the product may hold anything, so they skip the read.
-      if constexpr (MR == 1) cin[mt][0] = lds_cneg[lg];  // one float per group; rows 1..3 of the tile are never stored
-      else if (MR == 16 || kq == 0) cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
+      if constexpr (MR == 16) g.x[t][mt] = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + mt * 16 + m];
+      else if (m < MR) g.x[t][mt] = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + m];
     }
+  }
+}
+
+template <int KIND, int MT, int MR, int RT, int J0, int NJ>
+__device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int lg0, const uint4* lds_x, const float* lds_cneg, const float (&al)[RT],
+                                             const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, uint32_t c4300) {
+  using TR = Traits<KIND>;
+  GroupOperands<KIND, MT, MR> cur;
+  if constexpr (MR == 1) {
+#pragma unroll
+    for (int t = 0; t < TR::T; ++t) cur.x[t][0] = uint4{0u, 0u, 0u, 0u};
+    cur.cin[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int j = J0; j < J0 + NJ; ++j) {
+    const int lg = lg0 + (j - J0);
+    read_group_operands<KIND, MT, MR>(cur, lg, lds_x, lds_cneg, lane);
+    f32x4 P[RT][MT];
 #pragma unroll
     for (int t = 0; t < TR::T; ++t) {
-      bf16x8 xf[MT];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        // Rows of the product are independent: activation lanes of rows that are not held feed rows
-        // that are never stored, so they are left as they are instead of being zeroed.
-        uint4 v;
-        if (MR == 16 || m < MR) v = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + mt * 16 + m];
-        xf[mt] = __builtin_bit_cast(bf16x8, v);
-      }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], c4300);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          P[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mt], wf, t == 0 ? cin[mt] : P[rt][mt], 0, 0, 0);
+          P[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.x[t][mt]), wf, t == 0 ? cur.cin[mt] : P[rt][mt], 0, 0, 0);
       }
     }
 #pragma unroll
@@ -511,7 +529,7 @@ __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&c
 }
 
 template <int MT, int MR, int RT, int FM>
-__global__ void __launch_bounds__(MT == 4 ? 256 : (MT == 2 ? 512 : 1024)) ccq_skinny_kernel(const SkinnyArgs a) {
+__global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 1024)) ccq_skinny_kernel(const SkinnyArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int lane = tid & 63;
@@ -682,8 +700,7 @@ static SkinnyKernel pick_rt(int rt, int fm) {
 
 static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm) {
   if (mt == 1) {
-    if (mr == 1) return pick_rt<1, 1>(rt, fm);
-    if (mr == 4) return pick_rt<1, 4>(rt, fm);
+    if (mr == 1) return pick_fm<1, 1, 1>(fm);
     return pick_rt<1, 16>(rt, fm);
   }
   if (mt == 2) return pick_rt<2, 16>(rt, fm);
@@ -696,11 +713,11 @@ int launch_skinny(const SkinnyCall& c) {
   const int rows = std::min(std::max(c.m_tile_hint, 1), kMaxSkinnyM);
   int mt = (rows + 15) / 16;
   if (mt == 3) mt = 4;
-  const int mr = mt > 1 ? 16 : (rows == 1 ? 1 : (rows <= 4 ? 4 : 16));
+  const int mr = (mt == 1 && rows == 1) ? 1 : 16;  // rows of the first activation tile that are staged
   const int mrt = mt == 1 ? mr : mt * 16;
   const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
-  if (mt >= 2 && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
-  if (d.RT == 2 && (mt == 4 || fm != 1)) return CCQ_ERR_BAD_PARAM;  // two row tiles per wavefront: narrow format, at most 32 held rows
+  if ((mt >= 2 || mr == 1) && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
+  if (d.RT == 2 && (mt == 4 || mr == 1 || fm != 1)) return CCQ_ERR_BAD_PARAM;  // two row tiles per wavefront: narrow format, 2..32 held rows
   if (mt == 4 && d.WR * d.WK > 4) return CCQ_ERR_BAD_PARAM;            // 64 held rows: built for at most 256 threads
 
   SkinnyArgs a;

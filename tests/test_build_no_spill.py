@@ -1,0 +1,37 @@
+"""Build guard: no kernel of the library may spill registers to scratch memory (kernels that did
+produced wrong results on the device in some launch shapes), and no packed-fp32
+vector instruction may appear in the generated code."""
+import glob
+import os
+import re
+import subprocess
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2507_07145_amd", "csrc")
+
+
+def _compile(src, *extra):
+    cmd = ["/opt/rocm/bin/hipcc", "-O3", "--offload-arch=gfx950", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "--cuda-device-only", "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra, src]
+    return subprocess.run(cmd, capture_output=True, text=True)
+
+
+def test_no_kernel_spills_to_scratch(tmp_path):
+    for src in sorted(glob.glob(os.path.join(CSRC, "*.hip"))):
+        res = _compile(src, "-c", "-o", str(tmp_path / "o.o"), "-Rpass-analysis=kernel-resource-usage")
+        assert res.returncode == 0, res.stderr[-2000:]
+        names = re.findall(r"Function Name: (\S+)", res.stderr)
+        scratch = [int(v) for v in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", res.stderr)]
+        assert names and len(names) == len(scratch)
+        spilling = [n for n, s in zip(names, scratch) if s != 0]
+        assert not spilling, f"{os.path.basename(src)}: kernels using scratch: {spilling}"
+
+
+def test_no_packed_fp32_instructions(tmp_path):
+    for src in sorted(glob.glob(os.path.join(CSRC, "*.hip"))):
+        out = tmp_path / "k.s"
+        res = _compile(src, "-S", "-o", str(out))
+        assert res.returncode == 0, res.stderr[-2000:]
+        asm = out.read_text()
+        assert "v_mfma" in asm
+        assert not re.search(r"\bv_pk_(add|mul|fma)_f32\b", asm)
