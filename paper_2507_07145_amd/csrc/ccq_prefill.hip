@@ -50,11 +50,9 @@ constexpr int kBM = 256;          // output rows (activation rows) per workgroup
 constexpr int kBK = 64;           // one group per step
 constexpr int kLdsRow = kBK + 8;  // bf16 elements per padded LDS row (144 bytes)
 
-__device__ __forceinline__ uint32_t and_or_p(uint32_t a, uint32_t mask, uint32_t orv) {
-  uint32_t d;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(orv));
-  return d;
-}
+// (a & mask) | orv in plain C (no instruction is written as inline assembly: the compiler's hazard
+// recognizer does not see those); mask and orv are kept in registers so v_and_or_b32 is selected.
+__device__ __forceinline__ uint32_t and_or_p(uint32_t a, uint32_t mask, uint32_t orv) { return (a & mask) | orv; }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne_p(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
@@ -97,8 +95,8 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
     al[i] = a.alpha[rtile * 16 + nl];
     be[i] = a.beta[rtile * 16 + nl] + 8388608.f;
   }
-  uint32_t c43 = 0x43000000u;
-  asm volatile("" : "+v"(c43));
+  uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
+  asm volatile("" : "+v"(c43), "+s"(smask));
   const float neg_off = -(128.f + a.zp);
 
   // activation copy: 8 chunks of 16 bytes per thread and step
@@ -160,10 +158,10 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
       for (int b = 0; b < 4; ++b) {
         const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], be[i]);
         const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code
-        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, 0x003F0000u, c43)), s, c0);
-        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, 0x003F0000u, c43)), s, c0);
-        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, 0x003F0000u, c43)), s, c0);
-        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, 0x003F0000u, c43)), s, c0);
+        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, smask, c43)), s, c0);
+        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, smask, c43)), s, c0);
+        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, smask, c43)), s, c0);
+        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, smask, c43)), s, c0);
         o[2 * b] = pack_bf16(w0, w1);
         o[2 * b + 1] = pack_bf16(w2, w3);
       }

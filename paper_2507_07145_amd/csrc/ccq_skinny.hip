@@ -24,6 +24,13 @@
 //   C/D            : rows m = 4kq .. 4kq+3, column n = l % 16
 // so all four accumulator values of a lane share the output row n of W and one
 // group scale serves them.
+//
+// With a single activation row (M = 1) the 16x16x32 shape would spend 15/16 of the matrix-core time
+// on rows that do not exist, and that instruction runs at half the rate of the 32x32x16 shape on
+// this chip.  The M = 1 path uses MFMA 4x4x4 bf16 instead (16 independent 4x4 blocks per wavefront,
+// block = lane / 4): lane l still owns row n = l % 16 and quarter kq = l / 16, feeds 4 weights per
+// instruction as column l % 4 of its block, and receives in accumulator element 0 the partial sum of
+// its own row over its own quarter; the four quarters are added across lanes at the end.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -35,6 +42,8 @@ namespace ccq {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 
 struct SkinnyArgs {
   const uint8_t* codes;
@@ -75,11 +84,11 @@ template <int KIND> struct TileRegs {
   uint32_t s[Traits<KIND>::GPT / 2];
 };
 
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
-  uint32_t d;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(orv));
-  return d;
-}
+// (a & mask) | orv.  Plain C on purpose: an instruction written as inline assembly is invisible to the
+// compiler's hazard recognizer, and a hand-written v_and_or_b32 whose result fed an MFMA one instruction
+// later gave wrong results on the device.  The callers keep mask and orv in registers (not literals) so
+// that the compiler can still select the single v_and_or_b32.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) { return (a & mask) | orv; }
 
 __device__ __forceinline__ uint32_t dword_of(const u32x4& v, int j) {
   return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
@@ -106,9 +115,16 @@ __device__ __forceinline__ void load_tile(TileRegs<KIND>& r, const uint8_t* code
   }
 }
 
+// Constants of the decode, held in registers: bf16 128.0 twice, and the two-halfword state masks of
+// the narrow (0x3F) and wide (0xF) formats (Table 1).
+struct DecodeConsts {
+  uint32_t c4300;
+  uint32_t mask[2];
+};
+
 // Weight fragment (8 bf16 integers 128 + state) of group j, k-step t.
 template <int KIND>
-__device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, int t, float al, float be_magic, uint32_t c4300) {
+__device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, int t, float al, float be_magic, uint32_t c4300, uint32_t mask) {
   uint4 o;
   if constexpr (KIND == kNarrow) {
     // two clustered bytes -> two 15-bit codes (Alg. 3), side by side in one register
@@ -117,17 +133,17 @@ __device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, in
     const float fb = __builtin_fmaf((float)((d >> (16 * t + 8)) & 0xFFu), al, be_magic);
     const uint32_t yy = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, fb), __builtin_bit_cast(uint32_t, fa), 0x05040100u);
     // states by the shift list [9,6,3,0], mask 0x3F (Table 1), for both codes at once
-    o.x = and_or(yy >> 9, 0x003F003Fu, c4300);
-    o.y = and_or(yy >> 6, 0x003F003Fu, c4300);
-    o.z = and_or(yy >> 3, 0x003F003Fu, c4300);
-    o.w = and_or(yy, 0x003F003Fu, c4300);
+    o.x = and_or(yy >> 9, mask, c4300);
+    o.y = and_or(yy >> 6, mask, c4300);
+    o.z = and_or(yy >> 3, mask, c4300);
+    o.w = and_or(yy, mask, c4300);
   } else {
     // two 8-bit codes of (L=4,N=3,S=2); shift list [4,2,0], mask 0xF (Table 1)
     const uint32_t d = dword_of(r.c[t], j >> 1);
     const uint32_t p = __builtin_amdgcn_perm(0u, d, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // {0,b,0,a}
-    o.x = and_or(p >> 4, 0x000F000Fu, c4300);
-    o.y = and_or(p >> 2, 0x000F000Fu, c4300);
-    o.z = and_or(p, 0x000F000Fu, c4300);
+    o.x = and_or(p >> 4, mask, c4300);
+    o.y = and_or(p >> 2, mask, c4300);
+    o.z = and_or(p, mask, c4300);
     o.w = c4300;  // unused k-slots (their activations are staged as zero)
   }
   return __builtin_bit_cast(bf16x8, o);
@@ -229,8 +245,9 @@ struct GroupOperands {
 };
 
 // Rows of the product are independent: an activation lane of a row that is not held only feeds a row
-// of the product that is never stored.  With a single held row (MR = 1) such lanes skip the LDS read: the
-// operand registers are zeroed once per tile and only the lanes of row 0 are ever overwritten.
+// of the product that is never stored.  With a single held row (MR = 1, MFMA 4x4x4) only the lanes that
+// carry row 0 of a 4x4 block read; the operand registers are zeroed once per tile and the other lanes
+// are never overwritten.
 template <int KIND, int MT, int MR>
 __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>& g, int lg, const uint4* lds_x, const float* lds_cneg, int lane) {
   using TR = Traits<KIND>;
@@ -238,7 +255,7 @@ __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>&
   const int kq = lane >> 4, m = lane & 15;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    if constexpr (MR == 1) g.cin[mt][0] = lds_cneg[lg];  // one float per group; elements 1..3 keep their value
+    if constexpr (MR == 1) g.cin[mt][0] = lds_cneg[lg * 4 + kq];  // one float per group and quarter; elements 1..3 keep their value
     else g.cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
   }
 #pragma unroll
@@ -246,14 +263,14 @@ __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>&
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       if constexpr (MR == 16) g.x[t][mt] = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + mt * 16 + m];
-      else if (m < MR) g.x[t][mt] = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + m];
+      else if ((lane & 3) == 0) g.x[t][mt] = lds_x[(lg * TR::T + t) * 4 + kq];  // row 0 of each 4x4 block
     }
   }
 }
 
 template <int KIND, int MT, int MR, int RT, int J0, int NJ>
 __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int lg0, const uint4* lds_x, const float* lds_cneg, const float (&al)[RT],
-                                             const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, uint32_t c4300) {
+                                             const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, DecodeConsts dc) {
   using TR = Traits<KIND>;
   GroupOperands<KIND, MT, MR> cur;
   if constexpr (MR == 1) {
@@ -270,10 +287,20 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
     for (int t = 0; t < TR::T; ++t) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], c4300);
+        const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], dc.c4300, dc.mask[KIND]);
+        if constexpr (MR == 1) {
+          // two 4x4x4 steps: k-slots 0..3 and 4..7 of the fragment
+          const u32x4 wv = __builtin_bit_cast(u32x4, wf);
+          const uint4 xv = cur.x[t][0];
+          f32x4 p = t == 0 ? cur.cin[0] : P[rt][0];
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xv.x, xv.y}), __builtin_bit_cast(bf16x4, u32x2{wv.x, wv.y}), p, 0, 0, 0);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xv.z, xv.w}), __builtin_bit_cast(bf16x4, u32x2{wv.z, wv.w}), p, 0, 0, 0);
+          P[rt][0] = p;
+        } else {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          P[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.x[t][mt]), wf, t == 0 ? cur.cin[mt] : P[rt][mt], 0, 0, 0);
+          for (int mt = 0; mt < MT; ++mt)
+            P[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.x[t][mt]), wf, t == 0 ? cur.cin[mt] : P[rt][mt], 0, 0, 0);
+        }
       }
     }
 #pragma unroll
@@ -304,7 +331,7 @@ template <int KIND, int MT, int MR, int RT, bool META>
 __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
                                const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
-                               uint32_t c4300) {
+                               DecodeConsts dc) {
   using TR = Traits<KIND>;
   constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);  // tiles in flight per wavefront
   const int tiles = a.tiles[KIND];
@@ -331,7 +358,7 @@ __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[R
       for (int j = 0; j + 1 < ngroups; ++j) {
 #pragma unroll
         for (int i = 0; i < D; ++i) {
-          process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (k0 + j * D + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+          process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (k0 + j * D + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, dc);
 #pragma unroll
           for (int rt = 0; rt < RT; ++rt)
             load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], k0 + min((j + 1) * D + i, n - 1), lane);
@@ -341,7 +368,7 @@ __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[R
 #pragma unroll
       for (int i = 0; i < D; ++i) {
         if (jl * D + i < n)
-          process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (k0 + jl * D + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+          process_tile<KIND, MT, MR, RT, 0, TR::GPT>(buf[i], (k0 + jl * D + i - c0) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, dc);
       }
     }
   }
@@ -355,14 +382,14 @@ struct SubSteps {
   static __device__ __forceinline__ void run(const SkinnyArgs& a, const TileRegs<KIND> (&r)[RT], bool has, const float (&al)[RT],
                                              const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg, const uint16_t* x,
                                              int row_base, int rows_valid, int c0, int ntiles, int wk, int lane, int tid, int nthreads,
-                                             uint32_t c4300) {
+                                             DecodeConsts dc) {
     using TR = Traits<KIND>;
     if constexpr (J0 < TR::GPT) {
       __syncthreads();  // the previous step's fragments are no longer read
       stage_chunk<KIND, MT, MR, META>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, ntiles * SG, SG, J0, tid, nthreads);
-      if (has) process_tile<KIND, MT, MR, RT, J0, SG>(r, wk * SG, lds_x, lds_cneg, al, be, acc, lane, c4300);
+      if (has) process_tile<KIND, MT, MR, RT, J0, SG>(r, wk * SG, lds_x, lds_cneg, al, be, acc, lane, dc);
       SubSteps<KIND, MT, MR, RT, SG, J0 + SG, META>::run(a, r, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid,
-                                                   nthreads, c4300);
+                                                   nthreads, dc);
     }
   }
 };
@@ -371,7 +398,7 @@ template <int KIND, int MT, int MR, int RT, int SG, bool META>
 __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
                                 const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                 const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
-                                uint32_t c4300) {
+                                DecodeConsts dc) {
   using TR = Traits<KIND>;
   const int tiles = a.tiles[KIND];
   const int A = (int)(((int64_t)split * tiles) / a.S), B = (int)(((int64_t)(split + 1) * tiles) / a.S);
@@ -389,7 +416,7 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
       for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(nxt[rt], codes_rt[rt], scales_rt[rt], c0 + a.WK + wk, lane);
     }
     SubSteps<KIND, MT, MR, RT, SG, 0, META>::run(a, cur, has, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, c0, ntiles, wk, lane, tid, nthreads,
-                                           c4300);
+                                           dc);
     if (has_next) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) cur[rt] = nxt[rt];
@@ -402,7 +429,7 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
 // region, so no workgroup barrier is needed before the contraction and the
 // wavefronts of a workgroup drift apart instead of waiting for each other.
 //   lds_x   : fragments, index (lg*T + t)*4 + kq, 16 bytes each
-//   lds_cneg: one float per group
+//   lds_cneg: one float per group and quarter, index lg*4 + kq
 template <int KIND, bool META>
 __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, const uint16_t* xr, int pg0, int ng, int lane) {
   using TR = Traits<KIND>;
@@ -439,27 +466,27 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
     }
     lds_x[f] = o;
     if constexpr (KIND == kNarrow) {
-      // the 8 fragments of a group sit in 8 neighbouring lanes: add them up with DPP, fixed order
+      // the two fragments of a quarter (k-steps 0 and 1) sit 4 lanes apart: add them with one DPP step
       float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
                   ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
-      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0xB1, 0xF, 0xF, true));   // lane ^ 1
-      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x4E, 0xF, 0xF, true));   // lane ^ 2
-      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x141, 0xF, 0xF, true));  // mirror in 8 lanes
-      if ((f & 7) == 0) lds_cneg[lg] = a.cneg[KIND] * sum;
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
+      if ((f & 4) == 0) lds_cneg[lg * 4 + kq] = a.cneg[KIND] * sum;
     }
   }
   if constexpr (KIND == kWide) {
-    // 12 fragments per group: one lane per group adds them up from LDS (same wavefront: LDS operations stay in order)
+    // three fragments per quarter: one lane per (group, quarter) adds them up from LDS (same wavefront: LDS
+    // operations stay in order)
     __builtin_amdgcn_wave_barrier();
-    for (int lg = lane; lg < ng; lg += 64) {
+    for (int e = lane; e < ng * 4; e += 64) {
+      const int lg = e >> 2, kq = e & 3;
       float sum = 0.f;
 #pragma unroll
-      for (int tk = 0; tk < TR::T * 4; ++tk) {
-        const uint4 v = lds_x[lg * TR::T * 4 + tk];
+      for (int t = 0; t < TR::T; ++t) {
+        const uint4 v = lds_x[(lg * TR::T + t) * 4 + kq];
         sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
                bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
       }
-      lds_cneg[lg] = a.cneg[KIND] * sum;
+      lds_cneg[e] = a.cneg[KIND] * sum;
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -468,7 +495,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
 template <int KIND, int RT, bool META>
 __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
                                  const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][1], uint4* lds_x, float* lds_cneg,
-                                 const uint16_t* xr, int split, int wk, int lane, uint32_t c4300) {
+                                 const uint16_t* xr, int split, int wk, int lane, DecodeConsts dc) {
   using TR = Traits<KIND>;
   constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);
   if (!active) return;
@@ -489,7 +516,7 @@ __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)
     for (int j = 0; j + 1 < ngroups; ++j) {
 #pragma unroll
       for (int i = 0; i < D; ++i) {
-        process_tile<KIND, 1, 1, RT, 0, TR::GPT>(buf[i], (j * D + i) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+        process_tile<KIND, 1, 1, RT, 0, TR::GPT>(buf[i], (j * D + i) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, dc);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], c0 + min((j + 1) * D + i, n - 1), lane);
       }
@@ -497,7 +524,7 @@ __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)
     const int jl = ngroups - 1;
 #pragma unroll
     for (int i = 0; i < D; ++i) {
-      if (jl * D + i < n) process_tile<KIND, 1, 1, RT, 0, TR::GPT>(buf[i], (jl * D + i) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, c4300);
+      if (jl * D + i < n) process_tile<KIND, 1, 1, RT, 0, TR::GPT>(buf[i], (jl * D + i) * TR::GPT, lds_x, lds_cneg, al, be, acc, lane, dc);
     }
     __builtin_amdgcn_wave_barrier();  // the region is rewritten by the next chunk
   }
@@ -507,25 +534,25 @@ template <int KIND, int MT, int MR, int RT, bool META>
 __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
                                          const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                          const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
-                                         uint32_t c4300) {
+                                         DecodeConsts dc) {
   using TR = Traits<KIND>;
   if constexpr (MT >= 2) {
     const int sg = a.SG[KIND];
     if (sg != TR::GPT) {
       if (sg == 1)
         run_kind_groups<KIND, MT, MR, RT, 1, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
-                                             tid, nthreads, c4300);
+                                             tid, nthreads, dc);
       else if (sg == 2)
         run_kind_groups<KIND, MT, MR, RT, 2, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
-                                             tid, nthreads, c4300);
+                                             tid, nthreads, dc);
       else
         run_kind_groups<KIND, MT, MR, RT, 4, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
-                                             tid, nthreads, c4300);
+                                             tid, nthreads, dc);
       return;
     }
   }
   run_kind_tiles<KIND, MT, MR, RT, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane, tid,
-                                   nthreads, c4300);
+                                   nthreads, dc);
 }
 
 template <int MT, int MR, int RT, int FM>
@@ -574,8 +601,9 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
   uint4* lds_x = reinterpret_cast<uint4*>(smem);
   const int frag_cap = a.frag_cap;
   float* lds_cneg = reinterpret_cast<float*>(smem + (size_t)frag_cap * 16);
-  uint32_t c4300 = 0x43004300u;
-  asm volatile("" : "+v"(c4300));  // keep the constant in a vector register for v_and_or_b32
+  // the compiler must see these as register values, not literals, to select v_and_or_b32
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}};
+  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]));
 
   for (int m0 = 0; m0 < Me; m0 += MT * 16) {
     const int rows_valid = min(MT * 16, Me - m0);
@@ -590,17 +618,27 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
       uint4* my_x = lds_x + (size_t)wave * (a.frag_cap + a.cneg_cap / 4);
       float* my_cneg = reinterpret_cast<float*>(my_x + a.frag_cap);
       const uint16_t* xr = a.x + (a.sorted_rows ? (int64_t)a.sorted_rows[off0 + m0] : (int64_t)(off0 + m0)) * a.ldx;
-      if constexpr ((FM & 1) != 0) run_kind_private<kNarrow, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, c4300);
-      if constexpr ((FM & 2) != 0) run_kind_private<kWide, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, c4300);
+      if constexpr ((FM & 1) != 0) run_kind_private<kNarrow, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
+      if constexpr ((FM & 2) != 0) run_kind_private<kWide, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
     } else {
       if constexpr ((FM & 1) != 0)
         run_kind<kNarrow, MT, MR, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
-                                      nthreads, c4300);
+                                      nthreads, dc);
       if constexpr ((FM & 2) != 0)
         run_kind<kWide, MT, MR, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
-                                    nthreads, c4300);
+                                    nthreads, dc);
     }
 
+    if constexpr (MR == 1) {
+      // every lane holds the partial sum of its row over its own quarter: add the four quarters (fixed order)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        float v = acc[rt][0][0];
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        acc[rt][0][0] = v;
+      }
+    }
     // ---- reduce the K-splits of this workgroup through LDS (fixed order) ----
     if (a.WK > 1) {
       __syncthreads();
@@ -791,7 +829,7 @@ int launch_skinny(const SkinnyCall& c) {
       a.KC[k] = std::max(1, std::min(per_wave, fit));
       a.SG[k] = gpt;
       pf = std::max<int64_t>(pf, (int64_t)a.KC[k] * gpt * T * 4);
-      pc = std::max<int64_t>(pc, (int64_t)((a.KC[k] * gpt + 3) / 4) * 4);
+      pc = std::max<int64_t>(pc, (int64_t)a.KC[k] * gpt * 4);  // one start value per group and quarter
     }
     a.frag_cap = (int)pf;
     a.cneg_cap = (int)pc;
