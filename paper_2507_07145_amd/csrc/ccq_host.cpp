@@ -73,14 +73,13 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
   const int nt = L.tiles[kNarrow] + L.tiles[kWide];  // k-tiles per row tile
   const int64_t units = (int64_t)L.row_tiles * experts;  // row tiles over all experts
   if (M == 1) {
-    // bandwidth-bound GEMV: many wavefronts, K split inside the workgroup so
-    // that no workspace pass is needed
-    d.RT = 1;
-    const int64_t target_waves = 4096;
-    int ks = (int)std::max<int64_t>(1, std::min<int64_t>(nt, target_waves / std::max<int64_t>(1, units)));
-    if (ks <= 8) { d.WK = ks; d.S = 1; }
-    else { d.WK = 8; d.S = std::min(kMaxSplitsK, ceil_div(ks, 8)); }
-    d.WR = std::max(1, std::min(8 / d.WK, (int)std::min<int64_t>(8, L.row_tiles)));
+    // GEMV, bound by the vector ALU: a workgroup is one group of wavefronts that split K among
+    // themselves (reduced in LDS, no workspace pass); every wavefront gets about 8 k-tiles so that its
+    // set-up cost is amortised, and two row tiles when there are plenty of rows (narrow format only).
+    d.RT = (units >= 1024 && L.tiles[kWide] == 0) ? 2 : 1;
+    d.WR = 1;
+    d.WK = std::max(1, std::min(8, nt / 8));
+    d.S = 1;
   } else {
     // two row tiles per wavefront only for the narrow format with at most 32 held rows (register budget)
     d.RT = (L.row_tiles >= 2 && M <= 32 && L.tiles[kWide] == 0) ? 2 : 1;

@@ -308,10 +308,6 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
       const float s = group_scale<KIND>(r[rt], j);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        // Only element 0 is needed when one activation row is held, but all four registers of the
-        // MFMA result stay allocated up to here: reusing the unused ones as scratch while the
-        // MFMA is still in flight gave wrong results on the device.
-        if (MR == 1) asm volatile("" : "+v"(P[rt][mt]));
         acc[rt][mt][0] = __builtin_fmaf(s, P[rt][mt][0], acc[rt][mt][0]);
         if (MR > 1) {
           acc[rt][mt][1] = __builtin_fmaf(s, P[rt][mt][1], acc[rt][mt][1]);
@@ -738,7 +734,7 @@ static SkinnyKernel pick_rt(int rt, int fm) {
 
 static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm) {
   if (mt == 1) {
-    if (mr == 1) return pick_fm<1, 1, 1>(fm);
+    if (mr == 1) return pick_rt<1, 1>(rt, fm);
     return pick_rt<1, 16>(rt, fm);
   }
   if (mt == 2) return pick_rt<2, 16>(rt, fm);
@@ -755,7 +751,7 @@ int launch_skinny(const SkinnyCall& c) {
   const int mrt = mt == 1 ? mr : mt * 16;
   const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
   if ((mt >= 2 || mr == 1) && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
-  if (d.RT == 2 && (mt == 4 || mr == 1 || fm != 1)) return CCQ_ERR_BAD_PARAM;  // two row tiles per wavefront: narrow format, 2..32 held rows
+  if (d.RT == 2 && (mt == 4 || fm != 1)) return CCQ_ERR_BAD_PARAM;  // two row tiles per wavefront: narrow format, at most 32 held rows
   if (mt == 4 && d.WR * d.WK > 4) return CCQ_ERR_BAD_PARAM;            // 64 held rows: built for at most 256 threads
 
   SkinnyArgs a;

@@ -26,10 +26,10 @@ def _gemm_bits(w, x_bits, **kw):
 
 def _built(kinds, M, launch) -> bool:
     """Launch shapes the kernels are built for: two row tiles per wavefront only for the narrow format
-    with 2..32 held rows; at most 8 wavefronts per workgroup for M = 1 and beyond 16 held rows, 4 beyond 32."""
+    with at most 32 held rows; at most 8 wavefronts per workgroup for M = 1 and beyond 16 held rows, 4 beyond 32."""
     rt, wr, wk, _ = launch
     held = min(M, 64)
-    if rt == 2 and (held > 32 or held == 1 or "wide" in kinds):
+    if rt == 2 and (held > 32 or "wide" in kinds):
         return False
     if held > 32 and wr * wk > 4:
         return False
