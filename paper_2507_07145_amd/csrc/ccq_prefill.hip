@@ -21,6 +21,8 @@
 // own L2 and streams the (small) code bytes.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ccq_internal.h"
 
 namespace ccq {
@@ -99,14 +101,13 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   asm volatile("" : "+v"(c43), "+s"(smask));
   const float neg_off = -(128.f + a.zp);
 
-  // activation copy: 8 chunks of 16 bytes per thread and step
+  // activation copy: 8 chunks of 16 bytes per thread and step; rows past M re-read row M-1 (their
+  // products land in accumulator rows that are never stored)
   const uint16_t* xrow[8];
-  bool xok[8];
   int a_lds_off[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int c = tid + 256 * i, row = c >> 3, col = c & 7;
-    xok[i] = m0 + row < a.M;
     xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
     a_lds_off[i] = row * kLdsRow + col * 8;
   }
@@ -119,96 +120,141 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nsteps = a.K / kBK;
-  u32x4 areg[8];
-  u32x4 creg[RTW];
-  uint2 sreg[RTW];
+  const int nsteps = a.K / kBK;       // a multiple of 4 (narrow k-tiles span 4 groups)
+  const int ntiles = nsteps >> 2;
+  u32x4 areg[2][8];                   // activation chunks of steps s (parity s & 1), fetched two steps ahead
+  u32x4 creg[RTW], cnext[RTW];        // codes of the k-tile being decoded / of the next one
+  uint2 sreg[RTW], snext[RTW];
 
-  auto load_a = [&](int step) {
+  auto load_a = [&](u32x4 (&dst)[8], int step) {
+    const int64_t off = (int64_t)min(step, nsteps - 1) * kBK;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (xok[i]) v = *reinterpret_cast<const u32x4*>(xrow[i] + (int64_t)step * kBK);
-      areg[i] = v;
-    }
+    for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const u32x4*>(xrow[i] + off);
   };
-  auto load_codes = [&](int kt) {
+  auto load_codes = [&](u32x4 (&c)[RTW], uint2 (&sc)[RTW], int kt) {
+    kt = min(kt, ntiles - 1);
 #pragma unroll
     for (int i = 0; i < RTW; ++i) {
-      creg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_ptr[i] + (int64_t)kt * kNarrowTileBytes));
-      sreg[i] = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs);
+      c[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_ptr[i] + (int64_t)kt * kNarrowTileBytes));
+      sc[i] = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs);
     }
   };
-  auto store_a = [&](int buf) {
+  auto store_a = [&](int buf, const u32x4 (&src)[8], int i0, int i1) {
     uint16_t* dst = As + buf * kBM * kLdsRow;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = areg[i];
+    for (int i = i0; i < i1; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = src[i];
   };
-  // decode group j (0..3) of the held k-tile into LDS buffer `buf`
-  auto decode_b = [&](int buf, int j) {
+  // decode group j (0..3) of row tile i of the held k-tile into LDS buffer `buf`
+  auto decode_b = [&](int buf, int j, int i) {
     uint16_t* dst = Bs + buf * BN * kLdsRow;
+    const uint32_t d = j == 0 ? creg[i].x : (j == 1 ? creg[i].y : (j == 2 ? creg[i].z : creg[i].w));
+    const uint32_t sw = (j >> 1) ? sreg[i].y : sreg[i].x;
+    const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+    const float c0 = neg_off * s;  // exact: 8-bit times 11-bit significand
+    uint32_t o[8];
 #pragma unroll
-    for (int i = 0; i < RTW; ++i) {
-      const uint32_t d = j == 0 ? creg[i].x : (j == 1 ? creg[i].y : (j == 2 ? creg[i].z : creg[i].w));
-      const uint32_t sw = (j >> 1) ? sreg[i].y : sreg[i].x;
-      const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
-      const float c0 = neg_off * s;  // exact: 8-bit times 11-bit significand
-      uint32_t o[8];
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], be[i]);
-        const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code
-        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, smask, c43)), s, c0);
-        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, smask, c43)), s, c0);
-        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, smask, c43)), s, c0);
-        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, smask, c43)), s, c0);
-        o[2 * b] = pack_bf16(w0, w1);
-        o[2 * b + 1] = pack_bf16(w2, w3);
-      }
-      uint16_t* p = dst + ((wave * RTW + i) * 16 + nl) * kLdsRow + kq * 16;
-      *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
-      *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
+    for (int b = 0; b < 4; ++b) {
+      const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], be[i]);
+      const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code
+      const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, smask, c43)), s, c0);
+      const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, smask, c43)), s, c0);
+      const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, smask, c43)), s, c0);
+      const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, smask, c43)), s, c0);
+      o[2 * b] = pack_bf16(w0, w1);
+      o[2 * b + 1] = pack_bf16(w2, w3);
     }
+    uint16_t* p = dst + ((wave * RTW + i) * 16 + nl) * kLdsRow + kq * 16;
+    *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
+    *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
   };
 
-  // prologue: step 0 into buffer 0
-  load_a(0);
-  load_codes(0);
-  store_a(0);
-  decode_b(0, 0);
-  __syncthreads();
+  // MFMA operand fragments, double buffered in registers: while the 4 x NT products of one
+  // 16-wide k slice run, the fragments of the next slice are on their way from LDS.
+  bf16x8 af[2][4], bfr[2][NT];
+  const int a_frag_off = (wm * 128 + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+  const int b_frag_off = (wn * (BN / 2) + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+  auto load_frags = [&](int par, int buf, int kk) {
+    const uint16_t* Ab = As + buf * kBM * kLdsRow + a_frag_off + kk * 16;
+    const uint16_t* Bb = Bs + buf * BN * kLdsRow + b_frag_off + kk * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[par][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * kLdsRow));
+#pragma unroll
+    for (int j = 0; j < NT; ++j) bfr[par][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + j * 32 * kLdsRow));
+  };
+  auto mfma_rows = [&](int par, int i0, int i1) {
+#pragma unroll
+    for (int i = i0; i < i1; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][i], bfr[par][j], acc[i][j], 0, 0, 0);
+  };
+  // Workgroup barrier that orders LDS traffic only: global loads issued for later steps stay in
+  // flight across it.
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  };
 
-  for (int step = 0; step < nsteps; ++step) {
-    const int buf = step & 1;
-    const bool more = step + 1 < nsteps;
-    if (more) {
-      load_a(step + 1);
-      if (((step + 1) & 3) == 0) load_codes((step + 1) >> 2);
+  // prologue: steps 0 and 1 of the activations and k-tile 0 of the codes are fetched; step 0 goes to
+  // LDS buffer 0
+  load_a(areg[0], 0);
+  load_codes(creg, sreg, 0);
+  load_a(areg[1], 1);
+  store_a(0, areg[0], 0, 8);
+#pragma unroll
+  for (int i = 0; i < RTW; ++i) decode_b(0, 0, i);
+  lds_barrier();
+  load_frags(0, 0, 0);
+
+  // One step (J = step & 3).  While buffer J&1 is multiplied, step + 1 is written to the other
+  // buffer (activation chunks fetched a step earlier, weight group J+1 of the held k-tile), the
+  // activations of step + 2 and, once per k-tile, the codes of the next k-tile are requested.
+  // Everything is unconditional: past the end, loads re-read the last step and the extra LDS
+  // contents are never multiplied.
+  auto body = [&](int step, auto JC) {
+    constexpr int J = decltype(JC)::value;
+    constexpr int buf = J & 1;
+    load_a(areg[J & 1], step + 2);
+    if constexpr (J == 1) load_codes(cnext, snext, (step >> 2) + 1);
+    __builtin_amdgcn_sched_barrier(0);  // the requests go out first: nothing below may move above them
+    if constexpr (J == 3) {
+#pragma unroll
+      for (int i = 0; i < RTW; ++i) { creg[i] = cnext[i]; sreg[i] = snext[i]; }
     }
-    const uint16_t* Ab = As + buf * kBM * kLdsRow + (wm * 128 + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
-    const uint16_t* Bb = Bs + buf * BN * kLdsRow + (wn * (BN / 2) + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+    constexpr int jn = (J + 1) & 3;
+    // slice 0
+    load_frags(1, buf, 1);
+    mfma_rows(0, 0, 4);
+    store_a(buf ^ 1, areg[(J + 1) & 1], 0, 4);
+    decode_b(buf ^ 1, jn, 0);
+    // slice 1
+    load_frags(0, buf, 2);
+    mfma_rows(1, 0, 4);
+    store_a(buf ^ 1, areg[(J + 1) & 1], 4, 8);
+    decode_b(buf ^ 1, jn, 1);
+    // slice 2 and the first half of slice 3
+    load_frags(1, buf, 3);
+    mfma_rows(0, 0, 4);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[4], bfr[NT];
+    for (int i = 2; i < RTW; ++i) decode_b(buf ^ 1, jn, i);
+    mfma_rows(1, 0, 2);
+    // issue order inside this region: one MFMA, a few vector ALU instructions, one LDS access
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * kLdsRow + kk * 16));
-#pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + j * 32 * kLdsRow + kk * 16));
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < 14 * NT; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+      __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);
     }
-    if (more) {
-      store_a(buf ^ 1);
-      switch ((step + 1) & 3) {
-        case 0: decode_b(buf ^ 1, 0); break;
-        case 1: decode_b(buf ^ 1, 1); break;
-        case 2: decode_b(buf ^ 1, 2); break;
-        default: decode_b(buf ^ 1, 3); break;
-      }
-    }
-    __syncthreads();
+    lds_barrier();
+    // rest of slice 3, with the first fragments of the next step
+    load_frags(0, buf ^ 1, 0);
+    mfma_rows(1, 2, 4);
+  };
+  for (int step = 0; step < nsteps; step += 4) {
+    body(step, std::integral_constant<int, 0>{});
+    body(step + 1, std::integral_constant<int, 1>{});
+    body(step + 2, std::integral_constant<int, 2>{});
+    body(step + 3, std::integral_constant<int, 3>{});
   }
 
   // epilogue: D[row][col], row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32

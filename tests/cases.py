@@ -12,6 +12,11 @@ from paper_2507_07145_amd import synth
 # The error budget is the bf16 output rounding (2^-9 relative) plus fp32 accumulation noise;
 # the skinny path decodes weights exactly, the prefill path also rounds them to bf16.
 REL_TOL = 1e-2
+# The large-M kernel multiplies bf16-rounded weights (relative error <= 2^-9 each), so an element can be off by
+# 2^-9 * sum_k |x_k W_nk| whatever the size of the sum itself; with heavy-tailed group scales and a short K a
+# single large term can make that exceed 1e-2 * rms.  Tests of that kernel pass the absolute sum and allow
+# 2^-8 of it on top (weight rounding plus fp32 accumulation), a bound that follows from the arithmetic.
+ABS_SUM_TOL = 2.0 ** -8
 
 
 def canon_zero(bits: np.ndarray) -> np.ndarray:
@@ -20,13 +25,15 @@ def canon_zero(bits: np.ndarray) -> np.ndarray:
     return np.where((bits & 0x7FFF) == 0, np.uint16(0), bits)
 
 
-def assert_gemm_close(y_bits: np.ndarray, ref: np.ndarray, what: str = "") -> dict:
+def assert_gemm_close(y_bits: np.ndarray, ref: np.ndarray, what: str = "", abs_sum: np.ndarray | None = None) -> dict:
     y = o.bf16_bits_to_f64(y_bits)
     assert y.shape == ref.shape, (what, y.shape, ref.shape)
     assert np.all(np.isfinite(y)), what
     rms = float(np.sqrt(np.mean(ref ** 2))) if ref.size else 0.0
     err = np.abs(y - ref)
     tol = REL_TOL * np.maximum(np.abs(ref), rms)
+    if abs_sum is not None:
+        tol = tol + ABS_SUM_TOL * abs_sum
     bad = np.argwhere(err > tol)
     assert bad.size == 0, f"{what}: {len(bad)} elements out of tolerance, first {bad[:5].tolist()}, max err {err.max():.4g}, rms {rms:.4g}"
     rel = float(np.linalg.norm(y - ref) / max(np.linalg.norm(ref), 1e-300))

@@ -77,6 +77,21 @@ def test_more_rows_than_one_pass(cfg1):
         assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"cfg1 M={M}")
 
 
+@pytest.mark.parametrize("K,N,M", [(768, 384, 300), (512, 208, 70), (256, 16, 65), (1024, 576, 257), (2048, 192, 512)])
+def test_large_m_kernel_small_shapes(K, N, M):
+    """More than 64 rows on narrow-format weights go through the LDS-tiled MFMA kernel: column blocks of 192
+    and of 256, ragged last blocks in M and N, decoded weights exact and products within tolerance."""
+    c = random_case(K, N, ["narrow"], 1, stream0=900 + N)
+    w = c.device_weight(DEV)
+    x = synth.activations_bf16(M, K, synth.rng(1, 950 + M))
+    abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(c.W()))
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"large-M K={K} N={N} M={M}", abs_sum=abs_sum)
+    ks = synth.rng(1, 960 + M).integers(0, K, M)
+    got = _gemm_bits(w, synth.one_hot_bf16(ks, K))
+    want = o.to_bf16_bits(c.W()[:, ks].T)
+    assert np.array_equal(canon_zero(got), canon_zero(want)), "large-M kernel: decoded weights differ"
+
+
 @pytest.mark.parametrize("launch", [(1, 1, 1, 1), (2, 1, 1, 1), (1, 4, 1, 1), (1, 1, 4, 1), (2, 2, 2, 1), (1, 2, 1, 2), (2, 1, 2, 4),
                                     (1, 4, 4, 1), (1, 1, 16, 1), (2, 3, 3, 3), (1, 2, 8, 1), (1, 1, 1, 5)])
 @pytest.mark.parametrize("M", [1, 4, 16, 40])
