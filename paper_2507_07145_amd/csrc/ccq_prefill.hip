@@ -56,13 +56,6 @@ constexpr int kLdsRow = kBK + 8;  // bf16 elements per padded LDS row (144 bytes
 // recognizer does not see those); mask and orv are kept in registers so v_and_or_b32 is selected.
 __device__ __forceinline__ uint32_t and_or_p(uint32_t a, uint32_t mask, uint32_t orv) { return (a & mask) | orv; }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne_p(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   f32x2 v = {lo, hi};
   bf16x2 b = __builtin_convertvector(v, bf16x2);  // round to nearest even
@@ -257,20 +250,34 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
     body(step + 3, std::integral_constant<int, 3>{});
   }
 
-  // epilogue: D[row][col], row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32
+  // epilogue: D[row][col], row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32.  One store writes two
+  // 64-byte row segments; blocks that lie fully inside the output take the path without per-element tests.
+  const bool inside = (m0 + kBM <= a.M) && (n0 + BN <= a.N);
+  uint16_t* ybase = a.y + (int64_t)(m0 + wm * 128 + 4 * (lane >> 5)) * a.ldy + (n0 + wn * (BN / 2) + (lane & 31));
+  auto store_tile = [&](auto FULL) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) {
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+      for (int j = 0; j < NT; ++j) {
+        const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const float val = acc[i][j][r];  // by value: bit-casting the element lvalue itself reads element 0
-        if (m < a.M && n < a.N) a.y[(int64_t)m * a.ldy + n] = f32_to_bf16_rne_p(val);
+        for (int r = 0; r < 16; ++r) {
+          const int mrel = i * 32 + 8 * (r >> 2) + (r & 3);
+          const float val = acc[i][j][r];  // by value: bit-casting the element lvalue itself reads element 0
+          const uint16_t bits = (uint16_t)(pack_bf16(val, 0.f) & 0xFFFFu);  // round to nearest even
+          uint16_t* dst = ybase + (int64_t)mrel * a.ldy + j * 32;
+          if constexpr (decltype(FULL)::value) {
+            *dst = bits;
+          } else {
+            const int m = m0 + wm * 128 + 4 * (lane >> 5) + mrel;
+            if (m < a.M && n < a.N) *dst = bits;
+          }
+        }
       }
     }
-  }
+  };
+  if (inside) store_tile(std::true_type{});
+  else store_tile(std::false_type{});
 }
 
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
