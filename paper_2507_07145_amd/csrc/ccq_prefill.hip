@@ -71,7 +71,8 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   uint16_t* As = reinterpret_cast<uint16_t*>(smem);                          // [2][kBM][kLdsRow]
   uint16_t* Bs = As + 2 * kBM * kLdsRow;                                     // [2][BN][kLdsRow]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile base pointers stay in scalar registers
   const int wm = wave >> 1, wn = wave & 1;
   const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
   const int m0 = m_block * kBM, n0 = n_block * BN;
@@ -85,23 +86,25 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   for (int i = 0; i < RTW; ++i) {
     int rtile = n0 / 16 + wave * RTW + i;
     rtile = min(rtile, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
-    code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes + lane * 16;
-    scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + nl * 4;
+    code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;                 // + lane * 16 at the load
+    scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;         // + nl * 4 at the load
     al[i] = a.alpha[rtile * 16 + nl];
     be[i] = a.beta[rtile * 16 + nl] + 8388608.f;
   }
   uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
   asm volatile("" : "+v"(c43), "+s"(smask));
   const float neg_off = -(128.f + a.zp);
+  const uint32_t lane_code_off = lane * 16, lane_scale_off = nl * 4;
 
   // activation copy: 8 chunks of 16 bytes per thread and step; rows past M re-read row M-1 (their
   // products land in accumulator rows that are never stored)
-  const uint16_t* xrow[8];
+  // (32-bit byte offsets from the uniform base; the launcher checks that the tile fits 2^31 bytes)
+  uint32_t xoff[8];
   int a_lds_off[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int c = tid + 256 * i, row = c >> 3, col = c & 7;
-    xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
+    xoff[i] = (uint32_t)(((int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8) * 2);
     a_lds_off[i] = row * kLdsRow + col * 8;
   }
 
@@ -115,21 +118,25 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
 
   const int nsteps = a.K / kBK;       // a multiple of 4 (narrow k-tiles span 4 groups)
   const int ntiles = nsteps >> 2;
-  u32x4 areg[2][8];                   // activation chunks of steps s (parity s & 1), fetched two steps ahead
+  // Activation chunks in registers on their way to LDS: two sets (step s in set s & 1, requested two
+  // steps ahead of its multiplication).  AD = 1 keeps a single set, refilled as soon as its chunks have
+  // been written to LDS, should registers ever be short.
+  constexpr int AD = 2;
+  u32x4 areg[AD][8];
   u32x4 creg[RTW], cnext[RTW];        // codes of the k-tile being decoded / of the next one
   uint2 sreg[RTW], snext[RTW];
 
   auto load_a = [&](u32x4 (&dst)[8], int step) {
-    const int64_t off = (int64_t)min(step, nsteps - 1) * kBK;
+    const char* base = reinterpret_cast<const char*>(a.x + (int64_t)min(step, nsteps - 1) * kBK);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const u32x4*>(xrow[i] + off);
+    for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const u32x4*>(base + xoff[i]);
   };
   auto load_codes = [&](u32x4 (&c)[RTW], uint2 (&sc)[RTW], int kt) {
     kt = min(kt, ntiles - 1);
 #pragma unroll
     for (int i = 0; i < RTW; ++i) {
-      c[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_ptr[i] + (int64_t)kt * kNarrowTileBytes));
-      sc[i] = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs);
+      c[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_ptr[i] + (int64_t)kt * kNarrowTileBytes + lane_code_off));
+      sc[i] = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs + lane_scale_off);
     }
   };
   auto store_a = [&](int buf, const u32x4 (&src)[8], int i0, int i1) {
@@ -192,8 +199,9 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   // LDS buffer 0
   load_a(areg[0], 0);
   load_codes(creg, sreg, 0);
-  load_a(areg[1], 1);
+  if constexpr (AD == 2) load_a(areg[1], 1);
   store_a(0, areg[0], 0, 8);
+  if constexpr (AD == 1) load_a(areg[0], 1);
 #pragma unroll
   for (int i = 0; i < RTW; ++i) decode_b(0, 0, i);
   lds_barrier();
@@ -207,7 +215,7 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   auto body = [&](int step, auto JC) {
     constexpr int J = decltype(JC)::value;
     constexpr int buf = J & 1;
-    load_a(areg[J & 1], step + 2);
+    if constexpr (AD == 2) load_a(areg[J & 1], step + 2);
     if constexpr (J == 1) load_codes(cnext, snext, (step >> 2) + 1);
     __builtin_amdgcn_sched_barrier(0);  // the requests go out first: nothing below may move above them
     if constexpr (J == 3) {
@@ -218,12 +226,13 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
     // slice 0
     load_frags(1, buf, 1);
     mfma_rows(0, 0, 4);
-    store_a(buf ^ 1, areg[(J + 1) & 1], 0, 4);
+    store_a(buf ^ 1, areg[(J + 1) & (AD - 1)], 0, 4);
     decode_b(buf ^ 1, jn, 0);
     // slice 1
     load_frags(0, buf, 2);
     mfma_rows(1, 0, 4);
-    store_a(buf ^ 1, areg[(J + 1) & 1], 4, 8);
+    store_a(buf ^ 1, areg[(J + 1) & (AD - 1)], 4, 8);
+    if constexpr (AD == 1) load_a(areg[0], step + 2);
     decode_b(buf ^ 1, jn, 1);
     // slice 2 and the first half of slice 3
     load_frags(1, buf, 3);
@@ -254,30 +263,33 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   // 64-byte row segments; blocks that lie fully inside the output take the path without per-element tests.
   const bool inside = (m0 + kBM <= a.M) && (n0 + BN <= a.N);
   uint16_t* ybase = a.y + (int64_t)(m0 + wm * 128 + 4 * (lane >> 5)) * a.ldy + (n0 + wn * (BN / 2) + (lane & 31));
-  auto store_tile = [&](auto FULL) {
+  const int mlim = a.M - (m0 + wm * 128 + 4 * (lane >> 5));        // rows of this lane's row set that exist
+  const int nlim = a.N - (n0 + wn * (BN / 2) + (lane & 31));        // columns likewise
+  // (the test of `inside` sits inside the tile loop: around it, the compiler moves all 16 NT x 4 accumulator
+  // reads above the branch and runs out of registers)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 4; ++i) {
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+    for (int j = 0; j < NT; ++j) {
+      uint32_t bits[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float val = acc[i][j][r];  // by value: bit-casting the element lvalue itself reads element 0
+        bits[r] = pack_bf16(val, 0.f);   // round to nearest even
+      }
+      uint16_t* dst = ybase + (int64_t)(i * 32) * a.ldy + j * 32;
+      if (inside) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * a.ldy] = (uint16_t)bits[r];
+      } else if (j * 32 < nlim) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int mrel = i * 32 + 8 * (r >> 2) + (r & 3);
-          const float val = acc[i][j][r];  // by value: bit-casting the element lvalue itself reads element 0
-          const uint16_t bits = (uint16_t)(pack_bf16(val, 0.f) & 0xFFFFu);  // round to nearest even
-          uint16_t* dst = ybase + (int64_t)mrel * a.ldy + j * 32;
-          if constexpr (decltype(FULL)::value) {
-            *dst = bits;
-          } else {
-            const int m = m0 + wm * 128 + 4 * (lane >> 5) + mrel;
-            if (m < a.M && n < a.N) *dst = bits;
-          }
+          if (mrel < mlim) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * a.ldy] = (uint16_t)bits[r];
         }
       }
     }
-  };
-  if (inside) store_tile(std::true_type{});
-  else store_tile(std::false_type{});
+  }
 }
 
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
@@ -298,6 +310,7 @@ int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, i
   a.row_tiles = L.row_tiles;
   a.m_blocks = (M + kBM - 1) / kBM;
   a.zp = L.zp[kNarrow];
+  if (((int64_t)M * ldx + L.K) * 2 >= (int64_t)1 << 31) return CCQ_ERR_UNSUPPORTED;  // activation offsets are 32-bit
   // 192-column blocks when they tile N exactly (less tail imbalance on 256 CUs), else 256
   const bool use192 = (L.N % 192 == 0);
   const int BN = use192 ? 192 : 256;

@@ -66,6 +66,11 @@ struct SkinnyArgs {
   int32_t KC[2];      // k-tiles per wavefront per staged chunk, per kind
   int32_t SG[2];      // groups of a k-tile staged at a time (= groups per tile unless LDS is tight; then KC = 1)
   int32_t WR, WK, S;
+  int32_t inv_WR;     // ceil(2^16 / WR): wave / WR without a division
+  // K partition without divisions: workgroup `split` of S owns tiles [A, B) with A = split*sq + min(split, sr),
+  // B - A = sq + (split < sr); its WK wavefronts cut that range the same way with (wq, wr)[B - A - sq].
+  int32_t sq[2], sr[2];
+  int32_t wq[2][2], wrem[2][2];
   int32_t frag_cap;   // 16-byte fragments the LDS staging area holds (per wavefront when one row is held); the start values follow it
   int32_t cneg_cap;   // floats of start values per wavefront (one held row only; multiple of 4)
   float cneg[2];      // -(128 + zp) per kind
@@ -78,6 +83,20 @@ template <> struct Traits<kNarrow> {
 template <> struct Traits<kWide> {
   static constexpr int GPT = kWideGroupsPerTile, T = 3, SEGS = 3, TILE_BYTES = kWideTileBytes, SCALE_HALFS = kWideTileScaleHalfs;
 };
+
+// k-tiles [A, B) of kind `kind` that workgroup `split` owns.
+__device__ __forceinline__ void split_range(const SkinnyArgs& a, int kind, int split, int& A, int& B) {
+  const int q = a.sq[kind], r = a.sr[kind];
+  A = split * q + min(split, r);
+  B = A + q + (split < r ? 1 : 0);
+}
+// The part [k0, k1) of that range that wavefront wk of WK owns.
+__device__ __forceinline__ void wave_range(const SkinnyArgs& a, int kind, int split, int A, int wk, int& k0, int& k1) {
+  const int v = split < a.sr[kind] ? 1 : 0;
+  const int q = a.wq[kind][v], r = a.wrem[kind][v];
+  k0 = A + wk * q + min(wk, r);
+  k1 = k0 + q + (wk < r ? 1 : 0);
+}
 
 template <int KIND> struct TileRegs {
   u32x4 c[Traits<KIND>::SEGS];
@@ -245,9 +264,9 @@ struct GroupOperands {
 };
 
 // Rows of the product are independent: an activation lane of a row that is not held only feeds a row
-// of the product that is never stored.  With a single held row (MR = 1, MFMA 4x4x4) only the lanes that
-// carry row 0 of a 4x4 block read; the operand registers are zeroed once per tile and the other lanes
-// are never overwritten.
+// of the product that is never stored.  With a single held row (MR = 1, MFMA 4x4x4) every lane of a
+// 4x4 block reads the same fragment (an LDS broadcast, no lane masking): the four rows of the block's
+// product are then equal and row 0 is the one that is used.
 template <int KIND, int MT, int MR>
 __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>& g, int lg, const uint4* lds_x, const float* lds_cneg, int lane) {
   using TR = Traits<KIND>;
@@ -263,7 +282,7 @@ __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>&
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       if constexpr (MR == 16) g.x[t][mt] = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + mt * 16 + m];
-      else if ((lane & 3) == 0) g.x[t][mt] = lds_x[(lg * TR::T + t) * 4 + kq];  // row 0 of each 4x4 block
+      else g.x[t][mt] = lds_x[(lg * TR::T + t) * 4 + kq];
     }
   }
 }
@@ -273,11 +292,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
                                              const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, DecodeConsts dc) {
   using TR = Traits<KIND>;
   GroupOperands<KIND, MT, MR> cur;
-  if constexpr (MR == 1) {
-#pragma unroll
-    for (int t = 0; t < TR::T; ++t) cur.x[t][0] = uint4{0u, 0u, 0u, 0u};
-    cur.cin[0] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+  if constexpr (MR == 1) cur.cin[0] = f32x4{0.f, 0.f, 0.f, 0.f};  // elements 1..3 only need a defined value
 #pragma unroll
   for (int j = J0; j < J0 + NJ; ++j) {
     const int lg = lg0 + (j - J0);
@@ -331,7 +346,8 @@ __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[R
   using TR = Traits<KIND>;
   constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);  // tiles in flight per wavefront
   const int tiles = a.tiles[KIND];
-  const int A = (int)(((int64_t)split * tiles) / a.S), B = (int)(((int64_t)(split + 1) * tiles) / a.S);
+  int A, B;
+  split_range(a, KIND, split, A, B);
   const int KC = a.KC[KIND], CH = KC * a.WK;
   for (int c0 = A; c0 < B; c0 += CH) {
     const int cend = min(c0 + CH, B);
@@ -397,7 +413,8 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
                                 DecodeConsts dc) {
   using TR = Traits<KIND>;
   const int tiles = a.tiles[KIND];
-  const int A = (int)(((int64_t)split * tiles) / a.S), B = (int)(((int64_t)(split + 1) * tiles) / a.S);
+  int A, B;
+  split_range(a, KIND, split, A, B);
   TileRegs<KIND> cur[RT], nxt[RT];
   if (active && A + wk < B) {
 #pragma unroll
@@ -488,27 +505,80 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
   __builtin_amdgcn_wave_barrier();
 }
 
+// Narrow format, one held row: the same staging in two halves, so that the activation requests can
+// go out before the (much slower) code tiles are requested and the conversion to fragments overlaps the
+// tiles' flight.  A lane holds up to kPrivFrags fragments of a chunk (6 KiB region / 16 bytes / 64 lanes).
+constexpr int kPrivFrags = 6;
+template <bool META>
+__device__ __forceinline__ void stage_private_request(uint4 (&v)[kPrivFrags], const SkinnyArgs& a, const uint16_t* xr, int pg0, int ng, int lane) {
+  const int nfrag = ng * 8;
+#pragma unroll
+  for (int i = 0; i < kPrivFrags; ++i) {
+    if (64 * i >= nfrag) break;  // wavefront-uniform
+    const int f = min(lane + 64 * i, nfrag - 1);
+    const int kq = f & 3, t = (f >> 2) & 1, pg = pg0 + (f >> 3);
+    const int g = META ? a.meta[pg] : pg;
+    v[i] = *reinterpret_cast<const uint4*>(xr + (int64_t)g * kGroup + 16 * kq + 8 * t);
+  }
+}
+__device__ __forceinline__ void stage_private_finish(const uint4 (&v)[kPrivFrags], uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, int ng, int lane) {
+  const int nfrag = ng * 8;
+#pragma unroll
+  for (int i = 0; i < kPrivFrags; ++i) {
+    if (64 * i >= nfrag) break;  // wavefront-uniform
+    const int f = lane + 64 * i;
+    if (f < nfrag) {
+      uint4 o;
+      o.x = __builtin_amdgcn_perm(v[i].z, v[i].x, 0x05040100u);
+      o.y = __builtin_amdgcn_perm(v[i].z, v[i].x, 0x07060302u);
+      o.z = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x05040100u);
+      o.w = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x07060302u);
+      lds_x[f] = o;
+      float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
+                  ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
+      if ((f & 4) == 0) lds_cneg[(f >> 3) * 4 + (f & 3)] = a.cneg[kNarrow] * sum;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+}
+
+// One held row.  The whole matrix is only a few microseconds of memory traffic, so the depth of the
+// register ring decides how much of it is in flight: D tiles per wavefront are requested up front
+// (8 for the narrow format: with ~8 k-tiles per wavefront that is all of them), each refilled as soon as
+// it has been consumed.
 template <int KIND, int RT, bool META>
 __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
-                                 const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][1], uint4* lds_x, float* lds_cneg,
+                                 const float (&al)[RT], const float (&be_raw)[RT], f32x4 (&acc)[RT][1], uint4* lds_x, float* lds_cneg,
                                  const uint16_t* xr, int split, int wk, int lane, DecodeConsts dc) {
   using TR = Traits<KIND>;
-  constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);
+  constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 8 : 4) : (RT == 1 ? 2 : 1);
   if (!active) return;
-  const int tiles = a.tiles[KIND];
-  const int A = (int)(((int64_t)split * tiles) / a.S), B = (int)(((int64_t)(split + 1) * tiles) / a.S);
-  const int k0 = A + (int)(((int64_t)(B - A) * wk) / a.WK), k1 = A + (int)(((int64_t)(B - A) * (wk + 1)) / a.WK);
+  int A, B;
+  split_range(a, KIND, split, A, B);
+  int k0, k1;
+  wave_range(a, KIND, split, A, wk, k0, k1);
   const int CT = a.KC[KIND];  // k-tiles the private region holds
   for (int c0 = k0; c0 < k1; c0 += CT) {
     const int cend = min(c0 + CT, k1);
     TileRegs<KIND> buf[D][RT];
     const int n = cend - c0, ngroups = (n + D - 1) / D;
+    uint4 xv[kPrivFrags];
+    if constexpr (KIND == kNarrow) stage_private_request<META>(xv, a, xr, c0 * TR::GPT, n * TR::GPT, lane);
 #pragma unroll
     for (int i = 0; i < D; ++i) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], c0 + min(i, n - 1), lane);
     }
-    stage_private<KIND, META>(lds_x, lds_cneg, a, xr, c0 * TR::GPT, n * TR::GPT, lane);
+    if constexpr (KIND == kNarrow) stage_private_finish(xv, lds_x, lds_cneg, a, n * TR::GPT, lane);
+    else stage_private<KIND, META>(lds_x, lds_cneg, a, xr, c0 * TR::GPT, n * TR::GPT, lane);
+    // the Code Cluster offset plus 2^23 (exact: beta is an integer below 2^15); added only here so that
+    // nothing above waits for the per-row parameters to arrive
+    float be[RT];
+    float magic = 8388608.f;
+    asm volatile("" : "+v"(magic));  // pins the addition below the requests
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) be[rt] = be_raw[rt] + magic;
     for (int j = 0; j + 1 < ngroups; ++j) {
 #pragma unroll
       for (int i = 0; i < D; ++i) {
@@ -557,7 +627,7 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps tile indices and base pointers in scalar registers
-  const int wr = wave % a.WR, wk = wave / a.WR;
+  const int wk = (wave * a.inv_WR) >> 16, wr = wave - wk * a.WR;
   const int split = blockIdx.y, e = blockIdx.z;
 
   int off0 = 0, Me = a.M;
@@ -587,11 +657,14 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
     scales_n[rt] = scales + (int64_t)rtile * a.row_tile_scale_halfs;
     scales_w[rt] = scales_n[rt] + (int64_t)a.tiles[kNarrow] * kNarrowTileScaleHalfs;
     al[rt] = 0.f;
-    be[rt] = 8388608.f;
+    be[rt] = 0.f;
     if ((FM & 1) && active) {
       al[rt] = alpha[rtile * 16 + (lane & 15)];
-      be[rt] = beta[rtile * 16 + (lane & 15)] + 8388608.f;  // + 2^23: exact, beta is an integer below 2^15
+      be[rt] = beta[rtile * 16 + (lane & 15)];
     }
+    // + 2^23 (exact: beta is an integer below 2^15) puts the rounded code into the low mantissa bits; with one
+    // held row the addition is made later, after the first tiles have been requested
+    if constexpr (MR != 1) be[rt] += 8388608.f;
   }
 
   uint4* lds_x = reinterpret_cast<uint4*>(smem);
@@ -781,6 +854,15 @@ int launch_skinny(const SkinnyCall& c) {
   a.WR = d.WR;
   a.WK = d.WK;
   a.S = d.S;
+  a.inv_WR = (65536 + d.WR - 1) / d.WR;
+  for (int k = 0; k < 2; ++k) {
+    a.sq[k] = L.tiles[k] / d.S;
+    a.sr[k] = L.tiles[k] % d.S;
+    for (int v = 0; v < 2; ++v) {
+      a.wq[k][v] = (a.sq[k] + v) / d.WK;
+      a.wrem[k][v] = (a.sq[k] + v) % d.WK;
+    }
+  }
   a.cneg[0] = -(128.f + L.zp[0]);
   a.cneg[1] = -(128.f + L.zp[1]);
 
