@@ -252,6 +252,12 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
   const bool explicit_launch = launch && (launch->rows_per_wave_tiles || launch->waves_rows || launch->waves_k || launch->splits_k);
   if (M > kMaxSkinnyM && L.tiles[kWide] == 0 && !explicit_launch) return launch_prefill(w, L, x, M, ldx, y, ldy, stream);
 
+  // one row, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
+  if (M == 1 && L.tiles[kWide] == 0 && !L.has_map && !explicit_launch) {
+    rc = launch_gemv_narrow(w, L, x, y, stream);
+    if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+  }
+
   // otherwise rows are processed in passes of at most kMaxSkinnyM
   for (int m0 = 0; m0 < M; m0 += kMaxSkinnyM) {
     const int mc = std::min(kMaxSkinnyM, M - m0);

@@ -88,6 +88,10 @@ struct SkinnyCall {
 };
 int launch_skinny(const SkinnyCall& c);
 
+// Dense one-row product on narrow-format weights (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does not
+// split into equal shares of at most 12 k-tiles over at most 8 wavefronts (the caller then uses launch_skinny).
+int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream);
+
 // Large-M kernel for narrow-format weights (ccq_prefill.hip).
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 

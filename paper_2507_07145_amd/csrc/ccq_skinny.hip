@@ -510,18 +510,18 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
 // tiles' flight.  A lane holds up to kPrivFrags fragments of a chunk (6 KiB region / 16 bytes / 64 lanes).
 constexpr int kPrivFrags = 6;
 template <bool META>
-__device__ __forceinline__ void stage_private_request(uint4 (&v)[kPrivFrags], const SkinnyArgs& a, const uint16_t* xr, int pg0, int ng, int lane) {
+__device__ __forceinline__ void stage_private_request(uint4 (&v)[kPrivFrags], const int32_t* meta, const uint16_t* xr, int pg0, int ng, int lane) {
   const int nfrag = ng * 8;
 #pragma unroll
   for (int i = 0; i < kPrivFrags; ++i) {
     if (64 * i >= nfrag) break;  // wavefront-uniform
     const int f = min(lane + 64 * i, nfrag - 1);
     const int kq = f & 3, t = (f >> 2) & 1, pg = pg0 + (f >> 3);
-    const int g = META ? a.meta[pg] : pg;
+    const int g = META ? meta[pg] : pg;
     v[i] = *reinterpret_cast<const uint4*>(xr + (int64_t)g * kGroup + 16 * kq + 8 * t);
   }
 }
-__device__ __forceinline__ void stage_private_finish(const uint4 (&v)[kPrivFrags], uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, int ng, int lane) {
+__device__ __forceinline__ void stage_private_finish(const uint4 (&v)[kPrivFrags], uint4* lds_x, float* lds_cneg, float cneg, int ng, int lane) {
   const int nfrag = ng * 8;
 #pragma unroll
   for (int i = 0; i < kPrivFrags; ++i) {
@@ -537,7 +537,7 @@ __device__ __forceinline__ void stage_private_finish(const uint4 (&v)[kPrivFrags
       float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
                   ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
       sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
-      if ((f & 4) == 0) lds_cneg[(f >> 3) * 4 + (f & 3)] = a.cneg[kNarrow] * sum;
+      if ((f & 4) == 0) lds_cneg[(f >> 3) * 4 + (f & 3)] = cneg * sum;
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -564,13 +564,13 @@ __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)
     TileRegs<KIND> buf[D][RT];
     const int n = cend - c0, ngroups = (n + D - 1) / D;
     uint4 xv[kPrivFrags];
-    if constexpr (KIND == kNarrow) stage_private_request<META>(xv, a, xr, c0 * TR::GPT, n * TR::GPT, lane);
+    if constexpr (KIND == kNarrow) stage_private_request<META>(xv, a.meta, xr, c0 * TR::GPT, n * TR::GPT, lane);
 #pragma unroll
     for (int i = 0; i < D; ++i) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], c0 + min(i, n - 1), lane);
     }
-    if constexpr (KIND == kNarrow) stage_private_finish(xv, lds_x, lds_cneg, a, n * TR::GPT, lane);
+    if constexpr (KIND == kNarrow) stage_private_finish(xv, lds_x, lds_cneg, a.cneg[kNarrow], n * TR::GPT, lane);
     else stage_private<KIND, META>(lds_x, lds_cneg, a, xr, c0 * TR::GPT, n * TR::GPT, lane);
     // the Code Cluster offset plus 2^23 (exact: beta is an integer below 2^15); added only here so that
     // nothing above waits for the per-row parameters to arrive
@@ -771,6 +771,119 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
     }
     if (m0 + MT * 16 < Me) __syncthreads();
   }
+}
+
+// ---- dense GEMV on narrow-format weights: the decode step of generation --------------------
+// Same arithmetic as the one-held-row path above (identical results), with everything that path
+// carries for the general case taken out: no experts, no row map, no format map, no K split over
+// workgroups, every wavefront owns the same number TPW <= kGemvMaxTiles of k-tiles and requests all
+// of them, and its activations, before it does anything else.  A call of this size lasts a few
+// microseconds, of which the argument fetch is a visible part: the arguments fit one 64-byte scalar
+// load.
+constexpr int kGemvMaxTiles = 12;
+struct GemvArgs {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const uint16_t* x;
+  uint16_t* y;
+  int32_t row_tile_bytes;        // bytes of one row tile's code stream
+  int32_t row_tile_scale_halfs;
+  int32_t tpw;                   // k-tiles per wavefront; the workgroup's blockDim.x / 64 wavefronts cover K
+  float cneg;                    // -(128 + zp)
+};
+
+// NT = register sets for k-tiles (4, 8 or 12); the wavefront owns tpw <= NT tiles.
+template <int NT>
+__global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nwaves = blockDim.x >> 6;
+  const int rtile = blockIdx.x, n = a.tpw;
+  const int t0 = wave * n;  // first k-tile of this wavefront
+
+  // all requests go out before anything else: activations first (they are needed first), then every code
+  // tile of this wavefront, then the per-row parameters
+  const uint16_t* xr = a.x + (int64_t)t0 * (kNarrowGroupsPerTile * kGroup);
+  uint4 xv[kPrivFrags];
+  stage_private_request<false>(xv, nullptr, xr, 0, n * kNarrowGroupsPerTile, lane);
+  float al[1], be[1];
+  al[0] = a.alpha[rtile * 16 + (lane & 15)];
+  const float be_raw = a.beta[rtile * 16 + (lane & 15)];
+  // private staging region of this wavefront: fragments, then start values
+  const int frag_cap = n * kNarrowGroupsPerTile * 8, cneg_cap = n * kNarrowGroupsPerTile * 4;
+  uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
+  float* my_cneg = reinterpret_cast<float*>(my_x + frag_cap);
+  const uint8_t* codes = a.codes + (int64_t)rtile * a.row_tile_bytes + (int64_t)t0 * kNarrowTileBytes;
+  const uint16_t* scales = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + (int64_t)t0 * kNarrowTileScaleHalfs;
+  // unconditional requests (a request under a condition would make the first use wait for all of them);
+  // sets beyond tpw re-request the last tile and are not used
+  TileRegs<kNarrow> buf[NT][1];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) load_tile<kNarrow>(buf[i][0], codes, scales, min(i, n - 1), lane);
+  stage_private_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}};
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+v"(magic));
+  be[0] = be_raw + magic;  // + 2^23: exact, beta is an integer below 2^15
+
+  f32x4 acc[1][1] = {{f32x4{0.f, 0.f, 0.f, 0.f}}};
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    if (i < n) process_tile<kNarrow, 1, 1, 1, 0, kNarrowGroupsPerTile>(buf[i], i * kNarrowGroupsPerTile, my_x, my_cneg, al, be, acc, lane, dc);
+  }
+
+  // the four quarters of a row, then the wavefronts of the workgroup (fixed order)
+  float v = acc[0][0][0];
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  if (nwaves > 1) {
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);
+    if (wave > 0 && lane < 16) red[(wave - 1) * 16 + lane] = v;
+    __syncthreads();
+    if (wave == 0 && lane < 16) {
+      for (int k = 1; k < nwaves; ++k) v += red[(k - 1) * 16 + lane];
+    }
+  }
+  if (wave == 0 && lane < 16) a.y[rtile * 16 + lane] = f32_to_bf16_rne(v);
+}
+
+int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream) {
+  // wavefronts per workgroup: a divisor of the k-tile count, at most 8.  Many short wavefronts (4 k-tiles
+  // each) hide the latency chain of a call this small best; when that would be more wavefronts than the
+  // chip holds at once (8 per SIMD), shares of 8 tiles are better.
+  const int tiles = L.tiles[kNarrow];
+  const int target = ((int64_t)L.row_tiles * tiles / 4 <= 8192) ? 4 : 8;
+  int wk = 0, best = 1 << 30;
+  for (int c = 1; c <= 8; ++c) {
+    if (tiles % c != 0 || tiles / c > kGemvMaxTiles) continue;
+    const int dist = std::abs(tiles / c - target);
+    if (dist < best) { best = dist; wk = c; }
+  }
+  if (wk == 0) return CCQ_ERR_UNSUPPORTED;  // the caller falls back to the general kernel
+  if (L.row_tile_bytes >= ((int64_t)1 << 31) || L.row_tile_scale_halfs >= ((int64_t)1 << 31)) return CCQ_ERR_UNSUPPORTED;
+  GemvArgs a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.row_tile_bytes = (int32_t)L.row_tile_bytes;
+  a.row_tile_scale_halfs = (int32_t)L.row_tile_scale_halfs;
+  a.tpw = tiles / wk;
+  a.cneg = -(128.f + L.zp[kNarrow]);
+  const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 4);
+  const dim3 grid((unsigned)L.row_tiles), block((unsigned)(64 * wk));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (a.tpw <= 4) hipLaunchKernelGGL(ccq_gemv_narrow_kernel<4>, grid, block, lds, st, a);
+  else if (a.tpw <= 8) hipLaunchKernelGGL(ccq_gemv_narrow_kernel<8>, grid, block, lds, st, a);
+  else hipLaunchKernelGGL(ccq_gemv_narrow_kernel<kGemvMaxTiles>, grid, block, lds, st, a);
+  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+  return CCQ_OK;
 }
 
 // y[p][n] = bf16( sum_s partial[s][p][n] ), splits added in index order.
