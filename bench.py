@@ -27,8 +27,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None until measured
-TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM bytes per launch of the GEMV kernel from rocprofv3 --pmc (profiles/gemv_narrow_config2_hbm_traffic.txt):
+# FETCH_SIZE 9407.26 KiB x 2.0 (a plain 64 MiB copy reads 32780 KiB on that counter) + WRITE_SIZE 16.0 KiB x 1.0
+TRAFFIC_BYTES_PER_LAUNCH = int(9407.26 * 1024 * 2.0 + 16.0 * 1024)
 
 
 def algorithmic_bytes(K: int, N: int, M: int, code_bytes: int, has_cluster: bool) -> int:
@@ -96,7 +97,7 @@ def cpu_baseline(canon, K, N, x_bits, budget_s=12.0):
     codes, scales, alpha, beta = canon
     reps, spent = 0, 0.0
     t_start = time.perf_counter()
-    while spent < budget_s and reps < 50:
+    while spent < budget_s and reps < 2000:
         W = o.decode(K, N, o.F2, codes, scales, alpha, beta)
         o.matmul(x_bits, W)
         reps += 1
@@ -104,6 +105,20 @@ def cpu_baseline(canon, K, N, x_bits, budget_s=12.0):
     nbytes = algorithmic_bytes(K, N, 1, codes.size, True)
     return {"value": round(nbytes * reps / spent / 1e9, 4), "unit": "GB/s", "cores": o.num_threads(), "kind": "oracle",
             "sample": f"whole workload (decode + fp64 GEMV of the {N}x{K} matrix, M=1), {reps} repetitions, {spent:.1f} s"}
+
+
+def calibrate_copy(dev) -> int:
+    """A plain copy kernel of known size, rotating over buffers that together exceed the last-level cache."""
+    import torch
+    nbytes = 64 << 20
+    srcs = [torch.full((nbytes,), i, dtype=torch.uint8, device=dev) for i in range(6)]
+    dsts = [torch.empty_like(s) for s in srcs]
+    launches = 24
+    for i in range(launches):
+        dsts[i % 6].copy_(srcs[i % 6])
+    torch.cuda.synchronize()
+    print(json.dumps({"calibration": "plain device copy", "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes, "launches": launches}))
+    return 0
 
 
 def main() -> int:
@@ -115,6 +130,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--launch", type=str, default="", help="explicit decomposition RT,WR,WK,S for tuning (default: the library's choice)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of known size (64 MiB read + 64 MiB written per launch): the reference that "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -127,6 +145,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     b.load()
+
+    if args.calibrate_copy:
+        return calibrate_copy(dev)
 
     K = N = 8192
     M = 1
@@ -156,7 +177,7 @@ def main() -> int:
                    "M": M, "K": K, "N": N, "weight_copies": args.copies, "bytes_per_step": nbytes, "launch": "HIP graph replay"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "ccq_skinny_kernel", "us_per_launch": round(per_launch_s * 1e6, 3)},
+                     "kernel": "ccq_gemv_narrow_kernel", "us_per_launch": round(per_launch_s * 1e6, 3)},
     }
 
     if not args.no_prefill:
