@@ -188,12 +188,12 @@ def main() -> int:
         wp = b.Weight.from_canonical(Kp, Np, [b.NARROW], cp, sp, ap_, bp_, device=dev)
         xp = b.bf16_tensor(synth.activations_bf16(Mp, Kp, synth.rng(5, 3)), dev)
         yp = torch.empty((Mp, Np), dtype=torch.bfloat16, device=dev)
-        wsp = torch.empty(max(b.pack_info(wp.desc, 64).workspace_bytes, 16), dtype=torch.uint8, device=dev)
+        wsp = torch.empty(max(b.pack_info(wp.desc, Mp).workspace_bytes, 16), dtype=torch.uint8, device=dev)
         for _ in range(2):
             b.gemm(wp, xp, out=yp, workspace=wsp)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 5
+        reps = 20
         e0.record()
         for _ in range(reps):
             b.gemm(wp, xp, out=yp, workspace=wsp)

@@ -98,11 +98,28 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
 
 using namespace ccq;
 
+// Which kernel a dense call of M rows uses when no launch shape is given.
+enum DensePath { kPathGemv, kPathSkinny, kPathMid, kPathPrefill };
+static DensePath dense_path(const Layout& L, int M) {
+  const bool narrow_only = L.tiles[kWide] == 0;
+  if (M == 1 && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
+  if (M < kMidMinM) return kPathSkinny;
+  if (narrow_only && M > 128) return kPathPrefill;            // 256-row tiles pay off
+  return kPathMid;
+}
+
 static int64_t dense_workspace_bytes(const Layout& L, int M) {
   int64_t need = 0;
-  for (int m = 1; m <= M && m <= kMaxSkinnyM; ++m) {
-    Decomp d = choose_decomp(L, m, 1, m);
-    if (d.S > 1) need = std::max(need, (int64_t)d.S * m * L.N * 4);
+  for (int m = 1; m <= M; ++m) {
+    const DensePath p = dense_path(L, m);
+    if (p == kPathPrefill) continue;
+    if (p == kPathMid) {
+      const int S = mid_splits(L, m);
+      if (S > 1) need = std::max(need, (int64_t)S * m * L.N * 4);
+    } else {
+      Decomp d = choose_decomp(L, m, 1, m);
+      if (d.S > 1) need = std::max(need, (int64_t)d.S * m * L.N * 4);
+    }
   }
   return need;
 }
@@ -248,14 +265,32 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
   if (ldx < L.K || ldy < L.N) return CCQ_ERR_BAD_PARAM;
   if (!aligned16(x) || !aligned16(y) || !aligned16(workspace) || ldx % 8 != 0 || ldy % 8 != 0) return CCQ_ERR_ALIGN;
 
-  // many rows, narrow format only: the LDS-tiled MFMA kernel
   const bool explicit_launch = launch && (launch->rows_per_wave_tiles || launch->waves_rows || launch->waves_k || launch->splits_k);
-  if (M > kMaxSkinnyM && L.tiles[kWide] == 0 && !explicit_launch) return launch_prefill(w, L, x, M, ldx, y, ldy, stream);
-
-  // one row, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
-  if (M == 1 && L.tiles[kWide] == 0 && !L.has_map && !explicit_launch) {
-    rc = launch_gemv_narrow(w, L, x, y, stream);
-    if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+  if (!explicit_launch) {
+    const DensePath path = dense_path(L, M);
+    // many rows, narrow format only: the 256-row LDS-tiled MFMA kernel
+    if (path == kPathPrefill) {
+      rc = launch_prefill(w, L, x, M, ldx, y, ldy, stream);
+      if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    }
+    // a few dozen rows (or many rows on wide / mixed formats): the 64-row LDS-tiled kernel
+    if (path == kPathMid || path == kPathPrefill) {
+      const int S = mid_splits(L, M);
+      float* partial = nullptr;
+      if (S > 1) {
+        const int64_t need = (int64_t)S * M * L.N * 4;
+        if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
+        partial = static_cast<float*>(workspace);
+      }
+      rc = launch_mid(w, L, x, M, ldx, y, ldy, partial, S, stream);
+      if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
+      if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    }
+    // one row, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
+    if (path == kPathGemv) {
+      rc = launch_gemv_narrow(w, L, x, y, stream);
+      if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    }
   }
 
   // otherwise rows are processed in passes of at most kMaxSkinnyM

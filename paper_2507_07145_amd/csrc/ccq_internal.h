@@ -92,6 +92,15 @@ int launch_skinny(const SkinnyCall& c);
 // split into equal shares of at most 12 k-tiles over at most 8 wavefronts (the caller then uses launch_skinny).
 int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream);
 
+// Kernel for a few dozen to a few hundred rows, any format mix (ccq_mid.hip): 64-row tiles, K cut into S
+// shares whose fp32 partial tiles go to `partial` ([S][M][N]) when S > 1 (then call launch_reduce_splits).
+constexpr int kMidMinM = 17;
+int mid_splits(const Layout& L, int M);
+int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
+               void* stream);
+// y[m][n] = bf16(sum_s partial[s][m][n]), shares added in index order (ccq_skinny.hip).
+int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int S, void* stream);
+
 // Large-M kernel for narrow-format weights (ccq_prefill.hip).
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 

@@ -1,0 +1,407 @@
+// Fused dequantize-and-multiply for a few dozen activation rows (about 17 to 128), any mix of the
+// narrow (L=6,N=4,S=3 + Code Cluster) and wide (L=4,N=3,S=2) formats, gfx950.
+//
+// With that many rows the per-row-tile kernel re-stages the activations far too often, and the
+// 256-row kernel wastes three quarters of its tile.  Here a workgroup owns a 64 x BN tile of the
+// output (BN = 128) and a contiguous share of K (grid.y = S shares; fp32 partial tiles go to the
+// workspace and are added in index order by the reduction kernel when S > 1).  K is walked one
+// 64-weight group per step; per step the workgroup
+//   - copies the 64 x 64 activation tile of that group's columns to LDS,
+//   - decodes the BN x 64 weight tile to bf16 in LDS: window extraction by the shift lists
+//     [9,6,3,0] / [4,2,0] and masks 0x3F / 0xF of Table 1 straight into the mantissa of fp32 128.0,
+//     then d = (w_uint - zp) * s (Alg. 2 / Alg. 3, last line) as fma(128 + state, s, -(128 + zp) s),
+//     which is exact in fp32, so the stored value is the correctly rounded bf16 of the exact weight,
+//   - multiplies the two tiles with MFMA 32x32x16 bf16 (fp32 accumulators).
+// The decode is the bound (about 4 vector instructions per weight, shared by 64 rows), so the
+// kernel is kept small enough (55 KiB of LDS, < 128 registers) for two workgroups per CU, whose
+// vector and matrix phases overlap.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <type_traits>
+
+#include "ccq_internal.h"
+
+namespace ccq {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+struct MidArgs {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const int32_t* meta;
+  const uint16_t* x;
+  uint16_t* y;
+  float* partial;
+  int64_t ldx, ldy;
+  int64_t row_tile_bytes, row_tile_scale_halfs;
+  int32_t M, N, row_tiles, m_blocks;
+  int32_t tiles[2];       // k-tiles per kind
+  int32_t groups_narrow;
+  int32_t sq[2], sr[2];   // K shares: share `split` owns tiles [split*sq + min(split, sr), +sq + (split < sr)) of each kind
+  float zp[2];
+};
+
+constexpr int kMidBM = 64;
+constexpr int kMidBN = 128;
+constexpr int kMidRow = 64 + 8;  // bf16 elements per padded LDS row (144 bytes)
+constexpr int kMidRTW = 2;       // 16-row weight tiles per wavefront
+
+__device__ __forceinline__ uint32_t and_or_m(uint32_t a, uint32_t mask, uint32_t orv) { return (a & mask) | orv; }
+
+__device__ __forceinline__ uint32_t pack_bf16_m(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 b = __builtin_convertvector(v, bf16x2);  // round to nearest even
+  return __builtin_bit_cast(uint32_t, b);
+}
+
+__device__ __forceinline__ uint32_t dword_sel(const u32x4& v, int j) { return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w)); }
+
+// FM: formats present (1 narrow, 2 wide, 3 both; a group map exists only for 3)
+template <int FM>
+__global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
+  constexpr bool HAS_N = (FM & 1) != 0, HAS_W = (FM & 2) != 0, META = FM == 3;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);   // [2][kMidBM][kMidRow]
+  uint16_t* Bs = As + 2 * kMidBM * kMidRow;           // [2][kMidBN][kMidRow]
+  int32_t* lds_meta = reinterpret_cast<int32_t*>(Bs + 2 * kMidBN * kMidRow);  // original group of each step of this share (META only)
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
+  const int split = blockIdx.y;
+  const int m0 = m_block * kMidBM, n0 = n_block * kMidBN;
+  const int kq = lane >> 4, nl = lane & 15;
+
+  // this share's k-tiles of each kind, and its steps (one 64-weight group each): narrow first, then wide
+  int tA[2], tB[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    tA[k] = split * a.sq[k] + min(split, a.sr[k]);
+    tB[k] = tA[k] + a.sq[k] + (split < a.sr[k] ? 1 : 0);
+  }
+  const int nsN = HAS_N ? (tB[kNarrow] - tA[kNarrow]) * kNarrowGroupsPerTile : 0;
+  const int nsW = HAS_W ? (tB[kWide] - tA[kWide]) * kWideGroupsPerTile : 0;
+  const int nsteps = nsN + nsW;  // even: both factors are
+
+  if constexpr (META) {
+    for (int s = tid; s < nsteps; s += 256) {
+      const int pg = s < nsN ? tA[kNarrow] * kNarrowGroupsPerTile + s : a.groups_narrow + tA[kWide] * kWideGroupsPerTile + (s - nsN);
+      lds_meta[s] = a.meta[pg];
+    }
+    __syncthreads();
+  }
+  // original group (activation columns 64 g .. 64 g + 63) of step s
+  auto group_of = [&](int s) -> int {
+    s = min(s, nsteps - 1);
+    if constexpr (META) return lds_meta[s];
+    return s < nsN ? tA[kNarrow] * kNarrowGroupsPerTile + s : tA[kWide] * kWideGroupsPerTile + (s - nsN);
+  };
+
+  // per-wavefront weight rows: row tiles n0/16 + wave*RTW + i, lane (nl, kq)
+  const uint8_t* code_base[kMidRTW];
+  const uint16_t* scale_base[kMidRTW];
+  float al[kMidRTW], be[kMidRTW];
+#pragma unroll
+  for (int i = 0; i < kMidRTW; ++i) {
+    const int rtile = min(n0 / 16 + wave * kMidRTW + i, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
+    code_base[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;
+    scale_base[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
+    al[i] = 0.f;
+    be[i] = 0.f;
+    if constexpr (HAS_N) {
+      al[i] = a.alpha[rtile * 16 + nl];
+      be[i] = a.beta[rtile * 16 + nl];
+    }
+  }
+  const int64_t wide_code_off = (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
+  const int64_t wide_scale_off = (int64_t)a.tiles[kNarrow] * kNarrowTileScaleHalfs;
+  uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u, mask_w = 0x000F0000u;
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(c43), "+s"(mask_n), "+s"(mask_w), "+v"(magic));
+
+  // code tiles in registers: the one being decoded and the next one of the same kind
+  u32x4 cn[kMidRTW], cn_next[kMidRTW];
+  uint2 sn[kMidRTW], sn_next[kMidRTW];
+  u32x4 cw[kMidRTW][3], cw_next[kMidRTW][3];
+  uint4 sw[kMidRTW], sw_next[kMidRTW];
+  auto load_narrow = [&](u32x4 (&c)[kMidRTW], uint2 (&sc)[kMidRTW], int kt) {
+    kt = min(kt, a.tiles[kNarrow] - 1);
+#pragma unroll
+    for (int i = 0; i < kMidRTW; ++i) {
+      c[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_base[i] + (int64_t)kt * kNarrowTileBytes + lane * 16));
+      sc[i] = *reinterpret_cast<const uint2*>(scale_base[i] + (int64_t)kt * kNarrowTileScaleHalfs + nl * 4);
+    }
+  };
+  auto load_wide = [&](u32x4 (&c)[kMidRTW][3], uint4 (&sc)[kMidRTW], int kt) {
+    kt = min(kt, a.tiles[kWide] - 1);
+#pragma unroll
+    for (int i = 0; i < kMidRTW; ++i) {
+      const uint8_t* t = code_base[i] + wide_code_off + (int64_t)kt * kWideTileBytes + lane * 16;
+      c[i][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
+      c[i][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
+      // the third segment has entries for 48 lanes only; lanes 48..63 re-read lane 47's entry (what they
+      // decode from it lands in the padding columns of the LDS row)
+      c[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47 ? (lane - 47) * 16 : 0)));
+      sc[i] = *reinterpret_cast<const uint4*>(scale_base[i] + wide_scale_off + (int64_t)kt * kWideTileScaleHalfs + nl * 8);
+    }
+  };
+
+  // activation copy: 2 chunks of 16 bytes per thread and step; rows past M re-read row M-1 (their
+  // products land in accumulator rows that are never stored)
+  const uint16_t* xrow[2];
+  int a_lds_off[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, col = c & 7;
+    xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
+    a_lds_off[i] = row * kMidRow + col * 8;
+  }
+  auto load_a = [&](u32x4 (&dst)[2], int s) {
+    const int64_t off = (int64_t)group_of(s) * kGroup;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) dst[i] = *reinterpret_cast<const u32x4*>(xrow[i] + off);
+  };
+  auto store_a = [&](int buf, const u32x4 (&src)[2]) {
+    uint16_t* dst = As + buf * kMidBM * kMidRow;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = src[i];
+  };
+
+  // decode group j of the held narrow k-tile: 16 weights per lane (k = 16 kq .. 16 kq + 15)
+  auto decode_narrow = [&](int buf, int j) {
+    uint16_t* dst = Bs + buf * kMidBN * kMidRow;
+#pragma unroll
+    for (int i = 0; i < kMidRTW; ++i) {
+      const uint32_t d = dword_sel(cn[i], j);
+      const uint32_t sd = (j >> 1) ? sn[i].y : sn[i].x;
+      const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+      const float c0 = -(128.f + a.zp[kNarrow]) * s;  // exact: 8-bit times 11-bit significand
+      const float bem = be[i] + magic;                 // + 2^23: exact, beta is an integer below 2^15
+      uint32_t o[8];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], bem);
+        const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code (Alg. 3)
+        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 7, mask_n, c43)), s, c0);
+        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 10, mask_n, c43)), s, c0);
+        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 13, mask_n, c43)), s, c0);
+        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 16, mask_n, c43)), s, c0);
+        o[2 * b] = pack_bf16_m(w0, w1);
+        o[2 * b + 1] = pack_bf16_m(w2, w3);
+      }
+      uint16_t* p = dst + ((wave * kMidRTW + i) * 16 + nl) * kMidRow + kq * 16;
+      *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
+      *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
+    }
+  };
+  // decode group j of the held wide k-tile: canonical bytes 6 kq .. 6 kq + 5 of the group, 3 weights each
+  // (k = 18 kq .. 18 kq + 17).  Quarter 3 owns bytes 18..21 only (weights 54..63); what it writes beyond
+  // column 63 falls into the padding of its own LDS row.
+  auto decode_wide = [&](int buf, int j) {
+    uint16_t* dst = Bs + buf * kMidBN * kMidRow;
+#pragma unroll
+    for (int i = 0; i < kMidRTW; ++i) {
+      const uint32_t sd = dword_sel(u32x4{sw[i].x, sw[i].y, sw[i].z, sw[i].w}, j >> 1);
+      const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+      const float c0 = -(128.f + a.zp[kWide]) * s;
+      float w[18];
+#pragma unroll
+      for (int t = 0; t < 3; ++t) {
+        const uint32_t dd = dword_sel(cw[i][t], j >> 1);
+        const uint32_t h = (j & 1) ? (dd >> 16) : (dd & 0xFFFFu);  // two codes: low byte first
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const uint32_t c = (h >> (8 * b)) & 0xFFu;
+          // shift list [4,2,0], mask 0xF (Table 1), into bits 16..19
+          w[6 * t + 3 * b + 0] = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(c << 12, mask_w, c43)), s, c0);
+          w[6 * t + 3 * b + 1] = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(c << 14, mask_w, c43)), s, c0);
+          w[6 * t + 3 * b + 2] = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(c << 16, mask_w, c43)), s, c0);
+        }
+      }
+      uint32_t* p = reinterpret_cast<uint32_t*>(dst + ((wave * kMidRTW + i) * 16 + nl) * kMidRow + kq * 18);
+#pragma unroll
+      for (int q = 0; q < 9; ++q) p[q] = pack_bf16_m(w[2 * q], w[2 * q + 1]);
+    }
+  };
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  const int a_frag_off = (lane & 31) * kMidRow + (lane >> 5) * 8;
+  const int b_frag_off = (wave * 32 + (lane & 31)) * kMidRow + (lane >> 5) * 8;
+  auto multiply = [&](int buf) {
+    const uint16_t* Ab = As + buf * kMidBM * kMidRow + a_frag_off;
+    const uint16_t* Bb = Bs + buf * kMidBN * kMidRow + b_frag_off;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const bf16x8 bfr = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + kk * 16));
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const bf16x8 af = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * kMidRow + kk * 16));
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[i], 0, 0, 0);
+      }
+    }
+  };
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  };
+
+  // Every share holds at least two k-tiles of each format present (the launcher sees to it).  All global
+  // loads below are unconditional and sit at fixed places of straight-line loop bodies: a request under a
+  // condition makes the compiler wait for every outstanding load at the next use of any of them.
+  {
+    // activation chunks of step s live in register set s & 3, requested four steps ahead of their use: a
+    // step is far shorter than a memory latency
+    u32x4 areg[4][2];
+    int s = 0;  // step counter of this share: narrow steps first, then wide ones
+    if constexpr (HAS_N) load_narrow(cn, sn, tA[kNarrow]);
+    if constexpr (HAS_W) load_wide(cw, sw, tA[kWide]);
+    load_a(areg[0], 0);
+    load_a(areg[1], 1);
+    load_a(areg[2], 2);
+    load_a(areg[3], 3);
+    store_a(0, areg[0]);
+    if constexpr (HAS_N) decode_narrow(0, 0);
+    else decode_wide(0, 0);
+    lds_barrier();
+    // one step (J = s & 3): LDS buffer J & 1 is multiplied while step s + 1 is written to the other buffer
+    // and the activations of step s + 4 are requested
+    auto step = [&](auto JC, auto&& decode_next) {
+      constexpr int J = decltype(JC)::value;
+      constexpr int P = J & 1;
+      load_a(areg[J], s + 4);
+      multiply(P);
+      store_a(P ^ 1, areg[(J + 1) & 3]);
+      decode_next(P ^ 1);
+      lds_barrier();
+      ++s;
+    };
+    using J0 = std::integral_constant<int, 0>;
+    using J1 = std::integral_constant<int, 1>;
+    using J2 = std::integral_constant<int, 2>;
+    using J3 = std::integral_constant<int, 3>;
+    if constexpr (HAS_N) {
+      for (int t = tA[kNarrow]; t < tB[kNarrow]; ++t) {
+        load_narrow(cn_next, sn_next, t + 1);
+        step(J0{}, [&](int nb) { decode_narrow(nb, 1); });
+        step(J1{}, [&](int nb) { decode_narrow(nb, 2); });
+        step(J2{}, [&](int nb) { decode_narrow(nb, 3); });
+        step(J3{}, [&](int nb) {
+#pragma unroll
+          for (int i = 0; i < kMidRTW; ++i) { cn[i] = cn_next[i]; sn[i] = sn_next[i]; }
+          if (t + 1 < tB[kNarrow]) decode_narrow(nb, 0);
+          else if constexpr (HAS_W) decode_wide(nb, 0);
+        });
+      }
+    }
+    if constexpr (HAS_W) {
+      for (int t = tA[kWide]; t < tB[kWide]; ++t) {
+        load_wide(cw_next, sw_next, t + 1);
+        step(J0{}, [&](int nb) { decode_wide(nb, 1); });
+        step(J1{}, [&](int nb) { decode_wide(nb, 2); });
+        step(J2{}, [&](int nb) { decode_wide(nb, 3); });
+        step(J3{}, [&](int nb) { decode_wide(nb, 4); });
+        step(J0{}, [&](int nb) { decode_wide(nb, 5); });
+        step(J1{}, [&](int nb) { decode_wide(nb, 6); });
+        step(J2{}, [&](int nb) { decode_wide(nb, 7); });
+        step(J3{}, [&](int nb) {
+#pragma unroll
+          for (int i = 0; i < kMidRTW; ++i) {
+#pragma unroll
+            for (int tt = 0; tt < 3; ++tt) cw[i][tt] = cw_next[i][tt];
+            sw[i] = sw_next[i];
+          }
+          if (t + 1 < tB[kWide]) decode_wide(nb, 0);
+        });
+      }
+    }
+  }
+
+  // epilogue: D[row][col], row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32
+  const int n = n0 + wave * 32 + (lane & 31);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      const float val = acc[i][r];  // by value: bit-casting the element lvalue itself reads element 0
+      if (m < a.M && n < a.N) {
+        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + m) * a.N + n] = val;
+        else a.y[(int64_t)m * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
+      }
+    }
+  }
+}
+
+// K shares for the mid-M kernel.  The kernel is bound by instruction issue, and a second workgroup on a CU
+// adds only about 15 %, while every share costs a pass of fp32 partial tiles through memory (written, then
+// read by the reduction): aim at one workgroup per CU, at least two k-tiles of every format per share.
+int mid_splits(const Layout& L, int M) {
+  const int64_t blocks = (int64_t)((M + kMidBM - 1) / kMidBM) * ((L.N + kMidBN - 1) / kMidBN);
+  const int min_tiles = std::min(L.tiles[kNarrow] > 0 ? L.tiles[kNarrow] : 1 << 30, L.tiles[kWide] > 0 ? L.tiles[kWide] : 1 << 30);
+  int64_t s = std::max<int64_t>(1, 256 / std::max<int64_t>(1, blocks));
+  s = std::min<int64_t>(s, 8);
+  s = std::min<int64_t>(s, std::max(1, min_tiles / 2));
+  return (int)s;
+}
+
+int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
+               void* stream) {
+  MidArgs a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.meta = static_cast<const int32_t*>(w->meta);
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.partial = partial;
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.row_tile_bytes = L.row_tile_bytes;
+  a.row_tile_scale_halfs = L.row_tile_scale_halfs;
+  a.M = M;
+  a.N = L.N;
+  a.row_tiles = L.row_tiles;
+  a.m_blocks = (M + kMidBM - 1) / kMidBM;
+  a.tiles[0] = L.tiles[0];
+  a.tiles[1] = L.tiles[1];
+  a.groups_narrow = L.groups[kNarrow];
+  for (int k = 0; k < 2; ++k) {
+    a.sq[k] = L.tiles[k] / S;
+    a.sr[k] = L.tiles[k] % S;
+    a.zp[k] = L.zp[k];
+  }
+  const int n_blocks = (L.N + kMidBN - 1) / kMidBN;
+  const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
+  const int max_steps = ((L.tiles[kNarrow] + S - 1) / S) * kNarrowGroupsPerTile + ((L.tiles[kWide] + S - 1) / S) * kWideGroupsPerTile;
+  const size_t lds = (size_t)2 * (kMidBM + kMidBN) * kMidRow * 2 + (fm == 3 ? (size_t)max_steps * 4 : 0);
+  if (lds > 64 * 1024) return CCQ_ERR_UNSUPPORTED;
+  const void* kern = fm == 1 ? reinterpret_cast<const void*>(ccq_mid_kernel<1>)
+                             : (fm == 2 ? reinterpret_cast<const void*>(ccq_mid_kernel<2>) : reinterpret_cast<const void*>(ccq_mid_kernel<3>));
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  dim3 grid((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block(256);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (fm == 1) hipLaunchKernelGGL(ccq_mid_kernel<1>, grid, block, lds, st, a);
+  else if (fm == 2) hipLaunchKernelGGL(ccq_mid_kernel<2>, grid, block, lds, st, a);
+  else hipLaunchKernelGGL(ccq_mid_kernel<3>, grid, block, lds, st, a);
+  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+  return CCQ_OK;
+}
+
+}  // namespace ccq

@@ -196,46 +196,64 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
                             int ng, int sg, int j0, int tid, int nthreads) {
   using TR = Traits<KIND>;
   constexpr int MRT = (MT == 1) ? MR : MT * 16;
+  constexpr int U = (KIND == kNarrow) ? 4 : 2;  // fragments requested per thread before the first is used
   const int nfrag = ng * TR::T * 4 * MRT;
   const int meta_base = (KIND == kWide) ? a.groups_narrow : 0;
-  for (int f = tid; f < nfrag; f += nthreads) {
-    const int m = f % MRT;
-    const int kq = (f / MRT) & 3;
-    const int t = (f / (MRT * 4)) % TR::T;
-    const int lg = f / (MRT * 4 * TR::T);
-    uint4 o = {0u, 0u, 0u, 0u};
-    if (m < rows_valid) {
+  // the workgroup size is a multiple of MRT, so a thread stages the same activation row every time
+  const int m = tid % MRT;
+  const bool row_ok = m < rows_valid;
+  const uint16_t* xrow = x;
+  if (row_ok) xrow = x + (a.sorted_rows ? (int64_t)a.sorted_rows[row_base + m] : (int64_t)(row_base + m)) * a.ldx;
+  for (int f0 = tid; f0 < nfrag; f0 += nthreads * U) {
+    uint4 v[U];
+    uint32_t h[U][6];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int f = min(f0 + u * nthreads, nfrag - 1);  // clamped: the request is unconditional
+      const int kq = (f / MRT) & 3;
+      const int t = (f / (MRT * 4)) % TR::T;
+      const int lg = f / (MRT * 4 * TR::T);
       const int pg = pg0 + (lg / sg) * TR::GPT + j0 + lg % sg;
       const int g = META ? a.meta[meta_base + pg] : pg;  // a group map exists only for mixed formats
-      const int64_t row = a.sorted_rows ? (int64_t)a.sorted_rows[row_base + m] : (int64_t)(row_base + m);
-      const uint16_t* xr = x + row * a.ldx + (int64_t)g * kGroup;
+      const uint16_t* xr = xrow + (int64_t)g * kGroup;
       if constexpr (KIND == kNarrow) {
-        // the two codes of a k-step cover weights 16kq+8t+{0..3} and +{4..7}; slots
-        // interleave them: {0,4,1,5,2,6,3,7}
-        const uint4 v = *reinterpret_cast<const uint4*>(xr + 16 * kq + 8 * t);
-        o.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);
-        o.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
-        o.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
-        o.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
+        v[u] = *reinterpret_cast<const uint4*>(xr + 16 * kq + 8 * t);
       } else {
         // codes ja = 6kq+2t and ja+1 cover weights 3ja+{0,1,2} and 3ja+3+{0,1,2};
         // slots {a0,b0,a1,b1,a2,b2,-,-}; code 21 carries weight 63 only
         const int ja = 6 * kq + 2 * t;
-        uint32_t h[6];
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
 #pragma unroll
           for (int which = 0; which < 2; ++which) {
             const int jj = ja + which, wi = 3 * jj + i;
-            h[2 * i + which] = (jj <= 21 && wi < kGroup) ? (uint32_t)xr[wi] : 0u;
+            h[u][2 * i + which] = (jj <= 21 && wi < kGroup) ? (uint32_t)xr[wi] : 0u;
           }
         }
-        o.x = h[0] | (h[1] << 16);
-        o.y = h[2] | (h[3] << 16);
-        o.z = h[4] | (h[5] << 16);
       }
     }
-    lds_x[f] = o;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int f = f0 + u * nthreads;
+      if (f < nfrag) {
+        uint4 o = {0u, 0u, 0u, 0u};
+        if (row_ok) {
+          if constexpr (KIND == kNarrow) {
+            // the two codes of a k-step cover weights 16kq+8t+{0..3} and +{4..7}; slots
+            // interleave them: {0,4,1,5,2,6,3,7}
+            o.x = __builtin_amdgcn_perm(v[u].z, v[u].x, 0x05040100u);
+            o.y = __builtin_amdgcn_perm(v[u].z, v[u].x, 0x07060302u);
+            o.z = __builtin_amdgcn_perm(v[u].w, v[u].y, 0x05040100u);
+            o.w = __builtin_amdgcn_perm(v[u].w, v[u].y, 0x07060302u);
+          } else {
+            o.x = h[u][0] | (h[u][1] << 16);
+            o.y = h[u][2] | (h[u][3] << 16);
+            o.z = h[u][4] | (h[u][5] << 16);
+          }
+        }
+        lds_x[f] = o;
+      }
+    }
   }
   __syncthreads();
   // start values for the rows that are really held; rows beyond them are never stored
@@ -334,18 +352,31 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
   }
 }
 
+// Code Cluster offset plus 2^23 (exact: beta is an integer below 2^15).  The constant is made opaque so that
+// the addition stays where it is written, below the first requests for code tiles: hoisted to the load of
+// beta it would make everything after it wait for that load.
+template <int RT>
+__device__ __forceinline__ void add_code_magic(float (&be)[RT], const float (&be_raw)[RT]) {
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(magic));
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) be[rt] = be_raw[rt] + magic;
+}
+
 // All k-tiles of one kind that belong to this workgroup, chunk by chunk: the
 // activations of a chunk (KC k-tiles for each of the WK wavefronts along K) are
 // staged in LDS, then every wavefront walks its own tiles with a register ring
 // of D tiles in flight.
 template <int KIND, int MT, int MR, int RT, bool META>
 __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
-                               const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
+                               const float (&al)[RT], const float (&be_raw)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
                                DecodeConsts dc) {
   using TR = Traits<KIND>;
-  constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 4 : 2) : (RT == 1 ? 2 : 1);  // tiles in flight per wavefront
-  const int tiles = a.tiles[KIND];
+  // tiles in flight per wavefront: as many as the register budget of the instantiation allows (a refill is
+  // requested one tile's work before it is needed, far less than a memory latency, so depth is what keeps
+  // the memory system busy)
+  constexpr int D = (KIND == kNarrow) ? (MT == 1 ? (RT == 1 ? 8 : 4) : (RT == 1 ? 4 : 2)) : (RT == 1 ? 2 : 1);
   int A, B;
   split_range(a, KIND, split, A, B);
   const int KC = a.KC[KIND], CH = KC * a.WK;
@@ -366,6 +397,8 @@ __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[R
     }
     __syncthreads();  // the previous chunk's fragments are no longer read
     stage_chunk<KIND, MT, MR, META>(lds_x, lds_cneg, a, x, row_base, rows_valid, c0 * TR::GPT, (cend - c0) * TR::GPT, TR::GPT, 0, tid, nthreads);
+    float be[RT];
+    add_code_magic<RT>(be, be_raw);
     if (active && n > 0) {
       for (int j = 0; j + 1 < ngroups; ++j) {
 #pragma unroll
@@ -408,7 +441,7 @@ struct SubSteps {
 
 template <int KIND, int MT, int MR, int RT, int SG, bool META>
 __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[RT], const uint16_t* (&scales_rt)[RT], bool active,
-                                const float (&al)[RT], const float (&be)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
+                                const float (&al)[RT], const float (&be_raw)[RT], f32x4 (&acc)[RT][MT], uint4* lds_x, float* lds_cneg,
                                 const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
                                 DecodeConsts dc) {
   using TR = Traits<KIND>;
@@ -420,6 +453,8 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(cur[rt], codes_rt[rt], scales_rt[rt], A + wk, lane);
   }
+  float be[RT];
+  add_code_magic<RT>(be, be_raw);
   for (int c0 = A; c0 < B; c0 += a.WK) {
     const int ntiles = min(a.WK, B - c0);
     const bool has = active && wk < ntiles;
@@ -575,10 +610,7 @@ __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)
     // the Code Cluster offset plus 2^23 (exact: beta is an integer below 2^15); added only here so that
     // nothing above waits for the per-row parameters to arrive
     float be[RT];
-    float magic = 8388608.f;
-    asm volatile("" : "+v"(magic));  // pins the addition below the requests
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) be[rt] = be_raw[rt] + magic;
+    add_code_magic<RT>(be, be_raw);
     for (int j = 0; j + 1 < ngroups; ++j) {
 #pragma unroll
       for (int i = 0; i < D; ++i) {
@@ -624,6 +656,13 @@ __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&c
 template <int MT, int MR, int RT, int FM>
 __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 1024)) ccq_skinny_kernel(const SkinnyArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
+  // Fetch the whole argument block now, in one batch of scalar loads: left to itself the compiler loads it
+  // piecemeal behind the early branches, four dependent round trips (about 2.5 us) before the first request
+  // for weights goes out.
+  asm volatile("" ::"s"(a.codes), "s"(a.scales), "s"(a.alpha), "s"(a.beta), "s"(a.meta), "s"(a.x), "s"(a.y), "s"(a.partial), "s"(a.sorted_rows),
+               "s"(a.expert_offsets), "s"(a.ldx), "s"(a.ldy), "s"(a.codes_stride), "s"(a.scales_stride), "s"(a.ab_stride), "s"(a.row_tile_bytes),
+               "s"(a.row_tile_scale_halfs), "s"(a.M), "s"(a.N), "s"(a.row_tiles), "s"(a.tiles[0]), "s"(a.tiles[1]), "s"(a.WR), "s"(a.WK),
+               "s"(a.S), "s"(a.inv_WR));
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps tile indices and base pointers in scalar registers
@@ -662,9 +701,8 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
       al[rt] = alpha[rtile * 16 + (lane & 15)];
       be[rt] = beta[rtile * 16 + (lane & 15)];
     }
-    // + 2^23 (exact: beta is an integer below 2^15) puts the rounded code into the low mantissa bits; with one
-    // held row the addition is made later, after the first tiles have been requested
-    if constexpr (MR != 1) be[rt] += 8388608.f;
+    // + 2^23 (exact: beta is an integer below 2^15), which puts the rounded code into the low mantissa bits, is
+    // added later, after the first tiles have been requested: nothing before that waits for these two loads
   }
 
   uint4* lds_x = reinterpret_cast<uint4*>(smem);
@@ -979,9 +1017,11 @@ int launch_skinny(const SkinnyCall& c) {
   a.cneg[0] = -(128.f + L.zp[0]);
   a.cneg[1] = -(128.f + L.zp[1]);
 
-  // chunk sizes: as many k-tiles per wavefront as fit a 56 KiB staging budget; if not even one
-  // tile per wavefront fits, the groups of a tile are staged a few at a time
-  const int64_t budget = 56 * 1024;
+  // chunk sizes: as many k-tiles per wavefront as fit the staging budget; if not even one tile per
+  // wavefront fits, the groups of a tile are staged a few at a time.  Up to 16 held rows the budget is
+  // 36 KiB, so that four workgroups share a CU and one workgroup's staging (barrier, gather, barrier)
+  // is covered by the others' contraction.
+  const int64_t budget = (mt == 1 ? 36 : 56) * 1024;
   int64_t frag_cap = 0, cneg_cap = 0;
   for (int k = 0; k < 2; ++k) {
     a.KC[k] = 1;
@@ -1042,13 +1082,16 @@ int launch_skinny(const SkinnyCall& c) {
   dim3 block((unsigned)(64 * d.WR * d.WK));
   hipLaunchKernelGGL(kern, grid, block, (size_t)lds, stream, a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
-  if (d.S > 1) {
-    const int64_t total = (int64_t)c.M * L.N;
-    const int threads = 256;
-    hipLaunchKernelGGL(ccq_reduce_splits_kernel, dim3((unsigned)((total + threads - 1) / threads)), dim3(threads), 0, stream, c.partial,
-                       static_cast<uint16_t*>(c.y), c.ldy, c.M, L.N, d.S);
-    if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
-  }
+  if (d.S > 1) return launch_reduce_splits(c.partial, c.y, c.ldy, c.M, L.N, d.S, c.stream);
+  return CCQ_OK;
+}
+
+int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int S, void* stream) {
+  const int64_t total = (int64_t)rows * N;
+  const int threads = 256;
+  hipLaunchKernelGGL(ccq_reduce_splits_kernel, dim3((unsigned)((total + threads - 1) / threads)), dim3(threads), 0, static_cast<hipStream_t>(stream),
+                     partial, static_cast<uint16_t*>(y), ldy, rows, N, S);
+  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }
 

@@ -12,7 +12,7 @@ from paper_2507_07145_amd import synth
 # The error budget is the bf16 output rounding (2^-9 relative) plus fp32 accumulation noise;
 # the skinny path decodes weights exactly, the prefill path also rounds them to bf16.
 REL_TOL = 1e-2
-# The large-M kernel multiplies bf16-rounded weights (relative error <= 2^-9 each), so an element can be off by
+# The LDS-tiled kernels (more than 16 rows) multiply bf16-rounded weights (relative error <= 2^-9 each), so an element can be off by
 # 2^-9 * sum_k |x_k W_nk| whatever the size of the sum itself; with heavy-tailed group scales and a short K a
 # single large term can make that exceed 1e-2 * rms.  Tests of that kernel pass the absolute sum and allow
 # 2^-8 of it on top (weight rounding plus fp32 accumulation), a bound that follows from the arithmetic.

@@ -33,7 +33,9 @@ def _check_sampled(case: Case, w, Ms, cfg, rows, decode_cols):
     for M in Ms:
         x = synth.activations_bf16(M, case.K, synth.rng(cfg, 100 + M))
         got = _run(w, x)
-        assert_gemm_close(got[:, rows], o.matmul(x, Wr), f"config {cfg} M={M}")
+        # beyond 16 rows the LDS-tiled kernels multiply bf16-rounded weights: the bound gains the term derived in cases.py
+        abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(Wr)) if M > 16 else None
+        assert_gemm_close(got[:, rows], o.matmul(x, Wr), f"config {cfg} M={M}", abs_sum=abs_sum)
     for i in range(0, len(decode_cols), 16):
         ks = [int(k) for k in decode_cols[i:i + 16]]
         got = _run(w, synth.one_hot_bf16(ks, case.K))

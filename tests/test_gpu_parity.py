@@ -130,6 +130,25 @@ def test_formats_decode_and_gemm(kinds, K, N, n_wide):
             assert_gemm_close(_gemm_bits(w, x, launch=b.ccq_launch(*launch)), ref, f"{kinds} M={M} launch={launch}")
 
 
+@pytest.mark.parametrize("kinds,K,N,M,n_wide", [(["wide"], 2048, 144, 70, None), (["narrow", "wide"], 4096, 272, 40, 32),
+                                                (["narrow"], 2048, 128, 100, None), (["narrow", "wide"], 2048, 64, 17, 8),
+                                                (["wide"], 1024, 400, 130, None)])
+def test_mid_kernel_formats(kinds, K, N, M, n_wide):
+    """17 and more rows (any format mix; beyond 128 rows unless narrow only) run the 64-row LDS-tiled kernel: K cut into
+    one or several shares, ragged row and column blocks, the group map of mixed formats.  Decoded weights exact through
+    one-hot rows, products within tolerance."""
+    c = random_case(K, N, kinds, 9, stream0=20 * len(kinds) + N % 11, n_wide=n_wide)
+    w = c.device_weight(DEV)
+    x = synth.activations_bf16(M, K, synth.rng(9, 300 + M))
+    abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(c.W()))
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"mid {kinds} K={K} N={N} M={M}", abs_sum=abs_sum)
+    ks = synth.rng(9, 310 + M).integers(0, K, M)
+    ks[:4] = [0, 63, K - 64, K - 1]
+    got = _gemm_bits(w, synth.one_hot_bf16(ks, K))
+    want = o.to_bf16_bits(c.W()[:, ks].T)
+    assert np.array_equal(canon_zero(got), canon_zero(want)), f"mid kernel {kinds}: decoded weights differ"
+
+
 def test_strided_activations_and_guard_bands():
     """ldx > K, ldy > N: nothing outside y[:M, :N] is written."""
     c = random_case(1024, 96, ["narrow"], 8)
