@@ -19,6 +19,9 @@
  *                         graph of Fig. 1 (must return the identical code)
  *   cco_refit_scale       Eq. 4 (closed-form least-squares scale)
  *   cco_quantize          Alg. 1 + Sec. 3.3 Code Cluster + Sec. 3.4 scale step
+ *   cco_expand_scales     Sec. 3.4 "Scale Compression": s = (4-bit field) * s_super,
+ *                         first line of Alg. 2 and of Alg. 3
+ *   cco_compress_scales   the encoder side of the same (channel-wise super scale)
  *   cco_matmul            y = x W^T in fp64 (the definition of the GEMM)
  *
  * Parity pins (tests/test_oracle_*.py): the (L=2,N=3,S=1) worked example of
@@ -199,12 +202,11 @@ int64_t cco_row_bytes(int K, int g, const cco_code fmt[2], const uint8_t *group_
   return total;
 }
 
-/* Decode the whole matrix to fp64: W[n][k] = (state - zp) * scale[n][k/g].
- * The value is exact (a <=7-bit integer or half-integer times an 11-bit
- * significand), so no rounding mode is involved.  group_fmt may be NULL. */
-int cco_decode(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *group_fmt,
-               const uint8_t *codes, const uint16_t *scales_fp16, const float *alpha,
-               const float *beta, double *W) {
+/* Decode the whole matrix to fp64 with the group scales given as fp64:
+ * W[n][k] = (state - zp) * scale[n][k/g].  group_fmt may be NULL. */
+int cco_decode_f64scales(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *group_fmt,
+                         const uint8_t *codes, const double *scales, const float *alpha,
+                         const float *beta, double *W) {
   if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0) return -2;
   int G = K / g;
   int64_t row_bytes = cco_row_bytes(K, g, fmt, group_fmt);
@@ -215,7 +217,7 @@ int cco_decode(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *gr
     for (int gi = 0; gi < G; ++gi) {
       const cco_code *f = &fmt[group_fmt ? group_fmt[gi] : 0];
       int cb = cco_code_bytes(f), T = cco_T(f->L, f->N, f->S);
-      double s = cco_fp16_to_double(scales_fp16[(int64_t)n * G + gi]);
+      double s = scales[(int64_t)n * G + gi];
       for (int idx = 0; idx < g; ++idx) {
         int j = idx / f->N, i = idx % f->N; /* Alg. 2/3: code index, shift index */
         uint32_t c = load_code(p + (int64_t)j * cb, cb);
@@ -236,6 +238,71 @@ int cco_decode(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *gr
     }
   }
   return status;
+}
+
+/* The same with fp16 group scales.  The value is exact (a <=7-bit integer or
+ * half-integer times an 11-bit significand), so no rounding mode is involved. */
+int cco_decode(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *group_fmt,
+               const uint8_t *codes, const uint16_t *scales_fp16, const float *alpha,
+               const float *beta, double *W) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0) return -2;
+  int64_t n = (int64_t)Nrows * (K / g);
+  double *sc = (double *)malloc(sizeof(double) * (size_t)n);
+  if (!sc) return -4;
+  for (int64_t i = 0; i < n; ++i) sc[i] = cco_fp16_to_double(scales_fp16[i]);
+  int rc = cco_decode_f64scales(K, Nrows, g, fmt, group_fmt, codes, sc, alpha, beta, W);
+  free(sc);
+  return rc;
+}
+
+/* ---------- Sec. 3.4 Scale Compression ----------------------------------- */
+
+/* Spare low bits of a group's last stored code: when g is not a multiple of N
+ * the last code carries only g mod N states, in its top bits. */
+int cco_spare_bits(const cco_code *f, int g) {
+  int r = g % f->N;
+  if (r == 0 || f->code_cluster) return 0;
+  return (f->N - r) * f->S;
+}
+
+/* Bytes of the packed 4-bit scale array s_q per row: one nibble for every group
+ * that has no spare bits of its own. */
+int64_t cco_sq_row_bytes(int K, int g, const cco_code fmt[2], const uint8_t *group_fmt) {
+  int64_t cnt = 0;
+  for (int gi = 0; gi < K / g; ++gi)
+    if (cco_spare_bits(&fmt[group_fmt ? group_fmt[gi] : 0], g) < 4) ++cnt;
+  return (cnt + 1) / 2;
+}
+
+/* scales[n][gi] = (4-bit field) * s_super[n]   (first line of Alg. 2 / Alg. 3;
+ * s_mask = 0xF).  Exact: a 4-bit integer times an 11-bit significand. */
+int cco_expand_scales(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *group_fmt,
+                      const uint8_t *codes, const uint8_t *sq_packed, const uint16_t *s_super_fp16,
+                      double *scales) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0) return -2;
+  int G = K / g;
+  int64_t row_bytes = cco_row_bytes(K, g, fmt, group_fmt);
+  int64_t sq_bytes = cco_sq_row_bytes(K, g, fmt, group_fmt);
+  for (int n = 0; n < Nrows; ++n) {
+    const uint8_t *p = codes + (int64_t)n * row_bytes;
+    double ssup = cco_fp16_to_double(s_super_fp16[n]);
+    int64_t pidx = 0; /* index among the groups that use s_q */
+    for (int gi = 0; gi < G; ++gi) {
+      const cco_code *f = &fmt[group_fmt ? group_fmt[gi] : 0];
+      int gb = cco_group_bytes(f, g);
+      uint32_t field;
+      if (cco_spare_bits(f, g) >= 4) {
+        field = p[gb - 1] & 0xFu; /* Alg. 2: s_uint = the last value of W_q, s_mask = 0xF */
+      } else {
+        uint32_t sq = sq_packed[(int64_t)n * sq_bytes + pidx / 2];
+        field = (sq >> (4 * (pidx % 2))) & 0xFu; /* Alg. 3: (s_q >> s_shift) & s_mask */
+        ++pidx;
+      }
+      scales[(int64_t)n * G + gi] = (double)field * ssup;
+      p += gb;
+    }
+  }
+  return 0;
 }
 
 /* ---------- the GEMM definition ------------------------------------------ */
@@ -371,7 +438,8 @@ static double fp16_scale(double s) {
  *   0 = plain Eq. 1 rounding of the unconstrained codes.
  * Outputs: codes (row stride cco_row_bytes), scales fp16 [Nrows][K/g],
  * alpha/beta [Nrows] (written only when a format uses Code Cluster).
- * Steps per group: scale = absmax/(2^(L-1)-1); search; Eq. 4 refit (kept when
+ * Steps per group (an all-zero group just gets scale 0): scale =
+ * absmax/(2^(L-1)-1); search; Eq. 4 refit (kept when
  * the error does not grow); scale rounded to fp16; search again with the
  * stored scale.  Per row with Code Cluster: beta = min code, alpha =
  * (max-min)/255, q = round((c-beta)/alpha) (Eq. 1), optional re-search, then
@@ -408,9 +476,14 @@ int cco_quantize(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *
           w[i] = (double)W[(int64_t)n * K + (int64_t)gi * g + i];
           if (fabs(w[i]) > amax) amax = fabs(w[i]);
         }
+        if (amax == 0.0) { /* an all-zero group: scale 0 reproduces it exactly whatever the codes (Alg. 1 is silent here) */
+          for (int j = 0; j < cco_codes_per_group(g, f->N); ++j) gc[j] = 0;
+          rowscale[gi] = 0.0;
+          continue;
+        }
         double qmax = (double)((1 << (f->L - 1)) - 1);
         if (qmax < 1.0) qmax = 1.0;
-        double s0 = amax > 0.0 ? amax / qmax : 1.0;
+        double s0 = amax / qmax;
         search_group(w, g, f, s0, method, gc);
         group_wq(gc, f, g, wq);
         double s1 = cco_refit_scale(w, wq, g, s0);
@@ -476,6 +549,83 @@ int cco_quantize(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *
       }
     }
     free(rowcodes); free(rowscale); free(w); free(wq); free(reach);
+  }
+  return 0;
+}
+
+/* Sec. 3.4 Scale Compression, encoder side.  Input: a matrix already quantized
+ * by cco_quantize (codes, fp16 group scales, alpha/beta).  Per row: super scale
+ * = fp16(max group scale / 15); every group scale becomes the nearest multiple
+ * k * s_super, k in 1..15 (0 only for an all-zero group); because the scale that
+ * is stored has changed, the codes of every group are searched again with it
+ * (over all codes, or over the 256 reachable ones under the row's Code Cluster
+ * map).  The 4-bit fields go to the spare nibble of the group's last byte or to
+ * sq_packed (see cco_expand_scales). */
+int cco_compress_scales(int K, int Nrows, int g, const cco_code fmt[2], const uint8_t *group_fmt,
+                        const float *W, int method, uint8_t *codes, const uint16_t *scales_fp16,
+                        const float *alpha, const float *beta, uint8_t *sq_packed,
+                        uint16_t *s_super_fp16) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0) return -2;
+  int G = K / g;
+  int64_t row_bytes = cco_row_bytes(K, g, fmt, group_fmt);
+  int64_t sq_bytes = cco_sq_row_bytes(K, g, fmt, group_fmt);
+  memset(sq_packed, 0, (size_t)(sq_bytes * Nrows));
+#pragma omp parallel
+  {
+    double *w = (double *)malloc(sizeof(double) * (size_t)g);
+    uint32_t *gc = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)g);
+    uint32_t(*reach)[CCO_MAX_N] = malloc(sizeof(uint32_t[CCO_MAX_N]) * 256);
+#pragma omp for schedule(dynamic, 4)
+    for (int n = 0; n < Nrows; ++n) {
+      double smax = 0.0;
+      for (int gi = 0; gi < G; ++gi) {
+        double s = cco_fp16_to_double(scales_fp16[(int64_t)n * G + gi]);
+        if (s > smax) smax = s;
+      }
+      uint16_t sup_bits = cco_double_to_fp16(smax / 15.0);
+      double ssup = cco_fp16_to_double(sup_bits);
+      s_super_fp16[n] = sup_bits;
+      uint8_t *p = codes + (int64_t)n * row_bytes;
+      int64_t pidx = 0;
+      for (int gi = 0; gi < G; ++gi) {
+        const cco_code *f = &fmt[group_fmt ? group_fmt[gi] : 0];
+        int gb = cco_group_bytes(f, g), cb = cco_code_bytes(f), cpg = cco_codes_per_group(g, f->N);
+        double s = cco_fp16_to_double(scales_fp16[(int64_t)n * G + gi]);
+        int k = 0;
+        if (ssup > 0.0 && s > 0.0) {
+          double kr = nearbyint(s / ssup);
+          k = kr < 1.0 ? 1 : (kr > 15.0 ? 15 : (int)kr);
+        }
+        double se = (double)k * ssup; /* the scale the decoder will use */
+        for (int i = 0; i < g; ++i) w[i] = (double)W[(int64_t)n * K + (int64_t)gi * g + i];
+        if (se > 0.0) {
+          if (f->code_cluster) {
+            for (int q = 0; q < 256; ++q) cco_states(cco_cluster_expand((uint32_t)q, alpha[n], beta[n]), f->L, f->N, f->S, reach[q]);
+            for (int j = 0; j < cpg; ++j) {
+              double bestc = INFINITY;
+              int qbest = 0;
+              for (int q = 0; q < 256; ++q) {
+                double cost = sqerr(w[j * f->N], se, f->zp, reach[q][0]);
+                for (int i = 1; i < f->N; ++i) cost = cost + sqerr(w[j * f->N + i], se, f->zp, reach[q][i]);
+                if (cost < bestc) { bestc = cost; qbest = q; }
+              }
+              p[j] = (uint8_t)qbest;
+            }
+          } else {
+            search_group(w, g, f, se, method, gc);
+            for (int j = 0; j < cpg; ++j) store_code(p + (int64_t)j * cb, cb, gc[j]);
+          }
+        }
+        if (cco_spare_bits(f, g) >= 4) {
+          p[gb - 1] = (uint8_t)((p[gb - 1] & 0xF0u) | (uint32_t)k);
+        } else {
+          sq_packed[(int64_t)n * sq_bytes + pidx / 2] |= (uint8_t)(k << (4 * (pidx % 2)));
+          ++pidx;
+        }
+        p += gb;
+      }
+    }
+    free(w); free(gc); free(reach);
   }
   return 0;
 }

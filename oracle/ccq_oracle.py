@@ -105,6 +105,16 @@ def lib():
         L.cco_row_bytes.argtypes = [I, I, cp, u8p]
         L.cco_decode.restype = I
         L.cco_decode.argtypes = [I, I, I, cp, u8p, u8p, u16p, f32p, f32p, f64p]
+        L.cco_decode_f64scales.restype = I
+        L.cco_decode_f64scales.argtypes = [I, I, I, cp, u8p, u8p, f64p, f32p, f32p, f64p]
+        L.cco_spare_bits.restype = I
+        L.cco_spare_bits.argtypes = [cp, I]
+        L.cco_sq_row_bytes.restype = ctypes.c_int64
+        L.cco_sq_row_bytes.argtypes = [I, I, cp, u8p]
+        L.cco_expand_scales.restype = I
+        L.cco_expand_scales.argtypes = [I, I, I, cp, u8p, u8p, u8p, u16p, f64p]
+        L.cco_compress_scales.restype = I
+        L.cco_compress_scales.argtypes = [I, I, I, cp, u8p, f32p, I, u8p, u16p, f32p, f32p, u8p, u16p]
         L.cco_matmul.restype = None
         L.cco_matmul.argtypes = [I, I, I, u16p, ctypes.c_int64, f64p, f64p]
         L.cco_num_threads.restype = I
@@ -203,6 +213,74 @@ def decode(K, N, fmt, codes, scales_fp16, alpha=None, beta=None, group_fmt=None,
     if rc != 0:
         raise ValueError(f"cco_decode failed with {rc}")
     return W
+
+
+def spare_bits(cfg: Code, g: int = 64) -> int:
+    """Unused low bits of a group's last stored code (Sec. 3.4): 4 for (L=4,N=3,S=2) at g=64."""
+    return lib().cco_spare_bits(ctypes.byref(cfg.c()), g)
+
+
+def sq_row_bytes(K: int, fmt, group_fmt=None, g: int = 64) -> int:
+    """Bytes per row of the packed 4-bit scale array s_q (groups without spare bits, two per byte)."""
+    arr, _ = _fmts(fmt)
+    gf = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
+    return lib().cco_sq_row_bytes(K, g, arr, _p(gf, ctypes.c_uint8))
+
+
+def expand_scales(K, N, fmt, codes, sq_packed, s_super_fp16, group_fmt=None, g=64) -> np.ndarray:
+    """Sec. 3.4 / first line of Alg. 2 and Alg. 3: fp64 group scales [N][K/g] = 4-bit field * s_super."""
+    arr, _ = _fmts(fmt)
+    gf = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    nb = sq_row_bytes(K, fmt, gf, g)
+    sq = np.zeros((N, max(nb, 1)), dtype=np.uint8) if sq_packed is None else np.ascontiguousarray(sq_packed, dtype=np.uint8)
+    assert sq_packed is None or sq.size == N * nb
+    ssup = np.ascontiguousarray(s_super_fp16, dtype=np.uint16)
+    assert ssup.size == N and codes.size == N * row_bytes(K, fmt, gf, g)
+    out = np.empty((N, K // g), dtype=np.float64)
+    rc = lib().cco_expand_scales(K, N, g, arr, _p(gf, ctypes.c_uint8), _p(codes, ctypes.c_uint8), _p(sq, ctypes.c_uint8),
+                                 _p(ssup, ctypes.c_uint16), _p(out, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"cco_expand_scales failed with {rc}")
+    return out
+
+
+def decode_cs(K, N, fmt, codes, sq_packed, s_super_fp16, alpha=None, beta=None, group_fmt=None, g=64) -> np.ndarray:
+    """Alg. 2 / Alg. 3 with compressed scales: canonical codes -> W fp64 [N][K] (exact values)."""
+    arr, _ = _fmts(fmt)
+    gf = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    sc = expand_scales(K, N, fmt, codes, sq_packed, s_super_fp16, gf, g)
+    al = None if alpha is None else np.ascontiguousarray(alpha, dtype=np.float32)
+    be = None if beta is None else np.ascontiguousarray(beta, dtype=np.float32)
+    W = np.empty((N, K), dtype=np.float64)
+    rc = lib().cco_decode_f64scales(K, N, g, arr, _p(gf, ctypes.c_uint8), _p(codes, ctypes.c_uint8), _p(sc, ctypes.c_double),
+                                    _p(al, ctypes.c_float), _p(be, ctypes.c_float), _p(W, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"cco_decode_f64scales failed with {rc}")
+    return W
+
+
+def compress_scales(W, fmt, codes, scales_fp16, alpha=None, beta=None, group_fmt=None, method: str = "viterbi", g: int = 64):
+    """Sec. 3.4 Scale Compression on the output of quantize(): returns (codes, sq_packed uint8 [N][sq_row_bytes],
+    s_super fp16 bits [N]).  Codes are searched again with the scales that will be stored."""
+    arr, _ = _fmts(fmt)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    N, K = W.shape
+    gf = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
+    codes = np.array(codes, dtype=np.uint8, copy=True, order="C")
+    scales = np.ascontiguousarray(scales_fp16, dtype=np.uint16)
+    al = np.ones(N, dtype=np.float32) if alpha is None else np.ascontiguousarray(alpha, dtype=np.float32)
+    be = np.zeros(N, dtype=np.float32) if beta is None else np.ascontiguousarray(beta, dtype=np.float32)
+    nb = sq_row_bytes(K, fmt, gf, g)
+    sq = np.zeros((N, max(nb, 1)), dtype=np.uint8)
+    ssup = np.zeros(N, dtype=np.uint16)
+    rc = lib().cco_compress_scales(K, N, g, arr, _p(gf, ctypes.c_uint8), _p(W, ctypes.c_float), 0 if method == "brute" else 1,
+                                   _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint16), _p(al, ctypes.c_float), _p(be, ctypes.c_float),
+                                   _p(sq, ctypes.c_uint8), _p(ssup, ctypes.c_uint16))
+    if rc != 0:
+        raise ValueError(f"cco_compress_scales failed with {rc}")
+    return codes, sq[:, :nb], ssup
 
 
 def matmul(x_bf16: np.ndarray, W: np.ndarray) -> np.ndarray:
