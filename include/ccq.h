@@ -71,19 +71,28 @@ typedef struct {
   ccq_code fmt[2];          /* fmt[0] = narrow (6,4,3)+cluster or wide; with 2 formats fmt[0] narrow, fmt[1] wide */
   const uint8_t *group_fmt; /* HOST, K/group entries in {0,1} selecting fmt[] per group; NULL = all fmt[0] */
   const void *codes;        /* DEVICE, packed codes in device order (ccq_pack_codes)   */
-  const void *scales;       /* DEVICE, fp16 group scales in device order (ccq_pack_scales) */
+  const void *scales;       /* DEVICE.  scale_mode 0: fp16 group scales in device order (ccq_pack_scales).
+                               scale_mode 1: the packed 4-bit scale fields s_q of the narrow-format
+                               groups in device order (ccq_pack_scales4); may be NULL when there are
+                               no narrow-format groups (a wide-format group carries its field in the
+                               spare low nibble of its last code byte, Sec. 3.4)          */
   const float *code_alpha;  /* DEVICE, fp32[N]: Code Cluster scale s_code, >= 0        */
   const float *code_beta;   /* DEVICE, fp32[N]: Code Cluster zero-point zp_code, an
                                integer value with 255*alpha + beta < 2^15 (the
                                kernels rely on it; device data is not checked)         */
   const void *meta;         /* DEVICE, group map in device order (ccq_pack_meta); may be NULL when group_fmt is NULL */
-  int32_t scale_mode;       /* 0 = fp16 group scales (the only mode built)   */
+  int32_t scale_mode;       /* 0 = fp16 group scales; 1 = compressed scales of Sec. 3.4: group scale =
+                               4-bit field * scale_super[n] (first line of Alg. 2 / Alg. 3).  Mode 1 is
+                               built for ccq_gemm with up to 16 rows per launch shape chosen by the
+                               library and for 17 rows and more; explicit launch shapes that hold more
+                               than 16 rows and ccq_grouped_gemm return CCQ_ERR_UNSUPPORTED           */
+  const void *scale_super;  /* DEVICE, fp16[N]: per-output-channel super scale s_super (scale_mode 1) */
 } ccq_weight;
 
 /* Sizes and accounting of the device layout (Eq. 5 for the bpw fields). */
 typedef struct {
   int64_t code_bytes;       /* bytes of the packed code stream (= canonical bytes)      */
-  int64_t scale_bytes;      /* bytes of the fp16 scale array                             */
+  int64_t scale_bytes;      /* bytes of the `scales` array (fp16 scales, or packed 4-bit fields)      */
   int64_t meta_bytes;       /* bytes ccq_pack_meta writes                                */
   int64_t workspace_bytes;  /* workspace ccq_gemm may need for M <= M_max                */
   int64_t row_tile_bytes;   /* code bytes of one tile of 16 output rows (all of K)       */
@@ -91,7 +100,7 @@ typedef struct {
   int32_t groups[2];        /* number of groups along K in each format                   */
   int32_t align;            /* required alignment of DEVICE pointers (16)                */
   double code_bpw;          /* code bits per weight: exactly 2.0 narrow, 2.75 wide       */
-  double total_bpw;         /* + fp16 scales + per-row alpha/beta                        */
+  double total_bpw;         /* + scales (+ super scales) + per-row alpha/beta                        */
 } ccq_info;
 
 /* Validate a descriptor (DEVICE pointers may be NULL here) and report the
@@ -101,12 +110,15 @@ int ccq_pack_info(const ccq_weight *w, int32_t M_max, ccq_info *out);
 
 /* Host-side permutations from canonical order to device order.
  *   ccq_pack_codes : canonical_codes HOST uint8 [N][row bytes]  -> out HOST [code_bytes]
- *   ccq_pack_scales: canonical fp16 bits HOST [N][K/64]         -> out HOST [scale_bytes/2]
+ *   ccq_pack_scales: canonical fp16 bits HOST [N][K/64]         -> out HOST [scale_bytes/2]  (scale_mode 0)
  *   ccq_pack_meta  : group_fmt                                  -> out HOST [meta_bytes]
  * Byte values are copied, never altered.  The caller uploads the results. */
 int ccq_pack_codes(const ccq_weight *w, const uint8_t *canonical_codes, void *out);
 int ccq_pack_scales(const ccq_weight *w, const uint16_t *canonical_scales, void *out);
 int ccq_pack_meta(const ccq_weight *w, void *out);
+/* scale_mode 1: canonical s_q HOST uint8 [N][ceil(narrow groups / 2)] (the p-th narrow-format group of a row,
+ * in k order, in byte p/2 at s_shift = 4*(p%2), Alg. 3) -> out HOST [scale_bytes]. */
+int ccq_pack_scales4(const ccq_weight *w, const uint8_t *canonical_sq, void *out);
 
 /* y[m][n] = sum_k x[m][k] * W_dq[n][k]   (the W2A16 GEMV / GEMM of the
  * "Inference Performance" section; Alg. 2/3 fused into the contraction).

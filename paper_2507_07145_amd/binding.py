@@ -37,7 +37,7 @@ class ccq_weight(ctypes.Structure):
     _fields_ = [("K", ctypes.c_int32), ("N", ctypes.c_int32), ("group", ctypes.c_int32), ("n_formats", ctypes.c_int32),
                 ("fmt", ccq_code * 2), ("group_fmt", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
                 ("code_alpha", ctypes.c_void_p), ("code_beta", ctypes.c_void_p), ("meta", ctypes.c_void_p),
-                ("scale_mode", ctypes.c_int32)]
+                ("scale_mode", ctypes.c_int32), ("scale_super", ctypes.c_void_p)]
 
 
 class ccq_info(ctypes.Structure):
@@ -55,7 +55,7 @@ class ccq_launch(ctypes.Structure):
 NARROW = ccq_code(6, 4, 3, 1, 32.0)   # (L=6,N=4,S=3) + Code Cluster, 2.0 bpw
 WIDE = ccq_code(4, 3, 2, 0, 8.0)      # (L=4,N=3,S=2), 2.75 bpw
 
-EXPORTS = ["ccq_pack_info", "ccq_pack_codes", "ccq_pack_scales", "ccq_pack_meta", "ccq_gemm", "ccq_gemm_ex",
+EXPORTS = ["ccq_pack_info", "ccq_pack_codes", "ccq_pack_scales", "ccq_pack_scales4", "ccq_pack_meta", "ccq_gemm", "ccq_gemm_ex",
            "ccq_grouped_gemm", "ccq_grouped_workspace_bytes", "ccq_status_string"]
 
 _lib = None
@@ -74,7 +74,7 @@ def load() -> ctypes.CDLL:
     wp = ctypes.POINTER(ccq_weight)
     L.ccq_pack_info.restype = ctypes.c_int
     L.ccq_pack_info.argtypes = [wp, i32, ctypes.POINTER(ccq_info)]
-    for name in ("ccq_pack_codes", "ccq_pack_scales"):
+    for name in ("ccq_pack_codes", "ccq_pack_scales", "ccq_pack_scales4"):
         f = getattr(L, name)
         f.restype = ctypes.c_int
         f.argtypes = [wp, vp, vp]
@@ -112,10 +112,10 @@ def _stream_ptr(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def descriptor(K: int, N: int, fmts, group_fmt: np.ndarray | None = None) -> ccq_weight:
+def descriptor(K: int, N: int, fmts, group_fmt: np.ndarray | None = None, scale_mode: int = 0) -> ccq_weight:
     """A ccq_weight with shape/format fields set and all DEVICE pointers NULL."""
     w = ccq_weight()
-    w.K, w.N, w.group, w.n_formats, w.scale_mode = K, N, 64, len(fmts), 0
+    w.K, w.N, w.group, w.n_formats, w.scale_mode = K, N, 64, len(fmts), scale_mode
     for i, f in enumerate(fmts):
         w.fmt[i] = f
     w.group_fmt = group_fmt.ctypes.data if group_fmt is not None else None
@@ -148,6 +148,15 @@ def pack_scales(w: ccq_weight, canonical_fp16_bits: np.ndarray) -> np.ndarray:
     return out
 
 
+def pack_scales4(w: ccq_weight, canonical_sq: np.ndarray) -> np.ndarray:
+    """scale_mode 1: canonical packed 4-bit scale fields of the narrow-format groups -> device order (uint16 words)."""
+    info = pack_info(w, 0)
+    src = np.ascontiguousarray(canonical_sq, dtype=np.uint8)
+    out = np.zeros(max(info.scale_bytes // 2, 1), dtype=np.uint16)
+    _check(load().ccq_pack_scales4(ctypes.byref(w), _np_ptr(src), _np_ptr(out)), "ccq_pack_scales4")
+    return out[:info.scale_bytes // 2]
+
+
 def pack_meta(w: ccq_weight) -> np.ndarray:
     info = pack_info(w, 0)
     out = np.empty(info.meta_bytes // 4, dtype=np.int32)
@@ -172,7 +181,7 @@ class Weight:
         self.desc = None
         self.info = None
         self.E = 1
-        self.codes = self.scales = self.alpha = self.beta = self.meta = None
+        self.codes = self.scales = self.alpha = self.beta = self.meta = self.ssup = None
         self._group_fmt = None
 
     @classmethod
@@ -201,6 +210,34 @@ class Weight:
         w.code_beta = self.beta.data_ptr() if needs_ab else None
         w.meta = self.meta.data_ptr() if self.meta is not None else None
         self.desc, self.info, self.E = w, info, E
+        return self
+
+    @classmethod
+    def from_canonical_compressed(cls, K, N, fmts, codes, sq_packed, s_super_fp16, alpha=None, beta=None, group_fmt=None, device="cuda:0"):
+        """The same for compressed scales (scale_mode 1): `sq_packed` holds the 4-bit fields of the narrow-format
+        groups (uint8 [N][ceil(narrow groups / 2)], may be empty), `s_super_fp16` the fp16 bits of the per-row super
+        scale; wide-format groups carry their field inside `codes`."""
+        self = cls()
+        self._group_fmt = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
+        w = descriptor(K, N, fmts, self._group_fmt, scale_mode=1)
+        info = pack_info(w, 64)
+        self.codes = torch.from_numpy(pack_codes(w, np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1))).to(device)
+        if info.scale_bytes > 0:
+            self.scales = torch.from_numpy(pack_scales4(w, sq_packed).view(np.int16)).to(device)
+        self.ssup = torch.from_numpy(np.ascontiguousarray(s_super_fp16, dtype=np.uint16).reshape(N).view(np.int16)).to(device)
+        needs_ab = any(f.code_cluster for f in fmts)
+        if needs_ab:
+            self.alpha = torch.from_numpy(np.ascontiguousarray(alpha, dtype=np.float32).reshape(N)).to(device)
+            self.beta = torch.from_numpy(np.ascontiguousarray(beta, dtype=np.float32).reshape(N)).to(device)
+        if group_fmt is not None:
+            self.meta = torch.from_numpy(pack_meta(w)).to(device)
+        w.codes = self.codes.data_ptr()
+        w.scales = self.scales.data_ptr() if self.scales is not None else None
+        w.scale_super = self.ssup.data_ptr()
+        w.code_alpha = self.alpha.data_ptr() if needs_ab else None
+        w.code_beta = self.beta.data_ptr() if needs_ab else None
+        w.meta = self.meta.data_ptr() if self.meta is not None else None
+        self.desc, self.info, self.E = w, info, 1
         return self
 
     @property

@@ -18,9 +18,10 @@ int make_layout(const ccq_weight* w, Layout* out) {
   if (w->K <= 0 || w->N <= 0 || w->n_formats < 1 || w->n_formats > 2) return CCQ_ERR_BAD_PARAM;
   if (w->group != kGroup) return w->group > 0 ? CCQ_ERR_UNSUPPORTED : CCQ_ERR_BAD_PARAM;
   if (w->K % kGroup != 0) return CCQ_ERR_BAD_PARAM;
-  if (w->scale_mode != 0) return CCQ_ERR_UNSUPPORTED;
+  if (w->scale_mode != 0 && w->scale_mode != 1) return CCQ_ERR_UNSUPPORTED;
   if (w->n_formats == 1 && w->group_fmt) return CCQ_ERR_BAD_PARAM;
   Layout L;
+  L.scale_mode = w->scale_mode;
   L.K = w->K;
   L.N = w->N;
   L.G = w->K / kGroup;
@@ -48,7 +49,9 @@ int make_layout(const ccq_weight* w, Layout* out) {
   L.tiles[kNarrow] = L.groups[kNarrow] / kNarrowGroupsPerTile;
   L.tiles[kWide] = L.groups[kWide] / kWideGroupsPerTile;
   L.row_tile_bytes = (int64_t)L.tiles[kNarrow] * kNarrowTileBytes + (int64_t)L.tiles[kWide] * kWideTileBytes;
-  L.row_tile_scale_halfs = (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs + (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;
+  L.row_tile_scale_halfs = L.scale_mode == 1
+                               ? (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs4
+                               : (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs + (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;
   L.row_tiles = w->N / kRowsPerTile;
   if (L.row_tile_bytes * (int64_t)L.row_tiles >= (int64_t)1 << 40) return CCQ_ERR_BAD_PARAM;
   *out = L;
@@ -147,7 +150,7 @@ extern "C" int ccq_pack_info(const ccq_weight* w, int32_t M_max, ccq_info* out) 
   // codes (g = 1 mod N: the spare bits of the last code are part of the count).
   const double weights = (double)L.N * (double)L.K;
   info.code_bpw = 8.0 * (double)info.code_bytes / weights;
-  const double ab_bytes = L.groups[kNarrow] > 0 ? 8.0 * (double)L.N : 0.0;
+  const double ab_bytes = (L.groups[kNarrow] > 0 ? 8.0 * (double)L.N : 0.0) + (L.scale_mode == 1 ? 2.0 * (double)L.N : 0.0);
   info.total_bpw = 8.0 * ((double)info.code_bytes + (double)info.scale_bytes + ab_bytes) / weights;
   *out = info;
   return CCQ_OK;
@@ -205,11 +208,32 @@ extern "C" int ccq_pack_codes(const ccq_weight* w, const uint8_t* src, void* out
   return CCQ_OK;
 }
 
+extern "C" int ccq_pack_scales4(const ccq_weight* w, const uint8_t* src, void* out_v) {
+  if (!w || !src || !out_v) return CCQ_ERR_NULL;
+  Layout L;
+  int rc = make_layout(w, &L);
+  if (rc != CCQ_OK) return rc;
+  if (L.scale_mode != 1) return CCQ_ERR_BAD_PARAM;
+  uint16_t* out = static_cast<uint16_t*>(out_v);
+  const int64_t src_row_bytes = (L.groups[kNarrow] + 1) / 2;
+  std::memset(out, 0, (size_t)(L.row_tile_scale_halfs * L.row_tiles * 2));
+  for (int n = 0; n < L.N; ++n) {
+    uint16_t* tile_row = out + (int64_t)(n / kRowsPerTile) * L.row_tile_scale_halfs;
+    const int r = n % kRowsPerTile;
+    for (int p = 0; p < L.groups[kNarrow]; ++p) {  // p-th narrow-format group of the row, k order
+      const uint32_t field = (src[(int64_t)n * src_row_bytes + p / 2] >> (4 * (p % 2))) & 0xFu;  // (s_q >> s_shift) & s_mask, Alg. 3
+      tile_row[(int64_t)(p / 4) * kNarrowTileScaleHalfs4 + r] |= (uint16_t)(field << (4 * (p % 4)));
+    }
+  }
+  return CCQ_OK;
+}
+
 extern "C" int ccq_pack_scales(const ccq_weight* w, const uint16_t* src, void* out_v) {
   if (!w || !src || !out_v) return CCQ_ERR_NULL;
   Layout L;
   int rc = make_layout(w, &L);
   if (rc != CCQ_OK) return rc;
+  if (L.scale_mode != 0) return CCQ_ERR_BAD_PARAM;
   uint16_t* out = static_cast<uint16_t*>(out_v);
   std::vector<int> pos, kind;
   packed_order(w, L, pos, kind);
@@ -243,10 +267,13 @@ extern "C" int ccq_pack_meta(const ccq_weight* w, void* out_v) {
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static int check_weight_ptrs(const ccq_weight* w, const Layout& L) {
-  if (!w->codes || !w->scales) return CCQ_ERR_NULL;
+  if (!w->codes) return CCQ_ERR_NULL;
+  if (!w->scales && (L.scale_mode == 0 || L.groups[kNarrow] > 0)) return CCQ_ERR_NULL;
+  if (L.scale_mode == 1 && !w->scale_super) return CCQ_ERR_NULL;
   if (L.groups[kNarrow] > 0 && (!w->code_alpha || !w->code_beta)) return CCQ_ERR_NULL;
   if (L.has_map && !w->meta) return CCQ_ERR_NULL;
-  if (!aligned16(w->codes) || !aligned16(w->scales) || !aligned16(w->code_alpha) || !aligned16(w->code_beta) || !aligned16(w->meta))
+  if (!aligned16(w->codes) || !aligned16(w->scales) || !aligned16(w->code_alpha) || !aligned16(w->code_beta) || !aligned16(w->meta) ||
+      (L.scale_mode == 1 && !aligned16(w->scale_super)))
     return CCQ_ERR_ALIGN;
   return CCQ_OK;
 }
@@ -361,6 +388,7 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
   int rc = make_layout(w0, &L);
   if (rc != CCQ_OK) return rc;
   if (E <= 0 || P < 0 || T < 0 || workspace_bytes < 0) return CCQ_ERR_BAD_PARAM;
+  if (L.scale_mode != 0) return CCQ_ERR_UNSUPPORTED;  // compressed scales: dense entry point only
   if (expert_offsets_host) {
     if (expert_offsets_host[0] != 0 || expert_offsets_host[E] != P) return CCQ_ERR_ROUTING;
     for (int e = 0; e < E; ++e)

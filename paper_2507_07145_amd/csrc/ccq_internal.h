@@ -32,6 +32,9 @@ constexpr int kWideGroupBytes = 22;
 // fp16 scales: per row tile, per k-tile, [row 0..15][group of the tile]
 constexpr int kNarrowTileScaleHalfs = 16 * 4;
 constexpr int kWideTileScaleHalfs = 16 * 8;
+// compressed scales (Sec. 3.4): per narrow k-tile one 16-bit word per row, holding the four 4-bit
+// fields of the tile's groups (group j in bits 4j..4j+3); wide groups keep theirs in the code stream
+constexpr int kNarrowTileScaleHalfs4 = 16;
 
 constexpr int kMaxSkinnyM = 64;   // rows one pass of the skinny kernel holds
 constexpr int kMaxSplitsK = 32;
@@ -46,6 +49,7 @@ struct Layout {
   int kind_of_fmt[2] = {0, 0};  // descriptor format index -> Kind
   float zp[2] = {0.f, 0.f};     // zero-point per kind
   bool has_map = false;         // group_fmt given
+  int scale_mode = 0;           // 0 fp16 group scales, 1 4-bit fields times a per-row super scale
   int64_t row_tile_bytes = 0;
   int64_t row_tile_scale_halfs = 0;
   int row_tiles = 0;

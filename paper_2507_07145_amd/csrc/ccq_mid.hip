@@ -36,6 +36,7 @@ struct MidArgs {
   const float* alpha;
   const float* beta;
   const int32_t* meta;
+  const uint16_t* scale_super;  // fp16 [N], compressed scales only
   const uint16_t* x;
   uint16_t* y;
   float* partial;
@@ -63,8 +64,11 @@ __device__ __forceinline__ uint32_t pack_bf16_m(float lo, float hi) {
 
 __device__ __forceinline__ uint32_t dword_sel(const u32x4& v, int j) { return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w)); }
 
-// FM: formats present (1 narrow, 2 wide, 3 both; a group map exists only for 3)
-template <int FM>
+// FM: formats present (1 narrow, 2 wide, 3 both; a group map exists only for 3).  SM: scale mode (0 fp16 group
+// scales; 1 the compressed scales of Sec. 3.4: group scale = 4-bit field * per-row super scale, first line of
+// Alg. 2 / Alg. 3; the field of a narrow group comes from the packed scale array, that of a wide group from the
+// spare low nibble of the group's last code byte).
+template <int FM, int SM>
 __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   constexpr bool HAS_N = (FM & 1) != 0, HAS_W = (FM & 2) != 0, META = FM == 3;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -107,7 +111,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   // per-wavefront weight rows: row tiles n0/16 + wave*RTW + i, lane (nl, kq)
   const uint8_t* code_base[kMidRTW];
   const uint16_t* scale_base[kMidRTW];
-  float al[kMidRTW], be[kMidRTW];
+  float al[kMidRTW], be[kMidRTW], ssup[kMidRTW];
 #pragma unroll
   for (int i = 0; i < kMidRTW; ++i) {
     const int rtile = min(n0 / 16 + wave * kMidRTW + i, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
@@ -115,6 +119,8 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
     scale_base[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
     al[i] = 0.f;
     be[i] = 0.f;
+    ssup[i] = 0.f;
+    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
     if constexpr (HAS_N) {
       al[i] = a.alpha[rtile * 16 + nl];
       be[i] = a.beta[rtile * 16 + nl];
@@ -136,7 +142,8 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
 #pragma unroll
     for (int i = 0; i < kMidRTW; ++i) {
       c[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_base[i] + (int64_t)kt * kNarrowTileBytes + lane * 16));
-      sc[i] = *reinterpret_cast<const uint2*>(scale_base[i] + (int64_t)kt * kNarrowTileScaleHalfs + nl * 4);
+      if constexpr (SM == 0) sc[i] = *reinterpret_cast<const uint2*>(scale_base[i] + (int64_t)kt * kNarrowTileScaleHalfs + nl * 4);
+      else sc[i] = uint2{(uint32_t)scale_base[i][(int64_t)kt * kNarrowTileScaleHalfs4 + nl], 0u};  // the tile's four 4-bit fields
     }
   };
   auto load_wide = [&](u32x4 (&c)[kMidRTW][3], uint4 (&sc)[kMidRTW], int kt) {
@@ -149,7 +156,8 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
       // the third segment has entries for 48 lanes only; lanes 48..63 re-read lane 47's entry (what they
       // decode from it lands in the padding columns of the LDS row)
       c[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47 ? (lane - 47) * 16 : 0)));
-      sc[i] = *reinterpret_cast<const uint4*>(scale_base[i] + wide_scale_off + (int64_t)kt * kWideTileScaleHalfs + nl * 8);
+      if constexpr (SM == 0) sc[i] = *reinterpret_cast<const uint4*>(scale_base[i] + wide_scale_off + (int64_t)kt * kWideTileScaleHalfs + nl * 8);
+      else sc[i] = uint4{0u, 0u, 0u, 0u};  // the fields sit in the code stream
     }
   };
 
@@ -180,9 +188,14 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
 #pragma unroll
     for (int i = 0; i < kMidRTW; ++i) {
       const uint32_t d = dword_sel(cn[i], j);
-      const uint32_t sd = (j >> 1) ? sn[i].y : sn[i].x;
-      const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
-      const float c0 = -(128.f + a.zp[kNarrow]) * s;  // exact: 8-bit times 11-bit significand
+      float s;
+      if constexpr (SM == 0) {
+        const uint32_t sd = (j >> 1) ? sn[i].y : sn[i].x;
+        s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+      } else {
+        s = (float)((sn[i].x >> (4 * j)) & 0xFu) * ssup[i];  // (s_q >> s_shift) & s_mask times s_super: exact
+      }
+      const float c0 = -(128.f + a.zp[kNarrow]) * s;  // exact: 8-bit times at most 15-bit significand
       const float bem = be[i] + magic;                 // + 2^23: exact, beta is an integer below 2^15
       uint32_t o[8];
 #pragma unroll
@@ -208,8 +221,17 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
     uint16_t* dst = Bs + buf * kMidBN * kMidRow;
 #pragma unroll
     for (int i = 0; i < kMidRTW; ++i) {
-      const uint32_t sd = dword_sel(u32x4{sw[i].x, sw[i].y, sw[i].z, sw[i].w}, j >> 1);
-      const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+      float s;
+      if constexpr (SM == 0) {
+        const uint32_t sd = dword_sel(u32x4{sw[i].x, sw[i].y, sw[i].z, sw[i].w}, j >> 1);
+        s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+      } else {
+        // Alg. 2: the low nibble of the group's last code byte (byte 21), which quarter 3 of the row holds in
+        // segment 1, halfword j, high byte
+        const uint32_t own = dword_sel(cw[i][1], j >> 1);
+        const uint32_t q3 = (uint32_t)__builtin_amdgcn_ds_bpermute((48 + nl) * 4, (int)own);
+        s = (float)((q3 >> (16 * (j & 1) + 8)) & 0xFu) * ssup[i];
+      }
       const float c0 = -(128.f + a.zp[kWide]) * s;
       float w[18];
 #pragma unroll
@@ -365,6 +387,7 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   a.alpha = w->code_alpha;
   a.beta = w->code_beta;
   a.meta = static_cast<const int32_t*>(w->meta);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
   a.x = static_cast<const uint16_t*>(x);
   a.y = static_cast<uint16_t*>(y);
   a.partial = partial;
@@ -389,17 +412,16 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   const int max_steps = ((L.tiles[kNarrow] + S - 1) / S) * kNarrowGroupsPerTile + ((L.tiles[kWide] + S - 1) / S) * kWideGroupsPerTile;
   const size_t lds = (size_t)2 * (kMidBM + kMidBN) * kMidRow * 2 + (fm == 3 ? (size_t)max_steps * 4 : 0);
   if (lds > 64 * 1024) return CCQ_ERR_UNSUPPORTED;
-  const void* kern = fm == 1 ? reinterpret_cast<const void*>(ccq_mid_kernel<1>)
-                             : (fm == 2 ? reinterpret_cast<const void*>(ccq_mid_kernel<2>) : reinterpret_cast<const void*>(ccq_mid_kernel<3>));
-  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+  typedef void (*MidKernel)(const MidArgs);
+  const MidKernel table[2][3] = {{ccq_mid_kernel<1, 0>, ccq_mid_kernel<2, 0>, ccq_mid_kernel<3, 0>},
+                                 {ccq_mid_kernel<1, 1>, ccq_mid_kernel<2, 1>, ccq_mid_kernel<3, 1>}};
+  const MidKernel kern = table[L.scale_mode][fm - 1];
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return CCQ_ERR_HIP;
   }
   dim3 grid((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block(256);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (fm == 1) hipLaunchKernelGGL(ccq_mid_kernel<1>, grid, block, lds, st, a);
-  else if (fm == 2) hipLaunchKernelGGL(ccq_mid_kernel<2>, grid, block, lds, st, a);
-  else hipLaunchKernelGGL(ccq_mid_kernel<3>, grid, block, lds, st, a);
+  hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }

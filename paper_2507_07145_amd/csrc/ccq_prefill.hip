@@ -38,6 +38,7 @@ struct PrefillArgs {
   const uint16_t* scales;
   const float* alpha;
   const float* beta;
+  const uint16_t* scale_super;  // fp16 [N], compressed scales only
   const uint16_t* x;
   uint16_t* y;
   int64_t ldx, ldy;
@@ -63,7 +64,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 
 // RTW = 16-row weight tiles decoded per wavefront per step; BN = 64 * RTW.
-template <int RTW>
+// SM: scale mode (0 fp16 group scales; 1 the compressed scales of Sec. 3.4: 4-bit field * per-row super scale).
+template <int RTW, int SM>
 __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   constexpr int BN = 64 * RTW;
   constexpr int NT = BN / 64;  // 32-wide MFMA column tiles per wavefront (wave tile is 128 x BN/2)
@@ -81,15 +83,17 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   // per-thread weight rows: tiles rt = wave*RTW + i of this block, row nl, quarter kq
   const uint8_t* code_ptr[RTW];
   const uint16_t* scale_ptr[RTW];
-  float al[RTW], be[RTW];
+  float al[RTW], be[RTW], ssup[RTW];
 #pragma unroll
   for (int i = 0; i < RTW; ++i) {
     int rtile = n0 / 16 + wave * RTW + i;
     rtile = min(rtile, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
     code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;                 // + lane * 16 at the load
-    scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;         // + nl * 4 at the load
+    scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;         // + nl * 4 (or + nl) at the load
     al[i] = a.alpha[rtile * 16 + nl];
     be[i] = a.beta[rtile * 16 + nl] + 8388608.f;
+    ssup[i] = 0.f;
+    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
   }
   uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
   asm volatile("" : "+v"(c43), "+s"(smask));
@@ -136,7 +140,8 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
 #pragma unroll
     for (int i = 0; i < RTW; ++i) {
       c[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_ptr[i] + (int64_t)kt * kNarrowTileBytes + lane_code_off));
-      sc[i] = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs + lane_scale_off);
+      if constexpr (SM == 0) sc[i] = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs + lane_scale_off);
+      else sc[i] = uint2{(uint32_t)scale_ptr[i][(int64_t)kt * kNarrowTileScaleHalfs4 + nl], 0u};  // the tile's four 4-bit fields
     }
   };
   auto store_a = [&](int buf, const u32x4 (&src)[8], int i0, int i1) {
@@ -148,8 +153,13 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   auto decode_b = [&](int buf, int j, int i) {
     uint16_t* dst = Bs + buf * BN * kLdsRow;
     const uint32_t d = j == 0 ? creg[i].x : (j == 1 ? creg[i].y : (j == 2 ? creg[i].z : creg[i].w));
-    const uint32_t sw = (j >> 1) ? sreg[i].y : sreg[i].x;
-    const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+    float s;
+    if constexpr (SM == 0) {
+      const uint32_t sw = (j >> 1) ? sreg[i].y : sreg[i].x;
+      s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+    } else {
+      s = (float)((sreg[i].x >> (4 * j)) & 0xFu) * ssup[i];  // (s_q >> s_shift) & s_mask times s_super (Alg. 3): exact
+    }
     const float c0 = neg_off * s;  // exact: 8-bit times 11-bit significand
     uint32_t o[8];
 #pragma unroll
@@ -298,6 +308,7 @@ int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, i
   a.scales = static_cast<const uint16_t*>(w->scales);
   a.alpha = w->code_alpha;
   a.beta = w->code_beta;
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
   a.x = static_cast<const uint16_t*>(x);
   a.y = static_cast<uint16_t*>(y);
   a.ldx = ldx;
@@ -316,15 +327,15 @@ int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, i
   const int BN = use192 ? 192 : 256;
   const int n_blocks = (L.N + BN - 1) / BN;
   const size_t lds = (size_t)2 * (kBM + BN) * kLdsRow * 2;
-  const void* kern = use192 ? reinterpret_cast<const void*>(ccq_prefill_kernel<3>) : reinterpret_cast<const void*>(ccq_prefill_kernel<4>);
-  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+  typedef void (*PrefillKernel)(const PrefillArgs);
+  const PrefillKernel table[2][2] = {{ccq_prefill_kernel<3, 0>, ccq_prefill_kernel<4, 0>}, {ccq_prefill_kernel<3, 1>, ccq_prefill_kernel<4, 1>}};
+  const PrefillKernel kern = table[L.scale_mode][use192 ? 0 : 1];
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return CCQ_ERR_HIP;
   }
   dim3 grid((unsigned)(a.m_blocks * n_blocks)), block(256);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (use192) hipLaunchKernelGGL(ccq_prefill_kernel<3>, grid, block, lds, s, a);
-  else hipLaunchKernelGGL(ccq_prefill_kernel<4>, grid, block, lds, s, a);
+  hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }

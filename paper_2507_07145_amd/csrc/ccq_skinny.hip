@@ -51,6 +51,7 @@ struct SkinnyArgs {
   const float* alpha;
   const float* beta;
   const int32_t* meta;
+  const uint16_t* scale_super;  // fp16 [N] per expert, compressed scales only
   const uint16_t* x;
   uint16_t* y;
   float* partial;
@@ -76,12 +77,21 @@ struct SkinnyArgs {
   float cneg[2];      // -(128 + zp) per kind
 };
 
+// KIND = format (bit 0: kNarrow / kWide) | scale mode << 1 (bit 1: 0 fp16 group scales, 1 the compressed
+// scales of Sec. 3.4: a 4-bit field per group times a per-row super scale).
+constexpr int kScale4 = 2;
 template <int KIND> struct Traits;
 template <> struct Traits<kNarrow> {
   static constexpr int GPT = kNarrowGroupsPerTile, T = 2, SEGS = 1, TILE_BYTES = kNarrowTileBytes, SCALE_HALFS = kNarrowTileScaleHalfs;
 };
 template <> struct Traits<kWide> {
   static constexpr int GPT = kWideGroupsPerTile, T = 3, SEGS = 3, TILE_BYTES = kWideTileBytes, SCALE_HALFS = kWideTileScaleHalfs;
+};
+template <> struct Traits<kNarrow | kScale4> : Traits<kNarrow> {
+  static constexpr int SCALE_HALFS = kNarrowTileScaleHalfs4;
+};
+template <> struct Traits<kWide | kScale4> : Traits<kWide> {
+  static constexpr int SCALE_HALFS = 0;
 };
 
 // k-tiles [A, B) of kind `kind` that workgroup `split` owns.
@@ -118,19 +128,35 @@ __device__ __forceinline__ void load_tile(TileRegs<KIND>& r, const uint8_t* code
   using TR = Traits<KIND>;
   const uint8_t* t = codes_kind + (int64_t)kt * TR::TILE_BYTES + lane * 16;
   r.c[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
-  if constexpr (KIND == kWide) {
+  if constexpr ((KIND & 1) == kWide) {
     r.c[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
     // the third segment has entries for 48 lanes only; lanes 48..63 re-read lane 47's entry (their k-slots
     // are staged as zero activations, and every bit pattern decodes to a finite value)
     r.c[2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47 ? (lane - 47) * 16 : 0)));
   }
-  const uint16_t* sp = scales_kind + (int64_t)kt * TR::SCALE_HALFS + (lane & 15) * TR::GPT;
   if constexpr (KIND == kNarrow) {
-    uint2 v = *reinterpret_cast<const uint2*>(sp);
+    const uint2 v = *reinterpret_cast<const uint2*>(scales_kind + (int64_t)kt * TR::SCALE_HALFS + (lane & 15) * TR::GPT);
     r.s[0] = v.x; r.s[1] = v.y;
-  } else {
-    uint4 v = *reinterpret_cast<const uint4*>(sp);
+  } else if constexpr (KIND == kWide) {
+    const uint4 v = *reinterpret_cast<const uint4*>(scales_kind + (int64_t)kt * TR::SCALE_HALFS + (lane & 15) * TR::GPT);
     r.s[0] = v.x; r.s[1] = v.y; r.s[2] = v.z; r.s[3] = v.w;
+  } else if constexpr (KIND == (kNarrow | kScale4)) {
+    r.s[0] = scales_kind[(int64_t)kt * TR::SCALE_HALFS + (lane & 15)];  // the tile's four 4-bit fields of this row
+  }
+  // wide format with compressed scales: the fields sit in the code stream (see tile_scale_fields)
+}
+
+// Compressed scales of a wide k-tile: the field of group j is the low nibble of the group's last code byte
+// (byte 21), which quarter 3 of the row holds in segment 1, halfword j, high byte.  Every lane fetches
+// the four dwords of its row's quarter-3 lane.
+template <int KIND>
+__device__ __forceinline__ void tile_scale_fields(uint32_t (&f)[4], const TileRegs<KIND>& r, int lane) {
+  if constexpr (KIND == (kWide | kScale4)) {
+    const int src = (48 + (lane & 15)) * 4;
+    f[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[1].x);
+    f[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[1].y);
+    f[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[1].z);
+    f[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[1].w);
   }
 }
 
@@ -139,13 +165,14 @@ __device__ __forceinline__ void load_tile(TileRegs<KIND>& r, const uint8_t* code
 struct DecodeConsts {
   uint32_t c4300;
   uint32_t mask[2];
+  float ssup[2];  // per-row super scale of each row tile the wavefront owns (compressed scales only)
 };
 
 // Weight fragment (8 bf16 integers 128 + state) of group j, k-step t.
 template <int KIND>
 __device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, int t, float al, float be_magic, uint32_t c4300, uint32_t mask) {
   uint4 o;
-  if constexpr (KIND == kNarrow) {
+  if constexpr ((KIND & 1) == kNarrow) {
     // two clustered bytes -> two 15-bit codes (Alg. 3), side by side in one register
     const uint32_t d = dword_of(r.c[0], j);
     const float fa = __builtin_fmaf((float)((d >> (16 * t)) & 0xFFu), al, be_magic);
@@ -168,11 +195,19 @@ __device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, in
   return __builtin_bit_cast(bf16x8, o);
 }
 
+// Scale of group j of the tile.  fp16 group scales, or (Alg. 2 / Alg. 3, first line) the 4-bit field times the
+// row's super scale: exact in fp32 (4-bit integer times 11-bit significand).
 template <int KIND>
-__device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, int j) {
-  const uint32_t d = r.s[j >> 1];
-  const uint16_t h = (uint16_t)((j & 1) ? (d >> 16) : (d & 0xFFFFu));
-  return (float)__builtin_bit_cast(_Float16, h);
+__device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, const uint32_t (&fields)[4], float ssup, int j) {
+  if constexpr ((KIND & kScale4) == 0) {
+    const uint32_t d = r.s[j >> 1];
+    const uint16_t h = (uint16_t)((j & 1) ? (d >> 16) : (d & 0xFFFFu));
+    return (float)__builtin_bit_cast(_Float16, h);
+  } else if constexpr ((KIND & 1) == kNarrow) {
+    return (float)((r.s[0] >> (4 * j)) & 0xFu) * ssup;
+  } else {
+    return (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu) * ssup;
+  }
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __builtin_bit_cast(float, bits16 << 16); }
@@ -196,9 +231,9 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
                             int ng, int sg, int j0, int tid, int nthreads) {
   using TR = Traits<KIND>;
   constexpr int MRT = (MT == 1) ? MR : MT * 16;
-  constexpr int U = (KIND == kNarrow) ? 4 : 2;  // fragments requested per thread before the first is used
+  constexpr int U = ((KIND & 1) == kNarrow) ? 4 : 2;  // fragments requested per thread before the first is used
   const int nfrag = ng * TR::T * 4 * MRT;
-  const int meta_base = (KIND == kWide) ? a.groups_narrow : 0;
+  const int meta_base = ((KIND & 1) == kWide) ? a.groups_narrow : 0;
   // the workgroup size is a multiple of MRT, so a thread stages the same activation row every time
   const int m = tid % MRT;
   const bool row_ok = m < rows_valid;
@@ -216,7 +251,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
       const int pg = pg0 + (lg / sg) * TR::GPT + j0 + lg % sg;
       const int g = META ? a.meta[meta_base + pg] : pg;  // a group map exists only for mixed formats
       const uint16_t* xr = xrow + (int64_t)g * kGroup;
-      if constexpr (KIND == kNarrow) {
+      if constexpr ((KIND & 1) == kNarrow) {
         v[u] = *reinterpret_cast<const uint4*>(xr + 16 * kq + 8 * t);
       } else {
         // codes ja = 6kq+2t and ja+1 cover weights 3ja+{0,1,2} and 3ja+3+{0,1,2};
@@ -238,7 +273,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
       if (f < nfrag) {
         uint4 o = {0u, 0u, 0u, 0u};
         if (row_ok) {
-          if constexpr (KIND == kNarrow) {
+          if constexpr ((KIND & 1) == kNarrow) {
             // the two codes of a k-step cover weights 16kq+8t+{0..3} and +{4..7}; slots
             // interleave them: {0,4,1,5,2,6,3,7}
             o.x = __builtin_amdgcn_perm(v[u].z, v[u].x, 0x05040100u);
@@ -258,7 +293,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
   __syncthreads();
   // start values for the rows that are really held; rows beyond them are never stored
   const int ncneg = ng * MRT;
-  const float factor = a.cneg[KIND];
+  const float factor = a.cneg[KIND & 1];
   for (int i = tid; i < ncneg; i += nthreads) {
     const int m = i % MRT;
     const int lg = i / MRT;
@@ -311,6 +346,9 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
   using TR = Traits<KIND>;
   GroupOperands<KIND, MT, MR> cur;
   if constexpr (MR == 1) cur.cin[0] = f32x4{0.f, 0.f, 0.f, 0.f};  // elements 1..3 only need a defined value
+  uint32_t fields[RT][4];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) tile_scale_fields<KIND>(fields[rt], r[rt], lane);
 #pragma unroll
   for (int j = J0; j < J0 + NJ; ++j) {
     const int lg = lg0 + (j - J0);
@@ -320,7 +358,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
     for (int t = 0; t < TR::T; ++t) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], dc.c4300, dc.mask[KIND]);
+        const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], dc.c4300, dc.mask[KIND & 1]);
         if constexpr (MR == 1) {
           // two 4x4x4 steps: k-slots 0..3 and 4..7 of the fragment
           const u32x4 wv = __builtin_bit_cast(u32x4, wf);
@@ -338,7 +376,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
     }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const float s = group_scale<KIND>(r[rt], j);
+      const float s = group_scale<KIND>(r[rt], fields[rt], dc.ssup[rt], j);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         acc[rt][mt][0] = __builtin_fmaf(s, P[rt][mt][0], acc[rt][mt][0]);
@@ -376,10 +414,10 @@ __device__ void run_kind_tiles(const SkinnyArgs& a, const uint8_t* (&codes_rt)[R
   // tiles in flight per wavefront: as many as the register budget of the instantiation allows (a refill is
   // requested one tile's work before it is needed, far less than a memory latency, so depth is what keeps
   // the memory system busy)
-  constexpr int D = (KIND == kNarrow) ? (MT == 1 ? (RT == 1 ? 8 : 4) : (RT == 1 ? 4 : 2)) : (RT == 1 ? 2 : 1);
+  constexpr int D = ((KIND & 1) == kNarrow) ? (MT == 1 ? (RT == 1 ? 8 : 4) : (RT == 1 ? 4 : 2)) : (RT == 1 ? 2 : 1);
   int A, B;
-  split_range(a, KIND, split, A, B);
-  const int KC = a.KC[KIND], CH = KC * a.WK;
+  split_range(a, KIND & 1, split, A, B);
+  const int KC = a.KC[KIND & 1], CH = KC * a.WK;
   for (int c0 = A; c0 < B; c0 += CH) {
     const int cend = min(c0 + CH, B);
     const int k0 = min(c0 + wk * KC, cend), k1 = min(k0 + KC, cend);
@@ -445,9 +483,9 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
                                 const uint16_t* x, int row_base, int rows_valid, int split, int wk, int lane, int tid, int nthreads,
                                 DecodeConsts dc) {
   using TR = Traits<KIND>;
-  const int tiles = a.tiles[KIND];
+  const int tiles = a.tiles[KIND & 1];
   int A, B;
-  split_range(a, KIND, split, A, B);
+  split_range(a, KIND & 1, split, A, B);
   TileRegs<KIND> cur[RT], nxt[RT];
   if (active && A + wk < B) {
 #pragma unroll
@@ -481,7 +519,7 @@ __device__ void run_kind_groups(const SkinnyArgs& a, const uint8_t* (&codes_rt)[
 template <int KIND, bool META>
 __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, const uint16_t* xr, int pg0, int ng, int lane) {
   using TR = Traits<KIND>;
-  const int meta_base = (KIND == kWide) ? a.groups_narrow : 0;
+  const int meta_base = ((KIND & 1) == kWide) ? a.groups_narrow : 0;
   const int nfrag = ng * TR::T * 4;
   for (int f = lane; f < nfrag; f += 64) {
     const int kq = f & 3;
@@ -491,7 +529,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
     const int g = META ? a.meta[meta_base + pg] : pg;  // a group map exists only for mixed formats
     const uint16_t* xg = xr + (int64_t)g * kGroup;
     uint4 o = {0u, 0u, 0u, 0u};
-    if constexpr (KIND == kNarrow) {
+    if constexpr ((KIND & 1) == kNarrow) {
       const uint4 v = *reinterpret_cast<const uint4*>(xg + 16 * kq + 8 * t);
       o.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);
       o.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
@@ -513,15 +551,15 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
       o.z = h[4] | (h[5] << 16);
     }
     lds_x[f] = o;
-    if constexpr (KIND == kNarrow) {
+    if constexpr ((KIND & 1) == kNarrow) {
       // the two fragments of a quarter (k-steps 0 and 1) sit 4 lanes apart: add them with one DPP step
       float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
                   ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
       sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
-      if ((f & 4) == 0) lds_cneg[lg * 4 + kq] = a.cneg[KIND] * sum;
+      if ((f & 4) == 0) lds_cneg[lg * 4 + kq] = a.cneg[KIND & 1] * sum;
     }
   }
-  if constexpr (KIND == kWide) {
+  if constexpr ((KIND & 1) == kWide) {
     // three fragments per quarter: one lane per (group, quarter) adds them up from LDS (same wavefront: LDS
     // operations stay in order)
     __builtin_amdgcn_wave_barrier();
@@ -534,7 +572,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
         sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
                bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
       }
-      lds_cneg[e] = a.cneg[KIND] * sum;
+      lds_cneg[e] = a.cneg[KIND & 1] * sum;
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -587,25 +625,25 @@ __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)
                                  const float (&al)[RT], const float (&be_raw)[RT], f32x4 (&acc)[RT][1], uint4* lds_x, float* lds_cneg,
                                  const uint16_t* xr, int split, int wk, int lane, DecodeConsts dc) {
   using TR = Traits<KIND>;
-  constexpr int D = (KIND == kNarrow) ? (RT == 1 ? 8 : 4) : (RT == 1 ? 2 : 1);
+  constexpr int D = ((KIND & 1) == kNarrow) ? (RT == 1 ? 8 : 4) : (RT == 1 ? 2 : 1);
   if (!active) return;
   int A, B;
-  split_range(a, KIND, split, A, B);
+  split_range(a, KIND & 1, split, A, B);
   int k0, k1;
-  wave_range(a, KIND, split, A, wk, k0, k1);
-  const int CT = a.KC[KIND];  // k-tiles the private region holds
+  wave_range(a, KIND & 1, split, A, wk, k0, k1);
+  const int CT = a.KC[KIND & 1];  // k-tiles the private region holds
   for (int c0 = k0; c0 < k1; c0 += CT) {
     const int cend = min(c0 + CT, k1);
     TileRegs<KIND> buf[D][RT];
     const int n = cend - c0, ngroups = (n + D - 1) / D;
     uint4 xv[kPrivFrags];
-    if constexpr (KIND == kNarrow) stage_private_request<META>(xv, a.meta, xr, c0 * TR::GPT, n * TR::GPT, lane);
+    if constexpr ((KIND & 1) == kNarrow) stage_private_request<META>(xv, a.meta, xr, c0 * TR::GPT, n * TR::GPT, lane);
 #pragma unroll
     for (int i = 0; i < D; ++i) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) load_tile<KIND>(buf[i][rt], codes_rt[rt], scales_rt[rt], c0 + min(i, n - 1), lane);
     }
-    if constexpr (KIND == kNarrow) stage_private_finish(xv, lds_x, lds_cneg, a.cneg[kNarrow], n * TR::GPT, lane);
+    if constexpr ((KIND & 1) == kNarrow) stage_private_finish(xv, lds_x, lds_cneg, a.cneg[kNarrow], n * TR::GPT, lane);
     else stage_private<KIND, META>(lds_x, lds_cneg, a, xr, c0 * TR::GPT, n * TR::GPT, lane);
     // the Code Cluster offset plus 2^23 (exact: beta is an integer below 2^15); added only here so that
     // nothing above waits for the per-row parameters to arrive
@@ -635,7 +673,7 @@ __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&c
                                          DecodeConsts dc) {
   using TR = Traits<KIND>;
   if constexpr (MT >= 2) {
-    const int sg = a.SG[KIND];
+    const int sg = a.SG[KIND & 1];
     if (sg != TR::GPT) {
       if (sg == 1)
         run_kind_groups<KIND, MT, MR, RT, 1, META>(a, codes_rt, scales_rt, active, al, be, acc, lds_x, lds_cneg, x, row_base, rows_valid, split, wk, lane,
@@ -653,13 +691,15 @@ __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&c
                                    nthreads, dc);
 }
 
-template <int MT, int MR, int RT, int FM>
+// SM: scale mode (0 fp16 group scales, 1 compressed scales)
+template <int MT, int MR, int RT, int FM, int SM>
 __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 1024)) ccq_skinny_kernel(const SkinnyArgs a) {
+  constexpr int KN = kNarrow | (SM << 1), KW = kWide | (SM << 1);
   extern __shared__ __align__(16) unsigned char smem[];
   // Fetch the whole argument block now, in one batch of scalar loads: left to itself the compiler loads it
   // piecemeal behind the early branches, four dependent round trips (about 2.5 us) before the first request
   // for weights goes out.
-  asm volatile("" ::"s"(a.codes), "s"(a.scales), "s"(a.alpha), "s"(a.beta), "s"(a.meta), "s"(a.x), "s"(a.y), "s"(a.partial), "s"(a.sorted_rows),
+  asm volatile("" ::"s"(a.codes), "s"(a.scales), "s"(a.alpha), "s"(a.beta), "s"(a.meta), "s"(a.scale_super), "s"(a.x), "s"(a.y), "s"(a.partial), "s"(a.sorted_rows),
                "s"(a.expert_offsets), "s"(a.ldx), "s"(a.ldy), "s"(a.codes_stride), "s"(a.scales_stride), "s"(a.ab_stride), "s"(a.row_tile_bytes),
                "s"(a.row_tile_scale_halfs), "s"(a.M), "s"(a.N), "s"(a.row_tiles), "s"(a.tiles[0]), "s"(a.tiles[1]), "s"(a.WR), "s"(a.WK),
                "s"(a.S), "s"(a.inv_WR));
@@ -694,7 +734,7 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
     codes_n[rt] = codes + (int64_t)rtile * a.row_tile_bytes;
     codes_w[rt] = codes_n[rt] + (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
     scales_n[rt] = scales + (int64_t)rtile * a.row_tile_scale_halfs;
-    scales_w[rt] = scales_n[rt] + (int64_t)a.tiles[kNarrow] * kNarrowTileScaleHalfs;
+    scales_w[rt] = scales_n[rt] + (int64_t)a.tiles[kNarrow] * Traits<KN>::SCALE_HALFS;
     al[rt] = 0.f;
     be[rt] = 0.f;
     if ((FM & 1) && active) {
@@ -709,8 +749,15 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
   const int frag_cap = a.frag_cap;
   float* lds_cneg = reinterpret_cast<float*>(smem + (size_t)frag_cap * 16);
   // the compiler must see these as register values, not literals, to select v_and_or_b32
-  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}};
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}, {0.f, 0.f}};
   asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]));
+  if constexpr (SM == 1) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int rtile = min(rtile0 + rt, a.row_tiles - 1);
+      dc.ssup[rt] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + (lane & 15)]);
+    }
+  }
 
   for (int m0 = 0; m0 < Me; m0 += MT * 16) {
     const int rows_valid = min(MT * 16, Me - m0);
@@ -725,14 +772,14 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
       uint4* my_x = lds_x + (size_t)wave * (a.frag_cap + a.cneg_cap / 4);
       float* my_cneg = reinterpret_cast<float*>(my_x + a.frag_cap);
       const uint16_t* xr = a.x + (a.sorted_rows ? (int64_t)a.sorted_rows[off0 + m0] : (int64_t)(off0 + m0)) * a.ldx;
-      if constexpr ((FM & 1) != 0) run_kind_private<kNarrow, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
-      if constexpr ((FM & 2) != 0) run_kind_private<kWide, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
+      if constexpr ((FM & 1) != 0) run_kind_private<KN, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
+      if constexpr ((FM & 2) != 0) run_kind_private<KW, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
     } else {
       if constexpr ((FM & 1) != 0)
-        run_kind<kNarrow, MT, MR, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
+        run_kind<KN, MT, MR, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
                                       nthreads, dc);
       if constexpr ((FM & 2) != 0)
-        run_kind<kWide, MT, MR, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
+        run_kind<KW, MT, MR, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
                                     nthreads, dc);
     }
 
@@ -830,11 +877,13 @@ struct GemvArgs {
   int32_t row_tile_scale_halfs;
   int32_t tpw;                   // k-tiles per wavefront; the workgroup's blockDim.x / 64 wavefronts cover K
   float cneg;                    // -(128 + zp)
+  const uint16_t* scale_super;   // fp16 [N], compressed scales only (a second, 8-byte scalar load)
 };
 
-// NT = register sets for k-tiles (4, 8 or 12); the wavefront owns tpw <= NT tiles.
-template <int NT>
+// NT = register sets for k-tiles (4, 8 or 12); the wavefront owns tpw <= NT tiles.  SM = scale mode.
+template <int NT, int SM>
 __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) {
+  constexpr int KN = kNarrow | (SM << 1);
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -855,22 +904,25 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
   uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
   float* my_cneg = reinterpret_cast<float*>(my_x + frag_cap);
   const uint8_t* codes = a.codes + (int64_t)rtile * a.row_tile_bytes + (int64_t)t0 * kNarrowTileBytes;
-  const uint16_t* scales = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + (int64_t)t0 * kNarrowTileScaleHalfs;
+  const uint16_t* scales = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + (int64_t)t0 * Traits<KN>::SCALE_HALFS;
   // unconditional requests (a request under a condition would make the first use wait for all of them);
   // sets beyond tpw re-request the last tile and are not used
-  TileRegs<kNarrow> buf[NT][1];
+  TileRegs<KN> buf[NT][1];
 #pragma unroll
-  for (int i = 0; i < NT; ++i) load_tile<kNarrow>(buf[i][0], codes, scales, min(i, n - 1), lane);
+  for (int i = 0; i < NT; ++i) load_tile<KN>(buf[i][0], codes, scales, min(i, n - 1), lane);
+  uint16_t ssup_bits = 0;
+  if constexpr (SM == 1) ssup_bits = a.scale_super[rtile * 16 + (lane & 15)];
   stage_private_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
-  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}};
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}, {0.f, 0.f}};
   float magic = 8388608.f;
   asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+v"(magic));
+  dc.ssup[0] = (float)__builtin_bit_cast(_Float16, ssup_bits);
   be[0] = be_raw + magic;  // + 2^23: exact, beta is an integer below 2^15
 
   f32x4 acc[1][1] = {{f32x4{0.f, 0.f, 0.f, 0.f}}};
 #pragma unroll
   for (int i = 0; i < NT; ++i) {
-    if (i < n) process_tile<kNarrow, 1, 1, 1, 0, kNarrowGroupsPerTile>(buf[i], i * kNarrowGroupsPerTile, my_x, my_cneg, al, be, acc, lane, dc);
+    if (i < n) process_tile<KN, 1, 1, 1, 0, kNarrowGroupsPerTile>(buf[i], i * kNarrowGroupsPerTile, my_x, my_cneg, al, be, acc, lane, dc);
   }
 
   // the four quarters of a row, then the wavefronts of the workgroup (fixed order)
@@ -914,12 +966,19 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void
   a.row_tile_scale_halfs = (int32_t)L.row_tile_scale_halfs;
   a.tpw = tiles / wk;
   a.cneg = -(128.f + L.zp[kNarrow]);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
   const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 4);
   const dim3 grid((unsigned)L.row_tiles), block((unsigned)(64 * wk));
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (a.tpw <= 4) hipLaunchKernelGGL(ccq_gemv_narrow_kernel<4>, grid, block, lds, st, a);
-  else if (a.tpw <= 8) hipLaunchKernelGGL(ccq_gemv_narrow_kernel<8>, grid, block, lds, st, a);
-  else hipLaunchKernelGGL(ccq_gemv_narrow_kernel<kGemvMaxTiles>, grid, block, lds, st, a);
+  if (L.scale_mode == 0) {
+    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 0>), grid, block, lds, st, a);
+    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 0>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 0>), grid, block, lds, st, a);
+  } else {
+    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 1>), grid, block, lds, st, a);
+    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 1>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 1>), grid, block, lds, st, a);
+  }
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }
@@ -939,30 +998,36 @@ __global__ void ccq_reduce_splits_kernel(const float* partial, uint16_t* y, int6
 
 typedef void (*SkinnyKernel)(const SkinnyArgs);
 
-template <int MT, int MR, int RT>
+template <int MT, int MR, int RT, int SM>
 static SkinnyKernel pick_fm(int fm) {
   switch (fm) {
-    case 1: return ccq_skinny_kernel<MT, MR, RT, 1>;
-    case 2: return ccq_skinny_kernel<MT, MR, RT, 2>;
-    default: return ccq_skinny_kernel<MT, MR, RT, 3>;
+    case 1: return ccq_skinny_kernel<MT, MR, RT, 1, SM>;
+    case 2: return ccq_skinny_kernel<MT, MR, RT, 2, SM>;
+    default: return ccq_skinny_kernel<MT, MR, RT, 3, SM>;
   }
 }
 
 // Two row tiles per wavefront are built for the narrow format only: with the wide format the
 // register file does not hold both tiles' code registers and the compiler would spill to scratch.
-template <int MT, int MR>
+template <int MT, int MR, int SM>
 static SkinnyKernel pick_rt(int rt, int fm) {
-  if (rt == 2) return ccq_skinny_kernel<MT, MR, 2, 1>;
-  return pick_fm<MT, MR, 1>(fm);
+  if (rt == 2) return ccq_skinny_kernel<MT, MR, 2, 1, SM>;
+  return pick_fm<MT, MR, 1, SM>(fm);
 }
 
-static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm) {
-  if (mt == 1) {
-    if (mr == 1) return pick_rt<1, 1>(rt, fm);
-    return pick_rt<1, 16>(rt, fm);
+// Compressed scales (sm = 1) are built for up to 16 held rows; more rows go to the 64-row kernel.
+static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm, int sm) {
+  if (sm == 1) {
+    if (mt != 1) return nullptr;
+    if (mr == 1) return pick_rt<1, 1, 1>(rt, fm);
+    return pick_rt<1, 16, 1>(rt, fm);
   }
-  if (mt == 2) return pick_rt<2, 16>(rt, fm);
-  return pick_fm<4, 16, 1>(fm);
+  if (mt == 1) {
+    if (mr == 1) return pick_rt<1, 1, 0>(rt, fm);
+    return pick_rt<1, 16, 0>(rt, fm);
+  }
+  if (mt == 2) return pick_rt<2, 16, 0>(rt, fm);
+  return pick_fm<4, 16, 1, 0>(fm);
 }
 
 int launch_skinny(const SkinnyCall& c) {
@@ -984,6 +1049,7 @@ int launch_skinny(const SkinnyCall& c) {
   a.alpha = c.w->code_alpha;
   a.beta = c.w->code_beta;
   a.meta = static_cast<const int32_t*>(c.w->meta);
+  a.scale_super = static_cast<const uint16_t*>(c.w->scale_super);
   a.x = static_cast<const uint16_t*>(c.x);
   a.y = static_cast<uint16_t*>(c.y);
   a.partial = c.partial;
@@ -1069,7 +1135,8 @@ int launch_skinny(const SkinnyCall& c) {
   if (d.WK > 1) lds = std::max<int64_t>(lds, (int64_t)(d.WK - 1) * d.WR * d.RT * mt * 64 * 16);
   if (lds > 150 * 1024) return CCQ_ERR_BAD_PARAM;
 
-  SkinnyKernel kern = pick_kernel(mt, mr, d.RT, fm);
+  SkinnyKernel kern = pick_kernel(mt, mr, d.RT, fm, L.scale_mode);
+  if (!kern) return CCQ_ERR_UNSUPPORTED;
   hipStream_t stream = static_cast<hipStream_t>(c.stream);
   if (lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {

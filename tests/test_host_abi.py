@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     lib = b.load()
     header = open(os.path.join(ROOT, "include", "ccq.h")).read()
-    declared = set(re.findall(r"\b(ccq_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(ccq_[a-z_0-9]+)\s*\(", header))
     assert {"ccq_pack_info", "ccq_gemm", "ccq_grouped_gemm"} <= declared
     for name in declared:
         assert hasattr(lib, name), name
@@ -41,6 +41,41 @@ def test_pack_info_accounting_matches_eq5_and_oracle():
     assert i.code_bpw == 2.1875 and list(i.groups) == [96, 32]
     assert i.code_bytes == 28672 * o.row_bytes(8192, (o.F2, o.F275), gf) == 64225280
     assert i.total_bpw == 8.0 * (i.code_bytes + i.scale_bytes + 8 * 28672) / (28672 * 8192)
+
+
+def test_compressed_scale_accounting_and_packing():
+    """scale_mode 1 (Sec. 3.4): 4 bits per narrow-format group in an array of their own -> the 2.06 bpw the paper prints;
+    nothing extra for the wide format, whose field rides in the spare nibble -> 2.75 bpw all told."""
+    K, N = 8192, 8192
+    w = b.descriptor(K, N, [b.NARROW], scale_mode=1)
+    i = b.pack_info(w, 16)
+    assert i.scale_bytes == N * (K // 64) // 2 and i.code_bpw == 2.0
+    assert 8.0 * (i.code_bytes + i.scale_bytes) / (N * K) == 2.0625 == o.bpw(8, 64, 4, 4)
+    assert i.total_bpw == 8.0 * (i.code_bytes + i.scale_bytes + 8 * N + 2 * N) / (N * K)   # + alpha, beta, super scale per row
+    w2 = b.descriptor(K, N, [b.WIDE], scale_mode=1)
+    i2 = b.pack_info(w2, 16)
+    assert i2.scale_bytes == 0 and i2.code_bpw == 2.75 and i2.total_bpw == 8.0 * (i2.code_bytes + 2 * N) / (N * K)
+    bad = b.descriptor(K, N, [b.NARROW], scale_mode=2)
+    with pytest.raises(b.CcqError):
+        b.pack_info(bad)
+    # the permutation of the 4-bit fields: the p-th narrow group of row n (byte p/2, shift 4*(p%2) in paper order)
+    # lands in the 16-bit word [row tile][p/4][n%16] at bits 4*(p%4)
+    K, N = 1024, 32
+    gf = synth.group_format_map(K // 64, 8, synth.rng(3, 5))
+    w3 = b.descriptor(K, N, [b.NARROW, b.WIDE], gf, scale_mode=1)
+    gn = int((gf == 0).sum())
+    sq = synth.rng(3, 6).integers(0, 256, size=(N, gn // 2), dtype=np.uint8)
+    dev = b.pack_scales4(w3, sq)
+    assert dev.size == (N // 16) * (gn // 4) * 16
+    for n in (0, 5, 17, 31):
+        for p in range(gn):
+            field = (int(sq[n, p // 2]) >> (4 * (p % 2))) & 15
+            word = int(dev[((n // 16) * (gn // 4) + p // 4) * 16 + n % 16])
+            assert (word >> (4 * (p % 4))) & 15 == field
+    buf = np.zeros(N * (K // 64), np.uint16)
+    assert b.load().ccq_pack_scales(ctypes.byref(w3), b._np_ptr(buf), b._np_ptr(buf.copy())) == -2   # fp16 scales belong to scale_mode 0
+    w0 = b.descriptor(K, N, [b.NARROW, b.WIDE], gf)
+    assert b.load().ccq_pack_scales4(ctypes.byref(w0), b._np_ptr(sq), b._np_ptr(buf)) == -2           # and the fields to scale_mode 1
 
 
 def _device_offset_narrow(n, pos, byte):
