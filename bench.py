@@ -37,24 +37,36 @@ def algorithmic_bytes(K: int, N: int, M: int, code_bytes: int, has_cluster: bool
     return code_bytes + N * (K // 64) * 2 + (8 * N if has_cluster else 0) + 2 * M * K + 2 * M * N
 
 
-def make_weight_copies(K, N, copies, device):
-    """Random code bitstream (valid: every bit pattern decodes), log-uniform fp16 scales, random
-    Code Cluster parameters; packed once and cloned to `copies` distinct device buffers."""
+def make_weight_copies(K, N, copies, device, compressed=False):
+    """Random code bitstream (valid: every bit pattern decodes), log-uniform fp16 scales (or, with compressed scales,
+    random 4-bit fields and log-uniform fp16 super scales), random Code Cluster parameters; packed once and cloned to
+    `copies` distinct device buffers."""
+    import numpy as np
     import torch
     from paper_2507_07145_amd import binding as b, synth
     codes = synth.random_codes(N, K // 4, synth.rng(2, 0))
-    scales = synth.scales_log_uniform_fp16(N, K // 64, synth.rng(2, 1))
     alpha, beta = synth.cluster_params(N, synth.rng(2, 2))
-    w0 = b.Weight.from_canonical(K, N, [b.NARROW], codes, scales, alpha, beta, device=device)
+    if compressed:
+        sq = synth.rng(2, 5).integers(0, 256, size=(N, K // 128), dtype=np.uint8)
+        ssup = synth.scales_log_uniform_fp16(N, 1, synth.rng(2, 6), 1e-4, 1e-2).reshape(N)
+        w0 = b.Weight.from_canonical_compressed(K, N, [b.NARROW], codes, sq, ssup, alpha, beta, device=device)
+        canon = (codes, sq, ssup, alpha, beta)
+    else:
+        scales = synth.scales_log_uniform_fp16(N, K // 64, synth.rng(2, 1))
+        w0 = b.Weight.from_canonical(K, N, [b.NARROW], codes, scales, alpha, beta, device=device)
+        canon = (codes, scales, alpha, beta)
     ws = [w0]
     for _ in range(copies - 1):
         w = b.Weight()
         w.codes, w.scales, w.alpha, w.beta = w0.codes.clone(), w0.scales.clone(), w0.alpha.clone(), w0.beta.clone()
-        d = b.descriptor(K, N, [b.NARROW])
+        d = b.descriptor(K, N, [b.NARROW], scale_mode=1 if compressed else 0)
         d.codes, d.scales, d.code_alpha, d.code_beta = w.codes.data_ptr(), w.scales.data_ptr(), w.alpha.data_ptr(), w.beta.data_ptr()
+        if compressed:
+            w.ssup = w0.ssup.clone()
+            d.scale_super = w.ssup.data_ptr()
         w.desc, w.info, w.E = d, w0.info, 1
         ws.append(w)
-    return ws, (codes, scales, alpha, beta)
+    return ws, canon
 
 
 def time_steps(step_fns, steps, warmup, device):
@@ -129,6 +141,7 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=32, help="weight copies the step rotates over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-compressed", action="store_true", help="skip the compressed-scale variant of the GEMV")
     ap.add_argument("--launch", type=str, default="", help="explicit decomposition RT,WR,WK,S for tuning (default: the library's choice)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (64 MiB read + 64 MiB written per launch): the reference that "
@@ -205,6 +218,20 @@ def main() -> int:
                           "value": round(tf, 2), "unit": "TFLOP/s",
                           "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                        "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}}
+
+    if not args.no_compressed:
+        # the same GEMV with the compressed scales of Sec. 3.4 (2.0625 bits per weight all told)
+        weights_c, _ = make_weight_copies(K, N, args.copies, dev, compressed=True)
+        ys_c = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in weights_c]
+        fns_c = [(lambda w=w, y=y: b.gemm(w, x, out=y, workspace=ws)) for w, y in zip(weights_c, ys_c)]
+        steps_c = max(args.copies * 8, (args.steps // 4) // args.copies * args.copies)
+        _, ev_c = time_steps(fns_c, steps_c, args.copies, dev)
+        nbytes_c = weights_c[0].info.code_bytes + weights_c[0].info.scale_bytes + 8 * N + 2 * N + 2 * M * K + 2 * M * N
+        out["compressed_scales"] = {"workload": "config 2 shape with 4-bit group scales x fp16 super scale per row (Sec. 3.4), M=1",
+                                    "bytes_per_step": nbytes_c, "us_per_launch": round(ev_c / steps_c * 1e6, 3),
+                                    "value": round(nbytes_c / (ev_c / steps_c) / 1e9, 1), "unit": "GB/s",
+                                    "frac_of_hbm_peak": round(nbytes_c / (ev_c / steps_c) / 1e9 / HBM_PEAK_GBS, 4)}
+        del weights_c, ys_c, fns_c
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(canon, K, N, x_bits)
