@@ -119,6 +119,84 @@ def cpu_baseline(canon, K, N, x_bits, budget_s=12.0):
             "sample": f"whole workload (decode + fp64 GEMV of the {N}x{K} matrix, M=1), {reps} repetitions, {spent:.1f} s"}
 
 
+PAPER_TABLE4_MS = {(4096, 4096, 1): 0.034, (4096, 1024, 1): 0.017, (8192, 8192, 1): 0.090, (8192, 1024, 1): 0.022,
+                   (4096, 4096, 4): 0.035, (4096, 1024, 4): 0.017, (8192, 8192, 4): 0.104, (8192, 1024, 4): 0.024}
+PAPER_TABLE5_MS = {(7168, 512, 1): 0.021, (1024, 7168, 1): 0.058, (7168, 512, 4): 0.027, (1024, 7168, 4): 0.166,
+                   (7168, 512, 16): 0.059, (1024, 7168, 16): 0.527, (7168, 512, 64): 0.161, (1024, 7168, 64): 1.386}
+
+
+def paper_tables(dev) -> int:
+    """Second workload: the shapes of the paper's operator benchmarks (Table 4 GEMV, Table 5 Grouped-GEMM) at 2.06 bits
+    per weight (narrow format, compressed scales).  Table 5 is read as 256 experts of one shape, M tokens, each routed to
+    8 distinct experts.  One JSON line; the paper's H20 times ride along as context, not as a target."""
+    import numpy as np
+    import torch
+    from paper_2507_07145_amd import binding as b, synth
+
+    def comp_weights(E, K, N, seed):
+        rng = synth.rng(8, seed)
+        codes = synth.random_codes(E * N, K // 4, rng).reshape(E, N, K // 4)
+        sq = rng.integers(0, 256, size=(E, N, K // 128), dtype=np.uint8)
+        ssup = synth.scales_log_uniform_fp16(E * N, 1, rng, 1e-4, 1e-2).reshape(E, N)
+        alpha, beta = synth.cluster_params(E * N, rng)
+        return b.Weight.from_canonical_compressed(K, N, [b.NARROW], codes, sq, ssup, alpha.reshape(E, N), beta.reshape(E, N), device=dev,
+                                                  experts=None if E == 1 else E)
+
+    def clone(w0, K, N):
+        w = b.Weight()
+        w.codes, w.scales, w.alpha, w.beta, w.ssup = w0.codes.clone(), w0.scales.clone(), w0.alpha.clone(), w0.beta.clone(), w0.ssup.clone()
+        d = b.descriptor(K, N, [b.NARROW], scale_mode=1)
+        d.codes, d.scales, d.code_alpha, d.code_beta, d.scale_super = (w.codes.data_ptr(), w.scales.data_ptr(), w.alpha.data_ptr(),
+                                                                       w.beta.data_ptr(), w.ssup.data_ptr())
+        w.desc, w.info, w.E = d, w0.info, w0.E
+        return w
+
+    out = {"workload": "paper Tables 4 and 5 at 2.06 bpw (narrow format + compressed scales)", "table4_gemv": [], "table5_grouped": []}
+    for (K, N) in ((4096, 4096), (4096, 1024), (8192, 8192), (8192, 1024)):
+        w0 = comp_weights(1, K, N, K + N)
+        per_copy = w0.info.code_bytes + w0.info.scale_bytes + 10 * N
+        copies = max(2, min(64, int(600e6 // per_copy) + 1))
+        ws = [w0] + [clone(w0, K, N) for _ in range(copies - 1)]
+        for M in (1, 4):
+            x = b.bf16_tensor(synth.activations_bf16(M, K, synth.rng(8, 3)), dev)
+            ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in ws]
+            wsp = torch.empty(max(b.pack_info(w0.desc, M).workspace_bytes, 16), dtype=torch.uint8, device=dev)
+            fns = [(lambda w=w, y=y: b.gemm(w, x, out=y, workspace=wsp)) for w, y in zip(ws, ys)]
+            steps = copies * 20
+            _, ev = time_steps(fns, steps, copies, dev)
+            nbytes = per_copy + 2 * M * K + 2 * M * N
+            us = ev / steps * 1e6
+            out["table4_gemv"].append({"K": K, "N": N, "M": M, "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                                       "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4), "paper_h20_ms": PAPER_TABLE4_MS[(K, N, M)]})
+        del ws
+    E, topk = 256, 8
+    for (N, K) in ((7168, 512), (1024, 7168)):
+        w0 = comp_weights(E, K, N, 1000 + N)
+        ws = [w0, clone(w0, K, N)]
+        per_expert = (w0.info.code_bytes + w0.info.scale_bytes + 10 * N)
+        for M in (1, 4, 16, 64):
+            P = M * topk
+            x = b.bf16_tensor(synth.activations_bf16(M, K, synth.rng(8, 4)), dev)
+            routes, active = [], []
+            for r in range(8):
+                rows, offs = synth.routing_topk(M, E, topk, synth.rng(8, 100 * M + r))
+                routes.append((torch.from_numpy(rows).to(dev), torch.from_numpy(offs).to(dev), offs))
+                active.append(int(np.count_nonzero(np.diff(offs))))
+            y = torch.empty((P, N), dtype=torch.bfloat16, device=dev)
+            wsp = torch.empty(max(b.grouped_workspace_bytes(w0, P), 16), dtype=torch.uint8, device=dev)
+            fns = [(lambda i=i: b.grouped_gemm(ws[i % 2], x, routes[i][0], routes[i][1], routes[i][2], out=y, workspace=wsp)) for i in range(8)]
+            steps = 8 * 10
+            _, ev = time_steps(fns, steps, 8, dev)
+            nbytes = float(np.mean(active)) * per_expert + 2 * M * K + 2 * P * N
+            us = ev / steps * 1e6
+            out["table5_grouped"].append({"experts": E, "N": N, "K": K, "M": M, "rows": P, "active_experts_mean": round(float(np.mean(active)), 1),
+                                          "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                                          "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4), "paper_h20_ms": PAPER_TABLE5_MS[(N, K, M)]})
+        del ws
+    print(json.dumps(out))
+    return 0
+
+
 def calibrate_copy(dev) -> int:
     """A plain copy kernel of known size, rotating over buffers that together exceed the last-level cache."""
     import torch
@@ -143,6 +221,8 @@ def main() -> int:
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-compressed", action="store_true", help="skip the compressed-scale variant of the GEMV")
     ap.add_argument("--launch", type=str, default="", help="explicit decomposition RT,WR,WK,S for tuning (default: the library's choice)")
+    ap.add_argument("--paper-tables", action="store_true",
+                    help="run the second workload instead: the GEMV and Grouped-GEMM shapes of the paper's Tables 4 and 5 at 2.06 bpw")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (64 MiB read + 64 MiB written per launch): the reference that "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -161,6 +241,8 @@ def main() -> int:
 
     if args.calibrate_copy:
         return calibrate_copy(dev)
+    if args.paper_tables:
+        return paper_tables(dev)
 
     K = N = 8192
     M = 1

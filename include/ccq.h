@@ -83,9 +83,9 @@ typedef struct {
   const void *meta;         /* DEVICE, group map in device order (ccq_pack_meta); may be NULL when group_fmt is NULL */
   int32_t scale_mode;       /* 0 = fp16 group scales; 1 = compressed scales of Sec. 3.4: group scale =
                                4-bit field * scale_super[n] (first line of Alg. 2 / Alg. 3).  Mode 1 is
-                               built for ccq_gemm with up to 16 rows per launch shape chosen by the
-                               library and for 17 rows and more; explicit launch shapes that hold more
-                               than 16 rows and ccq_grouped_gemm return CCQ_ERR_UNSUPPORTED           */
+                               built for ccq_gemm at any M with the launch shape chosen by the library
+                               and for ccq_grouped_gemm; launch shapes that hold more than 16 rows in the
+                               skinny kernel return CCQ_ERR_UNSUPPORTED                               */
   const void *scale_super;  /* DEVICE, fp16[N]: per-output-channel super scale s_super (scale_mode 1) */
 } ccq_weight;
 
@@ -144,7 +144,12 @@ int ccq_gemm_ex(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void
 /* Grouped GEMM for mixture-of-experts layers (the Grouped-GEMM operator of the
  * "Inference Performance" section).  All E experts share one shape and format:
  * `w0` describes expert 0 and expert e's DEVICE arrays start
- * e * {codes,scales,ab}_stride bytes after expert 0's.
+ * e * {codes,scales,ab}_stride bytes after expert 0's (ab_stride for code_alpha
+ * and code_beta; with scale_mode 1 it must be given, at least 4 N, also for
+ * weights without Code Cluster, and expert e's scale_super starts e * ab_stride / 2
+ * bytes after expert 0's: fp16 where alpha and beta are fp32).  With scale_mode 1
+ * at most 16 rows per expert fit one pass; routings that would need more return
+ * CCQ_ERR_UNSUPPORTED.
  *   Output row p in [expert_offsets[e], expert_offsets[e+1]) is
  *       y[p][:] = x[sorted_rows[p]][:] * W_dq(e)^T.
  *   x DEVICE bf16 [T][ldx]; sorted_rows DEVICE int32 [P], values in [0,T);
@@ -159,7 +164,9 @@ int ccq_grouped_gemm(const ccq_weight *w0, int32_t E, int64_t codes_stride, int6
                      const int32_t *expert_offsets_host, void *y, int64_t ldy, void *workspace,
                      int64_t workspace_bytes, void *hip_stream);
 
-/* Workspace bytes ccq_grouped_gemm needs for P output rows. */
+/* Recommended workspace for P output rows (at most 64 MiB).  ccq_grouped_gemm works with any smaller
+ * workspace, down to none: it only cuts K into fewer shares, which matters when few experts have rows
+ * (pass expert_offsets_host so that the library can see that). */
 int64_t ccq_grouped_workspace_bytes(const ccq_weight *w0, int32_t E, int32_t P);
 
 /* Human-readable name of a status code. */

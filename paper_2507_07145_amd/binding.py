@@ -213,7 +213,8 @@ class Weight:
         return self
 
     @classmethod
-    def from_canonical_compressed(cls, K, N, fmts, codes, sq_packed, s_super_fp16, alpha=None, beta=None, group_fmt=None, device="cuda:0"):
+    def from_canonical_compressed(cls, K, N, fmts, codes, sq_packed, s_super_fp16, alpha=None, beta=None, group_fmt=None, device="cuda:0",
+                                  experts: int | None = None):
         """The same for compressed scales (scale_mode 1): `sq_packed` holds the 4-bit fields of the narrow-format
         groups (uint8 [N][ceil(narrow groups / 2)], may be empty), `s_super_fp16` the fp16 bits of the per-row super
         scale; wide-format groups carry their field inside `codes`."""
@@ -221,14 +222,17 @@ class Weight:
         self._group_fmt = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
         w = descriptor(K, N, fmts, self._group_fmt, scale_mode=1)
         info = pack_info(w, 64)
-        self.codes = torch.from_numpy(pack_codes(w, np.ascontiguousarray(codes, dtype=np.uint8).reshape(-1))).to(device)
+        E = 1 if experts is None else int(experts)
+        codes = np.ascontiguousarray(codes, dtype=np.uint8).reshape(E, -1)
+        self.codes = torch.from_numpy(np.stack([pack_codes(w, codes[e]) for e in range(E)])).to(device)
         if info.scale_bytes > 0:
-            self.scales = torch.from_numpy(pack_scales4(w, sq_packed).view(np.int16)).to(device)
-        self.ssup = torch.from_numpy(np.ascontiguousarray(s_super_fp16, dtype=np.uint16).reshape(N).view(np.int16)).to(device)
+            sq = np.ascontiguousarray(sq_packed, dtype=np.uint8).reshape(E, N, -1)
+            self.scales = torch.from_numpy(np.stack([pack_scales4(w, sq[e]) for e in range(E)]).view(np.int16)).to(device)
+        self.ssup = torch.from_numpy(np.ascontiguousarray(s_super_fp16, dtype=np.uint16).reshape(E, N).view(np.int16)).to(device)
         needs_ab = any(f.code_cluster for f in fmts)
         if needs_ab:
-            self.alpha = torch.from_numpy(np.ascontiguousarray(alpha, dtype=np.float32).reshape(N)).to(device)
-            self.beta = torch.from_numpy(np.ascontiguousarray(beta, dtype=np.float32).reshape(N)).to(device)
+            self.alpha = torch.from_numpy(np.ascontiguousarray(alpha, dtype=np.float32).reshape(E, N)).to(device)
+            self.beta = torch.from_numpy(np.ascontiguousarray(beta, dtype=np.float32).reshape(E, N)).to(device)
         if group_fmt is not None:
             self.meta = torch.from_numpy(pack_meta(w)).to(device)
         w.codes = self.codes.data_ptr()
@@ -237,7 +241,7 @@ class Weight:
         w.code_alpha = self.alpha.data_ptr() if needs_ab else None
         w.code_beta = self.beta.data_ptr() if needs_ab else None
         w.meta = self.meta.data_ptr() if self.meta is not None else None
-        self.desc, self.info, self.E = w, info, 1
+        self.desc, self.info, self.E = w, info, E
         return self
 
     @property
@@ -254,7 +258,8 @@ class Weight:
 
     def strides(self):
         """(codes, scales, alpha/beta) byte strides between consecutive experts."""
-        return (self.codes.stride(0), self.scales.stride(0) * 2, self.alpha.stride(0) * 4 if self.alpha is not None else 0)
+        ab = self.alpha.stride(0) * 4 if self.alpha is not None else (self.ssup.stride(0) * 4 if self.ssup is not None else 0)
+        return (self.codes.stride(0), self.scales.stride(0) * 2 if self.scales is not None else 0, ab)
 
 
 def _workspace(nbytes: int, device) -> torch.Tensor | None:

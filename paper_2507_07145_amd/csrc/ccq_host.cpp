@@ -105,7 +105,7 @@ using namespace ccq;
 enum DensePath { kPathGemv, kPathSkinny, kPathMid, kPathPrefill };
 static DensePath dense_path(const Layout& L, int M) {
   const bool narrow_only = L.tiles[kWide] == 0;
-  if (M == 1 && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
+  if (M <= kGemvMaxM && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
   if (M < kMidMinM) return kPathSkinny;
   if (narrow_only && M > 128) return kPathPrefill;            // 256-row tiles pay off
   return kPathMid;
@@ -315,7 +315,7 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
     }
     // one row, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
     if (path == kPathGemv) {
-      rc = launch_gemv_narrow(w, L, x, y, stream);
+      rc = launch_gemv_narrow(w, L, x, M, ldx, y, ldy, stream);
       if (rc != CCQ_ERR_UNSUPPORTED) return rc;
     }
   }
@@ -371,12 +371,27 @@ static int grouped_tile_rows(int E, int P) {
   return rows;
 }
 
+// Launch shape of a grouped call.  `active` = experts that have rows (known only when the caller passes the
+// host copy of the offsets; otherwise all E are assumed busy).  With few active experts -- a decode step routes
+// a handful of tokens to 8 of 256 experts -- the row blocks alone cannot fill the chip, so K is cut into more
+// shares, as many as the workspace the caller brought allows.
+static Decomp grouped_decomp(const Layout& L, int E, int P, int active, int64_t workspace_bytes) {
+  Decomp d = choose_decomp(L, grouped_tile_rows(E, P), std::max(1, active), P);
+  const int64_t per_share = (int64_t)P * L.N * 4;
+  if (d.S > 1 && per_share > 0) d.S = (int)std::max<int64_t>(1, std::min<int64_t>(d.S, workspace_bytes / per_share));
+  return d;
+}
+
+// Recommended workspace: room for the K shares a call with few active experts would like (at most 64 MiB); a
+// smaller workspace, down to none, only means fewer shares.
 extern "C" int64_t ccq_grouped_workspace_bytes(const ccq_weight* w0, int32_t E, int32_t P) {
   Layout L;
   if (make_layout(w0, &L) != CCQ_OK || E <= 0 || P < 0) return -1;
   if (P == 0) return 0;
-  Decomp d = choose_decomp(L, grouped_tile_rows(E, P), E, P);
-  return d.S > 1 ? (int64_t)d.S * P * L.N * 4 : 0;
+  const int active_min = std::max(1, std::min(E, (P + kMaxSkinnyM - 1) / kMaxSkinnyM));
+  Decomp d = choose_decomp(L, grouped_tile_rows(E, P), active_min, P);
+  const int64_t want = d.S > 1 ? (int64_t)d.S * P * L.N * 4 : 0;
+  return std::min<int64_t>(want, (int64_t)64 << 20);
 }
 
 extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride,
@@ -388,7 +403,6 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
   int rc = make_layout(w0, &L);
   if (rc != CCQ_OK) return rc;
   if (E <= 0 || P < 0 || T < 0 || workspace_bytes < 0) return CCQ_ERR_BAD_PARAM;
-  if (L.scale_mode != 0) return CCQ_ERR_UNSUPPORTED;  // compressed scales: dense entry point only
   if (expert_offsets_host) {
     if (expert_offsets_host[0] != 0 || expert_offsets_host[E] != P) return CCQ_ERR_ROUTING;
     for (int e = 0; e < E; ++e)
@@ -403,7 +417,7 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
   if (E > 1) {
     const int64_t code_bytes = L.row_tile_bytes * L.row_tiles, scale_bytes = L.row_tile_scale_halfs * L.row_tiles * 2;
     if (codes_stride < code_bytes || scales_stride < scale_bytes) return CCQ_ERR_BAD_PARAM;
-    if (L.groups[kNarrow] > 0 && ab_stride < (int64_t)L.N * 4) return CCQ_ERR_BAD_PARAM;
+    if ((L.groups[kNarrow] > 0 || L.scale_mode == 1) && ab_stride < (int64_t)L.N * 4) return CCQ_ERR_BAD_PARAM;
     if (codes_stride % 16 || scales_stride % 16 || ab_stride % 16) return CCQ_ERR_ALIGN;
   }
   if (!aligned16(x) || !aligned16(y) || !aligned16(workspace) || !aligned16(sorted_rows) || !aligned16(expert_offsets_dev) ||
@@ -413,12 +427,13 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
   c.w = w0;
   c.L = L;
   c.m_tile_hint = grouped_tile_rows(E, P);
-  c.d = choose_decomp(L, c.m_tile_hint, E, P);
-  if (c.d.S > 1) {
-    const int64_t need = (int64_t)c.d.S * P * L.N * 4;
-    if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
-    c.partial = static_cast<float*>(workspace);
+  int active = E;
+  if (expert_offsets_host) {
+    active = 0;
+    for (int e = 0; e < E; ++e) active += expert_offsets_host[e + 1] > expert_offsets_host[e] ? 1 : 0;
   }
+  c.d = grouped_decomp(L, E, P, active, workspace ? workspace_bytes : 0);
+  if (c.d.S > 1) c.partial = static_cast<float*>(workspace);
   c.E = E;
   c.codes_stride = codes_stride;
   c.scales_stride = scales_stride;

@@ -92,9 +92,11 @@ struct SkinnyCall {
 };
 int launch_skinny(const SkinnyCall& c);
 
-// Dense one-row product on narrow-format weights (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does not
-// split into equal shares of at most 12 k-tiles over at most 8 wavefronts (the caller then uses launch_skinny).
-int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream);
+// Dense product of one to four rows on narrow-format weights (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does
+// not split into equal shares of at most 12 k-tiles (4 with more than one row) over at most 8 wavefronts (the
+// caller then uses launch_skinny).
+constexpr int kGemvMaxM = 4;
+int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 
 // Kernel for a few dozen to a few hundred rows, any format mix (ccq_mid.hip): 64-row tiles, K cut into S
 // shares whose fp32 partial tiles go to `partial` ([S][M][N]) when S > 1 (then call launch_reduce_splits).

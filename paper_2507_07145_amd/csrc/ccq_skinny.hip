@@ -319,7 +319,8 @@ struct GroupOperands {
 // Rows of the product are independent: an activation lane of a row that is not held only feeds a row
 // of the product that is never stored.  With a single held row (MR = 1, MFMA 4x4x4) every lane of a
 // 4x4 block reads the same fragment (an LDS broadcast, no lane masking): the four rows of the block's
-// product are then equal and row 0 is the one that is used.
+// product are then equal and row 0 is the one that is used.  With up to four held rows (MR = 4) lane
+// l of a block supplies row l % 4, and the block's product holds the four rows' results of each column.
 template <int KIND, int MT, int MR>
 __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>& g, int lg, const uint4* lds_x, const float* lds_cneg, int lane) {
   using TR = Traits<KIND>;
@@ -328,6 +329,7 @@ __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>&
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     if constexpr (MR == 1) g.cin[mt][0] = lds_cneg[lg * 4 + kq];  // one float per group and quarter; elements 1..3 keep their value
+    else if constexpr (MR == 4) g.cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * 4 + kq) * 4);  // the four held rows
     else g.cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
   }
 #pragma unroll
@@ -335,6 +337,7 @@ __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>&
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       if constexpr (MR == 16) g.x[t][mt] = lds_x[((lg * TR::T + t) * 4 + kq) * MRT + mt * 16 + m];
+      else if constexpr (MR == 4) g.x[t][mt] = lds_x[((lg * TR::T + t) * 4 + kq) * 4 + (lane & 3)];  // row lane % 4 of the 4x4 block
       else g.x[t][mt] = lds_x[(lg * TR::T + t) * 4 + kq];
     }
   }
@@ -359,7 +362,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], dc.c4300, dc.mask[KIND & 1]);
-        if constexpr (MR == 1) {
+        if constexpr (MR <= 4) {
           // two 4x4x4 steps: k-slots 0..3 and 4..7 of the fragment
           const u32x4 wv = __builtin_bit_cast(u32x4, wf);
           const uint4 xv = cur.x[t][0];
@@ -755,7 +758,9 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       const int rtile = min(rtile0 + rt, a.row_tiles - 1);
-      dc.ssup[rt] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + (lane & 15)]);
+      // expert e's super scales: half the byte stride of alpha / beta (fp16 against fp32)
+      const uint16_t* ssup = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + (int64_t)e * (a.ab_stride / 2));
+      dc.ssup[rt] = (float)__builtin_bit_cast(_Float16, ssup[rtile * 16 + (lane & 15)]);
     }
   }
 
@@ -858,6 +863,39 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
   }
 }
 
+// Private staging for up to four held rows (narrow format): fragment f = ((group * 2 + t) * 4 + kq) * 4 + m.
+constexpr int kPrivFrags4 = 8;  // 4 k-tiles x 32 fragments x 4 rows / 64 lanes
+__device__ __forceinline__ void stage_private4_request(uint4 (&v)[kPrivFrags4], const uint16_t* x, int64_t ldx, int M, int ng, int lane) {
+  const int nfrag = ng * 32;
+#pragma unroll
+  for (int i = 0; i < kPrivFrags4; ++i) {
+    if (64 * i >= nfrag) break;  // wavefront-uniform
+    const int f = min(lane + 64 * i, nfrag - 1);
+    const int m = min(f & 3, M - 1), kq = (f >> 2) & 3, t = (f >> 4) & 1, pg = f >> 5;  // rows past M repeat row M-1, never stored
+    v[i] = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + (int64_t)pg * kGroup + 16 * kq + 8 * t);
+  }
+}
+__device__ __forceinline__ void stage_private4_finish(const uint4 (&v)[kPrivFrags4], uint4* lds_x, float* lds_cneg, float cneg, int ng, int lane) {
+  const int nfrag = ng * 32;
+#pragma unroll
+  for (int i = 0; i < kPrivFrags4; ++i) {
+    if (64 * i >= nfrag) break;  // wavefront-uniform
+    const int f = lane + 64 * i;  // nfrag is a multiple of 64 here: every lane is active
+    uint4 o;
+    o.x = __builtin_amdgcn_perm(v[i].z, v[i].x, 0x05040100u);
+    o.y = __builtin_amdgcn_perm(v[i].z, v[i].x, 0x07060302u);
+    o.z = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x05040100u);
+    o.w = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x07060302u);
+    lds_x[f] = o;
+    float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
+                ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
+    const float other = __shfl_xor(sum, 16);  // the other k-step of the same (group, quarter, row) sits 16 lanes away
+    const float both = (f & 16) ? other + sum : sum + other;  // k-step 0 first on both sides: identical bits
+    if ((f & 16) == 0) lds_cneg[((f >> 5) * 4 + ((f >> 2) & 3)) * 4 + (f & 3)] = cneg * both;
+  }
+  __builtin_amdgcn_wave_barrier();
+}
+
 // ---- dense GEMV on narrow-format weights: the decode step of generation --------------------
 // Same arithmetic as the one-held-row path above (identical results), with everything that path
 // carries for the general case taken out: no experts, no row map, no format map, no K split over
@@ -941,15 +979,89 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
   if (wave == 0 && lane < 16) a.y[rtile * 16 + lane] = f32_to_bf16_rne(v);
 }
 
-int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream) {
+// Two to four activation rows: the same kernel shape with MFMA 4x4x4 used as it is meant (lane l of a 4x4
+// block supplies row l % 4, the block's product holds the four rows' results of each of its columns), so
+// the weights are streamed and decoded once for all rows at the cost of three more scale multiplies per group.
+// Every wavefront owns at most 4 k-tiles.
+struct Gemv4Args {
+  GemvArgs g;
+  int64_t ldx, ldy;
+  int32_t M;
+};
+
+template <int SM>
+__global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args aa) {
+  constexpr int KN = kNarrow | (SM << 1), NT = 4;
+  const GemvArgs& a = aa.g;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nwaves = blockDim.x >> 6;
+  const int rtile = blockIdx.x, n = a.tpw;
+  const int t0 = wave * n;
+
+  uint4 xv[kPrivFrags4];
+  stage_private4_request(xv, a.x + (int64_t)t0 * (kNarrowGroupsPerTile * kGroup), aa.ldx, aa.M, n * kNarrowGroupsPerTile, lane);
+  float al[1], be[1];
+  al[0] = a.alpha[rtile * 16 + (lane & 15)];
+  const float be_raw = a.beta[rtile * 16 + (lane & 15)];
+  const int frag_cap = n * kNarrowGroupsPerTile * 32, cneg_cap = n * kNarrowGroupsPerTile * 16;
+  uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
+  float* my_cneg = reinterpret_cast<float*>(my_x + frag_cap);
+  const uint8_t* codes = a.codes + (int64_t)rtile * a.row_tile_bytes + (int64_t)t0 * kNarrowTileBytes;
+  const uint16_t* scales = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + (int64_t)t0 * Traits<KN>::SCALE_HALFS;
+  TileRegs<KN> buf[NT][1];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) load_tile<KN>(buf[i][0], codes, scales, min(i, n - 1), lane);
+  uint16_t ssup_bits = 0;
+  if constexpr (SM == 1) ssup_bits = a.scale_super[rtile * 16 + (lane & 15)];
+  stage_private4_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}, {0.f, 0.f}};
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+v"(magic));
+  dc.ssup[0] = (float)__builtin_bit_cast(_Float16, ssup_bits);
+  be[0] = be_raw + magic;  // + 2^23: exact, beta is an integer below 2^15
+
+  f32x4 acc[1][1] = {{f32x4{0.f, 0.f, 0.f, 0.f}}};
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    if (i < n) process_tile<KN, 1, 4, 1, 0, kNarrowGroupsPerTile>(buf[i], i * kNarrowGroupsPerTile, my_x, my_cneg, al, be, acc, lane, dc);
+  }
+
+  // per row: the four quarters, then the wavefronts of the workgroup (fixed order)
+  f32x4 v = acc[0][0];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    v[r] += __shfl_xor(v[r], 16);
+    v[r] += __shfl_xor(v[r], 32);
+  }
+  if (nwaves > 1) {
+    __syncthreads();
+    f32x4* red = reinterpret_cast<f32x4*>(smem);
+    if (wave > 0 && lane < 16) red[(wave - 1) * 16 + lane] = v;
+    __syncthreads();
+    if (wave == 0 && lane < 16) {
+      for (int k = 1; k < nwaves; ++k) v += red[(k - 1) * 16 + lane];
+    }
+  }
+  if (wave == 0 && lane < 16) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (r < aa.M) a.y[(int64_t)r * aa.ldy + rtile * 16 + lane] = f32_to_bf16_rne(v[r]);
+  }
+}
+
+int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
   // wavefronts per workgroup: a divisor of the k-tile count, at most 8.  Many short wavefronts (4 k-tiles
   // each) hide the latency chain of a call this small best; when that would be more wavefronts than the
-  // chip holds at once (8 per SIMD), shares of 8 tiles are better.
+  // chip holds at once (8 per SIMD), shares of 8 tiles are better.  With 2..4 rows a share is at most 4 tiles.
+  if (M < 1 || M > 4) return CCQ_ERR_UNSUPPORTED;
   const int tiles = L.tiles[kNarrow];
-  const int target = ((int64_t)L.row_tiles * tiles / 4 <= 8192) ? 4 : 8;
+  const int max_share = M == 1 ? kGemvMaxTiles : 4;
+  const int target = (M > 1 || (int64_t)L.row_tiles * tiles / 4 <= 8192) ? 4 : 8;
   int wk = 0, best = 1 << 30;
   for (int c = 1; c <= 8; ++c) {
-    if (tiles % c != 0 || tiles / c > kGemvMaxTiles) continue;
+    if (tiles % c != 0 || tiles / c > max_share) continue;
     const int dist = std::abs(tiles / c - target);
     if (dist < best) { best = dist; wk = c; }
   }
@@ -967,17 +1079,34 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void
   a.tpw = tiles / wk;
   a.cneg = -(128.f + L.zp[kNarrow]);
   a.scale_super = static_cast<const uint16_t*>(w->scale_super);
-  const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 4);
   const dim3 grid((unsigned)L.row_tiles), block((unsigned)(64 * wk));
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (L.scale_mode == 0) {
-    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 0>), grid, block, lds, st, a);
-    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 0>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 0>), grid, block, lds, st, a);
+  if (M == 1) {
+    const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 4);
+    if (L.scale_mode == 0) {
+      if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 0>), grid, block, lds, st, a);
+      else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 0>), grid, block, lds, st, a);
+      else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 0>), grid, block, lds, st, a);
+    } else {
+      if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 1>), grid, block, lds, st, a);
+      else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 1>), grid, block, lds, st, a);
+      else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 1>), grid, block, lds, st, a);
+    }
   } else {
-    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 1>), grid, block, lds, st, a);
-    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 1>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 1>), grid, block, lds, st, a);
+    Gemv4Args a4;
+    a4.g = a;
+    a4.ldx = ldx;
+    a4.ldy = ldy;
+    a4.M = M;
+    const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (32 * 16 + 16 * 4);
+    typedef void (*Gemv4Kernel)(const Gemv4Args);
+    const Gemv4Kernel kern = L.scale_mode == 0 ? ccq_gemv4_narrow_kernel<0> : ccq_gemv4_narrow_kernel<1>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      (void)hipGetLastError();
+      return CCQ_ERR_HIP;
+    }
+    hipLaunchKernelGGL(kern, grid, block, lds, st, a4);
   }
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;

@@ -1,0 +1,82 @@
+"""The shapes of the paper's operator benchmarks (Table 4: GEMV; Table 5: Grouped-GEMM) at the bit width the paper
+benchmarks, 2.06 bpw (narrow format with compressed scales, Sec. 3.4), against the oracle on sampled output channels.
+Reading of Table 5: 256 experts of one shape, M tokens, every token routed to 8 distinct experts (P = 8 M rows)."""
+import numpy as np
+import pytest
+import torch
+
+from cases import assert_gemm_close
+from oracle import ccq_oracle as o
+from paper_2507_07145_amd import binding as b
+from paper_2507_07145_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _weights(E, K, N, stream0):
+    rng = synth.rng(7, stream0)
+    codes = synth.random_codes(E * N, K // 4, rng).reshape(E, N, K // 4)
+    sq = rng.integers(0, 256, size=(E, N, K // 128), dtype=np.uint8)
+    ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(E * N, 1, rng).reshape(E, N)) * 0.1).astype(np.float16).view(np.uint16)
+    alpha, beta = synth.cluster_params(E * N, rng)
+    return codes, sq, ssup, alpha.reshape(E, N), beta.reshape(E, N)
+
+
+@pytest.mark.parametrize("K,N", [(4096, 4096), (4096, 1024), (8192, 8192), (8192, 1024)])
+def test_table4_gemv_shapes(K, N):
+    codes, sq, ssup, alpha, beta = _weights(1, K, N, K // 64 + N // 1024)
+    w = b.Weight.from_canonical_compressed(K, N, [b.NARROW], codes[0], sq[0], ssup[0], alpha[0], beta[0], device=DEV)
+    rows = np.concatenate([np.arange(16), np.arange(N // 2, N // 2 + 16), np.arange(N - 16, N)])
+    Wr = o.decode_cs(K, len(rows), o.F2, codes[0][rows], sq[0][rows], ssup[0][rows], alpha[0][rows], beta[0][rows])
+    for M in (1, 4):
+        x = synth.activations_bf16(M, K, synth.rng(7, 50 + M))
+        y = b.gemm(w, b.bf16_tensor(x, DEV))
+        torch.cuda.synchronize()
+        assert_gemm_close(b.bf16_bits(y)[:, rows], o.matmul(x, Wr), f"Table 4 shape {K}x{N} M={M}")
+
+
+@pytest.mark.parametrize("N,K", [(7168, 512), (1024, 7168)])
+def test_table5_grouped_shapes(N, K):
+    E, topk = 256, 8
+    codes, sq, ssup, alpha, beta = _weights(E, K, N, 100 + K // 512)
+    w = b.Weight.from_canonical_compressed(K, N, [b.NARROW], codes, sq, ssup, alpha, beta, device=DEV, experts=E)
+    cols = np.concatenate([np.arange(16), np.arange(N - 16, N)])
+    for M in (1, 4, 16, 64):
+        rows, offs = synth.routing_topk(M, E, topk, synth.rng(7, 200 + M))
+        P = M * topk
+        x = synth.activations_bf16(M, K, synth.rng(7, 210 + M))
+        y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
+        torch.cuda.synchronize()
+        got = b.bf16_bits(y)
+        ref = np.zeros((P, len(cols)))
+        for e in range(E):
+            lo, hi = int(offs[e]), int(offs[e + 1])
+            if hi > lo:
+                We = o.decode_cs(K, len(cols), o.F2, codes[e][cols], sq[e][cols], ssup[e][cols], alpha[e][cols], beta[e][cols])
+                ref[lo:hi] = o.matmul(x[rows[lo:hi]], We)
+        assert_gemm_close(got[:, cols], ref, f"Table 5 shape 256x{N}x{K} M={M}")
+
+
+def test_grouped_compressed_scales_wide_and_mixed():
+    """Grouped entry point with compressed scales on formats that carry the field in the code stream."""
+    E, K, N, T, topk = 6, 1024, 64, 10, 3
+    for kinds, n_wide in ((["wide"], None), (["narrow", "wide"], 8)):
+        rng = synth.rng(7, 300 + len(kinds))
+        ofmt = o.F275 if len(kinds) == 1 else (o.F2, o.F275)
+        gf = synth.group_format_map(K // 64, n_wide, rng) if len(kinds) == 2 else None
+        rb = o.row_bytes(K, ofmt, gf)
+        nb = o.sq_row_bytes(K, ofmt, gf)
+        codes = synth.random_codes(E * N, rb, rng).reshape(E, N, rb)
+        sq = rng.integers(0, 256, size=(E, N, max(nb, 1)), dtype=np.uint8)[:, :, :nb]
+        ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(E * N, 1, rng).reshape(E, N)) * 0.1).astype(np.float16).view(np.uint16)
+        alpha, beta = synth.cluster_params(E * N, rng)
+        alpha, beta = alpha.reshape(E, N), beta.reshape(E, N)
+        fm = [b.WIDE] if len(kinds) == 1 else [b.NARROW, b.WIDE]
+        w = b.Weight.from_canonical_compressed(K, N, fm, codes, sq, ssup, alpha, beta, gf, device=DEV, experts=E)
+        rows, offs = synth.routing_topk(T, E, topk, rng)
+        x = synth.activations_bf16(T, K, rng)
+        y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
+        torch.cuda.synchronize()
+        ref = o.grouped_matmul(x, rows, offs, lambda e: o.decode_cs(K, N, ofmt, codes[e], sq[e], ssup[e], alpha[e], beta[e], gf))
+        assert_gemm_close(b.bf16_bits(y), ref, f"grouped, compressed scales, {kinds}")

@@ -149,11 +149,28 @@ def test_mid_kernel_formats(kinds, K, N, M, n_wide):
     assert np.array_equal(canon_zero(got), canon_zero(want)), f"mid kernel {kinds}: decoded weights differ"
 
 
+@pytest.mark.parametrize("K,N", [(2048, 96), (8192, 64), (1280, 48)])
+def test_two_to_four_rows(K, N):
+    """2..4 rows on narrow-format weights: the GEMV kernel with MFMA 4x4x4 fed four different rows (K = 1280 does not
+    split into shares of at most 4 k-tiles and takes the general kernel instead).  Decoded weights exact, products close,
+    and identical to the one-row kernel's result for each row."""
+    c = random_case(K, N, ["narrow"], 12, stream0=K % 97)
+    w = c.device_weight(DEV)
+    for M in (2, 3, 4):
+        x = synth.activations_bf16(M, K, synth.rng(12, 40 + M))
+        got = _gemm_bits(w, x)
+        assert_gemm_close(got, o.matmul(x, c.W()), f"K={K} M={M}")
+        for m in range(M):
+            assert np.array_equal(got[m], _gemm_bits(w, x[m:m + 1])[0]), f"row {m} differs from the one-row kernel"
+        ks = [0, K - 1, 63, 64][:M]
+        _check_decode(c, w, ks)
+
+
 def test_strided_activations_and_guard_bands():
     """ldx > K, ldy > N: nothing outside y[:M, :N] is written."""
     c = random_case(1024, 96, ["narrow"], 8)
     w = c.device_weight(DEV)
-    for M in (1, 7, 64, 70):
+    for M in (1, 2, 3, 4, 7, 17, 64, 70, 200):
         xb = synth.activations_bf16(M, c.K, synth.rng(8, M))
         xt = torch.zeros((M, c.K + 64), dtype=torch.bfloat16, device=DEV)
         xt[:, :c.K] = b.bf16_tensor(xb, DEV)
