@@ -19,6 +19,8 @@
  *                         graph of Fig. 1 (must return the identical code)
  *   cco_refit_scale       Eq. 4 (closed-form least-squares scale)
  *   cco_quantize          Alg. 1 + Sec. 3.3 Code Cluster + Sec. 3.4 scale step
+ *   cco_h16_*             Sec. 3.2 "Hybrid Encoding": (3,3,2) and (3,4,2) side by side in
+ *                         one 16-bit word, seven weights per word (Table 1 row 2)
  *   cco_expand_scales     Sec. 3.4 "Scale Compression": s = (4-bit field) * s_super,
  *                         first line of Alg. 2 and of Alg. 3
  *   cco_compress_scales   the encoder side of the same (channel-wise super scale)
@@ -626,6 +628,94 @@ int cco_compress_scales(int K, int Nrows, int g, const cco_code fmt[2], const ui
       }
     }
     free(w); free(gc); free(reach);
+  }
+  return 0;
+}
+
+/* ---------- Sec. 3.2 Hybrid Encoding: the 16-bit word ---------------------- */
+
+/* One little-endian uint16 holds a (L=3,N=3,S=2) code in its top 7 bits and a
+ * (L=3,N=4,S=2) code in its low 9 bits: seven 3-bit states.  Written out from
+ * the two code definitions; Table 1's shift list [13,11,9,6,4,2,0] with mask
+ * 0x7 is what this must reproduce (pinned in the tests). */
+void cco_h16_states(uint32_t word, uint32_t st[7]) {
+  cco_states((word >> 9) & 0x7Fu, 3, 3, 2, st);
+  cco_states(word & 0x1FFu, 3, 4, 2, st + 3);
+}
+
+int cco_h16_words_per_group(int g) { return (g + 6) / 7; }
+
+/* W[n][k] = (state - zp) * scale[n][k/g], fp16 group scales.  A group stores
+ * ceil(g/7) words; the last word of a 64-weight group carries weight 63 in its
+ * first state and 13 spare bits (Sec. 3.4), which are ignored here. */
+int cco_h16_decode(int K, int Nrows, int g, double zp, const uint8_t *codes, const uint16_t *scales_fp16, double *W) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0) return -2;
+  int G = K / g, wpg = cco_h16_words_per_group(g);
+#pragma omp parallel for schedule(static)
+  for (int n = 0; n < Nrows; ++n) {
+    const uint8_t *p = codes + (int64_t)n * G * wpg * 2;
+    for (int gi = 0; gi < G; ++gi) {
+      double s = cco_fp16_to_double(scales_fp16[(int64_t)n * G + gi]);
+      for (int idx = 0; idx < g; ++idx) {
+        uint32_t st[7];
+        cco_h16_states(load_code(p + (int64_t)(idx / 7) * 2, 2), st); /* Alg. 2: q_w = W_q[idx / p_w], p_w = 7 */
+        W[(int64_t)n * K + (int64_t)gi * g + idx] = ((double)st[idx % 7] - zp) * s;
+      }
+      p += wpg * 2;
+    }
+  }
+  return 0;
+}
+
+/* Alg. 1 for the hybrid word: the two codes of a word are searched independently
+ * (their bits do not overlap), group scale as in cco_quantize:
+ * absmax/(2^(L-1)-1), search, Eq. 4 refit kept when the error does not grow,
+ * fp16 rounding, search again with the stored scale.  method as in cco_quantize. */
+int cco_h16_quantize(int K, int Nrows, int g, double zp, const float *W, int method, uint8_t *codes, uint16_t *scales_fp16) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0) return -2;
+  int G = K / g, wpg = cco_h16_words_per_group(g);
+#pragma omp parallel
+  {
+    double *w = (double *)malloc(sizeof(double) * (size_t)(wpg * 7));
+    double *wq = (double *)malloc(sizeof(double) * (size_t)(wpg * 7));
+    uint32_t *words = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)wpg);
+#pragma omp for schedule(dynamic, 4)
+    for (int n = 0; n < Nrows; ++n) {
+      for (int gi = 0; gi < G; ++gi) {
+        double amax = 0.0;
+        for (int i = 0; i < wpg * 7; ++i) {
+          w[i] = i < g ? (double)W[(int64_t)n * K + (int64_t)gi * g + i] : 0.0; /* zero-padded tail (Sec. 3.1) */
+          if (fabs(w[i]) > amax) amax = fabs(w[i]);
+        }
+        double s = 0.0;
+        for (int j = 0; j < wpg; ++j) words[j] = 0;
+        if (amax > 0.0) {
+          double s0 = amax / 3.0; /* 2^(L-1) - 1 with L = 3 */
+          for (int pass = 0; pass < 2; ++pass) {
+            double sc = pass == 0 ? s0 : s;
+            for (int j = 0; j < wpg; ++j) {
+              uint32_t a = method == 0 ? cco_search_brute(w + 7 * j, sc, zp, 3, 3, 2) : cco_search_viterbi(w + 7 * j, sc, zp, 3, 3, 2);
+              uint32_t b = method == 0 ? cco_search_brute(w + 7 * j + 3, sc, zp, 3, 4, 2) : cco_search_viterbi(w + 7 * j + 3, sc, zp, 3, 4, 2);
+              words[j] = (a << 9) | b;
+            }
+            if (pass == 0) {
+              for (int j = 0; j < wpg; ++j) {
+                uint32_t st[7];
+                cco_h16_states(words[j], st);
+                for (int i = 0; i < 7; ++i) wq[7 * j + i] = (double)st[i] - zp;
+              }
+              double s1 = cco_refit_scale(w, wq, g, s0);
+              if (!(s1 > 0.0) || group_error(w, wq, g, s1) > group_error(w, wq, g, s0)) s1 = s0;
+              s = fp16_scale(s1);
+            }
+          }
+        }
+        uint8_t *p = codes + ((int64_t)n * G + gi) * wpg * 2;
+        for (int j = 0; j < wpg; ++j) store_code(p + 2 * j, 2, words[j]);
+        scales_fp16[(int64_t)n * G + gi] = cco_double_to_fp16(s);
+      }
+    }
+    free(w); free(wq); free(words);
   }
   return 0;
 }

@@ -115,6 +115,14 @@ def lib():
         L.cco_expand_scales.argtypes = [I, I, I, cp, u8p, u8p, u8p, u16p, f64p]
         L.cco_compress_scales.restype = I
         L.cco_compress_scales.argtypes = [I, I, I, cp, u8p, f32p, I, u8p, u16p, f32p, f32p, u8p, u16p]
+        L.cco_h16_states.restype = None
+        L.cco_h16_states.argtypes = [ctypes.c_uint32, u32p]
+        L.cco_h16_words_per_group.restype = I
+        L.cco_h16_words_per_group.argtypes = [I]
+        L.cco_h16_decode.restype = I
+        L.cco_h16_decode.argtypes = [I, I, I, ctypes.c_double, u8p, u16p, f64p]
+        L.cco_h16_quantize.restype = I
+        L.cco_h16_quantize.argtypes = [I, I, I, ctypes.c_double, f32p, I, u8p, u16p]
         L.cco_matmul.restype = None
         L.cco_matmul.argtypes = [I, I, I, u16p, ctypes.c_int64, f64p, f64p]
         L.cco_num_threads.restype = I
@@ -281,6 +289,45 @@ def compress_scales(W, fmt, codes, scales_fp16, alpha=None, beta=None, group_fmt
     if rc != 0:
         raise ValueError(f"cco_compress_scales failed with {rc}")
     return codes, sq[:, :nb], ssup
+
+
+# ---- Sec. 3.2 hybrid word: (3,3,2) + (3,4,2) in 16 bits, 2.28 bpw per word, 2.5 bpw at g = 64
+H16_ZP = 4.0
+
+
+def h16_states(word: int) -> list[int]:
+    st = (ctypes.c_uint32 * 7)()
+    lib().cco_h16_states(int(word), st)
+    return list(st)
+
+
+def h16_row_bytes(K: int, g: int = 64) -> int:
+    return (K // g) * lib().cco_h16_words_per_group(g) * 2
+
+
+def h16_decode(K, N, codes, scales_fp16, zp: float = H16_ZP, g: int = 64) -> np.ndarray:
+    """Alg. 2 on hybrid words: canonical bytes (little-endian uint16 words, 10 per 64-weight group) -> W fp64 [N][K]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales_fp16, dtype=np.uint16)
+    assert codes.size == N * h16_row_bytes(K, g) and scales.size == N * (K // g)
+    W = np.empty((N, K), dtype=np.float64)
+    rc = lib().cco_h16_decode(K, N, g, float(zp), _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint16), _p(W, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"cco_h16_decode failed with {rc}")
+    return W
+
+
+def h16_quantize(W: np.ndarray, method: str = "viterbi", zp: float = H16_ZP, g: int = 64):
+    """Alg. 1 on hybrid words: returns (codes uint8 [N][h16_row_bytes], scales fp16 bits [N][K/g])."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    N, K = W.shape
+    codes = np.zeros((N, h16_row_bytes(K, g)), dtype=np.uint8)
+    scales = np.zeros((N, K // g), dtype=np.uint16)
+    rc = lib().cco_h16_quantize(K, N, g, float(zp), _p(W, ctypes.c_float), 0 if method == "brute" else 1, _p(codes, ctypes.c_uint8),
+                                _p(scales, ctypes.c_uint16))
+    if rc != 0:
+        raise ValueError(f"cco_h16_quantize failed with {rc}")
+    return codes, scales
 
 
 def matmul(x_bf16: np.ndarray, W: np.ndarray) -> np.ndarray:
