@@ -15,9 +15,17 @@
  *           the byte q is first expanded to the 15-bit code
  *           c = round(q * code_alpha[n] + code_beta[n])   (Alg. 3, Eq. 1)
  *   wide    (L=4,N=3,S=2): 22 bytes per 64 weights (2.75 bpw), Alg. 2.
- * A weight matrix uses the narrow format, the wide format, or a per-group mix
- * (group_fmt), all rows sharing the same map.  Group size is 64 along K and
- * scales are fp16, one per (row, group).
+ *   hybrid  (L=3,N=3,S=2) and (L=3,N=4,S=2) side by side in one little-endian
+ *           16-bit word (Sec. 3.2 "Hybrid Encoding", Table 1 row 2): seven
+ *           3-bit states per word at the shifts [13,11,9,6,4,2,0]; a 64-weight
+ *           group is 10 words (20 bytes, 2.5 bpw), the last of which carries
+ *           weight 63 in its top state and 13 unused bits.  Selected by
+ *           n_formats = 2, fmt[0] = (3,3,2), fmt[1] = (3,4,2), both with the
+ *           same zp and code_cluster = 0, group_fmt = NULL; fp16 scales only.
+ * A weight matrix uses the narrow format, the wide format, a per-group mix of
+ * those two (group_fmt), all rows sharing the same map, or the hybrid word.
+ * Group size is 64 along K and scales are fp16, one per (row, group), unless
+ * scale_mode says otherwise.
  *
  * Conventions
  *   - Every pointer is marked HOST or DEVICE.  The caller owns all buffers; the
@@ -68,8 +76,10 @@ typedef struct {
   int32_t K, N;
   int32_t group;            /* weights per scale along K; must be 64         */
   int32_t n_formats;        /* 1 or 2                                        */
-  ccq_code fmt[2];          /* fmt[0] = narrow (6,4,3)+cluster or wide; with 2 formats fmt[0] narrow, fmt[1] wide */
-  const uint8_t *group_fmt; /* HOST, K/group entries in {0,1} selecting fmt[] per group; NULL = all fmt[0] */
+  ccq_code fmt[2];          /* fmt[0] = narrow (6,4,3)+cluster or wide; with 2 formats fmt[0] narrow, fmt[1] wide,
+                               or the two halves (3,3,2), (3,4,2) of the hybrid word                  */
+  const uint8_t *group_fmt; /* HOST, K/group entries in {0,1} selecting fmt[] per group; NULL = all fmt[0]
+                               (must be NULL for the hybrid word, whose two codes share every word) */
   const void *codes;        /* DEVICE, packed codes in device order (ccq_pack_codes)   */
   const void *scales;       /* DEVICE.  scale_mode 0: fp16 group scales in device order (ccq_pack_scales).
                                scale_mode 1: the packed 4-bit scale fields s_q of the narrow-format

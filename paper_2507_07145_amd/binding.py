@@ -54,6 +54,10 @@ class ccq_launch(ctypes.Structure):
 # the two code configurations of Table 1 the kernels are built for
 NARROW = ccq_code(6, 4, 3, 1, 32.0)   # (L=6,N=4,S=3) + Code Cluster, 2.0 bpw
 WIDE = ccq_code(4, 3, 2, 0, 8.0)      # (L=4,N=3,S=2), 2.75 bpw
+# the two halves of the hybrid 16-bit word of Sec. 3.2 (pass both, in this order, without a group map)
+H16_HI = ccq_code(3, 3, 2, 0, 4.0)    # (L=3,N=3,S=2): top 7 bits of the word
+H16_LO = ccq_code(3, 4, 2, 0, 4.0)    # (L=3,N=4,S=2): low 9 bits; 10 words per 64 weights, 2.5 bpw
+H16 = [H16_HI, H16_LO]
 
 EXPORTS = ["ccq_pack_info", "ccq_pack_codes", "ccq_pack_scales", "ccq_pack_scales4", "ccq_pack_meta", "ccq_gemm", "ccq_gemm_ex",
            "ccq_grouped_gemm", "ccq_grouped_workspace_bytes", "ccq_status_string"]

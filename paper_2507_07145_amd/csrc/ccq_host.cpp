@@ -12,6 +12,11 @@ namespace ccq {
 
 static bool is_narrow(const ccq_code& c) { return c.L == 6 && c.N == 4 && c.S == 3 && c.code_cluster == 1; }
 static bool is_wide(const ccq_code& c) { return c.L == 4 && c.N == 3 && c.S == 2 && c.code_cluster == 0; }
+// the two halves of the hybrid word of Sec. 3.2: (3,3,2) in the top 7 bits, (3,4,2) in the low 9 bits
+static bool is_h16(const ccq_weight* w) {
+  return w->n_formats == 2 && !w->group_fmt && w->fmt[0].L == 3 && w->fmt[0].N == 3 && w->fmt[0].S == 2 && w->fmt[0].code_cluster == 0 &&
+         w->fmt[1].L == 3 && w->fmt[1].N == 4 && w->fmt[1].S == 2 && w->fmt[1].code_cluster == 0;
+}
 
 int make_layout(const ccq_weight* w, Layout* out) {
   if (!w || !out) return CCQ_ERR_NULL;
@@ -25,6 +30,25 @@ int make_layout(const ccq_weight* w, Layout* out) {
   L.K = w->K;
   L.N = w->N;
   L.G = w->K / kGroup;
+  if (is_h16(w)) {
+    // one zero-point for the seven states of a word; fp16 group scales only
+    const float zp = w->fmt[0].zp;
+    if (w->fmt[1].zp != zp) return CCQ_ERR_UNSUPPORTED;
+    if (!(zp * 2.0f == std::floor(zp * 2.0f)) || zp < 0.f || zp > 64.f) return CCQ_ERR_BAD_PARAM;
+    if (w->scale_mode != 0) return CCQ_ERR_UNSUPPORTED;
+    if (L.G % kWideGroupsPerTile != 0 || w->N % kRowsPerTile != 0) return CCQ_ERR_UNSUPPORTED;
+    L.h16 = true;
+    L.kind_of_fmt[0] = L.kind_of_fmt[1] = kWide;
+    L.zp[kWide] = zp;
+    L.groups[kWide] = L.G;
+    L.tiles[kWide] = L.G / kWideGroupsPerTile;
+    L.row_tile_bytes = (int64_t)L.tiles[kWide] * kH16TileBytes;
+    L.row_tile_scale_halfs = (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;
+    L.row_tiles = w->N / kRowsPerTile;
+    if (L.row_tile_bytes * (int64_t)L.row_tiles >= (int64_t)1 << 40) return CCQ_ERR_BAD_PARAM;
+    *out = L;
+    return CCQ_OK;
+  }
   for (int f = 0; f < w->n_formats; ++f) {
     const ccq_code& c = w->fmt[f];
     if (c.L < 1 || c.N < 1 || c.S < 1 || c.S > c.L || c.L > 16) return CCQ_ERR_BAD_PARAM;
@@ -106,7 +130,7 @@ enum DensePath { kPathGemv, kPathSkinny, kPathMid, kPathPrefill };
 static DensePath dense_path(const Layout& L, int M) {
   const bool narrow_only = L.tiles[kWide] == 0;
   if (M <= kGemvMaxM && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
-  if (M < kMidMinM) return kPathSkinny;
+  if (M < kMidMinM || L.h16) return kPathSkinny;
   if (narrow_only && M > 128) return kPathPrefill;            // 256-row tiles pay off
   return kPathMid;
 }
@@ -137,7 +161,7 @@ extern "C" int ccq_pack_info(const ccq_weight* w, int32_t M_max, ccq_info* out) 
   std::memset(&info, 0, sizeof(info));
   info.bytes_per_group[0] = info.bytes_per_group[1] = 0;
   for (int f = 0; f < w->n_formats; ++f)
-    info.bytes_per_group[f] = L.kind_of_fmt[f] == kNarrow ? kNarrowGroupBytes : kWideGroupBytes;
+    info.bytes_per_group[f] = L.h16 ? kH16GroupBytes : (L.kind_of_fmt[f] == kNarrow ? kNarrowGroupBytes : kWideGroupBytes);
   for (int f = 0; f < w->n_formats; ++f) info.groups[f] = L.groups[L.kind_of_fmt[f]];
   info.row_tile_bytes = L.row_tile_bytes;
   info.code_bytes = L.row_tile_bytes * L.row_tiles;
@@ -174,6 +198,22 @@ extern "C" int ccq_pack_codes(const ccq_weight* w, const uint8_t* src, void* out
   int rc = make_layout(w, &L);
   if (rc != CCQ_OK) return rc;
   uint8_t* out = static_cast<uint8_t*>(out_v);
+  if (L.h16) {
+    for (int n = 0; n < L.N; ++n) {
+      const uint8_t* row = src + (int64_t)n * L.G * kH16GroupBytes;
+      uint8_t* tile_row = out + (int64_t)(n / kRowsPerTile) * L.row_tile_bytes;
+      const int r = n % kRowsPerTile;
+      for (int g = 0; g < L.G; ++g) {
+        uint8_t* tile = tile_row + (int64_t)(g / kWideGroupsPerTile) * kH16TileBytes;
+        const int j = g % kWideGroupsPerTile;
+        for (int word = 0; word < 10; ++word) {
+          const int t = word / 4, kq = word % 4;
+          for (int b = 0; b < 2; ++b) tile[t * 1024 + (kq * 16 + r) * 16 + j * 2 + b] = row[(int64_t)g * kH16GroupBytes + 2 * word + b];
+        }
+      }
+    }
+    return CCQ_OK;
+  }
   std::vector<int> pos, kind;
   packed_order(w, L, pos, kind);
   std::vector<int64_t> goff(L.G);  // canonical byte offset of each group inside a row

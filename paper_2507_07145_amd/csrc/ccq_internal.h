@@ -21,6 +21,10 @@ namespace ccq {
 //     lane l reads 16 bytes of segment t: halfword j is group j of the tile,
 //     holding canonical bytes 6kq+2t, 6kq+2t+1 of the group (quarter 3 has only
 //     bytes 18..21, so segment 2 has no entries for lanes 48..63).
+//   hybrid-word k-tile (2560 B; Sec. 3.2, one (3,3,2) and one (3,4,2) code in a 16-bit word, ten
+//     words per group): takes the place of the wide kind.  Three segments t = 0,1,2 of 1024, 1024,
+//     512 bytes; halfword j of lane l's 16 bytes of segment t is word 4t + kq of group j (words 8
+//     and 9 only: segment 2 has no entries for lanes 32..63).
 constexpr int kGroup = 64;
 constexpr int kRowsPerTile = 16;
 constexpr int kNarrowGroupsPerTile = 4;
@@ -29,6 +33,8 @@ constexpr int kNarrowTileBytes = 1024;
 constexpr int kWideTileBytes = 2816;
 constexpr int kNarrowGroupBytes = 16;
 constexpr int kWideGroupBytes = 22;
+constexpr int kH16TileBytes = 2560;
+constexpr int kH16GroupBytes = 20;
 // fp16 scales: per row tile, per k-tile, [row 0..15][group of the tile]
 constexpr int kNarrowTileScaleHalfs = 16 * 4;
 constexpr int kWideTileScaleHalfs = 16 * 8;
@@ -49,6 +55,7 @@ struct Layout {
   int kind_of_fmt[2] = {0, 0};  // descriptor format index -> Kind
   float zp[2] = {0.f, 0.f};     // zero-point per kind
   bool has_map = false;         // group_fmt given
+  bool h16 = false;             // the second kind is the hybrid 16-bit word of Sec. 3.2 (then there are no narrow groups)
   int scale_mode = 0;           // 0 fp16 group scales, 1 4-bit fields times a per-row super scale
   int64_t row_tile_bytes = 0;
   int64_t row_tile_scale_halfs = 0;

@@ -381,6 +381,7 @@ int mid_splits(const Layout& L, int M) {
 
 int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
                void* stream) {
+  if (L.h16) return CCQ_ERR_UNSUPPORTED;
   MidArgs a;
   a.codes = static_cast<const uint8_t*>(w->codes);
   a.scales = static_cast<const uint16_t*>(w->scales);

@@ -78,8 +78,11 @@ struct SkinnyArgs {
 };
 
 // KIND = format (bit 0: kNarrow / kWide) | scale mode << 1 (bit 1: 0 fp16 group scales, 1 the compressed
-// scales of Sec. 3.4: a 4-bit field per group times a per-row super scale).
+// scales of Sec. 3.4: a 4-bit field per group times a per-row super scale) | hybrid word << 2 (bit 2, on top
+// of kWide: the second kind is the 16-bit word of Sec. 3.2 that holds a (3,3,2) and a (3,4,2) code, which
+// shares the wide kind's shape: 8 groups per k-tile, three k-steps per group, three segments per tile).
 constexpr int kScale4 = 2;
+constexpr int kH16 = 4;
 template <int KIND> struct Traits;
 template <> struct Traits<kNarrow> {
   static constexpr int GPT = kNarrowGroupsPerTile, T = 2, SEGS = 1, TILE_BYTES = kNarrowTileBytes, SCALE_HALFS = kNarrowTileScaleHalfs;
@@ -93,6 +96,12 @@ template <> struct Traits<kNarrow | kScale4> : Traits<kNarrow> {
 template <> struct Traits<kWide | kScale4> : Traits<kWide> {
   static constexpr int SCALE_HALFS = 0;
 };
+template <> struct Traits<kWide | kH16> : Traits<kWide> {
+  static constexpr int TILE_BYTES = kH16TileBytes;
+};
+// activation index inside a group for k-slot i (0..6) of a hybrid word: the decode pairs the states at
+// shifts (13,11), (6,4), (2,0) and leaves the one at shift 9 alone, i.e. weights {0,1}, {3,4}, {5,6}, {2}
+__device__ __forceinline__ int h16_slot_weight(int i) { return i < 2 ? i : (i < 6 ? i + 1 : 2); }
 
 // k-tiles [A, B) of kind `kind` that workgroup `split` owns.
 __device__ __forceinline__ void split_range(const SkinnyArgs& a, int kind, int split, int& A, int& B) {
@@ -130,14 +139,15 @@ __device__ __forceinline__ void load_tile(TileRegs<KIND>& r, const uint8_t* code
   r.c[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
   if constexpr ((KIND & 1) == kWide) {
     r.c[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
-    // the third segment has entries for 48 lanes only; lanes 48..63 re-read lane 47's entry (their k-slots
-    // are staged as zero activations, and every bit pattern decodes to a finite value)
-    r.c[2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47 ? (lane - 47) * 16 : 0)));
+    // the third segment has entries for 48 lanes only (32 for the hybrid word); the lanes above re-read the last
+    // entry (their k-slots are staged as zero activations, and every bit pattern decodes to a finite value)
+    constexpr int last = (KIND & kH16) ? 31 : 47;
+    r.c[2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > last ? (lane - last) * 16 : 0)));
   }
   if constexpr (KIND == kNarrow) {
     const uint2 v = *reinterpret_cast<const uint2*>(scales_kind + (int64_t)kt * TR::SCALE_HALFS + (lane & 15) * TR::GPT);
     r.s[0] = v.x; r.s[1] = v.y;
-  } else if constexpr (KIND == kWide) {
+  } else if constexpr (KIND == kWide || KIND == (kWide | kH16)) {
     const uint4 v = *reinterpret_cast<const uint4*>(scales_kind + (int64_t)kt * TR::SCALE_HALFS + (lane & 15) * TR::GPT);
     r.s[0] = v.x; r.s[1] = v.y; r.s[2] = v.z; r.s[3] = v.w;
   } else if constexpr (KIND == (kNarrow | kScale4)) {
@@ -164,7 +174,7 @@ __device__ __forceinline__ void tile_scale_fields(uint32_t (&f)[4], const TileRe
 // the narrow (0x3F) and wide (0xF) formats (Table 1).
 struct DecodeConsts {
   uint32_t c4300;
-  uint32_t mask[2];
+  uint32_t mask[3];  // narrow, wide, hybrid word
   float ssup[2];  // per-row super scale of each row tile the wavefront owns (compressed scales only)
 };
 
@@ -183,6 +193,19 @@ __device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, in
     o.y = and_or(yy >> 6, mask, c4300);
     o.z = and_or(yy >> 3, mask, c4300);
     o.w = and_or(yy, mask, c4300);
+  } else if constexpr ((KIND & kH16) != 0) {
+    // one 16-bit word w = (3,3,2) code | (3,4,2) code: seven 3-bit states at the shifts [13,11,9,6,4,2,0],
+    // mask 0x7 (Table 1).  v = w | w << 18 puts a second copy of the word 18 bits up, so that the state
+    // at shift s - 2 of the copy lands 16 bits above the state at shift s: one shift and one and-or cut
+    // out two states.  (Bits 14 and 15 of the copy fall off the register; no state of the copy that is
+    // used reaches them.)
+    const uint32_t d = dword_of(r.c[t], j >> 1);
+    const uint32_t w = (j & 1) ? (d >> 16) : (d & 0xFFFFu);
+    const uint32_t v = w | (w << 18);
+    o.x = and_or(v >> 13, mask, c4300);  // states 0, 1
+    o.y = and_or(v >> 6, mask, c4300);   // states 3, 4
+    o.z = and_or(v >> 2, mask, c4300);   // states 5, 6
+    o.w = and_or(v >> 9, mask, c4300);   // state 2; the upper half is an unused k-slot (zero activation)
   } else {
     // two 8-bit codes of (L=4,N=3,S=2); shift list [4,2,0], mask 0xF (Table 1)
     const uint32_t d = dword_of(r.c[t], j >> 1);
@@ -241,7 +264,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
   if (row_ok) xrow = x + (a.sorted_rows ? (int64_t)a.sorted_rows[row_base + m] : (int64_t)(row_base + m)) * a.ldx;
   for (int f0 = tid; f0 < nfrag; f0 += nthreads * U) {
     uint4 v[U];
-    uint32_t h[U][6];
+    uint32_t h[U][8];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int f = min(f0 + u * nthreads, nfrag - 1);  // clamped: the request is unconditional
@@ -253,6 +276,15 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
       const uint16_t* xr = xrow + (int64_t)g * kGroup;
       if constexpr ((KIND & 1) == kNarrow) {
         v[u] = *reinterpret_cast<const uint4*>(xr + 16 * kq + 8 * t);
+      } else if constexpr ((KIND & kH16) != 0) {
+        // word 4t + kq covers weights 7 word .. 7 word + 6; word 9 carries weight 63 only
+        const int word = 4 * t + kq;
+#pragma unroll
+        for (int i = 0; i < 7; ++i) {
+          const int wi = 7 * word + h16_slot_weight(i);
+          h[u][i] = (word <= 9 && wi < kGroup) ? (uint32_t)xr[wi] : 0u;
+        }
+        h[u][7] = 0u;
       } else {
         // codes ja = 6kq+2t and ja+1 cover weights 3ja+{0,1,2} and 3ja+3+{0,1,2};
         // slots {a0,b0,a1,b1,a2,b2,-,-}; code 21 carries weight 63 only
@@ -284,6 +316,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
             o.x = h[u][0] | (h[u][1] << 16);
             o.y = h[u][2] | (h[u][3] << 16);
             o.z = h[u][4] | (h[u][5] << 16);
+            if constexpr ((KIND & kH16) != 0) o.w = h[u][6];
           }
         }
         lds_x[f] = o;
@@ -361,7 +394,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
     for (int t = 0; t < TR::T; ++t) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], dc.c4300, dc.mask[KIND & 1]);
+        const bf16x8 wf = decode_frag<KIND>(r[rt], j, t, al[rt], be[rt], dc.c4300, dc.mask[(KIND & kH16) ? 2 : (KIND & 1)]);
         if constexpr (MR <= 4) {
           // two 4x4x4 steps: k-slots 0..3 and 4..7 of the fragment
           const u32x4 wv = __builtin_bit_cast(u32x4, wf);
@@ -538,6 +571,18 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
       o.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
       o.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
       o.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
+    } else if constexpr ((KIND & kH16) != 0) {
+      const int word = 4 * t + kq;
+      uint32_t h[7];
+#pragma unroll
+      for (int i = 0; i < 7; ++i) {
+        const int wi = 7 * word + h16_slot_weight(i);
+        h[i] = (word <= 9 && wi < kGroup) ? (uint32_t)xg[wi] : 0u;
+      }
+      o.x = h[0] | (h[1] << 16);
+      o.y = h[2] | (h[3] << 16);
+      o.z = h[4] | (h[5] << 16);
+      o.w = h[6];
     } else {
       const int ja = 6 * kq + 2 * t;
       uint32_t h[6];
@@ -694,10 +739,12 @@ __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&c
                                    nthreads, dc);
 }
 
+// FM: formats present (1 narrow, 2 wide, 3 both, 4 the hybrid word in place of the wide kind).
 // SM: scale mode (0 fp16 group scales, 1 compressed scales)
 template <int MT, int MR, int RT, int FM, int SM>
 __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 1024)) ccq_skinny_kernel(const SkinnyArgs a) {
-  constexpr int KN = kNarrow | (SM << 1), KW = kWide | (SM << 1);
+  constexpr int KN = kNarrow | (SM << 1), KW = kWide | (SM << 1) | (FM == 4 ? kH16 : 0);
+  constexpr bool HAS_N = FM == 1 || FM == 3, HAS_W = FM >= 2;
   extern __shared__ __align__(16) unsigned char smem[];
   // Fetch the whole argument block now, in one batch of scalar loads: left to itself the compiler loads it
   // piecemeal behind the early branches, four dependent round trips (about 2.5 us) before the first request
@@ -740,7 +787,7 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
     scales_w[rt] = scales_n[rt] + (int64_t)a.tiles[kNarrow] * Traits<KN>::SCALE_HALFS;
     al[rt] = 0.f;
     be[rt] = 0.f;
-    if ((FM & 1) && active) {
+    if (HAS_N && active) {
       al[rt] = alpha[rtile * 16 + (lane & 15)];
       be[rt] = beta[rtile * 16 + (lane & 15)];
     }
@@ -752,8 +799,8 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
   const int frag_cap = a.frag_cap;
   float* lds_cneg = reinterpret_cast<float*>(smem + (size_t)frag_cap * 16);
   // the compiler must see these as register values, not literals, to select v_and_or_b32
-  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}, {0.f, 0.f}};
-  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]));
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
+  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+s"(dc.mask[2]));
   if constexpr (SM == 1) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -777,13 +824,13 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
       uint4* my_x = lds_x + (size_t)wave * (a.frag_cap + a.cneg_cap / 4);
       float* my_cneg = reinterpret_cast<float*>(my_x + a.frag_cap);
       const uint16_t* xr = a.x + (a.sorted_rows ? (int64_t)a.sorted_rows[off0 + m0] : (int64_t)(off0 + m0)) * a.ldx;
-      if constexpr ((FM & 1) != 0) run_kind_private<KN, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
-      if constexpr ((FM & 2) != 0) run_kind_private<KW, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
+      if constexpr (HAS_N) run_kind_private<KN, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
+      if constexpr (HAS_W) run_kind_private<KW, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, my_x, my_cneg, xr, split, wk, lane, dc);
     } else {
-      if constexpr ((FM & 1) != 0)
+      if constexpr (HAS_N)
         run_kind<KN, MT, MR, RT, FM == 3>(a, codes_n, scales_n, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
                                       nthreads, dc);
-      if constexpr ((FM & 2) != 0)
+      if constexpr (HAS_W)
         run_kind<KW, MT, MR, RT, FM == 3>(a, codes_w, scales_w, active, al, be, acc, lds_x, lds_cneg, a.x, off0 + m0, rows_valid, split, wk, lane, tid,
                                     nthreads, dc);
     }
@@ -951,7 +998,7 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
   uint16_t ssup_bits = 0;
   if constexpr (SM == 1) ssup_bits = a.scale_super[rtile * 16 + (lane & 15)];
   stage_private_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
-  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}, {0.f, 0.f}};
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
   float magic = 8388608.f;
   asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+v"(magic));
   dc.ssup[0] = (float)__builtin_bit_cast(_Float16, ssup_bits);
@@ -1016,7 +1063,7 @@ __global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args a
   uint16_t ssup_bits = 0;
   if constexpr (SM == 1) ssup_bits = a.scale_super[rtile * 16 + (lane & 15)];
   stage_private4_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
-  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu}, {0.f, 0.f}};
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
   float magic = 8388608.f;
   asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+v"(magic));
   dc.ssup[0] = (float)__builtin_bit_cast(_Float16, ssup_bits);
@@ -1132,6 +1179,9 @@ static SkinnyKernel pick_fm(int fm) {
   switch (fm) {
     case 1: return ccq_skinny_kernel<MT, MR, RT, 1, SM>;
     case 2: return ccq_skinny_kernel<MT, MR, RT, 2, SM>;
+    case 4:
+      if constexpr (SM == 0) return ccq_skinny_kernel<MT, MR, RT, 4, 0>;  // hybrid word: fp16 group scales only
+      else return nullptr;
     default: return ccq_skinny_kernel<MT, MR, RT, 3, SM>;
   }
 }
@@ -1167,7 +1217,7 @@ int launch_skinny(const SkinnyCall& c) {
   if (mt == 3) mt = 4;
   const int mr = (mt == 1 && rows == 1) ? 1 : 16;  // rows of the first activation tile that are staged
   const int mrt = mt == 1 ? mr : mt * 16;
-  const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
+  const int fm = L.h16 ? 4 : (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
   if ((mt >= 2 || mr == 1) && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
   if (d.RT == 2 && (mt == 4 || fm != 1)) return CCQ_ERR_BAD_PARAM;  // two row tiles per wavefront: narrow format, at most 32 held rows
   if (mt == 4 && d.WR * d.WK > 4) return CCQ_ERR_BAD_PARAM;            // 64 held rows: built for at most 256 threads

@@ -126,6 +126,32 @@ def test_pack_codes_is_the_documented_permutation():
     assert ps[0 * tile_halfs + (n_narrow // 4) * 64 + 9 * 8 + 7] == scales[9, g1]
 
 
+def test_hybrid_word_accounting_and_packing():
+    """Sec. 3.2 / 3.4: ten 16-bit words per 64 weights = 2.5 bpw; the device order is a permutation of the canonical bytes
+    (segment t = word // 4, lane = 16 (word % 4) + row, halfword = group within the k-tile of 8 groups)."""
+    K, N = 1024, 32
+    w = b.descriptor(K, N, b.H16)
+    i = b.pack_info(w, 64)
+    assert i.code_bpw == 2.5 and i.code_bytes == N * o.h16_row_bytes(K) and i.bytes_per_group[0] == i.bytes_per_group[1] == 20
+    assert i.scale_bytes == N * (K // 64) * 2 and i.row_tile_bytes == (K // 512) * 2560
+    assert i.total_bpw == 2.5 + 16 / 64
+    canon = np.arange(N * o.h16_row_bytes(K), dtype=np.uint32)
+    tagged = (canon * 2654435761 >> 7).astype(np.uint8)           # any byte pattern; positions are what is tested
+    dev = b.pack_codes(w, tagged)
+    assert sorted(dev.tolist()) == sorted(tagged.tolist())
+    rb = o.h16_row_bytes(K)
+    for (n, g, word, byte) in [(0, 0, 0, 0), (5, 3, 9, 1), (17, 8, 4, 0), (31, 15, 7, 1), (16, 9, 8, 0)]:
+        src = n * rb + g * 20 + word * 2 + byte
+        off = (n // 16) * i.row_tile_bytes + (g // 8) * 2560 + (word // 4) * 1024 + ((word % 4) * 16 + n % 16) * 16 + (g % 8) * 2 + byte
+        assert dev[off] == tagged[src], (n, g, word, byte)
+    info = b.ccq_info()
+    lib = b.load()
+    assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, b.H16, scale_mode=1)), 1, ctypes.byref(info)) == -3   # compressed scales: not built
+    assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K + 64, N, b.H16)), 1, ctypes.byref(info)) == -3            # whole k-tiles of 512 only
+    assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, [b.H16_HI, b.ccq_code(3, 4, 2, 0, 3.0)])), 1, ctypes.byref(info)) == -3  # one zp per word
+    assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, [b.H16_LO, b.H16_HI])), 1, ctypes.byref(info)) != 0   # halves in the wrong order
+
+
 def test_descriptor_validation():
     def status(fn):
         try:
