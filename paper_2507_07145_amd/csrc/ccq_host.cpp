@@ -105,7 +105,7 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     // set-up cost is amortised, and two row tiles when there are plenty of rows (narrow format only).
     d.RT = (units >= 1024 && L.tiles[kWide] == 0) ? 2 : 1;
     d.WR = 1;
-    d.WK = std::max(1, std::min(8, nt / 8));
+    d.WK = std::max(1, std::min(8, nt / (L.tiles[kNarrow] > 0 ? 8 : 4)));  // wide k-tiles are 2.75 times the bytes of narrow ones
     d.S = 1;
   } else {
     // two row tiles per wavefront only for the narrow format with at most 32 held rows (register budget)
@@ -130,7 +130,7 @@ enum DensePath { kPathGemv, kPathSkinny, kPathMid, kPathPrefill };
 static DensePath dense_path(const Layout& L, int M) {
   const bool narrow_only = L.tiles[kWide] == 0;
   if (M <= kGemvMaxM && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
-  if (M < kMidMinM || L.h16) return kPathSkinny;
+  if (M < kMidMinM) return kPathSkinny;
   if (narrow_only && M > 128) return kPathPrefill;            // 256-row tiles pay off
   return kPathMid;
 }

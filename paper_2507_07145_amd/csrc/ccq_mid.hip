@@ -12,6 +12,11 @@
 //     then d = (w_uint - zp) * s (Alg. 2 / Alg. 3, last line) as fma(128 + state, s, -(128 + zp) s),
 //     which is exact in fp32, so the stored value is the correctly rounded bf16 of the exact weight,
 //   - multiplies the two tiles with MFMA 32x32x16 bf16 (fp32 accumulators).
+// The hybrid 16-bit word of Sec. 3.2 (a (3,3,2) and a (3,4,2) code side by side, seven weights per
+// word, ten words per group) takes the place of the wide format when it is used: its weights are kept
+// in LDS word by word, eight bf16 slots per word (seven weights and one unused slot, 80 slots per
+// group), and the activation tile is scattered into the same slot order, so that a decoded word is one
+// 16-byte LDS write and a group is five MFMA k-steps instead of four.
 // The decode is the bound (about 4 vector instructions per weight, shared by 64 rows), so the
 // kernel is kept small enough (55 KiB of LDS, < 128 registers) for two workgroups per CU, whose
 // vector and matrix phases overlap.
@@ -51,7 +56,8 @@ struct MidArgs {
 
 constexpr int kMidBM = 64;
 constexpr int kMidBN = 128;
-constexpr int kMidRow = 64 + 8;  // bf16 elements per padded LDS row (144 bytes)
+constexpr int kMidRow = 64 + 8;     // bf16 elements per padded LDS row (144 bytes)
+constexpr int kMidRowH16 = 80 + 8;  // the same for the hybrid word: ten words of eight slots (176 bytes)
 constexpr int kMidRTW = 2;       // 16-row weight tiles per wavefront
 
 __device__ __forceinline__ uint32_t and_or_m(uint32_t a, uint32_t mask, uint32_t orv) { return (a & mask) | orv; }
@@ -64,17 +70,19 @@ __device__ __forceinline__ uint32_t pack_bf16_m(float lo, float hi) {
 
 __device__ __forceinline__ uint32_t dword_sel(const u32x4& v, int j) { return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w)); }
 
-// FM: formats present (1 narrow, 2 wide, 3 both; a group map exists only for 3).  SM: scale mode (0 fp16 group
+// FM: formats present (1 narrow, 2 wide, 3 both, 4 the hybrid word; a group map exists only for 3).  SM: scale mode (0 fp16 group
 // scales; 1 the compressed scales of Sec. 3.4: group scale = 4-bit field * per-row super scale, first line of
 // Alg. 2 / Alg. 3; the field of a narrow group comes from the packed scale array, that of a wide group from the
 // spare low nibble of the group's last code byte).
 template <int FM, int SM>
 __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
-  constexpr bool HAS_N = (FM & 1) != 0, HAS_W = (FM & 2) != 0, META = FM == 3;
+  constexpr bool HAS_N = FM == 1 || FM == 3, HAS_W = FM >= 2, META = FM == 3, H16 = FM == 4;
+  constexpr int ROW = H16 ? kMidRowH16 : kMidRow;
+  constexpr int WTILE = H16 ? kH16TileBytes : kWideTileBytes;
   extern __shared__ __align__(16) unsigned char smem[];
-  uint16_t* As = reinterpret_cast<uint16_t*>(smem);   // [2][kMidBM][kMidRow]
-  uint16_t* Bs = As + 2 * kMidBM * kMidRow;           // [2][kMidBN][kMidRow]
-  int32_t* lds_meta = reinterpret_cast<int32_t*>(Bs + 2 * kMidBN * kMidRow);  // original group of each step of this share (META only)
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);   // [2][kMidBM][ROW]
+  uint16_t* Bs = As + 2 * kMidBM * ROW;               // [2][kMidBN][ROW]
+  int32_t* lds_meta = reinterpret_cast<int32_t*>(Bs + 2 * kMidBN * ROW);  // original group of each step of this share (META only)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -128,7 +136,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   }
   const int64_t wide_code_off = (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
   const int64_t wide_scale_off = (int64_t)a.tiles[kNarrow] * kNarrowTileScaleHalfs;
-  uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u, mask_w = 0x000F0000u;
+  uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u, mask_w = H16 ? 0x00070000u : 0x000F0000u;
   float magic = 8388608.f;
   asm volatile("" : "+v"(c43), "+s"(mask_n), "+s"(mask_w), "+v"(magic));
 
@@ -150,12 +158,13 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
     kt = min(kt, a.tiles[kWide] - 1);
 #pragma unroll
     for (int i = 0; i < kMidRTW; ++i) {
-      const uint8_t* t = code_base[i] + wide_code_off + (int64_t)kt * kWideTileBytes + lane * 16;
+      const uint8_t* t = code_base[i] + wide_code_off + (int64_t)kt * WTILE + lane * 16;
       c[i][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
       c[i][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
-      // the third segment has entries for 48 lanes only; lanes 48..63 re-read lane 47's entry (what they
-      // decode from it lands in the padding columns of the LDS row)
-      c[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47 ? (lane - 47) * 16 : 0)));
+      // the third segment has entries for 48 lanes only (32 for the hybrid word); the lanes above re-read the
+      // last entry (what they decode from it lands in the padding columns of the LDS row, or is not written)
+      constexpr int last = H16 ? 31 : 47;
+      c[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > last ? (lane - last) * 16 : 0)));
       if constexpr (SM == 0) sc[i] = *reinterpret_cast<const uint4*>(scale_base[i] + wide_scale_off + (int64_t)kt * kWideTileScaleHalfs + nl * 8);
       else sc[i] = uint4{0u, 0u, 0u, 0u};  // the fields sit in the code stream
     }
@@ -169,7 +178,19 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   for (int i = 0; i < 2; ++i) {
     const int c = tid + 256 * i, row = c >> 3, col = c & 7;
     xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
-    a_lds_off[i] = row * kMidRow + col * 8;
+    a_lds_off[i] = row * ROW + (H16 ? 0 : col * 8);
+  }
+  // hybrid word: element e of a group sits in slot 8 (e / 7) + e % 7 (weight 63, alone in the last word, in
+  // slot 72); the unused slots are cleared once and never written again
+  int a_slot[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int e = (tid & 7) * 8 + j;
+    a_slot[j] = H16 ? (e == 63 ? 72 : 8 * (e / 7) + e % 7) : 0;
+  }
+  if constexpr (H16) {
+    for (int i = tid; i < 2 * kMidBM * ROW / 8; i += 256) reinterpret_cast<u32x4*>(As)[i] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
   }
   auto load_a = [&](u32x4 (&dst)[2], int s) {
     const int64_t off = (int64_t)group_of(s) * kGroup;
@@ -177,14 +198,26 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
     for (int i = 0; i < 2; ++i) dst[i] = *reinterpret_cast<const u32x4*>(xrow[i] + off);
   };
   auto store_a = [&](int buf, const u32x4 (&src)[2]) {
-    uint16_t* dst = As + buf * kMidBM * kMidRow;
+    uint16_t* dst = As + buf * kMidBM * ROW;
+    if constexpr (H16) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = src[i];
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t d = src[i][q];
+          dst[a_lds_off[i] + a_slot[2 * q]] = (uint16_t)(d & 0xFFFFu);
+          dst[a_lds_off[i] + a_slot[2 * q + 1]] = (uint16_t)(d >> 16);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = src[i];
+    }
   };
 
   // decode group j of the held narrow k-tile: 16 weights per lane (k = 16 kq .. 16 kq + 15)
   auto decode_narrow = [&](int buf, int j) {
-    uint16_t* dst = Bs + buf * kMidBN * kMidRow;
+    uint16_t* dst = Bs + buf * kMidBN * ROW;
 #pragma unroll
     for (int i = 0; i < kMidRTW; ++i) {
       const uint32_t d = dword_sel(cn[i], j);
@@ -209,7 +242,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
         o[2 * b] = pack_bf16_m(w0, w1);
         o[2 * b + 1] = pack_bf16_m(w2, w3);
       }
-      uint16_t* p = dst + ((wave * kMidRTW + i) * 16 + nl) * kMidRow + kq * 16;
+      uint16_t* p = dst + ((wave * kMidRTW + i) * 16 + nl) * ROW + kq * 16;
       *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
       *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
     }
@@ -218,7 +251,34 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   // (k = 18 kq .. 18 kq + 17).  Quarter 3 owns bytes 18..21 only (weights 54..63); what it writes beyond
   // column 63 falls into the padding of its own LDS row.
   auto decode_wide = [&](int buf, int j) {
-    uint16_t* dst = Bs + buf * kMidBN * kMidRow;
+    uint16_t* dst = Bs + buf * kMidBN * ROW;
+    if constexpr (H16) {
+      // words kq, 4 + kq and (kq < 2) 8 + kq of group j: seven 3-bit states at the shifts [13,11,9,6,4,2,0]
+      // (Table 1), each moved to bit 16, the lowest integer bit of fp32 128.0
+#pragma unroll
+      for (int i = 0; i < kMidRTW; ++i) {
+        const uint32_t sd = dword_sel(u32x4{sw[i].x, sw[i].y, sw[i].z, sw[i].w}, j >> 1);
+        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        const float c0 = -(128.f + a.zp[kWide]) * s;
+        uint16_t* row = dst + ((wave * kMidRTW + i) * 16 + nl) * ROW;
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+          const uint32_t dd = dword_sel(cw[i][t], j >> 1);
+          const uint32_t w = (j & 1) ? (dd >> 16) : (dd & 0xFFFFu);
+          const float f0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 3, mask_w, c43)), s, c0);
+          const float f1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 5, mask_w, c43)), s, c0);
+          const float f2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 7, mask_w, c43)), s, c0);
+          const float f3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 10, mask_w, c43)), s, c0);
+          const float f4 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 12, mask_w, c43)), s, c0);
+          const float f5 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 14, mask_w, c43)), s, c0);
+          const float f6 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 16, mask_w, c43)), s, c0);
+          // the eighth slot of a word meets a zero activation; any finite value will do
+          const u32x4 o = {pack_bf16_m(f0, f1), pack_bf16_m(f2, f3), pack_bf16_m(f4, f5), pack_bf16_m(f6, f6)};
+          if (t < 2 || kq < 2) *reinterpret_cast<u32x4*>(row + (4 * t + kq) * 8) = o;
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < kMidRTW; ++i) {
       float s;
@@ -247,7 +307,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
           w[6 * t + 3 * b + 2] = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(c << 16, mask_w, c43)), s, c0);
         }
       }
-      uint32_t* p = reinterpret_cast<uint32_t*>(dst + ((wave * kMidRTW + i) * 16 + nl) * kMidRow + kq * 18);
+      uint32_t* p = reinterpret_cast<uint32_t*>(dst + ((wave * kMidRTW + i) * 16 + nl) * ROW + kq * 18);
 #pragma unroll
       for (int q = 0; q < 9; ++q) p[q] = pack_bf16_m(w[2 * q], w[2 * q + 1]);
     }
@@ -259,17 +319,17 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-  const int a_frag_off = (lane & 31) * kMidRow + (lane >> 5) * 8;
-  const int b_frag_off = (wave * 32 + (lane & 31)) * kMidRow + (lane >> 5) * 8;
+  const int a_frag_off = (lane & 31) * ROW + (lane >> 5) * 8;
+  const int b_frag_off = (wave * 32 + (lane & 31)) * ROW + (lane >> 5) * 8;
   auto multiply = [&](int buf) {
-    const uint16_t* Ab = As + buf * kMidBM * kMidRow + a_frag_off;
-    const uint16_t* Bb = Bs + buf * kMidBN * kMidRow + b_frag_off;
+    const uint16_t* Ab = As + buf * kMidBM * ROW + a_frag_off;
+    const uint16_t* Bb = Bs + buf * kMidBN * ROW + b_frag_off;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < (H16 ? 5 : 4); ++kk) {  // 16 k-slots per MFMA: 64 weights, or ten words of eight slots
       const bf16x8 bfr = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + kk * 16));
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const bf16x8 af = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * kMidRow + kk * 16));
+        const bf16x8 af = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * ROW + kk * 16));
         acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[i], 0, 0, 0);
       }
     }
@@ -381,7 +441,6 @@ int mid_splits(const Layout& L, int M) {
 
 int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
                void* stream) {
-  if (L.h16) return CCQ_ERR_UNSUPPORTED;
   MidArgs a;
   a.codes = static_cast<const uint8_t*>(w->codes);
   a.scales = static_cast<const uint16_t*>(w->scales);
@@ -409,14 +468,15 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
     a.zp[k] = L.zp[k];
   }
   const int n_blocks = (L.N + kMidBN - 1) / kMidBN;
-  const int fm = (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
+  const int fm = L.h16 ? 4 : (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
   const int max_steps = ((L.tiles[kNarrow] + S - 1) / S) * kNarrowGroupsPerTile + ((L.tiles[kWide] + S - 1) / S) * kWideGroupsPerTile;
-  const size_t lds = (size_t)2 * (kMidBM + kMidBN) * kMidRow * 2 + (fm == 3 ? (size_t)max_steps * 4 : 0);
-  if (lds > 64 * 1024) return CCQ_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)2 * (kMidBM + kMidBN) * (fm == 4 ? kMidRowH16 : kMidRow) * 2 + (fm == 3 ? (size_t)max_steps * 4 : 0);
+  if (lds > (fm == 4 ? 72 : 64) * 1024) return CCQ_ERR_UNSUPPORTED;
   typedef void (*MidKernel)(const MidArgs);
-  const MidKernel table[2][3] = {{ccq_mid_kernel<1, 0>, ccq_mid_kernel<2, 0>, ccq_mid_kernel<3, 0>},
-                                 {ccq_mid_kernel<1, 1>, ccq_mid_kernel<2, 1>, ccq_mid_kernel<3, 1>}};
+  const MidKernel table[2][4] = {{ccq_mid_kernel<1, 0>, ccq_mid_kernel<2, 0>, ccq_mid_kernel<3, 0>, ccq_mid_kernel<4, 0>},
+                                 {ccq_mid_kernel<1, 1>, ccq_mid_kernel<2, 1>, ccq_mid_kernel<3, 1>, nullptr}};
   const MidKernel kern = table[L.scale_mode][fm - 1];
+  if (!kern) return CCQ_ERR_UNSUPPORTED;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return CCQ_ERR_HIP;

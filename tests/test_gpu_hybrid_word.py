@@ -76,6 +76,19 @@ def test_gemm_rows(M):
     assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"hybrid word M={M}", abs_sum=abs_sum)
 
 
+@pytest.mark.parametrize("K,N,M", [(4096, 144, 70), (2048, 16, 65), (8192, 272, 40), (512, 400, 257)])
+def test_tiled_kernel_shapes(K, N, M):
+    """More than 16 rows go through the 64-row LDS-tiled kernel: K cut into shares, ragged last blocks in M and N."""
+    c = random_h16(K, N, 26, stream0=N)
+    w = c.device_weight()
+    x = synth.activations_bf16(M, K, synth.rng(26, 100 + M))
+    abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(c.W()))
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"K={K} N={N} M={M}", abs_sum=abs_sum)
+    ks = synth.rng(26, 200 + M).integers(0, K, M)
+    ks[:8] = [0, 6, 7, 62, 63, 64, K - 1, K - 2]
+    _check_decode(c, w, ks)
+
+
 @pytest.mark.parametrize("launch", [(1, 1, 1, 1), (1, 4, 1, 1), (1, 1, 4, 1), (1, 2, 2, 2), (1, 1, 1, 4), (1, 3, 2, 1)])
 @pytest.mark.parametrize("M", [1, 4, 16, 40])
 def test_launch_shapes(launch, M):
