@@ -719,3 +719,88 @@ int cco_h16_quantize(int K, int Nrows, int g, double zp, const float *W, int met
   }
   return 0;
 }
+
+/* ---------- Sec. 3.4 on the hybrid word: the 13 spare bits hold the scale --- */
+
+/* Alg. 2, first lines, with Table 1's scale mask 0x1FFF: s_uint is the group's
+ * last word, s = (s_uint & 0x1FFF) * s_super[n].  Needs a full last word, i.e.
+ * g = 64 (g mod 7 = 1: the last word carries one weight and 13 spare bits). */
+int cco_h16_expand_scales(int K, int Nrows, int g, const uint8_t *codes, const uint16_t *s_super_fp16, double *scales) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0 || g % 7 != 1) return -2;
+  int G = K / g, wpg = cco_h16_words_per_group(g);
+  for (int n = 0; n < Nrows; ++n) {
+    double ssup = cco_fp16_to_double(s_super_fp16[n]);
+    for (int gi = 0; gi < G; ++gi) {
+      uint32_t s_uint = load_code(codes + (((int64_t)n * G + gi) * wpg + (wpg - 1)) * 2, 2);
+      scales[(int64_t)n * G + gi] = (double)(s_uint & 0x1FFFu) * ssup;
+    }
+  }
+  return 0;
+}
+
+int cco_h16_decode_cs(int K, int Nrows, int g, double zp, const uint8_t *codes, const uint16_t *s_super_fp16, double *W) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0 || g % 7 != 1) return -2;
+  int G = K / g, wpg = cco_h16_words_per_group(g);
+  double *sc = (double *)malloc(sizeof(double) * (size_t)Nrows * (size_t)G);
+  int rc = cco_h16_expand_scales(K, Nrows, g, codes, s_super_fp16, sc);
+  if (rc == 0) {
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < Nrows; ++n)
+      for (int gi = 0; gi < G; ++gi)
+        for (int idx = 0; idx < g; ++idx) {
+          uint32_t st[7];
+          cco_h16_states(load_code(codes + (((int64_t)n * G + gi) * wpg + idx / 7) * 2, 2), st);
+          W[(int64_t)n * K + (int64_t)gi * g + idx] = ((double)st[idx % 7] - zp) * sc[(int64_t)n * G + gi];
+        }
+  }
+  free(sc);
+  return rc;
+}
+
+/* Encoder side: channel-wise super scale = largest group scale of the row / 8191
+ * (fp16), field = nearest multiple clipped to 1..8191 (0 for an all-zero group),
+ * codes searched again with the scale the decoder will use, field written into
+ * the low 13 bits of the group's last word. */
+int cco_h16_compress_scales(int K, int Nrows, int g, double zp, const float *W, int method, uint8_t *codes,
+                            const uint16_t *scales_fp16, uint16_t *s_super_fp16) {
+  if (K <= 0 || Nrows <= 0 || g <= 0 || K % g != 0 || g % 7 != 1) return -2;
+  int G = K / g, wpg = cco_h16_words_per_group(g);
+#pragma omp parallel
+  {
+    double *w = (double *)malloc(sizeof(double) * (size_t)(wpg * 7));
+#pragma omp for schedule(dynamic, 4)
+    for (int n = 0; n < Nrows; ++n) {
+      double smax = 0.0;
+      for (int gi = 0; gi < G; ++gi) {
+        double s = cco_fp16_to_double(scales_fp16[(int64_t)n * G + gi]);
+        if (s > smax) smax = s;
+      }
+      uint16_t sup_bits = cco_double_to_fp16(smax / 8191.0);
+      double ssup = cco_fp16_to_double(sup_bits);
+      s_super_fp16[n] = sup_bits;
+      for (int gi = 0; gi < G; ++gi) {
+        uint8_t *p = codes + ((int64_t)n * G + gi) * wpg * 2;
+        double s = cco_fp16_to_double(scales_fp16[(int64_t)n * G + gi]);
+        int k = 0;
+        if (ssup > 0.0 && s > 0.0) {
+          double kr = nearbyint(s / ssup);
+          k = kr < 1.0 ? 1 : (kr > 8191.0 ? 8191 : (int)kr);
+        }
+        double se = (double)k * ssup;
+        for (int i = 0; i < wpg * 7; ++i) w[i] = i < g ? (double)W[(int64_t)n * K + (int64_t)gi * g + i] : 0.0;
+        for (int j = 0; j < wpg; ++j) {
+          uint32_t word = load_code(p + 2 * j, 2);
+          if (se > 0.0) {
+            uint32_t a = method == 0 ? cco_search_brute(w + 7 * j, se, zp, 3, 3, 2) : cco_search_viterbi(w + 7 * j, se, zp, 3, 3, 2);
+            uint32_t b = method == 0 ? cco_search_brute(w + 7 * j + 3, se, zp, 3, 4, 2) : cco_search_viterbi(w + 7 * j + 3, se, zp, 3, 4, 2);
+            word = (a << 9) | b;
+          }
+          if (j == wpg - 1) word = (word & 0xE000u) | (uint32_t)k;
+          store_code(p + 2 * j, 2, word);
+        }
+      }
+    }
+    free(w);
+  }
+  return 0;
+}

@@ -123,6 +123,12 @@ def lib():
         L.cco_h16_decode.argtypes = [I, I, I, ctypes.c_double, u8p, u16p, f64p]
         L.cco_h16_quantize.restype = I
         L.cco_h16_quantize.argtypes = [I, I, I, ctypes.c_double, f32p, I, u8p, u16p]
+        L.cco_h16_expand_scales.restype = I
+        L.cco_h16_expand_scales.argtypes = [I, I, I, u8p, u16p, f64p]
+        L.cco_h16_decode_cs.restype = I
+        L.cco_h16_decode_cs.argtypes = [I, I, I, ctypes.c_double, u8p, u16p, f64p]
+        L.cco_h16_compress_scales.restype = I
+        L.cco_h16_compress_scales.argtypes = [I, I, I, ctypes.c_double, f32p, I, u8p, u16p, u16p]
         L.cco_matmul.restype = None
         L.cco_matmul.argtypes = [I, I, I, u16p, ctypes.c_int64, f64p, f64p]
         L.cco_num_threads.restype = I
@@ -328,6 +334,42 @@ def h16_quantize(W: np.ndarray, method: str = "viterbi", zp: float = H16_ZP, g: 
     if rc != 0:
         raise ValueError(f"cco_h16_quantize failed with {rc}")
     return codes, scales
+
+
+def h16_expand_scales(K, N, codes, s_super_fp16, g: int = 64) -> np.ndarray:
+    """Alg. 2, first lines, scale mask 0x1FFF (Table 1): group scales fp64 [N][K/g] from the last word of every group."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    ssup = np.ascontiguousarray(s_super_fp16, dtype=np.uint16)
+    out = np.empty((N, K // g), dtype=np.float64)
+    rc = lib().cco_h16_expand_scales(K, N, g, _p(codes, ctypes.c_uint8), _p(ssup, ctypes.c_uint16), _p(out, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"cco_h16_expand_scales failed with {rc}")
+    return out
+
+
+def h16_decode_cs(K, N, codes, s_super_fp16, zp: float = H16_ZP, g: int = 64) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    ssup = np.ascontiguousarray(s_super_fp16, dtype=np.uint16)
+    assert codes.size == N * h16_row_bytes(K, g) and ssup.size == N
+    W = np.empty((N, K), dtype=np.float64)
+    rc = lib().cco_h16_decode_cs(K, N, g, float(zp), _p(codes, ctypes.c_uint8), _p(ssup, ctypes.c_uint16), _p(W, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"cco_h16_decode_cs failed with {rc}")
+    return W
+
+
+def h16_compress_scales(W, codes, scales_fp16, method: str = "viterbi", zp: float = H16_ZP, g: int = 64):
+    """Encoder side of Sec. 3.4 on the hybrid word: returns (codes with the 13-bit fields in place, s_super fp16 bits [N])."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    N, K = W.shape
+    codes = np.array(codes, dtype=np.uint8, copy=True).reshape(N, -1)
+    scales = np.ascontiguousarray(scales_fp16, dtype=np.uint16)
+    ssup = np.zeros(N, dtype=np.uint16)
+    rc = lib().cco_h16_compress_scales(K, N, g, float(zp), _p(W, ctypes.c_float), 0 if method == "brute" else 1, _p(codes, ctypes.c_uint8),
+                                       _p(scales, ctypes.c_uint16), _p(ssup, ctypes.c_uint16))
+    if rc != 0:
+        raise ValueError(f"cco_h16_compress_scales failed with {rc}")
+    return codes, ssup
 
 
 def matmul(x_bf16: np.ndarray, W: np.ndarray) -> np.ndarray:

@@ -77,3 +77,72 @@ def test_quantize_round_trip_and_search():
     W[2, 64:128] = 0
     c2, s2 = o.h16_quantize(W)
     assert np.all(o.h16_decode(K, N, c2, s2)[2, 64:128] == 0)
+
+
+# ---------------------------------------------------------------- Sec. 3.4 on the hybrid word
+
+
+def _fp16(x: float) -> int:
+    return int(np.float16(x).view(np.uint16))
+
+
+def test_scale_field_by_hand():
+    """Alg. 2: s = (last word & 0x1FFF) * s_super; Table 1 gives the mask.  Last word 0xDABC: weight 63 has state 6,
+    the field is 0x1ABC = 6844."""
+    words = np.zeros(10, dtype=np.uint16)
+    words[0] = 0x8000                                     # first weight: state 4 -> value 0; the others state 0 -> -4 s
+    words[9] = 0xDABC
+    codes = words.view(np.uint8).reshape(1, 20)
+    ssup = np.array([_fp16(2.0 ** -10)], dtype=np.uint16)
+    sc = o.h16_expand_scales(64, 1, codes, ssup)
+    assert sc[0, 0] == 6844 * 2.0 ** -10
+    W = o.h16_decode_cs(64, 1, codes, ssup)
+    assert W[0, 0] == 0.0 and W[0, 1] == -4 * 6844 * 2.0 ** -10 and W[0, 63] == (6 - 4) * 6844 * 2.0 ** -10
+    # the field does not leak into weight 63 and the weight does not leak into the field
+    words[9] = 0xC000 | 0x1ABC
+    assert o.h16_expand_scales(64, 1, words.view(np.uint8).reshape(1, 20), ssup)[0, 0] == sc[0, 0]
+    words[9] = 0xC000 | 0x1001
+    assert o.h16_decode_cs(64, 1, words.view(np.uint8).reshape(1, 20), ssup)[0, 63] == (6 - 4) * 0x1001 * 2.0 ** -10
+
+
+def test_power_of_two_super_scale_reduces_to_fp16_scales():
+    """Fields below 2^11 times s_super = 2^-14 are fp16 numbers: the compressed-scale decoder must then agree bit for bit
+    with the fp16-scale decoder (pinned above) fed those numbers."""
+    rng = synth.rng(1, 810)
+    K, N = 512, 12
+    codes = synth.random_codes(N, o.h16_row_bytes(K), rng).reshape(N, K // 64, 10, 2)
+    codes[:, :, 9, 1] &= 0xE7                              # clear field bits 11 and 12: fields < 2048
+    codes = codes.reshape(N, -1)
+    ssup = np.full(N, _fp16(2.0 ** -14), dtype=np.uint16)
+    sc = o.h16_expand_scales(K, N, codes, ssup)
+    assert sc.max() < 2048 * 2.0 ** -14 and np.array_equal(sc.astype(np.float16).astype(np.float64), sc)
+    W1 = o.h16_decode_cs(K, N, codes, ssup)
+    W0 = o.h16_decode(K, N, codes, sc.astype(np.float16).view(np.uint16))
+    assert np.array_equal(W1, W0)
+
+
+def test_encoder_side_of_scale_compression():
+    rng = synth.rng(1, 820)
+    N, K = 8, 256
+    W = synth.weights_normal(N, K, rng)
+    W[5] = 0.0
+    codes, scales = o.h16_quantize(W)
+    c2, ssup = o.h16_compress_scales(W, codes, scales)
+    s16, sup = o.fp16_bits_to_f64(scales), o.fp16_bits_to_f64(ssup)
+    assert np.array_equal(ssup, (s16.max(axis=1) / 8191.0).astype(np.float16).view(np.uint16))
+    fields = c2.view(np.uint16).reshape(N, K // 64, 10)[:, :, 9] & 0x1FFF
+    nz = sup > 0
+    assert np.array_equal(fields[nz], np.clip(np.rint(s16[nz] / sup[nz][:, None]), 1, 8191).astype(np.uint16))
+    assert np.all(fields[~nz] == 0) and fields.max() >= 8190
+    W_new = o.h16_decode_cs(K, N, c2, ssup)
+    assert np.all(W_new[5] == 0)
+    # 13-bit scales cost next to nothing against fp16 scales
+    W_fp16 = o.h16_decode(K, N, codes, scales)
+    assert np.linalg.norm(W_new - W) <= 1.001 * np.linalg.norm(W_fp16 - W)
+    # searching again with the stored scale is never worse than keeping the old words with it
+    keep = codes.view(np.uint16).reshape(N, K // 64, 10).copy()
+    keep[:, :, 9] = (keep[:, :, 9] & 0xE000) | fields
+    W_keep = o.h16_decode_cs(K, N, keep.view(np.uint8).reshape(N, -1), ssup)
+    e_new = ((W_new - W) ** 2).reshape(N, K // 64, 64).sum(axis=2)
+    e_keep = ((W_keep - W) ** 2).reshape(N, K // 64, 64).sum(axis=2)
+    assert np.all(e_new <= e_keep * (1 + 1e-12) + 1e-30)
