@@ -21,7 +21,10 @@
  *           group is 10 words (20 bytes, 2.5 bpw), the last of which carries
  *           weight 63 in its top state and 13 unused bits.  Selected by
  *           n_formats = 2, fmt[0] = (3,3,2), fmt[1] = (3,4,2), both with the
- *           same zp and code_cluster = 0, group_fmt = NULL; fp16 scales only.
+ *           same zp and code_cluster = 0, group_fmt = NULL.  With scale_mode 1
+ *           the 13 unused bits hold the scale field (scale mask 0x1FFF of
+ *           Table 1; Alg. 2: s = (last word & 0x1FFF) * scale_super[n]) and
+ *           `scales` is not used.
  * A weight matrix uses the narrow format, the wide format, a per-group mix of
  * those two (group_fmt), all rows sharing the same map, or the hybrid word.
  * Group size is 64 along K and scales are fp16, one per (row, group), unless
@@ -85,14 +88,15 @@ typedef struct {
                                scale_mode 1: the packed 4-bit scale fields s_q of the narrow-format
                                groups in device order (ccq_pack_scales4); may be NULL when there are
                                no narrow-format groups (a wide-format group carries its field in the
-                               spare low nibble of its last code byte, Sec. 3.4)          */
+                               spare low nibble of its last code byte, a hybrid-word group in the low
+                               13 bits of its last word, Sec. 3.4)                        */
   const float *code_alpha;  /* DEVICE, fp32[N]: Code Cluster scale s_code, >= 0        */
   const float *code_beta;   /* DEVICE, fp32[N]: Code Cluster zero-point zp_code, an
                                integer value with 255*alpha + beta < 2^15 (the
                                kernels rely on it; device data is not checked)         */
   const void *meta;         /* DEVICE, group map in device order (ccq_pack_meta); may be NULL when group_fmt is NULL */
   int32_t scale_mode;       /* 0 = fp16 group scales; 1 = compressed scales of Sec. 3.4: group scale =
-                               4-bit field * scale_super[n] (first line of Alg. 2 / Alg. 3).  Mode 1 is
+                               4-bit (hybrid word: 13-bit) field * scale_super[n] (first line of Alg. 2 / Alg. 3).  Mode 1 is
                                built for ccq_gemm at any M with the launch shape chosen by the library
                                and for ccq_grouped_gemm; launch shapes that hold more than 16 rows in the
                                skinny kernel return CCQ_ERR_UNSUPPORTED                               */

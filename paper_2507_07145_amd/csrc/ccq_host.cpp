@@ -31,11 +31,10 @@ int make_layout(const ccq_weight* w, Layout* out) {
   L.N = w->N;
   L.G = w->K / kGroup;
   if (is_h16(w)) {
-    // one zero-point for the seven states of a word; fp16 group scales only
+    // one zero-point for the seven states of a word
     const float zp = w->fmt[0].zp;
     if (w->fmt[1].zp != zp) return CCQ_ERR_UNSUPPORTED;
     if (!(zp * 2.0f == std::floor(zp * 2.0f)) || zp < 0.f || zp > 64.f) return CCQ_ERR_BAD_PARAM;
-    if (w->scale_mode != 0) return CCQ_ERR_UNSUPPORTED;
     if (L.G % kWideGroupsPerTile != 0 || w->N % kRowsPerTile != 0) return CCQ_ERR_UNSUPPORTED;
     L.h16 = true;
     L.kind_of_fmt[0] = L.kind_of_fmt[1] = kWide;
@@ -43,7 +42,7 @@ int make_layout(const ccq_weight* w, Layout* out) {
     L.groups[kWide] = L.G;
     L.tiles[kWide] = L.G / kWideGroupsPerTile;
     L.row_tile_bytes = (int64_t)L.tiles[kWide] * kH16TileBytes;
-    L.row_tile_scale_halfs = (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;
+    L.row_tile_scale_halfs = L.scale_mode == 1 ? 0 : (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;  // mode 1: the fields sit in the words
     L.row_tiles = w->N / kRowsPerTile;
     if (L.row_tile_bytes * (int64_t)L.row_tiles >= (int64_t)1 << 40) return CCQ_ERR_BAD_PARAM;
     *out = L;

@@ -257,21 +257,33 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
       // (Table 1), each moved to bit 16, the lowest integer bit of fp32 128.0
 #pragma unroll
       for (int i = 0; i < kMidRTW; ++i) {
-        const uint32_t sd = dword_sel(u32x4{sw[i].x, sw[i].y, sw[i].z, sw[i].w}, j >> 1);
-        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        float s;
+        if constexpr (SM == 0) {
+          const uint32_t sd = dword_sel(u32x4{sw[i].x, sw[i].y, sw[i].z, sw[i].w}, j >> 1);
+          s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else {
+          // Alg. 2 with the scale mask 0x1FFF of Table 1: the low 13 bits of the group's last word (word 9), which
+          // quarter 1 of the row holds in segment 2, halfword j
+          const uint32_t q1 = (uint32_t)__builtin_amdgcn_ds_bpermute((16 + nl) * 4, (int)dword_sel(cw[i][2], j >> 1));
+          s = (float)((q1 >> (16 * (j & 1))) & 0x1FFFu) * ssup[i];  // exact: 13-bit integer times 11-bit significand
+        }
         const float c0 = -(128.f + a.zp[kWide]) * s;
+        const float zoff = 128.f + a.zp[kWide];
         uint16_t* row = dst + ((wave * kMidRTW + i) * 16 + nl) * ROW;
 #pragma unroll
         for (int t = 0; t < 3; ++t) {
           const uint32_t dd = dword_sel(cw[i][t], j >> 1);
           const uint32_t w = (j & 1) ? (dd >> 16) : (dd & 0xFFFFu);
-          const float f0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 3, mask_w, c43)), s, c0);
-          const float f1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 5, mask_w, c43)), s, c0);
-          const float f2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 7, mask_w, c43)), s, c0);
-          const float f3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 10, mask_w, c43)), s, c0);
-          const float f4 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 12, mask_w, c43)), s, c0);
-          const float f5 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 14, mask_w, c43)), s, c0);
-          const float f6 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(w << 16, mask_w, c43)), s, c0);
+          // With fp16 group scales (128 + zp) s is exact and one fused multiply-add gives the exactly rounded
+          // weight.  A 13-bit field times an 11-bit super scale fills all 24 bits of s, so there the offset is
+          // taken off first (exact) and the product (state - zp) s is rounded once to fp32.
+          auto value = [&](uint32_t shifted) -> float {
+            const float st = __builtin_bit_cast(float, and_or_m(shifted, mask_w, c43));  // 128 + state
+            if constexpr (SM == 0) return __builtin_fmaf(st, s, c0);
+            else return (st - zoff) * s;
+          };
+          const float f0 = value(w << 3), f1 = value(w << 5), f2 = value(w << 7), f3 = value(w << 10);
+          const float f4 = value(w << 12), f5 = value(w << 14), f6 = value(w << 16);
           // the eighth slot of a word meets a zero activation; any finite value will do
           const u32x4 o = {pack_bf16_m(f0, f1), pack_bf16_m(f2, f3), pack_bf16_m(f4, f5), pack_bf16_m(f6, f6)};
           if (t < 2 || kq < 2) *reinterpret_cast<u32x4*>(row + (4 * t + kq) * 8) = o;
@@ -474,7 +486,7 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   if (lds > (fm == 4 ? 72 : 64) * 1024) return CCQ_ERR_UNSUPPORTED;
   typedef void (*MidKernel)(const MidArgs);
   const MidKernel table[2][4] = {{ccq_mid_kernel<1, 0>, ccq_mid_kernel<2, 0>, ccq_mid_kernel<3, 0>, ccq_mid_kernel<4, 0>},
-                                 {ccq_mid_kernel<1, 1>, ccq_mid_kernel<2, 1>, ccq_mid_kernel<3, 1>, nullptr}};
+                                 {ccq_mid_kernel<1, 1>, ccq_mid_kernel<2, 1>, ccq_mid_kernel<3, 1>, ccq_mid_kernel<4, 1>}};
   const MidKernel kern = table[L.scale_mode][fm - 1];
   if (!kern) return CCQ_ERR_UNSUPPORTED;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {

@@ -99,6 +99,9 @@ template <> struct Traits<kWide | kScale4> : Traits<kWide> {
 template <> struct Traits<kWide | kH16> : Traits<kWide> {
   static constexpr int TILE_BYTES = kH16TileBytes;
 };
+template <> struct Traits<kWide | kH16 | kScale4> : Traits<kWide | kH16> {
+  static constexpr int SCALE_HALFS = 0;
+};
 // activation index inside a group for k-slot i (0..6) of a hybrid word: the decode pairs the states at
 // shifts (13,11), (6,4), (2,0) and leaves the one at shift 9 alone, i.e. weights {0,1}, {3,4}, {5,6}, {2}
 __device__ __forceinline__ int h16_slot_weight(int i) { return i < 2 ? i : (i < 6 ? i + 1 : 2); }
@@ -167,6 +170,14 @@ __device__ __forceinline__ void tile_scale_fields(uint32_t (&f)[4], const TileRe
     f[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[1].y);
     f[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[1].z);
     f[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[1].w);
+  } else if constexpr (KIND == (kWide | kH16 | kScale4)) {
+    // hybrid word: the field of group j is the low 13 bits of the group's last word (word 9, scale mask
+    // 0x1FFF of Table 1), which quarter 1 of the row holds in segment 2, halfword j
+    const int src = (16 + (lane & 15)) * 4;
+    f[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[2].x);
+    f[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[2].y);
+    f[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[2].z);
+    f[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)r.c[2].w);
   }
 }
 
@@ -218,8 +229,8 @@ __device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, in
   return __builtin_bit_cast(bf16x8, o);
 }
 
-// Scale of group j of the tile.  fp16 group scales, or (Alg. 2 / Alg. 3, first line) the 4-bit field times the
-// row's super scale: exact in fp32 (4-bit integer times 11-bit significand).
+// Scale of group j of the tile.  fp16 group scales, or (Alg. 2 / Alg. 3, first line) the 4-bit field (13-bit for
+// the hybrid word) times the row's super scale: exact in fp32 (at most 13-bit integer times 11-bit significand).
 template <int KIND>
 __device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, const uint32_t (&fields)[4], float ssup, int j) {
   if constexpr ((KIND & kScale4) == 0) {
@@ -228,6 +239,8 @@ __device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, const uint
     return (float)__builtin_bit_cast(_Float16, h);
   } else if constexpr ((KIND & 1) == kNarrow) {
     return (float)((r.s[0] >> (4 * j)) & 0xFu) * ssup;
+  } else if constexpr ((KIND & kH16) != 0) {
+    return (float)((fields[j >> 1] >> (16 * (j & 1))) & 0x1FFFu) * ssup;
   } else {
     return (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu) * ssup;
   }
@@ -1179,9 +1192,7 @@ static SkinnyKernel pick_fm(int fm) {
   switch (fm) {
     case 1: return ccq_skinny_kernel<MT, MR, RT, 1, SM>;
     case 2: return ccq_skinny_kernel<MT, MR, RT, 2, SM>;
-    case 4:
-      if constexpr (SM == 0) return ccq_skinny_kernel<MT, MR, RT, 4, 0>;  // hybrid word: fp16 group scales only
-      else return nullptr;
+    case 4: return ccq_skinny_kernel<MT, MR, RT, 4, SM>;
     default: return ccq_skinny_kernel<MT, MR, RT, 3, SM>;
   }
 }

@@ -47,10 +47,16 @@ def _gemm_bits(w, x_bits, **kw):
     return b.bf16_bits(y)
 
 
-def _check_decode(c, w, ks, **kw):
+def _check_decode(c, w, ks, fp32_first=False, **kw):
     ks = list(ks)
     got = _gemm_bits(w, synth.one_hot_bf16(ks, c.K), **kw)
-    want = o.to_bf16_bits(c.W()[:, ks].T)
+    want = c.W()[:, ks].T
+    if fp32_first:
+        # a 13-bit scale field times an 11-bit super scale times a 3-bit state difference has up to 27 significant
+        # bits: the kernels hold that product in fp32 (one rounding) before the bf16 output rounding, and so does
+        # the expected value here
+        want = want.astype(np.float32).astype(np.float64)
+    want = o.to_bf16_bits(want)
     assert np.array_equal(canon_zero(got), canon_zero(want)), f"decoded weights differ at columns {ks[:8]}..."
 
 
@@ -122,6 +128,68 @@ def test_grouped():
     x = synth.activations_bf16(T, K, synth.rng(25, 99))
     offs = np.array([0, 5, 5, 14, 20], dtype=np.int32)
     rows = synth.rng(25, 98).integers(0, T, 20).astype(np.int32)
+    y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
+    torch.cuda.synchronize()
+    got = b.bf16_bits(y)
+    for e in range(E):
+        lo, hi = offs[e], offs[e + 1]
+        if hi > lo:
+            assert_gemm_close(got[lo:hi], o.matmul(x[rows[lo:hi]], cases[e].W()), f"expert {e}")
+
+
+# ---------------------------------------------------------------- compressed scales (Sec. 3.4; Alg. 2 with scale mask 0x1FFF)
+
+
+class H16CaseCS:
+    def __init__(self, K, N, codes, ssup):
+        self.K, self.N, self.codes, self.ssup = K, N, codes, ssup
+        self._W = None
+
+    def W(self):
+        if self._W is None:
+            self._W = o.h16_decode_cs(self.K, self.N, self.codes, self.ssup)
+        return self._W
+
+    def device_weight(self):
+        return b.Weight.from_canonical_compressed(self.K, self.N, b.H16, self.codes, None, self.ssup, device=DEV)
+
+
+def random_h16_cs(K, N, seed) -> H16CaseCS:
+    """Random words (so random 13-bit fields) and log-uniform fp16 super scales."""
+    codes = synth.random_codes(N, o.h16_row_bytes(K), synth.rng(seed, 0))
+    ssup = synth.scales_log_uniform_fp16(N, 1, synth.rng(seed, 1), lo=1e-5, hi=1e-3).reshape(N)
+    return H16CaseCS(K, N, codes, ssup)
+
+
+@pytest.mark.parametrize("K,N", [(512, 32), (2048, 208)])
+def test_compressed_scales_decode_bit_exact(K, N):
+    c = random_h16_cs(K, N, 27)
+    w = c.device_weight()
+    assert w.info.scale_bytes == 0 and w.info.total_bpw == 2.5 + 16 / K
+    for ks in (range(48, 64), range(K - 16, K), [63], [0, 62, 63], synth.rng(27, 5).integers(0, K, 40)):
+        _check_decode(c, w, ks, fp32_first=True)
+
+
+@pytest.mark.parametrize("M", [1, 3, 16, 17, 64, 130])
+def test_compressed_scales_gemm(M):
+    Wf = synth.weights_normal(192, 1536, synth.rng(28, 0))
+    codes, scales = o.h16_quantize(Wf)
+    codes, ssup = o.h16_compress_scales(Wf, codes, scales)
+    c = H16CaseCS(1536, 192, codes, ssup)
+    w = c.device_weight()
+    x = synth.activations_bf16(M, c.K, synth.rng(28, 100 + M))
+    abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(c.W())) if M > 16 else None
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"hybrid word, compressed scales, M={M}", abs_sum=abs_sum)
+
+
+def test_compressed_scales_grouped():
+    E, K, N, T = 3, 512, 48, 9
+    cases = [random_h16_cs(K, N, 29 + e) for e in range(E)]
+    w = b.Weight.from_canonical_compressed(K, N, b.H16, np.stack([c.codes for c in cases]), None, np.stack([c.ssup for c in cases]),
+                                           device=DEV, experts=E)
+    x = synth.activations_bf16(T, K, synth.rng(29, 99))
+    offs = np.array([0, 4, 4, 11], dtype=np.int32)
+    rows = synth.rng(29, 98).integers(0, T, 11).astype(np.int32)
     y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
     torch.cuda.synchronize()
     got = b.bf16_bits(y)

@@ -146,7 +146,8 @@ def test_hybrid_word_accounting_and_packing():
         assert dev[off] == tagged[src], (n, g, word, byte)
     info = b.ccq_info()
     lib = b.load()
-    assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, b.H16, scale_mode=1)), 1, ctypes.byref(info)) == -3   # compressed scales: not built
+    i1 = b.pack_info(b.descriptor(K, N, b.H16, scale_mode=1), 64)      # Sec. 3.4: the scale rides in the 13 spare bits, 2.5 bpw in all
+    assert i1.scale_bytes == 0 and i1.code_bytes == i.code_bytes and i1.total_bpw == 2.5 + 16 / K
     assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K + 64, N, b.H16)), 1, ctypes.byref(info)) == -3            # whole k-tiles of 512 only
     assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, [b.H16_HI, b.ccq_code(3, 4, 2, 0, 3.0)])), 1, ctypes.byref(info)) == -3  # one zp per word
     assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, [b.H16_LO, b.H16_HI])), 1, ctypes.byref(info)) != 0   # halves in the wrong order
