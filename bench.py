@@ -197,6 +197,65 @@ def paper_tables(dev) -> int:
     return 0
 
 
+def hybrid_word(dev) -> int:
+    """Third workload: the hybrid 16-bit word of Sec. 3.2 with its scale in the 13 spare bits (Sec. 3.4; 2.5 bits per
+    weight in all) on the 8192 x 8192 shape, from one activation row to a prefill-sized batch.  One JSON line."""
+    import numpy as np
+    import torch
+    from paper_2507_07145_amd import binding as b, synth
+    K = N = 8192
+    codes = synth.random_codes(N, (K // 64) * 20, synth.rng(9, 0))
+    ssup = synth.scales_log_uniform_fp16(N, 1, synth.rng(9, 1), 1e-5, 1e-3).reshape(N)
+    copies = 24
+    ws = [b.Weight.from_canonical_compressed(K, N, b.H16, codes, None, ssup, device=dev) for _ in range(copies)]
+    per_copy = ws[0].info.code_bytes + 2 * N
+    out = {"workload": "hybrid word (3,3,2)+(3,4,2), scale in the 13 spare bits, 2.5 bpw, K=N=8192", "bytes_of_weights": per_copy, "rows": []}
+    for M in (1, 4, 16, 64, 256, 2048):
+        x = b.bf16_tensor(synth.activations_bf16(M, K, synth.rng(9, 3)), dev)
+        ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in ws]
+        wsp = torch.empty(max(b.pack_info(ws[0].desc, M).workspace_bytes, 16), dtype=torch.uint8, device=dev)
+        fns = [(lambda w=w, y=y: b.gemm(w, x, out=y, workspace=wsp)) for w, y in zip(ws, ys)]
+        steps = copies * (20 if M <= 64 else 2)
+        _, ev = time_steps(fns, steps, copies, dev)
+        nbytes = per_copy + 2 * M * K + 2 * M * N
+        us = ev / steps * 1e6
+        out["rows"].append({"M": M, "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                            "TFLOPs": round(2.0 * M * K * N / us / 1e6, 1), "frac_of_mfma_peak": round(2.0 * M * K * N / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
+        del ys, fns
+    print(json.dumps(out))
+    return 0
+
+
+def quantize_workload(dev) -> int:
+    """Fourth workload: the quantizer itself (Alg. 1 search + Eq. 4 + Code Cluster) on an 8192 x 8192 fp32 matrix of
+    N(0, 0.02) weights, narrow and wide formats, next to the oracle's encoder timed on a sample of rows.  One JSON line."""
+    import numpy as np
+    import torch
+    from paper_2507_07145_amd import binding as b, synth
+    from oracle import ccq_oracle as o
+    K = N = 8192
+    Wh = synth.weights_normal(N, K, synth.rng(12, 0))
+    W = torch.from_numpy(Wh).to(dev)
+    out = {"workload": "quantize 8192 x 8192 fp32 weights ~ N(0, 0.02), group 64", "rows": []}
+    for name, fmt, ofmt in (("narrow (6,4,3) + Code Cluster", b.NARROW, o.F2), ("wide (4,3,2)", b.WIDE, o.F275)):
+        b.quantize(W, fmt)
+        torch.cuda.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            b.quantize(W, fmt)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        rows = 32
+        t0 = time.perf_counter()
+        o.quantize(Wh[:rows], ofmt)
+        cpu_s = time.perf_counter() - t0
+        out["rows"].append({"format": name, "ms": round(ms, 2), "Gweights_per_s": round(N * K / ms / 1e6, 2),
+                            "cpu_oracle": {"Gweights_per_s": round(rows * K / cpu_s / 1e9, 5), "cores": o.num_threads(), "sample": f"{rows} rows"}})
+    print(json.dumps(out))
+    return 0
+
+
 def calibrate_copy(dev) -> int:
     """A plain copy kernel of known size, rotating over buffers that together exceed the last-level cache."""
     import torch
@@ -223,6 +282,9 @@ def main() -> int:
     ap.add_argument("--launch", type=str, default="", help="explicit decomposition RT,WR,WK,S for tuning (default: the library's choice)")
     ap.add_argument("--paper-tables", action="store_true",
                     help="run the second workload instead: the GEMV and Grouped-GEMM shapes of the paper's Tables 4 and 5 at 2.06 bpw")
+    ap.add_argument("--hybrid-word", action="store_true",
+                    help="run the third workload instead: the hybrid 16-bit word of Sec. 3.2 at 2.5 bpw on the 8192 x 8192 shape")
+    ap.add_argument("--quantize", action="store_true", help="run the fourth workload instead: the GPU quantizer on an 8192 x 8192 matrix")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (64 MiB read + 64 MiB written per launch): the reference that "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -243,6 +305,10 @@ def main() -> int:
         return calibrate_copy(dev)
     if args.paper_tables:
         return paper_tables(dev)
+    if args.hybrid_word:
+        return hybrid_word(dev)
+    if args.quantize:
+        return quantize_workload(dev)
 
     K = N = 8192
     M = 1

@@ -183,6 +183,24 @@ int ccq_grouped_gemm(const ccq_weight *w0, int32_t E, int64_t codes_stride, int6
  * (pass expert_offsets_host so that the library can see that). */
 int64_t ccq_grouped_workspace_bytes(const ccq_weight *w0, int32_t E, int32_t P);
 
+/* The offline quantizer on the GPU: Alg. 1 (group scale absmax / (2^(L-1) - 1), nearest codeword of the
+ * convolutional codebook for every N-vector, ties to the lowest code), the least-squares scale of Eq. 4
+ * (kept when the group's squared error does not grow; the scale is then rounded to fp16 and the search run
+ * again with the stored value), and for the narrow format the Code Cluster map of Sec. 3.3 / Eq. 1 per
+ * output channel (beta = smallest 15-bit code of the row, alpha = (largest - smallest) / 255; every vector is
+ * searched again over the 256 codes round(q alpha + beta), then Eq. 4 once more).  An all-zero group gets
+ * scale 0.  All decisions are taken in fp64.
+ *   w: shape and format (one format, narrow or wide, scale_mode 0, no group map; others return
+ *      CCQ_ERR_UNSUPPORTED); its DEVICE pointers are not read.
+ *   W DEVICE fp32 [N][ldw], ldw >= K, a multiple of 4.
+ *   codes_out DEVICE [code_bytes], scales_out DEVICE [scale_bytes] (sizes from ccq_pack_info), both in
+ *   device order: what ccq_gemm reads.  alpha_out, beta_out DEVICE fp32 [N], narrow format only (may be
+ *   NULL otherwise).  workspace DEVICE, at least ccq_quantize_workspace_bytes(w) bytes (-1: not built).
+ *   Enqueues on hip_stream and returns; nothing is allocated. */
+int64_t ccq_quantize_workspace_bytes(const ccq_weight *w);
+int ccq_quantize(const ccq_weight *w, const float *W, int64_t ldw, void *codes_out, void *scales_out,
+                 float *alpha_out, float *beta_out, void *workspace, int64_t workspace_bytes, void *hip_stream);
+
 /* Human-readable name of a status code. */
 const char *ccq_status_string(int status);
 

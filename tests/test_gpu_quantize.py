@@ -1,0 +1,122 @@
+"""GPU parity of the quantizer (Alg. 1 search, Eq. 4 scale refit, Code Cluster map of Sec. 3.3 / Eq. 1) through the C ABI:
+codes, fp16 scales and the per-channel alpha / beta must equal the oracle's bit for bit (the oracle's canonical arrays
+are put into device order by the library's own pack routines), on Gaussian weights, heavy-tailed weights, all-zero rows
+and groups, and values that produce exact ties."""
+import numpy as np
+import pytest
+import torch
+
+from cases import assert_gemm_close
+from oracle import ccq_oracle as o
+from paper_2507_07145_amd import binding as b
+from paper_2507_07145_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+FMT = {"narrow": (b.NARROW, o.F2), "wide": (b.WIDE, o.F275)}
+
+
+def _weights(kind: str, N: int, K: int, seed: int) -> np.ndarray:
+    rng = synth.rng(30, seed)
+    if kind == "normal":
+        return synth.weights_normal(N, K, rng)
+    if kind == "heavy":                                   # outliers decide the group scale
+        W = synth.weights_normal(N, K, rng)
+        W[rng.random((N, K)) < 0.01] *= 12.0
+        return W.astype(np.float32)
+    if kind == "zeros":                                   # all-zero rows and groups among ordinary ones
+        W = synth.weights_normal(N, K, rng)
+        W[1] = 0.0
+        W[3, 64:192] = 0.0
+        W[N - 1, K - 64:] = 0.0
+        return W
+    if kind == "ties":                                    # few distinct values on a dyadic grid: many exact ties
+        return (rng.integers(-8, 9, size=(N, K)) / 64.0).astype(np.float32)
+    raise ValueError(kind)
+
+
+def _compare(fmt_name, W):
+    bfmt, ofmt = FMT[fmt_name]
+    N, K = W.shape
+    codes, scales, alpha, beta = o.quantize(W, ofmt)
+    d = b.descriptor(K, N, [bfmt])
+    want_codes = b.pack_codes(d, codes)
+    want_scales = b.pack_scales(d, scales)
+    got = b.quantize(torch.from_numpy(W).to(DEV), bfmt)
+    torch.cuda.synchronize()
+    g_codes = got.codes.cpu().numpy().reshape(-1)
+    g_scales = got.scales.cpu().numpy().view(np.uint16).reshape(-1)
+    if fmt_name == "narrow":
+        assert np.array_equal(got.alpha.cpu().numpy().reshape(-1), alpha), "alpha differs"
+        assert np.array_equal(got.beta.cpu().numpy().reshape(-1), beta), "beta differs"
+    bad = np.flatnonzero(g_codes != want_codes)
+    assert bad.size == 0, f"{bad.size} code bytes differ, first at {bad[:5]}"
+    assert np.array_equal(g_scales, want_scales), "scales differ"
+    return got, (codes, scales, alpha, beta)
+
+
+@pytest.mark.parametrize("fmt_name", ["narrow", "wide"])
+@pytest.mark.parametrize("kind", ["normal", "heavy", "zeros", "ties"])
+def test_quantizer_matches_the_oracle(fmt_name, kind):
+    K = 512 if fmt_name == "wide" else 256
+    _compare(fmt_name, _weights(kind, 48, K, 1))
+
+
+@pytest.mark.parametrize("fmt_name,N,K", [("narrow", 16, 1024), ("narrow", 208, 768), ("wide", 16, 1024), ("wide", 80, 1536)])
+def test_shapes_and_row_stride(fmt_name, N, K):
+    W = _weights("normal", N, K, 2)
+    got, _ = _compare(fmt_name, W)
+    # a strided source (ldw > K) gives the same result
+    bfmt = FMT[fmt_name][0]
+    big = torch.zeros((N, K + 64), dtype=torch.float32, device=DEV)
+    big[:, :K] = torch.from_numpy(W).to(DEV)
+    again = b.quantize(big[:, :K], bfmt)
+    torch.cuda.synchronize()
+    assert torch.equal(again.codes, got.codes) and torch.equal(again.scales, got.scales)
+
+
+def test_quantize_then_multiply():
+    """The quantizer's output is what ccq_gemm reads: quantize on the GPU, multiply on the GPU, compare with the oracle's
+    product over the oracle's own encoding of the same matrix."""
+    N, K, M = 256, 1024, 5
+    W = _weights("normal", N, K, 3)
+    got, (codes, scales, alpha, beta) = _compare("narrow", W)
+    x = synth.activations_bf16(M, K, synth.rng(30, 9))
+    y = b.gemm(got, b.bf16_tensor(x, DEV))
+    torch.cuda.synchronize()
+    Wd = o.decode(K, N, o.F2, codes, scales, alpha, beta)
+    assert_gemm_close(b.bf16_bits(y), o.matmul(x, Wd), "quantize -> gemm")
+    assert np.linalg.norm(Wd - W) / np.linalg.norm(W) < 0.45         # 2 bits per weight on Gaussian weights
+
+
+def test_full_size_sampled_rows():
+    """The 8192 x 8192 matrix of the benchmark: every row is independent of the others (scales per group, alpha / beta per
+    row), so the oracle encodes a sample of rows and those are compared bit for bit, read out of the device layout
+    (narrow k-tile: byte 4 kq + b of group j of the tile at (kq * 16 + row) * 16 + 4 j + b)."""
+    K = N = 8192
+    W = synth.weights_normal(N, K, synth.rng(30, 40))
+    got = b.quantize(torch.from_numpy(W).to(DEV), b.NARROW)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 15, 16, 17, 4095, 4096, 8176, 8191] + synth.rng(30, 41).integers(0, N, 7).tolist())
+    codes, scales, alpha, beta = o.quantize(W[rows], o.F2)
+    dev_codes = got.codes.cpu().numpy().reshape(-1)
+    dev_scales = got.scales.cpu().numpy().view(np.uint16).reshape(-1)
+    G = K // 64
+    g, j = np.meshgrid(np.arange(G), np.arange(16), indexing="ij")
+    for i, n in enumerate(rows):
+        off = (n // 16) * got.info.row_tile_bytes + (g // 4) * 1024 + ((j // 4) * 16 + n % 16) * 16 + (g % 4) * 4 + j % 4
+        assert np.array_equal(dev_codes[off].reshape(-1), codes[i]), f"row {n}: codes differ"
+        soff = (n // 16) * (G // 4) * 64 + (np.arange(G) // 4) * 64 + (n % 16) * 4 + np.arange(G) % 4
+        assert np.array_equal(dev_scales[soff], scales[i]), f"row {n}: scales differ"
+    assert np.array_equal(got.alpha.cpu().numpy().reshape(-1)[rows], alpha) and np.array_equal(got.beta.cpu().numpy().reshape(-1)[rows], beta)
+
+
+def test_rejections_need_no_kernel():
+    lib = b.load()
+    gf = np.zeros(8, dtype=np.uint8)
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, [b.NARROW, b.WIDE], gf))) == -1     # mixed formats
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, b.H16))) == -1                      # hybrid word
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, [b.NARROW], scale_mode=1))) == -1   # compressed scales
+    d = b.descriptor(512, 16, [b.NARROW])
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(d)) == (16 * 8 * 16 + 16 * 8) * 2
+    assert lib.ccq_quantize(b.ctypes.byref(d), None, 512, None, None, None, None, None, 0, None) == -1
