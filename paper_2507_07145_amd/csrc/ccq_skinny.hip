@@ -106,6 +106,58 @@ template <> struct Traits<kWide | kH16 | kScale4> : Traits<kWide | kH16> {
 // shifts (13,11), (6,4), (2,0) and leaves the one at shift 9 alone, i.e. weights {0,1}, {3,4}, {5,6}, {2}
 __device__ __forceinline__ int h16_slot_weight(int i) { return i < 2 ? i : (i < 6 ? i + 1 : 2); }
 
+// Activation fragments of the wide and hybrid-word kinds: the k-slots of (quarter kq, k-step t) of a group
+// are six or seven consecutive activations, so one 16-byte load (4-byte aligned; never past the group's own
+// 64 elements) fetches them and a few byte permutes put them into slot order.
+//   wide:   codes 6kq+2t and 6kq+2t+1, weights 18kq+6t+{0..5}, slots {0,3,1,4,2,5,-,-}; code 21 carries weight
+//           63 only (quarter 3: k-step 1 holds {60,63,61,-,62,-}, k-step 2 nothing)
+//   hybrid: word 4t+kq, weights 7 word+{0..6}, slots {0,1,3,4,5,6,2,-}; word 9 carries weight 63 only
+struct __attribute__((packed, aligned(4))) Chunk16 {  // 16 bytes at 4-byte alignment
+  uint32_t x, y, z, w;
+};
+__device__ __forceinline__ uint4 load_chunk16(const uint16_t* p) {
+  const Chunk16 c = *reinterpret_cast<const Chunk16*>(p);
+  return uint4{c.x, c.y, c.z, c.w};
+}
+template <int KIND>
+__device__ __forceinline__ int frag_first_element(int kq, int t) {
+  if constexpr ((KIND & kH16) != 0) return min((7 * (4 * t + kq)) & ~1, 56);
+  else return min(18 * kq + 6 * t, 56);
+}
+template <int KIND>
+__device__ __forceinline__ uint4 frag_from_chunk(const uint4 v, int kq, int t) {
+  uint4 o = {0u, 0u, 0u, 0u};
+  if constexpr ((KIND & kH16) != 0) {
+    const int word = 4 * t + kq;
+    if (word == 9) {
+      o.x = v.w >> 16;  // element 63 of the chunk that starts at 56
+    } else if (word < 9) {
+      if (word & 1) {   // the word starts at the chunk's second element
+        o.x = __builtin_amdgcn_perm(v.y, v.x, 0x05040302u);  // elements 1, 2
+        o.y = v.z;                                            // 4, 5
+        o.z = v.w;                                            // 6, 7
+        o.w = v.y >> 16;                                      // 3
+      } else {
+        o.x = v.x;                                            // 0, 1
+        o.y = __builtin_amdgcn_perm(v.z, v.y, 0x05040302u);  // 3, 4
+        o.z = __builtin_amdgcn_perm(v.w, v.z, 0x05040302u);  // 5, 6
+        o.w = v.y & 0xFFFFu;                                  // 2
+      }
+    }
+  } else {
+    if (kq < 3 || t == 0) {
+      o.x = __builtin_amdgcn_perm(v.y, v.x, 0x07060100u);  // elements 0, 3
+      o.y = __builtin_amdgcn_perm(v.z, v.x, 0x05040302u);  // 1, 4
+      o.z = __builtin_amdgcn_perm(v.z, v.y, 0x07060100u);  // 2, 5
+    } else if (t == 1) {  // chunk starts at 56: weights 60, 63 | 61 | 62
+      o.x = __builtin_amdgcn_perm(v.w, v.z, 0x07060100u);
+      o.y = v.z >> 16;
+      o.z = v.w & 0xFFFFu;
+    }
+  }
+  return o;
+}
+
 // k-tiles [A, B) of kind `kind` that workgroup `split` owns.
 __device__ __forceinline__ void split_range(const SkinnyArgs& a, int kind, int split, int& A, int& B) {
   const int q = a.sq[kind], r = a.sr[kind];
@@ -267,7 +319,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
                             int ng, int sg, int j0, int tid, int nthreads) {
   using TR = Traits<KIND>;
   constexpr int MRT = (MT == 1) ? MR : MT * 16;
-  constexpr int U = ((KIND & 1) == kNarrow) ? 4 : 2;  // fragments requested per thread before the first is used
+  constexpr int U = 4;  // fragments requested per thread before the first is used
   const int nfrag = ng * TR::T * 4 * MRT;
   const int meta_base = ((KIND & 1) == kWide) ? a.groups_narrow : 0;
   // the workgroup size is a multiple of MRT, so a thread stages the same activation row every time
@@ -277,7 +329,6 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
   if (row_ok) xrow = x + (a.sorted_rows ? (int64_t)a.sorted_rows[row_base + m] : (int64_t)(row_base + m)) * a.ldx;
   for (int f0 = tid; f0 < nfrag; f0 += nthreads * U) {
     uint4 v[U];
-    uint32_t h[U][8];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int f = min(f0 + u * nthreads, nfrag - 1);  // clamped: the request is unconditional
@@ -289,27 +340,8 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
       const uint16_t* xr = xrow + (int64_t)g * kGroup;
       if constexpr ((KIND & 1) == kNarrow) {
         v[u] = *reinterpret_cast<const uint4*>(xr + 16 * kq + 8 * t);
-      } else if constexpr ((KIND & kH16) != 0) {
-        // word 4t + kq covers weights 7 word .. 7 word + 6; word 9 carries weight 63 only
-        const int word = 4 * t + kq;
-#pragma unroll
-        for (int i = 0; i < 7; ++i) {
-          const int wi = 7 * word + h16_slot_weight(i);
-          h[u][i] = (word <= 9 && wi < kGroup) ? (uint32_t)xr[wi] : 0u;
-        }
-        h[u][7] = 0u;
       } else {
-        // codes ja = 6kq+2t and ja+1 cover weights 3ja+{0,1,2} and 3ja+3+{0,1,2};
-        // slots {a0,b0,a1,b1,a2,b2,-,-}; code 21 carries weight 63 only
-        const int ja = 6 * kq + 2 * t;
-#pragma unroll
-        for (int i = 0; i < 3; ++i) {
-#pragma unroll
-          for (int which = 0; which < 2; ++which) {
-            const int jj = ja + which, wi = 3 * jj + i;
-            h[u][2 * i + which] = (jj <= 21 && wi < kGroup) ? (uint32_t)xr[wi] : 0u;
-          }
-        }
+        v[u] = load_chunk16(xr + frag_first_element<KIND>(kq, t));
       }
     }
 #pragma unroll
@@ -326,10 +358,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
             o.z = __builtin_amdgcn_perm(v[u].w, v[u].y, 0x05040100u);
             o.w = __builtin_amdgcn_perm(v[u].w, v[u].y, 0x07060302u);
           } else {
-            o.x = h[u][0] | (h[u][1] << 16);
-            o.y = h[u][2] | (h[u][3] << 16);
-            o.z = h[u][4] | (h[u][5] << 16);
-            if constexpr ((KIND & kH16) != 0) o.w = h[u][6];
+            o = frag_from_chunk<KIND>(v[u], (f / MRT) & 3, (f / (MRT * 4)) % TR::T);
           }
         }
         lds_x[f] = o;
@@ -584,32 +613,8 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
       o.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
       o.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
       o.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
-    } else if constexpr ((KIND & kH16) != 0) {
-      const int word = 4 * t + kq;
-      uint32_t h[7];
-#pragma unroll
-      for (int i = 0; i < 7; ++i) {
-        const int wi = 7 * word + h16_slot_weight(i);
-        h[i] = (word <= 9 && wi < kGroup) ? (uint32_t)xg[wi] : 0u;
-      }
-      o.x = h[0] | (h[1] << 16);
-      o.y = h[2] | (h[3] << 16);
-      o.z = h[4] | (h[5] << 16);
-      o.w = h[6];
     } else {
-      const int ja = 6 * kq + 2 * t;
-      uint32_t h[6];
-#pragma unroll
-      for (int i = 0; i < 3; ++i) {
-#pragma unroll
-        for (int which = 0; which < 2; ++which) {
-          const int jj = ja + which, wi = 3 * jj + i;
-          h[2 * i + which] = (jj <= 21 && wi < kGroup) ? (uint32_t)xg[wi] : 0u;
-        }
-      }
-      o.x = h[0] | (h[1] << 16);
-      o.y = h[2] | (h[3] << 16);
-      o.z = h[4] | (h[5] << 16);
+      o = frag_from_chunk<KIND>(load_chunk16(xg + frag_first_element<KIND>(kq, t)), kq, t);
     }
     lds_x[f] = o;
     if constexpr ((KIND & 1) == kNarrow) {
