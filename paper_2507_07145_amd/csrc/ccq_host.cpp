@@ -112,7 +112,10 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     d.WR = (int)std::min<int64_t>(4, std::max(1, L.row_tiles / d.RT));
     d.WK = 1;
     int64_t row_blocks = (int64_t)ceil_div(L.row_tiles, d.RT * d.WR) * experts;
-    int s = (int)std::max<int64_t>(1, 512 / std::max<int64_t>(1, row_blocks));
+    // workgroups wanted: two per CU for the narrow format, four for the wide kinds, whose per-chunk staging is longer
+    // than the contraction it feeds and is best hidden by other workgroups of the same CU
+    const int64_t want_blocks = L.tiles[kNarrow] > 0 ? 512 : 1024;
+    int s = (int)std::max<int64_t>(1, want_blocks / std::max<int64_t>(1, row_blocks));
     s = std::min(s, std::max(1, nt / 2));
     if (M > 16) s = std::min(s, 2);
     d.S = std::min(s, kMaxSplitsK);
