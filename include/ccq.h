@@ -196,7 +196,8 @@ int64_t ccq_grouped_workspace_bytes(const ccq_weight *w0, int32_t E, int32_t P);
  *   codes_out DEVICE [code_bytes], scales_out DEVICE [scale_bytes] (sizes from ccq_pack_info), both in
  *   device order: what ccq_gemm reads.  alpha_out, beta_out DEVICE fp32 [N], narrow format only (may be
  *   NULL otherwise).  workspace DEVICE, at least ccq_quantize_workspace_bytes(w) bytes (-1: not built).
- *   Enqueues on hip_stream and returns; nothing is allocated. */
+ *   Enqueues on hip_stream and returns; nothing is allocated.  W must be finite (NaN or infinity in a
+ *   group gives unspecified codes and scale for that group). */
 int64_t ccq_quantize_workspace_bytes(const ccq_weight *w);
 int ccq_quantize(const ccq_weight *w, const float *W, int64_t ldw, void *codes_out, void *scales_out,
                  float *alpha_out, float *beta_out, void *workspace, int64_t workspace_bytes, void *hip_stream);
