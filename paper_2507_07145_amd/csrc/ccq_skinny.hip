@@ -300,6 +300,17 @@ __device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, const uint
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __builtin_bit_cast(float, bits16 << 16); }
 
+// Sum of the eight bf16 values of a fragment in fp32: four two-element dot products against (1, 1).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ float frag_sum(const uint4 o) {
+  const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+  float sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, o.x), ones, 0.f, false);
+  sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, o.y), ones, sum, false);
+  sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, o.z), ones, sum, false);
+  sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, o.w), ones, sum, false);
+  return sum;
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
   if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
@@ -376,8 +387,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
 #pragma unroll
     for (int tk = 0; tk < TR::T * 4; ++tk) {
       const uint4 v = lds_x[(lg * TR::T * 4 + tk) * MRT + m];
-      sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
-             bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
+      sum += frag_sum(v);
     }
     lds_cneg[lg * (MT * 16) + m] = factor * sum;
   }
@@ -441,7 +451,9 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
           // two 4x4x4 steps: k-slots 0..3 and 4..7 of the fragment
           const u32x4 wv = __builtin_bit_cast(u32x4, wf);
           const uint4 xv = cur.x[t][0];
-          f32x4 p = t == 0 ? cur.cin[0] : P[rt][0];
+          // one held row: the start value is added after the contraction (a zero C operand is an inline constant,
+          // a start value in element 0 of a four-register operand costs four moves per group)
+          f32x4 p = t == 0 ? (MR == 1 ? f32x4{0.f, 0.f, 0.f, 0.f} : cur.cin[0]) : P[rt][0];
           p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xv.x, xv.y}), __builtin_bit_cast(bf16x4, u32x2{wv.x, wv.y}), p, 0, 0, 0);
           p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xv.z, xv.w}), __builtin_bit_cast(bf16x4, u32x2{wv.z, wv.w}), p, 0, 0, 0);
           P[rt][0] = p;
@@ -457,7 +469,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
       const float s = group_scale<KIND>(r[rt], fields[rt], dc.ssup[rt], j);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        acc[rt][mt][0] = __builtin_fmaf(s, P[rt][mt][0], acc[rt][mt][0]);
+        acc[rt][mt][0] = __builtin_fmaf(s, MR == 1 ? P[rt][mt][0] + cur.cin[mt][0] : P[rt][mt][0], acc[rt][mt][0]);
         if (MR > 1) {
           acc[rt][mt][1] = __builtin_fmaf(s, P[rt][mt][1], acc[rt][mt][1]);
           acc[rt][mt][2] = __builtin_fmaf(s, P[rt][mt][2], acc[rt][mt][2]);
@@ -619,8 +631,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
     lds_x[f] = o;
     if constexpr ((KIND & 1) == kNarrow) {
       // the two fragments of a quarter (k-steps 0 and 1) sit 4 lanes apart: add them with one DPP step
-      float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
-                  ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
+      float sum = frag_sum(o);
       sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
       if ((f & 4) == 0) lds_cneg[lg * 4 + kq] = a.cneg[KIND & 1] * sum;
     }
@@ -635,8 +646,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
 #pragma unroll
       for (int t = 0; t < TR::T; ++t) {
         const uint4 v = lds_x[(lg * TR::T + t) * 4 + kq];
-        sum += bf16_to_f32(v.x & 0xFFFFu) + bf16_to_f32(v.x >> 16) + bf16_to_f32(v.y & 0xFFFFu) + bf16_to_f32(v.y >> 16) +
-               bf16_to_f32(v.z & 0xFFFFu) + bf16_to_f32(v.z >> 16) + bf16_to_f32(v.w & 0xFFFFu) + bf16_to_f32(v.w >> 16);
+        sum += frag_sum(v);
       }
       lds_cneg[e] = a.cneg[KIND & 1] * sum;
     }
@@ -673,8 +683,7 @@ __device__ __forceinline__ void stage_private_finish(const uint4 (&v)[kPrivFrags
       o.z = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x05040100u);
       o.w = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x07060302u);
       lds_x[f] = o;
-      float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
-                  ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
+      float sum = frag_sum(o);
       sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
       if ((f & 4) == 0) lds_cneg[(f >> 3) * 4 + (f & 3)] = cneg * sum;
     }
@@ -952,8 +961,7 @@ __device__ __forceinline__ void stage_private4_finish(const uint4 (&v)[kPrivFrag
     o.z = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x05040100u);
     o.w = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x07060302u);
     lds_x[f] = o;
-    float sum = ((bf16_to_f32(o.x & 0xFFFFu) + bf16_to_f32(o.x >> 16)) + (bf16_to_f32(o.y & 0xFFFFu) + bf16_to_f32(o.y >> 16))) +
-                ((bf16_to_f32(o.z & 0xFFFFu) + bf16_to_f32(o.z >> 16)) + (bf16_to_f32(o.w & 0xFFFFu) + bf16_to_f32(o.w >> 16)));
+    float sum = frag_sum(o);
     const float other = __shfl_xor(sum, 16);  // the other k-step of the same (group, quarter, row) sits 16 lanes away
     const float both = (f & 16) ? other + sum : sum + other;  // k-step 0 first on both sides: identical bits
     if ((f & 16) == 0) lds_cneg[((f >> 5) * 4 + ((f >> 2) & 3)) * 4 + (f & 3)] = cneg * both;
