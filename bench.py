@@ -237,18 +237,21 @@ def quantize_workload(dev) -> int:
     Wh = synth.weights_normal(N, K, synth.rng(12, 0))
     W = torch.from_numpy(Wh).to(dev)
     out = {"workload": "quantize 8192 x 8192 fp32 weights ~ N(0, 0.02), group 64", "rows": []}
-    for name, fmt, ofmt in (("narrow (6,4,3) + Code Cluster", b.NARROW, o.F2), ("wide (4,3,2)", b.WIDE, o.F275)):
-        b.quantize(W, fmt)
+    for name, fmt, ofmt, mode in (("narrow (6,4,3) + Code Cluster, fp16 scales", b.NARROW, o.F2, 0), ("wide (4,3,2), fp16 scales", b.WIDE, o.F275, 0),
+                                  ("narrow, compressed scales (2.06 bpw)", b.NARROW, o.F2, 1)):
+        b.quantize(W, fmt, scale_mode=mode)
         torch.cuda.synchronize()
         reps = 3
         t0 = time.perf_counter()
         for _ in range(reps):
-            b.quantize(W, fmt)
+            b.quantize(W, fmt, scale_mode=mode)
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) / reps * 1e3
         rows = 32
         t0 = time.perf_counter()
-        o.quantize(Wh[:rows], ofmt)
+        enc = o.quantize(Wh[:rows], ofmt)
+        if mode == 1:
+            o.compress_scales(Wh[:rows], ofmt, *enc)
         cpu_s = time.perf_counter() - t0
         out["rows"].append({"format": name, "ms": round(ms, 2), "Gweights_per_s": round(N * K / ms / 1e6, 2),
                             "cpu_oracle": {"Gweights_per_s": round(rows * K / cpu_s / 1e9, 5), "cores": o.num_threads(), "sample": f"{rows} rows"}})

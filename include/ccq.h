@@ -189,18 +189,23 @@ int64_t ccq_grouped_workspace_bytes(const ccq_weight *w0, int32_t E, int32_t P);
  * again with the stored value), and for the narrow format the Code Cluster map of Sec. 3.3 / Eq. 1 per
  * output channel (beta = smallest 15-bit code of the row, alpha = (largest - smallest) / 255; every vector is
  * searched again over the 256 codes round(q alpha + beta), then Eq. 4 once more).  An all-zero group gets
- * scale 0.  All decisions are taken in fp64.
- *   w: shape and format (one format, narrow or wide, scale_mode 0, no group map; others return
+ * scale 0.  With scale_mode 1 the scales are then compressed (Sec. 3.4): per output channel s_super =
+ * fp16(largest group scale / 15), every group scale becomes the nearest multiple field * s_super with the
+ * field in 1..15 (0 for an all-zero group), and every group's codes are searched once more with the scale
+ * that is stored.  All decisions are taken in fp64.
+ *   w: shape and format (one format, narrow or wide, either scale mode, no group map; others return
  *      CCQ_ERR_UNSUPPORTED); its DEVICE pointers are not read.
  *   W DEVICE fp32 [N][ldw], ldw >= K, a multiple of 4.
  *   codes_out DEVICE [code_bytes], scales_out DEVICE [scale_bytes] (sizes from ccq_pack_info), both in
- *   device order: what ccq_gemm reads.  alpha_out, beta_out DEVICE fp32 [N], narrow format only (may be
- *   NULL otherwise).  workspace DEVICE, at least ccq_quantize_workspace_bytes(w) bytes (-1: not built).
+ *   device order: what ccq_gemm reads (scale_mode 1: scales_out receives the packed fields of the narrow
+ *   format and may be NULL for the wide one).  alpha_out, beta_out DEVICE fp32 [N], narrow format only (may be
+ *   NULL otherwise).  scale_super_out DEVICE fp16 [N], scale_mode 1 only.  workspace DEVICE, at least ccq_quantize_workspace_bytes(w) bytes (-1: not built).
  *   Enqueues on hip_stream and returns; nothing is allocated.  W must be finite (NaN or infinity in a
  *   group gives unspecified codes and scale for that group). */
 int64_t ccq_quantize_workspace_bytes(const ccq_weight *w);
 int ccq_quantize(const ccq_weight *w, const float *W, int64_t ldw, void *codes_out, void *scales_out,
-                 float *alpha_out, float *beta_out, void *workspace, int64_t workspace_bytes, void *hip_stream);
+                 float *alpha_out, float *beta_out, void *scale_super_out, void *workspace,
+                 int64_t workspace_bytes, void *hip_stream);
 
 /* Human-readable name of a status code. */
 const char *ccq_status_string(int status);

@@ -95,7 +95,7 @@ def load() -> ctypes.CDLL:
     L.ccq_quantize_workspace_bytes.restype = i64
     L.ccq_quantize_workspace_bytes.argtypes = [wp]
     L.ccq_quantize.restype = ctypes.c_int
-    L.ccq_quantize.argtypes = [wp, vp, i64, vp, vp, vp, vp, vp, i64, vp]
+    L.ccq_quantize.argtypes = [wp, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
     L.ccq_status_string.restype = ctypes.c_char_p
     L.ccq_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -270,15 +270,18 @@ class Weight:
         return (self.codes.stride(0), self.scales.stride(0) * 2 if self.scales is not None else 0, ab)
 
 
-def quantize(W: torch.Tensor, fmt: ccq_code, stream=None) -> Weight:
+def quantize(W: torch.Tensor, fmt: ccq_code, scale_mode: int = 0, stream=None) -> Weight:
     """Quantize fp32 W [N][K] on the GPU through ccq_quantize; the result is ready for gemm()."""
     assert W.dtype == torch.float32 and W.dim() == 2 and W.stride(1) == 1 and W.is_cuda
     N, K = W.shape
     self = Weight()
-    d = descriptor(K, N, [fmt])
+    d = descriptor(K, N, [fmt], scale_mode=scale_mode)
     info = pack_info(d, 64)
     self.codes = torch.empty(info.code_bytes, dtype=torch.uint8, device=W.device)
-    self.scales = torch.empty(info.scale_bytes // 2, dtype=torch.int16, device=W.device)
+    if info.scale_bytes > 0:
+        self.scales = torch.empty(info.scale_bytes // 2, dtype=torch.int16, device=W.device)
+    if scale_mode == 1:
+        self.ssup = torch.empty(N, dtype=torch.int16, device=W.device)
     if fmt.code_cluster:
         self.alpha = torch.empty(N, dtype=torch.float32, device=W.device)
         self.beta = torch.empty(N, dtype=torch.float32, device=W.device)
@@ -287,13 +290,19 @@ def quantize(W: torch.Tensor, fmt: ccq_code, stream=None) -> Weight:
         raise CcqError(-3, "ccq_quantize_workspace_bytes")
     ws = _workspace(need, W.device)
     rc = load().ccq_quantize(ctypes.byref(d), _t_ptr(W), W.stride(0), _t_ptr(self.codes), _t_ptr(self.scales), _t_ptr(self.alpha),
-                             _t_ptr(self.beta), _t_ptr(ws), need, _stream_ptr(stream))
+                             _t_ptr(self.beta), _t_ptr(self.ssup), _t_ptr(ws), need, _stream_ptr(stream))
     _check(rc, "ccq_quantize")
     torch.cuda.current_stream().synchronize() if stream is None else stream.synchronize()   # the workspace is released on return
-    d.codes, d.scales = self.codes.data_ptr(), self.scales.data_ptr()
+    d.codes = self.codes.data_ptr()
+    d.scales = self.scales.data_ptr() if self.scales is not None else None
+    d.scale_super = self.ssup.data_ptr() if self.ssup is not None else None
     d.code_alpha = self.alpha.data_ptr() if self.alpha is not None else None
     d.code_beta = self.beta.data_ptr() if self.beta is not None else None
-    self.codes, self.scales = self.codes.reshape(1, -1), self.scales.reshape(1, -1)
+    self.codes = self.codes.reshape(1, -1)
+    if self.scales is not None:
+        self.scales = self.scales.reshape(1, -1)
+    if self.ssup is not None:
+        self.ssup = self.ssup.reshape(1, -1)
     if self.alpha is not None:
         self.alpha, self.beta = self.alpha.reshape(1, -1), self.beta.reshape(1, -1)
     self.desc, self.info, self.E = d, info, 1

@@ -34,6 +34,10 @@ struct EncArgs {
   float* beta;
   uint16_t* rowcodes;   // workspace: the unclustered codes, [N][G][16] (narrow format only)
   uint16_t* rowscale;   // workspace: fp16 bits of the group scales after the first pass, [N][G]
+  // compressed scales (Sec. 3.4) only:
+  uint16_t* canon_scales;  // workspace: final fp16 group scales, [N][G] (not in device order); NULL = fp16 scales are the output
+  uint8_t* fields;         // workspace: the 4-bit field of every group, [N][G]
+  uint16_t* ssup;          // output: fp16 super scale per output channel, [N]
   int64_t row_tile_bytes, row_tile_scale_halfs;
 };
 
@@ -197,9 +201,12 @@ __global__ void __launch_bounds__(256) ccq_encode_groups_kernel(const EncArgs a)
       a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kWideGroupsPerTile) * kWideTileBytes + (rem / 2) * 1024 +
               (kq * 16 + r) * 16 + (gi % kWideGroupsPerTile) * 2 + (rem % 2)] = (uint8_t)code;
     }
-    if (lane == 0)
-      a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kWideGroupsPerTile) * kWideTileScaleHalfs +
-               r * kWideGroupsPerTile + gi % kWideGroupsPerTile] = fp16_bits(s);
+    if (lane == 0) {
+      if (a.canon_scales) a.canon_scales[gidx] = fp16_bits(s);
+      else
+        a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kWideGroupsPerTile) * kWideTileScaleHalfs +
+                 r * kWideGroupsPerTile + gi % kWideGroupsPerTile] = fp16_bits(s);
+    }
   }
 }
 
@@ -288,18 +295,126 @@ __global__ void __launch_bounds__(256) ccq_encode_finish_narrow_kernel(const Enc
   if (lane < 16)
     a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileBytes + ((lane >> 2) * 16 + r) * 16 +
             (gi % kNarrowGroupsPerTile) * 4 + (lane & 3)] = (uint8_t)myq;
-  if (lane == 0)
-    a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileScaleHalfs +
-             r * kNarrowGroupsPerTile + gi % kNarrowGroupsPerTile] = fp16_bits(s);
+  if (lane == 0) {
+    if (a.canon_scales) a.canon_scales[gidx] = fp16_bits(s);
+    else
+      a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileScaleHalfs +
+               r * kNarrowGroupsPerTile + gi % kNarrowGroupsPerTile] = fp16_bits(s);
+  }
 }
 
+// ---- Sec. 3.4 "Scale Compression", encoder side ------------------------------------------------------
+// Channel-wise super scale: the largest group scale of the row / 15, rounded to fp16.  (fp16 bit patterns of
+// non-negative numbers order like the numbers.)
+__global__ void __launch_bounds__(256) ccq_encode_super_kernel(const EncArgs a) {
+  __shared__ uint32_t smax[256];
+  const int n = blockIdx.x;
+  uint32_t hi = 0;
+  for (int i = threadIdx.x; i < a.G; i += 256) hi = max(hi, (uint32_t)a.canon_scales[(int64_t)n * a.G + i]);
+  smax[threadIdx.x] = hi;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {
+    if ((int)threadIdx.x < off) smax[threadIdx.x] = max(smax[threadIdx.x], smax[threadIdx.x + off]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) a.ssup[n] = fp16_bits(fp16_round(fp16_value((uint16_t)smax[0]) / 15.0));
+}
+
+// One wavefront per (row, group): the group scale becomes the nearest multiple field * s_super, field in 1..15 (0 only
+// when the scale or the super scale is 0); because the scale that is stored has changed, the group's codes are
+// searched again with it -- over all codes (wide format) or over the 256 codes the row's Code Cluster map reaches
+// (narrow format).  The field goes into the spare low nibble of the wide group's last byte, or to the workspace
+// for the packing pass.
+template <bool NARROW>
+__global__ void __launch_bounds__(256) ccq_encode_compress_kernel(const EncArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
+  if (gidx >= (int64_t)a.N * a.G) return;
+  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
+  const double s = fp16_value(a.canon_scales[gidx]), ssup = fp16_value(a.ssup[n]);
+  int k = 0;
+  if (ssup > 0.0 && s > 0.0) {
+    const double kr = nearbyint(s / ssup);
+    k = kr < 1.0 ? 1 : (kr > 15.0 ? 15 : (int)kr);
+  }
+  const double se = (double)k * ssup;  // the scale the decoder will use
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  const int r = n % kRowsPerTile;
+  if constexpr (NARROW) {
+    if (se > 0.0) {
+      const double al = (double)a.alpha[n], be = (double)a.beta[n];
+      uint32_t mycodes[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) mycodes[t] = (uint32_t)nearbyint((double)(lane + 64 * t) * al + be);
+      uint32_t myq = 0;
+      for (int j = 0; j < 16; ++j) {
+        double v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = __shfl(w, 4 * j + i);
+        double best = INFINITY;
+        uint32_t bq = 0xFFFFFFFFu;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint32_t c = mycodes[t];
+          double cost = sqerr(v[0], se, (double)((c >> 9) & 63u) - a.zp);
+          cost = cost + sqerr(v[1], se, (double)((c >> 6) & 63u) - a.zp);
+          cost = cost + sqerr(v[2], se, (double)((c >> 3) & 63u) - a.zp);
+          cost = cost + sqerr(v[3], se, (double)(c & 63u) - a.zp);
+          if (cost < best) { best = cost; bq = (uint32_t)(lane + 64 * t); }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+          const double oc = __shfl_xor(best, off);
+          const uint32_t oq = (uint32_t)__shfl_xor((int)bq, off);
+          if (oc < best || (oc == best && oq < bq)) { best = oc; bq = oq; }
+        }
+        if (lane == j) myq = bq;
+      }
+      if (lane < 16)
+        a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileBytes + ((lane >> 2) * 16 + r) * 16 +
+                (gi % kNarrowGroupsPerTile) * 4 + (lane & 3)] = (uint8_t)myq;
+    }
+    if (lane == 0) a.fields[gidx] = (uint8_t)k;
+  } else {
+    uint32_t code = 0;
+    if (se > 0.0) code = search_group<4, 3, 2>(w, se, a.zp, lane);
+    if (lane < 22) {
+      const int kq = lane / 6, rem = lane % 6;
+      uint8_t* p = a.codes + (int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kWideGroupsPerTile) * kWideTileBytes + (rem / 2) * 1024 +
+                   (kq * 16 + r) * 16 + (gi % kWideGroupsPerTile) * 2 + (rem % 2);
+      uint32_t byte = se > 0.0 ? code : (uint32_t)*p;  // an all-zero group keeps its codes
+      if (lane == 21) byte = (byte & 0xF0u) | (uint32_t)k;
+      if (se > 0.0 || lane == 21) *p = (uint8_t)byte;
+    }
+  }
+}
+
+// Narrow format: the four 4-bit fields of a k-tile's groups into one 16-bit word per row (group j in bits 4j..4j+3).
+__global__ void __launch_bounds__(256) ccq_encode_pack_fields_kernel(const EncArgs a) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int tiles = a.G / kNarrowGroupsPerTile;
+  if (i >= (int64_t)a.N * tiles) return;
+  const int n = (int)(i / tiles), t = (int)(i % tiles);
+  const uint8_t* f = a.fields + (int64_t)n * a.G + t * kNarrowGroupsPerTile;
+  const uint32_t word = (uint32_t)f[0] | ((uint32_t)f[1] << 4) | ((uint32_t)f[2] << 8) | ((uint32_t)f[3] << 12);
+  a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)t * kNarrowTileScaleHalfs4 + n % kRowsPerTile] = (uint16_t)word;
+}
+
+static int64_t round16(int64_t v) { return (v + 15) / 16 * 16; }
+
+// workspace: [unclustered codes and first-pass scales (narrow)] [final fp16 scales, fields (compressed scales)]
 int64_t encode_workspace_bytes(const Layout& L) {
-  if (L.groups[kNarrow] == 0) return 0;
-  return ((int64_t)L.N * L.G * 16 + (int64_t)L.N * L.G) * 2;
+  const int64_t groups = (int64_t)L.N * L.G;
+  int64_t need = 0;
+  if (L.groups[kNarrow] > 0) need += round16(groups * 16 * 2) + round16(groups * 2);
+  if (L.scale_mode == 1) need += round16(groups * 2) + round16(groups);
+  return need;
 }
 
-int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, void* scales, float* alpha, float* beta, void* workspace,
-                  void* stream) {
+int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, void* scales, float* alpha, float* beta, void* scale_super,
+                  void* workspace, void* stream) {
+  const int64_t groups = (int64_t)L.N * L.G;
+  const bool narrow = L.groups[kNarrow] > 0;
   EncArgs a;
   a.W = W;
   a.ldw = ldw;
@@ -309,14 +424,28 @@ int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, voi
   a.scales = static_cast<uint16_t*>(scales);
   a.alpha = alpha;
   a.beta = beta;
-  a.rowcodes = static_cast<uint16_t*>(workspace);
-  a.rowscale = a.rowcodes ? a.rowcodes + (int64_t)L.N * L.G * 16 : nullptr;
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  a.rowcodes = nullptr;
+  a.rowscale = nullptr;
+  if (narrow) {
+    a.rowcodes = reinterpret_cast<uint16_t*>(ws);
+    ws += round16(groups * 16 * 2);
+    a.rowscale = reinterpret_cast<uint16_t*>(ws);
+    ws += round16(groups * 2);
+  }
+  a.canon_scales = nullptr;
+  a.fields = nullptr;
+  a.ssup = static_cast<uint16_t*>(scale_super);
+  if (L.scale_mode == 1) {
+    a.canon_scales = reinterpret_cast<uint16_t*>(ws);
+    ws += round16(groups * 2);
+    a.fields = ws;
+  }
   a.row_tile_bytes = L.row_tile_bytes;
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int64_t groups = (int64_t)L.N * L.G;
   const dim3 grid((unsigned)((groups + 3) / 4)), block(256);
-  if (L.groups[kNarrow] > 0) {
+  if (narrow) {
     a.zp = (double)L.zp[kNarrow];
     hipLaunchKernelGGL((ccq_encode_groups_kernel<6, 4, 3, true>), grid, block, 0, st, a);
     hipLaunchKernelGGL(ccq_encode_cluster_kernel, dim3((unsigned)L.N), block, 0, st, a);
@@ -324,6 +453,16 @@ int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, voi
   } else {
     a.zp = (double)L.zp[kWide];
     hipLaunchKernelGGL((ccq_encode_groups_kernel<4, 3, 2, false>), grid, block, 0, st, a);
+  }
+  if (L.scale_mode == 1) {
+    hipLaunchKernelGGL(ccq_encode_super_kernel, dim3((unsigned)L.N), block, 0, st, a);
+    if (narrow) {
+      hipLaunchKernelGGL(ccq_encode_compress_kernel<true>, grid, block, 0, st, a);
+      const int64_t words = (int64_t)L.N * L.tiles[kNarrow];
+      hipLaunchKernelGGL(ccq_encode_pack_fields_kernel, dim3((unsigned)((words + 255) / 256)), block, 0, st, a);
+    } else {
+      hipLaunchKernelGGL(ccq_encode_compress_kernel<false>, grid, block, 0, st, a);
+    }
   }
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;

@@ -89,6 +89,35 @@ def test_quantize_then_multiply():
     assert np.linalg.norm(Wd - W) / np.linalg.norm(W) < 0.45         # 2 bits per weight on Gaussian weights
 
 
+@pytest.mark.parametrize("fmt_name", ["narrow", "wide"])
+@pytest.mark.parametrize("kind", ["normal", "heavy", "zeros", "ties"])
+def test_compressed_scales_match_the_oracle(fmt_name, kind):
+    """scale_mode 1 (Sec. 3.4): quantize, then channel-wise super scale, 4-bit fields and one more search with the scale
+    that is stored; codes (with the wide format's fields inside), packed narrow fields, super scales, alpha and beta."""
+    bfmt, ofmt = FMT[fmt_name]
+    N, K = 48, (512 if fmt_name == "wide" else 256)
+    W = _weights(kind, N, K, 5)
+    codes, scales, alpha, beta = o.quantize(W, ofmt)
+    c2, sq, ssup = o.compress_scales(W, ofmt, codes, scales, alpha, beta)
+    d = b.descriptor(K, N, [bfmt], scale_mode=1)
+    got = b.quantize(torch.from_numpy(W).to(DEV), bfmt, scale_mode=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.ssup.cpu().numpy().view(np.uint16).reshape(-1), ssup), "super scales differ"
+    bad = np.flatnonzero(got.codes.cpu().numpy().reshape(-1) != b.pack_codes(d, c2))
+    assert bad.size == 0, f"{bad.size} code bytes differ, first at {bad[:5]}"
+    if fmt_name == "narrow":
+        assert np.array_equal(got.scales.cpu().numpy().view(np.uint16).reshape(-1), b.pack_scales4(d, sq)), "scale fields differ"
+        assert np.array_equal(got.alpha.cpu().numpy().reshape(-1), alpha) and np.array_equal(got.beta.cpu().numpy().reshape(-1), beta)
+    else:
+        assert got.scales is None
+    # and the result multiplies: against the oracle's decode of its own compressed encoding
+    x = synth.activations_bf16(3, K, synth.rng(30, 77))
+    y = b.gemm(got, b.bf16_tensor(x, DEV))
+    torch.cuda.synchronize()
+    Wd = o.decode_cs(K, N, ofmt, c2, sq, ssup, alpha, beta)
+    assert_gemm_close(b.bf16_bits(y), o.matmul(x, Wd), "quantize (compressed scales) -> gemm")
+
+
 def test_full_size_sampled_rows():
     """The 8192 x 8192 matrix of the benchmark: every row is independent of the others (scales per group, alpha / beta per
     row), so the oracle encodes a sample of rows and those are compared bit for bit, read out of the device layout
@@ -116,7 +145,8 @@ def test_rejections_need_no_kernel():
     gf = np.zeros(8, dtype=np.uint8)
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, [b.NARROW, b.WIDE], gf))) == -1     # mixed formats
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, b.H16))) == -1                      # hybrid word
-    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, [b.NARROW], scale_mode=1))) == -1   # compressed scales
     d = b.descriptor(512, 16, [b.NARROW])
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(d)) == (16 * 8 * 16 + 16 * 8) * 2
-    assert lib.ccq_quantize(b.ctypes.byref(d), None, 512, None, None, None, None, None, 0, None) == -1
+    d1 = b.descriptor(512, 16, [b.NARROW], scale_mode=1)
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(d1)) == (16 * 8 * 16 + 16 * 8) * 2 + 16 * 8 * 2 + 16 * 8
+    assert lib.ccq_quantize(b.ctypes.byref(d), None, 512, None, None, None, None, None, None, 0, None) == -1
