@@ -270,19 +270,20 @@ class Weight:
         return (self.codes.stride(0), self.scales.stride(0) * 2 if self.scales is not None else 0, ab)
 
 
-def quantize(W: torch.Tensor, fmt: ccq_code, scale_mode: int = 0, stream=None) -> Weight:
-    """Quantize fp32 W [N][K] on the GPU through ccq_quantize; the result is ready for gemm()."""
+def quantize(W: torch.Tensor, fmt, scale_mode: int = 0, stream=None) -> Weight:
+    """Quantize fp32 W [N][K] on the GPU through ccq_quantize; the result is ready for gemm().  `fmt`: NARROW, WIDE or H16."""
     assert W.dtype == torch.float32 and W.dim() == 2 and W.stride(1) == 1 and W.is_cuda
     N, K = W.shape
     self = Weight()
-    d = descriptor(K, N, [fmt], scale_mode=scale_mode)
+    fmts = list(fmt) if isinstance(fmt, (list, tuple)) else [fmt]
+    d = descriptor(K, N, fmts, scale_mode=scale_mode)
     info = pack_info(d, 64)
     self.codes = torch.empty(info.code_bytes, dtype=torch.uint8, device=W.device)
     if info.scale_bytes > 0:
         self.scales = torch.empty(info.scale_bytes // 2, dtype=torch.int16, device=W.device)
     if scale_mode == 1:
         self.ssup = torch.empty(N, dtype=torch.int16, device=W.device)
-    if fmt.code_cluster:
+    if any(f.code_cluster for f in fmts):
         self.alpha = torch.empty(N, dtype=torch.float32, device=W.device)
         self.beta = torch.empty(N, dtype=torch.float32, device=W.device)
     need = int(load().ccq_quantize_workspace_bytes(ctypes.byref(d)))

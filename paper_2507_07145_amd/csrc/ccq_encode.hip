@@ -38,6 +38,7 @@ struct EncArgs {
   uint16_t* canon_scales;  // workspace: final fp16 group scales, [N][G] (not in device order); NULL = fp16 scales are the output
   uint8_t* fields;         // workspace: the 4-bit field of every group, [N][G]
   uint16_t* ssup;          // output: fp16 super scale per output channel, [N]
+  double field_max;        // largest value of a scale field: 15, or 8191 for the hybrid word
   int64_t row_tile_bytes, row_tile_scale_halfs;
 };
 
@@ -304,7 +305,7 @@ __global__ void __launch_bounds__(256) ccq_encode_finish_narrow_kernel(const Enc
 }
 
 // ---- Sec. 3.4 "Scale Compression", encoder side ------------------------------------------------------
-// Channel-wise super scale: the largest group scale of the row / 15, rounded to fp16.  (fp16 bit patterns of
+// Channel-wise super scale: the largest group scale of the row / the largest field value, rounded to fp16.  (fp16 bit patterns of
 // non-negative numbers order like the numbers.)
 __global__ void __launch_bounds__(256) ccq_encode_super_kernel(const EncArgs a) {
   __shared__ uint32_t smax[256];
@@ -317,7 +318,7 @@ __global__ void __launch_bounds__(256) ccq_encode_super_kernel(const EncArgs a) 
     if ((int)threadIdx.x < off) smax[threadIdx.x] = max(smax[threadIdx.x], smax[threadIdx.x + off]);
     __syncthreads();
   }
-  if (threadIdx.x == 0) a.ssup[n] = fp16_bits(fp16_round(fp16_value((uint16_t)smax[0]) / 15.0));
+  if (threadIdx.x == 0) a.ssup[n] = fp16_bits(fp16_round(fp16_value((uint16_t)smax[0]) / a.field_max));
 }
 
 // One wavefront per (row, group): the group scale becomes the nearest multiple field * s_super, field in 1..15 (0 only
@@ -389,6 +390,97 @@ __global__ void __launch_bounds__(256) ccq_encode_compress_kernel(const EncArgs 
   }
 }
 
+// ---- the hybrid 16-bit word (Sec. 3.2): a (3,3,2) code on weights 7j..7j+2 and a (3,4,2) code on weights 7j+3..7j+6
+// of word j, searched independently (their bits do not overlap); ten words per group, the last one zero-padded ----
+
+// Lane j (j < 10) returns word j of the group held one weight per lane.
+__device__ __forceinline__ uint32_t search_h16(double w, double s, double zp, int lane) {
+  uint32_t mine = 0;
+  for (int j0 = 0; j0 < 10; j0 += 8) {
+    const int j = min(j0 + (lane >> 3), 9);
+    double va[3], vb[4];
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+      const int idx = 7 * j + i;
+      const double val = __shfl(w, min(idx, kGroup - 1));
+      const double v = idx < kGroup ? val : 0.0;
+      if (i < 3) va[i] = v;
+      else vb[i - 3] = v;
+    }
+    const uint32_t ca = nearest_code<3, 3, 2>(va, s, zp, lane);
+    const uint32_t cb = nearest_code<3, 4, 2>(vb, s, zp, lane);
+    const uint32_t word = (ca << 9) | cb;
+#pragma unroll
+    for (int sg = 0; sg < 8; ++sg) {
+      const uint32_t c = (uint32_t)__shfl((int)word, sg * 8);
+      if (lane == j0 + sg && j0 + sg < 10) mine = c;
+    }
+  }
+  return mine;
+}
+
+// word j of group gi, row n, in the hybrid-word k-tile: segment j / 4, lane (j % 4) * 16 + row, halfword gi % 8
+__device__ __forceinline__ uint16_t* h16_word_ptr(const EncArgs& a, int n, int gi, int j) {
+  return reinterpret_cast<uint16_t*>(a.codes + (int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kWideGroupsPerTile) * kH16TileBytes +
+                                     (j >> 2) * 1024 + ((j & 3) * 16 + n % kRowsPerTile) * 16 + (gi % kWideGroupsPerTile) * 2);
+}
+
+// One wavefront per (row, group): Alg. 1 with the Eq. 4 refit as for the other formats; 2^(L-1) - 1 = 3.
+__global__ void __launch_bounds__(256) ccq_encode_h16_kernel(const EncArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
+  if (gidx >= (int64_t)a.N * a.G) return;
+  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  const double amax = wave_max(fabs(w));
+  uint32_t word = 0;
+  double s = 0.0;
+  if (amax != 0.0) {
+    const double s0 = amax / 3.0;
+    word = search_h16(w, s0, a.zp, lane);
+    const uint32_t wj = (uint32_t)__shfl((int)word, lane / 7);
+    const int i = lane % 7;
+    const int shift = i < 3 ? 13 - 2 * i : 12 - 2 * i;  // Table 1: [13,11,9,6,4,2,0]
+    const double wq = (double)((wj >> shift) & 7u) - a.zp;
+    double s1 = refit_scale(w, wq, s0);
+    if (!(s1 > 0.0) || group_error(w, wq, s1) > group_error(w, wq, s0)) s1 = s0;
+    s = fp16_scale(s1);
+    word = search_h16(w, s, a.zp, lane);
+  }
+  if (lane < 10) *h16_word_ptr(a, n, gi, lane) = (uint16_t)word;
+  if (lane == 0) {
+    if (a.canon_scales) a.canon_scales[gidx] = fp16_bits(s);
+    else
+      a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kWideGroupsPerTile) * kWideTileScaleHalfs +
+               (n % kRowsPerTile) * kWideGroupsPerTile + gi % kWideGroupsPerTile] = fp16_bits(s);
+  }
+}
+
+// Compressed scales of the hybrid word: 13-bit field in the low bits of the group's last word (scale mask 0x1FFF of
+// Table 1), words searched again with the scale that is stored.
+__global__ void __launch_bounds__(256) ccq_encode_h16_compress_kernel(const EncArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
+  if (gidx >= (int64_t)a.N * a.G) return;
+  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
+  const double s = fp16_value(a.canon_scales[gidx]), ssup = fp16_value(a.ssup[n]);
+  int k = 0;
+  if (ssup > 0.0 && s > 0.0) {
+    const double kr = nearbyint(s / ssup);
+    k = kr < 1.0 ? 1 : (kr > 8191.0 ? 8191 : (int)kr);
+  }
+  const double se = (double)k * ssup;
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  uint32_t word = 0;
+  if (se > 0.0) word = search_h16(w, se, a.zp, lane);
+  if (lane < 10) {
+    uint16_t* p = h16_word_ptr(a, n, gi, lane);
+    uint32_t v = se > 0.0 ? word : (uint32_t)*p;  // an all-zero group keeps its words
+    if (lane == 9) v = (v & 0xE000u) | (uint32_t)k;
+    if (se > 0.0 || lane == 9) *p = (uint16_t)v;
+  }
+}
+
 // Narrow format: the four 4-bit fields of a k-tile's groups into one 16-bit word per row (group j in bits 4j..4j+3).
 __global__ void __launch_bounds__(256) ccq_encode_pack_fields_kernel(const EncArgs a) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -416,6 +508,7 @@ int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, voi
   const int64_t groups = (int64_t)L.N * L.G;
   const bool narrow = L.groups[kNarrow] > 0;
   EncArgs a;
+  a.field_max = L.h16 ? 8191.0 : 15.0;
   a.W = W;
   a.ldw = ldw;
   a.N = L.N;
@@ -450,13 +543,18 @@ int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, voi
     hipLaunchKernelGGL((ccq_encode_groups_kernel<6, 4, 3, true>), grid, block, 0, st, a);
     hipLaunchKernelGGL(ccq_encode_cluster_kernel, dim3((unsigned)L.N), block, 0, st, a);
     hipLaunchKernelGGL(ccq_encode_finish_narrow_kernel, grid, block, 0, st, a);
+  } else if (L.h16) {
+    a.zp = (double)L.zp[kWide];
+    hipLaunchKernelGGL(ccq_encode_h16_kernel, grid, block, 0, st, a);
   } else {
     a.zp = (double)L.zp[kWide];
     hipLaunchKernelGGL((ccq_encode_groups_kernel<4, 3, 2, false>), grid, block, 0, st, a);
   }
   if (L.scale_mode == 1) {
     hipLaunchKernelGGL(ccq_encode_super_kernel, dim3((unsigned)L.N), block, 0, st, a);
-    if (narrow) {
+    if (L.h16) {
+      hipLaunchKernelGGL(ccq_encode_h16_compress_kernel, grid, block, 0, st, a);
+    } else if (narrow) {
       hipLaunchKernelGGL(ccq_encode_compress_kernel<true>, grid, block, 0, st, a);
       const int64_t words = (int64_t)L.N * L.tiles[kNarrow];
       hipLaunchKernelGGL(ccq_encode_pack_fields_kernel, dim3((unsigned)((words + 255) / 256)), block, 0, st, a);

@@ -491,11 +491,11 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
   return launch_skinny(c);
 }
 
-// Formats the GPU quantizer is built for: one format (narrow or wide), either scale mode.
+// Formats the GPU quantizer is built for: narrow, wide or the hybrid word (no per-group mix), either scale mode.
 static int encode_layout(const ccq_weight* w, Layout* L) {
   int rc = make_layout(w, L);
   if (rc != CCQ_OK) return rc;
-  if (L->h16 || L->has_map || (L->groups[kNarrow] > 0 && L->groups[kWide] > 0)) return CCQ_ERR_UNSUPPORTED;
+  if (L->has_map || (L->groups[kNarrow] > 0 && L->groups[kWide] > 0)) return CCQ_ERR_UNSUPPORTED;
   return CCQ_OK;
 }
 

@@ -118,6 +118,33 @@ def test_compressed_scales_match_the_oracle(fmt_name, kind):
     assert_gemm_close(b.bf16_bits(y), o.matmul(x, Wd), "quantize (compressed scales) -> gemm")
 
 
+@pytest.mark.parametrize("kind", ["normal", "heavy", "zeros", "ties"])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_hybrid_word_matches_the_oracle(kind, mode):
+    """The hybrid 16-bit word (Sec. 3.2): two independent searches per word, fp16 scales or the 13-bit field of Sec. 3.4."""
+    N, K = 32, 512
+    W = _weights(kind, N, K, 6)
+    codes, scales = o.h16_quantize(W)
+    ssup = None
+    if mode == 1:
+        codes, ssup = o.h16_compress_scales(W, codes, scales)
+    d = b.descriptor(K, N, b.H16, scale_mode=mode)
+    got = b.quantize(torch.from_numpy(W).to(DEV), b.H16, scale_mode=mode)
+    torch.cuda.synchronize()
+    bad = np.flatnonzero(got.codes.cpu().numpy().reshape(-1) != b.pack_codes(d, codes))
+    assert bad.size == 0, f"{bad.size} code bytes differ, first at {bad[:5]}"
+    if mode == 0:
+        assert np.array_equal(got.scales.cpu().numpy().view(np.uint16).reshape(-1), b.pack_scales(d, scales)), "scales differ"
+        Wd = o.h16_decode(K, N, codes, scales)
+    else:
+        assert np.array_equal(got.ssup.cpu().numpy().view(np.uint16).reshape(-1), ssup), "super scales differ"
+        Wd = o.h16_decode_cs(K, N, codes, ssup)
+    x = synth.activations_bf16(2, K, synth.rng(30, 78))
+    y = b.gemm(got, b.bf16_tensor(x, DEV))
+    torch.cuda.synchronize()
+    assert_gemm_close(b.bf16_bits(y), o.matmul(x, Wd), "quantize (hybrid word) -> gemm")
+
+
 def test_full_size_sampled_rows():
     """The 8192 x 8192 matrix of the benchmark: every row is independent of the others (scales per group, alpha / beta per
     row), so the oracle encodes a sample of rows and those are compared bit for bit, read out of the device layout
@@ -144,7 +171,7 @@ def test_rejections_need_no_kernel():
     lib = b.load()
     gf = np.zeros(8, dtype=np.uint8)
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, [b.NARROW, b.WIDE], gf))) == -1     # mixed formats
-    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, b.H16))) == -1                      # hybrid word
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, b.H16))) == 0                       # hybrid word: no workspace
     d = b.descriptor(512, 16, [b.NARROW])
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(d)) == (16 * 8 * 16 + 16 * 8) * 2
     d1 = b.descriptor(512, 16, [b.NARROW], scale_mode=1)
