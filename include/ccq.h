@@ -193,13 +193,14 @@ int64_t ccq_grouped_workspace_bytes(const ccq_weight *w0, int32_t E, int32_t P);
  * fp16(largest group scale / 15), every group scale becomes the nearest multiple field * s_super with the
  * field in 1..15 (0 for an all-zero group), and every group's codes are searched once more with the scale
  * that is stored.  All decisions are taken in fp64.
- *   w: shape and format (one format, narrow or wide, either scale mode, no group map; others return
- *      CCQ_ERR_UNSUPPORTED); its DEVICE pointers are not read.
+ *   w: shape and format (any the multiply entry points accept: narrow, wide, a per-group mix, the hybrid
+ *      word whose two codes are searched independently and whose field is 13 bits; either scale mode).  Of its
+ *      DEVICE pointers only `meta` is read, and only for a per-group mix (ccq_pack_meta).
  *   W DEVICE fp32 [N][ldw], ldw >= K, a multiple of 4.
  *   codes_out DEVICE [code_bytes], scales_out DEVICE [scale_bytes] (sizes from ccq_pack_info), both in
- *   device order: what ccq_gemm reads (scale_mode 1: scales_out receives the packed fields of the narrow
- *   format and may be NULL for the wide one).  alpha_out, beta_out DEVICE fp32 [N], narrow format only (may be
- *   NULL otherwise).  scale_super_out DEVICE fp16 [N], scale_mode 1 only.  workspace DEVICE, at least ccq_quantize_workspace_bytes(w) bytes (-1: not built).
+ *   device order: what ccq_gemm reads (scale_mode 1: scales_out receives the packed fields of the narrow-format
+ *   groups and may be NULL when there are none).  alpha_out, beta_out DEVICE fp32 [N], needed when there are
+ *   narrow-format groups (may be NULL otherwise).  scale_super_out DEVICE fp16 [N], scale_mode 1 only.  workspace DEVICE, at least ccq_quantize_workspace_bytes(w) bytes (-1: not built).
  *   Enqueues on hip_stream and returns; nothing is allocated.  W must be finite (NaN or infinity in a
  *   group gives unspecified codes and scale for that group). */
 int64_t ccq_quantize_workspace_bytes(const ccq_weight *w);

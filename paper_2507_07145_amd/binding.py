@@ -270,14 +270,19 @@ class Weight:
         return (self.codes.stride(0), self.scales.stride(0) * 2 if self.scales is not None else 0, ab)
 
 
-def quantize(W: torch.Tensor, fmt, scale_mode: int = 0, stream=None) -> Weight:
-    """Quantize fp32 W [N][K] on the GPU through ccq_quantize; the result is ready for gemm().  `fmt`: NARROW, WIDE or H16."""
+def quantize(W: torch.Tensor, fmt, scale_mode: int = 0, group_fmt=None, stream=None) -> Weight:
+    """Quantize fp32 W [N][K] on the GPU through ccq_quantize; the result is ready for gemm().  `fmt`: NARROW, WIDE, H16, or
+    [NARROW, WIDE] with `group_fmt` (uint8 [K/64], 0 = narrow, 1 = wide)."""
     assert W.dtype == torch.float32 and W.dim() == 2 and W.stride(1) == 1 and W.is_cuda
     N, K = W.shape
     self = Weight()
     fmts = list(fmt) if isinstance(fmt, (list, tuple)) else [fmt]
-    d = descriptor(K, N, fmts, scale_mode=scale_mode)
+    self._group_fmt = None if group_fmt is None else np.ascontiguousarray(group_fmt, dtype=np.uint8)
+    d = descriptor(K, N, fmts, self._group_fmt, scale_mode=scale_mode)
     info = pack_info(d, 64)
+    if self._group_fmt is not None:
+        self.meta = torch.from_numpy(pack_meta(d)).to(W.device)
+        d.meta = self.meta.data_ptr()
     self.codes = torch.empty(info.code_bytes, dtype=torch.uint8, device=W.device)
     if info.scale_bytes > 0:
         self.scales = torch.empty(info.scale_bytes // 2, dtype=torch.int16, device=W.device)

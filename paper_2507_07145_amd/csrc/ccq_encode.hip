@@ -26,7 +26,13 @@ namespace ccq {
 struct EncArgs {
   const float* W;       // fp32 [N][ldw]
   int64_t ldw;
-  int32_t N, G;
+  int32_t N, G;        // rows; groups per row (all kinds)
+  // the groups of the kind this launch works on (all of them unless the matrix mixes formats): GK groups per row,
+  // the p-th of them is original group meta[pbase + p] (p itself without a map) and sits at packed position p of
+  // the kind's k-tiles, which start kind_code_off bytes / kind_scale_off halfwords into a row tile
+  int32_t GK, pbase;
+  const int32_t* meta;
+  int64_t kind_code_off, kind_scale_off;
   double zp;
   uint8_t* codes;       // device order
   uint16_t* scales;     // device order, fp16 bits
@@ -72,6 +78,21 @@ __device__ __forceinline__ uint16_t fp16_bits(double y) {
 __device__ __forceinline__ double fp16_value(uint16_t h) {
   const int e = (h >> 10) & 0x1F, m = h & 0x3FF;
   return e == 0 ? ldexp((double)m, -24) : ldexp((double)(m | 0x400), e - 25);
+}
+
+// (row, group) of a wavefront: n = row, p = position among the row's groups of this kind, g = original group
+// (activation columns 64 g ..), widx = index into the per-(row, group) workspace arrays that span all kinds
+struct GroupId {
+  int n, p, g;
+  int64_t widx;
+};
+__device__ __forceinline__ bool group_id(const EncArgs& a, int64_t gidx, GroupId& id) {
+  if (gidx >= (int64_t)a.N * a.GK) return false;
+  id.n = (int)(gidx / a.GK);
+  id.p = (int)(gidx % a.GK);
+  id.g = a.meta ? a.meta[a.pbase + id.p] : id.p;
+  id.widx = (int64_t)id.n * a.G + a.pbase + id.p;
+  return true;
 }
 
 __device__ __forceinline__ double sqerr(double v, double s, double lv) {
@@ -173,9 +194,10 @@ __global__ void __launch_bounds__(256) ccq_encode_groups_kernel(const EncArgs a)
   constexpr int NS = 1 << L, CPG = (kGroup + NV - 1) / NV;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
-  if (gidx >= (int64_t)a.N * a.G) return;
-  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
-  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  GroupId id;
+  if (!group_id(a, gidx, id)) return;
+  const int n = id.n, gi = id.p;
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)id.g * kGroup + lane];
   const double amax = wave_max(fabs(w));
   uint32_t code = 0;
   double s = 0.0;
@@ -199,13 +221,13 @@ __global__ void __launch_bounds__(256) ccq_encode_groups_kernel(const EncArgs a)
     const int r = n % kRowsPerTile;
     if (lane < CPG) {
       const int kq = lane / 6, rem = lane % 6;
-      a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kWideGroupsPerTile) * kWideTileBytes + (rem / 2) * 1024 +
+      a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + a.kind_code_off + (int64_t)(gi / kWideGroupsPerTile) * kWideTileBytes + (rem / 2) * 1024 +
               (kq * 16 + r) * 16 + (gi % kWideGroupsPerTile) * 2 + (rem % 2)] = (uint8_t)code;
     }
     if (lane == 0) {
-      if (a.canon_scales) a.canon_scales[gidx] = fp16_bits(s);
+      if (a.canon_scales) a.canon_scales[id.widx] = fp16_bits(s);
       else
-        a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kWideGroupsPerTile) * kWideTileScaleHalfs +
+        a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + a.kind_scale_off + (int64_t)(gi / kWideGroupsPerTile) * kWideTileScaleHalfs +
                  r * kWideGroupsPerTile + gi % kWideGroupsPerTile] = fp16_bits(s);
     }
   }
@@ -215,7 +237,7 @@ __global__ void __launch_bounds__(256) ccq_encode_groups_kernel(const EncArgs a)
 // alpha = (largest - smallest) / 255 (1 when they are equal).
 __global__ void __launch_bounds__(256) ccq_encode_cluster_kernel(const EncArgs a) {
   __shared__ uint32_t smin[256], smax[256];
-  const int n = blockIdx.x, per_row = a.G * 16;
+  const int n = blockIdx.x, per_row = a.GK * 16;
   uint32_t lo = 0xFFFFFFFFu, hi = 0;
   for (int i = threadIdx.x; i < per_row; i += 256) {
     const uint32_t c = a.rowcodes[(int64_t)n * per_row + i];
@@ -247,8 +269,9 @@ __global__ void __launch_bounds__(256) ccq_encode_finish_narrow_kernel(const Enc
   __shared__ uint32_t reach[4][256];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
-  if (gidx >= (int64_t)a.N * a.G) return;
-  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
+  GroupId id;
+  if (!group_id(a, gidx, id)) return;
+  const int n = id.n, gi = id.p;
   const double al = (double)a.alpha[n], be = (double)a.beta[n];
   uint32_t mycodes[4];
 #pragma unroll
@@ -259,7 +282,7 @@ __global__ void __launch_bounds__(256) ccq_encode_finish_narrow_kernel(const Enc
     reach[wave][q] = mycodes[t];
   }
   __builtin_amdgcn_wave_barrier();
-  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)id.g * kGroup + lane];
   double s = fp16_value(a.rowscale[gidx]);
   uint32_t myq = 0;
   for (int j = 0; j < 16; ++j) {
@@ -294,12 +317,12 @@ __global__ void __launch_bounds__(256) ccq_encode_finish_narrow_kernel(const Enc
   // narrow k-tile: byte 4 kq + b of group j of the tile sits at (kq * 16 + row) * 16 + 4 j + b
   const int r = n % kRowsPerTile;
   if (lane < 16)
-    a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileBytes + ((lane >> 2) * 16 + r) * 16 +
+    a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + a.kind_code_off + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileBytes + ((lane >> 2) * 16 + r) * 16 +
             (gi % kNarrowGroupsPerTile) * 4 + (lane & 3)] = (uint8_t)myq;
   if (lane == 0) {
-    if (a.canon_scales) a.canon_scales[gidx] = fp16_bits(s);
+    if (a.canon_scales) a.canon_scales[id.widx] = fp16_bits(s);
     else
-      a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileScaleHalfs +
+      a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + a.kind_scale_off + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileScaleHalfs +
                r * kNarrowGroupsPerTile + gi % kNarrowGroupsPerTile] = fp16_bits(s);
   }
 }
@@ -330,16 +353,17 @@ template <bool NARROW>
 __global__ void __launch_bounds__(256) ccq_encode_compress_kernel(const EncArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
-  if (gidx >= (int64_t)a.N * a.G) return;
-  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
-  const double s = fp16_value(a.canon_scales[gidx]), ssup = fp16_value(a.ssup[n]);
+  GroupId id;
+  if (!group_id(a, gidx, id)) return;
+  const int n = id.n, gi = id.p;
+  const double s = fp16_value(a.canon_scales[id.widx]), ssup = fp16_value(a.ssup[n]);
   int k = 0;
   if (ssup > 0.0 && s > 0.0) {
     const double kr = nearbyint(s / ssup);
     k = kr < 1.0 ? 1 : (kr > 15.0 ? 15 : (int)kr);
   }
   const double se = (double)k * ssup;  // the scale the decoder will use
-  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)id.g * kGroup + lane];
   const int r = n % kRowsPerTile;
   if constexpr (NARROW) {
     if (se > 0.0) {
@@ -372,7 +396,7 @@ __global__ void __launch_bounds__(256) ccq_encode_compress_kernel(const EncArgs 
         if (lane == j) myq = bq;
       }
       if (lane < 16)
-        a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileBytes + ((lane >> 2) * 16 + r) * 16 +
+        a.codes[(int64_t)(n / kRowsPerTile) * a.row_tile_bytes + a.kind_code_off + (int64_t)(gi / kNarrowGroupsPerTile) * kNarrowTileBytes + ((lane >> 2) * 16 + r) * 16 +
                 (gi % kNarrowGroupsPerTile) * 4 + (lane & 3)] = (uint8_t)myq;
     }
     if (lane == 0) a.fields[gidx] = (uint8_t)k;
@@ -381,7 +405,7 @@ __global__ void __launch_bounds__(256) ccq_encode_compress_kernel(const EncArgs 
     if (se > 0.0) code = search_group<4, 3, 2>(w, se, a.zp, lane);
     if (lane < 22) {
       const int kq = lane / 6, rem = lane % 6;
-      uint8_t* p = a.codes + (int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kWideGroupsPerTile) * kWideTileBytes + (rem / 2) * 1024 +
+      uint8_t* p = a.codes + (int64_t)(n / kRowsPerTile) * a.row_tile_bytes + a.kind_code_off + (int64_t)(gi / kWideGroupsPerTile) * kWideTileBytes + (rem / 2) * 1024 +
                    (kq * 16 + r) * 16 + (gi % kWideGroupsPerTile) * 2 + (rem % 2);
       uint32_t byte = se > 0.0 ? code : (uint32_t)*p;  // an all-zero group keeps its codes
       if (lane == 21) byte = (byte & 0xF0u) | (uint32_t)k;
@@ -421,7 +445,7 @@ __device__ __forceinline__ uint32_t search_h16(double w, double s, double zp, in
 
 // word j of group gi, row n, in the hybrid-word k-tile: segment j / 4, lane (j % 4) * 16 + row, halfword gi % 8
 __device__ __forceinline__ uint16_t* h16_word_ptr(const EncArgs& a, int n, int gi, int j) {
-  return reinterpret_cast<uint16_t*>(a.codes + (int64_t)(n / kRowsPerTile) * a.row_tile_bytes + (int64_t)(gi / kWideGroupsPerTile) * kH16TileBytes +
+  return reinterpret_cast<uint16_t*>(a.codes + (int64_t)(n / kRowsPerTile) * a.row_tile_bytes + a.kind_code_off + (int64_t)(gi / kWideGroupsPerTile) * kH16TileBytes +
                                      (j >> 2) * 1024 + ((j & 3) * 16 + n % kRowsPerTile) * 16 + (gi % kWideGroupsPerTile) * 2);
 }
 
@@ -429,9 +453,10 @@ __device__ __forceinline__ uint16_t* h16_word_ptr(const EncArgs& a, int n, int g
 __global__ void __launch_bounds__(256) ccq_encode_h16_kernel(const EncArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
-  if (gidx >= (int64_t)a.N * a.G) return;
-  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
-  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  GroupId id;
+  if (!group_id(a, gidx, id)) return;
+  const int n = id.n, gi = id.p;
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)id.g * kGroup + lane];
   const double amax = wave_max(fabs(w));
   uint32_t word = 0;
   double s = 0.0;
@@ -449,9 +474,9 @@ __global__ void __launch_bounds__(256) ccq_encode_h16_kernel(const EncArgs a) {
   }
   if (lane < 10) *h16_word_ptr(a, n, gi, lane) = (uint16_t)word;
   if (lane == 0) {
-    if (a.canon_scales) a.canon_scales[gidx] = fp16_bits(s);
+    if (a.canon_scales) a.canon_scales[id.widx] = fp16_bits(s);
     else
-      a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)(gi / kWideGroupsPerTile) * kWideTileScaleHalfs +
+      a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + a.kind_scale_off + (int64_t)(gi / kWideGroupsPerTile) * kWideTileScaleHalfs +
                (n % kRowsPerTile) * kWideGroupsPerTile + gi % kWideGroupsPerTile] = fp16_bits(s);
   }
 }
@@ -461,16 +486,17 @@ __global__ void __launch_bounds__(256) ccq_encode_h16_kernel(const EncArgs a) {
 __global__ void __launch_bounds__(256) ccq_encode_h16_compress_kernel(const EncArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t gidx = (int64_t)blockIdx.x * 4 + wave;
-  if (gidx >= (int64_t)a.N * a.G) return;
-  const int n = (int)(gidx / a.G), gi = (int)(gidx % a.G);
-  const double s = fp16_value(a.canon_scales[gidx]), ssup = fp16_value(a.ssup[n]);
+  GroupId id;
+  if (!group_id(a, gidx, id)) return;
+  const int n = id.n, gi = id.p;
+  const double s = fp16_value(a.canon_scales[id.widx]), ssup = fp16_value(a.ssup[n]);
   int k = 0;
   if (ssup > 0.0 && s > 0.0) {
     const double kr = nearbyint(s / ssup);
     k = kr < 1.0 ? 1 : (kr > 8191.0 ? 8191 : (int)kr);
   }
   const double se = (double)k * ssup;
-  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)gi * kGroup + lane];
+  const double w = (double)a.W[(int64_t)n * a.ldw + (int64_t)id.g * kGroup + lane];
   uint32_t word = 0;
   if (se > 0.0) word = search_h16(w, se, a.zp, lane);
   if (lane < 10) {
@@ -484,35 +510,35 @@ __global__ void __launch_bounds__(256) ccq_encode_h16_compress_kernel(const EncA
 // Narrow format: the four 4-bit fields of a k-tile's groups into one 16-bit word per row (group j in bits 4j..4j+3).
 __global__ void __launch_bounds__(256) ccq_encode_pack_fields_kernel(const EncArgs a) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int tiles = a.G / kNarrowGroupsPerTile;
+  const int tiles = a.GK / kNarrowGroupsPerTile;
   if (i >= (int64_t)a.N * tiles) return;
   const int n = (int)(i / tiles), t = (int)(i % tiles);
-  const uint8_t* f = a.fields + (int64_t)n * a.G + t * kNarrowGroupsPerTile;
+  const uint8_t* f = a.fields + (int64_t)n * a.GK + t * kNarrowGroupsPerTile;
   const uint32_t word = (uint32_t)f[0] | ((uint32_t)f[1] << 4) | ((uint32_t)f[2] << 8) | ((uint32_t)f[3] << 12);
-  a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + (int64_t)t * kNarrowTileScaleHalfs4 + n % kRowsPerTile] = (uint16_t)word;
+  a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + a.kind_scale_off + (int64_t)t * kNarrowTileScaleHalfs4 + n % kRowsPerTile] = (uint16_t)word;
 }
 
 static int64_t round16(int64_t v) { return (v + 15) / 16 * 16; }
 
 // workspace: [unclustered codes and first-pass scales (narrow)] [final fp16 scales, fields (compressed scales)]
 int64_t encode_workspace_bytes(const Layout& L) {
-  const int64_t groups = (int64_t)L.N * L.G;
+  const int64_t groups = (int64_t)L.N * L.G, narrow = (int64_t)L.N * L.groups[kNarrow];
   int64_t need = 0;
-  if (L.groups[kNarrow] > 0) need += round16(groups * 16 * 2) + round16(groups * 2);
-  if (L.scale_mode == 1) need += round16(groups * 2) + round16(groups);
+  if (narrow > 0) need += round16(narrow * 16 * 2) + round16(narrow * 2);
+  if (L.scale_mode == 1) need += round16(groups * 2) + round16(narrow);
   return need;
 }
 
 int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, void* scales, float* alpha, float* beta, void* scale_super,
-                  void* workspace, void* stream) {
-  const int64_t groups = (int64_t)L.N * L.G;
-  const bool narrow = L.groups[kNarrow] > 0;
+                  const int32_t* meta, void* workspace, void* stream) {
+  const int64_t groups = (int64_t)L.N * L.G, narrow = (int64_t)L.N * L.groups[kNarrow];
   EncArgs a;
   a.field_max = L.h16 ? 8191.0 : 15.0;
   a.W = W;
   a.ldw = ldw;
   a.N = L.N;
   a.G = L.G;
+  a.meta = L.has_map ? meta : nullptr;
   a.codes = static_cast<uint8_t*>(codes);
   a.scales = static_cast<uint16_t*>(scales);
   a.alpha = alpha;
@@ -520,11 +546,11 @@ int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, voi
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   a.rowcodes = nullptr;
   a.rowscale = nullptr;
-  if (narrow) {
+  if (narrow > 0) {
     a.rowcodes = reinterpret_cast<uint16_t*>(ws);
-    ws += round16(groups * 16 * 2);
+    ws += round16(narrow * 16 * 2);
     a.rowscale = reinterpret_cast<uint16_t*>(ws);
-    ws += round16(groups * 2);
+    ws += round16(narrow * 2);
   }
   a.canon_scales = nullptr;
   a.fields = nullptr;
@@ -537,29 +563,39 @@ int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, voi
   a.row_tile_bytes = L.row_tile_bytes;
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const dim3 grid((unsigned)((groups + 3) / 4)), block(256);
-  if (narrow) {
-    a.zp = (double)L.zp[kNarrow];
-    hipLaunchKernelGGL((ccq_encode_groups_kernel<6, 4, 3, true>), grid, block, 0, st, a);
-    hipLaunchKernelGGL(ccq_encode_cluster_kernel, dim3((unsigned)L.N), block, 0, st, a);
-    hipLaunchKernelGGL(ccq_encode_finish_narrow_kernel, grid, block, 0, st, a);
-  } else if (L.h16) {
-    a.zp = (double)L.zp[kWide];
-    hipLaunchKernelGGL(ccq_encode_h16_kernel, grid, block, 0, st, a);
-  } else {
-    a.zp = (double)L.zp[kWide];
-    hipLaunchKernelGGL((ccq_encode_groups_kernel<4, 3, 2, false>), grid, block, 0, st, a);
+  const dim3 block(256);
+  // the narrow groups of every row, then the wide ones (or the hybrid words, which never mix)
+  EncArgs an = a, aw = a;
+  an.GK = L.groups[kNarrow];
+  an.pbase = 0;
+  an.kind_code_off = 0;
+  an.kind_scale_off = 0;
+  an.zp = (double)L.zp[kNarrow];
+  aw.GK = L.groups[kWide];
+  aw.pbase = L.groups[kNarrow];
+  aw.kind_code_off = (int64_t)L.tiles[kNarrow] * kNarrowTileBytes;
+  aw.kind_scale_off = L.scale_mode == 1 ? 0 : (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs;
+  aw.zp = (double)L.zp[kWide];
+  const dim3 grid_n((unsigned)((narrow + 3) / 4)), grid_w((unsigned)(((int64_t)L.N * L.groups[kWide] + 3) / 4));
+  if (an.GK > 0) {
+    hipLaunchKernelGGL((ccq_encode_groups_kernel<6, 4, 3, true>), grid_n, block, 0, st, an);
+    hipLaunchKernelGGL(ccq_encode_cluster_kernel, dim3((unsigned)L.N), block, 0, st, an);
+    hipLaunchKernelGGL(ccq_encode_finish_narrow_kernel, grid_n, block, 0, st, an);
+  }
+  if (aw.GK > 0) {
+    if (L.h16) hipLaunchKernelGGL(ccq_encode_h16_kernel, grid_w, block, 0, st, aw);
+    else hipLaunchKernelGGL((ccq_encode_groups_kernel<4, 3, 2, false>), grid_w, block, 0, st, aw);
   }
   if (L.scale_mode == 1) {
     hipLaunchKernelGGL(ccq_encode_super_kernel, dim3((unsigned)L.N), block, 0, st, a);
-    if (L.h16) {
-      hipLaunchKernelGGL(ccq_encode_h16_compress_kernel, grid, block, 0, st, a);
-    } else if (narrow) {
-      hipLaunchKernelGGL(ccq_encode_compress_kernel<true>, grid, block, 0, st, a);
+    if (an.GK > 0) {
+      hipLaunchKernelGGL(ccq_encode_compress_kernel<true>, grid_n, block, 0, st, an);
       const int64_t words = (int64_t)L.N * L.tiles[kNarrow];
-      hipLaunchKernelGGL(ccq_encode_pack_fields_kernel, dim3((unsigned)((words + 255) / 256)), block, 0, st, a);
-    } else {
-      hipLaunchKernelGGL(ccq_encode_compress_kernel<false>, grid, block, 0, st, a);
+      hipLaunchKernelGGL(ccq_encode_pack_fields_kernel, dim3((unsigned)((words + 255) / 256)), block, 0, st, an);
+    }
+    if (aw.GK > 0) {
+      if (L.h16) hipLaunchKernelGGL(ccq_encode_h16_compress_kernel, grid_w, block, 0, st, aw);
+      else hipLaunchKernelGGL(ccq_encode_compress_kernel<false>, grid_w, block, 0, st, aw);
     }
   }
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;

@@ -491,13 +491,8 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
   return launch_skinny(c);
 }
 
-// Formats the GPU quantizer is built for: narrow, wide or the hybrid word (no per-group mix), either scale mode.
-static int encode_layout(const ccq_weight* w, Layout* L) {
-  int rc = make_layout(w, L);
-  if (rc != CCQ_OK) return rc;
-  if (L->has_map || (L->groups[kNarrow] > 0 && L->groups[kWide] > 0)) return CCQ_ERR_UNSUPPORTED;
-  return CCQ_OK;
-}
+// The GPU quantizer is built for every layout the multiply kernels read.
+static int encode_layout(const ccq_weight* w, Layout* L) { return make_layout(w, L); }
 
 extern "C" int64_t ccq_quantize_workspace_bytes(const ccq_weight* w) {
   Layout L;
@@ -516,13 +511,16 @@ extern "C" int ccq_quantize(const ccq_weight* w, const float* W, int64_t ldw, vo
   if (!scales_out && (L.scale_mode == 0 || cluster)) return CCQ_ERR_NULL;  // wide groups keep compressed scales in the code stream
   if (cluster && (!alpha_out || !beta_out)) return CCQ_ERR_NULL;
   if (L.scale_mode == 1 && !scale_super_out) return CCQ_ERR_NULL;
+  if (L.has_map && !w->meta) return CCQ_ERR_NULL;
+  if (!aligned16(w->meta)) return CCQ_ERR_ALIGN;
   if (ldw < L.K) return CCQ_ERR_BAD_PARAM;
   if (!aligned16(W) || !aligned16(codes_out) || !aligned16(scales_out) || !aligned16(alpha_out) || !aligned16(beta_out) || !aligned16(scale_super_out) ||
       !aligned16(workspace) || ldw % 4 != 0)
     return CCQ_ERR_ALIGN;
   const int64_t need = encode_workspace_bytes(L);
   if (need > 0 && (!workspace || workspace_bytes < need)) return CCQ_ERR_WORKSPACE;
-  return launch_encode(L, W, ldw, codes_out, scales_out, alpha_out, beta_out, scale_super_out, need > 0 ? workspace : nullptr, hip_stream);
+  return launch_encode(L, W, ldw, codes_out, scales_out, alpha_out, beta_out, scale_super_out, static_cast<const int32_t*>(w->meta),
+                       need > 0 ? workspace : nullptr, hip_stream);
 }
 
 extern "C" const char* ccq_status_string(int status) {

@@ -117,9 +117,9 @@ int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, i
 // Large-M kernel for narrow-format weights (ccq_prefill.hip).
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 
-// The quantizer (ccq_encode.hip): narrow-only or wide-only layouts, fp16 or compressed group scales.
+// The quantizer (ccq_encode.hip): every layout the multiply kernels read, fp16 or compressed group scales.
 int64_t encode_workspace_bytes(const Layout& L);
 int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, void* scales, float* alpha, float* beta, void* scale_super,
-                  void* workspace, void* stream);
+                  const int32_t* meta, void* workspace, void* stream);
 
 }  // namespace ccq

@@ -145,6 +145,38 @@ def test_hybrid_word_matches_the_oracle(kind, mode):
     assert_gemm_close(b.bf16_bits(y), o.matmul(x, Wd), "quantize (hybrid word) -> gemm")
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+def test_mixed_formats_match_the_oracle(mode):
+    """A per-group mix of the narrow and wide formats (group_fmt shared by all rows): the Code Cluster map is fitted to the
+    narrow groups' codes only, the super scale to all groups of the row."""
+    N, K = 32, 2048
+    G = K // 64
+    gf = synth.group_format_map(G, 8, synth.rng(30, 50))
+    W = _weights("heavy", N, K, 7)
+    W[2, 64 * int(np.flatnonzero(gf == 1)[0]):][:64] = 0.0          # an all-zero wide group
+    fmt = (o.F2, o.F275)
+    codes, scales, alpha, beta = o.quantize(W, fmt, gf)
+    d = b.descriptor(K, N, [b.NARROW, b.WIDE], gf, scale_mode=mode)
+    got = b.quantize(torch.from_numpy(W).to(DEV), [b.NARROW, b.WIDE], scale_mode=mode, group_fmt=gf)
+    torch.cuda.synchronize()
+    if mode == 0:
+        want_codes, want_scales = b.pack_codes(d, codes), b.pack_scales(d, scales)
+        Wd = o.decode(K, N, fmt, codes, scales, alpha, beta, gf)
+    else:
+        c2, sq, ssup = o.compress_scales(W, fmt, codes, scales, alpha, beta, gf)
+        want_codes, want_scales = b.pack_codes(d, c2), b.pack_scales4(d, sq)
+        assert np.array_equal(got.ssup.cpu().numpy().view(np.uint16).reshape(-1), ssup), "super scales differ"
+        Wd = o.decode_cs(K, N, fmt, c2, sq, ssup, alpha, beta, gf)
+    bad = np.flatnonzero(got.codes.cpu().numpy().reshape(-1) != want_codes)
+    assert bad.size == 0, f"{bad.size} code bytes differ, first at {bad[:5]}"
+    assert np.array_equal(got.scales.cpu().numpy().view(np.uint16).reshape(-1), want_scales), "scales differ"
+    assert np.array_equal(got.alpha.cpu().numpy().reshape(-1), alpha) and np.array_equal(got.beta.cpu().numpy().reshape(-1), beta)
+    x = synth.activations_bf16(2, K, synth.rng(30, 79))
+    y = b.gemm(got, b.bf16_tensor(x, DEV))
+    torch.cuda.synchronize()
+    assert_gemm_close(b.bf16_bits(y), o.matmul(x, Wd), "quantize (mixed formats) -> gemm")
+
+
 def test_full_size_sampled_rows():
     """The 8192 x 8192 matrix of the benchmark: every row is independent of the others (scales per group, alpha / beta per
     row), so the oracle encodes a sample of rows and those are compared bit for bit, read out of the device layout
@@ -169,8 +201,7 @@ def test_full_size_sampled_rows():
 
 def test_rejections_need_no_kernel():
     lib = b.load()
-    gf = np.zeros(8, dtype=np.uint8)
-    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, [b.NARROW, b.WIDE], gf))) == -1     # mixed formats
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512 + 64, 16, [b.NARROW]))) == -1            # not a whole number of k-tiles
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, b.H16))) == 0                       # hybrid word: no workspace
     d = b.descriptor(512, 16, [b.NARROW])
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(d)) == (16 * 8 * 16 + 16 * 8) * 2
