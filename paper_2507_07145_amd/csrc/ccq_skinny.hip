@@ -413,7 +413,9 @@ __device__ __forceinline__ void read_group_operands(GroupOperands<KIND, MT, MR>&
   const int kq = lane >> 4, m = lane & 15;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    if constexpr (MR == 1) g.cin[mt][0] = lds_cneg[lg * 4 + kq];  // one float per group and quarter; elements 1..3 keep their value
+    // one held row: a 16-byte record per group and quarter whose first float is the start value; the other three
+    // are never written and feed accumulator elements that are never read
+    if constexpr (MR == 1) g.cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * 4 + kq) * 4);
     else if constexpr (MR == 4) g.cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * 4 + kq) * 4);  // the four held rows
     else g.cin[mt] = *reinterpret_cast<const f32x4*>(lds_cneg + (lg * MT + mt) * 16 + 4 * kq);
   }
@@ -433,7 +435,6 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
                                              const float (&be)[RT], f32x4 (&acc)[RT][MT], int lane, DecodeConsts dc) {
   using TR = Traits<KIND>;
   GroupOperands<KIND, MT, MR> cur;
-  if constexpr (MR == 1) cur.cin[0] = f32x4{0.f, 0.f, 0.f, 0.f};  // elements 1..3 only need a defined value
   uint32_t fields[RT][4];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) tile_scale_fields<KIND>(fields[rt], r[rt], lane);
@@ -451,9 +452,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
           // two 4x4x4 steps: k-slots 0..3 and 4..7 of the fragment
           const u32x4 wv = __builtin_bit_cast(u32x4, wf);
           const uint4 xv = cur.x[t][0];
-          // one held row: the start value is added after the contraction (a zero C operand is an inline constant,
-          // a start value in element 0 of a four-register operand costs four moves per group)
-          f32x4 p = t == 0 ? (MR == 1 ? f32x4{0.f, 0.f, 0.f, 0.f} : cur.cin[0]) : P[rt][0];
+          f32x4 p = t == 0 ? cur.cin[0] : P[rt][0];
           p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xv.x, xv.y}), __builtin_bit_cast(bf16x4, u32x2{wv.x, wv.y}), p, 0, 0, 0);
           p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xv.z, xv.w}), __builtin_bit_cast(bf16x4, u32x2{wv.z, wv.w}), p, 0, 0, 0);
           P[rt][0] = p;
@@ -469,7 +468,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
       const float s = group_scale<KIND>(r[rt], fields[rt], dc.ssup[rt], j);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        acc[rt][mt][0] = __builtin_fmaf(s, MR == 1 ? P[rt][mt][0] + cur.cin[mt][0] : P[rt][mt][0], acc[rt][mt][0]);
+        acc[rt][mt][0] = __builtin_fmaf(s, P[rt][mt][0], acc[rt][mt][0]);
         if (MR > 1) {
           acc[rt][mt][1] = __builtin_fmaf(s, P[rt][mt][1], acc[rt][mt][1]);
           acc[rt][mt][2] = __builtin_fmaf(s, P[rt][mt][2], acc[rt][mt][2]);
@@ -633,7 +632,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
       // the two fragments of a quarter (k-steps 0 and 1) sit 4 lanes apart: add them with one DPP step
       float sum = frag_sum(o);
       sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
-      if ((f & 4) == 0) lds_cneg[lg * 4 + kq] = a.cneg[KIND & 1] * sum;
+      if ((f & 4) == 0) lds_cneg[(lg * 4 + kq) * 4] = a.cneg[KIND & 1] * sum;
     }
   }
   if constexpr ((KIND & 1) == kWide) {
@@ -648,7 +647,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
         const uint4 v = lds_x[(lg * TR::T + t) * 4 + kq];
         sum += frag_sum(v);
       }
-      lds_cneg[e] = a.cneg[KIND & 1] * sum;
+      lds_cneg[e * 4] = a.cneg[KIND & 1] * sum;
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -665,9 +664,11 @@ __device__ __forceinline__ void stage_private_request(uint4 (&v)[kPrivFrags], co
   for (int i = 0; i < kPrivFrags; ++i) {
     if (64 * i >= nfrag) break;  // wavefront-uniform
     const int f = min(lane + 64 * i, nfrag - 1);
-    const int kq = f & 3, t = (f >> 2) & 1, pg = pg0 + (f >> 3);
-    const int g = META ? meta[pg] : pg;
-    v[i] = *reinterpret_cast<const uint4*>(xr + (int64_t)g * kGroup + 16 * kq + 8 * t);
+    const int pg = pg0 + (f >> 3);
+    const uint32_t g = META ? (uint32_t)meta[pg] : (uint32_t)pg;
+    // element offset: group * 64 + quarter (f & 3) * 16 + k-step ((f >> 2) & 1) * 8, in 32-bit arithmetic (K < 2^31)
+    const uint32_t off = (g << 6) | ((uint32_t)(f & 3) << 4) | ((uint32_t)(f & 4) << 1);
+    v[i] = *reinterpret_cast<const uint4*>(xr + off);
   }
 }
 __device__ __forceinline__ void stage_private_finish(const uint4 (&v)[kPrivFrags], uint4* lds_x, float* lds_cneg, float cneg, int ng, int lane) {
@@ -685,7 +686,7 @@ __device__ __forceinline__ void stage_private_finish(const uint4 (&v)[kPrivFrags
       lds_x[f] = o;
       float sum = frag_sum(o);
       sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x104, 0xF, 0xF, true));  // + lane 4 up: the other k-step
-      if ((f & 4) == 0) lds_cneg[(f >> 3) * 4 + (f & 3)] = cneg * sum;
+      if ((f & 4) == 0) lds_cneg[((f >> 3) * 4 + (f & 3)) * 4] = cneg * sum;
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -1011,7 +1012,7 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
   al[0] = a.alpha[rtile * 16 + (lane & 15)];
   const float be_raw = a.beta[rtile * 16 + (lane & 15)];
   // private staging region of this wavefront: fragments, then start values
-  const int frag_cap = n * kNarrowGroupsPerTile * 8, cneg_cap = n * kNarrowGroupsPerTile * 4;
+  const int frag_cap = n * kNarrowGroupsPerTile * 8, cneg_cap = n * kNarrowGroupsPerTile * 16;
   uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
   float* my_cneg = reinterpret_cast<float*>(my_x + frag_cap);
   const uint8_t* codes = a.codes + (int64_t)rtile * a.row_tile_bytes + (int64_t)t0 * kNarrowTileBytes;
@@ -1155,7 +1156,7 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
   const dim3 grid((unsigned)L.row_tiles), block((unsigned)(64 * wk));
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (M == 1) {
-    const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 4);
+    const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 16);
     if (L.scale_mode == 0) {
       if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 0>), grid, block, lds, st, a);
       else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 0>), grid, block, lds, st, a);
@@ -1329,7 +1330,7 @@ int launch_skinny(const SkinnyCall& c) {
       a.KC[k] = std::max(1, std::min(per_wave, fit));
       a.SG[k] = gpt;
       pf = std::max<int64_t>(pf, (int64_t)a.KC[k] * gpt * T * 4);
-      pc = std::max<int64_t>(pc, (int64_t)a.KC[k] * gpt * 4);  // one start value per group and quarter
+      pc = std::max<int64_t>(pc, (int64_t)a.KC[k] * gpt * 16);  // one 16-byte record per group and quarter
     }
     a.frag_cap = (int)pf;
     a.cneg_cap = (int)pc;
