@@ -1186,15 +1186,25 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
   return CCQ_OK;
 }
 
-// y[p][n] = bf16( sum_s partial[s][p][n] ), splits added in index order.
-__global__ void ccq_reduce_splits_kernel(const float* partial, uint16_t* y, int64_t ldy, int rows, int N, int S) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// y[p][n] = bf16( sum_s partial[s][p][n] ), splits added in index order.  Four consecutive columns per thread (N is a
+// multiple of 16, partial and y rows are 16-byte aligned); all S requests of a thread go out before the first add.
+template <int SMAX>
+__global__ void __launch_bounds__(256) ccq_reduce_splits_kernel(const float* partial, uint16_t* y, int64_t ldy, int rows, int N, int S) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   const int64_t total = (int64_t)rows * N;
   if (i >= total) return;
-  float sum = partial[i];
-  for (int s = 1; s < S; ++s) sum += partial[(int64_t)s * total + i];
+  f32x4 v[SMAX];
+#pragma unroll
+  for (int s = 0; s < SMAX; ++s) v[s] = *reinterpret_cast<const f32x4*>(partial + (int64_t)min(s, S - 1) * total + i);
+  f32x4 sum = v[0];
+#pragma unroll
+  for (int s = 1; s < SMAX; ++s)
+    if (s < S) sum += v[s];
   const int64_t p = i / N, n = i % N;
-  y[p * ldy + n] = f32_to_bf16_rne(sum);
+  uint2 o;
+  o.x = (uint32_t)f32_to_bf16_rne(sum[0]) | ((uint32_t)f32_to_bf16_rne(sum[1]) << 16);
+  o.y = (uint32_t)f32_to_bf16_rne(sum[2]) | ((uint32_t)f32_to_bf16_rne(sum[3]) << 16);
+  *reinterpret_cast<uint2*>(y + p * ldy + n) = o;
 }
 
 // ---------------------------------------------------------------------------
@@ -1358,10 +1368,14 @@ int launch_skinny(const SkinnyCall& c) {
 }
 
 int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int S, void* stream) {
-  const int64_t total = (int64_t)rows * N;
+  const int64_t total = (int64_t)rows * N;  // a multiple of 16
   const int threads = 256;
-  hipLaunchKernelGGL(ccq_reduce_splits_kernel, dim3((unsigned)((total + threads - 1) / threads)), dim3(threads), 0, static_cast<hipStream_t>(stream),
-                     partial, static_cast<uint16_t*>(y), ldy, rows, N, S);
+  const dim3 grid((unsigned)((total / 4 + threads - 1) / threads)), block(threads);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint16_t* yy = static_cast<uint16_t*>(y);
+  if (S <= 4) hipLaunchKernelGGL(ccq_reduce_splits_kernel<4>, grid, block, 0, st, partial, yy, ldy, rows, N, S);
+  else if (S <= 8) hipLaunchKernelGGL(ccq_reduce_splits_kernel<8>, grid, block, 0, st, partial, yy, ldy, rows, N, S);
+  else hipLaunchKernelGGL(ccq_reduce_splits_kernel<kMaxSplitsK>, grid, block, 0, st, partial, yy, ldy, rows, N, S);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }
