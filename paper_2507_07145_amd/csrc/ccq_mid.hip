@@ -439,6 +439,217 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   }
 }
 
+// ---- narrow format: the same tile with the decoded weights kept in registers ----------------------------
+// A wavefront multiplies exactly the 32 columns it decodes, so the decoded tile need not pass through LDS: MFMA
+// 32x32x16 wants lane l to hold column l % 32 and eight k-slots of half l / 32, while the code stream gives lane l
+// row l % 16 of both of the wavefront's row tiles and quarter l / 16 of every group.  The *codes* (2 bits per
+// weight) are exchanged between lanes instead of the decoded weights: lane (half h, tile ti, row nl) fetches the
+// dwords of quarters 2h and 2h+1 of its own column from lanes nl + 16 (2h + q) with ds_bpermute, once per k-tile,
+// and then decodes 32 weights of one column per group: k-slots 8 kk .. 8 kk + 7 of MFMA step kk are weights
+// 32 h + 8 kk .. of the group, which is also how the activation fragment is read.  Only the activation tile
+// lives in LDS (18 KiB).
+template <int SM>
+__global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
+  constexpr int ROW = kMidRow;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);  // [2][kMidBM][ROW]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
+  const int split = blockIdx.y;
+  const int m0 = m_block * kMidBM, n0 = n_block * kMidBN;
+  const int nl = lane & 15;
+  const int ti = (lane >> 4) & 1, h = lane >> 5;  // the column this lane multiplies: row tile ti of the wavefront, row nl; k half h
+
+  const int tA = split * a.sq[kNarrow] + min(split, a.sr[kNarrow]);
+  const int tB = tA + a.sq[kNarrow] + (split < a.sr[kNarrow] ? 1 : 0);
+  const int nsteps = (tB - tA) * kNarrowGroupsPerTile;
+
+  const uint8_t* code_base[2];
+  const uint16_t* scale_base[2];
+  float al_t = 0.f, be_t = 0.f, ssup_t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int rtile = min(n0 / 16 + wave * 2 + i, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
+    code_base[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;
+    scale_base[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
+  }
+  {
+    const int rtile = min(n0 / 16 + wave * 2 + ti, a.row_tiles - 1);
+    al_t = a.alpha[rtile * 16 + nl];
+    be_t = a.beta[rtile * 16 + nl];
+    if constexpr (SM == 1) ssup_t = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+  }
+  uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u;
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(c43), "+s"(mask_n), "+v"(magic));
+
+  // raw code tiles as loaded (lane = row nl, quarter lane / 16, both row tiles), and the exchanged ones (this lane's
+  // column: ex[q] = the four groups' dwords of quarter 2h + q)
+  u32x4 craw[2], craw_next[2];
+  uint2 sraw[2], sraw_next[2];
+  u32x4 ex[2];
+  uint2 s_t;
+  auto load_codes = [&](u32x4 (&c)[2], uint2 (&sc)[2], int kt) {
+    kt = min(kt, a.tiles[kNarrow] - 1);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      c[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_base[i] + (int64_t)kt * kNarrowTileBytes + lane * 16));
+      if constexpr (SM == 0) sc[i] = *reinterpret_cast<const uint2*>(scale_base[i] + (int64_t)kt * kNarrowTileScaleHalfs + nl * 4);
+      else sc[i] = uint2{(uint32_t)scale_base[i][(int64_t)kt * kNarrowTileScaleHalfs4 + nl], 0u};
+    }
+  };
+  auto exchange = [&]() {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int src = (nl + 16 * (2 * h + q)) * 4;
+      u32x4 r;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const uint32_t r0 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)craw[0][d]);
+        const uint32_t r1 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)craw[1][d]);
+        r[d] = ti ? r1 : r0;
+      }
+      ex[q] = r;
+    }
+    s_t = ti ? sraw[1] : sraw[0];  // every quarter-lane of a row holds the row's scales
+  };
+
+  const uint16_t* xrow[2];
+  int a_lds_off[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, col = c & 7;
+    xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
+    a_lds_off[i] = row * ROW + col * 8;
+  }
+  auto load_a = [&](u32x4 (&dst)[2], int s) {
+    const int64_t off = (int64_t)(tA * kNarrowGroupsPerTile + min(s, nsteps - 1)) * kGroup;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) dst[i] = *reinterpret_cast<const u32x4*>(xrow[i] + off);
+  };
+  auto store_a = [&](int buf, const u32x4 (&src)[2]) {
+    uint16_t* dst = As + buf * kMidBM * ROW;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = src[i];
+  };
+
+  // group j of the held k-tile: 32 weights of this lane's column, as four MFMA B fragments
+  auto decode = [&](u32x4 (&bf)[4], int j) {
+    float s;
+    if constexpr (SM == 0) {
+      const uint32_t sd = (j >> 1) ? s_t.y : s_t.x;
+      s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+    } else {
+      s = (float)((s_t.x >> (4 * j)) & 0xFu) * ssup_t;
+    }
+    const float c0 = -(128.f + a.zp[kNarrow]) * s;
+    const float bem = be_t + magic;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const uint32_t d = dword_sel(ex[q], j);
+      uint32_t o[8];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al_t, bem);
+        const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code (Alg. 3)
+        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 7, mask_n, c43)), s, c0);
+        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 10, mask_n, c43)), s, c0);
+        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 13, mask_n, c43)), s, c0);
+        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 16, mask_n, c43)), s, c0);
+        o[2 * b] = pack_bf16_m(w0, w1);
+        o[2 * b + 1] = pack_bf16_m(w2, w3);
+      }
+      bf[2 * q] = u32x4{o[0], o[1], o[2], o[3]};
+      bf[2 * q + 1] = u32x4{o[4], o[5], o[6], o[7]};
+    }
+  };
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  const int a_frag_off = (lane & 31) * ROW + h * 32;
+  auto multiply = [&](int buf, const u32x4 (&bf)[4]) {
+    const uint16_t* Ab = As + buf * kMidBM * ROW + a_frag_off;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const bf16x8 af = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * ROW + kk * 8));
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, __builtin_bit_cast(bf16x8, bf[kk]), acc[i], 0, 0, 0);
+      }
+    }
+  };
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  };
+
+  {
+    u32x4 areg[4][2];
+    u32x4 bcur[4], bnext[4];
+    int s = 0;
+    load_codes(craw, sraw, tA);
+    load_a(areg[0], 0);
+    load_a(areg[1], 1);
+    load_a(areg[2], 2);
+    load_a(areg[3], 3);
+    store_a(0, areg[0]);
+    exchange();
+    decode(bcur, 0);
+    lds_barrier();
+    // one step (J = s & 3): the activation tile of step s is multiplied with the fragments decoded during the previous
+    // step, while the fragments of step s + 1 are decoded and its activation tile goes to the other LDS buffer
+    auto step = [&](auto JC, auto&& prepare_next) {
+      constexpr int J = decltype(JC)::value;
+      constexpr int P = J & 1;
+      load_a(areg[J], s + 4);
+      prepare_next();
+      multiply(P, bcur);
+      store_a(P ^ 1, areg[(J + 1) & 3]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) bcur[k] = bnext[k];
+      lds_barrier();
+      ++s;
+    };
+    using J0 = std::integral_constant<int, 0>;
+    using J1 = std::integral_constant<int, 1>;
+    using J2 = std::integral_constant<int, 2>;
+    using J3 = std::integral_constant<int, 3>;
+    for (int t = tA; t < tB; ++t) {
+      load_codes(craw_next, sraw_next, t + 1);
+      step(J0{}, [&]() { decode(bnext, 1); });
+      step(J1{}, [&]() { decode(bnext, 2); });
+      step(J2{}, [&]() { decode(bnext, 3); });
+      step(J3{}, [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) { craw[i] = craw_next[i]; sraw[i] = sraw_next[i]; }
+        exchange();
+        decode(bnext, 0);  // of the next k-tile (a repeat of the last one after the last: not used)
+      });
+    }
+  }
+
+  const int n = n0 + wave * 32 + (lane & 31);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      const float val = acc[i][r];
+      if (m < a.M && n < a.N) {
+        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + m) * a.N + n] = val;
+        else a.y[(int64_t)m * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
+      }
+    }
+  }
+}
+
 // K shares for the mid-M kernel.  The kernel is bound by instruction issue, and a second workgroup on a CU
 // adds only about 15 %, while every share costs a pass of fp32 partial tiles through memory (written, then
 // read by the reduction): aim at one workgroup per CU, at least two k-tiles of every format per share.
@@ -482,6 +693,14 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   const int n_blocks = (L.N + kMidBN - 1) / kMidBN;
   const int fm = L.h16 ? 4 : (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
   const int max_steps = ((L.tiles[kNarrow] + S - 1) / S) * kNarrowGroupsPerTile + ((L.tiles[kWide] + S - 1) / S) * kWideGroupsPerTile;
+  if (fm == 1) {  // narrow format only: decoded weights stay in registers
+    const size_t lds_r = (size_t)2 * kMidBM * kMidRow * 2;
+    dim3 grid_r((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block_r(256);
+    if (L.scale_mode == 0) hipLaunchKernelGGL(ccq_midr_narrow_kernel<0>, grid_r, block_r, lds_r, static_cast<hipStream_t>(stream), a);
+    else hipLaunchKernelGGL(ccq_midr_narrow_kernel<1>, grid_r, block_r, lds_r, static_cast<hipStream_t>(stream), a);
+    if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+    return CCQ_OK;
+  }
   const size_t lds = (size_t)2 * (kMidBM + kMidBN) * (fm == 4 ? kMidRowH16 : kMidRow) * 2 + (fm == 3 ? (size_t)max_steps * 4 : 0);
   if (lds > (fm == 4 ? 72 : 64) * 1024) return CCQ_ERR_UNSUPPORTED;
   typedef void (*MidKernel)(const MidArgs);
