@@ -128,11 +128,15 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
 using namespace ccq;
 
 // Which kernel a dense call of M rows uses when no launch shape is given.
-enum DensePath { kPathGemv, kPathSkinny, kPathMid, kPathPrefill };
+enum DensePath { kPathGemv, kPathSkinny, kPathRows, kPathMid, kPathPrefill };
 static DensePath dense_path(const Layout& L, int M) {
-  const bool narrow_only = L.tiles[kWide] == 0;
+  const bool narrow_only = L.tiles[kWide] == 0, wide_only = L.tiles[kNarrow] == 0;
   if (M <= kGemvMaxM && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
+  // per-group activation tiles with the weights in registers: measured faster than its neighbours for 5-16 rows on the
+  // wide and hybrid-word formats (whose whole-k-tile staging is the costliest) and for 17-32 rows on the narrow one
+  if (wide_only && M > kGemvMaxM && M < kMidMinM) return kPathRows;
   if (M < kMidMinM) return kPathSkinny;
+  if (narrow_only && M <= 32) return kPathRows;
   if (narrow_only && M > 128) return kPathPrefill;            // 256-row tiles pay off
   return kPathMid;
 }
@@ -142,8 +146,8 @@ static int64_t dense_workspace_bytes(const Layout& L, int M) {
   for (int m = 1; m <= M; ++m) {
     const DensePath p = dense_path(L, m);
     if (p == kPathPrefill) continue;
-    if (p == kPathMid) {
-      const int S = mid_splits(L, m);
+    if (p == kPathMid || p == kPathRows) {
+      const int S = p == kPathMid ? mid_splits(L, m) : rows_splits(L, m);
       if (S > 1) need = std::max(need, (int64_t)S * m * L.N * 4);
     } else {
       Decomp d = choose_decomp(L, m, 1, m);
@@ -341,6 +345,18 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
     if (path == kPathPrefill) {
       rc = launch_prefill(w, L, x, M, ldx, y, ldy, stream);
       if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    }
+    if (path == kPathRows) {
+      const int S = rows_splits(L, M);
+      float* partial = nullptr;
+      if (S > 1) {
+        const int64_t need = (int64_t)S * M * L.N * 4;
+        if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
+        partial = static_cast<float*>(workspace);
+      }
+      rc = launch_rows(w, L, x, M, ldx, y, ldy, partial, S, stream);
+      if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
+      return rc;
     }
     // a few dozen rows (or many rows on wide / mixed formats): the 64-row LDS-tiled kernel
     if (path == kPathMid || path == kPathPrefill) {

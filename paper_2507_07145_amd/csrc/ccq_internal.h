@@ -114,6 +114,11 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
 // y[m][n] = bf16(sum_s partial[s][m][n]), shares added in index order (ccq_skinny.hip).
 int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int S, void* stream);
 
+// Per-group activation tiles, weights in registers (ccq_skinny.hip): up to 64 rows per workgroup, any format mix.
+int rows_splits(const Layout& L, int M);
+int launch_rows(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
+                void* stream);
+
 // Large-M kernel for narrow-format weights (ccq_prefill.hip).
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 

@@ -34,6 +34,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "ccq_internal.h"
 
@@ -1205,6 +1206,330 @@ __global__ void __launch_bounds__(256) ccq_reduce_splits_kernel(const float* par
   o.x = (uint32_t)f32_to_bf16_rne(sum[0]) | ((uint32_t)f32_to_bf16_rne(sum[1]) << 16);
   o.y = (uint32_t)f32_to_bf16_rne(sum[2]) | ((uint32_t)f32_to_bf16_rne(sum[3]) << 16);
   *reinterpret_cast<uint2*>(y + p * ldy + n) = o;
+}
+
+// ---- 17 to 128 activation rows, dense: the per-row-tile contraction fed by a per-group activation tile ------
+// With several 16-row activation tiles held, staging whole k-tiles of activations (above) exposes a memory
+// latency, a gather and two barriers per chunk.  Here a workgroup of four wavefronts (four 16-row weight tiles)
+// walks K one 64-weight group per step: the 16 MT x 64 activation tile of the step after next is requested, the
+// one of the next step is written to the other LDS buffer as MFMA A fragments (already in k-slot order) together
+// with the accumulator start values -(128 + zp) sum_k x (the lanes that hold one row's fragments sit side by
+// side, so the sum is a few lane shuffles), and the current one is multiplied.  The weights never pass through LDS
+// and are decoded exactly as in the kernels above (bf16 integers, scale applied after the group's contraction),
+// so the results are those of the per-row-tile kernel, not bf16-rounded weights.
+struct RowsArgs {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const int32_t* meta;
+  const uint16_t* scale_super;
+  const uint16_t* x;
+  uint16_t* y;
+  float* partial;
+  int64_t ldx, ldy;
+  int64_t row_tile_bytes, row_tile_scale_halfs;
+  int32_t M, N, row_tiles, m_blocks;
+  int32_t tiles[2];
+  int32_t groups_narrow;
+  int32_t sq[2], sr[2];  // K shares, as in SkinnyArgs
+  float cneg[2];
+};
+
+template <int MT, int FM, int SM>
+__global__ void __launch_bounds__(256) ccq_rows_kernel(const RowsArgs a) {
+  constexpr int KN = kNarrow | (SM << 1), KW = kWide | (SM << 1) | (FM == 4 ? kH16 : 0);
+  constexpr bool HAS_N = FM == 1 || FM == 3, HAS_W = FM >= 2, META = FM == 3;
+  constexpr int MRT = 16 * MT;
+  constexpr int RS = HAS_W ? 13 : 9;  // 16-byte fragments per LDS row: 8 or 12, plus one of padding (odd: conflict-free)
+  constexpr int NPN = (MRT + 31) / 32, NPW = MRT / 16;  // staging passes: 8 lanes per row (narrow), 16 lanes per row (wide kinds)
+  constexpr int NP = HAS_W ? NPW : NPN;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint4* As = reinterpret_cast<uint4*>(smem);                          // [2][MRT][RS]
+  float* Cn = reinterpret_cast<float*>(smem + (size_t)2 * MRT * RS * 16);  // [2][MRT]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
+  const int split = blockIdx.y;
+  const int m0 = m_block * MRT;
+  const int kq = lane >> 4, nl = lane & 15;
+
+  int tA[2], tB[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    tA[k] = split * a.sq[k] + min(split, a.sr[k]);
+    tB[k] = tA[k] + a.sq[k] + (split < a.sr[k] ? 1 : 0);
+  }
+
+  const int rtile_raw = n_block * 4 + wave;
+  const bool active = rtile_raw < a.row_tiles;
+  const int rtile = min(rtile_raw, a.row_tiles - 1);  // a ragged last block re-decodes the last tile; nothing of it is stored
+  const uint8_t* codes_n = a.codes + (int64_t)rtile * a.row_tile_bytes;
+  const uint8_t* codes_w = codes_n + (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
+  const uint16_t* scales_n = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
+  const uint16_t* scales_w = scales_n + (int64_t)a.tiles[kNarrow] * Traits<KN>::SCALE_HALFS;
+  float al = 0.f, be_raw = 0.f;
+  if constexpr (HAS_N) {
+    al = a.alpha[rtile * 16 + nl];
+    be_raw = a.beta[rtile * 16 + nl];
+  }
+  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+s"(dc.mask[2]), "+v"(magic));
+  if constexpr (SM == 1) dc.ssup[0] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+
+  // ---- activation staging: thread -> (row, fragment) -------------------------------------------------------
+  // narrow: 8 lanes per row, lane c holds elements 8c .. 8c+7 = fragment (quarter c / 2, k-step c % 2);
+  // wide kinds: 16 lanes per row, lane c < 12 holds fragment (quarter c % 4, k-step c / 4), the others nothing
+  const uint16_t* xrow[NP];
+  bool xvalid[NP];
+  auto rows_of = [&](int lpr, int u) -> int { return tid / lpr + u * (256 / lpr); };
+  auto request = [&](uint4 (&v)[NP], int kind, int g) {
+    if (HAS_N && (!HAS_W || kind == kNarrow)) {
+#pragma unroll
+      for (int u = 0; u < NPN; ++u) v[u] = *reinterpret_cast<const uint4*>(xrow[u] + (int64_t)g * kGroup + (tid & 7) * 8);
+    } else {
+      const int c = min(tid & 15, 11);
+#pragma unroll
+      for (int u = 0; u < NPW; ++u) v[u] = load_chunk16(xrow[u] + (int64_t)g * kGroup + frag_first_element<KW>(c & 3, c >> 2));
+    }
+  };
+  // xrow / xvalid depend on the lanes-per-row of the kind; a mixed matrix switches once, from narrow to wide
+  auto set_rows = [&](int lpr) {
+#pragma unroll
+    for (int u = 0; u < NP; ++u) {
+      const int m = rows_of(lpr, u);
+      xvalid[u] = m < MRT && m0 + m < a.M;
+      xrow[u] = a.x + (int64_t)min(m0 + min(m, MRT - 1), a.M - 1) * a.ldx;
+    }
+  };
+  auto commit = [&](int buf, const uint4 (&v)[NP], int kind) {
+    uint4* dst = As + (size_t)buf * MRT * RS;
+    float* cn = Cn + buf * MRT;
+    if (HAS_N && (!HAS_W || kind == kNarrow)) {
+      const int c = tid & 7;
+#pragma unroll
+      for (int u = 0; u < NPN; ++u) {
+        const int m = rows_of(8, u);
+        uint4 o = {0u, 0u, 0u, 0u};
+        if (xvalid[u]) {
+          o.x = __builtin_amdgcn_perm(v[u].z, v[u].x, 0x05040100u);
+          o.y = __builtin_amdgcn_perm(v[u].z, v[u].x, 0x07060302u);
+          o.z = __builtin_amdgcn_perm(v[u].w, v[u].y, 0x05040100u);
+          o.w = __builtin_amdgcn_perm(v[u].w, v[u].y, 0x07060302u);
+        }
+        if (m < MRT) dst[m * RS + (c & 1) * 4 + (c >> 1)] = o;  // with 16 rows held half of the threads have no row
+        float sum = frag_sum(o);
+        sum += __shfl_xor(sum, 1);
+        sum += __shfl_xor(sum, 2);
+        sum += __shfl_xor(sum, 4);
+        if (c == 0 && m < MRT) cn[m] = a.cneg[kNarrow] * sum;
+      }
+    } else {
+      const int c = tid & 15;
+#pragma unroll
+      for (int u = 0; u < NPW; ++u) {
+        const int m = rows_of(16, u);
+        uint4 o = {0u, 0u, 0u, 0u};
+        if (xvalid[u] && c < 12) o = frag_from_chunk<KW>(v[u], c & 3, c >> 2);
+        if (c < 12) dst[m * RS + c] = o;
+        float sum = frag_sum(o);
+        sum += __shfl_xor(sum, 1);
+        sum += __shfl_xor(sum, 2);
+        sum += __shfl_xor(sum, 4);
+        sum += __shfl_xor(sum, 8);
+        if (c == 0) cn[m] = a.cneg[kWide] * sum;
+      }
+    }
+  };
+
+  f32x4 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // group j of the held k-tile against the activation tile in LDS buffer `buf`
+  auto contract = [&](auto kind_c, const auto& r, const uint32_t (&fields)[4], int buf, int j, float be) {
+    constexpr int KIND = decltype(kind_c)::value;
+    using TR = Traits<KIND>;
+    const uint4* src = As + (size_t)buf * MRT * RS;
+    const float* cn = Cn + buf * MRT;
+    f32x4 P[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) P[mt] = *reinterpret_cast<const f32x4*>(cn + mt * 16 + 4 * kq);
+#pragma unroll
+    for (int t = 0; t < TR::T; ++t) {
+      const bf16x8 wf = decode_frag<KIND>(r, j, t, al, be, dc.c4300, dc.mask[(KIND & kH16) ? 2 : (KIND & 1)]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const uint4 xa = src[(mt * 16 + nl) * RS + t * 4 + kq];
+        P[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa), wf, P[mt], 0, 0, 0);
+      }
+    }
+    const float s = group_scale<KIND>(r, fields, dc.ssup[0], j);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[mt][e] = __builtin_fmaf(s, P[mt][e], acc[mt][e]);
+    }
+  };
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  };
+
+  // steps of this share: the groups of its narrow k-tiles, then those of its wide ones
+  const int nsN = HAS_N ? (tB[kNarrow] - tA[kNarrow]) * kNarrowGroupsPerTile : 0;
+  const int nsW = HAS_W ? (tB[kWide] - tA[kWide]) * kWideGroupsPerTile : 0;
+  const int nsteps = nsN + nsW;
+  auto kind_of = [&](int s) -> int { return (HAS_N && (!HAS_W || s < nsN)) ? kNarrow : kWide; };
+  auto group_of = [&](int s) -> int {  // original group (activation columns) of step s
+    s = min(s, nsteps - 1);
+    const int pg = s < nsN ? tA[kNarrow] * kNarrowGroupsPerTile + s : a.groups_narrow + tA[kWide] * kWideGroupsPerTile + (s - nsN);
+    if constexpr (META) return a.meta[pg];
+    return s < nsN ? pg : pg - a.groups_narrow;
+  };
+
+  uint4 areg[2][NP];
+  int s = 0;
+  set_rows(kind_of(0) == kNarrow ? 8 : 16);
+  request(areg[0], kind_of(0), group_of(0));
+  if (HAS_N && HAS_W && nsN == 1) set_rows(16);  // not reachable: narrow groups come in k-tiles of four
+  request(areg[1], kind_of(min(1, nsteps - 1)), group_of(1));
+  commit(0, areg[0], kind_of(0));
+  lds_barrier();
+  const float be = be_raw + magic;  // Code Cluster offset + 2^23 (exact: beta is an integer below 2^15)
+  const uint32_t nofields[4] = {0u, 0u, 0u, 0u};
+
+  // one step: request the tile of step s + 2, multiply step s, write the tile of step s + 1
+  auto step = [&](auto JC, auto&& multiply_this) {
+    constexpr int J = decltype(JC)::value;
+    const int s2 = min(s + 2, nsteps - 1), s1 = min(s + 1, nsteps - 1);
+    uint4 keep[NP];
+#pragma unroll
+    for (int u = 0; u < NP; ++u) keep[u] = areg[J ^ 1][u];  // step s + 1, requested one step ago
+    if (HAS_N && HAS_W && kind_of(s2) != kind_of(s1)) {
+      // the request two steps ahead is the first of the other kind: it needs that kind's row assignment, and the
+      // commit below still needs the old one -- commit first
+      multiply_this(J);
+      commit(J ^ 1, keep, kind_of(s1));
+      set_rows(16);
+      request(areg[J], kind_of(s2), group_of(s + 2));
+    } else {
+      request(areg[J], kind_of(s2), group_of(s + 2));
+      multiply_this(J);
+      commit(J ^ 1, keep, kind_of(s1));
+    }
+    lds_barrier();
+    ++s;
+  };
+  using J0 = std::integral_constant<int, 0>;
+  using J1 = std::integral_constant<int, 1>;
+
+  if constexpr (HAS_N) {
+    TileRegs<KN> cur, nxt;
+    load_tile<KN>(cur, codes_n, scales_n, tA[kNarrow], lane);
+    for (int t = tA[kNarrow]; t < tB[kNarrow]; ++t) {
+      load_tile<KN>(nxt, codes_n, scales_n, min(t + 1, a.tiles[kNarrow] - 1), lane);
+      step(J0{}, [&](int buf) { contract(std::integral_constant<int, KN>{}, cur, nofields, buf, 0, be); });
+      step(J1{}, [&](int buf) { contract(std::integral_constant<int, KN>{}, cur, nofields, buf, 1, be); });
+      step(J0{}, [&](int buf) { contract(std::integral_constant<int, KN>{}, cur, nofields, buf, 2, be); });
+      step(J1{}, [&](int buf) { contract(std::integral_constant<int, KN>{}, cur, nofields, buf, 3, be); });
+      cur = nxt;
+    }
+  }
+  if constexpr (HAS_W) {
+    TileRegs<KW> cur, nxt;
+    load_tile<KW>(cur, codes_w, scales_w, tA[kWide], lane);
+    for (int t = tA[kWide]; t < tB[kWide]; ++t) {
+      load_tile<KW>(nxt, codes_w, scales_w, min(t + 1, a.tiles[kWide] - 1), lane);
+      uint32_t fields[4] = {0u, 0u, 0u, 0u};
+      tile_scale_fields<KW>(fields, cur, lane);
+      step(J0{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 0, be); });
+      step(J1{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 1, be); });
+      step(J0{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 2, be); });
+      step(J1{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 3, be); });
+      step(J0{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 4, be); });
+      step(J1{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 5, be); });
+      step(J0{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 6, be); });
+      step(J1{}, [&](int buf) { contract(std::integral_constant<int, KW>{}, cur, fields, buf, 7, be); });
+      cur = nxt;
+    }
+  }
+
+  if (active) {
+    const int n = rtile * 16 + nl;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int m = m0 + mt * 16 + 4 * kq + e;
+        if (m < a.M) {
+          if (gridDim.y > 1) a.partial[((int64_t)split * a.M + m) * a.N + n] = acc[mt][e];
+          else a.y[(int64_t)m * a.ldy + n] = f32_to_bf16_rne(acc[mt][e]);
+        }
+      }
+    }
+  }
+}
+
+// K shares for ccq_rows_kernel: about four workgroups per CU, at least one k-tile of every format per share.
+int rows_splits(const Layout& L, int M) {
+  const int mrt = M > 32 ? 64 : (M > 16 ? 32 : 16);
+  const int64_t blocks = (int64_t)((M + mrt - 1) / mrt) * ((L.row_tiles + 3) / 4);
+  const int min_tiles = std::min(L.tiles[kNarrow] > 0 ? L.tiles[kNarrow] : 1 << 30, L.tiles[kWide] > 0 ? L.tiles[kWide] : 1 << 30);
+  int64_t s = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, blocks));
+  s = std::min<int64_t>(s, 8);
+  s = std::min<int64_t>(s, std::max(1, min_tiles));
+  return (int)s;
+}
+
+int launch_rows(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
+                void* stream) {
+  RowsArgs a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.meta = static_cast<const int32_t*>(w->meta);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.partial = partial;
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.row_tile_bytes = L.row_tile_bytes;
+  a.row_tile_scale_halfs = L.row_tile_scale_halfs;
+  a.M = M;
+  a.N = L.N;
+  a.row_tiles = L.row_tiles;
+  const int mt = M > 32 ? 4 : (M > 16 ? 2 : 1);
+  a.m_blocks = (M + 16 * mt - 1) / (16 * mt);
+  a.groups_narrow = L.groups[kNarrow];
+  for (int k = 0; k < 2; ++k) {
+    a.tiles[k] = L.tiles[k];
+    a.sq[k] = L.tiles[k] / S;
+    a.sr[k] = L.tiles[k] % S;
+    a.cneg[k] = -(128.f + L.zp[k]);
+    if (L.tiles[k] > 0 && a.sq[k] == 0) return CCQ_ERR_BAD_PARAM;  // every share needs a k-tile of every format present
+  }
+  const int fm = L.h16 ? 4 : (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
+  // built where it is the fastest path: 16 held rows on the wide and hybrid-word formats, 32 on the narrow one
+  typedef void (*RowsKernel)(const RowsArgs);
+  RowsKernel kern = nullptr;
+  const bool cs = L.scale_mode == 1;
+  if (mt == 1 && fm == 2) kern = cs ? ccq_rows_kernel<1, 2, 1> : ccq_rows_kernel<1, 2, 0>;
+  else if (mt == 1 && fm == 4) kern = cs ? ccq_rows_kernel<1, 4, 1> : ccq_rows_kernel<1, 4, 0>;
+  else if (mt == 2 && fm == 1) kern = cs ? ccq_rows_kernel<2, 1, 1> : ccq_rows_kernel<2, 1, 0>;
+  if (!kern) return CCQ_ERR_UNSUPPORTED;
+  const int rs = fm == 1 ? 9 : 13;
+  const size_t lds = (size_t)2 * 16 * mt * rs * 16 + (size_t)2 * 16 * mt * 4;
+  const int n_blocks = (L.row_tiles + 3) / 4;
+  dim3 grid((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block(256);
+  hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
+  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+  return CCQ_OK;
 }
 
 // ---------------------------------------------------------------------------

@@ -149,6 +149,21 @@ def test_mid_kernel_formats(kinds, K, N, M, n_wide):
     assert np.array_equal(canon_zero(got), canon_zero(want)), f"mid kernel {kinds}: decoded weights differ"
 
 
+@pytest.mark.parametrize("kinds,K,N,M", [(["wide"], 1024, 48, 7), (["wide"], 4096, 64, 9), (["wide"], 512, 208, 16), (["wide"], 2048, 16, 5),
+                                         (["narrow"], 1280, 80, 20), (["narrow"], 4096, 48, 32), (["narrow"], 256, 144, 17)])
+def test_per_group_tile_kernel(kinds, K, N, M):
+    """5-16 rows on the wide format and 17-32 rows on the narrow one go through the kernel that stages one activation
+    tile per 64-weight group: ragged last row block (fewer than four row tiles), K cut into shares, rows past M in the
+    last activation tile; decoded weights exact, products within the tolerance of the exact-weight kernels."""
+    c = random_case(K, N, kinds, 9, stream0=N + M)
+    w = c.device_weight(DEV)
+    x = synth.activations_bf16(M, K, synth.rng(9, 500 + M))
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"{kinds} K={K} N={N} M={M}")
+    ks = synth.rng(9, 600 + M).integers(0, K, M)
+    ks[:5] = [0, 63, 64, K - 1, K - 64]
+    _check_decode(c, w, ks)
+
+
 @pytest.mark.parametrize("K,N", [(2048, 96), (8192, 64), (1280, 48)])
 def test_two_to_four_rows(K, N):
     """2..4 rows on narrow-format weights: the GEMV kernel with MFMA 4x4x4 fed four different rows (K = 1280 does not
