@@ -1237,7 +1237,7 @@ struct RowsArgs {
 };
 
 template <int MT, int FM, int SM>
-__global__ void __launch_bounds__(256) ccq_rows_kernel(const RowsArgs a) {
+__global__ void __launch_bounds__(256, 2) ccq_rows_kernel(const RowsArgs a) {
   constexpr int KN = kNarrow | (SM << 1), KW = kWide | (SM << 1) | (FM == 4 ? kH16 : 0);
   constexpr bool HAS_N = FM == 1 || FM == 3, HAS_W = FM >= 2, META = FM == 3;
   constexpr int MRT = 16 * MT;
@@ -1406,20 +1406,18 @@ __global__ void __launch_bounds__(256) ccq_rows_kernel(const RowsArgs a) {
   auto step = [&](auto JC, auto&& multiply_this) {
     constexpr int J = decltype(JC)::value;
     const int s2 = min(s + 2, nsteps - 1), s1 = min(s + 1, nsteps - 1);
-    uint4 keep[NP];
-#pragma unroll
-    for (int u = 0; u < NP; ++u) keep[u] = areg[J ^ 1][u];  // step s + 1, requested one step ago
+    // areg[J ^ 1] holds step s + 1, requested one step ago; areg[J] (step s, already in LDS) is free for step s + 2
     if (HAS_N && HAS_W && kind_of(s2) != kind_of(s1)) {
       // the request two steps ahead is the first of the other kind: it needs that kind's row assignment, and the
       // commit below still needs the old one -- commit first
       multiply_this(J);
-      commit(J ^ 1, keep, kind_of(s1));
+      commit(J ^ 1, areg[J ^ 1], kind_of(s1));
       set_rows(16);
       request(areg[J], kind_of(s2), group_of(s + 2));
     } else {
       request(areg[J], kind_of(s2), group_of(s + 2));
       multiply_this(J);
-      commit(J ^ 1, keep, kind_of(s1));
+      commit(J ^ 1, areg[J ^ 1], kind_of(s1));
     }
     lds_barrier();
     ++s;
