@@ -114,7 +114,8 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
 // y[m][n] = bf16(sum_s partial[s][m][n]), shares added in index order (ccq_skinny.hip).
 int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int S, void* stream);
 
-// Per-group activation tiles, weights in registers (ccq_skinny.hip): up to 64 rows per workgroup, any format mix.
+// Per-group activation tiles, weights in registers (ccq_skinny.hip).  Built for up to 16 rows on wide-only and
+// hybrid-word layouts and for 17-32 rows on narrow-only ones; CCQ_ERR_UNSUPPORTED otherwise.
 int rows_splits(const Layout& L, int M);
 int launch_rows(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
                 void* stream);

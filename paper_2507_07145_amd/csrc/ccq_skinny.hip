@@ -299,8 +299,6 @@ __device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, const uint
   }
 }
 
-__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __builtin_bit_cast(float, bits16 << 16); }
-
 // Sum of the eight bf16 values of a fragment in fp32: four two-element dot products against (1, 1).
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 __device__ __forceinline__ float frag_sum(const uint4 o) {
