@@ -282,20 +282,22 @@ __device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, in
   return __builtin_bit_cast(bf16x8, o);
 }
 
-// Scale of group j of the tile.  fp16 group scales, or (Alg. 2 / Alg. 3, first line) the 4-bit field (13-bit for
-// the hybrid word) times the row's super scale: exact in fp32 (at most 13-bit integer times 11-bit significand).
+// Scale of group j of the tile.  fp16 group scales; or, with compressed scales (Alg. 2 / Alg. 3, first line: field
+// times the row's super scale), the field alone: the super scale is the same for every group of a row, so the
+// kernels accumulate sum_g field_g * (group result) and multiply by it once, before the store.  For one-hot
+// activations that is the same single rounding of field * s_super * (state - zp) as scaling group by group.
 template <int KIND>
-__device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, const uint32_t (&fields)[4], float ssup, int j) {
+__device__ __forceinline__ float group_scale(const TileRegs<KIND>& r, const uint32_t (&fields)[4], int j) {
   if constexpr ((KIND & kScale4) == 0) {
     const uint32_t d = r.s[j >> 1];
     const uint16_t h = (uint16_t)((j & 1) ? (d >> 16) : (d & 0xFFFFu));
     return (float)__builtin_bit_cast(_Float16, h);
   } else if constexpr ((KIND & 1) == kNarrow) {
-    return (float)((r.s[0] >> (4 * j)) & 0xFu) * ssup;
+    return (float)((r.s[0] >> (4 * j)) & 0xFu);
   } else if constexpr ((KIND & kH16) != 0) {
-    return (float)((fields[j >> 1] >> (16 * (j & 1))) & 0x1FFFu) * ssup;
+    return (float)((fields[j >> 1] >> (16 * (j & 1))) & 0x1FFFu);
   } else {
-    return (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu) * ssup;
+    return (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu);
   }
 }
 
@@ -464,7 +466,7 @@ __device__ __forceinline__ void process_tile(const TileRegs<KIND> (&r)[RT], int 
     }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-      const float s = group_scale<KIND>(r[rt], fields[rt], dc.ssup[rt], j);
+      const float s = group_scale<KIND>(r[rt], fields[rt], j);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         acc[rt][mt][0] = __builtin_fmaf(s, P[rt][mt][0], acc[rt][mt][0]);
@@ -918,6 +920,11 @@ __global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         if (rtile0 + rt >= a.row_tiles) continue;
+        if constexpr (SM == 1) acc[rt][0] *= dc.ssup[rt];  // compressed scales: the row's super scale, once (see group_scale)
+        if constexpr (SM == 1 && MT > 1) {
+#pragma unroll
+          for (int mt = 1; mt < MT; ++mt) acc[rt][mt] *= dc.ssup[rt];
+        }
         const int n = (rtile0 + rt) * 16 + (lane & 15);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -1049,6 +1056,7 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
       for (int k = 1; k < nwaves; ++k) v += red[(k - 1) * 16 + lane];
     }
   }
+  if constexpr (SM == 1) v *= dc.ssup[0];  // compressed scales: the row's super scale, once (see group_scale)
   if (wave == 0 && lane < 16) a.y[rtile * 16 + lane] = f32_to_bf16_rne(v);
 }
 
@@ -1117,6 +1125,7 @@ __global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args a
       for (int k = 1; k < nwaves; ++k) v += red[(k - 1) * 16 + lane];
     }
   }
+  if constexpr (SM == 1) v *= dc.ssup[0];  // compressed scales: the row's super scale, once (see group_scale)
   if (wave == 0 && lane < 16) {
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -1364,7 +1373,7 @@ __global__ void __launch_bounds__(256, 2) ccq_rows_kernel(const RowsArgs a) {
         P[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa), wf, P[mt], 0, 0, 0);
       }
     }
-    const float s = group_scale<KIND>(r, fields, dc.ssup[0], j);
+    const float s = group_scale<KIND>(r, fields, j);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -1458,6 +1467,7 @@ __global__ void __launch_bounds__(256, 2) ccq_rows_kernel(const RowsArgs a) {
     const int n = rtile * 16 + nl;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
+      if constexpr (SM == 1) acc[mt] *= dc.ssup[0];  // compressed scales: the row's super scale, once (see group_scale)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int m = m0 + mt * 16 + 4 * kq + e;
