@@ -97,9 +97,8 @@ typedef struct {
   const void *meta;         /* DEVICE, group map in device order (ccq_pack_meta); may be NULL when group_fmt is NULL */
   int32_t scale_mode;       /* 0 = fp16 group scales; 1 = compressed scales of Sec. 3.4: group scale =
                                4-bit (hybrid word: 13-bit) field * scale_super[n] (first line of Alg. 2 / Alg. 3).  Mode 1 is
-                               built for ccq_gemm at any M with the launch shape chosen by the library
-                               and for ccq_grouped_gemm; launch shapes that hold more than 16 rows in the
-                               skinny kernel return CCQ_ERR_UNSUPPORTED                               */
+                               built in every entry point; the per-row-tile kernel then holds 16 rows at
+                               a time whatever launch shape is asked for                              */
   const void *scale_super;  /* DEVICE, fp16[N]: per-output-channel super scale s_super (scale_mode 1) */
 } ccq_weight;
 
@@ -161,9 +160,7 @@ int ccq_gemm_ex(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void
  * e * {codes,scales,ab}_stride bytes after expert 0's (ab_stride for code_alpha
  * and code_beta; with scale_mode 1 it must be given, at least 4 N, also for
  * weights without Code Cluster, and expert e's scale_super starts e * ab_stride / 2
- * bytes after expert 0's: fp16 where alpha and beta are fp32).  With scale_mode 1
- * at most 16 rows per expert fit one pass; routings that would need more return
- * CCQ_ERR_UNSUPPORTED.
+ * bytes after expert 0's: fp16 where alpha and beta are fp32).
  *   Output row p in [expert_offsets[e], expert_offsets[e+1]) is
  *       y[p][:] = x[sorted_rows[p]][:] * W_dq(e)^T.
  *   x DEVICE bf16 [T][ldx]; sorted_rows DEVICE int32 [P], values in [0,T);

@@ -1560,7 +1560,7 @@ static SkinnyKernel pick_rt(int rt, int fm) {
   return pick_fm<MT, MR, 1, SM>(fm);
 }
 
-// Compressed scales (sm = 1) are built for up to 16 held rows; more rows go to the 64-row kernel.
+// Compressed scales (sm = 1) are built for up to 16 held rows (the launcher never asks for more).
 static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm, int sm) {
   if (sm == 1) {
     if (mt != 1) return nullptr;
@@ -1578,7 +1578,8 @@ static SkinnyKernel pick_kernel(int mt, int mr, int rt, int fm, int sm) {
 int launch_skinny(const SkinnyCall& c) {
   const Layout& L = c.L;
   const Decomp& d = c.d;
-  const int rows = std::min(std::max(c.m_tile_hint, 1), kMaxSkinnyM);
+  // compressed scales are built for one 16-row activation tile held at a time: more rows are walked 16 at a time
+  const int rows = std::min(std::max(c.m_tile_hint, 1), L.scale_mode == 1 ? 16 : kMaxSkinnyM);
   int mt = (rows + 15) / 16;
   if (mt == 3) mt = 4;
   const int mr = (mt == 1 && rows == 1) ? 1 : 16;  // rows of the first activation tile that are staged

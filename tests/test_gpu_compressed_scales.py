@@ -62,10 +62,35 @@ def test_compressed_scales_explicit_shapes_and_errors():
     ref = o.matmul(x, W)
     for launch in ((1, 1, 1, 1), (1, 2, 2, 1), (1, 1, 2, 2), (1, 4, 1, 1)):
         assert_gemm_close(_gemm_bits(w, x, launch=b.ccq_launch(*launch)), ref, f"launch={launch}")
+    # more rows than the kernel holds at a time with compressed scales (16): walked 16 at a time
     x40 = synth.activations_bf16(40, 2048, synth.rng(6, 501))
-    with pytest.raises(b.CcqError) as e:            # explicit launch shapes holding more than 16 rows are not built
-        _gemm_bits(w, x40, launch=b.ccq_launch(1, 1, 1, 1))
-    assert e.value.status == -3
+    assert_gemm_close(_gemm_bits(w, x40, launch=b.ccq_launch(1, 2, 1, 2)), o.matmul(x40, W), "40 rows, explicit launch")
+
+
+def test_compressed_scales_grouped_many_rows_per_expert():
+    """Experts with more than 16 rows (a prefill-sized routing) through the grouped entry point."""
+    E, K, N, T = 3, 512, 48, 50
+    rng = synth.rng(6, 600)
+    cases = []
+    for e in range(E):
+        codes = synth.random_codes(N, K // 4, rng)
+        sq = rng.integers(0, 256, size=(N, K // 128), dtype=np.uint8)
+        ssup = synth.scales_log_uniform_fp16(N, 1, rng, 1e-4, 1e-2).reshape(N)
+        alpha, beta = synth.cluster_params(N, rng)
+        cases.append((codes, sq, ssup, alpha, beta))
+    w = b.Weight.from_canonical_compressed(K, N, [b.NARROW], np.stack([c[0] for c in cases]), np.stack([c[1] for c in cases]),
+                                           np.stack([c[2] for c in cases]), np.stack([c[3] for c in cases]), np.stack([c[4] for c in cases]),
+                                           device=DEV, experts=E)
+    x = synth.activations_bf16(T, K, synth.rng(6, 601))
+    offs = np.array([0, 40, 43, 100], dtype=np.int32)          # 40, 3 and 57 rows
+    rows = synth.rng(6, 602).integers(0, T, 100).astype(np.int32)
+    y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
+    torch.cuda.synchronize()
+    got = b.bf16_bits(y)
+    for e in range(E):
+        lo, hi = offs[e], offs[e + 1]
+        Wd = o.decode_cs(K, N, o.F2, *cases[e][:3], cases[e][3], cases[e][4])
+        assert_gemm_close(got[lo:hi], o.matmul(x[rows[lo:hi]], Wd), f"expert {e}")
 
 
 def test_config2_shape_compressed_scales():
