@@ -132,9 +132,9 @@ enum DensePath { kPathGemv, kPathSkinny, kPathRows, kPathMid, kPathPrefill };
 static DensePath dense_path(const Layout& L, int M) {
   const bool narrow_only = L.tiles[kWide] == 0, wide_only = L.tiles[kNarrow] == 0;
   if (M <= kGemvMaxM && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
-  // per-group activation tiles with the weights in registers: measured faster than its neighbours for 5-16 rows on the
+  // per-group activation tiles with the weights in registers: measured faster than its neighbours for 2-16 rows on the
   // wide and hybrid-word formats (whose whole-k-tile staging is the costliest) and for 17-32 rows on the narrow one
-  if (wide_only && M > kGemvMaxM && M < kMidMinM) return kPathRows;
+  if (wide_only && M >= 2 && M < kMidMinM) return kPathRows;
   if (M < kMidMinM) return kPathSkinny;
   if (narrow_only && M <= 32) return kPathRows;
   if (narrow_only && M > 128) return kPathPrefill;            // 256-row tiles pay off
