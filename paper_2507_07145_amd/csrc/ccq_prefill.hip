@@ -302,6 +302,247 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   }
 }
 
+// The same tile with eight wavefronts (two per SIMD): a single wavefront cannot issue its LDS and
+// global-memory instructions underneath its own MFMAs (each costs it several issue slots), a second
+// one on the SIMD fills those slots.  Wave grid 4 (M) x 2 (N), wave tile 64 x 96, BN = 192.  Every
+// wavefront decodes row tile `wave` of the block inside the MFMA stream; wavefronts 0-3 decode row
+// tiles 8-11 as well, ahead of their MFMAs, while their SIMD partners (wavefronts 4-7) already multiply.
+template <int SM>
+__global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) {
+  constexpr int BN = 192;
+  constexpr int NT = 3;         // 32-wide MFMA column tiles per wavefront
+  constexpr int kExtra = 4;     // wavefronts that own a second row tile
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);                          // [2][kBM][kLdsRow]
+  uint16_t* Bs = As + 2 * kBM * kLdsRow;                                     // [2][BN][kLdsRow]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
+  const int m0 = m_block * kBM, n0 = n_block * BN;
+  const int kq = lane >> 4, nl = lane & 15;
+  const bool has_extra = wave < kExtra;
+
+  // row tiles of this wavefront: slot 0 = tile `wave`, slot 1 = tile 8 + wave (wavefronts 0-3 only)
+  const uint8_t* code_ptr[2];
+  const uint16_t* scale_ptr[2];
+  float al[2], be[2], ssup[2];
+  int tile_in_block[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    tile_in_block[i] = i == 0 ? wave : 8 + (wave & (kExtra - 1));
+    int rtile = n0 / 16 + tile_in_block[i];
+    rtile = min(rtile, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
+    code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;
+    scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
+    al[i] = a.alpha[rtile * 16 + nl];
+    be[i] = a.beta[rtile * 16 + nl] + 8388608.f;
+    ssup[i] = 0.f;
+    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+  }
+  uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
+  asm volatile("" : "+v"(c43), "+s"(smask));
+  const float neg_off = -(128.f + a.zp);
+  const uint32_t lane_code_off = lane * 16, lane_scale_off = nl * 4;
+
+  // activation copy: 4 chunks of 16 bytes per thread and step (rows past M re-read row M-1)
+  uint32_t xoff[4];
+  int a_lds_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tid + 512 * i, row = c >> 3, col = c & 7;
+    xoff[i] = (uint32_t)(((int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8) * 2);
+    a_lds_off[i] = row * kLdsRow + col * 8;
+  }
+
+  f32x16 acc[2][NT];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nsteps = a.K / kBK;
+  const int ntiles = nsteps >> 2;
+  u32x4 areg[4];  // activation chunks of the next step on their way to LDS
+  u32x4 creg[2], cnext[2];
+  uint2 sreg[2], snext[2];
+
+  auto load_a = [&](u32x4 (&dst)[4], int step) {
+    const char* base = reinterpret_cast<const char*>(a.x + (int64_t)min(step, nsteps - 1) * kBK);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t off = xoff[i];
+      asm volatile("" : "+v"(off));  // keeps the zero extension next to the load: uniform base + 32-bit lane offset
+      dst[i] = *reinterpret_cast<const u32x4*>(base + off);
+    }
+  };
+  auto load_codes_slot = [&](u32x4& c, uint2& sc, int kt, int i) {
+    c = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_ptr[i] + (int64_t)kt * kNarrowTileBytes + lane_code_off));
+    if constexpr (SM == 0) sc = *reinterpret_cast<const uint2*>(scale_ptr[i] + (int64_t)kt * kNarrowTileScaleHalfs + lane_scale_off);
+    else sc = uint2{(uint32_t)scale_ptr[i][(int64_t)kt * kNarrowTileScaleHalfs4 + nl], 0u};
+  };
+  auto load_codes = [&](u32x4 (&c)[2], uint2 (&sc)[2], int kt) {
+    kt = min(kt, ntiles - 1);
+    load_codes_slot(c[0], sc[0], kt, 0);
+    if (has_extra) load_codes_slot(c[1], sc[1], kt, 1);
+  };
+  auto store_a = [&](int buf, const u32x4 (&src)[4], int i0, int i1) {
+    uint16_t* dst = As + buf * kBM * kLdsRow;
+#pragma unroll
+    for (int i = i0; i < i1; ++i) *reinterpret_cast<u32x4*>(dst + a_lds_off[i]) = src[i];
+  };
+  // decode group j (0..3) of row-tile slot i of the held k-tile into LDS buffer `buf`
+  auto decode_b = [&](int buf, int j, int i) {
+    uint16_t* dst = Bs + buf * BN * kLdsRow;
+    const uint32_t d = j == 0 ? creg[i].x : (j == 1 ? creg[i].y : (j == 2 ? creg[i].z : creg[i].w));
+    float s;
+    if constexpr (SM == 0) {
+      const uint32_t sw = (j >> 1) ? sreg[i].y : sreg[i].x;
+      s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+    } else {
+      s = (float)((sreg[i].x >> (4 * j)) & 0xFu) * ssup[i];
+    }
+    const float c0 = neg_off * s;  // exact: 8-bit times 11-bit significand
+    uint32_t o[8];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], be[i]);
+      const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code
+      const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, smask, c43)), s, c0);
+      const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, smask, c43)), s, c0);
+      const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, smask, c43)), s, c0);
+      const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, smask, c43)), s, c0);
+      o[2 * b] = pack_bf16(w0, w1);
+      o[2 * b + 1] = pack_bf16(w2, w3);
+    }
+    uint16_t* p = dst + (tile_in_block[i] * 16 + nl) * kLdsRow + kq * 16;
+    *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
+    *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
+  };
+
+  bf16x8 af[2][2], bfr[2][NT];
+  const int a_frag_off = (wm * 64 + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+  const int b_frag_off = (wn * (BN / 2) + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+  auto load_frags = [&](int par, int buf, int kk) {
+    const uint16_t* Ab = As + buf * kBM * kLdsRow + a_frag_off + kk * 16;
+    const uint16_t* Bb = Bs + buf * BN * kLdsRow + b_frag_off + kk * 16;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) af[par][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + i * 32 * kLdsRow));
+#pragma unroll
+    for (int j = 0; j < NT; ++j) bfr[par][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + j * 32 * kLdsRow));
+  };
+  auto mfma_rows = [&](int par, int i0, int i1) {
+#pragma unroll
+    for (int i = i0; i < i1; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[par][i], bfr[par][j], acc[i][j], 0, 0, 0);
+  };
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  };
+
+  load_a(areg, 0);
+  load_codes(creg, sreg, 0);
+  store_a(0, areg, 0, 4);
+  load_a(areg, 1);
+  decode_b(0, 0, 0);
+  if (has_extra) decode_b(0, 0, 1);
+  lds_barrier();
+  load_frags(0, 0, 0);
+
+  // One step (J = step & 3): buffer J&1 is multiplied while step + 1 is written to the other buffer.
+  // HEAVY wavefronts (those with a second row tile) decode it inside the same stream, with more vector
+  // instructions between two MFMAs; the two kinds run separate copies of the loop.
+  auto body = [&](int step, auto JC, auto HC) {
+    constexpr int J = decltype(JC)::value;
+    constexpr bool HEAVY = decltype(HC)::value;
+    constexpr int buf = J & 1;
+    constexpr int jn = (J + 1) & 3;
+    if constexpr (J == 1) {
+      const int kt = min((step >> 2) + 1, ntiles - 1);
+      load_codes_slot(cnext[0], snext[0], kt, 0);
+      if constexpr (HEAVY) load_codes_slot(cnext[1], snext[1], kt, 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (J == 3) {
+      creg[0] = cnext[0]; sreg[0] = snext[0];
+      if constexpr (HEAVY) { creg[1] = cnext[1]; sreg[1] = snext[1]; }
+    }
+    // Program order: all fragment reads of this step first, the LDS writes of step + 1 last (the compiler
+    // keeps LDS reads behind earlier LDS writes, so a write waiting for its decode would hold them back);
+    // the issue order below spreads the decode arithmetic under the MFMAs all the same.
+    load_frags(1, buf, 1);
+    mfma_rows(0, 0, 2);
+    load_frags(0, buf, 2);
+    mfma_rows(1, 0, 2);
+    load_frags(1, buf, 3);
+    mfma_rows(0, 0, 2);
+    mfma_rows(1, 0, 1);
+    store_a(buf ^ 1, areg, 0, 4);
+    load_a(areg, step + 2);
+    decode_b(buf ^ 1, jn, 0);
+    if constexpr (HEAVY) decode_b(buf ^ 1, jn, 1);
+    // issue order inside this region: one MFMA, a few vector ALU instructions, one LDS access
+#pragma unroll
+    for (int i = 0; i < 7 * NT; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, HEAVY ? 7 : 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);
+    }
+    lds_barrier();
+    load_frags(0, buf ^ 1, 0);
+    mfma_rows(1, 1, 2);
+  };
+  if (has_extra) {
+    for (int step = 0; step < nsteps; step += 4) {
+      body(step, std::integral_constant<int, 0>{}, std::true_type{});
+      body(step + 1, std::integral_constant<int, 1>{}, std::true_type{});
+      body(step + 2, std::integral_constant<int, 2>{}, std::true_type{});
+      body(step + 3, std::integral_constant<int, 3>{}, std::true_type{});
+    }
+  } else {
+    for (int step = 0; step < nsteps; step += 4) {
+      body(step, std::integral_constant<int, 0>{}, std::false_type{});
+      body(step + 1, std::integral_constant<int, 1>{}, std::false_type{});
+      body(step + 2, std::integral_constant<int, 2>{}, std::false_type{});
+      body(step + 3, std::integral_constant<int, 3>{}, std::false_type{});
+    }
+  }
+
+  const bool inside = (m0 + kBM <= a.M) && (n0 + BN <= a.N);
+  uint16_t* ybase = a.y + (int64_t)(m0 + wm * 64 + 4 * (lane >> 5)) * a.ldy + (n0 + wn * (BN / 2) + (lane & 31));
+  const int mlim = a.M - (m0 + wm * 64 + 4 * (lane >> 5));
+  const int nlim = a.N - (n0 + wn * (BN / 2) + (lane & 31));
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      uint32_t bits[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float val = acc[i][j][r];
+        bits[r] = pack_bf16(val, 0.f);
+      }
+      uint16_t* dst = ybase + (int64_t)(i * 32) * a.ldy + j * 32;
+      if (inside) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * a.ldy] = (uint16_t)bits[r];
+      } else if (j * 32 < nlim) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int mrel = i * 32 + 8 * (r >> 2) + (r & 3);
+          if (mrel < mlim) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * a.ldy] = (uint16_t)bits[r];
+        }
+      }
+    }
+  }
+}
+
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
   PrefillArgs a;
   a.codes = static_cast<const uint8_t*>(w->codes);
@@ -328,13 +569,13 @@ int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, i
   const int n_blocks = (L.N + BN - 1) / BN;
   const size_t lds = (size_t)2 * (kBM + BN) * kLdsRow * 2;
   typedef void (*PrefillKernel)(const PrefillArgs);
-  const PrefillKernel table[2][2] = {{ccq_prefill_kernel<3, 0>, ccq_prefill_kernel<4, 0>}, {ccq_prefill_kernel<3, 1>, ccq_prefill_kernel<4, 1>}};
+  const PrefillKernel table[2][2] = {{ccq_prefill8_kernel<0>, ccq_prefill_kernel<4, 0>}, {ccq_prefill8_kernel<1>, ccq_prefill_kernel<4, 1>}};
   const PrefillKernel kern = table[L.scale_mode][use192 ? 0 : 1];
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return CCQ_ERR_HIP;
   }
-  dim3 grid((unsigned)(a.m_blocks * n_blocks)), block(256);
+  dim3 grid((unsigned)(a.m_blocks * n_blocks)), block(use192 ? 512 : 256);
   hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;

@@ -1,5 +1,5 @@
 """Build guard: no kernel of the library may spill registers to scratch memory (kernels that did
-produced wrong results on the device in some launch shapes, see DESIGN.md), and no packed-fp32
+produced wrong results on the device in some launch shapes), and no packed-fp32
 vector instruction may appear in the generated code."""
 import glob
 import os
