@@ -19,6 +19,9 @@
 // Workgroup-to-tile map: consecutive workgroup ids walk the M blocks first; with
 // 8 M blocks (M = 2048) every XCD keeps one 256-row slab of the activations in its
 // own L2 and streams the (small) code bytes.
+//
+// Two kernels share this design: ccq_prefill8_kernel (BN = 192, eight wavefronts, two per
+// SIMD) when 192 divides N, and ccq_prefill_kernel<4> (BN = 256, four wavefronts) otherwise.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -563,7 +566,7 @@ int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, i
   a.m_blocks = (M + kBM - 1) / kBM;
   a.zp = L.zp[kNarrow];
   if (((int64_t)M * ldx + L.K) * 2 >= (int64_t)1 << 31) return CCQ_ERR_UNSUPPORTED;  // activation offsets are 32-bit
-  // 192-column blocks when they tile N exactly (less tail imbalance on 256 CUs), else 256
+  // 192-column blocks (eight wavefronts) when they tile N exactly, else 256-column blocks (four wavefronts)
   const bool use192 = (L.N % 192 == 0);
   const int BN = use192 ? 192 : 256;
   const int n_blocks = (L.N + BN - 1) / BN;
