@@ -768,10 +768,17 @@ __device__ __forceinline__ void run_kind(const SkinnyArgs& a, const uint8_t* (&c
                                    nthreads, dc);
 }
 
+// Threads a workgroup of ccq_skinny_kernel may have (the register budget per lane follows from it).  The wide
+// format with compressed scales holds the tile's scale fields besides its eight code registers and does not fit
+// the 128 registers of a 1024-thread workgroup.
+constexpr int skinny_max_threads(int MT, int MR, int FM, int SM) {
+  return MT == 4 ? 256 : ((MT == 2 || MR == 1 || (FM == 2 && SM == 1)) ? 512 : 1024);
+}
+
 // FM: formats present (1 narrow, 2 wide, 3 both, 4 the hybrid word in place of the wide kind).
 // SM: scale mode (0 fp16 group scales, 1 compressed scales)
 template <int MT, int MR, int RT, int FM, int SM>
-__global__ void __launch_bounds__(MT == 4 ? 256 : ((MT == 2 || MR == 1) ? 512 : 1024)) ccq_skinny_kernel(const SkinnyArgs a) {
+__global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny_kernel(const SkinnyArgs a) {
   constexpr int KN = kNarrow | (SM << 1), KW = kWide | (SM << 1) | (FM == 4 ? kH16 : 0);
   constexpr bool HAS_N = FM == 1 || FM == 3, HAS_W = FM >= 2;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1585,9 +1592,8 @@ int launch_skinny(const SkinnyCall& c) {
   const int mr = (mt == 1 && rows == 1) ? 1 : 16;  // rows of the first activation tile that are staged
   const int mrt = mt == 1 ? mr : mt * 16;
   const int fm = L.h16 ? 4 : (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
-  if ((mt >= 2 || mr == 1) && d.WR * d.WK > 8) return CCQ_ERR_BAD_PARAM;  // those kernels are built for at most 512 threads
+  if (64 * d.WR * d.WK > skinny_max_threads(mt, mr, fm, L.scale_mode)) return CCQ_ERR_BAD_PARAM;  // more threads than the kernel is built for
   if (d.RT == 2 && (mt == 4 || fm != 1)) return CCQ_ERR_BAD_PARAM;  // two row tiles per wavefront: narrow format, at most 32 held rows
-  if (mt == 4 && d.WR * d.WK > 4) return CCQ_ERR_BAD_PARAM;            // 64 held rows: built for at most 256 threads
 
   SkinnyArgs a;
   a.codes = static_cast<const uint8_t*>(c.w->codes);
