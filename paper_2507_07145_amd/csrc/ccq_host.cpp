@@ -137,7 +137,20 @@ static DensePath dense_path(const Layout& L, int M) {
   if (wide_only && M >= 2 && M < kMidMinM) return kPathRows;
   if (M < kMidMinM) return kPathSkinny;
   if (narrow_only && M <= 32) return kPathRows;
-  if (narrow_only && M > 128) return kPathPrefill;            // 256-row tiles pay off
+  if (narrow_only && M > 128) {
+    // 256-row tiles pay off once they fill enough of the chip.  Estimated times in us at K = 8192, fitted to
+    // measurements: a round of up to 256 workgroups of the 256-row kernel takes 98 / 120 / 197 us with 128 / 192 /
+    // 256 columns per workgroup when at most half of the CUs are busy and up to 40 % more when all are (the clock
+    // sinks); the 64-row kernel takes 20 us + 0.187 us per workgroup of 64 x 128 results (at least 256 of them).
+    const int bn = prefill_block_cols(L, M);
+    const int64_t wg_p = (int64_t)ceil_div(M, 256) * ceil_div(L.N, bn);
+    const int64_t rounds = (wg_p + 255) / 256;
+    const double fill = (double)wg_p / (double)(rounds * 256);
+    const double t_p = (double)rounds * (bn == 128 ? 98.0 : (bn == 192 ? 120.0 : 197.0)) * (1.0 + 0.8 * std::max(0.0, fill - 0.5));
+    const int64_t wg_m = (int64_t)ceil_div(M, 64) * ceil_div(L.N, 128);
+    const double t_m = 20.0 + 0.187 * (double)std::max<int64_t>(wg_m, 256);
+    return t_p <= t_m ? kPathPrefill : kPathMid;
+  }
   return kPathMid;
 }
 

@@ -121,6 +121,7 @@ int launch_rows(const ccq_weight* w, const Layout& L, const void* x, int M, int6
                 void* stream);
 
 // Large-M kernel for narrow-format weights (ccq_prefill.hip).
+int prefill_block_cols(const Layout& L, int M);  // column-block width launch_prefill uses: 128, 192 or 256
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 
 // The quantizer (ccq_encode.hip): every layout the multiply kernels read, fp16 or compressed group scales.

@@ -20,8 +20,8 @@
 // 8 M blocks (M = 2048) every XCD keeps one 256-row slab of the activations in its
 // own L2 and streams the (small) code bytes.
 //
-// Two kernels share this design: ccq_prefill8_kernel (BN = 192, eight wavefronts, two per
-// SIMD) when 192 divides N, and ccq_prefill_kernel<4> (BN = 256, four wavefronts) otherwise.
+// Two kernels share this design: ccq_prefill8_kernel (BN = 192 or 128, eight wavefronts, two per
+// SIMD) when that block width divides N, and ccq_prefill_kernel<4> (BN = 256, four wavefronts) otherwise.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -307,14 +307,14 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
 
 // The same tile with eight wavefronts (two per SIMD): a single wavefront cannot issue its LDS and
 // global-memory instructions underneath its own MFMAs (each costs it several issue slots), a second
-// one on the SIMD fills those slots.  Wave grid 4 (M) x 2 (N), wave tile 64 x 96, BN = 192.  Every
-// wavefront decodes row tile `wave` of the block inside the MFMA stream; wavefronts 0-3 decode row
-// tiles 8-11 as well, ahead of their MFMAs, while their SIMD partners (wavefronts 4-7) already multiply.
-template <int SM>
+// one on the SIMD fills those slots.  Wave grid 4 (M) x 2 (N), wave tile 64 x 32 NT, BN = 64 NT
+// (NT = 3: 192 columns, NT = 2: 128).  Every wavefront decodes row tile `wave` of the block; with 192
+// columns wavefronts 0-3 decode row tiles 8-11 as well (their SIMD partners, wavefronts 4-7, have one
+// tile each, so every SIMD carries the same work).
+template <int NT, int SM>
 __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) {
-  constexpr int BN = 192;
-  constexpr int NT = 3;         // 32-wide MFMA column tiles per wavefront
-  constexpr int kExtra = 4;     // wavefronts that own a second row tile
+  constexpr int BN = 64 * NT;
+  constexpr int kExtra = BN / 16 - 8;  // wavefronts that own a second row tile (4 or 0)
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* As = reinterpret_cast<uint16_t*>(smem);                          // [2][kBM][kLdsRow]
   uint16_t* Bs = As + 2 * kBM * kLdsRow;                                     // [2][BN][kLdsRow]
@@ -325,7 +325,7 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
   const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
   const int m0 = m_block * kBM, n0 = n_block * BN;
   const int kq = lane >> 4, nl = lane & 15;
-  const bool has_extra = wave < kExtra;
+  const bool has_extra = kExtra > 0 && wave < kExtra;
 
   // row tiles of this wavefront: slot 0 = tile `wave`, slot 1 = tile 8 + wave (wavefronts 0-3 only)
   const uint8_t* code_ptr[2];
@@ -334,7 +334,7 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
   int tile_in_block[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    tile_in_block[i] = i == 0 ? wave : 8 + (wave & (kExtra - 1));
+    tile_in_block[i] = (i == 0 || kExtra == 0) ? wave : 8 + (wave & (kExtra > 0 ? kExtra - 1 : 0));
     int rtile = n0 / 16 + tile_in_block[i];
     rtile = min(rtile, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
     code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;
@@ -494,19 +494,23 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
 #pragma unroll
     for (int i = 0; i < 7 * NT; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, HEAVY ? 7 : 4, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, HEAVY ? 7 : (NT == 2 ? 5 : 4), 0);
       __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);
     }
     lds_barrier();
     load_frags(0, buf ^ 1, 0);
     mfma_rows(1, 1, 2);
   };
-  if (has_extra) {
-    for (int step = 0; step < nsteps; step += 4) {
-      body(step, std::integral_constant<int, 0>{}, std::true_type{});
-      body(step + 1, std::integral_constant<int, 1>{}, std::true_type{});
-      body(step + 2, std::integral_constant<int, 2>{}, std::true_type{});
-      body(step + 3, std::integral_constant<int, 3>{}, std::true_type{});
+  bool heavy_loop = false;
+  if constexpr (kExtra > 0) heavy_loop = has_extra;
+  if (heavy_loop) {
+    if constexpr (kExtra > 0) {
+      for (int step = 0; step < nsteps; step += 4) {
+        body(step, std::integral_constant<int, 0>{}, std::true_type{});
+        body(step + 1, std::integral_constant<int, 1>{}, std::true_type{});
+        body(step + 2, std::integral_constant<int, 2>{}, std::true_type{});
+        body(step + 3, std::integral_constant<int, 3>{}, std::true_type{});
+      }
     }
   } else {
     for (int step = 0; step < nsteps; step += 4) {
@@ -546,6 +550,15 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
   }
 }
 
+// Column blocks: 192 (eight wavefronts) when they tile N exactly; else 128 (eight wavefronts) when those tile N
+// and fit one round of 256 workgroups; else 256 (four wavefronts, ragged last block allowed).
+int prefill_block_cols(const Layout& L, int M) {
+  const int64_t m_blocks = (M + kBM - 1) / kBM;
+  if (L.N % 192 == 0) return 192;
+  if (L.N % 128 == 0 && m_blocks * (L.N / 128) <= 256) return 128;
+  return 256;
+}
+
 int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
   PrefillArgs a;
   a.codes = static_cast<const uint8_t*>(w->codes);
@@ -566,19 +579,18 @@ int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, i
   a.m_blocks = (M + kBM - 1) / kBM;
   a.zp = L.zp[kNarrow];
   if (((int64_t)M * ldx + L.K) * 2 >= (int64_t)1 << 31) return CCQ_ERR_UNSUPPORTED;  // activation offsets are 32-bit
-  // 192-column blocks (eight wavefronts) when they tile N exactly, else 256-column blocks (four wavefronts)
-  const bool use192 = (L.N % 192 == 0);
-  const int BN = use192 ? 192 : 256;
+  const int BN = prefill_block_cols(L, M);
   const int n_blocks = (L.N + BN - 1) / BN;
   const size_t lds = (size_t)2 * (kBM + BN) * kLdsRow * 2;
   typedef void (*PrefillKernel)(const PrefillArgs);
-  const PrefillKernel table[2][2] = {{ccq_prefill8_kernel<0>, ccq_prefill_kernel<4, 0>}, {ccq_prefill8_kernel<1>, ccq_prefill_kernel<4, 1>}};
-  const PrefillKernel kern = table[L.scale_mode][use192 ? 0 : 1];
+  const PrefillKernel table[2][3] = {{ccq_prefill8_kernel<2, 0>, ccq_prefill8_kernel<3, 0>, ccq_prefill_kernel<4, 0>},
+                                     {ccq_prefill8_kernel<2, 1>, ccq_prefill8_kernel<3, 1>, ccq_prefill_kernel<4, 1>}};
+  const PrefillKernel kern = table[L.scale_mode][BN == 128 ? 0 : (BN == 192 ? 1 : 2)];
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return CCQ_ERR_HIP;
   }
-  dim3 grid((unsigned)(a.m_blocks * n_blocks)), block(use192 ? 512 : 256);
+  dim3 grid((unsigned)(a.m_blocks * n_blocks)), block(BN == 256 ? 256 : 512);
   hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;

@@ -56,6 +56,18 @@ def test_compressed_scales_every_kernel(kinds, K, N, n_wide, M):
     assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, ks].T))), f"{kinds} M={M}: decoded weights differ"
 
 
+@pytest.mark.parametrize("K,N,M", [(256, 1536, 2900), (256, 1024, 3400), (256, 2064, 4000)])
+def test_compressed_scales_256_row_kernel(K, N, M):
+    """Shapes the library sends to the 256-row kernel (column blocks of 192, 128 and 256)."""
+    W, w = _case(["narrow"], K, N, 31 + N % 7, None)
+    x = synth.activations_bf16(M, K, synth.rng(6, 600 + M))
+    abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(W))
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, W), f"compressed scales, 256-row kernel N={N} M={M}", abs_sum=abs_sum)
+    ks = synth.rng(6, 610 + M).integers(0, K, M)
+    got = _gemm_bits(w, synth.one_hot_bf16(ks, K))
+    assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, ks].T))), f"N={N} M={M}: decoded weights differ"
+
+
 def test_compressed_scales_explicit_shapes_and_errors():
     W, w = _case(["narrow", "wide"], 2048, 64, 77, 8)
     x = synth.activations_bf16(8, 2048, synth.rng(6, 500))

@@ -77,10 +77,12 @@ def test_more_rows_than_one_pass(cfg1):
         assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"cfg1 M={M}")
 
 
-@pytest.mark.parametrize("K,N,M", [(768, 384, 300), (512, 208, 70), (256, 16, 65), (1024, 576, 257), (2048, 192, 512)])
+@pytest.mark.parametrize("K,N,M", [(768, 384, 300), (512, 208, 70), (256, 16, 65), (1024, 576, 257), (2048, 192, 512),
+                                   (256, 1536, 2900), (256, 1024, 3400), (256, 2064, 4000)])
 def test_large_m_kernel_small_shapes(K, N, M):
-    """More than 64 rows on narrow-format weights go through the LDS-tiled MFMA kernel: column blocks of 192
-    and of 256, ragged last blocks in M and N, decoded weights exact and products within tolerance."""
+    """More than 64 rows on narrow-format weights go through the LDS-tiled MFMA kernels: the 64-row one, and (the
+    three shapes with thousands of rows, where the library expects it to be faster) the 256-row one with column
+    blocks of 192, 128 and 256; ragged last blocks in M and N, decoded weights exact and products within tolerance."""
     c = random_case(K, N, ["narrow"], 1, stream0=900 + N)
     w = c.device_weight(DEV)
     x = synth.activations_bf16(M, K, synth.rng(1, 950 + M))
