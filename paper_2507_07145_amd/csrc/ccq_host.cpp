@@ -498,12 +498,28 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
   c.w = w0;
   c.L = L;
   c.m_tile_hint = grouped_tile_rows(E, P);
-  int active = E;
+  int active = E, most_rows = P;
   if (expert_offsets_host) {
     active = 0;
-    for (int e = 0; e < E; ++e) active += expert_offsets_host[e + 1] > expert_offsets_host[e] ? 1 : 0;
+    most_rows = 0;
+    for (int e = 0; e < E; ++e) {
+      const int rows = expert_offsets_host[e + 1] - expert_offsets_host[e];
+      active += rows > 0 ? 1 : 0;
+      most_rows = std::max(most_rows, rows);
+    }
   }
-  c.d = grouped_decomp(L, E, P, active, workspace ? workspace_bytes : 0);
+  if (most_rows == 1) {
+    // one token's decode step: no expert has more than one row, so every expert is a GEMV and takes the
+    // one-held-row kernel (wavefront-private staging, no 16-row activation tile)
+    c.m_tile_hint = 1;
+    c.d = choose_decomp(L, 1, std::max(1, active), P);
+    // the grid spans all E experts and most of them have no row: beyond about 16384 workgroups the dispatch of the
+    // empty ones shows, and fewer, larger workgroups (several row tiles side by side, at most 512 threads) are faster
+    const int wr_max = std::max(1, std::min(std::min(4, 8 / c.d.WK), L.row_tiles / c.d.RT));
+    while (c.d.WR * 2 <= wr_max && (int64_t)ceil_div(L.row_tiles, c.d.RT * c.d.WR) * E > 16384) c.d.WR *= 2;
+  } else {
+    c.d = grouped_decomp(L, E, P, active, workspace ? workspace_bytes : 0);
+  }
   if (c.d.S > 1) c.partial = static_cast<float*>(workspace);
   c.E = E;
   c.codes_stride = codes_stride;

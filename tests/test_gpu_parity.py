@@ -256,6 +256,37 @@ def test_grouped_small(kinds, K, N):
         assert np.array_equal(canon_zero(got[e]), canon_zero(o.to_bf16_bits(cases[e].W()[:, ks].T))), f"expert {e}"
 
 
+@pytest.mark.parametrize("kinds,K,N", [(["narrow"], 512, 64), (["wide"], 512, 32), (["narrow"], 2048, 160)])
+def test_grouped_one_token(kinds, K, N):
+    """One token's decode step: no expert has more than one row (some have none); with the host copy of the
+    offsets the library treats every expert as a GEMV, without it the 16-row path runs; both must agree with the oracle."""
+    E = 6
+    cases = [random_case(K, N, kinds, 12, stream0=10 * e) for e in range(E)]
+    w = b.Weight.from_canonical(K, N, [b.NARROW if kinds[0] == "narrow" else b.WIDE],
+                                np.stack([c.codes for c in cases]), np.stack([c.scales for c in cases]),
+                                None if kinds[0] != "narrow" else np.stack([c.alpha for c in cases]),
+                                None if kinds[0] != "narrow" else np.stack([c.beta for c in cases]), device=DEV, experts=E)
+    x = synth.activations_bf16(3, K, synth.rng(12, 99))
+    counts = [1, 0, 1, 1, 0, 1]
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    rows = np.array([2, 0, 2, 1], dtype=np.int32)
+    ref = _grouped_reference(cases, x, rows, offs)
+    for host_offsets in (offs, None):
+        y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), host_offsets)
+        torch.cuda.synchronize()
+        assert_gemm_close(b.bf16_bits(y), ref, f"grouped, one token, {kinds}, host offsets {'given' if host_offsets is not None else 'absent'}")
+    # decoded weights, bit exact: a one-hot token per expert
+    ks = [0, 63, K - 64, K - 1, 17, 64]
+    xe = synth.one_hot_bf16(ks, K)
+    offs2 = np.arange(E + 1, dtype=np.int32)
+    rows2 = np.arange(E, dtype=np.int32)
+    y2 = b.grouped_gemm(w, b.bf16_tensor(xe, DEV), torch.from_numpy(rows2).to(DEV), torch.from_numpy(offs2).to(DEV), offs2)
+    torch.cuda.synchronize()
+    got = b.bf16_bits(y2)
+    for e in range(E):
+        assert np.array_equal(canon_zero(got[e]), canon_zero(o.to_bf16_bits(cases[e].W()[:, ks[e]]))), f"expert {e}"
+
+
 def test_grouped_all_experts_empty_and_errors():
     c = random_case(512, 32, ["narrow"], 10)
     w = c.device_weight(DEV)
