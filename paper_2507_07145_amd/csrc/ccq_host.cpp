@@ -508,6 +508,13 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
       most_rows = std::max(most_rows, rows);
     }
   }
+  if (expert_offsets_host && active < E && active <= kMaxActiveList && E <= 65536) {
+    // launch over the experts that have rows only
+    c.n_active = active;
+    int k = 0;
+    for (int e = 0; e < E; ++e)
+      if (expert_offsets_host[e + 1] > expert_offsets_host[e]) c.active_ids[k++] = (uint16_t)e;
+  }
   if (most_rows == 1) {
     // one token's decode step: no expert has more than one row, so every expert is a GEMV and takes the
     // one-held-row kernel (wavefront-private staging, no 16-row activation tile)
@@ -516,7 +523,7 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
     // the grid spans all E experts and most of them have no row: beyond about 16384 workgroups the dispatch of the
     // empty ones shows, and fewer, larger workgroups (several row tiles side by side, at most 512 threads) are faster
     const int wr_max = std::max(1, std::min(std::min(4, 8 / c.d.WK), L.row_tiles / c.d.RT));
-    while (c.d.WR * 2 <= wr_max && (int64_t)ceil_div(L.row_tiles, c.d.RT * c.d.WR) * E > 16384) c.d.WR *= 2;
+    while (c.d.WR * 2 <= wr_max && (int64_t)ceil_div(L.row_tiles, c.d.RT * c.d.WR) * (c.n_active > 0 ? c.n_active : E) > 16384) c.d.WR *= 2;
   } else {
     c.d = grouped_decomp(L, E, P, active, workspace ? workspace_bytes : 0);
   }

@@ -80,6 +80,10 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total);
 bool decomp_ok(const Layout& L, const Decomp& d);
 
 // Kernel launchers (ccq_skinny.hip).  All pointers DEVICE unless noted.
+// Grouped calls whose host copy of the offsets shows at most this many experts with rows launch a grid over those
+// experts only; their ids travel in the kernel arguments.
+constexpr int kMaxActiveList = 128;
+
 struct SkinnyCall {
   const ccq_weight* w = nullptr;  // HOST descriptor of expert 0
   Layout L;
@@ -96,6 +100,8 @@ struct SkinnyCall {
   const int32_t* expert_offsets = nullptr;
   float* partial = nullptr;             // fp32 [S][M][N] when S > 1
   void* stream = nullptr;
+  int n_active = 0;                     // > 0: the grid's z extent; block z works on expert active_ids[z]
+  uint16_t active_ids[kMaxActiveList] = {};
 };
 int launch_skinny(const SkinnyCall& c);
 

@@ -33,6 +33,9 @@
 // its own row over its own quarter; the four quarters are added across lanes at the end.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
+#include <cstring>
+
 #include <algorithm>
 #include <type_traits>
 
@@ -76,6 +79,8 @@ struct SkinnyArgs {
   int32_t frag_cap;   // 16-byte fragments the LDS staging area holds (per wavefront when one row is held); the start values follow it
   int32_t cneg_cap;   // floats of start values per wavefront (one held row only; multiple of 4)
   float cneg[2];      // -(128 + zp) per kind
+  int32_t n_active;   // > 0: gridDim.z experts are listed in active_ids (the others have no rows)
+  uint16_t active_ids[kMaxActiveList];
 };
 
 // KIND = format (bit 0: kNarrow / kWide) | scale mode << 1 (bit 1: 0 fp16 group scales, 1 the compressed
@@ -793,7 +798,16 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps tile indices and base pointers in scalar registers
   const int wk = (wave * a.inv_WR) >> 16, wr = wave - wk * a.WR;
-  const int split = blockIdx.y, e = blockIdx.z;
+  const int split = blockIdx.y;
+  int e = blockIdx.z;
+  if (a.n_active > 0) {
+    // read straight from the argument segment (a uniform scalar load): indexing the by-value copy with a run-time
+    // index would make the compiler keep the whole argument block in scratch memory
+    typedef const __attribute__((address_space(4))) uint16_t* KernargU16;
+    typedef const __attribute__((address_space(4))) char* KernargBytes;
+    KernargBytes args = (KernargBytes)__builtin_amdgcn_kernarg_segment_ptr();
+    e = ((KernargU16)(args + offsetof(SkinnyArgs, active_ids)))[blockIdx.z];
+  }
 
   int off0 = 0, Me = a.M;
   if (a.expert_offsets) {
@@ -1634,6 +1648,8 @@ int launch_skinny(const SkinnyCall& c) {
   }
   a.cneg[0] = -(128.f + L.zp[0]);
   a.cneg[1] = -(128.f + L.zp[1]);
+  a.n_active = c.n_active;
+  std::memcpy(a.active_ids, c.active_ids, sizeof(a.active_ids));
 
   // chunk sizes: as many k-tiles per wavefront as fit the staging budget; if not even one tile per
   // wavefront fits, the groups of a tile are staged a few at a time.  Up to 16 held rows the budget is
@@ -1697,7 +1713,7 @@ int launch_skinny(const SkinnyCall& c) {
     }
   }
   const int row_blocks = (L.row_tiles + d.WR * d.RT - 1) / (d.WR * d.RT);
-  dim3 grid((unsigned)row_blocks, (unsigned)d.S, (unsigned)c.E);
+  dim3 grid((unsigned)row_blocks, (unsigned)d.S, (unsigned)(c.n_active > 0 ? c.n_active : c.E));
   dim3 block((unsigned)(64 * d.WR * d.WK));
   hipLaunchKernelGGL(kern, grid, block, (size_t)lds, stream, a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
