@@ -166,7 +166,10 @@ int ccq_gemm_ex(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void
  *   x DEVICE bf16 [T][ldx]; sorted_rows DEVICE int32 [P], values in [0,T);
  *   expert_offsets_dev DEVICE int32 [E+1] with [0] = 0, monotone, [E] = P;
  *   expert_offsets_host HOST copy of the same, or NULL: when given it is
- *   validated (CCQ_ERR_ROUTING) -- device data is never read back;
+ *   validated (CCQ_ERR_ROUTING) and shapes the launch -- it must equal the
+ *   device array: experts it shows as empty may not be visited at all, and
+ *   with at most one row per expert the one-row kernel runs; device data is
+ *   never read back;
  *   y DEVICE bf16 [P][ldy].  An expert with no rows writes nothing.
  *   The top-k combine and any activation function stay with the caller. */
 int ccq_grouped_gemm(const ccq_weight *w0, int32_t E, int64_t codes_stride, int64_t scales_stride,
