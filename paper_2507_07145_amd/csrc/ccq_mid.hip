@@ -656,7 +656,11 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
 int mid_splits(const Layout& L, int M) {
   const int64_t blocks = (int64_t)((M + kMidBM - 1) / kMidBM) * ((L.N + kMidBN - 1) / kMidBN);
   const int min_tiles = std::min(L.tiles[kNarrow] > 0 ? L.tiles[kNarrow] : 1 << 30, L.tiles[kWide] > 0 ? L.tiles[kWide] : 1 << 30);
-  int64_t s = std::max<int64_t>(1, 256 / std::max<int64_t>(1, blocks));
+  // one workgroup per CU, or two when the weights have wide-format groups and there are at least 128 blocks: that
+  // kernel moves more through LDS per MFMA and gains from a second workgroup on the CU (config 3, M = 64: 84 -> 75 us),
+  // the register-decode kernel for the narrow format does not
+  const int64_t target = (L.tiles[kWide] > 0 && blocks >= 128) ? 512 : 256;
+  int64_t s = std::max<int64_t>(1, target / std::max<int64_t>(1, blocks));
   s = std::min<int64_t>(s, 8);
   s = std::min<int64_t>(s, std::max(1, min_tiles / 2));
   return (int)s;
