@@ -109,7 +109,11 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
   } else {
     // two row tiles per wavefront only for the narrow format with at most 32 held rows (register budget)
     d.RT = (L.row_tiles >= 2 && M <= 32 && L.tiles[kWide] == 0) ? 2 : 1;
-    d.WR = (int)std::min<int64_t>(4, std::max(1, L.row_tiles / d.RT));
+    // wavefronts side by side that share one staged activation chunk: four, or eight for mixed formats with many
+    // rows, whose staging (a gather through the group map, one row tile per wavefront) is the larger part of the
+    // work (config 3, M = 16: 61 -> 42 us; 8192 x 8192 mixed: 21.8 -> 18.8 us; 4096 x 4096 is better off with four)
+    const int wr_max = (L.tiles[kNarrow] > 0 && L.tiles[kWide] > 0 && L.row_tiles >= 512 && M <= 16) ? 8 : 4;
+    d.WR = (int)std::min<int64_t>(wr_max, std::max(1, L.row_tiles / d.RT));
     d.WK = 1;
     int64_t row_blocks = (int64_t)ceil_div(L.row_tiles, d.RT * d.WR) * experts;
     // workgroups wanted: two per CU for the narrow format, four for the wide kinds, whose per-chunk staging is longer
