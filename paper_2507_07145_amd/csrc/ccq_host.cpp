@@ -112,7 +112,11 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     // wavefronts side by side that share one staged activation chunk: four, or eight for mixed formats with many
     // rows, whose staging (a gather through the group map, one row tile per wavefront) is the larger part of the
     // work (config 3, M = 16: 61 -> 42 us; 8192 x 8192 mixed: 21.8 -> 18.8 us; 4096 x 4096 is better off with four)
-    const int wr_max = (L.tiles[kNarrow] > 0 && L.tiles[kWide] > 0 && L.row_tiles >= 512 && M <= 16) ? 8 : 4;
+    // -- and for grouped calls on long rows of narrow-format weights (config 4, K = 7168: 108 -> 96 us; with K = 2048
+    // four are better)
+    const bool mixed_many_rows = L.tiles[kNarrow] > 0 && L.tiles[kWide] > 0 && L.row_tiles >= 512 && M <= 16;
+    const bool grouped_long_k = experts > 1 && L.tiles[kWide] == 0 && L.tiles[kNarrow] >= 24 && M <= 32;
+    const int wr_max = (mixed_many_rows || grouped_long_k) ? 8 : 4;
     d.WR = (int)std::min<int64_t>(wr_max, std::max(1, L.row_tiles / d.RT));
     d.WK = 1;
     int64_t row_blocks = (int64_t)ceil_div(L.row_tiles, d.RT * d.WR) * experts;
