@@ -1512,13 +1512,13 @@ static int rows_waves(const Layout& L, int M) {
   return L.row_tiles >= 512 ? 8 : 4;
 }
 
-// K shares for ccq_rows_kernel: about four workgroups per CU, at least one k-tile of every format per share.
+// K shares for ccq_rows_kernel: about four wavefronts per SIMD, at least one k-tile of every format per share.
 int rows_splits(const Layout& L, int M) {
   const int mrt = M > 32 ? 64 : (M > 16 ? 32 : 16);
   const int nw = rows_waves(L, M);
   const int64_t blocks = (int64_t)((M + mrt - 1) / mrt) * ((L.row_tiles + nw - 1) / nw);
   const int min_tiles = std::min(L.tiles[kNarrow] > 0 ? L.tiles[kNarrow] : 1 << 30, L.tiles[kWide] > 0 ? L.tiles[kWide] : 1 << 30);
-  int64_t s = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, blocks));
+  int64_t s = std::max<int64_t>(1, (4096 / nw) / std::max<int64_t>(1, blocks));  // 4096 wavefronts: four per SIMD
   s = std::min<int64_t>(s, 8);
   s = std::min<int64_t>(s, std::max(1, min_tiles));
   return (int)s;
