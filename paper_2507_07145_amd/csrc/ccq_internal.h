@@ -114,6 +114,9 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
 // Kernel for a few dozen to a few hundred rows, any format mix (ccq_mid.hip): 64-row tiles, K cut into S
 // shares whose fp32 partial tiles go to `partial` ([S][M][N]) when S > 1 (then call launch_reduce_splits).
 constexpr int kMidMinM = 17;
+int launch_mid_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride, const void* x,
+                       int64_t ldx, const int32_t* sorted_rows, int P, const int32_t* expert_offsets, int most_rows, void* y, int64_t ldy,
+                       void* stream);
 int mid_splits(const Layout& L, int M);
 int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
                void* stream);

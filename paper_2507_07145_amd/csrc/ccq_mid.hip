@@ -52,6 +52,11 @@ struct MidArgs {
   int32_t groups_narrow;
   int32_t sq[2], sr[2];   // K shares: share `split` owns tiles [split*sq + min(split, sr), +sq + (split < sr)) of each kind
   float zp[2];
+  // grouped calls (narrow-format kernel only): blockIdx.z = expert; its rows are output rows [offsets[e], offsets[e+1]),
+  // activation row sorted_rows[p] for output row p; expert e's arrays start e * stride bytes after expert 0's
+  const int32_t* sorted_rows;
+  const int32_t* expert_offsets;
+  int64_t codes_stride, scales_stride, ab_stride;
 };
 
 constexpr int kMidBM = 64;
@@ -448,7 +453,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
 // and then decodes 32 weights of one column per group: k-slots 8 kk .. 8 kk + 7 of MFMA step kk are weights
 // 32 h + 8 kk .. of the group, which is also how the activation fragment is read.  Only the activation tile
 // lives in LDS (18 KiB).
-template <int SM>
+template <int SM, bool GROUPED>
 __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
   constexpr int ROW = kMidRow;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -459,6 +464,18 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
   const int m_block = blockIdx.x % a.m_blocks, n_block = blockIdx.x / a.m_blocks;
   const int split = blockIdx.y;
   const int m0 = m_block * kMidBM, n0 = n_block * kMidBN;
+  // rows of this block's matrix: all M (dense), or the expert's (grouped; row_off = its first output row)
+  int Me = a.M, row_off = 0;
+  int64_t e_codes = 0, e_scales = 0, e_ab = 0;
+  if constexpr (GROUPED) {
+    const int e = blockIdx.z;
+    row_off = a.expert_offsets[e];
+    Me = a.expert_offsets[e + 1] - row_off;
+    if (m0 >= Me) return;  // uniform: before any barrier
+    e_codes = e * a.codes_stride;
+    e_scales = e * a.scales_stride;
+    e_ab = e * a.ab_stride;
+  }
   const int nl = lane & 15;
   const int ti = (lane >> 4) & 1, h = lane >> 5;  // the column this lane multiplies: row tile ti of the wavefront, row nl; k half h
 
@@ -472,14 +489,16 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int rtile = min(n0 / 16 + wave * 2 + i, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
-    code_base[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;
-    scale_base[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
+    code_base[i] = a.codes + e_codes + (int64_t)rtile * a.row_tile_bytes;
+    scale_base[i] = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scales) + e_scales) + (int64_t)rtile * a.row_tile_scale_halfs;
   }
   {
     const int rtile = min(n0 / 16 + wave * 2 + ti, a.row_tiles - 1);
-    al_t = a.alpha[rtile * 16 + nl];
-    be_t = a.beta[rtile * 16 + nl];
-    if constexpr (SM == 1) ssup_t = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+    al_t = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + e_ab)[rtile * 16 + nl];
+    be_t = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + e_ab)[rtile * 16 + nl];
+    // expert e's super scales: half the byte stride of alpha / beta (fp16 against fp32)
+    if constexpr (SM == 1)
+      ssup_t = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + e_ab / 2)[rtile * 16 + nl]);
   }
   uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u;
   float magic = 8388608.f;
@@ -521,7 +540,11 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int c = tid + 256 * i, row = c >> 3, col = c & 7;
-    xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
+    int64_t xr = row_off + min(m0 + row, Me - 1);  // rows past the end re-read the last row; their products are never stored
+    if constexpr (GROUPED) {
+      if (a.sorted_rows) xr = a.sorted_rows[xr];
+    }
+    xrow[i] = a.x + xr * a.ldx + col * 8;
     a_lds_off[i] = row * ROW + col * 8;
   }
   auto load_a = [&](u32x4 (&dst)[2], int s) {
@@ -642,9 +665,9 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       const float val = acc[i][r];
-      if (m < a.M && n < a.N) {
-        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + m) * a.N + n] = val;
-        else a.y[(int64_t)m * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
+      if (m < Me && n < a.N) {
+        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + row_off + m) * a.N + n] = val;
+        else a.y[(int64_t)(row_off + m) * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
       }
     }
   }
@@ -689,6 +712,9 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   a.tiles[0] = L.tiles[0];
   a.tiles[1] = L.tiles[1];
   a.groups_narrow = L.groups[kNarrow];
+  a.sorted_rows = nullptr;
+  a.expert_offsets = nullptr;
+  a.codes_stride = a.scales_stride = a.ab_stride = 0;
   for (int k = 0; k < 2; ++k) {
     a.sq[k] = L.tiles[k] / S;
     a.sr[k] = L.tiles[k] % S;
@@ -700,8 +726,8 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   if (fm == 1) {  // narrow format only: decoded weights stay in registers
     const size_t lds_r = (size_t)2 * kMidBM * kMidRow * 2;
     dim3 grid_r((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block_r(256);
-    if (L.scale_mode == 0) hipLaunchKernelGGL(ccq_midr_narrow_kernel<0>, grid_r, block_r, lds_r, static_cast<hipStream_t>(stream), a);
-    else hipLaunchKernelGGL(ccq_midr_narrow_kernel<1>, grid_r, block_r, lds_r, static_cast<hipStream_t>(stream), a);
+    if (L.scale_mode == 0) hipLaunchKernelGGL((ccq_midr_narrow_kernel<0, false>), grid_r, block_r, lds_r, static_cast<hipStream_t>(stream), a);
+    else hipLaunchKernelGGL((ccq_midr_narrow_kernel<1, false>), grid_r, block_r, lds_r, static_cast<hipStream_t>(stream), a);
     if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
     return CCQ_OK;
   }
@@ -718,6 +744,53 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   }
   dim3 grid((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block(256);
   hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
+  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+  return CCQ_OK;
+}
+
+// Grouped GEMM on narrow-format weights with many rows per expert: the register-decode 64-row kernel over
+// (row block of the expert, column block, expert); blocks past an expert's rows return at once.  `most_rows` = the
+// largest row count of an expert (from the host copy of the offsets); K is not cut (no workspace).
+int launch_mid_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride, const void* x,
+                       int64_t ldx, const int32_t* sorted_rows, int P, const int32_t* expert_offsets, int most_rows, void* y, int64_t ldy,
+                       void* stream) {
+  if (L.tiles[kWide] > 0 || L.tiles[kNarrow] == 0 || E < 1 || E > 65535 || most_rows < 1) return CCQ_ERR_UNSUPPORTED;
+  MidArgs a;
+  a.codes = static_cast<const uint8_t*>(w0->codes);
+  a.scales = static_cast<const uint16_t*>(w0->scales);
+  a.alpha = w0->code_alpha;
+  a.beta = w0->code_beta;
+  a.meta = nullptr;
+  a.scale_super = static_cast<const uint16_t*>(w0->scale_super);
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.partial = nullptr;
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.row_tile_bytes = L.row_tile_bytes;
+  a.row_tile_scale_halfs = L.row_tile_scale_halfs;
+  a.M = P;
+  a.N = L.N;
+  a.row_tiles = L.row_tiles;
+  a.m_blocks = (most_rows + kMidBM - 1) / kMidBM;
+  a.tiles[0] = L.tiles[0];
+  a.tiles[1] = L.tiles[1];
+  a.groups_narrow = L.groups[kNarrow];
+  for (int k = 0; k < 2; ++k) {
+    a.sq[k] = L.tiles[k];
+    a.sr[k] = 0;
+    a.zp[k] = L.zp[k];
+  }
+  a.sorted_rows = sorted_rows;
+  a.expert_offsets = expert_offsets;
+  a.codes_stride = codes_stride;
+  a.scales_stride = scales_stride;
+  a.ab_stride = ab_stride;
+  const int n_blocks = (L.N + kMidBN - 1) / kMidBN;
+  const size_t lds_r = (size_t)2 * kMidBM * kMidRow * 2;
+  dim3 grid((unsigned)(a.m_blocks * n_blocks), 1u, (unsigned)E), block(256);
+  if (L.scale_mode == 0) hipLaunchKernelGGL((ccq_midr_narrow_kernel<0, true>), grid, block, lds_r, static_cast<hipStream_t>(stream), a);
+  else hipLaunchKernelGGL((ccq_midr_narrow_kernel<1, true>), grid, block, lds_r, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }

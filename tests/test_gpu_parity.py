@@ -256,6 +256,40 @@ def test_grouped_small(kinds, K, N):
         assert np.array_equal(canon_zero(got[e]), canon_zero(o.to_bf16_bits(cases[e].W()[:, ks].T))), f"expert {e}"
 
 
+@pytest.mark.parametrize("K,N", [(512, 160), (1024, 64)])
+def test_grouped_many_rows_per_expert(K, N):
+    """A prefill-sized routing on narrow-format weights: experts with several 64-row blocks, one with none, one with a
+    single row; with the host copy of the offsets the 64-row kernel runs, without it the per-row-tile kernel does."""
+    E, T = 5, 90
+    cases = [random_case(K, N, ["narrow"], 13, stream0=10 * e) for e in range(E)]
+    w = b.Weight.from_canonical(K, N, [b.NARROW], np.stack([c.codes for c in cases]), np.stack([c.scales for c in cases]),
+                                np.stack([c.alpha for c in cases]), np.stack([c.beta for c in cases]), device=DEV, experts=E)
+    x = synth.activations_bf16(T, K, synth.rng(13, 99))
+    counts = [130, 0, 70, 1, 33]
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    P = int(offs[-1])
+    rows = synth.rng(13, 98).integers(0, T, size=P).astype(np.int32)
+    ref = _grouped_reference(cases, x, rows, offs)
+    abs_sum = o.grouped_matmul(x & np.uint16(0x7FFF), rows, offs, lambda e: np.abs(cases[e].W()))
+    for host_offsets in (offs, None):
+        y = torch.full((P + 1, N), 3.0, dtype=torch.bfloat16, device=DEV)
+        b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), host_offsets, out=y[:P])
+        torch.cuda.synchronize()
+        assert_gemm_close(b.bf16_bits(y[:P]), ref, f"grouped, many rows, host offsets {'given' if host_offsets is not None else 'absent'}", abs_sum=abs_sum)
+        assert bool((y[P] == 3.0).all())
+    # decoded weights, bit exact, through the 64-row kernel: 40 one-hot tokens per expert
+    ks = synth.rng(13, 97).integers(0, K, 40)
+    ks[:4] = [0, 63, K - 64, K - 1]
+    xe = synth.one_hot_bf16(ks, K)
+    offs2 = (np.arange(E + 1) * len(ks)).astype(np.int32)
+    rows2 = np.tile(np.arange(len(ks), dtype=np.int32), E)
+    y2 = b.grouped_gemm(w, b.bf16_tensor(xe, DEV), torch.from_numpy(rows2).to(DEV), torch.from_numpy(offs2).to(DEV), offs2)
+    torch.cuda.synchronize()
+    got = b.bf16_bits(y2).reshape(E, len(ks), N)
+    for e in range(E):
+        assert np.array_equal(canon_zero(got[e]), canon_zero(o.to_bf16_bits(cases[e].W()[:, ks].T))), f"expert {e}"
+
+
 @pytest.mark.parametrize("kinds,K,N", [(["narrow"], 512, 64), (["wide"], 512, 32), (["narrow"], 2048, 160)])
 def test_grouped_one_token(kinds, K, N):
     """One token's decode step: no expert has more than one row (some have none); with the host copy of the
