@@ -281,6 +281,7 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=32, help="weight copies the step rotates over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-more-rows", action="store_true", help="skip the M = 8 and M = 16 rows of config 2")
     ap.add_argument("--no-compressed", action="store_true", help="skip the compressed-scale variant of the GEMV")
     ap.add_argument("--launch", type=str, default="", help="explicit decomposition RT,WR,WK,S for tuning (default: the library's choice)")
     ap.add_argument("--paper-tables", action="store_true",
@@ -343,6 +344,20 @@ def main() -> int:
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
                      "kernel": "ccq_gemv_narrow_kernel", "us_per_launch": round(per_launch_s * 1e6, 3)},
     }
+
+    if not args.no_more_rows:
+        # the other row counts of config 2 (M = 8, 16), same weights, as context
+        rows_out = []
+        for Mr in (8, 16):
+            xr = b.bf16_tensor(synth.activations_bf16(Mr, K, synth.rng(2, 30 + Mr)), dev)
+            yr = [torch.empty((Mr, N), dtype=torch.bfloat16, device=dev) for _ in weights]
+            wsr = torch.empty(max(b.pack_info(weights[0].desc, Mr).workspace_bytes, 16), dtype=torch.uint8, device=dev)
+            fns = [(lambda w=w, y=y: b.gemm(w, xr, out=y, workspace=wsr)) for w, y in zip(weights, yr)]
+            _, ev_r = time_steps(fns, 20 * len(fns), len(fns), dev)
+            us = ev_r / (20 * len(fns)) * 1e6
+            nb = algorithmic_bytes(K, N, Mr, weights[0].info.code_bytes, True)
+            rows_out.append({"M": Mr, "us_per_launch": round(us, 2), "GBps": round(nb / us / 1e3, 1), "frac_of_hbm_peak": round(nb / us / 1e3 / HBM_PEAK_GBS, 4)})
+        out["config2_more_rows"] = rows_out
 
     if not args.no_prefill:
         Kp, Np, Mp = 7168, 18432, 2048
