@@ -169,7 +169,7 @@ int ccq_gemm_ex(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void
  *   validated (CCQ_ERR_ROUTING) and shapes the launch -- it must equal the
  *   device array: experts it shows as empty may not be visited at all, and
  *   with at most one row per expert the one-row kernel runs, with more than
- *   32 rows on an expert of narrow-format weights the 64-row kernel; device data is
+ *   32 rows on an expert the 64-row kernel; device data is
  *   never read back.  A call captured into a HIP graph that is replayed
  *   with other routings must pass NULL here: the launch recorded with a
  *   host copy is tied to that routing's set of busy experts;

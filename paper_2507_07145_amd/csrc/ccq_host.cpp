@@ -523,10 +523,10 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
     for (int e = 0; e < E; ++e)
       if (expert_offsets_host[e + 1] > expert_offsets_host[e]) c.active_ids[k++] = (uint16_t)e;
   }
-  if (expert_offsets_host && most_rows > 32 && L.tiles[kWide] == 0) {
-    // many rows per expert on narrow-format weights (a prefill-sized routing): the 64-row register-decode kernel, one
-    // grid over (row block, column block, expert); measured 2.2-2.4 times faster than 64-row passes of the per-row-tile
-    // kernel from 33 rows on, slower below
+  if (expert_offsets_host && most_rows > 32) {
+    // many rows per expert (a prefill-sized routing): the 64-row kernel, one grid over (row block, column block,
+    // expert); on narrow-format weights measured 2.2-2.4 times faster than 64-row passes of the per-row-tile kernel
+    // from 33 rows on, slower below
     rc = launch_mid_grouped(w0, L, E, codes_stride, scales_stride, ab_stride, x, ldx, sorted_rows, P, expert_offsets_dev, most_rows, y, ldy,
                             hip_stream);
     if (rc != CCQ_ERR_UNSUPPORTED) return rc;

@@ -79,7 +79,7 @@ __device__ __forceinline__ uint32_t dword_sel(const u32x4& v, int j) { return j 
 // scales; 1 the compressed scales of Sec. 3.4: group scale = 4-bit field * per-row super scale, first line of
 // Alg. 2 / Alg. 3; the field of a narrow group comes from the packed scale array, that of a wide group from the
 // spare low nibble of the group's last code byte).
-template <int FM, int SM>
+template <int FM, int SM, bool GROUPED>
 __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   constexpr bool HAS_N = FM == 1 || FM == 3, HAS_W = FM >= 2, META = FM == 3, H16 = FM == 4;
   constexpr int ROW = H16 ? kMidRowH16 : kMidRow;
@@ -95,6 +95,18 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   const int split = blockIdx.y;
   const int m0 = m_block * kMidBM, n0 = n_block * kMidBN;
   const int kq = lane >> 4, nl = lane & 15;
+  // rows of this block's matrix: all M (dense), or the expert's (grouped; row_off = its first output row)
+  int Me = a.M, row_off = 0;
+  int64_t e_codes = 0, e_scales = 0, e_ab = 0;
+  if constexpr (GROUPED) {
+    const int e = blockIdx.z;
+    row_off = a.expert_offsets[e];
+    Me = a.expert_offsets[e + 1] - row_off;
+    if (m0 >= Me) return;  // uniform: before any barrier
+    e_codes = e * a.codes_stride;
+    e_scales = e * a.scales_stride;
+    e_ab = e * a.ab_stride;
+  }
 
   // this share's k-tiles of each kind, and its steps (one 64-weight group each): narrow first, then wide
   int tA[2], tB[2];
@@ -128,15 +140,17 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
 #pragma unroll
   for (int i = 0; i < kMidRTW; ++i) {
     const int rtile = min(n0 / 16 + wave * kMidRTW + i, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
-    code_base[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;
-    scale_base[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
+    code_base[i] = a.codes + e_codes + (int64_t)rtile * a.row_tile_bytes;
+    scale_base[i] = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scales) + e_scales) + (int64_t)rtile * a.row_tile_scale_halfs;
     al[i] = 0.f;
     be[i] = 0.f;
     ssup[i] = 0.f;
-    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+    // expert e's super scales: half the byte stride of alpha / beta (fp16 against fp32)
+    if constexpr (SM == 1)
+      ssup[i] = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + e_ab / 2)[rtile * 16 + nl]);
     if constexpr (HAS_N) {
-      al[i] = a.alpha[rtile * 16 + nl];
-      be[i] = a.beta[rtile * 16 + nl];
+      al[i] = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + e_ab)[rtile * 16 + nl];
+      be[i] = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + e_ab)[rtile * 16 + nl];
     }
   }
   const int64_t wide_code_off = (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
@@ -182,7 +196,11 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int c = tid + 256 * i, row = c >> 3, col = c & 7;
-    xrow[i] = a.x + (int64_t)min(m0 + row, a.M - 1) * a.ldx + col * 8;
+    int64_t xr = row_off + min(m0 + row, Me - 1);
+    if constexpr (GROUPED) {
+      if (a.sorted_rows) xr = a.sorted_rows[xr];
+    }
+    xrow[i] = a.x + xr * a.ldx + col * 8;
     a_lds_off[i] = row * ROW + (H16 ? 0 : col * 8);
   }
   // hybrid word: element e of a group sits in slot 8 (e / 7) + e % 7 (weight 63, alone in the last word, in
@@ -436,9 +454,9 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       const float val = acc[i][r];  // by value: bit-casting the element lvalue itself reads element 0
-      if (m < a.M && n < a.N) {
-        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + m) * a.N + n] = val;
-        else a.y[(int64_t)m * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
+      if (m < Me && n < a.N) {
+        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + row_off + m) * a.N + n] = val;
+        else a.y[(int64_t)(row_off + m) * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
       }
     }
   }
@@ -734,8 +752,8 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   const size_t lds = (size_t)2 * (kMidBM + kMidBN) * (fm == 4 ? kMidRowH16 : kMidRow) * 2 + (fm == 3 ? (size_t)max_steps * 4 : 0);
   if (lds > (fm == 4 ? 72 : 64) * 1024) return CCQ_ERR_UNSUPPORTED;
   typedef void (*MidKernel)(const MidArgs);
-  const MidKernel table[2][4] = {{ccq_mid_kernel<1, 0>, ccq_mid_kernel<2, 0>, ccq_mid_kernel<3, 0>, ccq_mid_kernel<4, 0>},
-                                 {ccq_mid_kernel<1, 1>, ccq_mid_kernel<2, 1>, ccq_mid_kernel<3, 1>, ccq_mid_kernel<4, 1>}};
+  const MidKernel table[2][4] = {{ccq_mid_kernel<1, 0, false>, ccq_mid_kernel<2, 0, false>, ccq_mid_kernel<3, 0, false>, ccq_mid_kernel<4, 0, false>},
+                                 {ccq_mid_kernel<1, 1, false>, ccq_mid_kernel<2, 1, false>, ccq_mid_kernel<3, 1, false>, ccq_mid_kernel<4, 1, false>}};
   const MidKernel kern = table[L.scale_mode][fm - 1];
   if (!kern) return CCQ_ERR_UNSUPPORTED;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -748,19 +766,19 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   return CCQ_OK;
 }
 
-// Grouped GEMM on narrow-format weights with many rows per expert: the register-decode 64-row kernel over
+// Grouped GEMM with many rows per expert: the 64-row kernel (register-decode variant for the narrow format) over
 // (row block of the expert, column block, expert); blocks past an expert's rows return at once.  `most_rows` = the
 // largest row count of an expert (from the host copy of the offsets); K is not cut (no workspace).
 int launch_mid_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride, const void* x,
                        int64_t ldx, const int32_t* sorted_rows, int P, const int32_t* expert_offsets, int most_rows, void* y, int64_t ldy,
                        void* stream) {
-  if (L.tiles[kWide] > 0 || L.tiles[kNarrow] == 0 || E < 1 || E > 65535 || most_rows < 1) return CCQ_ERR_UNSUPPORTED;
+  if (E < 1 || E > 65535 || most_rows < 1) return CCQ_ERR_UNSUPPORTED;
   MidArgs a;
   a.codes = static_cast<const uint8_t*>(w0->codes);
   a.scales = static_cast<const uint16_t*>(w0->scales);
   a.alpha = w0->code_alpha;
   a.beta = w0->code_beta;
-  a.meta = nullptr;
+  a.meta = static_cast<const int32_t*>(w0->meta);
   a.scale_super = static_cast<const uint16_t*>(w0->scale_super);
   a.x = static_cast<const uint16_t*>(x);
   a.y = static_cast<uint16_t*>(y);
@@ -787,10 +805,27 @@ int launch_mid_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t cod
   a.scales_stride = scales_stride;
   a.ab_stride = ab_stride;
   const int n_blocks = (L.N + kMidBN - 1) / kMidBN;
-  const size_t lds_r = (size_t)2 * kMidBM * kMidRow * 2;
   dim3 grid((unsigned)(a.m_blocks * n_blocks), 1u, (unsigned)E), block(256);
-  if (L.scale_mode == 0) hipLaunchKernelGGL((ccq_midr_narrow_kernel<0, true>), grid, block, lds_r, static_cast<hipStream_t>(stream), a);
-  else hipLaunchKernelGGL((ccq_midr_narrow_kernel<1, true>), grid, block, lds_r, static_cast<hipStream_t>(stream), a);
+  const int fm = L.h16 ? 4 : (L.tiles[kNarrow] > 0 ? 1 : 0) | (L.tiles[kWide] > 0 ? 2 : 0);
+  if (fm == 1) {  // narrow format only: decoded weights stay in registers
+    const size_t lds_r = (size_t)2 * kMidBM * kMidRow * 2;
+    if (L.scale_mode == 0) hipLaunchKernelGGL((ccq_midr_narrow_kernel<0, true>), grid, block, lds_r, static_cast<hipStream_t>(stream), a);
+    else hipLaunchKernelGGL((ccq_midr_narrow_kernel<1, true>), grid, block, lds_r, static_cast<hipStream_t>(stream), a);
+    if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
+    return CCQ_OK;
+  }
+  const int max_steps = L.tiles[kNarrow] * kNarrowGroupsPerTile + L.tiles[kWide] * kWideGroupsPerTile;
+  const size_t lds = (size_t)2 * (kMidBM + kMidBN) * (fm == 4 ? kMidRowH16 : kMidRow) * 2 + (fm == 3 ? (size_t)max_steps * 4 : 0);
+  if (lds > (fm == 4 ? 72 : 64) * 1024) return CCQ_ERR_UNSUPPORTED;
+  typedef void (*MidKernel)(const MidArgs);
+  const MidKernel table[2][3] = {{ccq_mid_kernel<2, 0, true>, ccq_mid_kernel<3, 0, true>, ccq_mid_kernel<4, 0, true>},
+                                 {ccq_mid_kernel<2, 1, true>, ccq_mid_kernel<3, 1, true>, ccq_mid_kernel<4, 1, true>}};
+  const MidKernel kern = table[L.scale_mode][fm - 2];
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }

@@ -256,14 +256,20 @@ def test_grouped_small(kinds, K, N):
         assert np.array_equal(canon_zero(got[e]), canon_zero(o.to_bf16_bits(cases[e].W()[:, ks].T))), f"expert {e}"
 
 
-@pytest.mark.parametrize("K,N", [(512, 160), (1024, 64)])
-def test_grouped_many_rows_per_expert(K, N):
-    """A prefill-sized routing on narrow-format weights: experts with several 64-row blocks, one with none, one with a
-    single row; with the host copy of the offsets the 64-row kernel runs, without it the per-row-tile kernel does."""
+@pytest.mark.parametrize("kinds,K,N,n_wide", [(["narrow"], 512, 160, None), (["narrow"], 1024, 64, None), (["wide"], 512, 160, None),
+                                              (["narrow", "wide"], 2048, 144, 8)])
+def test_grouped_many_rows_per_expert(kinds, K, N, n_wide):
+    """A prefill-sized routing: experts with several 64-row blocks, one with none, one with a single row; with the
+    host copy of the offsets the 64-row kernel runs, without it the per-row-tile kernel does."""
     E, T = 5, 90
-    cases = [random_case(K, N, ["narrow"], 13, stream0=10 * e) for e in range(E)]
-    w = b.Weight.from_canonical(K, N, [b.NARROW], np.stack([c.codes for c in cases]), np.stack([c.scales for c in cases]),
-                                np.stack([c.alpha for c in cases]), np.stack([c.beta for c in cases]), device=DEV, experts=E)
+    cases = [random_case(K, N, kinds, 13, stream0=10 * e, n_wide=n_wide) for e in range(E)]
+    for c in cases:
+        c.group_fmt = cases[0].group_fmt  # one format map for all experts
+    fmts = [b.NARROW if k == "narrow" else b.WIDE for k in kinds]
+    has_n = "narrow" in kinds
+    w = b.Weight.from_canonical(K, N, fmts, np.stack([c.codes for c in cases]), np.stack([c.scales for c in cases]),
+                                np.stack([c.alpha for c in cases]) if has_n else None, np.stack([c.beta for c in cases]) if has_n else None,
+                                cases[0].group_fmt, device=DEV, experts=E)
     x = synth.activations_bf16(T, K, synth.rng(13, 99))
     counts = [130, 0, 70, 1, 33]
     offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
