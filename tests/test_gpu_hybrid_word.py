@@ -137,6 +137,36 @@ def test_grouped():
             assert_gemm_close(got[lo:hi], o.matmul(x[rows[lo:hi]], cases[e].W()), f"expert {e}")
 
 
+def test_grouped_many_rows_per_expert():
+    """More than 32 rows on an expert: with the host copy of the offsets the 64-row kernel runs, without it the
+    per-row-tile kernel; decoded weights bit exact through the 64-row kernel."""
+    E, K, N, T = 3, 1024, 80, 50
+    cases = [random_h16(K, N, 29, stream0=10 * e) for e in range(E)]
+    w = b.Weight.from_canonical(K, N, b.H16, np.stack([c.codes for c in cases]), np.stack([c.scales for c in cases]), device=DEV, experts=E)
+    x = synth.activations_bf16(T, K, synth.rng(29, 99))
+    offs = np.array([0, 70, 70, 105], dtype=np.int32)
+    rows = synth.rng(29, 98).integers(0, T, 105).astype(np.int32)
+    for host_offsets in (offs, None):
+        y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), host_offsets)
+        torch.cuda.synchronize()
+        got = b.bf16_bits(y)
+        for e in range(E):
+            lo, hi = offs[e], offs[e + 1]
+            if hi > lo:
+                xe = x[rows[lo:hi]]
+                abs_sum = o.matmul(xe & np.uint16(0x7FFF), np.abs(cases[e].W()))
+                assert_gemm_close(got[lo:hi], o.matmul(xe, cases[e].W()), f"expert {e}", abs_sum=abs_sum)
+    ks = synth.rng(29, 97).integers(0, K, 40)
+    ks[:4] = [0, 62, 63, K - 1]
+    offs2 = (np.arange(E + 1) * len(ks)).astype(np.int32)
+    rows2 = np.tile(np.arange(len(ks), dtype=np.int32), E)
+    y2 = b.grouped_gemm(w, b.bf16_tensor(synth.one_hot_bf16(ks, K), DEV), torch.from_numpy(rows2).to(DEV), torch.from_numpy(offs2).to(DEV), offs2)
+    torch.cuda.synchronize()
+    got = b.bf16_bits(y2).reshape(E, len(ks), N)
+    for e in range(E):
+        assert np.array_equal(canon_zero(got[e]), canon_zero(o.to_bf16_bits(cases[e].W()[:, ks].T))), f"expert {e}"
+
+
 # ---------------------------------------------------------------- compressed scales (Sec. 3.4; Alg. 2 with scale mask 0x1FFF)
 
 
