@@ -74,9 +74,12 @@ def test_grouped_compressed_scales_wide_and_mixed():
         alpha, beta = alpha.reshape(E, N), beta.reshape(E, N)
         fm = [b.WIDE] if len(kinds) == 1 else [b.NARROW, b.WIDE]
         w = b.Weight.from_canonical_compressed(K, N, fm, codes, sq, ssup, alpha, beta, gf, device=DEV, experts=E)
-        rows, offs = synth.routing_topk(T, E, topk, rng)
-        x = synth.activations_bf16(T, K, rng)
-        y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
-        torch.cuda.synchronize()
-        ref = o.grouped_matmul(x, rows, offs, lambda e: o.decode_cs(K, N, ofmt, codes[e], sq[e], ssup[e], alpha[e], beta[e], gf))
-        assert_gemm_close(b.bf16_bits(y), ref, f"grouped, compressed scales, {kinds}")
+        for Tt in (T, 90):  # 5 rows per expert on average (per-row-tile kernel), then 45 (64-row kernel)
+            rows, offs = synth.routing_topk(Tt, E, topk, rng)
+            x = synth.activations_bf16(Tt, K, rng)
+            y = b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
+            torch.cuda.synchronize()
+            Wd = [o.decode_cs(K, N, ofmt, codes[e], sq[e], ssup[e], alpha[e], beta[e], gf) for e in range(E)]
+            ref = o.grouped_matmul(x, rows, offs, lambda e: Wd[e])
+            abs_sum = o.grouped_matmul(x & np.uint16(0x7FFF), rows, offs, lambda e: np.abs(Wd[e])) if Tt > T else None
+            assert_gemm_close(b.bf16_bits(y), ref, f"grouped, compressed scales, {kinds}, {Tt} tokens", abs_sum=abs_sum)
