@@ -368,11 +368,13 @@ def main() -> int:
         xp = b.bf16_tensor(synth.activations_bf16(Mp, Kp, synth.rng(5, 3)), dev)
         yp = torch.empty((Mp, Np), dtype=torch.bfloat16, device=dev)
         wsp = torch.empty(max(b.pack_info(wp.desc, Mp).workspace_bytes, 16), dtype=torch.uint8, device=dev)
-        for _ in range(2):
+        # the clock takes some 20 ms of this load to settle (the first launches after the GEMV legs run about 20 %
+        # slower than the sustained rate): 50 untimed launches, then 100 timed ones (about 50 ms)
+        for _ in range(50):
             b.gemm(wp, xp, out=yp, workspace=wsp)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 20
+        reps = 100
         e0.record()
         for _ in range(reps):
             b.gemm(wp, xp, out=yp, workspace=wsp)
