@@ -172,7 +172,7 @@ int ccq_gemm_ex(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void
  *   32 rows on an expert the 64-row kernel; device data is
  *   never read back.  A call captured into a HIP graph that is replayed
  *   with other routings must pass NULL here: the launch recorded with a
- *   host copy is tied to that routing's set of busy experts;
+ *   host copy is tied to that routing (its busy experts, their row counts);
  *   y DEVICE bf16 [P][ldy].  An expert with no rows writes nothing.
  *   The top-k combine and any activation function stay with the caller. */
 int ccq_grouped_gemm(const ccq_weight *w0, int32_t E, int64_t codes_stride, int64_t scales_stride,
