@@ -215,8 +215,9 @@ def hybrid_word(dev) -> int:
         ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in ws]
         wsp = torch.empty(max(b.pack_info(ws[0].desc, M).workspace_bytes, 16), dtype=torch.uint8, device=dev)
         fns = [(lambda w=w, y=y: b.gemm(w, x, out=y, workspace=wsp)) for w, y in zip(ws, ys)]
-        steps = copies * (20 if M <= 64 else 2)
-        _, ev = time_steps(fns, steps, copies, dev)
+        # enough launches before and inside the timed region for the clock to settle (about 20 ms of load)
+        steps = copies * (20 if M <= 64 else (8 if M <= 256 else 2))
+        _, ev = time_steps(fns, steps, copies * (4 if 64 < M <= 256 else 1), dev)
         nbytes = per_copy + 2 * M * K + 2 * M * N
         us = ev / steps * 1e6
         out["rows"].append({"M": M, "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
