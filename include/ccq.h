@@ -32,12 +32,16 @@
  *
  * Conventions
  *   - Every pointer is marked HOST or DEVICE.  The caller owns all buffers; the
- *     library never allocates, frees or synchronises.  DEVICE pointers must be
- *     16-byte aligned.
+ *     library never allocates or frees device memory and never synchronises
+ *     (the host-side ccq_pack_* routines use temporary host memory of their
+ *     own).  DEVICE pointers must be 16-byte aligned.
  *   - ccq_gemm / ccq_grouped_gemm enqueue work on `hip_stream` (a hipStream_t
  *     passed as void*, NULL = the default stream) and return immediately.
- *   - Return value: CCQ_OK or a negative ccq_status.  On error nothing has
- *     been enqueued.
+ *   - Return value: CCQ_OK or a negative ccq_status.  Arguments, launch shapes
+ *     and workspace sizes are all checked before the first launch: on any
+ *     error other than CCQ_ERR_HIP nothing has been enqueued (CCQ_ERR_HIP
+ *     reports a HIP launch that failed, possibly after earlier launches of
+ *     the same call).
  *   - "Canonical" order is the paper's: row n of W_q is the concatenation over
  *     groups (k order) of the group's codes, code j covering weights N*j..N*j+N-1
  *     of the group (Alg. 2/3: q_w = W_q[idx / p_w]); the first state of a code
@@ -92,8 +96,9 @@ typedef struct {
                                13 bits of its last word, Sec. 3.4)                        */
   const float *code_alpha;  /* DEVICE, fp32[N]: Code Cluster scale s_code, >= 0        */
   const float *code_beta;   /* DEVICE, fp32[N]: Code Cluster zero-point zp_code, an
-                               integer value with 255*alpha + beta < 2^15 (the
-                               kernels rely on it; device data is not checked)         */
+                               integer value >= 0 with round(255*alpha + beta) <= 2^15 - 1,
+                               i.e. every byte expands to a 15-bit code (the kernels
+                               rely on it; device data is not checked)                 */
   const void *meta;         /* DEVICE, group map in device order (ccq_pack_meta); may be NULL when group_fmt is NULL */
   int32_t scale_mode;       /* 0 = fp16 group scales; 1 = compressed scales of Sec. 3.4: group scale =
                                4-bit (hybrid word: 13-bit) field * scale_super[n] (first line of Alg. 2 / Alg. 3).  Mode 1 is
@@ -141,6 +146,10 @@ int ccq_pack_scales4(const ccq_weight *w, const uint8_t *canonical_sq, void *out
  *   ccq_pack_info reports for M_max >= M (may be NULL if that value is 0). */
 int ccq_gemm(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void *y, int64_t ldy,
              void *workspace, int64_t workspace_bytes, void *hip_stream);
+
+/* Workspace bytes ccq_gemm needs for exactly M rows (<= the ccq_pack_info figure for any M_max >= M);
+ * -1 for an invalid descriptor.  Pure host code. */
+int64_t ccq_gemm_workspace_bytes(const ccq_weight *w, int32_t M);
 
 /* Explicit launch shape for ccq_gemm_ex (0 = let the library choose).  */
 typedef struct {
@@ -210,6 +219,21 @@ int64_t ccq_quantize_workspace_bytes(const ccq_weight *w);
 int ccq_quantize(const ccq_weight *w, const float *W, int64_t ldw, void *codes_out, void *scales_out,
                  float *alpha_out, float *beta_out, void *scale_super_out, void *workspace,
                  int64_t workspace_bytes, void *hip_stream);
+
+/* Ceiling probes (measurement only; not on the hot path).  The "Inference Performance" section
+ * calls the operator memory-bound; these two kernels show what the memory system and the matrix cores deliver
+ * when nothing else is asked of them, so that a kernel's rate can be set against an achievable figure as well
+ * as against the published peak.
+ *   ccq_probe_stream_read: reads src DEVICE [bytes] (a multiple of 16) once with 16-byte nontemporal loads,
+ *     loads_per_thread (1, 2, 4 or 8) requests in flight per thread, block_threads (a multiple of 64, at most
+ *     512) threads per workgroup; sink DEVICE, at least 4 bytes (written with probability 2^-32 per thread).
+ *   ccq_probe_mfma_bf16: `workgroups` workgroups of four wavefronts, each issuing iters x 4 independent
+ *     32x32x16 bf16 MFMAs on operands DEVICE bf16 [8][64][8] (read once); sink DEVICE fp32 [workgroups * 256];
+ *     *flop_out (HOST, may be NULL) receives the floating-point operations of the launch.
+ * Both enqueue one kernel on hip_stream and return a ccq_status. */
+int ccq_probe_stream_read(const void *src, int64_t bytes, int32_t loads_per_thread, int32_t block_threads, void *sink,
+                          void *hip_stream);
+int ccq_probe_mfma_bf16(const void *operands, int32_t workgroups, int32_t iters, void *sink, void *hip_stream, double *flop_out);
 
 /* Human-readable name of a status code. */
 const char *ccq_status_string(int status);

@@ -60,7 +60,8 @@ H16_LO = ccq_code(3, 4, 2, 0, 4.0)    # (L=3,N=4,S=2): low 9 bits; 10 words per 
 H16 = [H16_HI, H16_LO]
 
 EXPORTS = ["ccq_pack_info", "ccq_pack_codes", "ccq_pack_scales", "ccq_pack_scales4", "ccq_pack_meta", "ccq_gemm", "ccq_gemm_ex",
-           "ccq_grouped_gemm", "ccq_grouped_workspace_bytes", "ccq_quantize", "ccq_quantize_workspace_bytes", "ccq_status_string"]
+           "ccq_grouped_gemm", "ccq_grouped_workspace_bytes", "ccq_quantize", "ccq_quantize_workspace_bytes", "ccq_status_string",
+           "ccq_probe_stream_read", "ccq_probe_mfma_bf16", "ccq_gemm_workspace_bytes"]
 
 _lib = None
 
@@ -90,12 +91,18 @@ def load() -> ctypes.CDLL:
     L.ccq_gemm_ex.argtypes = [wp, vp, i32, i64, vp, i64, vp, i64, vp, ctypes.POINTER(ccq_launch)]
     L.ccq_grouped_gemm.restype = ctypes.c_int
     L.ccq_grouped_gemm.argtypes = [wp, i32, i64, i64, i64, vp, i32, i64, vp, i32, vp, vp, vp, i64, vp, i64, vp]
+    L.ccq_gemm_workspace_bytes.restype = i64
+    L.ccq_gemm_workspace_bytes.argtypes = [wp, i32]
     L.ccq_grouped_workspace_bytes.restype = i64
     L.ccq_grouped_workspace_bytes.argtypes = [wp, i32, i32]
     L.ccq_quantize_workspace_bytes.restype = i64
     L.ccq_quantize_workspace_bytes.argtypes = [wp]
     L.ccq_quantize.restype = ctypes.c_int
     L.ccq_quantize.argtypes = [wp, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    L.ccq_probe_stream_read.restype = ctypes.c_int
+    L.ccq_probe_stream_read.argtypes = [vp, i64, i32, i32, vp, vp]
+    L.ccq_probe_mfma_bf16.restype = ctypes.c_int
+    L.ccq_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.ccq_status_string.restype = ctypes.c_char_p
     L.ccq_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -326,8 +333,10 @@ def gemm(w: Weight, x: torch.Tensor, out: torch.Tensor | None = None, workspace:
     M = x.shape[0]
     y = out if out is not None else torch.empty((M, w.N), dtype=torch.bfloat16, device=x.device)
     if workspace is None:
-        need = launch.splits_k * M * w.N * 4 if (launch is not None and launch.splits_k > 1) else pack_info(w.desc, max(M, 1)).workspace_bytes
+        need = launch.splits_k * min(M, 64) * w.N * 4 if (launch is not None and launch.splits_k > 1) else gemm_workspace_bytes(w.desc, M)
         workspace = _workspace(need, x.device)
+        if workspace is not None and stream is not None:
+            workspace.record_stream(stream)   # the temporary returns to the allocator at once; its memory must outlive the kernels
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     L = load()
     if launch is None:
@@ -337,6 +346,13 @@ def gemm(w: Weight, x: torch.Tensor, out: torch.Tensor | None = None, workspace:
                            _stream_ptr(stream), ctypes.byref(launch))
     _check(rc, "ccq_gemm")
     return y
+
+
+def gemm_workspace_bytes(desc: ccq_weight, M: int) -> int:
+    need = int(load().ccq_gemm_workspace_bytes(ctypes.byref(desc), M))
+    if need < 0:
+        raise CcqError(-2, "ccq_gemm_workspace_bytes")
+    return need
 
 
 def grouped_workspace_bytes(w: Weight, P: int) -> int:
@@ -353,6 +369,8 @@ def grouped_gemm(w: Weight, x: torch.Tensor, sorted_rows: torch.Tensor, expert_o
     y = out if out is not None else torch.empty((P, w.N), dtype=torch.bfloat16, device=x.device)
     if workspace is None:
         workspace = _workspace(max(grouped_workspace_bytes(w, P), 0), x.device)
+        if workspace is not None and stream is not None:
+            workspace.record_stream(stream)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     cs, ss, abs_ = w.strides()
     host = None
@@ -363,3 +381,19 @@ def grouped_gemm(w: Weight, x: torch.Tensor, sorted_rows: torch.Tensor, expert_o
                                  _stream_ptr(stream))
     _check(rc, "ccq_grouped_gemm")
     return y
+
+
+def probe_stream_read(src: torch.Tensor, sink: torch.Tensor, loads_per_thread: int = 4, block_threads: int = 512, stream=None) -> None:
+    """Read `src` (uint8, a multiple of 16 bytes) once through ccq_probe_stream_read."""
+    nbytes = src.numel() * src.element_size()
+    _check(load().ccq_probe_stream_read(_t_ptr(src), nbytes, loads_per_thread, block_threads, _t_ptr(sink), _stream_ptr(stream)),
+           "ccq_probe_stream_read")
+
+
+def probe_mfma_bf16(operands: torch.Tensor, sink: torch.Tensor, workgroups: int, iters: int, stream=None) -> float:
+    """Back-to-back bf16 MFMAs through ccq_probe_mfma_bf16; returns the floating-point operations of the launch."""
+    assert operands.numel() * operands.element_size() >= 8 * 64 * 16 and sink.numel() >= workgroups * 256
+    flop = ctypes.c_double(0.0)
+    _check(load().ccq_probe_mfma_bf16(_t_ptr(operands), workgroups, iters, _t_ptr(sink), _stream_ptr(stream), ctypes.byref(flop)),
+           "ccq_probe_mfma_bf16")
+    return float(flop.value)

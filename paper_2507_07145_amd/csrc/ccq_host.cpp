@@ -162,19 +162,50 @@ static DensePath dense_path(const Layout& L, int M) {
   return kPathMid;
 }
 
-static int64_t dense_workspace_bytes(const Layout& L, int M) {
+// Workspace the per-row-tile kernel needs for M rows in the library's own decomposition: it walks the rows in
+// passes of kMaxSkinnyM and a last, shorter one.
+static int64_t skinny_need(const Layout& L, int M) {
   int64_t need = 0;
-  for (int m = 1; m <= M; ++m) {
-    const DensePath p = dense_path(L, m);
-    if (p == kPathPrefill) continue;
-    if (p == kPathMid || p == kPathRows) {
-      const int S = p == kPathMid ? mid_splits(L, m) : rows_splits(L, m);
-      if (S > 1) need = std::max(need, (int64_t)S * m * L.N * 4);
-    } else {
-      Decomp d = choose_decomp(L, m, 1, m);
-      if (d.S > 1) need = std::max(need, (int64_t)d.S * m * L.N * 4);
-    }
+  for (int mc : {M >= kMaxSkinnyM ? kMaxSkinnyM : 0, M % kMaxSkinnyM}) {
+    if (mc == 0) continue;
+    const Decomp d = choose_decomp(L, mc, 1, mc);
+    if (d.S > 1) need = std::max(need, (int64_t)d.S * mc * L.N * 4);
   }
+  return need;
+}
+
+// Workspace one dense call of exactly M rows needs (fp32 partial tiles of the K shares) on the kernel the library
+// picks for it.
+static int64_t dense_need(const Layout& L, int M) {
+  if (M <= 0) return 0;
+  switch (dense_path(L, M)) {
+    case kPathGemv:
+      return gemv_narrow_shares(L, M) > 0 ? 0 : skinny_need(L, M);
+    case kPathRows: {
+      const int S = rows_splits(L, M);
+      return S > 1 ? (int64_t)S * M * L.N * 4 : 0;
+    }
+    case kPathMid:
+    case kPathPrefill: {  // the 256-row kernel needs none; where it does not apply the 64-row kernel runs
+      const int S = mid_splits(L, M);
+      return S > 1 ? (int64_t)S * M * L.N * 4 : 0;
+    }
+    default:
+      return skinny_need(L, M);
+  }
+}
+
+// The largest need over 1..M_max rows.  Between two multiples of 16 the kernel choice and the number of K shares
+// do not change (they depend on the row count through its 16-, 32-, 64- and 256-row blocks and the thresholds 1,
+// 4, 16, 32, 128), and with both fixed the need grows with the row count: only those row counts are looked at.
+// K is cut only while the row and column blocks do not fill the chip, which bounds the row counts that matter.
+static int64_t dense_workspace_bytes(const Layout& L, int M_max) {
+  int64_t need = 0;
+  const int cap = std::min(M_max, 4096);
+  for (int m : {1, 2, 4}) if (m <= M_max) need = std::max(need, dense_need(L, m));
+  for (int m = 16; m <= cap; m += 16) need = std::max(need, dense_need(L, m));
+  need = std::max(need, dense_need(L, std::min(M_max, cap)));
+  if (M_max > cap) need = std::max(need, dense_need(L, M_max));
   return need;
 }
 
@@ -345,8 +376,28 @@ static int check_weight_ptrs(const ccq_weight* w, const Layout& L) {
   return CCQ_OK;
 }
 
-static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
-                     int64_t workspace_bytes, void* stream, const ccq_launch* launch) {
+namespace ccq {
+
+static bool is_explicit(const ccq_launch* l) { return l && (l->rows_per_wave_tiles || l->waves_rows || l->waves_k || l->splits_k); }
+
+// Decomposition of one pass of mc rows of the per-row-tile kernel.
+static int pass_decomp(const Layout& L, int mc, const ccq_launch* launch, Decomp* d) {
+  if (is_explicit(launch)) {
+    d->RT = launch->rows_per_wave_tiles ? launch->rows_per_wave_tiles : 1;
+    d->WR = launch->waves_rows ? launch->waves_rows : 1;
+    d->WK = launch->waves_k ? launch->waves_k : 1;
+    d->S = launch->splits_k ? launch->splits_k : 1;
+    if (!decomp_ok(L, *d)) return CCQ_ERR_BAD_PARAM;
+  } else {
+    *d = choose_decomp(L, mc, 1, mc);
+  }
+  return CCQ_OK;
+}
+
+// Everything is checked before the first launch: arguments, the decomposition of every pass and the workspace
+// each of them needs.  After that only a failing HIP launch (CCQ_ERR_HIP) can end a call part-way.
+int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
+                  int64_t workspace_bytes, void* stream, const ccq_launch* launch) {
   if (!w) return CCQ_ERR_NULL;
   Layout L;
   int rc = make_layout(w, &L);
@@ -358,8 +409,20 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
   if (rc != CCQ_OK) return rc;
   if (ldx < L.K || ldy < L.N) return CCQ_ERR_BAD_PARAM;
   if (!aligned16(x) || !aligned16(y) || !aligned16(workspace) || ldx % 8 != 0 || ldy % 8 != 0) return CCQ_ERR_ALIGN;
+  const int64_t have = workspace ? workspace_bytes : 0;
 
-  const bool explicit_launch = launch && (launch->rows_per_wave_tiles || launch->waves_rows || launch->waves_k || launch->splits_k);
+  const bool explicit_launch = is_explicit(launch);
+  // the passes of the per-row-tile kernel (the explicit path, and what the other paths fall back to)
+  int64_t need_passes = 0;
+  for (int mc : {M >= kMaxSkinnyM ? kMaxSkinnyM : 0, M % kMaxSkinnyM}) {
+    if (mc == 0) continue;
+    Decomp d;
+    rc = pass_decomp(L, mc, launch, &d);
+    if (rc != CCQ_OK) return rc;
+    if (d.S > 1) need_passes = std::max(need_passes, (int64_t)d.S * mc * L.N * 4);
+  }
+  if (!explicit_launch && have < dense_need(L, M)) return CCQ_ERR_WORKSPACE;
+
   if (!explicit_launch) {
     const DensePath path = dense_path(L, M);
     // many rows, narrow format only: the 256-row LDS-tiled MFMA kernel
@@ -369,12 +432,7 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
     }
     if (path == kPathRows) {
       const int S = rows_splits(L, M);
-      float* partial = nullptr;
-      if (S > 1) {
-        const int64_t need = (int64_t)S * M * L.N * 4;
-        if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
-        partial = static_cast<float*>(workspace);
-      }
+      float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
       rc = launch_rows(w, L, x, M, ldx, y, ldy, partial, S, stream);
       if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
       return rc;
@@ -382,43 +440,28 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
     // a few dozen rows (or many rows on wide / mixed formats): the 64-row LDS-tiled kernel
     if (path == kPathMid || path == kPathPrefill) {
       const int S = mid_splits(L, M);
-      float* partial = nullptr;
-      if (S > 1) {
-        const int64_t need = (int64_t)S * M * L.N * 4;
-        if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
-        partial = static_cast<float*>(workspace);
-      }
+      float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
       rc = launch_mid(w, L, x, M, ldx, y, ldy, partial, S, stream);
       if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
       if (rc != CCQ_ERR_UNSUPPORTED) return rc;
     }
-    // one row, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
+    // one to four rows, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
     if (path == kPathGemv) {
       rc = launch_gemv_narrow(w, L, x, M, ldx, y, ldy, stream);
       if (rc != CCQ_ERR_UNSUPPORTED) return rc;
     }
   }
 
-  // otherwise rows are processed in passes of at most kMaxSkinnyM
+  // otherwise rows are processed in passes of at most kMaxSkinnyM (nothing has been enqueued when control gets here)
+  if (have < need_passes) return CCQ_ERR_WORKSPACE;
   for (int m0 = 0; m0 < M; m0 += kMaxSkinnyM) {
     const int mc = std::min(kMaxSkinnyM, M - m0);
     SkinnyCall c;
     c.w = w;
     c.L = L;
-    if (launch && (launch->rows_per_wave_tiles || launch->waves_rows || launch->waves_k || launch->splits_k)) {
-      c.d.RT = launch->rows_per_wave_tiles ? launch->rows_per_wave_tiles : 1;
-      c.d.WR = launch->waves_rows ? launch->waves_rows : 1;
-      c.d.WK = launch->waves_k ? launch->waves_k : 1;
-      c.d.S = launch->splits_k ? launch->splits_k : 1;
-      if (!decomp_ok(L, c.d)) return CCQ_ERR_BAD_PARAM;
-    } else {
-      c.d = choose_decomp(L, mc, 1, mc);
-    }
-    if (c.d.S > 1) {
-      const int64_t need = (int64_t)c.d.S * mc * L.N * 4;
-      if (!workspace || workspace_bytes < need) return CCQ_ERR_WORKSPACE;
-      c.partial = static_cast<float*>(workspace);
-    }
+    rc = pass_decomp(L, mc, launch, &c.d);
+    if (rc != CCQ_OK) return rc;
+    if (c.d.S > 1) c.partial = static_cast<float*>(workspace);
     c.E = 1;
     c.x = static_cast<const uint16_t*>(x) + (int64_t)m0 * ldx;
     c.ldx = ldx;
@@ -433,14 +476,24 @@ static int gemm_impl(const ccq_weight* w, const void* x, int32_t M, int64_t ldx,
   return CCQ_OK;
 }
 
+int64_t gemm_workspace_need(const ccq_weight* w, int32_t M) {
+  Layout L;
+  if (!w || M < 0 || make_layout(w, &L) != CCQ_OK) return -1;
+  return dense_need(L, M);
+}
+
+}  // namespace ccq
+
+extern "C" int64_t ccq_gemm_workspace_bytes(const ccq_weight* w, int32_t M) { return ccq::gemm_workspace_need(w, M); }
+
 extern "C" int ccq_gemm(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
                         int64_t workspace_bytes, void* hip_stream) {
-  return gemm_impl(w, x, M, ldx, y, ldy, workspace, workspace_bytes, hip_stream, nullptr);
+  return gemm_dispatch(w, x, M, ldx, y, ldy, workspace, workspace_bytes, hip_stream, nullptr);
 }
 
 extern "C" int ccq_gemm_ex(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
                            int64_t workspace_bytes, void* hip_stream, const ccq_launch* launch) {
-  return gemm_impl(w, x, M, ldx, y, ldy, workspace, workspace_bytes, hip_stream, launch);
+  return gemm_dispatch(w, x, M, ldx, y, ldy, workspace, workspace_bytes, hip_stream, launch);
 }
 
 static int grouped_tile_rows(int E, int P) {

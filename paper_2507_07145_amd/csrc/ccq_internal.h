@@ -109,6 +109,7 @@ int launch_skinny(const SkinnyCall& c);
 // not split into equal shares of at most 12 k-tiles (4 with more than one row) over at most 8 wavefronts (the
 // caller then uses launch_skinny).
 constexpr int kGemvMaxM = 4;
+int gemv_narrow_shares(const Layout& L, int M);  // wavefronts along K per workgroup; 0 = not applicable
 int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 
 // Kernel for a few dozen to a few hundred rows, any format mix (ccq_mid.hip): 64-row tiles, K cut into S
@@ -128,6 +129,11 @@ int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, i
 int rows_splits(const Layout& L, int M);
 int launch_rows(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
                 void* stream);
+
+// The dispatcher behind ccq_gemm / ccq_gemm_ex (ccq_host.cpp) and the workspace a call of exactly M rows needs.
+int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, void* y, int64_t ldy, void* workspace,
+                  int64_t workspace_bytes, void* stream, const ccq_launch* launch);
+int64_t gemm_workspace_need(const ccq_weight* w, int32_t M);
 
 // Large-M kernel for narrow-format weights (ccq_prefill.hip).
 int prefill_block_cols(const Layout& L, int M);  // column-block width launch_prefill uses: 128, 192 or 256

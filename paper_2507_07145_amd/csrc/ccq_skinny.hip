@@ -1154,11 +1154,13 @@ __global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args a
   }
 }
 
-int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
-  // wavefronts per workgroup: a divisor of the k-tile count, at most 8.  Many short wavefronts (4 k-tiles
-  // each) hide the latency chain of a call this small best; when that would be more wavefronts than the
-  // chip holds at once (8 per SIMD), shares of 8 tiles are better.  With 2..4 rows a share is at most 4 tiles.
-  if (M < 1 || M > 4) return CCQ_ERR_UNSUPPORTED;
+// Wavefronts per workgroup of the GEMV kernels = shares of K: a divisor of the k-tile count, at most 8.  Many short
+// wavefronts (4 k-tiles each) hide the latency chain of a call this small best; when that would be more wavefronts
+// than the chip holds at once (8 per SIMD), shares of 8 tiles are better.  With 2..4 rows a share is at most 4 tiles.
+// 0: K does not split that way (the caller uses the general kernel).
+int gemv_narrow_shares(const Layout& L, int M) {
+  if (M < 1 || M > kGemvMaxM || L.tiles[kWide] != 0 || L.has_map) return 0;
+  if (L.row_tile_bytes >= ((int64_t)1 << 31) || L.row_tile_scale_halfs >= ((int64_t)1 << 31)) return 0;
   const int tiles = L.tiles[kNarrow];
   const int max_share = M == 1 ? kGemvMaxTiles : 4;
   const int target = (M > 1 || (int64_t)L.row_tiles * tiles / 4 <= 8192) ? 4 : 8;
@@ -1168,8 +1170,13 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
     const int dist = std::abs(tiles / c - target);
     if (dist < best) { best = dist; wk = c; }
   }
+  return wk;
+}
+
+int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
+  const int wk = gemv_narrow_shares(L, M);
   if (wk == 0) return CCQ_ERR_UNSUPPORTED;  // the caller falls back to the general kernel
-  if (L.row_tile_bytes >= ((int64_t)1 << 31) || L.row_tile_scale_halfs >= ((int64_t)1 << 31)) return CCQ_ERR_UNSUPPORTED;
+  const int tiles = L.tiles[kNarrow];
   GemvArgs a;
   a.codes = static_cast<const uint8_t*>(w->codes);
   a.scales = static_cast<const uint16_t*>(w->scales);

@@ -12,11 +12,14 @@ from paper_2507_07145_amd import synth
 # The error budget is the bf16 output rounding (2^-9 relative) plus fp32 accumulation noise;
 # the skinny path decodes weights exactly, the prefill path also rounds them to bf16.
 REL_TOL = 1e-2
-# The LDS-tiled kernels (more than 16 rows) multiply bf16-rounded weights (relative error <= 2^-9 each), so an element can be off by
-# 2^-9 * sum_k |x_k W_nk| whatever the size of the sum itself; with heavy-tailed group scales and a short K a
-# single large term can make that exceed 1e-2 * rms.  Tests of that kernel pass the absolute sum and allow
-# 2^-8 of it on top (weight rounding plus fp32 accumulation), a bound that follows from the arithmetic.
-ABS_SUM_TOL = 2.0 ** -8
+# The LDS-tiled kernels round every decoded weight to bf16 before the matrix core multiplies it: each product
+# x_k W_nk then carries an independent relative error of at most 2^-9 (uniform, standard deviation 2^-9 / sqrt(3)),
+# so an output element carries an error of standard deviation 2^-9 / sqrt(3) * sqrt(sum_k x_k^2 W_nk^2), whatever
+# the size of the sum itself.  With heavy-tailed group scales and a short K one large term can make that exceed
+# 1e-2 * rms.  Tests that name such a case pass `rounded=(x_bits, W)` and are then allowed, on top of the plain
+# bound, ROUNDED_WEIGHT_SIGMAS standard deviations of that error (a bound of the size the arithmetic produces;
+# the earlier 2^-8 * sum_k |x_k W_nk| was about sqrt(K) times looser).  The L2 criterion is never widened.
+ROUNDED_WEIGHT_SIGMAS = 7.0
 
 
 def canon_zero(bits: np.ndarray) -> np.ndarray:
@@ -25,20 +28,44 @@ def canon_zero(bits: np.ndarray) -> np.ndarray:
     return np.where((bits & 0x7FFF) == 0, np.uint16(0), bits)
 
 
-def assert_gemm_close(y_bits: np.ndarray, ref: np.ndarray, what: str = "", abs_sum: np.ndarray | None = None) -> dict:
+def rounded_weight_sigma(x_bits: np.ndarray, W: np.ndarray) -> np.ndarray:
+    """Standard deviation [M][N] of the error that rounding every weight to bf16 adds to x W^T."""
+    x = o.bf16_bits_to_f64(np.asarray(x_bits, dtype=np.uint16))
+    return 2.0 ** -9 / np.sqrt(3.0) * np.sqrt((x * x) @ (W * W).T)
+
+
+def grouped_rounded_weight_sigma(x_bits, sorted_rows, expert_offsets, W_of_expert) -> np.ndarray:
+    """The same for a grouped product: rows expert_offsets[e]..expert_offsets[e+1] use expert e's weights."""
+    parts = []
+    for e in range(len(expert_offsets) - 1):
+        lo, hi = int(expert_offsets[e]), int(expert_offsets[e + 1])
+        if hi > lo:
+            parts.append(rounded_weight_sigma(np.asarray(x_bits)[np.asarray(sorted_rows[lo:hi])], W_of_expert(e)))
+    return np.concatenate(parts, axis=0)
+
+
+def assert_gemm_close(y_bits: np.ndarray, ref: np.ndarray, what: str = "", rounded=None) -> dict:
+    """Plain bound, printed with the observed worst ratio err / tol; `rounded` = (x_bits, W) or a precomputed sigma array
+    widens the per-element bound as described above (the report then also says whether the plain bound held)."""
     y = o.bf16_bits_to_f64(y_bits)
     assert y.shape == ref.shape, (what, y.shape, ref.shape)
     assert np.all(np.isfinite(y)), what
     rms = float(np.sqrt(np.mean(ref ** 2))) if ref.size else 0.0
     err = np.abs(y - ref)
     tol = REL_TOL * np.maximum(np.abs(ref), rms)
-    if abs_sum is not None:
-        tol = tol + ABS_SUM_TOL * abs_sum
+    plain_ratio = float(np.max(err / np.maximum(tol, 1e-300))) if err.size else 0.0
+    note = ""
+    if rounded is not None:
+        sigma = rounded if isinstance(rounded, np.ndarray) else rounded_weight_sigma(*rounded)
+        tol = tol + ROUNDED_WEIGHT_SIGMAS * sigma
+        note = f", widened bound in use (plain bound {'held' if plain_ratio <= 1.0 else 'exceeded'}: worst err/tol {plain_ratio:.3f})"
+    ratio = float(np.max(err / np.maximum(tol, 1e-300))) if err.size else 0.0
+    print(f"[parity] {what}: worst err/tol {ratio:.3f}{note}")
     bad = np.argwhere(err > tol)
     assert bad.size == 0, f"{what}: {len(bad)} elements out of tolerance, first {bad[:5].tolist()}, max err {err.max():.4g}, rms {rms:.4g}"
     rel = float(np.linalg.norm(y - ref) / max(np.linalg.norm(ref), 1e-300))
     assert rel <= REL_TOL, f"{what}: relative L2 error {rel}"
-    return {"max_abs_err": float(err.max()) if err.size else 0.0, "rel_l2": rel}
+    return {"max_abs_err": float(err.max()) if err.size else 0.0, "rel_l2": rel, "worst_ratio": ratio, "plain_ratio": plain_ratio}
 
 
 class Case:

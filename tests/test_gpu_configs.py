@@ -34,8 +34,7 @@ def _check_sampled(case: Case, w, Ms, cfg, rows, decode_cols):
         x = synth.activations_bf16(M, case.K, synth.rng(cfg, 100 + M))
         got = _run(w, x)
         # beyond 16 rows the LDS-tiled kernels multiply bf16-rounded weights: the bound gains the term derived in cases.py
-        abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(Wr)) if M > 16 else None
-        assert_gemm_close(got[:, rows], o.matmul(x, Wr), f"config {cfg} M={M}", abs_sum=abs_sum)
+        assert_gemm_close(got[:, rows], o.matmul(x, Wr), f"config {cfg} M={M}", rounded=(x, Wr) if M > 16 else None)
     for i in range(0, len(decode_cols), 16):
         ks = [int(k) for k in decode_cols[i:i + 16]]
         got = _run(w, synth.one_hot_bf16(ks, case.K))
@@ -91,12 +90,24 @@ def test_config4_moe_grouped(proj, K, N):
     got = b.bf16_bits(y)
     sel = _sample_rows(N, 6, synth.rng(4, s0 + 5))
     ref = np.zeros((P, len(sel)))
+    Wsel = {}
     for e in range(E):
         lo, hi = int(offs[e]), int(offs[e + 1])
         if hi > lo:
-            We = o.decode(K, len(sel), o.F2, codes[e][sel], scales[e][sel], alpha[e][sel], beta[e][sel])
-            ref[lo:hi] = o.matmul(x[rows[lo:hi]], We)
+            Wsel[e] = o.decode(K, len(sel), o.F2, codes[e][sel], scales[e][sel], alpha[e][sel], beta[e][sel])
+            ref[lo:hi] = o.matmul(x[rows[lo:hi]], Wsel[e])
     assert_gemm_close(got[:, sel], ref, f"config 4 {proj}")
+    # decoded weights at full size, bit for bit: every token is a unit vector, so output row p of expert e is
+    # column ks[token of p] of that expert's decoded matrix
+    ks = synth.rng(4, s0 + 6).integers(0, K, T)
+    ks[:4] = [0, 63, K - 64, K - 1]
+    y1 = b.grouped_gemm(w, b.bf16_tensor(synth.one_hot_bf16(ks, K), DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), offs)
+    torch.cuda.synchronize()
+    got1 = b.bf16_bits(y1)
+    for e, We in Wsel.items():
+        lo, hi = int(offs[e]), int(offs[e + 1])
+        want = o.to_bf16_bits(We[:, ks[rows[lo:hi]]].T)
+        assert np.array_equal(canon_zero(got1[lo:hi][:, sel]), canon_zero(want)), f"config 4 {proj}: decoded weights of expert {e}"
 
 
 def test_config5_prefill():

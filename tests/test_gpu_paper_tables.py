@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from cases import assert_gemm_close
+from cases import assert_gemm_close, grouped_rounded_weight_sigma
 from oracle import ccq_oracle as o
 from paper_2507_07145_amd import binding as b
 from paper_2507_07145_amd import synth
@@ -81,5 +81,5 @@ def test_grouped_compressed_scales_wide_and_mixed():
             torch.cuda.synchronize()
             Wd = [o.decode_cs(K, N, ofmt, codes[e], sq[e], ssup[e], alpha[e], beta[e], gf) for e in range(E)]
             ref = o.grouped_matmul(x, rows, offs, lambda e: Wd[e])
-            abs_sum = o.grouped_matmul(x & np.uint16(0x7FFF), rows, offs, lambda e: np.abs(Wd[e])) if Tt > T else None
-            assert_gemm_close(b.bf16_bits(y), ref, f"grouped, compressed scales, {kinds}, {Tt} tokens", abs_sum=abs_sum)
+            sigma = grouped_rounded_weight_sigma(x, rows, offs, lambda e: Wd[e]) if Tt > T else None
+            assert_gemm_close(b.bf16_bits(y), ref, f"grouped, compressed scales, {kinds}, {Tt} tokens", rounded=sigma)

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from cases import Case, assert_gemm_close, canon_zero, encoded_case, random_case
+from cases import Case, assert_gemm_close, canon_zero, encoded_case, random_case, grouped_rounded_weight_sigma
 from oracle import ccq_oracle as o
 from paper_2507_07145_amd import binding as b
 from paper_2507_07145_amd import synth
@@ -86,8 +86,7 @@ def test_large_m_kernel_small_shapes(K, N, M):
     c = random_case(K, N, ["narrow"], 1, stream0=900 + N)
     w = c.device_weight(DEV)
     x = synth.activations_bf16(M, K, synth.rng(1, 950 + M))
-    abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(c.W()))
-    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"large-M K={K} N={N} M={M}", abs_sum=abs_sum)
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"large-M K={K} N={N} M={M}", rounded=(x, c.W()))
     ks = synth.rng(1, 960 + M).integers(0, K, M)
     got = _gemm_bits(w, synth.one_hot_bf16(ks, K))
     want = o.to_bf16_bits(c.W()[:, ks].T)
@@ -142,8 +141,7 @@ def test_mid_kernel_formats(kinds, K, N, M, n_wide):
     c = random_case(K, N, kinds, 9, stream0=20 * len(kinds) + N % 11, n_wide=n_wide)
     w = c.device_weight(DEV)
     x = synth.activations_bf16(M, K, synth.rng(9, 300 + M))
-    abs_sum = o.matmul(x & np.uint16(0x7FFF), np.abs(c.W()))
-    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"mid {kinds} K={K} N={N} M={M}", abs_sum=abs_sum)
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, c.W()), f"mid {kinds} K={K} N={N} M={M}", rounded=(x, c.W()))
     ks = synth.rng(9, 310 + M).integers(0, K, M)
     ks[:4] = [0, 63, K - 64, K - 1]
     got = _gemm_bits(w, synth.one_hot_bf16(ks, K))
@@ -276,12 +274,12 @@ def test_grouped_many_rows_per_expert(kinds, K, N, n_wide):
     P = int(offs[-1])
     rows = synth.rng(13, 98).integers(0, T, size=P).astype(np.int32)
     ref = _grouped_reference(cases, x, rows, offs)
-    abs_sum = o.grouped_matmul(x & np.uint16(0x7FFF), rows, offs, lambda e: np.abs(cases[e].W()))
+    sigma = grouped_rounded_weight_sigma(x, rows, offs, lambda e: cases[e].W())
     for host_offsets in (offs, None):
         y = torch.full((P + 1, N), 3.0, dtype=torch.bfloat16, device=DEV)
         b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), host_offsets, out=y[:P])
         torch.cuda.synchronize()
-        assert_gemm_close(b.bf16_bits(y[:P]), ref, f"grouped, many rows, host offsets {'given' if host_offsets is not None else 'absent'}", abs_sum=abs_sum)
+        assert_gemm_close(b.bf16_bits(y[:P]), ref, f"grouped, many rows, host offsets {'given' if host_offsets is not None else 'absent'}", rounded=sigma)
         assert bool((y[P] == 3.0).all())
     # decoded weights, bit exact, through the 64-row kernel: 40 one-hot tokens per expert
     ks = synth.rng(13, 97).integers(0, K, 40)
