@@ -151,6 +151,17 @@ int ccq_gemm(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void *y
  * -1 for an invalid descriptor.  Pure host code. */
 int64_t ccq_gemm_workspace_bytes(const ccq_weight *w, int32_t M);
 
+/* ccq_gemm for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as ccq_gemm (bit for
+ * bit), without the workspace: the fp32 partial tiles of the K shares live in a device array that belongs to the
+ * library (ccq_gemm_static_max_workspace() bytes, 8 MiB, held on every GPU the library has run on until the
+ * process ends).  A call that would need more (ccq_gemm_workspace_bytes(w, M) tells) returns CCQ_ERR_WORKSPACE and
+ * enqueues nothing.  No hipMalloc, hipFree or other allocating call is made.  All calls on one GPU share the
+ * array: calls that may overlap on one GPU (different streams, concurrent graph launches) race on it and
+ * must be ordered by the caller; calls on one stream are ordered by the stream. */
+int ccq_gemm_static(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void *y, int64_t ldy, void *hip_stream);
+int64_t ccq_gemm_static_max_workspace(void);
+
 /* Explicit launch shape for ccq_gemm_ex (0 = let the library choose).  */
 typedef struct {
   int32_t rows_per_wave_tiles; /* 16-row tiles each wavefront owns: 1 or 2      */

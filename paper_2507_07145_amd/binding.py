@@ -61,7 +61,8 @@ H16 = [H16_HI, H16_LO]
 
 EXPORTS = ["ccq_pack_info", "ccq_pack_codes", "ccq_pack_scales", "ccq_pack_scales4", "ccq_pack_meta", "ccq_gemm", "ccq_gemm_ex",
            "ccq_grouped_gemm", "ccq_grouped_workspace_bytes", "ccq_quantize", "ccq_quantize_workspace_bytes", "ccq_status_string",
-           "ccq_probe_stream_read", "ccq_probe_mfma_bf16", "ccq_gemm_workspace_bytes"]
+           "ccq_probe_stream_read", "ccq_probe_mfma_bf16", "ccq_gemm_workspace_bytes",
+           "ccq_gemm_static", "ccq_gemm_static_max_workspace"]
 
 _lib = None
 
@@ -93,6 +94,10 @@ def load() -> ctypes.CDLL:
     L.ccq_grouped_gemm.argtypes = [wp, i32, i64, i64, i64, vp, i32, i64, vp, i32, vp, vp, vp, i64, vp, i64, vp]
     L.ccq_gemm_workspace_bytes.restype = i64
     L.ccq_gemm_workspace_bytes.argtypes = [wp, i32]
+    L.ccq_gemm_static.restype = ctypes.c_int
+    L.ccq_gemm_static.argtypes = [wp, vp, i32, i64, vp, i64, vp]
+    L.ccq_gemm_static_max_workspace.restype = i64
+    L.ccq_gemm_static_max_workspace.argtypes = []
     L.ccq_grouped_workspace_bytes.restype = i64
     L.ccq_grouped_workspace_bytes.argtypes = [wp, i32, i32]
     L.ccq_quantize_workspace_bytes.restype = i64
@@ -346,6 +351,15 @@ def gemm(w: Weight, x: torch.Tensor, out: torch.Tensor | None = None, workspace:
                            _stream_ptr(stream), ctypes.byref(launch))
     _check(rc, "ccq_gemm")
     return y
+
+
+def gemm_static(w: Weight, x: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """y = x W_dq^T through ccq_gemm_static: no workspace, nothing allocated (the caller passes `out`)."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1 and x.is_cuda
+    assert out.dtype == torch.bfloat16 and out.shape == (x.shape[0], w.N) and out.stride(1) == 1
+    _check(load().ccq_gemm_static(ctypes.byref(w.desc), _t_ptr(x), x.shape[0], x.stride(0), _t_ptr(out), out.stride(0), _stream_ptr(stream)),
+           "ccq_gemm_static")
+    return out
 
 
 def gemm_workspace_bytes(desc: ccq_weight, M: int) -> int:
