@@ -1,0 +1,567 @@
+// Dense GEMV on narrow-format weights -- the decode step of generation (one activation row, Alg. 3 fused into the
+// contraction; the GEMV operator of the "Inference Performance" section).
+//
+// A call of this size (19 MB for 8192 x 8192) lasts a few microseconds and is bound by instruction issue, not by
+// HBM: what counts is the number of instructions per weight and how early every wavefront has all of its requests
+// in flight.  Shape of the kernel:
+//   * a workgroup owns one row tile (16 output rows; RT = 1 is what is built) and all of K; its W wavefronts cut K into W shares of TPW
+//     k-tiles (4 groups of 64 weights each), so the K reduction stays inside the workgroup (LDS, fixed order);
+//   * a wavefront requests its slice of x, its TPW code tiles (one 16-byte nontemporal load per lane and tile:
+//     the device order of the code stream is the operand order of the matrix core) and their scales before it does
+//     anything else; nothing is requested later and no request sits under a condition;
+//   * x is staged once per wavefront in a private LDS region, already permuted into matrix-core operand fragments
+//     (no workgroup barrier before the contraction);
+//   * decode: the clustered byte q becomes the 15-bit code round(q alpha + beta) with one fused multiply-add against
+//     beta + 2^23 (the sum lies in [2^23, 2^24), where fp32 spacing is 1, so the hardware's round-to-nearest-even is
+//     the rounding of Eq. 1 and the code sits in the low mantissa bits); two codes are put side by side in one register
+//     and each of the four windows of Table 1 (shifts 9, 6, 3, 0, mask 0x3F) is cut out of both with one shift and one
+//     and-or into the mantissa of bf16 128.0: the operand is the bf16 integer 128 + state, exactly;
+//   * contraction: MFMA 4x4x4 bf16 (lane l feeds its own 4 weights as one column of its 4x4 block, the activations are
+//     the same fragment for the whole block); the accumulator of a (group, quarter) starts at -(128 + zp) sum x, so the
+//     group's result is sum (state - zp) x, which is multiplied by the group scale afterwards: the linear map
+//     (w_uint - zp) * s of Alg. 3 applied after the contraction.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstdint>
+#include <cstdlib>
+
+#include "ccq_internal.h"
+
+namespace ccq {
+namespace gemv {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+struct Args {          // 64 bytes: one scalar load
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const uint16_t* x;
+  uint16_t* y;
+  const uint16_t* scale_super;   // fp16 [N], compressed scales only
+  int32_t tiles;                 // k-tiles per row tile
+  float cneg;                    // -(128 + zp)
+};
+
+__device__ __forceinline__ uint16_t to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Sum of the eight bf16 values of a fragment in fp32.  (The elements are taken by value first: a bit cast applied
+// to an element of an ext-vector lvalue reads element 0.)
+__device__ __forceinline__ float frag_sum(const u32x4 o) {
+  const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3F803F80u);
+  const uint32_t o0 = o.x, o1 = o.y, o2 = o.z, o3 = o.w;
+  float s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, o0), ones, 0.f, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, o1), ones, s, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, o2), ones, s, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, o3), ones, s, false);
+  return s;
+}
+
+// Plain C on purpose (no inline assembly: the compiler's hazard recognizer must see the instruction); mask and orv
+// are kept in registers by the caller so that a single v_and_or_b32 is selected.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) { return (a & mask) | orv; }
+
+// The 16 weights of one lane for one group: dword d holds the clustered bytes of codes 4kq .. 4kq+3 of the group.
+// Returns, per k-step t (codes 2t, 2t+1), the four registers {state i of code 2t | state i of code 2t+1 << 16} + 128.
+__device__ __forceinline__ void decode_dword(uint32_t d, float al, float be_magic, uint32_t c4300, uint32_t mask, u32x4 (&w)[2]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const float fa = __builtin_fmaf((float)((d >> (16 * t)) & 0xFFu), al, be_magic);       // Alg. 3: round(q s_code + zp_code)
+    const float fb = __builtin_fmaf((float)((d >> (16 * t + 8)) & 0xFFu), al, be_magic);
+    const uint32_t yy = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, fb), __builtin_bit_cast(uint32_t, fa), 0x05040100u);
+    w[t].x = and_or(yy >> 9, mask, c4300);   // Table 1: shifts [9, 6, 3, 0], mask 0x3F, both codes at once
+    w[t].y = and_or(yy >> 6, mask, c4300);
+    w[t].z = and_or(yy >> 3, mask, c4300);
+    w[t].w = and_or(yy, mask, c4300);
+  }
+}
+
+template <int RT, int TPW, int SM>
+__global__ void __launch_bounds__(1024) kernel(const Args a) {
+  constexpr int NG = TPW * 4;                         // groups per wavefront
+  constexpr int NF = (NG * 8 + 63) / 64;              // x fragments per lane while staging
+  constexpr int SH = SM == 0 ? 64 : 16;               // scale halfwords per k-tile and row tile
+  constexpr int REGION = NG * 8 * 16 + NG * 4 * 16;   // private LDS bytes per wavefront: fragments, then start-value records
+  extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t nwaves = blockDim.x >> 6;
+  const uint32_t n = lane & 15u, kq = lane >> 4;
+  const uint32_t t0 = wave * TPW;                     // first k-tile of this wavefront
+  const uint32_t rtile0 = blockIdx.x * RT;
+  // ---- every request, before anything else ------------------------------------------------------------------
+  // x: fragment f = (group * 2 + k-step) * 4 + quarter covers elements 64 group + 16 quarter + 8 k-step .. + 7
+  u32x4 xv[NF];
+  const uint16_t* xs = a.x + (size_t)t0 * 256u;
+#pragma unroll
+  for (int i = 0; i < NF; ++i) {
+    uint32_t f = lane + 64u * i;
+    if (NG * 8 % 64 != 0) f = min(f, (uint32_t)(NG * 8 - 1));
+    const uint32_t off = ((f >> 3) << 6) | ((f & 3u) << 4) | ((f & 4u) << 1);
+    xv[i] = *reinterpret_cast<const u32x4*>(xs + off);
+  }
+  // per-row parameters next (they are waited for before the first tile: in-order return makes anything requested
+  // after the tiles wait for all of them), then the tiles in the order they are consumed
+  float al[RT], be_raw[RT];
+  uint32_t ssup[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    al[rt] = a.alpha[(rtile0 + rt) * 16u + n];
+    be_raw[rt] = a.beta[(rtile0 + rt) * 16u + n];
+    if constexpr (SM == 1) ssup[rt] = a.scale_super[(rtile0 + rt) * 16u + n];
+  }
+  u32x4 cw[RT][TPW];
+  uint32_t sw[RT][TPW][SM == 0 ? 2 : 1];
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const uint16_t* sb = a.scales + ((size_t)(rtile0 + rt) * (uint32_t)a.tiles + t0) * SH;
+      if constexpr (SM == 0) {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+        sw[rt][i][0] = v.x;
+        sw[rt][i][1] = v.y;
+      } else {
+        sw[rt][i][0] = sb[i * 16u + n];   // the tile's four 4-bit fields of this row (first line of Alg. 3)
+      }
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);   // keep the (small) scale requests ahead of the code tiles: returns are in order
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const uint8_t* cb = a.codes + ((size_t)(rtile0 + rt) * (uint32_t)a.tiles + t0) * 1024u;
+      cw[rt][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + i * 1024u + lane * 16u));
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- stage x: permuted fragments and the accumulator start values -(128 + zp) sum x per (group, quarter) ------
+  unsigned char* region = smem + (size_t)wave * REGION;
+  u32x4* lds_x = reinterpret_cast<u32x4*>(region);
+  float* lds_c = reinterpret_cast<float*>(region + NG * 8 * 16);
+#pragma unroll
+  for (int i = 0; i < NF; ++i) {
+    const uint32_t f = lane + 64u * i;
+    // the two codes of a k-step cover weights +0..3 and +4..7; their states share registers pairwise, so the
+    // k-slots interleave them: {0,4,1,5,2,6,3,7}
+    u32x4 o;
+    o.x = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x05040100u);
+    o.y = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x07060302u);
+    o.z = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x05040100u);
+    o.w = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x07060302u);
+    float s = frag_sum(o);
+    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x104, 0xF, 0xF, true));  // + the other k-step, 4 lanes up
+    if (NG * 8 % 64 == 0 || f < (uint32_t)(NG * 8)) {
+      lds_x[f] = o;
+      if ((f & 4u) == 0) lds_c[((f >> 3) * 4u + (f & 3u)) * 4u] = a.cneg * s;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  uint32_t c4300 = 0x43004300u, mask = 0x003F003Fu;
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(c4300), "+s"(mask), "+v"(magic));   // register values, not literals: v_and_or_b32 gets selected
+  float be[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) be[rt] = be_raw[rt] + magic;   // + 2^23: exact, beta is an integer below 2^15
+
+  // ---- contraction ------------------------------------------------------------------------------------------------
+  float acc[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) acc[rt] = 0.f;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int lg = i * 4 + j;
+      const u32x4 x0 = lds_x[(lg * 2 + 0) * 4 + kq];
+      const u32x4 x1 = lds_x[(lg * 2 + 1) * 4 + kq];
+      const f32x4 cin = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        u32x4 w[2];
+        const uint32_t d = j == 0 ? cw[rt][i].x : (j == 1 ? cw[rt][i].y : (j == 2 ? cw[rt][i].z : cw[rt][i].w));
+        decode_dword(d, al[rt], be[rt], c4300, mask, w);
+        f32x4 p = cin;
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.x, x0.y}), __builtin_bit_cast(bf16x4, u32x2{w[0].x, w[0].y}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.z, x0.w}), __builtin_bit_cast(bf16x4, u32x2{w[0].z, w[0].w}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.x, x1.y}), __builtin_bit_cast(bf16x4, u32x2{w[1].x, w[1].y}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.z, x1.w}), __builtin_bit_cast(bf16x4, u32x2{w[1].z, w[1].w}), p, 0, 0, 0);
+        float s;
+        if constexpr (SM == 0) {
+          const uint32_t sd = sw[rt][i][j >> 1];
+          s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else {
+          s = (float)((sw[rt][i][0] >> (4 * j)) & 0xFu);   // the field alone; the row's super scale multiplies the sum once
+        }
+        acc[rt] = __builtin_fmaf(s, p[0], acc[rt]);
+      }
+    }
+  }
+  // ---- the four quarters of a row, then the wavefronts of the workgroup (fixed order) ------------------------------
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    acc[rt] += __shfl_xor(acc[rt], 16);
+    acc[rt] += __shfl_xor(acc[rt], 32);
+  }
+  if (nwaves > 1) {
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);
+    if (wave > 0 && lane < 16u) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) red[((wave - 1) * RT + rt) * 16u + lane] = acc[rt];
+    }
+    __syncthreads();
+    if (wave == 0 && lane < 16u) {
+      for (uint32_t k = 1; k < nwaves; ++k) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) acc[rt] += red[((k - 1) * RT + rt) * 16u + lane];
+      }
+    }
+  }
+  if (wave == 0 && lane < 16u) {
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      float v = acc[rt];
+      if constexpr (SM == 1) v *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup[rt]);
+      a.y[(rtile0 + rt) * 16u + lane] = to_bf16_rne(v);
+    }
+  }
+}
+
+// ---- two to sixteen activation rows --------------------------------------------------------------------------------
+// Same decode, MFMA 16x16x32 bf16 in place of 4x4x4: lane l owns output row n = l % 16 of its row tile and quarter
+// kq = l / 16 of every group (the B operand), the activations are the A operand (row m = l % 16, k-slots of quarter
+// kq), and the lane receives rows m = 4 kq .. 4 kq + 3 of column n.  The activation fragments of 16 rows are sixteen
+// times those of one row, so they are staged once per workgroup and shared by its NW wavefronts = NW row tiles; K is
+// cut into shares of TPW k-tiles across workgroups (gridDim.y), whose fp32 partial tiles are added in index
+// order by a second, small kernel (a share that covers all of K writes bf16 results directly).  Letting the share that
+// arrives last at a row block add the tiles inside this kernel was measured and is slower on this chip: the shares run
+// on different XCDs, whose L2 caches are not coherent with each other, so the partial tiles, the arrival counter and the
+// final reads each make a round trip to memory (three dependent ones, 6-8 us at 8192 x 8192 against 3.9 us for the
+// second launch).  One workgroup barrier in the whole kernel.
+struct Args16 {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const uint16_t* x;
+  uint16_t* y;
+  const uint16_t* scale_super;
+  float* partial;                // fp32 [shares][M][N] when K is cut
+  int64_t ldx, ldy;
+  int32_t tiles, row_tiles, M, N;
+  float cneg;
+};
+
+template <int TPW, int SM, int NW>
+__global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
+  constexpr int NG = TPW * 4;                  // groups per share
+  constexpr int NU = NG * 4 * 16;              // staging units: (group, row, quarter) = 16 consecutive activations
+  constexpr int SH = SM == 0 ? 64 : 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  u32x4* lds_x = reinterpret_cast<u32x4*>(smem);                       // [group][k-step][quarter][row]
+  float* lds_c = reinterpret_cast<float*>(smem + (size_t)NG * 8 * 16 * 16);  // [group][row]
+  constexpr uint32_t nthreads = 64u * NW;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t n = lane & 15u, kq = lane >> 4;
+  const uint32_t t0 = blockIdx.y * TPW;
+  const uint32_t rtile_raw = blockIdx.x * NW + wave;
+  const bool active = rtile_raw < (uint32_t)a.row_tiles;
+  const uint32_t rtile = active ? rtile_raw : (uint32_t)a.row_tiles - 1u;   // a ragged last block re-reads the last tile; nothing of it is stored
+
+  // ---- every request, before anything else --------------------------------------------------------------------
+  // unit u = (group * 16 + row) * 4 + quarter: the quarters of a (group, row) sit in neighbouring lanes
+  constexpr int NUT = (NU + (int)nthreads - 1) / (int)nthreads;   // units per thread
+  u32x4 xv[NUT][2];
+#pragma unroll
+  for (int i = 0; i < NUT; ++i) {
+    uint32_t u = tid + (uint32_t)i * nthreads;
+    if (NU % nthreads != 0) u = min(u, (uint32_t)NU - 1u);             // clamped: the request is unconditional
+    const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
+    const uint32_t row = min(m, (uint32_t)a.M - 1u);                    // rows past M repeat the last one; never stored
+    const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + ((size_t)t0 * 256u + lg * 64u + q * 16u);
+    xv[i][0] = *reinterpret_cast<const u32x4*>(p);
+    xv[i][1] = *reinterpret_cast<const u32x4*>(p + 8);
+  }
+  const float al = a.alpha[rtile * 16u + n];
+  const float be_raw = a.beta[rtile * 16u + n];
+  uint32_t ssup = 0;
+  if constexpr (SM == 1) ssup = a.scale_super[rtile * 16u + n];
+  u32x4 cw[TPW];
+  uint32_t sw[TPW][SM == 0 ? 2 : 1];
+  const uint16_t* sb = a.scales + ((size_t)rtile * (uint32_t)a.tiles + t0) * SH;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    if constexpr (SM == 0) {
+      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+      sw[i][0] = v.x;
+      sw[i][1] = v.y;
+    } else {
+      sw[i][0] = sb[i * 16u + n];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  const uint8_t* cb = a.codes + ((size_t)rtile * (uint32_t)a.tiles + t0) * 1024u;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + i * 1024u + lane * 16u));
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- stage the activations: fragments in k-slot order {0,4,1,5,2,6,3,7} and the start values ----------------------
+#pragma unroll
+  for (int i = 0; i < NUT; ++i) {
+    const uint32_t u = tid + (uint32_t)i * nthreads;
+    float s = 0.f;
+    u32x4 o[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      o[t].x = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x05040100u);
+      o[t].y = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x07060302u);
+      o[t].z = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x05040100u);
+      o[t].w = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x07060302u);
+      s += frag_sum(o[t]);
+    }
+    // the four quarters of a (group, row): neighbouring lanes
+    s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    if (NU % nthreads == 0 || u < (uint32_t)NU) {
+      const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
+      lds_x[((lg * 2u + 0u) * 4u + q) * 16u + m] = o[0];
+      lds_x[((lg * 2u + 1u) * 4u + q) * 16u + m] = o[1];
+      if (q == 0) lds_c[lg * 16u + m] = a.cneg * s;
+    }
+  }
+  __syncthreads();
+
+  uint32_t c4300 = 0x43004300u, mask = 0x003F003Fu;
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(c4300), "+s"(mask), "+v"(magic));
+  const float be = be_raw + magic;   // + 2^23: exact, beta is an integer below 2^15
+
+  // ---- contraction ------------------------------------------------------------------------------------------------
+  typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int lg = i * 4 + j;
+      const u32x4 x0 = lds_x[((lg * 2 + 0) * 4 + kq) * 16 + n];        // here n is the activation row of this lane's A fragment
+      const u32x4 x1 = lds_x[((lg * 2 + 1) * 4 + kq) * 16 + n];
+      f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + lg * 16 + 4 * kq);
+      u32x4 w[2];
+      const uint32_t d = j == 0 ? cw[i].x : (j == 1 ? cw[i].y : (j == 2 ? cw[i].z : cw[i].w));
+      decode_dword(d, al, be, c4300, mask, w);
+      p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0), __builtin_bit_cast(bf16x8, w[0]), p, 0, 0, 0);
+      p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1), __builtin_bit_cast(bf16x8, w[1]), p, 0, 0, 0);
+      float sc;
+      if constexpr (SM == 0) {
+        const uint32_t sd = sw[i][j >> 1];
+        sc = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+      } else {
+        sc = (float)((sw[i][0] >> (4 * j)) & 0xFu);
+      }
+      acc[0] = __builtin_fmaf(sc, p[0], acc[0]);
+      acc[1] = __builtin_fmaf(sc, p[1], acc[1]);
+      acc[2] = __builtin_fmaf(sc, p[2], acc[2]);
+      acc[3] = __builtin_fmaf(sc, p[3], acc[3]);
+    }
+  }
+  if constexpr (SM == 1) acc *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
+
+  // ---- store: lane (n, kq) holds rows 4 kq .. 4 kq + 3 of column n -------------------------------------------------------
+  if (active) {
+    const uint32_t col = rtile * 16u + n;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t m = 4u * kq + r;
+      if (m < (uint32_t)a.M) {
+        if (gridDim.y > 1) a.partial[((size_t)blockIdx.y * (uint32_t)a.M + m) * (uint32_t)a.N + col] = acc[r];
+        else a.y[(size_t)m * (size_t)a.ldy + col] = to_bf16_rne(acc[r]);
+      }
+    }
+  }
+}
+
+typedef void (*Kernel)(const Args);
+
+template <int SM>
+static Kernel pick_tpw(int tpw) {
+  switch (tpw) {
+    case 1: return kernel<1, 1, SM>;
+    case 2: return kernel<1, 2, SM>;
+    case 3: return kernel<1, 3, SM>;
+    case 4: return kernel<1, 4, SM>;
+    case 6: return kernel<1, 6, SM>;
+    case 7: return kernel<1, 7, SM>;
+    case 8: return kernel<1, 8, SM>;
+    default: return nullptr;
+  }
+}
+
+}  // namespace gemv
+
+// Shape of a GEMV launch: one row tile per workgroup, W <= 16 wavefronts of TPW k-tiles each (W * TPW = k-tiles of a
+// row).  Measured on 1024^2 ... 8192 x 28672: shares of two k-tiles are best as long as the chip can hold all
+// wavefronts at once (eight per SIMD = 32 per CU: more wavefronts hide more of the issue latency of a stream that is
+// bound by instruction issue); beyond that, longer shares (less set-up per weight) win, and when even shares of two
+// leave most of the chip empty, shares of one k-tile do.  Two row tiles per wavefront (shared activation fragments)
+// measured slower in every shape and are not built.  false: K does not split that way.
+bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out) {
+  if (L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return false;
+  const int tiles = L.tiles[kNarrow];
+  const int64_t waves2 = (int64_t)L.row_tiles * ((tiles + 1) / 2);   // wavefronts with shares of two k-tiles
+  int want = 2;
+  if (waves2 > (int64_t)32 * cus) want = 4;
+  else if (2 * waves2 < (int64_t)3 * cus) want = 1;
+  static const int kBuilt[] = {1, 2, 3, 4, 6, 7, 8};
+  int best = 0, best_dist = 1 << 30;
+  for (int tpw : kBuilt) {
+    if (tiles % tpw != 0 || tiles / tpw > 16) continue;
+    const int dist = std::abs(tpw - want) * 2 + (tpw < want ? 1 : 0);   // nearest; of two equally near the longer share
+    if (dist < best_dist) { best_dist = dist; best = tpw; }
+  }
+  if (best == 0) return false;
+  *tpw_out = best;
+  *w_out = tiles / best;
+  return true;
+}
+
+int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves) {
+  using namespace gemv;
+  if (tpw < 1 || waves < 1 || waves > 16 || waves * tpw != L.tiles[kNarrow] || L.tiles[kWide] != 0 || L.has_map) return CCQ_ERR_UNSUPPORTED;
+  if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  Args a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
+  a.tiles = L.tiles[kNarrow];
+  a.cneg = -(128.f + L.zp[kNarrow]);
+  const Kernel k = L.scale_mode == 0 ? pick_tpw<0>(tpw) : pick_tpw<1>(tpw);
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)waves * (tpw * 4) * (8 * 16 + 4 * 16);   // at most 16 * 32 * 192 bytes = 96 KiB
+  if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * waves)), lds, static_cast<hipStream_t>(stream), a);
+  return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
+}
+
+// Shares of K for the 2..16-row kernel: shares of four k-tiles (the least partial-tile traffic) unless that leaves
+// compute units without a workgroup, then shorter ones -- but never more shares than `max_shares` (what the caller's
+// workspace holds).  false: K does not split into at most min(max_shares, kMaxSplitsK) shares of 1, 2 or 4 k-tiles.
+bool gemv16_shape(const Layout& L, int cus, int64_t max_shares, int* tpw_out, int* nw_out) {
+  if (L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return false;
+  const int tiles = L.tiles[kNarrow], nw = 8;
+  const int64_t row_blocks = (L.row_tiles + nw - 1) / nw;
+  const int64_t cap = std::min<int64_t>(max_shares, kMaxSplitsK);
+  int pick = 0;
+  for (int tpw : {4, 2, 1}) {
+    if (tiles % tpw != 0 || tiles / tpw > cap) continue;
+    pick = tpw;                                   // the shortest share that qualifies, unless a longer one fills the chip
+    if (row_blocks * (tiles / tpw) >= cus) break;
+  }
+  if (pick == 0) return false;
+  *tpw_out = pick;
+  *nw_out = nw;
+  return true;
+}
+
+// Two to sixteen rows, narrow format, dense.  nw = 8 or 16 wavefronts (row tiles) per workgroup share one staged slice of the
+// activations; S = tiles / tpw <= 32 shares of K across workgroups (S > 1 needs `partial`, fp32 [S][M][N], and a pass of
+// launch_reduce_splits afterwards).
+int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int tpw,
+                  int nw, void* stream) {
+  using namespace gemv;
+  if (M < 1 || M > 16 || L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return CCQ_ERR_UNSUPPORTED;
+  if (tpw < 1 || L.tiles[kNarrow] % tpw != 0 || nw < 1 || nw > 16) return CCQ_ERR_UNSUPPORTED;
+  const int S = L.tiles[kNarrow] / tpw;
+  if (S > kMaxSplitsK || (S > 1 && !partial)) return CCQ_ERR_UNSUPPORTED;
+  if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  Args16 a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
+  a.partial = partial;
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.tiles = L.tiles[kNarrow];
+  a.row_tiles = L.row_tiles;
+  a.M = M;
+  a.N = L.N;
+  a.cneg = -(128.f + L.zp[kNarrow]);
+  typedef void (*Kernel16)(const Args16);
+  Kernel16 k = nullptr;
+  const int key = tpw * 100 + nw;
+  if (L.scale_mode == 0) {
+    switch (key) {
+      case 108: k = kernel16<1, 0, 8>; break;
+      case 116: k = kernel16<1, 0, 16>; break;
+      case 208: k = kernel16<2, 0, 8>; break;
+      case 216: k = kernel16<2, 0, 16>; break;
+      case 408: k = kernel16<4, 0, 8>; break;
+      case 416: k = kernel16<4, 0, 16>; break;
+    }
+  } else {
+    switch (key) {
+      case 108: k = kernel16<1, 1, 8>; break;
+      case 116: k = kernel16<1, 1, 16>; break;
+      case 208: k = kernel16<2, 1, 8>; break;
+      case 216: k = kernel16<2, 1, 16>; break;
+      case 408: k = kernel16<4, 1, 8>; break;
+      case 416: k = kernel16<4, 1, 16>; break;
+    }
+  }
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)(tpw * 4) * (8 * 16 * 16 + 16 * 4);
+  if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  const dim3 grid((unsigned)((L.row_tiles + nw - 1) / nw), (unsigned)S);
+  hipLaunchKernelGGL(k, grid, dim3((unsigned)(64 * nw)), lds, static_cast<hipStream_t>(stream), a);
+  return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
+}
+
+// Compute units of the current device, looked up once per device.
+int device_cus() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  int c = cached[dev].load(std::memory_order_relaxed);
+  if (c <= 0) {
+    if (hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || c <= 0) {
+      (void)hipGetLastError();
+      c = 256;
+    }
+    cached[dev].store(c, std::memory_order_relaxed);
+  }
+  return c;
+}
+
+}  // namespace ccq

@@ -136,10 +136,16 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
 using namespace ccq;
 
 // Which kernel a dense call of M rows uses when no launch shape is given.
-enum DensePath { kPathGemv, kPathSkinny, kPathRows, kPathMid, kPathPrefill };
+enum DensePath { kPathGemv, kPathGemv16, kPathSkinny, kPathRows, kPathMid, kPathPrefill };
 static DensePath dense_path(const Layout& L, int M) {
   const bool narrow_only = L.tiles[kWide] == 0, wide_only = L.tiles[kNarrow] == 0;
-  if (M <= kGemvMaxM && narrow_only && !L.has_map) return kPathGemv;  // falls back to the skinny kernel if K does not split evenly
+  if (narrow_only && !L.has_map && M < kMidMinM) {
+    // one row: the GEMV kernel; two to four: its four-row variant where K splits into its shares; up to sixteen: the
+    // 16-row kernel (each falls back to the per-row-tile kernel if K does not split its way)
+    int tpw = 0, nw = 0;
+    if (M == 1 || (M <= kGemvMaxM && gemv_narrow_shares(L, M) > 0)) return kPathGemv;
+    if (gemv16_shape(L, 256, kMaxSplitsK, &tpw, &nw)) return kPathGemv16;
+  }
   // per-group activation tiles with the weights in registers: measured faster than its neighbours for 2-16 rows on the
   // wide and hybrid-word formats (whose whole-k-tile staging is the costliest) and for 17-32 rows on the narrow one
   if (wide_only && M >= 2 && M < kMidMinM) return kPathRows;
@@ -179,8 +185,17 @@ static int64_t skinny_need(const Layout& L, int M) {
 static int64_t dense_need(const Layout& L, int M) {
   if (M <= 0) return 0;
   switch (dense_path(L, M)) {
-    case kPathGemv:
+    case kPathGemv: {
+      int tpw = 0, waves = 0;
+      if (M == 1 && gemv1_shape(L, 256, &tpw, &waves)) return 0;   // whether K splits does not depend on the chip
       return gemv_narrow_shares(L, M) > 0 ? 0 : skinny_need(L, M);
+    }
+    case kPathGemv16: {
+      int tpw = 0, nw = 0;
+      if (!gemv16_shape(L, device_cus(), kMaxSplitsK, &tpw, &nw)) return skinny_need(L, M);
+      const int S = L.tiles[kNarrow] / tpw;
+      return S > 1 ? (int64_t)S * M * L.N * 4 : 0;
+    }
     case kPathRows: {
       const int S = rows_splits(L, M);
       return S > 1 ? (int64_t)S * M * L.N * 4 : 0;
@@ -421,7 +436,7 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
     if (rc != CCQ_OK) return rc;
     if (d.S > 1) need_passes = std::max(need_passes, (int64_t)d.S * mc * L.N * 4);
   }
-  if (!explicit_launch && have < dense_need(L, M)) return CCQ_ERR_WORKSPACE;
+  if (!explicit_launch && dense_path(L, M) != kPathGemv16 && have < dense_need(L, M)) return CCQ_ERR_WORKSPACE;
 
   if (!explicit_launch) {
     const DensePath path = dense_path(L, M);
@@ -429,6 +444,18 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
     if (path == kPathPrefill) {
       rc = launch_prefill(w, L, x, M, ldx, y, ldy, stream);
       if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    }
+    if (path == kPathGemv16) {
+      // as many shares of K as the chip wants and the workspace holds (a smaller workspace only means longer shares)
+      int tpw = 0, nw = 0;
+      const int64_t plane = (int64_t)M * L.N * 4;
+      if (gemv16_shape(L, device_cus(), std::max<int64_t>(1, have / plane), &tpw, &nw)) {
+        const int S = L.tiles[kNarrow] / tpw;
+        float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
+        rc = launch_gemv16(w, L, x, M, ldx, y, ldy, partial, tpw, nw, stream);
+        if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
+        if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+      }
     }
     if (path == kPathRows) {
       const int S = rows_splits(L, M);
@@ -447,6 +474,11 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
     }
     // one to four rows, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
     if (path == kPathGemv) {
+      int tpw = 0, waves = 0;
+      if (M == 1 && gemv1_shape(L, device_cus(), &tpw, &waves)) {
+        rc = launch_gemv1(w, L, x, y, stream, tpw, waves);
+        if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+      }
       rc = launch_gemv_narrow(w, L, x, M, ldx, y, ldy, stream);
       if (rc != CCQ_ERR_UNSUPPORTED) return rc;
     }

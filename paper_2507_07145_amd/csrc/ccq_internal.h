@@ -112,6 +112,17 @@ constexpr int kGemvMaxM = 4;
 int gemv_narrow_shares(const Layout& L, int M);  // wavefronts along K per workgroup; 0 = not applicable
 int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
 
+// One activation row on narrow-format weights (ccq_gemv.hip): shape of the launch for a chip of `cus` compute units
+// (false when K does not split into at most 16 equal shares of a built length), and the launcher.
+bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
+int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves);
+int device_cus();  // compute units of the current device (cached per device)
+// Two to sixteen rows on narrow-format weights (ccq_gemv.hip): K is cut into tiles / tpw shares across workgroups; with
+// more than one share the fp32 partial tiles go to `partial` ([shares][M][N]) and launch_reduce_splits adds them.
+bool gemv16_shape(const Layout& L, int cus, int64_t max_shares, int* tpw_out, int* nw_out);
+int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int tpw,
+                  int nw, void* stream);
+
 // Kernel for a few dozen to a few hundred rows, any format mix (ccq_mid.hip): 64-row tiles, K cut into S
 // shares whose fp32 partial tiles go to `partial` ([S][M][N]) when S > 1 (then call launch_reduce_splits).
 constexpr int kMidMinM = 17;
