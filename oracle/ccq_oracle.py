@@ -67,7 +67,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        # CCQ_ORACLE_LIBRARY names another build of ccq_oracle.c (the host-sanitizer test points it at an instrumented one)
+        L = ctypes.CDLL(os.environ.get("CCQ_ORACLE_LIBRARY") or build())
         u8p = ctypes.POINTER(ctypes.c_uint8)
         u16p = ctypes.POINTER(ctypes.c_uint16)
         u32p = ctypes.POINTER(ctypes.c_uint32)

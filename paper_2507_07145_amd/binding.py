@@ -15,7 +15,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libccq.so")
+# CCQ_LIBRARY names another build of the same library (the host-sanitizer test points it at an instrumented one)
+LIB_PATH = os.environ.get("CCQ_LIBRARY") or os.path.join(_HERE, "libccq.so")
 
 CCQ_OK = 0
 STATUS = {0: "CCQ_OK", -1: "CCQ_ERR_NULL", -2: "CCQ_ERR_BAD_PARAM", -3: "CCQ_ERR_UNSUPPORTED", -4: "CCQ_ERR_ALIGN",

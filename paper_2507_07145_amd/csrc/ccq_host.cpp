@@ -96,13 +96,14 @@ static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
   (void)rows_total;
   Decomp d;
+  const int64_t cus = device_cus();
   const int nt = L.tiles[kNarrow] + L.tiles[kWide];  // k-tiles per row tile
   const int64_t units = (int64_t)L.row_tiles * experts;  // row tiles over all experts
   if (M == 1) {
     // GEMV, bound by the vector ALU: a workgroup is one group of wavefronts that split K among
     // themselves (reduced in LDS, no workspace pass); every wavefront gets about 8 k-tiles so that its
     // set-up cost is amortised, and two row tiles when there are plenty of rows (narrow format only).
-    d.RT = (units >= 1024 && L.tiles[kWide] == 0) ? 2 : 1;
+    d.RT = (units >= 4 * cus && L.tiles[kWide] == 0) ? 2 : 1;
     d.WR = 1;
     d.WK = std::max(1, std::min(8, nt / (L.tiles[kNarrow] > 0 ? 8 : 4)));  // wide k-tiles are 2.75 times the bytes of narrow ones
     d.S = 1;
@@ -114,7 +115,7 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     // work (config 3, M = 16: 61 -> 42 us; 8192 x 8192 mixed: 21.8 -> 18.8 us; 4096 x 4096 is better off with four)
     // -- and for grouped calls on long rows of narrow-format weights (config 4, K = 7168: 108 -> 96 us; with K = 2048
     // four are better)
-    const bool mixed_many_rows = L.tiles[kNarrow] > 0 && L.tiles[kWide] > 0 && L.row_tiles >= 512 && M <= 16;
+    const bool mixed_many_rows = L.tiles[kNarrow] > 0 && L.tiles[kWide] > 0 && L.row_tiles >= 2 * cus && M <= 16;
     const bool grouped_long_k = experts > 1 && L.tiles[kWide] == 0 && L.tiles[kNarrow] >= 24 && M <= 32;
     const int wr_max = (mixed_many_rows || grouped_long_k) ? 8 : 4;
     d.WR = (int)std::min<int64_t>(wr_max, std::max(1, L.row_tiles / d.RT));
@@ -122,7 +123,7 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
     int64_t row_blocks = (int64_t)ceil_div(L.row_tiles, d.RT * d.WR) * experts;
     // workgroups wanted: two per CU for the narrow format, four for the wide kinds, whose per-chunk staging is longer
     // than the contraction it feeds and is best hidden by other workgroups of the same CU
-    const int64_t want_blocks = L.tiles[kNarrow] > 0 ? 512 : 1024;
+    const int64_t want_blocks = (L.tiles[kNarrow] > 0 ? 2 : 4) * cus;
     int s = (int)std::max<int64_t>(1, want_blocks / std::max<int64_t>(1, row_blocks));
     s = std::min(s, std::max(1, nt / 2));
     if (M > 16) s = std::min(s, 2);
@@ -152,17 +153,22 @@ static DensePath dense_path(const Layout& L, int M) {
   if (M < kMidMinM) return kPathSkinny;
   if (narrow_only && M <= 32) return kPathRows;
   if (narrow_only && M > 128) {
-    // 256-row tiles pay off once they fill enough of the chip.  Estimated times in us at K = 8192, fitted to
-    // measurements: a round of up to 256 workgroups of the 256-row kernel takes 98 / 120 / 197 us with 128 / 192 /
-    // 256 columns per workgroup when at most half of the CUs are busy and up to 40 % more when all are (the clock
-    // sinks); the 64-row kernel takes 20 us + 0.187 us per workgroup of 64 x 128 results (at least 256 of them).
+    // 256-row tiles pay off once they fill enough of the chip.  Both kernels are bound by the same two things (matrix
+    // core time, and the vector work of decoding a weight tile once per row block of the output), so their times
+    // are compared in units of one output element per round of workgroups over the chip's CUs; the relative costs
+    // per element are ratios measured between the kernels, not times: the 256-row kernel costs 1.0 with 192-column
+    // blocks and 1.22 with 128 or 256 columns, up to 40 % more when more than half of the CUs are busy (the clock
+    // sinks under a full matrix load); the 64-row kernel, which decodes every weight tile four times as often,
+    // costs 2.4 and about 0.4 of a round in fixed set-up.
+    const int64_t cus = device_cus();
     const int bn = prefill_block_cols(L, M);
     const int64_t wg_p = (int64_t)ceil_div(M, 256) * ceil_div(L.N, bn);
-    const int64_t rounds = (wg_p + 255) / 256;
-    const double fill = (double)wg_p / (double)(rounds * 256);
-    const double t_p = (double)rounds * (bn == 128 ? 98.0 : (bn == 192 ? 120.0 : 197.0)) * (1.0 + 0.8 * std::max(0.0, fill - 0.5));
+    const int64_t rounds_p = (wg_p + cus - 1) / cus;
+    const double fill = (double)wg_p / (double)(rounds_p * cus);
+    const double t_p = (double)rounds_p * 256.0 * bn * (bn == 192 ? 1.0 : 1.22) * (1.0 + 0.8 * std::max(0.0, fill - 0.5));
     const int64_t wg_m = (int64_t)ceil_div(M, 64) * ceil_div(L.N, 128);
-    const double t_m = 20.0 + 0.187 * (double)std::max<int64_t>(wg_m, 256);
+    const double rounds_m = std::max(1.0, (double)wg_m / (double)cus);   // its workgroups are short: partial rounds overlap
+    const double t_m = (rounds_m + 0.42) * 64.0 * 128.0 * 2.4;
     return t_p <= t_m ? kPathPrefill : kPathMid;
   }
   return kPathMid;
@@ -621,10 +627,10 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
     // one-held-row kernel (wavefront-private staging, no 16-row activation tile)
     c.m_tile_hint = 1;
     c.d = choose_decomp(L, 1, std::max(1, active), P);
-    // the grid spans all E experts and most of them have no row: beyond about 16384 workgroups the dispatch of the
+    // the grid spans all E experts and most of them have no row: beyond about 64 workgroups per CU the dispatch of the
     // empty ones shows, and fewer, larger workgroups (several row tiles side by side, at most 512 threads) are faster
     const int wr_max = std::max(1, std::min(std::min(4, 8 / c.d.WK), L.row_tiles / c.d.RT));
-    while (c.d.WR * 2 <= wr_max && (int64_t)ceil_div(L.row_tiles, c.d.RT * c.d.WR) * (c.n_active > 0 ? c.n_active : E) > 16384) c.d.WR *= 2;
+    while (c.d.WR * 2 <= wr_max && (int64_t)ceil_div(L.row_tiles, c.d.RT * c.d.WR) * (c.n_active > 0 ? c.n_active : E) > 64 * (int64_t)device_cus()) c.d.WR *= 2;
   } else {
     c.d = grouped_decomp(L, E, P, active, workspace ? workspace_bytes : 0);
   }

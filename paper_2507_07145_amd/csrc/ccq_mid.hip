@@ -700,7 +700,8 @@ int mid_splits(const Layout& L, int M) {
   // one workgroup per CU, or two when the weights have wide-format groups and there are at least 128 blocks: that
   // kernel moves more through LDS per MFMA and gains from a second workgroup on the CU (config 3, M = 64: 84 -> 75 us),
   // the register-decode kernel for the narrow format does not
-  const int64_t target = (L.tiles[kWide] > 0 && blocks >= 128) ? 512 : 256;
+  const int64_t cus = device_cus();
+  const int64_t target = (L.tiles[kWide] > 0 && 2 * blocks >= cus) ? 2 * cus : cus;
   int64_t s = std::max<int64_t>(1, target / std::max<int64_t>(1, blocks));
   s = std::min<int64_t>(s, 8);
   s = std::min<int64_t>(s, std::max(1, min_tiles / 2));

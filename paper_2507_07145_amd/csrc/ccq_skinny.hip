@@ -1163,7 +1163,7 @@ int gemv_narrow_shares(const Layout& L, int M) {
   if (L.row_tile_bytes >= ((int64_t)1 << 31) || L.row_tile_scale_halfs >= ((int64_t)1 << 31)) return 0;
   const int tiles = L.tiles[kNarrow];
   const int max_share = M == 1 ? kGemvMaxTiles : 4;
-  const int target = (M > 1 || (int64_t)L.row_tiles * tiles / 4 <= 8192) ? 4 : 8;
+  const int target = (M > 1 || (int64_t)L.row_tiles * tiles / 4 <= 32 * (int64_t)device_cus()) ? 4 : 8;
   int wk = 0, best = 1 << 30;
   for (int c = 1; c <= 8; ++c) {
     if (tiles % c != 0 || tiles / c > max_share) continue;
@@ -1516,7 +1516,7 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) ccq_rows_kernel(const RowsArg
 // sixteen gain on 8192 rows and lose on 28672), else four.
 static int rows_waves(const Layout& L, int M) {
   (void)M;
-  return L.row_tiles >= 512 ? 8 : 4;
+  return L.row_tiles >= 2 * device_cus() ? 8 : 4;
 }
 
 // K shares for ccq_rows_kernel: about four wavefronts per SIMD, at least one k-tile of every format per share.
@@ -1525,7 +1525,7 @@ int rows_splits(const Layout& L, int M) {
   const int nw = rows_waves(L, M);
   const int64_t blocks = (int64_t)((M + mrt - 1) / mrt) * ((L.row_tiles + nw - 1) / nw);
   const int min_tiles = std::min(L.tiles[kNarrow] > 0 ? L.tiles[kNarrow] : 1 << 30, L.tiles[kWide] > 0 ? L.tiles[kWide] : 1 << 30);
-  int64_t s = std::max<int64_t>(1, (4096 / nw) / std::max<int64_t>(1, blocks));  // 4096 wavefronts: four per SIMD
+  int64_t s = std::max<int64_t>(1, (16 * (int64_t)device_cus() / nw) / std::max<int64_t>(1, blocks));  // 16 wavefronts per CU: four per SIMD
   s = std::min<int64_t>(s, 8);
   s = std::min<int64_t>(s, std::max(1, min_tiles));
   return (int)s;

@@ -339,3 +339,36 @@ def test_grouped_all_experts_empty_and_errors():
     with pytest.raises(b.CcqError) as ei:
         b.grouped_gemm(w, x, rows, offs, np.array([0, 3], np.int32))      # offsets[E] != P
     assert ei.value.status == -6
+
+
+@pytest.mark.parametrize("kinds,K,N,M", [(["narrow"], 2048, 1024, 16), (["narrow"], 2048, 1024, 8), (["narrow"], 2048, 1024, 64),
+                                         (["narrow"], 4096, 256, 24), (["wide"], 4096, 256, 12), (["wide"], 2048, 272, 70),
+                                         (["narrow", "wide"], 4096, 128, 40)])
+def test_workspace_guard_bands(kinds, K, N, M):
+    """The K shares' fp32 partial tiles stay inside the workspace the library asked for: canaries on both sides of a
+    workspace of exactly ccq_gemm_workspace_bytes are untouched, and the result does not depend on what the workspace held."""
+    c = random_case(K, N, kinds, 14, stream0=M, n_wide=32 if len(kinds) == 2 else None)
+    w = c.device_weight(DEV)
+    need = b.gemm_workspace_bytes(w.desc, M)
+    assert need > 0, "the case must cut K"
+    band = 4096
+    buf = torch.full((need + 2 * band,), 0x5A, dtype=torch.uint8, device=DEV)
+    ws = buf[band:band + need]
+    x = synth.activations_bf16(M, K, synth.rng(14, 70 + M))
+    xt = b.bf16_tensor(x, DEV)
+    y1 = b.bf16_bits(b.gemm(w, xt, workspace=ws))
+    torch.cuda.synchronize()
+    assert bool((buf[:band] == 0x5A).all()) and bool((buf[band + need:] == 0x5A).all()), "wrote outside the workspace"
+    assert_gemm_close(y1, o.matmul(x, c.W()), f"guarded workspace {kinds} M={M}", rounded=(x, c.W()) if M > 32 else None)
+    buf.fill_(0xFF)   # NaN patterns in the workspace must not leak into the result
+    y2 = b.bf16_bits(b.gemm(w, xt, workspace=ws))
+    torch.cuda.synchronize()
+    assert np.array_equal(y1, y2)
+    if M > 16 or kinds != ["narrow"]:   # a smaller workspace is rejected (the 16-row narrow-format kernel only takes fewer, longer shares of K)
+        with pytest.raises(b.CcqError) as ei:
+            b.gemm(w, xt, workspace=buf[band:band + need - 16])
+        assert ei.value.status == -5
+    else:
+        y3 = b.bf16_bits(b.gemm(w, xt, workspace=buf[band:band + need // 2]))
+        torch.cuda.synchronize()
+        assert_gemm_close(y3, o.matmul(x, c.W()), f"half the workspace {kinds} M={M}")
