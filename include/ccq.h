@@ -27,8 +27,8 @@
  *           `scales` is not used.
  * A weight matrix uses the narrow format, the wide format, a per-group mix of
  * those two (group_fmt), all rows sharing the same map, or the hybrid word.
- * Group size is 64 along K and scales are fp16, one per (row, group), unless
- * scale_mode says otherwise.
+ * Group size is 64 along K (K a multiple of 64; N, K and the group map are otherwise free) and scales are fp16, one
+ * per (row, group), unless scale_mode says otherwise.
  *
  * Conventions
  *   - Every pointer is marked HOST or DEVICE.  The caller owns all buffers; the
@@ -47,8 +47,8 @@
  *     of the group (Alg. 2/3: q_w = W_q[idx / p_w]); the first state of a code
  *     sits in its most significant bits (Sec. 3.1, the 00->01->10 = 0010
  *     example).  The kernels read a permuted "device" order of the same bytes,
- *     produced by the ccq_pack_* host routines below; it stores exactly as many
- *     code bytes as the canonical order.
+ *     produced by the ccq_pack_* host routines below; it stores the same bytes, plus
+ *     zero padding up to whole tiles (see ccq_info).
  */
 #ifndef CCQ_H
 #define CCQ_H
@@ -107,9 +107,14 @@ typedef struct {
   const void *scale_super;  /* DEVICE, fp16[N]: per-output-channel super scale s_super (scale_mode 1) */
 } ccq_weight;
 
-/* Sizes and accounting of the device layout (Eq. 5 for the bpw fields). */
+/* Sizes of the device layout and the accounting of Eq. 5.  The device layout holds whole tiles of 16 output rows and
+ * whole k-tiles (4 narrow-format groups, 8 wide-format or hybrid-word groups): any N >= 1, any K that is a multiple of
+ * 64 and any group map are accepted, and what does not fill its last tile is padded by the ccq_pack_* routines with
+ * zero codes and zero scales (padded weights decode to zeros and padded rows are never stored).  code_bytes,
+ * scale_bytes and meta_bytes are the sizes of the device arrays, padding included; the bits-per-weight fields count
+ * what the method stores (the canonical arrays). */
 typedef struct {
-  int64_t code_bytes;       /* bytes of the packed code stream (= canonical bytes)      */
+  int64_t code_bytes;       /* bytes of the packed code stream in device order           */
   int64_t scale_bytes;      /* bytes of the `scales` array (fp16 scales, or packed 4-bit fields)      */
   int64_t meta_bytes;       /* bytes ccq_pack_meta writes                                */
   int64_t workspace_bytes;  /* workspace ccq_gemm may need for M <= M_max                */
@@ -119,6 +124,9 @@ typedef struct {
   int32_t align;            /* required alignment of DEVICE pointers (16)                */
   double code_bpw;          /* code bits per weight: exactly 2.0 narrow, 2.75 wide       */
   double total_bpw;         /* + scales (+ super scales) + per-row alpha/beta                        */
+  int64_t canonical_code_bytes; /* bytes of the canonical code array the pack routine reads (= code_bytes without padding) */
+  int32_t padded_N;         /* rows of the device layout: N rounded up to a multiple of 16            */
+  int32_t padded_groups[2]; /* groups of each format in the device layout (whole k-tiles)             */
 } ccq_info;
 
 /* Validate a descriptor (DEVICE pointers may be NULL here) and report the
@@ -127,7 +135,7 @@ typedef struct {
 int ccq_pack_info(const ccq_weight *w, int32_t M_max, ccq_info *out);
 
 /* Host-side permutations from canonical order to device order.
- *   ccq_pack_codes : canonical_codes HOST uint8 [N][row bytes]  -> out HOST [code_bytes]
+ *   ccq_pack_codes : canonical_codes HOST uint8 [N][row bytes] (canonical_code_bytes in all) -> out HOST [code_bytes]
  *   ccq_pack_scales: canonical fp16 bits HOST [N][K/64]         -> out HOST [scale_bytes/2]  (scale_mode 0)
  *   ccq_pack_meta  : group_fmt                                  -> out HOST [meta_bytes]
  * Byte values are copied, never altered.  The caller uploads the results. */
@@ -141,7 +149,8 @@ int ccq_pack_scales4(const ccq_weight *w, const uint8_t *canonical_sq, void *out
 /* y[m][n] = sum_k x[m][k] * W_dq[n][k]   (the W2A16 GEMV / GEMM of the
  * "Inference Performance" section; Alg. 2/3 fused into the contraction).
  *   x DEVICE bf16 [M][ldx], y DEVICE bf16 [M][ldy] (round to nearest even),
- *   fp32 accumulation.  ldx, ldy in elements, multiples of 8.
+ *   fp32 accumulation.  ldx >= K, ldy >= N, in elements, multiples of 8; columns N.. of y are not written.
+ *   The per-row arrays of the descriptor (code_alpha, code_beta, scale_super) hold N entries: no padding.
  *   M = 0 is a no-op.  workspace DEVICE, workspace_bytes >= the value
  *   ccq_pack_info reports for M_max >= M (may be NULL if that value is 0). */
 int ccq_gemm(const ccq_weight *w, const void *x, int32_t M, int64_t ldx, void *y, int64_t ldy,
@@ -221,7 +230,7 @@ int64_t ccq_grouped_workspace_bytes(const ccq_weight *w0, int32_t E, int32_t P);
  *      DEVICE pointers only `meta` is read, and only for a per-group mix (ccq_pack_meta).
  *   W DEVICE fp32 [N][ldw], ldw >= K, a multiple of 4.
  *   codes_out DEVICE [code_bytes], scales_out DEVICE [scale_bytes] (sizes from ccq_pack_info), both in
- *   device order: what ccq_gemm reads (scale_mode 1: scales_out receives the packed fields of the narrow-format
+ *   device order, padding included (written as zeros): what ccq_gemm reads (scale_mode 1: scales_out receives the packed fields of the narrow-format
  *   groups and may be NULL when there are none).  alpha_out, beta_out DEVICE fp32 [N], needed when there are
  *   narrow-format groups (may be NULL otherwise).  scale_super_out DEVICE fp16 [N], scale_mode 1 only.  workspace DEVICE, at least ccq_quantize_workspace_bytes(w) bytes (-1: not built).
  *   Enqueues on hip_stream and returns; nothing is allocated.  W must be finite (NaN or infinity in a

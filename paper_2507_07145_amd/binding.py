@@ -44,7 +44,8 @@ class ccq_weight(ctypes.Structure):
 class ccq_info(ctypes.Structure):
     _fields_ = [("code_bytes", ctypes.c_int64), ("scale_bytes", ctypes.c_int64), ("meta_bytes", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_int64), ("row_tile_bytes", ctypes.c_int64), ("bytes_per_group", ctypes.c_int32 * 2),
-                ("groups", ctypes.c_int32 * 2), ("align", ctypes.c_int32), ("code_bpw", ctypes.c_double), ("total_bpw", ctypes.c_double)]
+                ("groups", ctypes.c_int32 * 2), ("align", ctypes.c_int32), ("code_bpw", ctypes.c_double), ("total_bpw", ctypes.c_double),
+                ("canonical_code_bytes", ctypes.c_int64), ("padded_N", ctypes.c_int32), ("padded_groups", ctypes.c_int32 * 2)]
 
 
 class ccq_launch(ctypes.Structure):
@@ -152,8 +153,8 @@ def pack_info(w: ccq_weight, M_max: int = 64) -> ccq_info:
 def pack_codes(w: ccq_weight, canonical: np.ndarray) -> np.ndarray:
     info = pack_info(w, 0)
     src = np.ascontiguousarray(canonical, dtype=np.uint8)
-    if src.size != info.code_bytes:
-        raise ValueError(f"canonical code stream has {src.size} bytes, layout needs {info.code_bytes}")
+    if src.size != info.canonical_code_bytes:
+        raise ValueError(f"canonical code stream has {src.size} bytes, layout needs {info.canonical_code_bytes}")
     out = np.empty(info.code_bytes, dtype=np.uint8)
     _check(load().ccq_pack_codes(ctypes.byref(w), _np_ptr(src), _np_ptr(out)), "ccq_pack_codes")
     return out
@@ -162,9 +163,9 @@ def pack_codes(w: ccq_weight, canonical: np.ndarray) -> np.ndarray:
 def pack_scales(w: ccq_weight, canonical_fp16_bits: np.ndarray) -> np.ndarray:
     info = pack_info(w, 0)
     src = np.ascontiguousarray(canonical_fp16_bits, dtype=np.uint16)
-    if src.size * 2 != info.scale_bytes:
+    if src.size != w.N * (w.K // 64):
         raise ValueError("scale array size does not match the layout")
-    out = np.empty(src.size, dtype=np.uint16)
+    out = np.empty(info.scale_bytes // 2, dtype=np.uint16)
     _check(load().ccq_pack_scales(ctypes.byref(w), _np_ptr(src), _np_ptr(out)), "ccq_pack_scales")
     return out
 
@@ -195,6 +196,13 @@ def bf16_bits(t: torch.Tensor) -> np.ndarray:
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+def _per_row(values: np.ndarray, E: int, N: int, n_pad: int, dtype) -> np.ndarray:
+    """[E][N] per-row parameters in rows of n_pad entries (the experts of a stack then start 16-byte aligned whatever N is)."""
+    out = np.zeros((E, n_pad), dtype=dtype)
+    out[:, :N] = np.ascontiguousarray(values, dtype=dtype).reshape(E, N)
+    return out
+
+
 class Weight:
     """Device-resident quantized weights of one matrix, or of E same-shaped experts stacked along a leading axis."""
 
@@ -222,8 +230,8 @@ class Weight:
         self.scales = torch.from_numpy(ps.view(np.int16)).to(device)
         needs_ab = any(f.code_cluster for f in fmts)
         if needs_ab:
-            self.alpha = torch.from_numpy(np.ascontiguousarray(alpha, dtype=np.float32).reshape(E, N)).to(device)
-            self.beta = torch.from_numpy(np.ascontiguousarray(beta, dtype=np.float32).reshape(E, N)).to(device)
+            self.alpha = torch.from_numpy(_per_row(alpha, E, N, info.padded_N, np.float32)).to(device)
+            self.beta = torch.from_numpy(_per_row(beta, E, N, info.padded_N, np.float32)).to(device)
         if group_fmt is not None:
             self.meta = torch.from_numpy(pack_meta(w)).to(device)
         w.codes, w.scales = self.codes.data_ptr(), self.scales.data_ptr()
@@ -249,11 +257,11 @@ class Weight:
         if info.scale_bytes > 0:
             sq = np.ascontiguousarray(sq_packed, dtype=np.uint8).reshape(E, N, -1)
             self.scales = torch.from_numpy(np.stack([pack_scales4(w, sq[e]) for e in range(E)]).view(np.int16)).to(device)
-        self.ssup = torch.from_numpy(np.ascontiguousarray(s_super_fp16, dtype=np.uint16).reshape(E, N).view(np.int16)).to(device)
+        self.ssup = torch.from_numpy(_per_row(s_super_fp16, E, N, info.padded_N, np.uint16).view(np.int16)).to(device)
         needs_ab = any(f.code_cluster for f in fmts)
         if needs_ab:
-            self.alpha = torch.from_numpy(np.ascontiguousarray(alpha, dtype=np.float32).reshape(E, N)).to(device)
-            self.beta = torch.from_numpy(np.ascontiguousarray(beta, dtype=np.float32).reshape(E, N)).to(device)
+            self.alpha = torch.from_numpy(_per_row(alpha, E, N, info.padded_N, np.float32)).to(device)
+            self.beta = torch.from_numpy(_per_row(beta, E, N, info.padded_N, np.float32)).to(device)
         if group_fmt is not None:
             self.meta = torch.from_numpy(pack_meta(w)).to(device)
         w.codes = self.codes.data_ptr()
@@ -283,9 +291,10 @@ class Weight:
         return (self.codes.stride(0), self.scales.stride(0) * 2 if self.scales is not None else 0, ab)
 
 
-def quantize(W: torch.Tensor, fmt, scale_mode: int = 0, group_fmt=None, stream=None) -> Weight:
+def quantize(W: torch.Tensor, fmt, scale_mode: int = 0, group_fmt=None, stream=None, prefill_byte: int | None = None) -> Weight:
     """Quantize fp32 W [N][K] on the GPU through ccq_quantize; the result is ready for gemm().  `fmt`: NARROW, WIDE, H16, or
-    [NARROW, WIDE] with `group_fmt` (uint8 [K/64], 0 = narrow, 1 = wide)."""
+    [NARROW, WIDE] with `group_fmt` (uint8 [K/64], 0 = narrow, 1 = wide).  `prefill_byte`: every byte of the code and scale
+    arrays is set to it before the call (a test's way of showing that the call leaves none of them unwritten)."""
     assert W.dtype == torch.float32 and W.dim() == 2 and W.stride(1) == 1 and W.is_cuda
     N, K = W.shape
     self = Weight()
@@ -304,6 +313,10 @@ def quantize(W: torch.Tensor, fmt, scale_mode: int = 0, group_fmt=None, stream=N
     if any(f.code_cluster for f in fmts):
         self.alpha = torch.empty(N, dtype=torch.float32, device=W.device)
         self.beta = torch.empty(N, dtype=torch.float32, device=W.device)
+    if prefill_byte is not None:
+        self.codes.fill_(prefill_byte)
+        if self.scales is not None:
+            self.scales.view(torch.uint8).fill_(prefill_byte)
     need = int(load().ccq_quantize_workspace_bytes(ctypes.byref(d)))
     if need < 0:
         raise CcqError(-3, "ccq_quantize_workspace_bytes")
@@ -332,14 +345,21 @@ def _workspace(nbytes: int, device) -> torch.Tensor | None:
     return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes > 0 else None
 
 
+def _new_output(rows: int, N: int, device) -> torch.Tensor:
+    """bf16 [rows][N] whose row stride is a multiple of 8 elements, as the entry points require."""
+    ld = (N + 7) // 8 * 8
+    y = torch.empty((rows, ld), dtype=torch.bfloat16, device=device)
+    return y if ld == N else y[:, :N]
+
+
 def gemm(w: Weight, x: torch.Tensor, out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None,
          launch: ccq_launch | None = None) -> torch.Tensor:
     """y = x W_dq^T through ccq_gemm (or ccq_gemm_ex when `launch` is given).  x: bf16 [M][K] on the GPU."""
     assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1 and x.is_cuda
     M = x.shape[0]
-    y = out if out is not None else torch.empty((M, w.N), dtype=torch.bfloat16, device=x.device)
+    y = out if out is not None else _new_output(M, w.N, x.device)
     if workspace is None:
-        need = launch.splits_k * min(M, 64) * w.N * 4 if (launch is not None and launch.splits_k > 1) else gemm_workspace_bytes(w.desc, M)
+        need = launch.splits_k * min(M, 64) * w.info.padded_N * 4 if (launch is not None and launch.splits_k > 1) else gemm_workspace_bytes(w.desc, M)
         workspace = _workspace(need, x.device)
         if workspace is not None and stream is not None:
             workspace.record_stream(stream)   # the temporary returns to the allocator at once; its memory must outlive the kernels
@@ -381,7 +401,7 @@ def grouped_gemm(w: Weight, x: torch.Tensor, sorted_rows: torch.Tensor, expert_o
     assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1 and x.is_cuda
     assert sorted_rows.dtype == torch.int32 and expert_offsets.dtype == torch.int32
     P = sorted_rows.numel()
-    y = out if out is not None else torch.empty((P, w.N), dtype=torch.bfloat16, device=x.device)
+    y = out if out is not None else _new_output(P, w.N, x.device)
     if workspace is None:
         workspace = _workspace(max(grouped_workspace_bytes(w, P), 0), x.device)
         if workspace is not None and stream is not None:

@@ -28,9 +28,11 @@ struct EncArgs {
   int64_t ldw;
   int32_t N, G;        // rows; groups per row (all kinds)
   // the groups of the kind this launch works on (all of them unless the matrix mixes formats): GK groups per row,
-  // the p-th of them is original group meta[pbase + p] (p itself without a map) and sits at packed position p of
-  // the kind's k-tiles, which start kind_code_off bytes / kind_scale_off halfwords into a row tile
-  int32_t GK, pbase;
+  // the p-th of them is original group meta[mbase + p] (p itself without a map), entry pbase + p of a row in the
+  // per-(row, group) workspace arrays, and sits at packed position p of the kind's k-tiles, which start
+  // kind_code_off bytes / kind_scale_off halfwords into a row tile.  (The map holds whole k-tiles per kind, the
+  // workspace arrays only the real groups: with a ragged last narrow tile mbase > pbase for the wide kind.)
+  int32_t GK, pbase, mbase;
   const int32_t* meta;
   int64_t kind_code_off, kind_scale_off;
   double zp;
@@ -90,7 +92,7 @@ __device__ __forceinline__ bool group_id(const EncArgs& a, int64_t gidx, GroupId
   if (gidx >= (int64_t)a.N * a.GK) return false;
   id.n = (int)(gidx / a.GK);
   id.p = (int)(gidx % a.GK);
-  id.g = a.meta ? a.meta[a.pbase + id.p] : id.p;
+  id.g = a.meta ? a.meta[a.mbase + id.p] : id.p;
   id.widx = (int64_t)id.n * a.G + a.pbase + id.p;
   return true;
 }
@@ -510,12 +512,23 @@ __global__ void __launch_bounds__(256) ccq_encode_h16_compress_kernel(const EncA
 // Narrow format: the four 4-bit fields of a k-tile's groups into one 16-bit word per row (group j in bits 4j..4j+3).
 __global__ void __launch_bounds__(256) ccq_encode_pack_fields_kernel(const EncArgs a) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int tiles = a.GK / kNarrowGroupsPerTile;
+  const int tiles = (a.GK + kNarrowGroupsPerTile - 1) / kNarrowGroupsPerTile;
   if (i >= (int64_t)a.N * tiles) return;
   const int n = (int)(i / tiles), t = (int)(i % tiles);
-  const uint8_t* f = a.fields + (int64_t)n * a.GK + t * kNarrowGroupsPerTile;
-  const uint32_t word = (uint32_t)f[0] | ((uint32_t)f[1] << 4) | ((uint32_t)f[2] << 8) | ((uint32_t)f[3] << 12);
+  const uint8_t* f = a.fields + (int64_t)n * a.GK;
+  uint32_t word = 0;  // groups that pad the last k-tile keep field 0: scale 0
+#pragma unroll
+  for (int j = 0; j < kNarrowGroupsPerTile; ++j) {
+    const int p = t * kNarrowGroupsPerTile + j;
+    if (p < a.GK) word |= (uint32_t)f[p] << (4 * j);
+  }
   a.scales[(int64_t)(n / kRowsPerTile) * a.row_tile_scale_halfs + a.kind_scale_off + (int64_t)t * kNarrowTileScaleHalfs4 + n % kRowsPerTile] = (uint16_t)word;
+}
+
+// Clears `n16` 16-byte units (a kernel, not a memset node: the call may be recorded into a graph).
+__global__ void __launch_bounds__(256) ccq_encode_clear_kernel(uint4* p, int64_t n16) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = uint4{0u, 0u, 0u, 0u};
 }
 
 static int64_t round16(int64_t v) { return (v + 15) / 16 * 16; }
@@ -564,15 +577,25 @@ int launch_encode(const Layout& L, const float* W, int64_t ldw, void* codes, voi
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const dim3 block(256);
+  if (L.padded()) {
+    // rows that pad the last row tile and groups that pad the last k-tile of a kind are written by no kernel below:
+    // zero codes and zero scales (both arrays are whole 16-byte units: a row tile's share of either is)
+    const int64_t code16 = L.row_tile_bytes * L.row_tiles / 16, scale16 = L.row_tile_scale_halfs * L.row_tiles / 8;
+    if (code16 > 0) hipLaunchKernelGGL(ccq_encode_clear_kernel, dim3((unsigned)((code16 + 255) / 256)), block, 0, st, reinterpret_cast<uint4*>(codes), code16);
+    if (scale16 > 0 && scales)
+      hipLaunchKernelGGL(ccq_encode_clear_kernel, dim3((unsigned)((scale16 + 255) / 256)), block, 0, st, reinterpret_cast<uint4*>(scales), scale16);
+  }
   // the narrow groups of every row, then the wide ones (or the hybrid words, which never mix)
   EncArgs an = a, aw = a;
   an.GK = L.groups[kNarrow];
   an.pbase = 0;
+  an.mbase = 0;
   an.kind_code_off = 0;
   an.kind_scale_off = 0;
   an.zp = (double)L.zp[kNarrow];
   aw.GK = L.groups[kWide];
   aw.pbase = L.groups[kNarrow];
+  aw.mbase = L.pgroups[kNarrow];
   aw.kind_code_off = (int64_t)L.tiles[kNarrow] * kNarrowTileBytes;
   aw.kind_scale_off = L.scale_mode == 1 ? 0 : (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs;
   aw.zp = (double)L.zp[kWide];

@@ -38,7 +38,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
-struct Args {          // 64 bytes: one scalar load
+struct Args {          // 72 bytes: two scalar loads, issued together
   const uint8_t* codes;
   const uint16_t* scales;
   const float* alpha;
@@ -48,6 +48,9 @@ struct Args {          // 64 bytes: one scalar load
   const uint16_t* scale_super;   // fp16 [N], compressed scales only
   int32_t tiles;                 // k-tiles per row tile
   float cneg;                    // -(128 + zp)
+  int32_t g_last;                // last real group of K (groups past it are padding: their scale is 0, and the
+                                 // activations of this group are read in their place)
+  int32_t n_last;                // last real output row (rows past it are padding and are not stored)
 };
 
 __device__ __forceinline__ uint16_t to_bf16_rne(float f) {
@@ -104,13 +107,13 @@ __global__ void __launch_bounds__(1024) kernel(const Args a) {
   // ---- every request, before anything else ------------------------------------------------------------------
   // x: fragment f = (group * 2 + k-step) * 4 + quarter covers elements 64 group + 16 quarter + 8 k-step .. + 7
   u32x4 xv[NF];
-  const uint16_t* xs = a.x + (size_t)t0 * 256u;
 #pragma unroll
   for (int i = 0; i < NF; ++i) {
     uint32_t f = lane + 64u * i;
     if (NG * 8 % 64 != 0) f = min(f, (uint32_t)(NG * 8 - 1));
-    const uint32_t off = ((f >> 3) << 6) | ((f & 3u) << 4) | ((f & 4u) << 1);
-    xv[i] = *reinterpret_cast<const u32x4*>(xs + off);
+    const uint32_t g = min(t0 * 4u + (f >> 3), (uint32_t)a.g_last);
+    const uint32_t off = (g << 6) | ((f & 3u) << 4) | ((f & 4u) << 1);
+    xv[i] = *reinterpret_cast<const u32x4*>(a.x + off);
   }
   // per-row parameters next (they are waited for before the first tile: in-order return makes anything requested
   // after the tiles wait for all of them), then the tiles in the order they are consumed
@@ -118,9 +121,10 @@ __global__ void __launch_bounds__(1024) kernel(const Args a) {
   uint32_t ssup[RT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    al[rt] = a.alpha[(rtile0 + rt) * 16u + n];
-    be_raw[rt] = a.beta[(rtile0 + rt) * 16u + n];
-    if constexpr (SM == 1) ssup[rt] = a.scale_super[(rtile0 + rt) * 16u + n];
+    const uint32_t row = min((rtile0 + rt) * 16u + n, (uint32_t)a.n_last);
+    al[rt] = a.alpha[row];
+    be_raw[rt] = a.beta[row];
+    if constexpr (SM == 1) ssup[rt] = a.scale_super[row];
   }
   u32x4 cw[RT][TPW];
   uint32_t sw[RT][TPW][SM == 0 ? 2 : 1];
@@ -236,7 +240,7 @@ __global__ void __launch_bounds__(1024) kernel(const Args a) {
     for (int rt = 0; rt < RT; ++rt) {
       float v = acc[rt];
       if constexpr (SM == 1) v *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup[rt]);
-      a.y[(rtile0 + rt) * 16u + lane] = to_bf16_rne(v);
+      if ((rtile0 + rt) * 16u + lane <= (uint32_t)a.n_last) a.y[(rtile0 + rt) * 16u + lane] = to_bf16_rne(v);
     }
   }
 }
@@ -262,8 +266,9 @@ struct Args16 {
   const uint16_t* scale_super;
   float* partial;                // fp32 [shares][M][N] when K is cut
   int64_t ldx, ldy;
-  int32_t tiles, row_tiles, M, N;
+  int32_t tiles, row_tiles, M, N;   // N: rows of the device layout (a multiple of 16), the stride of the partial tiles
   float cneg;
+  int32_t g_last, n_last;           // last real group of K, last real output row (see Args)
 };
 
 template <int TPW, int SM, int NW>
@@ -293,14 +298,15 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
     if (NU % nthreads != 0) u = min(u, (uint32_t)NU - 1u);             // clamped: the request is unconditional
     const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
     const uint32_t row = min(m, (uint32_t)a.M - 1u);                    // rows past M repeat the last one; never stored
-    const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + ((size_t)t0 * 256u + lg * 64u + q * 16u);
+    const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + ((size_t)min(t0 * 4u + lg, (uint32_t)a.g_last) * 64u + q * 16u);
     xv[i][0] = *reinterpret_cast<const u32x4*>(p);
     xv[i][1] = *reinterpret_cast<const u32x4*>(p + 8);
   }
-  const float al = a.alpha[rtile * 16u + n];
-  const float be_raw = a.beta[rtile * 16u + n];
+  const uint32_t prow = min(rtile * 16u + n, (uint32_t)a.n_last);
+  const float al = a.alpha[prow];
+  const float be_raw = a.beta[prow];
   uint32_t ssup = 0;
-  if constexpr (SM == 1) ssup = a.scale_super[rtile * 16u + n];
+  if constexpr (SM == 1) ssup = a.scale_super[prow];
   u32x4 cw[TPW];
   uint32_t sw[TPW][SM == 0 ? 2 : 1];
   const uint16_t* sb = a.scales + ((size_t)rtile * (uint32_t)a.tiles + t0) * SH;
@@ -383,8 +389,8 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
   if constexpr (SM == 1) acc *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
 
   // ---- store: lane (n, kq) holds rows 4 kq .. 4 kq + 3 of column n -------------------------------------------------------
-  if (active) {
-    const uint32_t col = rtile * 16u + n;
+  const uint32_t col = rtile * 16u + n;
+  if (active && col <= (uint32_t)a.n_last) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const uint32_t m = 4u * kq + r;
@@ -454,6 +460,8 @@ int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, v
   a.scale_super = static_cast<const uint16_t*>(w->scale_super);
   a.tiles = L.tiles[kNarrow];
   a.cneg = -(128.f + L.zp[kNarrow]);
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
   const Kernel k = L.scale_mode == 0 ? pick_tpw<0>(tpw) : pick_tpw<1>(tpw);
   if (!k) return CCQ_ERR_UNSUPPORTED;
   const size_t lds = (size_t)waves * (tpw * 4) * (8 * 16 + 4 * 16);   // at most 16 * 32 * 192 bytes = 96 KiB
@@ -510,8 +518,10 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
   a.tiles = L.tiles[kNarrow];
   a.row_tiles = L.row_tiles;
   a.M = M;
-  a.N = L.N;
+  a.N = L.Npad;
   a.cneg = -(128.f + L.zp[kNarrow]);
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
   typedef void (*Kernel16)(const Args16);
   Kernel16 k = nullptr;
   const int key = tpw * 100 + nw;

@@ -18,6 +18,8 @@ static bool is_h16(const ccq_weight* w) {
          w->fmt[1].L == 3 && w->fmt[1].N == 4 && w->fmt[1].S == 2 && w->fmt[1].code_cluster == 0;
 }
 
+static int ceil_div_i(int a, int b) { return (a + b - 1) / b; }
+
 int make_layout(const ccq_weight* w, Layout* out) {
   if (!w || !out) return CCQ_ERR_NULL;
   if (w->K <= 0 || w->N <= 0 || w->n_formats < 1 || w->n_formats > 2) return CCQ_ERR_BAD_PARAM;
@@ -35,15 +37,16 @@ int make_layout(const ccq_weight* w, Layout* out) {
     const float zp = w->fmt[0].zp;
     if (w->fmt[1].zp != zp) return CCQ_ERR_UNSUPPORTED;
     if (!(zp * 2.0f == std::floor(zp * 2.0f)) || zp < 0.f || zp > 64.f) return CCQ_ERR_BAD_PARAM;
-    if (L.G % kWideGroupsPerTile != 0 || w->N % kRowsPerTile != 0) return CCQ_ERR_UNSUPPORTED;
     L.h16 = true;
     L.kind_of_fmt[0] = L.kind_of_fmt[1] = kWide;
     L.zp[kWide] = zp;
     L.groups[kWide] = L.G;
-    L.tiles[kWide] = L.G / kWideGroupsPerTile;
+    L.tiles[kWide] = ceil_div_i(L.G, kWideGroupsPerTile);
+    L.pgroups[kWide] = L.tiles[kWide] * kWideGroupsPerTile;
     L.row_tile_bytes = (int64_t)L.tiles[kWide] * kH16TileBytes;
     L.row_tile_scale_halfs = L.scale_mode == 1 ? 0 : (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;  // mode 1: the fields sit in the words
-    L.row_tiles = w->N / kRowsPerTile;
+    L.row_tiles = ceil_div_i(w->N, kRowsPerTile);
+    L.Npad = L.row_tiles * kRowsPerTile;
     if (L.row_tile_bytes * (int64_t)L.row_tiles >= (int64_t)1 << 40) return CCQ_ERR_BAD_PARAM;
     *out = L;
     return CCQ_OK;
@@ -66,16 +69,17 @@ int make_layout(const ccq_weight* w, Layout* out) {
     if (f < 0 || f >= w->n_formats) return CCQ_ERR_BAD_PARAM;
     L.groups[L.kind_of_fmt[f]]++;
   }
-  // whole k-tiles only, and whole row tiles (the kernels do not mask partial tiles)
-  if (L.groups[kNarrow] % kNarrowGroupsPerTile != 0 || L.groups[kWide] % kWideGroupsPerTile != 0) return CCQ_ERR_UNSUPPORTED;
-  if (w->N % kRowsPerTile != 0) return CCQ_ERR_UNSUPPORTED;
-  L.tiles[kNarrow] = L.groups[kNarrow] / kNarrowGroupsPerTile;
-  L.tiles[kWide] = L.groups[kWide] / kWideGroupsPerTile;
+  // whole k-tiles and whole row tiles in the device layout: what is missing is padding (zero codes, zero scales)
+  L.tiles[kNarrow] = ceil_div_i(L.groups[kNarrow], kNarrowGroupsPerTile);
+  L.tiles[kWide] = ceil_div_i(L.groups[kWide], kWideGroupsPerTile);
+  L.pgroups[kNarrow] = L.tiles[kNarrow] * kNarrowGroupsPerTile;
+  L.pgroups[kWide] = L.tiles[kWide] * kWideGroupsPerTile;
   L.row_tile_bytes = (int64_t)L.tiles[kNarrow] * kNarrowTileBytes + (int64_t)L.tiles[kWide] * kWideTileBytes;
   L.row_tile_scale_halfs = L.scale_mode == 1
                                ? (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs4
                                : (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs + (int64_t)L.tiles[kWide] * kWideTileScaleHalfs;
-  L.row_tiles = w->N / kRowsPerTile;
+  L.row_tiles = ceil_div_i(w->N, kRowsPerTile);
+  L.Npad = L.row_tiles * kRowsPerTile;
   if (L.row_tile_bytes * (int64_t)L.row_tiles >= (int64_t)1 << 40) return CCQ_ERR_BAD_PARAM;
   *out = L;
   return CCQ_OK;
@@ -181,7 +185,7 @@ static int64_t skinny_need(const Layout& L, int M) {
   for (int mc : {M >= kMaxSkinnyM ? kMaxSkinnyM : 0, M % kMaxSkinnyM}) {
     if (mc == 0) continue;
     const Decomp d = choose_decomp(L, mc, 1, mc);
-    if (d.S > 1) need = std::max(need, (int64_t)d.S * mc * L.N * 4);
+    if (d.S > 1) need = std::max(need, (int64_t)d.S * mc * L.Npad * 4);
   }
   return need;
 }
@@ -200,16 +204,16 @@ static int64_t dense_need(const Layout& L, int M) {
       int tpw = 0, nw = 0;
       if (!gemv16_shape(L, device_cus(), kMaxSplitsK, &tpw, &nw)) return skinny_need(L, M);
       const int S = L.tiles[kNarrow] / tpw;
-      return S > 1 ? (int64_t)S * M * L.N * 4 : 0;
+      return S > 1 ? (int64_t)S * M * L.Npad * 4 : 0;
     }
     case kPathRows: {
       const int S = rows_splits(L, M);
-      return S > 1 ? (int64_t)S * M * L.N * 4 : 0;
+      return S > 1 ? (int64_t)S * M * L.Npad * 4 : 0;
     }
     case kPathMid:
     case kPathPrefill: {  // the 256-row kernel needs none; where it does not apply the 64-row kernel runs
       const int S = mid_splits(L, M);
-      return S > 1 ? (int64_t)S * M * L.N * 4 : 0;
+      return S > 1 ? (int64_t)S * M * L.Npad * 4 : 0;
     }
     default:
       return skinny_need(L, M);
@@ -245,16 +249,24 @@ extern "C" int ccq_pack_info(const ccq_weight* w, int32_t M_max, ccq_info* out) 
   info.row_tile_bytes = L.row_tile_bytes;
   info.code_bytes = L.row_tile_bytes * L.row_tiles;
   info.scale_bytes = L.row_tile_scale_halfs * L.row_tiles * 2;
-  info.meta_bytes = (int64_t)L.G * 4;
+  info.meta_bytes = (int64_t)(L.pgroups[kNarrow] + L.pgroups[kWide]) * 4;
   info.align = 16;
   info.workspace_bytes = dense_workspace_bytes(L, M_max);
+  info.padded_N = L.Npad;
+  for (int f = 0; f < w->n_formats; ++f) info.padded_groups[f] = L.pgroups[L.kind_of_fmt[f]];
   // Eq. 5: stored code bits per weight; a narrow group holds 64/4 one-byte codes
   // (g = 0 mod N: scale bits come on top), a wide group ceil(64/3) = 22 one-byte
   // codes (g = 1 mod N: the spare bits of the last code are part of the count).
+  // The accounting is that of the canonical arrays (what the method stores); the padding of the device layout
+  // (whole row tiles and k-tiles) is reported separately.
   const double weights = (double)L.N * (double)L.K;
-  info.code_bpw = 8.0 * (double)info.code_bytes / weights;
+  const int64_t canon_row = L.h16 ? (int64_t)L.G * kH16GroupBytes : (int64_t)L.groups[kNarrow] * kNarrowGroupBytes + (int64_t)L.groups[kWide] * kWideGroupBytes;
+  info.canonical_code_bytes = canon_row * L.N;
+  const double canon_scale_bytes =
+      L.scale_mode == 0 ? 2.0 * (double)L.G * (double)L.N : (double)((L.groups[kNarrow] + 1) / 2) * (double)L.N;
+  info.code_bpw = 8.0 * (double)info.canonical_code_bytes / weights;
   const double ab_bytes = (L.groups[kNarrow] > 0 ? 8.0 * (double)L.N : 0.0) + (L.scale_mode == 1 ? 2.0 * (double)L.N : 0.0);
-  info.total_bpw = 8.0 * ((double)info.code_bytes + (double)info.scale_bytes + ab_bytes) / weights;
+  info.total_bpw = 8.0 * ((double)info.canonical_code_bytes + canon_scale_bytes + ab_bytes) / weights;
   *out = info;
   return CCQ_OK;
 }
@@ -277,6 +289,7 @@ extern "C" int ccq_pack_codes(const ccq_weight* w, const uint8_t* src, void* out
   int rc = make_layout(w, &L);
   if (rc != CCQ_OK) return rc;
   uint8_t* out = static_cast<uint8_t*>(out_v);
+  std::memset(out, 0, (size_t)(L.row_tile_bytes * L.row_tiles));   // padded rows and groups: zero codes
   if (L.h16) {
     for (int n = 0; n < L.N; ++n) {
       const uint8_t* row = src + (int64_t)n * L.G * kH16GroupBytes;
@@ -354,6 +367,7 @@ extern "C" int ccq_pack_scales(const ccq_weight* w, const uint16_t* src, void* o
   if (rc != CCQ_OK) return rc;
   if (L.scale_mode != 0) return CCQ_ERR_BAD_PARAM;
   uint16_t* out = static_cast<uint16_t*>(out_v);
+  std::memset(out, 0, (size_t)(L.row_tile_scale_halfs * L.row_tiles * 2));   // padded rows and groups: scale 0
   std::vector<int> pos, kind;
   packed_order(w, L, pos, kind);
   const int64_t wide_base = (int64_t)L.tiles[kNarrow] * kNarrowTileScaleHalfs;
@@ -379,7 +393,9 @@ extern "C" int ccq_pack_meta(const ccq_weight* w, void* out_v) {
   int32_t* out = static_cast<int32_t*>(out_v);
   std::vector<int> pos, kind;
   packed_order(w, L, pos, kind);
-  for (int g = 0; g < L.G; ++g) out[(kind[g] == kNarrow ? 0 : L.groups[kNarrow]) + pos[g]] = g;
+  // padded positions name the last real group: its activations are read in place of theirs (their scale is 0)
+  for (int i = 0; i < L.pgroups[kNarrow] + L.pgroups[kWide]; ++i) out[i] = L.G - 1;
+  for (int g = 0; g < L.G; ++g) out[(kind[g] == kNarrow ? 0 : L.pgroups[kNarrow]) + pos[g]] = g;
   return CCQ_OK;
 }
 
@@ -440,7 +456,7 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
     Decomp d;
     rc = pass_decomp(L, mc, launch, &d);
     if (rc != CCQ_OK) return rc;
-    if (d.S > 1) need_passes = std::max(need_passes, (int64_t)d.S * mc * L.N * 4);
+    if (d.S > 1) need_passes = std::max(need_passes, (int64_t)d.S * mc * L.Npad * 4);
   }
   if (!explicit_launch && dense_path(L, M) != kPathGemv16 && have < dense_need(L, M)) return CCQ_ERR_WORKSPACE;
 
@@ -454,12 +470,12 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
     if (path == kPathGemv16) {
       // as many shares of K as the chip wants and the workspace holds (a smaller workspace only means longer shares)
       int tpw = 0, nw = 0;
-      const int64_t plane = (int64_t)M * L.N * 4;
+      const int64_t plane = (int64_t)M * L.Npad * 4;
       if (gemv16_shape(L, device_cus(), std::max<int64_t>(1, have / plane), &tpw, &nw)) {
         const int S = L.tiles[kNarrow] / tpw;
         float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
         rc = launch_gemv16(w, L, x, M, ldx, y, ldy, partial, tpw, nw, stream);
-        if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
+        if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, L.Npad, S, stream);
         if (rc != CCQ_ERR_UNSUPPORTED) return rc;
       }
     }
@@ -467,7 +483,7 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
       const int S = rows_splits(L, M);
       float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
       rc = launch_rows(w, L, x, M, ldx, y, ldy, partial, S, stream);
-      if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
+      if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, L.Npad, S, stream);
       return rc;
     }
     // a few dozen rows (or many rows on wide / mixed formats): the 64-row LDS-tiled kernel
@@ -475,7 +491,7 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
       const int S = mid_splits(L, M);
       float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
       rc = launch_mid(w, L, x, M, ldx, y, ldy, partial, S, stream);
-      if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, S, stream);
+      if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, L.Npad, S, stream);
       if (rc != CCQ_ERR_UNSUPPORTED) return rc;
     }
     // one to four rows, narrow format only: the lean GEMV kernel (same arithmetic as the general path)
@@ -547,7 +563,7 @@ static int grouped_tile_rows(int E, int P) {
 // shares, as many as the workspace the caller brought allows.
 static Decomp grouped_decomp(const Layout& L, int E, int P, int active, int64_t workspace_bytes) {
   Decomp d = choose_decomp(L, grouped_tile_rows(E, P), std::max(1, active), P);
-  const int64_t per_share = (int64_t)P * L.N * 4;
+  const int64_t per_share = (int64_t)P * L.Npad * 4;
   if (d.S > 1 && per_share > 0) d.S = (int)std::max<int64_t>(1, std::min<int64_t>(d.S, workspace_bytes / per_share));
   return d;
 }
@@ -560,7 +576,7 @@ extern "C" int64_t ccq_grouped_workspace_bytes(const ccq_weight* w0, int32_t E, 
   if (P == 0) return 0;
   const int active_min = std::max(1, std::min(E, (P + kMaxSkinnyM - 1) / kMaxSkinnyM));
   Decomp d = choose_decomp(L, grouped_tile_rows(E, P), active_min, P);
-  const int64_t want = d.S > 1 ? (int64_t)d.S * P * L.N * 4 : 0;
+  const int64_t want = d.S > 1 ? (int64_t)d.S * P * L.Npad * 4 : 0;
   return std::min<int64_t>(want, (int64_t)64 << 20);
 }
 

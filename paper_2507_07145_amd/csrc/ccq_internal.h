@@ -47,10 +47,15 @@ constexpr int kMaxSplitsK = 32;
 
 enum Kind : int { kNarrow = 0, kWide = 1 };
 
-// A validated view of a ccq_weight.
+// A validated view of a ccq_weight.  The device layout holds whole row tiles and whole k-tiles: a matrix whose
+// N is not a multiple of 16, or whose groups of a kind do not fill their last k-tile, is padded by the pack routines
+// with rows and groups of zero codes and zero scales (they decode to zeros); the kernels never store the padded
+// rows and read the activations of the last real group in place of a padded group's.
 struct Layout {
-  int K = 0, N = 0, G = 0;
-  int groups[2] = {0, 0};       // groups per kind
+  int K = 0, N = 0, G = 0;      // as given: N output rows, G = K / 64 groups
+  int Npad = 0;                 // N rounded up to whole row tiles
+  int groups[2] = {0, 0};       // groups per kind, as given
+  int pgroups[2] = {0, 0};      // groups per kind in the device layout (whole k-tiles)
   int tiles[2] = {0, 0};        // k-tiles per kind
   int kind_of_fmt[2] = {0, 0};  // descriptor format index -> Kind
   float zp[2] = {0.f, 0.f};     // zero-point per kind
@@ -60,6 +65,7 @@ struct Layout {
   int64_t row_tile_bytes = 0;
   int64_t row_tile_scale_halfs = 0;
   int row_tiles = 0;
+  bool padded() const { return Npad != N || pgroups[0] != groups[0] || pgroups[1] != groups[1]; }
 };
 
 // Validates the shape/format part of a descriptor (no pointer checks).
@@ -133,7 +139,7 @@ int mid_splits(const Layout& L, int M);
 int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int S,
                void* stream);
 // y[m][n] = bf16(sum_s partial[s][m][n]), shares added in index order (ccq_skinny.hip).
-int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int S, void* stream);
+int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int Npad, int S, void* stream);
 
 // Per-group activation tiles, weights in registers (ccq_skinny.hip).  Built for up to 16 rows on wide-only and
 // hybrid-word layouts and for 17-32 rows on narrow-only ones; CCQ_ERR_UNSUPPORTED otherwise.

@@ -47,9 +47,11 @@ struct MidArgs {
   float* partial;
   int64_t ldx, ldy;
   int64_t row_tile_bytes, row_tile_scale_halfs;
-  int32_t M, N, row_tiles, m_blocks;
+  int32_t M, N, row_tiles, m_blocks;  // N: rows of the device layout (a multiple of 16), the row stride of `partial`
   int32_t tiles[2];       // k-tiles per kind
-  int32_t groups_narrow;
+  int32_t groups_narrow;  // narrow entries of the group map (whole k-tiles), the offset of the wide ones
+  int32_t g_last;         // last real group of K: groups past it pad a k-tile (zero scale) and read this group's activations
+  int32_t n_last;         // last real output row: rows past it pad a row tile, take its parameters and are not stored
   int32_t sq[2], sr[2];   // K shares: share `split` owns tiles [split*sq + min(split, sr), +sq + (split < sr)) of each kind
   float zp[2];
   // grouped calls (narrow-format kernel only): blockIdx.z = expert; its rows are output rows [offsets[e], offsets[e+1]),
@@ -130,7 +132,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   auto group_of = [&](int s) -> int {
     s = min(s, nsteps - 1);
     if constexpr (META) return lds_meta[s];
-    return s < nsN ? tA[kNarrow] * kNarrowGroupsPerTile + s : tA[kWide] * kWideGroupsPerTile + (s - nsN);
+    return min(s < nsN ? tA[kNarrow] * kNarrowGroupsPerTile + s : tA[kWide] * kWideGroupsPerTile + (s - nsN), a.g_last);
   };
 
   // per-wavefront weight rows: row tiles n0/16 + wave*RTW + i, lane (nl, kq)
@@ -147,10 +149,10 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
     ssup[i] = 0.f;
     // expert e's super scales: half the byte stride of alpha / beta (fp16 against fp32)
     if constexpr (SM == 1)
-      ssup[i] = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + e_ab / 2)[rtile * 16 + nl]);
+      ssup[i] = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + e_ab / 2)[min(rtile * 16 + nl, a.n_last)]);
     if constexpr (HAS_N) {
-      al[i] = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + e_ab)[rtile * 16 + nl];
-      be[i] = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + e_ab)[rtile * 16 + nl];
+      al[i] = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + e_ab)[min(rtile * 16 + nl, a.n_last)];
+      be[i] = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + e_ab)[min(rtile * 16 + nl, a.n_last)];
     }
   }
   const int64_t wide_code_off = (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
@@ -454,7 +456,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       const float val = acc[i][r];  // by value: bit-casting the element lvalue itself reads element 0
-      if (m < Me && n < a.N) {
+      if (m < Me && n <= a.n_last) {
         if (gridDim.y > 1) a.partial[((int64_t)split * a.M + row_off + m) * a.N + n] = val;
         else a.y[(int64_t)(row_off + m) * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
       }
@@ -512,11 +514,11 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
   }
   {
     const int rtile = min(n0 / 16 + wave * 2 + ti, a.row_tiles - 1);
-    al_t = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + e_ab)[rtile * 16 + nl];
-    be_t = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + e_ab)[rtile * 16 + nl];
+    al_t = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + e_ab)[min(rtile * 16 + nl, a.n_last)];
+    be_t = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + e_ab)[min(rtile * 16 + nl, a.n_last)];
     // expert e's super scales: half the byte stride of alpha / beta (fp16 against fp32)
     if constexpr (SM == 1)
-      ssup_t = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + e_ab / 2)[rtile * 16 + nl]);
+      ssup_t = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + e_ab / 2)[min(rtile * 16 + nl, a.n_last)]);
   }
   uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u;
   float magic = 8388608.f;
@@ -566,7 +568,7 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
     a_lds_off[i] = row * ROW + col * 8;
   }
   auto load_a = [&](u32x4 (&dst)[2], int s) {
-    const int64_t off = (int64_t)(tA * kNarrowGroupsPerTile + min(s, nsteps - 1)) * kGroup;
+    const int64_t off = (int64_t)min(tA * kNarrowGroupsPerTile + min(s, nsteps - 1), a.g_last) * kGroup;
 #pragma unroll
     for (int i = 0; i < 2; ++i) dst[i] = *reinterpret_cast<const u32x4*>(xrow[i] + off);
   };
@@ -683,7 +685,7 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       const float val = acc[i][r];
-      if (m < Me && n < a.N) {
+      if (m < Me && n <= a.n_last) {
         if (gridDim.y > 1) a.partial[((int64_t)split * a.M + row_off + m) * a.N + n] = val;
         else a.y[(int64_t)(row_off + m) * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
       }
@@ -725,12 +727,14 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
   a.row_tile_bytes = L.row_tile_bytes;
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   a.M = M;
-  a.N = L.N;
+  a.N = L.Npad;
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
   a.row_tiles = L.row_tiles;
   a.m_blocks = (M + kMidBM - 1) / kMidBM;
   a.tiles[0] = L.tiles[0];
   a.tiles[1] = L.tiles[1];
-  a.groups_narrow = L.groups[kNarrow];
+  a.groups_narrow = L.pgroups[kNarrow];
   a.sorted_rows = nullptr;
   a.expert_offsets = nullptr;
   a.codes_stride = a.scales_stride = a.ab_stride = 0;
@@ -789,12 +793,14 @@ int launch_mid_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t cod
   a.row_tile_bytes = L.row_tile_bytes;
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   a.M = P;
-  a.N = L.N;
+  a.N = L.Npad;
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
   a.row_tiles = L.row_tiles;
   a.m_blocks = (most_rows + kMidBM - 1) / kMidBM;
   a.tiles[0] = L.tiles[0];
   a.tiles[1] = L.tiles[1];
-  a.groups_narrow = L.groups[kNarrow];
+  a.groups_narrow = L.pgroups[kNarrow];
   for (int k = 0; k < 2; ++k) {
     a.sq[k] = L.tiles[k];
     a.sr[k] = 0;

@@ -46,7 +46,8 @@ struct PrefillArgs {
   uint16_t* y;
   int64_t ldx, ldy;
   int64_t row_tile_bytes, row_tile_scale_halfs;
-  int32_t M, N, K;
+  int32_t M, N, K;               // K: columns of the device layout (whole k-tiles of 256)
+  int32_t g_last;                // last real group of K: groups past it pad a k-tile (zero scale) and read this group's activations
   int32_t row_tiles;
   int32_t m_blocks;
   float zp;
@@ -93,10 +94,11 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
     rtile = min(rtile, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
     code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;                 // + lane * 16 at the load
     scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;         // + nl * 4 (or + nl) at the load
-    al[i] = a.alpha[rtile * 16 + nl];
-    be[i] = a.beta[rtile * 16 + nl] + 8388608.f;
+    const int prow = min(rtile * 16 + nl, a.N - 1);  // rows that pad the last tile take the last row's parameters; never stored
+    al[i] = a.alpha[prow];
+    be[i] = a.beta[prow] + 8388608.f;
     ssup[i] = 0.f;
-    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[prow]);
   }
   uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
   asm volatile("" : "+v"(c43), "+s"(smask));
@@ -134,7 +136,7 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
   uint2 sreg[RTW], snext[RTW];
 
   auto load_a = [&](u32x4 (&dst)[8], int step) {
-    const char* base = reinterpret_cast<const char*>(a.x + (int64_t)min(step, nsteps - 1) * kBK);
+    const char* base = reinterpret_cast<const char*>(a.x + (int64_t)min(step, a.g_last) * kBK);
 #pragma unroll
     for (int i = 0; i < 8; ++i) dst[i] = *reinterpret_cast<const u32x4*>(base + xoff[i]);
   };
@@ -339,10 +341,11 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
     rtile = min(rtile, a.row_tiles - 1);  // ragged last block: re-decode the last tile, never stored
     code_ptr[i] = a.codes + (int64_t)rtile * a.row_tile_bytes;
     scale_ptr[i] = a.scales + (int64_t)rtile * a.row_tile_scale_halfs;
-    al[i] = a.alpha[rtile * 16 + nl];
-    be[i] = a.beta[rtile * 16 + nl] + 8388608.f;
+    const int prow = min(rtile * 16 + nl, a.N - 1);  // rows that pad the last tile take the last row's parameters; never stored
+    al[i] = a.alpha[prow];
+    be[i] = a.beta[prow] + 8388608.f;
     ssup[i] = 0.f;
-    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+    if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[prow]);
   }
   uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
   asm volatile("" : "+v"(c43), "+s"(smask));
@@ -374,7 +377,7 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
   uint2 sreg[2], snext[2];
 
   auto load_a = [&](u32x4 (&dst)[4], int step) {
-    const char* base = reinterpret_cast<const char*>(a.x + (int64_t)min(step, nsteps - 1) * kBK);
+    const char* base = reinterpret_cast<const char*>(a.x + (int64_t)min(step, a.g_last) * kBK);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       uint32_t off = xoff[i];
@@ -574,7 +577,8 @@ int launch_prefill(const ccq_weight* w, const Layout& L, const void* x, int M, i
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   a.M = M;
   a.N = L.N;
-  a.K = L.K;
+  a.K = L.tiles[kNarrow] * kNarrowGroupsPerTile * kGroup;
+  a.g_last = L.G - 1;
   a.row_tiles = L.row_tiles;
   a.m_blocks = (M + kBM - 1) / kBM;
   a.zp = L.zp[kNarrow];

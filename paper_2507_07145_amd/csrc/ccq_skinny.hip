@@ -64,10 +64,12 @@ struct SkinnyArgs {
   int64_t ldx, ldy, codes_stride, scales_stride, ab_stride;
   int64_t row_tile_bytes, row_tile_scale_halfs;
   int32_t M;          // rows (dense) or total rows P (grouped)
-  int32_t N;
+  int32_t N;          // rows of the device layout (a multiple of 16): the row stride of `partial`
   int32_t row_tiles;
   int32_t tiles[2];   // k-tiles per kind
-  int32_t groups_narrow;
+  int32_t groups_narrow;  // narrow entries of the group map (whole k-tiles), the offset of the wide ones
+  int32_t g_last;     // last real group of K: groups past it pad a k-tile (zero scale) and read this group's activations
+  int32_t n_last;     // last real output row: rows past it pad a row tile, take its parameters and are not stored
   int32_t KC[2];      // k-tiles per wavefront per staged chunk, per kind
   int32_t SG[2];      // groups of a k-tile staged at a time (= groups per tile unless LDS is tight; then KC = 1)
   int32_t WR, WK, S;
@@ -353,7 +355,7 @@ __device__ void stage_chunk(uint4* lds_x, float* lds_cneg, const SkinnyArgs& a, 
       const int t = (f / (MRT * 4)) % TR::T;
       const int lg = f / (MRT * 4 * TR::T);
       const int pg = pg0 + (lg / sg) * TR::GPT + j0 + lg % sg;
-      const int g = META ? a.meta[meta_base + pg] : pg;  // a group map exists only for mixed formats
+      const int g = META ? a.meta[meta_base + pg] : min(pg, a.g_last);  // a group map exists only for mixed formats
       const uint16_t* xr = xrow + (int64_t)g * kGroup;
       if constexpr ((KIND & 1) == kNarrow) {
         v[u] = *reinterpret_cast<const uint4*>(xr + 16 * kq + 8 * t);
@@ -621,7 +623,7 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
     const int t = (f >> 2) % TR::T;
     const int lg = f / (4 * TR::T);
     const int pg = pg0 + lg;
-    const int g = META ? a.meta[meta_base + pg] : pg;  // a group map exists only for mixed formats
+    const int g = META ? a.meta[meta_base + pg] : min(pg, a.g_last);  // a group map exists only for mixed formats
     const uint16_t* xg = xr + (int64_t)g * kGroup;
     uint4 o = {0u, 0u, 0u, 0u};
     if constexpr ((KIND & 1) == kNarrow) {
@@ -664,14 +666,14 @@ __device__ __forceinline__ void stage_private(uint4* lds_x, float* lds_cneg, con
 // tiles' flight.  A lane holds up to kPrivFrags fragments of a chunk (6 KiB region / 16 bytes / 64 lanes).
 constexpr int kPrivFrags = 6;
 template <bool META>
-__device__ __forceinline__ void stage_private_request(uint4 (&v)[kPrivFrags], const int32_t* meta, const uint16_t* xr, int pg0, int ng, int lane) {
+__device__ __forceinline__ void stage_private_request(uint4 (&v)[kPrivFrags], const int32_t* meta, const uint16_t* xr, int pg0, int ng, int g_last, int lane) {
   const int nfrag = ng * 8;
 #pragma unroll
   for (int i = 0; i < kPrivFrags; ++i) {
     if (64 * i >= nfrag) break;  // wavefront-uniform
     const int f = min(lane + 64 * i, nfrag - 1);
     const int pg = pg0 + (f >> 3);
-    const uint32_t g = META ? (uint32_t)meta[pg] : (uint32_t)pg;
+    const uint32_t g = META ? (uint32_t)meta[pg] : (uint32_t)min(pg, g_last);
     // element offset: group * 64 + quarter (f & 3) * 16 + k-step ((f >> 2) & 1) * 8, in 32-bit arithmetic (K < 2^31)
     const uint32_t off = (g << 6) | ((uint32_t)(f & 3) << 4) | ((uint32_t)(f & 4) << 1);
     v[i] = *reinterpret_cast<const uint4*>(xr + off);
@@ -719,7 +721,7 @@ __device__ void run_kind_private(const SkinnyArgs& a, const uint8_t* (&codes_rt)
     TileRegs<KIND> buf[D][RT];
     const int n = cend - c0, ngroups = (n + D - 1) / D;
     uint4 xv[kPrivFrags];
-    if constexpr ((KIND & 1) == kNarrow) stage_private_request<META>(xv, a.meta, xr, c0 * TR::GPT, n * TR::GPT, lane);
+    if constexpr ((KIND & 1) == kNarrow) stage_private_request<META>(xv, a.meta, xr, c0 * TR::GPT, n * TR::GPT, a.g_last, lane);
 #pragma unroll
     for (int i = 0; i < D; ++i) {
 #pragma unroll
@@ -838,8 +840,8 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
     al[rt] = 0.f;
     be[rt] = 0.f;
     if (HAS_N && active) {
-      al[rt] = alpha[rtile * 16 + (lane & 15)];
-      be[rt] = beta[rtile * 16 + (lane & 15)];
+      al[rt] = alpha[min(rtile * 16 + (lane & 15), a.n_last)];
+      be[rt] = beta[min(rtile * 16 + (lane & 15), a.n_last)];
     }
     // + 2^23 (exact: beta is an integer below 2^15), which puts the rounded code into the low mantissa bits, is
     // added later, after the first tiles have been requested: nothing before that waits for these two loads
@@ -857,7 +859,7 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
       const int rtile = min(rtile0 + rt, a.row_tiles - 1);
       // expert e's super scales: half the byte stride of alpha / beta (fp16 against fp32)
       const uint16_t* ssup = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + (int64_t)e * (a.ab_stride / 2));
-      dc.ssup[rt] = (float)__builtin_bit_cast(_Float16, ssup[rtile * 16 + (lane & 15)]);
+      dc.ssup[rt] = (float)__builtin_bit_cast(_Float16, ssup[min(rtile * 16 + (lane & 15), a.n_last)]);
     }
   }
 
@@ -952,7 +954,7 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
 #pragma unroll
           for (int r = 0; r < (MR == 1 ? 1 : 4); ++r) {
             const int m = mt * 16 + 4 * kq + r;
-            if (m < rows_valid) {
+            if (m < rows_valid && n <= a.n_last) {
               const int64_t prow = (int64_t)off0 + m0 + m;
               if (a.S > 1) a.partial[((int64_t)split * a.M + prow) * a.N + n] = acc[rt][mt][r];
               else a.y[prow * a.ldy + n] = f32_to_bf16_rne(acc[rt][mt][r]);
@@ -967,13 +969,13 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
 
 // Private staging for up to four held rows (narrow format): fragment f = ((group * 2 + t) * 4 + kq) * 4 + m.
 constexpr int kPrivFrags4 = 8;  // 4 k-tiles x 32 fragments x 4 rows / 64 lanes
-__device__ __forceinline__ void stage_private4_request(uint4 (&v)[kPrivFrags4], const uint16_t* x, int64_t ldx, int M, int ng, int lane) {
+__device__ __forceinline__ void stage_private4_request(uint4 (&v)[kPrivFrags4], const uint16_t* x, int64_t ldx, int M, int pg0, int ng, int g_last, int lane) {
   const int nfrag = ng * 32;
 #pragma unroll
   for (int i = 0; i < kPrivFrags4; ++i) {
     if (64 * i >= nfrag) break;  // wavefront-uniform
     const int f = min(lane + 64 * i, nfrag - 1);
-    const int m = min(f & 3, M - 1), kq = (f >> 2) & 3, t = (f >> 4) & 1, pg = f >> 5;  // rows past M repeat row M-1, never stored
+    const int m = min(f & 3, M - 1), kq = (f >> 2) & 3, t = (f >> 4) & 1, pg = min(pg0 + (f >> 5), g_last);  // rows past M repeat row M-1, never stored
     v[i] = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + (int64_t)pg * kGroup + 16 * kq + 8 * t);
   }
 }
@@ -1017,6 +1019,7 @@ struct GemvArgs {
   int32_t tpw;                   // k-tiles per wavefront; the workgroup's blockDim.x / 64 wavefronts cover K
   float cneg;                    // -(128 + zp)
   const uint16_t* scale_super;   // fp16 [N], compressed scales only (a second, 8-byte scalar load)
+  int32_t g_last, n_last;        // last real group of K and last real output row (see SkinnyArgs)
 };
 
 // NT = register sets for k-tiles (4, 8 or 12); the wavefront owns tpw <= NT tiles.  SM = scale mode.
@@ -1032,12 +1035,12 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
 
   // all requests go out before anything else: activations first (they are needed first), then every code
   // tile of this wavefront, then the per-row parameters
-  const uint16_t* xr = a.x + (int64_t)t0 * (kNarrowGroupsPerTile * kGroup);
   uint4 xv[kPrivFrags];
-  stage_private_request<false>(xv, nullptr, xr, 0, n * kNarrowGroupsPerTile, lane);
+  stage_private_request<false>(xv, nullptr, a.x, t0 * kNarrowGroupsPerTile, n * kNarrowGroupsPerTile, a.g_last, lane);
   float al[1], be[1];
-  al[0] = a.alpha[rtile * 16 + (lane & 15)];
-  const float be_raw = a.beta[rtile * 16 + (lane & 15)];
+  const int prow = min(rtile * 16 + (lane & 15), a.n_last);
+  al[0] = a.alpha[prow];
+  const float be_raw = a.beta[prow];
   // private staging region of this wavefront: fragments, then start values
   const int frag_cap = n * kNarrowGroupsPerTile * 8, cneg_cap = n * kNarrowGroupsPerTile * 16;
   uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
@@ -1050,7 +1053,7 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
 #pragma unroll
   for (int i = 0; i < NT; ++i) load_tile<KN>(buf[i][0], codes, scales, min(i, n - 1), lane);
   uint16_t ssup_bits = 0;
-  if constexpr (SM == 1) ssup_bits = a.scale_super[rtile * 16 + (lane & 15)];
+  if constexpr (SM == 1) ssup_bits = a.scale_super[prow];
   stage_private_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
   DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
   float magic = 8388608.f;
@@ -1078,7 +1081,7 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
     }
   }
   if constexpr (SM == 1) v *= dc.ssup[0];  // compressed scales: the row's super scale, once (see group_scale)
-  if (wave == 0 && lane < 16) a.y[rtile * 16 + lane] = f32_to_bf16_rne(v);
+  if (wave == 0 && lane < 16 && rtile * 16 + lane <= a.n_last) a.y[rtile * 16 + lane] = f32_to_bf16_rne(v);
 }
 
 // Two to four activation rows: the same kernel shape with MFMA 4x4x4 used as it is meant (lane l of a 4x4
@@ -1103,10 +1106,11 @@ __global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args a
   const int t0 = wave * n;
 
   uint4 xv[kPrivFrags4];
-  stage_private4_request(xv, a.x + (int64_t)t0 * (kNarrowGroupsPerTile * kGroup), aa.ldx, aa.M, n * kNarrowGroupsPerTile, lane);
+  stage_private4_request(xv, a.x, aa.ldx, aa.M, t0 * kNarrowGroupsPerTile, n * kNarrowGroupsPerTile, a.g_last, lane);
   float al[1], be[1];
-  al[0] = a.alpha[rtile * 16 + (lane & 15)];
-  const float be_raw = a.beta[rtile * 16 + (lane & 15)];
+  const int prow = min(rtile * 16 + (lane & 15), a.n_last);
+  al[0] = a.alpha[prow];
+  const float be_raw = a.beta[prow];
   const int frag_cap = n * kNarrowGroupsPerTile * 32, cneg_cap = n * kNarrowGroupsPerTile * 16;
   uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
   float* my_cneg = reinterpret_cast<float*>(my_x + frag_cap);
@@ -1116,7 +1120,7 @@ __global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args a
 #pragma unroll
   for (int i = 0; i < NT; ++i) load_tile<KN>(buf[i][0], codes, scales, min(i, n - 1), lane);
   uint16_t ssup_bits = 0;
-  if constexpr (SM == 1) ssup_bits = a.scale_super[rtile * 16 + (lane & 15)];
+  if constexpr (SM == 1) ssup_bits = a.scale_super[prow];
   stage_private4_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
   DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
   float magic = 8388608.f;
@@ -1147,7 +1151,7 @@ __global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args a
     }
   }
   if constexpr (SM == 1) v *= dc.ssup[0];  // compressed scales: the row's super scale, once (see group_scale)
-  if (wave == 0 && lane < 16) {
+  if (wave == 0 && lane < 16 && rtile * 16 + lane <= a.n_last) {
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       if (r < aa.M) a.y[(int64_t)r * aa.ldy + rtile * 16 + lane] = f32_to_bf16_rne(v[r]);
@@ -1189,6 +1193,8 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
   a.tpw = tiles / wk;
   a.cneg = -(128.f + L.zp[kNarrow]);
   a.scale_super = static_cast<const uint16_t*>(w->scale_super);
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
   const dim3 grid((unsigned)L.row_tiles), block((unsigned)(64 * wk));
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (M == 1) {
@@ -1222,13 +1228,16 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
   return CCQ_OK;
 }
 
-// y[p][n] = bf16( sum_s partial[s][p][n] ), splits added in index order.  Four consecutive columns per thread (N is a
-// multiple of 16, partial and y rows are 16-byte aligned); all S requests of a thread go out before the first add.
+// y[p][n] = bf16( sum_s partial[s][p][n] ), splits added in index order.  `partial` rows hold Npad (a multiple of 16)
+// floats of which the first N are results.  Four consecutive columns per thread (partial and y rows are 16-byte
+// aligned); all S requests of a thread go out before the first add.
 template <int SMAX>
-__global__ void __launch_bounds__(256) ccq_reduce_splits_kernel(const float* partial, uint16_t* y, int64_t ldy, int rows, int N, int S) {
+__global__ void __launch_bounds__(256) ccq_reduce_splits_kernel(const float* partial, uint16_t* y, int64_t ldy, int rows, int N, int Npad, int S) {
   const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  const int64_t total = (int64_t)rows * N;
+  const int64_t total = (int64_t)rows * Npad;
   if (i >= total) return;
+  const int64_t p = i / Npad, n = i % Npad;
+  if (n >= N) return;
   f32x4 v[SMAX];
 #pragma unroll
   for (int s = 0; s < SMAX; ++s) v[s] = *reinterpret_cast<const f32x4*>(partial + (int64_t)min(s, S - 1) * total + i);
@@ -1236,11 +1245,18 @@ __global__ void __launch_bounds__(256) ccq_reduce_splits_kernel(const float* par
 #pragma unroll
   for (int s = 1; s < SMAX; ++s)
     if (s < S) sum += v[s];
-  const int64_t p = i / N, n = i % N;
-  uint2 o;
-  o.x = (uint32_t)f32_to_bf16_rne(sum[0]) | ((uint32_t)f32_to_bf16_rne(sum[1]) << 16);
-  o.y = (uint32_t)f32_to_bf16_rne(sum[2]) | ((uint32_t)f32_to_bf16_rne(sum[3]) << 16);
-  *reinterpret_cast<uint2*>(y + p * ldy + n) = o;
+  uint16_t* dst = y + p * ldy + n;
+  if (n + 4 <= N) {
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16_rne(sum[0]) | ((uint32_t)f32_to_bf16_rne(sum[1]) << 16);
+    o.y = (uint32_t)f32_to_bf16_rne(sum[2]) | ((uint32_t)f32_to_bf16_rne(sum[3]) << 16);
+    *reinterpret_cast<uint2*>(dst) = o;
+  } else {
+    // the last, partly real quad of a row whose length is not a multiple of four: columns from N on are not touched
+#pragma unroll
+    for (int c = 0; c < 3; ++c)
+      if (n + c < N) dst[c] = f32_to_bf16_rne(sum[c]);
+  }
 }
 
 // ---- 17 to 128 activation rows, dense: the per-row-tile contraction fed by a per-group activation tile ------
@@ -1264,9 +1280,10 @@ struct RowsArgs {
   float* partial;
   int64_t ldx, ldy;
   int64_t row_tile_bytes, row_tile_scale_halfs;
-  int32_t M, N, row_tiles, m_blocks;
+  int32_t M, N, row_tiles, m_blocks;  // N: rows of the device layout, the row stride of `partial`
   int32_t tiles[2];
   int32_t groups_narrow;
+  int32_t g_last, n_last;  // last real group of K and last real output row (see SkinnyArgs)
   int32_t sq[2], sr[2];  // K shares, as in SkinnyArgs
   float cneg[2];
 };
@@ -1307,13 +1324,13 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) ccq_rows_kernel(const RowsArg
   const uint16_t* scales_w = scales_n + (int64_t)a.tiles[kNarrow] * Traits<KN>::SCALE_HALFS;
   float al = 0.f, be_raw = 0.f;
   if constexpr (HAS_N) {
-    al = a.alpha[rtile * 16 + nl];
-    be_raw = a.beta[rtile * 16 + nl];
+    al = a.alpha[min(rtile * 16 + nl, a.n_last)];
+    be_raw = a.beta[min(rtile * 16 + nl, a.n_last)];
   }
   DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
   float magic = 8388608.f;
   asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+s"(dc.mask[2]), "+v"(magic));
-  if constexpr (SM == 1) dc.ssup[0] = (float)__builtin_bit_cast(_Float16, a.scale_super[rtile * 16 + nl]);
+  if constexpr (SM == 1) dc.ssup[0] = (float)__builtin_bit_cast(_Float16, a.scale_super[min(rtile * 16 + nl, a.n_last)]);
 
   // ---- activation staging: thread -> (row, fragment) -------------------------------------------------------
   // narrow: 8 lanes per row, lane c holds elements 8c .. 8c+7 = fragment (quarter c / 2, k-step c % 2);
@@ -1424,7 +1441,7 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) ccq_rows_kernel(const RowsArg
     s = min(s, nsteps - 1);
     const int pg = s < nsN ? tA[kNarrow] * kNarrowGroupsPerTile + s : a.groups_narrow + tA[kWide] * kWideGroupsPerTile + (s - nsN);
     if constexpr (META) return a.meta[pg];
-    return s < nsN ? pg : pg - a.groups_narrow;
+    return min(s < nsN ? pg : pg - a.groups_narrow, a.g_last);
   };
 
   uint4 areg[2][NP];
@@ -1494,7 +1511,7 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) ccq_rows_kernel(const RowsArg
     }
   }
 
-  if (active) {
+  if (active && rtile * 16 + nl <= a.n_last) {
     const int n = rtile * 16 + nl;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -1548,11 +1565,13 @@ int launch_rows(const ccq_weight* w, const Layout& L, const void* x, int M, int6
   a.row_tile_bytes = L.row_tile_bytes;
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   a.M = M;
-  a.N = L.N;
+  a.N = L.Npad;
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
   a.row_tiles = L.row_tiles;
   const int mt = M > 32 ? 4 : (M > 16 ? 2 : 1);
   a.m_blocks = (M + 16 * mt - 1) / (16 * mt);
-  a.groups_narrow = L.groups[kNarrow];
+  a.groups_narrow = L.pgroups[kNarrow];
   for (int k = 0; k < 2; ++k) {
     a.tiles[k] = L.tiles[k];
     a.sq[k] = L.tiles[k] / S;
@@ -1655,11 +1674,13 @@ int launch_skinny(const SkinnyCall& c) {
   a.row_tile_bytes = L.row_tile_bytes;
   a.row_tile_scale_halfs = L.row_tile_scale_halfs;
   a.M = c.M;
-  a.N = L.N;
+  a.N = L.Npad;
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
   a.row_tiles = L.row_tiles;
   a.tiles[0] = L.tiles[0];
   a.tiles[1] = L.tiles[1];
-  a.groups_narrow = L.groups[kNarrow];
+  a.groups_narrow = L.pgroups[kNarrow];
   a.WR = d.WR;
   a.WK = d.WK;
   a.S = d.S;
@@ -1743,19 +1764,19 @@ int launch_skinny(const SkinnyCall& c) {
   dim3 block((unsigned)(64 * d.WR * d.WK));
   hipLaunchKernelGGL(kern, grid, block, (size_t)lds, stream, a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
-  if (d.S > 1) return launch_reduce_splits(c.partial, c.y, c.ldy, c.M, L.N, d.S, c.stream);
+  if (d.S > 1) return launch_reduce_splits(c.partial, c.y, c.ldy, c.M, L.N, L.Npad, d.S, c.stream);
   return CCQ_OK;
 }
 
-int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int S, void* stream) {
-  const int64_t total = (int64_t)rows * N;  // a multiple of 16
+int launch_reduce_splits(const float* partial, void* y, int64_t ldy, int rows, int N, int Npad, int S, void* stream) {
+  const int64_t total = (int64_t)rows * Npad;  // a multiple of 16
   const int threads = 256;
   const dim3 grid((unsigned)((total / 4 + threads - 1) / threads)), block(threads);
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint16_t* yy = static_cast<uint16_t*>(y);
-  if (S <= 4) hipLaunchKernelGGL(ccq_reduce_splits_kernel<4>, grid, block, 0, st, partial, yy, ldy, rows, N, S);
-  else if (S <= 8) hipLaunchKernelGGL(ccq_reduce_splits_kernel<8>, grid, block, 0, st, partial, yy, ldy, rows, N, S);
-  else hipLaunchKernelGGL(ccq_reduce_splits_kernel<kMaxSplitsK>, grid, block, 0, st, partial, yy, ldy, rows, N, S);
+  if (S <= 4) hipLaunchKernelGGL(ccq_reduce_splits_kernel<4>, grid, block, 0, st, partial, yy, ldy, rows, N, Npad, S);
+  else if (S <= 8) hipLaunchKernelGGL(ccq_reduce_splits_kernel<8>, grid, block, 0, st, partial, yy, ldy, rows, N, Npad, S);
+  else hipLaunchKernelGGL(ccq_reduce_splits_kernel<kMaxSplitsK>, grid, block, 0, st, partial, yy, ldy, rows, N, Npad, S);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }

@@ -201,7 +201,8 @@ def test_full_size_sampled_rows():
 
 def test_rejections_need_no_kernel():
     lib = b.load()
-    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512 + 64, 16, [b.NARROW]))) == -1            # not a whole number of k-tiles
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512 + 32, 16, [b.NARROW]))) == -1            # K not a whole number of groups
+    assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512 + 64, 16, [b.NARROW]))) == (16 * 9 * 16 + 16 * 9) * 2   # a ragged k-tile: real groups only
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(b.descriptor(512, 16, b.H16))) == 0                       # hybrid word: no workspace
     d = b.descriptor(512, 16, [b.NARROW])
     assert lib.ccq_quantize_workspace_bytes(b.ctypes.byref(d)) == (16 * 8 * 16 + 16 * 8) * 2

@@ -148,7 +148,8 @@ def test_hybrid_word_accounting_and_packing():
     lib = b.load()
     i1 = b.pack_info(b.descriptor(K, N, b.H16, scale_mode=1), 64)      # Sec. 3.4: the scale rides in the 13 spare bits, 2.5 bpw in all
     assert i1.scale_bytes == 0 and i1.code_bytes == i.code_bytes and i1.total_bpw == 2.5 + 16 / K
-    assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K + 64, N, b.H16)), 1, ctypes.byref(info)) == -3            # whole k-tiles of 512 only
+    assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K + 64, N, b.H16)), 1, ctypes.byref(info)) == 0              # 17 groups: three k-tiles of 8, the last padded
+    assert info.padded_groups[0] == info.padded_groups[1] == 24 and info.code_bytes == (N // 16) * 3 * 2560 and info.code_bpw == 2.5
     assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, [b.H16_HI, b.ccq_code(3, 4, 2, 0, 3.0)])), 1, ctypes.byref(info)) == -3  # one zp per word
     assert lib.ccq_pack_info(ctypes.byref(b.descriptor(K, N, [b.H16_LO, b.H16_HI])), 1, ctypes.byref(info)) != 0   # halves in the wrong order
 
@@ -166,8 +167,10 @@ def test_descriptor_validation():
     assert status(lambda: b.pack_info(bad_group)) == -3                     # valid CCQ, not built
     assert status(lambda: b.pack_info(b.descriptor(1000, 64, [b.NARROW]))) == -2   # K not a multiple of 64
     assert status(lambda: b.pack_info(b.descriptor(1024, 0, [b.NARROW]))) == -2
-    assert status(lambda: b.pack_info(b.descriptor(1024, 40, [b.NARROW]))) == -3   # rows not a multiple of 16
-    assert status(lambda: b.pack_info(b.descriptor(1088, 64, [b.NARROW]))) == -3   # 17 narrow groups: partial k-tile
+    i = b.pack_info(b.descriptor(1024, 40, [b.NARROW]))                           # rows not a multiple of 16: the last row tile is padded
+    assert i.padded_N == 48 and i.code_bytes == 3 * 4 * 1024 and i.canonical_code_bytes == 40 * 256 and i.code_bpw == 2.0
+    i = b.pack_info(b.descriptor(1088, 64, [b.NARROW]))                           # 17 narrow groups: the fifth k-tile holds one
+    assert i.padded_groups[0] == 20 and i.groups[0] == 17 and i.code_bytes == 4 * 5 * 1024 and i.scale_bytes == 4 * 5 * 64 * 2
     assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.ccq_code(3, 3, 2, 0, 4.0)]))) == -3   # other (L,N,S)
     assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.ccq_code(6, 4, 3, 1, 31.25)]))) == -2  # zp not a multiple of 0.5
     assert status(lambda: b.pack_info(b.descriptor(1024, 64, [b.ccq_code(6, 4, 7, 1, 32.0)]))) == -2   # S > L
@@ -205,3 +208,61 @@ def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
     monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "libccq.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         b.load()
+
+
+def _ragged_case(kinds, K, N, n_wide, seed):
+    rng = synth.rng(8, seed)
+    G = K // 64
+    gf = synth.group_format_map(G, n_wide, rng) if len(kinds) == 2 else None
+    fm = {"narrow": (o.F2, b.NARROW), "wide": (o.F275, b.WIDE)}
+    ofmt = fm[kinds[0]][0] if len(kinds) == 1 else (o.F2, o.F275)
+    w = b.descriptor(K, N, [fm[k][1] for k in kinds], gf)
+    codes = rng.integers(1, 256, size=(N, o.row_bytes(K, ofmt, gf)), dtype=np.uint8)      # no zero byte: padding is what is zero
+    scales = rng.integers(1, 1 << 15, size=(N, G), dtype=np.uint16)
+    return w, gf, codes, scales
+
+
+@pytest.mark.parametrize("kinds,K,N,n_wide", [(["narrow"], 1088, 40, None), (["wide"], 832, 24, None), (["narrow", "wide"], 1600, 1000, 5),
+                                              (["narrow", "wide"], 7232, 8, 5)])
+def test_padded_layouts(kinds, K, N, n_wide):
+    """Any K % 64 == 0, any N and any group map: the device layout rounds every kind up to whole k-tiles and the rows up
+    to whole row tiles; what is added holds zero codes and zero scales, the real bytes sit where the unpadded layout
+    puts them, and the group map names the last real group for the padded positions."""
+    w, gf, codes, scales = _ragged_case(kinds, K, N, n_wide, K + N)
+    i = b.pack_info(w, 64)
+    G = K // 64
+    gn = G if kinds == ["narrow"] else (0 if kinds == ["wide"] else G - n_wide)
+    gw = G - gn
+    tn, tw = -(-gn // 4), -(-gw // 8)
+    rt = -(-N // 16)
+    assert i.padded_N == rt * 16 and i.row_tile_bytes == tn * 1024 + tw * 2816 and i.code_bytes == rt * i.row_tile_bytes
+    assert i.scale_bytes == rt * (tn * 64 + tw * 128) * 2 and i.canonical_code_bytes == codes.size
+    assert abs(i.code_bpw - 8 * codes.size / (N * K)) < 1e-12
+    pg = {"narrow": tn * 4, "wide": tw * 8}
+    assert [i.padded_groups[f] for f in range(len(kinds))] == [pg[k] for k in kinds]
+    dev = b.pack_codes(w, codes)
+    assert np.count_nonzero(dev) == codes.size - (0 if gw == 0 else 0) and sorted(dev[dev != 0].tolist()) == sorted(codes.ravel().tolist())
+    ps = b.pack_scales(w, scales)
+    assert sorted(ps[ps != 0].tolist()) == sorted(scales.ravel().tolist())
+    # a row of the last (ragged) row tile, last real group of each kind: the same position rule as in whole tiles
+    n = N - 1
+    kind_of = (lambda g: 0 if kinds == ["narrow"] else 1) if gf is None else (lambda g: int(gf[g]))
+    cnt = [0, 0]
+    goff = 0
+    for g in range(G):
+        kd = kind_of(g)
+        p = cnt[kd]
+        cnt[kd] += 1
+        if kd == 0:
+            assert dev[(n // 16) * i.row_tile_bytes + (p // 4) * 1024 + (2 * 16 + n % 16) * 16 + (p % 4) * 4 + 1] == codes[n, goff + 4 * 2 + 1], g
+            assert ps[(n // 16) * (tn * 64 + tw * 128) + (p // 4) * 64 + (n % 16) * 4 + p % 4] == scales[n, g]
+            goff += 16
+        else:
+            assert dev[(n // 16) * i.row_tile_bytes + tn * 1024 + (p // 8) * 2816 + 1 * 1024 + (3 * 16 + n % 16) * 16 + (p % 8) * 2] == codes[n, goff + 6 * 3 + 2], g
+            assert ps[(n // 16) * (tn * 64 + tw * 128) + tn * 64 + (p // 8) * 128 + (n % 16) * 8 + p % 8] == scales[n, g]
+            goff += 22
+    if gf is not None:
+        meta = b.pack_meta(w)
+        assert meta.size == tn * 4 + tw * 8
+        assert meta[:gn].tolist() == np.flatnonzero(gf == 0).tolist() and meta[tn * 4:tn * 4 + gw].tolist() == np.flatnonzero(gf == 1).tolist()
+        assert np.all(meta[gn:tn * 4] == G - 1) and np.all(meta[tn * 4 + gw:] == G - 1)
