@@ -37,8 +37,8 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the GEMV kernel, read from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a plain
 # copy of known size; a constant taken from the named profile, not a measurement of the run that prints it
-TRAFFIC_BYTES_PER_LAUNCH = int(9407.26 * 1024 * 2.0 + 16.0 * 1024)
-TRAFFIC_SOURCE = "profiles/gemv_narrow_config2_hbm_traffic.txt (FETCH_SIZE 9407.26 KiB x 2.0 + WRITE_SIZE 16.0 KiB x 1.0)"
+TRAFFIC_BYTES_PER_LAUNCH = int(9375.51 * 1024 * 2.0 + 16.0 * 1024)
+TRAFFIC_SOURCE = "profiles/gemv_config2_hbm_traffic.txt (FETCH_SIZE 9375.51 KiB x 2.0 + WRITE_SIZE 16.0 KiB x 1.0)"
 ALL_LEGS = ("headline", "more_rows", "compressed", "config3", "config4", "prefill", "ceilings", "cpu")
 SETTLE_MS = 20.0                # load the clock needs before it has settled
 
@@ -495,7 +495,7 @@ def main() -> int:
                                "synchronize, which weigh on a short timed region); roofline.achieved uses the HIP events of the same repetition"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH, "traffic_source": TRAFFIC_SOURCE,
-                     "kernel": "ccq_gemv_narrow_kernel", "us_per_launch": round(per_launch_s * 1e6, 3)},
+                     "kernel": "ccq::gemv::kernel<1, 2, 0>", "us_per_launch": round(per_launch_s * 1e6, 3)},
     }
 
     if "more_rows" in legs:
