@@ -25,6 +25,7 @@
 #include <algorithm>
 #include <type_traits>
 
+#include "ccq_decode.h"
 #include "ccq_internal.h"
 
 namespace ccq {
@@ -157,9 +158,9 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   }
   const int64_t wide_code_off = (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
   const int64_t wide_scale_off = (int64_t)a.tiles[kNarrow] * kNarrowTileScaleHalfs;
-  uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u, mask_w = H16 ? 0x00070000u : 0x000F0000u;
+  uint32_t c43 = 0x43000000u, mask2 = kDecMask2, base2 = kDecBase2, mask_w = H16 ? 0x00070000u : 0x000F0000u;
   float magic = 8388608.f;
-  asm volatile("" : "+v"(c43), "+s"(mask_n), "+s"(mask_w), "+v"(magic));
+  asm volatile("" : "+v"(c43), "+s"(mask2), "+v"(base2), "+s"(mask_w), "+v"(magic));
 
   // code tiles in registers: the one being decoded and the next one of the same kind
   u32x4 cn[kMidRTW], cn_next[kMidRTW];
@@ -253,20 +254,10 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
       } else {
         s = (float)((sn[i].x >> (4 * j)) & 0xFu) * ssup[i];  // (s_q >> s_shift) & s_mask times s_super: exact
       }
-      const float c0 = -(128.f + a.zp[kNarrow]) * s;  // exact: 8-bit times at most 15-bit significand
-      const float bem = be[i] + magic;                 // + 2^23: exact, beta is an integer below 2^15
+      const float c0 = -(kDecBase + a.zp[kNarrow]) * s;  // exact: 8-bit times at most 15-bit significand
+      const float bem = be[i] + magic;                    // + 2^23: exact, beta is an integer below 2^15
       uint32_t o[8];
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], bem);
-        const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code (Alg. 3)
-        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 7, mask_n, c43)), s, c0);
-        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 10, mask_n, c43)), s, c0);
-        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 13, mask_n, c43)), s, c0);
-        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 16, mask_n, c43)), s, c0);
-        o[2 * b] = pack_bf16_m(w0, w1);
-        o[2 * b + 1] = pack_bf16_m(w2, w3);
-      }
+      decode16_narrow(d, al[i], bem, s, c0, mask2, base2, o);
       uint16_t* p = dst + ((wave * kMidRTW + i) * 16 + nl) * ROW + kq * 16;
       *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
       *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
@@ -520,9 +511,9 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
     if constexpr (SM == 1)
       ssup_t = (float)__builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + e_ab / 2)[min(rtile * 16 + nl, a.n_last)]);
   }
-  uint32_t c43 = 0x43000000u, mask_n = 0x003F0000u;
+  uint32_t mask2 = kDecMask2, base2 = kDecBase2;
   float magic = 8388608.f;
-  asm volatile("" : "+v"(c43), "+s"(mask_n), "+v"(magic));
+  asm volatile("" : "+s"(mask2), "+v"(base2), "+v"(magic));
 
   // raw code tiles as loaded (lane = row nl, quarter lane / 16, both row tiles), and the exchanged ones (this lane's
   // column: ex[q] = the four groups' dwords of quarter 2h + q)
@@ -587,23 +578,13 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
     } else {
       s = (float)((s_t.x >> (4 * j)) & 0xFu) * ssup_t;
     }
-    const float c0 = -(128.f + a.zp[kNarrow]) * s;
+    const float c0 = -(kDecBase + a.zp[kNarrow]) * s;
     const float bem = be_t + magic;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const uint32_t d = dword_sel(ex[q], j);
       uint32_t o[8];
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al_t, bem);
-        const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code (Alg. 3)
-        const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 7, mask_n, c43)), s, c0);
-        const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 10, mask_n, c43)), s, c0);
-        const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 13, mask_n, c43)), s, c0);
-        const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(cb << 16, mask_n, c43)), s, c0);
-        o[2 * b] = pack_bf16_m(w0, w1);
-        o[2 * b + 1] = pack_bf16_m(w2, w3);
-      }
+      decode16_narrow(d, al_t, bem, s, c0, mask2, base2, o);
       bf[2 * q] = u32x4{o[0], o[1], o[2], o[3]};
       bf[2 * q + 1] = u32x4{o[4], o[5], o[6], o[7]};
     }

@@ -8,10 +8,10 @@
 //   - decodes the BN x 64 weight tile to bf16 in LDS: the stored byte q becomes
 //     the 15-bit code c = round(q*alpha + beta) (Alg. 3) with one FMA against
 //     beta + 2^23, the four states are cut out by the shift list [9,6,3,0] and mask
-//     0x3F (Table 1) directly into the mantissa of fp32 128.0, and one FMA applies
-//     d = (w_uint - zp) * s (Alg. 3, last line): fma(128 + state, s, -(128 + zp) s)
-//     is exact in fp32, so the value written is the correctly rounded bf16 of the
-//     exact weight,
+//     0x3F (Table 1), two codes at a time, into the mantissas of two fp16 64.0, and
+//     one mixed-precision FMA applies d = (w_uint - zp) * s (Alg. 3, last line):
+//     fma(64 + state, s, -(64 + zp) s) is exact in fp32, so the value written is the
+//     correctly rounded bf16 of the exact weight (decode16_narrow, ccq_decode.h),
 //   - multiplies the two tiles with MFMA 32x32x16 bf16 (fp32 accumulators).
 // LDS tiles are double buffered; rows are padded by 16 bytes so that operand
 // reads (16 bytes per lane, 32 consecutive rows) spread over all banks.
@@ -26,6 +26,7 @@
 
 #include <type_traits>
 
+#include "ccq_decode.h"
 #include "ccq_internal.h"
 
 namespace ccq {
@@ -100,9 +101,9 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
     ssup[i] = 0.f;
     if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[prow]);
   }
-  uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
-  asm volatile("" : "+v"(c43), "+s"(smask));
-  const float neg_off = -(128.f + a.zp);
+  uint32_t base2 = kDecBase2, mask2 = kDecMask2;
+  asm volatile("" : "+v"(base2), "+s"(mask2));
+  const float neg_off = -(kDecBase + a.zp);
   const uint32_t lane_code_off = lane * 16, lane_scale_off = nl * 4;
 
   // activation copy: 8 chunks of 16 bytes per thread and step; rows past M re-read row M-1 (their
@@ -165,19 +166,9 @@ __global__ void __launch_bounds__(256) ccq_prefill_kernel(const PrefillArgs a) {
     } else {
       s = (float)((sreg[i].x >> (4 * j)) & 0xFu) * ssup[i];  // (s_q >> s_shift) & s_mask times s_super (Alg. 3): exact
     }
-    const float c0 = neg_off * s;  // exact: 8-bit times 11-bit significand
+    const float c0 = neg_off * s;  // exact: 8-bit times at most 15-bit significand
     uint32_t o[8];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], be[i]);
-      const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code
-      const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, smask, c43)), s, c0);
-      const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, smask, c43)), s, c0);
-      const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, smask, c43)), s, c0);
-      const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, smask, c43)), s, c0);
-      o[2 * b] = pack_bf16(w0, w1);
-      o[2 * b + 1] = pack_bf16(w2, w3);
-    }
+    decode16_narrow(d, al[i], be[i], s, c0, mask2, base2, o);
     uint16_t* p = dst + ((wave * RTW + i) * 16 + nl) * kLdsRow + kq * 16;
     *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
     *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
@@ -347,9 +338,9 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
     ssup[i] = 0.f;
     if constexpr (SM == 1) ssup[i] = (float)__builtin_bit_cast(_Float16, a.scale_super[prow]);
   }
-  uint32_t c43 = 0x43000000u, smask = 0x003F0000u;
-  asm volatile("" : "+v"(c43), "+s"(smask));
-  const float neg_off = -(128.f + a.zp);
+  uint32_t base2 = kDecBase2, mask2 = kDecMask2;
+  asm volatile("" : "+v"(base2), "+s"(mask2));
+  const float neg_off = -(kDecBase + a.zp);
   const uint32_t lane_code_off = lane * 16, lane_scale_off = nl * 4;
 
   // activation copy: 4 chunks of 16 bytes per thread and step (rows past M re-read row M-1)
@@ -411,19 +402,9 @@ __global__ void __launch_bounds__(512) ccq_prefill8_kernel(const PrefillArgs a) 
     } else {
       s = (float)((sreg[i].x >> (4 * j)) & 0xFu) * ssup[i];
     }
-    const float c0 = neg_off * s;  // exact: 8-bit times 11-bit significand
+    const float c0 = neg_off * s;  // exact: 8-bit times at most 15-bit significand
     uint32_t o[8];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const float f = __builtin_fmaf((float)((d >> (8 * b)) & 0xFFu), al[i], be[i]);
-      const uint32_t cb = __builtin_bit_cast(uint32_t, f);  // 0x4B000000 | 15-bit code
-      const float w0 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 7, smask, c43)), s, c0);
-      const float w1 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 10, smask, c43)), s, c0);
-      const float w2 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 13, smask, c43)), s, c0);
-      const float w3 = __builtin_fmaf(__builtin_bit_cast(float, and_or_p(cb << 16, smask, c43)), s, c0);
-      o[2 * b] = pack_bf16(w0, w1);
-      o[2 * b + 1] = pack_bf16(w2, w3);
-    }
+    decode16_narrow(d, al[i], be[i], s, c0, mask2, base2, o);
     uint16_t* p = dst + (tile_in_block[i] * 16 + nl) * kLdsRow + kq * 16;
     *reinterpret_cast<u32x4*>(p) = u32x4{o[0], o[1], o[2], o[3]};
     *reinterpret_cast<u32x4*>(p + 8) = u32x4{o[4], o[5], o[6], o[7]};
