@@ -245,6 +245,260 @@ __global__ void __launch_bounds__(1024) kernel(const Args a) {
   }
 }
 
+// ---- one activation row on wide-format and mixed-format weights ----------------------------------------------------
+// The same kernel shape for the (L=4,N=3,S=2) code of Table 1 (Alg. 2) and for a per-group mix of the two formats
+// (Sec. 3.3, "Hybrid Bits Mix"): a workgroup owns one row tile and all of K; its first WN wavefronts take shares of
+// TPWN narrow k-tiles each, the other WW shares of TPWW wide k-tiles (8 groups of 64 weights, 2816 bytes: three
+// 16-byte segments per lane).  With a mix the original group of a packed group (the activation columns to read) comes
+// from the group map, which costs one more dependent request at the start.
+//   wide decode: lane (row n, quarter kq) holds bytes 6 kq + 2 t, 6 kq + 2 t + 1 of the group in segment t = 0, 1, 2:
+//   two 8-bit codes, each three 4-bit states at the shifts [4, 2, 0] with mask 0xF (Table 1); both codes go into one
+//   register {0, b, 0, a} and one shift + one and-or cut the same window out of both: bf16 integers 128 + state in
+//   k-slots {0,3}, {1,4}, {2,5} of k-step t; slots 6 and 7 are unused and meet zero activations.  Quarter 3 owns
+//   bytes 18..21 only: its k-step 1 holds weights {60, 63, 61, -, 62, -} and its k-step 2 nothing (zero activations).
+//   With compressed scales (Sec. 3.4) the 4-bit field of a wide group is the low nibble of its byte 21, which the
+//   quarter-3 lane of the row holds in segment 1: the other lanes of the row fetch it with ds_bpermute.
+struct ArgsNW {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const uint16_t* x;
+  uint16_t* y;
+  const uint16_t* scale_super;   // fp16 [N], compressed scales only
+  const int32_t* meta;           // original group of every packed group (narrow first), or NULL: a single format
+  int64_t row_tile_bytes, row_tile_scale_halfs;
+  int32_t tiles_n, tiles_w;      // k-tiles per row tile of each format
+  int32_t waves_n;               // wavefronts with narrow shares (the first ones)
+  int32_t meta_wide;             // entries of the group map that precede the wide groups (narrow groups in whole k-tiles)
+  float cneg_n, cneg_w;          // -(128 + zp) per format
+  int32_t g_last, n_last;        // last real group of K, last real output row (see Args)
+};
+
+__device__ __forceinline__ u32x4 load_chunk16(const uint16_t* p) {   // 16 bytes at 4-byte alignment
+  struct __attribute__((packed, aligned(4))) Chunk16 { uint32_t x, y, z, w; };
+  const Chunk16 c = *reinterpret_cast<const Chunk16*>(p);
+  return u32x4{c.x, c.y, c.z, c.w};
+}
+// Activation fragment of (quarter kq, k-step t) of a wide group from the 16-byte chunk that starts at element
+// min(18 kq + 6 t, 56): k-slots {0, 3, 1, 4, 2, 5, -, -}.
+__device__ __forceinline__ u32x4 wide_frag(const u32x4 v, uint32_t kq, int t) {
+  u32x4 o = {0u, 0u, 0u, 0u};
+  if (kq < 3u || t == 0) {
+    o.x = __builtin_amdgcn_perm(v.y, v.x, 0x07060100u);  // elements 0, 3
+    o.y = __builtin_amdgcn_perm(v.z, v.x, 0x05040302u);  // 1, 4
+    o.z = __builtin_amdgcn_perm(v.z, v.y, 0x07060100u);  // 2, 5
+  } else if (t == 1) {                                    // the chunk starts at 56: weights 60, 63 | 61 | 62
+    o.x = __builtin_amdgcn_perm(v.w, v.z, 0x07060100u);
+    o.y = v.z >> 16;
+    o.z = v.w & 0xFFFFu;
+  }
+  return o;
+}
+
+template <int TPWN, int TPWW, int SM>
+__global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
+  constexpr int NGN = TPWN * 4, NGW = TPWW * 8;                 // groups per narrow / wide share
+  constexpr int REGION_N = NGN * 8 * 16 + NGN * 4 * 16;         // private LDS bytes per wavefront: fragments, then start-value records
+  constexpr int REGION_W = NGW * 12 * 16 + NGW * 4 * 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t nwaves = blockDim.x >> 6;
+  const uint32_t n = lane & 15u, kq = lane >> 4;
+  const uint32_t rtile = blockIdx.x;
+  const uint32_t row = min(rtile * 16u + n, (uint32_t)a.n_last);
+  // private regions: the narrow shares' first, then the wide shares'
+  const uint32_t wn = TPWN > 0 ? (uint32_t)a.waves_n : 0u;
+  unsigned char* region = smem + (wave < wn ? (size_t)wave * REGION_N : (size_t)wn * REGION_N + (size_t)(wave - wn) * REGION_W);
+  u32x4* lds_x = reinterpret_cast<u32x4*>(region);
+  const uint8_t* code_row = a.codes + (size_t)rtile * (size_t)a.row_tile_bytes;
+  const uint16_t* scale_row = a.scales + (size_t)rtile * (size_t)a.row_tile_scale_halfs;
+  uint32_t c4300 = 0x43004300u, mask_n = 0x003F003Fu, mask_w = 0x000F000Fu;
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(c4300), "+s"(mask_n), "+s"(mask_w), "+v"(magic));   // register values, not literals: v_and_or_b32 gets selected
+  uint32_t ssup = 0;
+  float acc = 0.f;
+
+  if (TPWN > 0 && wave < wn) {
+    // ------------------------------------------------------------------ a share of narrow k-tiles (as in `kernel`)
+    constexpr int NF = (NGN * 8 + 63) / 64;
+    constexpr int SH = SM == 0 ? 64 : 16;
+    const uint32_t t0 = wave * TPWN;
+    u32x4 xv[NF > 0 ? NF : 1];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+      uint32_t f = lane + 64u * i;
+      if (NGN * 8 % 64 != 0) f = min(f, (uint32_t)(NGN * 8 - 1));
+      const uint32_t pg = t0 * 4u + (f >> 3);
+      const uint32_t g = a.meta ? (uint32_t)a.meta[pg] : min(pg, (uint32_t)a.g_last);
+      const uint32_t off = (g << 6) | ((f & 3u) << 4) | ((f & 4u) << 1);
+      xv[i] = *reinterpret_cast<const u32x4*>(a.x + off);
+    }
+    const float al = a.alpha[row];
+    const float be_raw = a.beta[row];
+    if constexpr (SM == 1) ssup = a.scale_super[row];
+    u32x4 cw[TPWN > 0 ? TPWN : 1];
+    uint32_t sw[TPWN > 0 ? TPWN : 1][SM == 0 ? 2 : 1];
+#pragma unroll
+    for (int i = 0; i < TPWN; ++i) {
+      const uint16_t* sb = scale_row + (size_t)t0 * SH;
+      if constexpr (SM == 0) {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+        sw[i][0] = v.x;
+        sw[i][1] = v.y;
+      } else {
+        sw[i][0] = sb[i * 16u + n];
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < TPWN; ++i) cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_row + (size_t)(t0 + i) * 1024u + lane * 16u));
+    __builtin_amdgcn_sched_barrier(0);
+    float* lds_c = reinterpret_cast<float*>(region + NGN * 8 * 16);
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+      const uint32_t f = lane + 64u * i;
+      u32x4 o;
+      o.x = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x05040100u);
+      o.y = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x07060302u);
+      o.z = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x05040100u);
+      o.w = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x07060302u);
+      float s = frag_sum(o);
+      s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x104, 0xF, 0xF, true));  // + the other k-step, 4 lanes up
+      if (NGN * 8 % 64 == 0 || f < (uint32_t)(NGN * 8)) {
+        lds_x[f] = o;
+        if ((f & 4u) == 0) lds_c[((f >> 3) * 4u + (f & 3u)) * 4u] = a.cneg_n * s;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const float be = be_raw + magic;   // + 2^23: exact, beta is an integer below 2^15
+#pragma unroll
+    for (int i = 0; i < TPWN; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int lg = i * 4 + j;
+        const u32x4 x0 = lds_x[(lg * 2 + 0) * 4 + kq];
+        const u32x4 x1 = lds_x[(lg * 2 + 1) * 4 + kq];
+        const f32x4 cin = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+        u32x4 w[2];
+        const uint32_t d = j == 0 ? cw[i].x : (j == 1 ? cw[i].y : (j == 2 ? cw[i].z : cw[i].w));
+        decode_dword(d, al, be, c4300, mask_n, w);
+        f32x4 p = cin;
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.x, x0.y}), __builtin_bit_cast(bf16x4, u32x2{w[0].x, w[0].y}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.z, x0.w}), __builtin_bit_cast(bf16x4, u32x2{w[0].z, w[0].w}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.x, x1.y}), __builtin_bit_cast(bf16x4, u32x2{w[1].x, w[1].y}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.z, x1.w}), __builtin_bit_cast(bf16x4, u32x2{w[1].z, w[1].w}), p, 0, 0, 0);
+        float s;
+        if constexpr (SM == 0) {
+          const uint32_t sd = sw[i][j >> 1];
+          s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else {
+          s = (float)((sw[i][0] >> (4 * j)) & 0xFu);
+        }
+        acc = __builtin_fmaf(s, p[0], acc);
+      }
+    }
+  } else {
+    // ------------------------------------------------------------------ a share of wide k-tiles
+    const uint32_t t0 = (wave - wn) * TPWW;
+    // x: lane p < 4 NGW stages (group p / 4, quarter p % 4): three chunks of 16 bytes, one per k-step
+    const uint32_t sp = min(lane, (uint32_t)(4 * NGW - 1));
+    const uint32_t slg = sp >> 2, skq = sp & 3u;
+    const uint32_t pg = t0 * 8u + slg;
+    const uint32_t g = a.meta ? (uint32_t)a.meta[(uint32_t)a.meta_wide + pg] : min(pg, (uint32_t)a.g_last);
+    u32x4 xc[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) xc[t] = load_chunk16(a.x + (g << 6) + min(18u * skq + 6u * t, 56u));
+    if constexpr (SM == 1) ssup = a.scale_super[row];
+    u32x4 cw[TPWW][3];
+    u32x4 sw[TPWW];
+    const uint16_t* sb = scale_row + (size_t)a.tiles_n * 64u + (size_t)t0 * 128u;   // fp16 scales only: [narrow tiles][wide tiles]
+#pragma unroll
+    for (int i = 0; i < TPWW; ++i) {
+      if constexpr (SM == 0) sw[i] = *reinterpret_cast<const u32x4*>(sb + i * 128u + n * 8u);
+      else sw[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const uint8_t* cb = code_row + (size_t)a.tiles_n * 1024u + (size_t)t0 * 2816u;
+#pragma unroll
+    for (int i = 0; i < TPWW; ++i) {
+      const uint8_t* t = cb + i * 2816u + lane * 16u;
+      cw[i][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
+      cw[i][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
+      // the third segment has entries for 48 lanes only; the lanes above re-read the last entry (their k-slots meet
+      // zero activations, and every bit pattern decodes to a finite value)
+      cw[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47u ? (lane - 47u) * 16u : 0u)));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float* lds_c = reinterpret_cast<float*>(region + NGW * 12 * 16);
+    {
+      float sum = 0.f;
+#pragma unroll
+      for (int t = 0; t < 3; ++t) {
+        const u32x4 o = wide_frag(xc[t], skq, t);
+        sum += frag_sum(o);
+        if (lane < (uint32_t)(4 * NGW)) lds_x[(slg * 3u + t) * 4u + skq] = o;
+      }
+      if (lane < (uint32_t)(4 * NGW)) lds_c[(slg * 4u + skq) * 4u] = a.cneg_w * sum;
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < TPWW; ++i) {
+      uint32_t fields[4] = {0u, 0u, 0u, 0u};
+      if constexpr (SM == 1) {
+        const int src = (int)((48u + n) * 4u);
+        fields[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].x);
+        fields[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].y);
+        fields[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].z);
+        fields[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].w);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int lg = i * 8 + j;
+        f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+          const u32x4 xf = lds_x[(lg * 3 + t) * 4 + kq];
+          const u32x4 seg = cw[i][t];
+          const uint32_t d = (j >> 1) == 0 ? seg.x : ((j >> 1) == 1 ? seg.y : ((j >> 1) == 2 ? seg.z : seg.w));
+          const uint32_t pp = __builtin_amdgcn_perm(0u, d, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // {0, b, 0, a}
+          const uint32_t w0 = and_or(pp >> 4, mask_w, c4300);   // Table 1: shifts [4, 2, 0], mask 0xF, both codes at once
+          const uint32_t w1 = and_or(pp >> 2, mask_w, c4300);
+          const uint32_t w2 = and_or(pp, mask_w, c4300);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.x, xf.y}), __builtin_bit_cast(bf16x4, u32x2{w0, w1}), p, 0, 0, 0);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.z, xf.w}), __builtin_bit_cast(bf16x4, u32x2{w2, w2}), p, 0, 0, 0);
+        }
+        float s;
+        if constexpr (SM == 0) {
+          const uint32_t sd = (j >> 1) == 0 ? sw[i].x : ((j >> 1) == 1 ? sw[i].y : ((j >> 1) == 2 ? sw[i].z : sw[i].w));
+          s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else {
+          s = (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu);   // the field alone; the row's super scale multiplies the sum once
+        }
+        acc = __builtin_fmaf(s, p[0], acc);
+      }
+    }
+  }
+  // ---- the four quarters of a row, then the wavefronts of the workgroup (fixed order) ------------------------------
+  acc += __shfl_xor(acc, 16);
+  acc += __shfl_xor(acc, 32);
+  if (nwaves > 1) {
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);
+    if (wave > 0 && lane < 16u) red[(wave - 1) * 16u + lane] = acc;
+    __syncthreads();
+    if (wave == 0 && lane < 16u) {
+      for (uint32_t k = 1; k < nwaves; ++k) acc += red[(k - 1) * 16u + lane];
+    }
+  }
+  if (wave == 0 && lane < 16u) {
+    float v = acc;
+    if constexpr (SM == 1) v *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
+    if (rtile * 16u + lane <= (uint32_t)a.n_last) a.y[rtile * 16u + lane] = to_bf16_rne(v);
+  }
+}
+
 // ---- two to sixteen activation rows --------------------------------------------------------------------------------
 // Same decode, MFMA 16x16x32 bf16 in place of 4x4x4: lane l owns output row n = l % 16 of its row tile and quarter
 // kq = l / 16 of every group (the B operand), the activations are the A operand (row m = l % 16, k-slots of quarter
@@ -470,6 +724,90 @@ int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, v
     return CCQ_ERR_HIP;
   }
   hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * waves)), lds, static_cast<hipStream_t>(stream), a);
+  return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
+}
+
+// Shape of a one-row launch on wide-format or mixed weights: wn wavefronts with shares of tpwn narrow k-tiles, then
+// ww wavefronts with shares of tpww wide k-tiles, at most 16 in all; shares of two k-tiles where K splits that way
+// (every lane of a wavefront then stages one (group, quarter) of the wide share's activations).  false: no wide
+// k-tiles, the hybrid word, or K does not split into at most 16 such shares (the caller uses the general kernel).
+bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out) {
+  if (L.h16 || L.tiles[kWide] < 1) return false;
+  const int tn = L.tiles[kNarrow], tw = L.tiles[kWide];
+  if (tn == 0) {
+    for (int pw : {2, 1}) {   // config 3, all wide: 21.7 us with shares of two k-tiles, 23.3 us with shares of one
+      if (tw % pw != 0 || tw / pw > 16) continue;
+      *tpwn_out = 0; *tpww_out = pw; *wn_out = 0; *ww_out = tw / pw;
+      return true;
+    }
+    return false;
+  }
+  // a mix: shares of about the same length first (one wide k-tile is 144 weights per lane, two narrow ones 128)
+  static const int kPairs[][2] = {{2, 1}, {4, 2}, {2, 2}, {4, 1}, {1, 1}, {1, 2}};
+  for (const auto& pr : kPairs) {
+    const int pn = pr[0], pw = pr[1];
+    if (tn % pn != 0 || tw % pw != 0 || tn / pn + tw / pw > 16) continue;
+    *tpwn_out = pn; *tpww_out = pw; *wn_out = tn / pn; *ww_out = tw / pw;
+    return true;
+  }
+  return false;
+}
+
+namespace gemv {
+typedef void (*KernelNW)(const ArgsNW);
+template <int SM>
+static KernelNW pick_nw(int tpwn, int tpww) {
+  if (tpww == 1) {
+    switch (tpwn) {
+      case 0: return kernel_nw<0, 1, SM>;
+      case 1: return kernel_nw<1, 1, SM>;
+      case 2: return kernel_nw<2, 1, SM>;
+      case 4: return kernel_nw<4, 1, SM>;
+    }
+  } else if (tpww == 2) {
+    switch (tpwn) {
+      case 0: return kernel_nw<0, 2, SM>;
+      case 1: return kernel_nw<1, 2, SM>;
+      case 2: return kernel_nw<2, 2, SM>;
+      case 4: return kernel_nw<4, 2, SM>;
+    }
+  }
+  return nullptr;
+}
+}  // namespace gemv
+
+int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww) {
+  using namespace gemv;
+  if (L.h16 || ww < 1 || wn < 0 || wn + ww > 16 || wn * tpwn != L.tiles[kNarrow] || ww * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
+  if (L.row_tile_bytes * (int64_t)L.row_tiles >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  ArgsNW a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
+  a.meta = L.has_map ? static_cast<const int32_t*>(w->meta) : nullptr;
+  a.row_tile_bytes = L.row_tile_bytes;
+  a.row_tile_scale_halfs = L.row_tile_scale_halfs;
+  a.tiles_n = L.tiles[kNarrow];
+  a.tiles_w = L.tiles[kWide];
+  a.waves_n = wn;
+  a.meta_wide = L.pgroups[kNarrow];
+  a.cneg_n = -(128.f + L.zp[kNarrow]);
+  a.cneg_w = -(128.f + L.zp[kWide]);
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
+  const KernelNW k = L.scale_mode == 0 ? pick_nw<0>(tpwn, tpww) : pick_nw<1>(tpwn, tpww);
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  const size_t region_n = (size_t)tpwn * 4 * (8 * 16 + 4 * 16), region_w = (size_t)tpww * 8 * (12 * 16 + 4 * 16);
+  const size_t lds = std::max<size_t>((size_t)wn * region_n + (size_t)ww * region_w, 1024);   // at most 16 * 4 KiB; the K reduction reuses the start
+  if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * (wn + ww))), lds, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
 }
 

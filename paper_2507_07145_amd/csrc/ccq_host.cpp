@@ -506,6 +506,15 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
     }
   }
 
+  // one row on wide-format or mixed weights: the one-row kernel for those formats
+  if (!explicit_launch && M == 1) {
+    int tpwn = 0, tpww = 0, wn = 0, ww = 0;
+    if (gemv_nw_shape(L, &tpwn, &tpww, &wn, &ww)) {
+      rc = launch_gemv_nw(w, L, x, y, stream, tpwn, tpww, wn, ww);
+      if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    }
+  }
+
   // otherwise rows are processed in passes of at most kMaxSkinnyM (nothing has been enqueued when control gets here)
   if (have < need_passes) return CCQ_ERR_WORKSPACE;
   for (int m0 = 0; m0 < M; m0 += kMaxSkinnyM) {

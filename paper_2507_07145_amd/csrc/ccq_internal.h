@@ -121,6 +121,8 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
 // One activation row on narrow-format weights (ccq_gemv.hip): shape of the launch for a chip of `cus` compute units
 // (false when K does not split into at most 16 equal shares of a built length), and the launcher.
 bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
+bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out);
+int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww);
 int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves);
 int device_cus();  // compute units of the current device (cached per device)
 // Two to sixteen rows on narrow-format weights (ccq_gemv.hip): K is cut into tiles / tpw shares across workgroups; with

@@ -372,3 +372,37 @@ def test_workspace_guard_bands(kinds, K, N, M):
         y3 = b.bf16_bits(b.gemm(w, xt, workspace=buf[band:band + need // 2]))
         torch.cuda.synchronize()
         assert_gemm_close(y3, o.matmul(x, c.W()), f"half the workspace {kinds} M={M}")
+
+
+@pytest.mark.parametrize("n_narrow,n_wide,what", [(0, 16, "wide, shares of two k-tiles"), (0, 8 * 5, "wide, five shares of one"), (96, 64, "(4,2)"),
+                                                  (72, 80, "(2,2)"), (96, 56, "(4,1)"), (36, 80, "(1,2)"), (20, 8, "(1,1)"), (24, 8, "(2,1)"),
+                                                  (108, 8, "27 narrow k-tiles: no split into 16 shares, general kernel")])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_one_row_kernel_every_share_shape(n_narrow, n_wide, what, mode):
+    """One activation row on wide-format and mixed weights: every (narrow share, wide share) pair the one-row kernel is
+    built for, both scale modes; decoded weights bit-exact (one-hot rows, one per call) and the product within tolerance."""
+    G = n_narrow + n_wide
+    K, N = 64 * G, 48
+    kinds = ["wide"] if n_narrow == 0 else ["narrow", "wide"]
+    rng = synth.rng(17, G + mode)
+    gf = synth.group_format_map(G, n_wide, rng) if n_narrow else None
+    ofmt = o.F275 if n_narrow == 0 else (o.F2, o.F275)
+    bfmt = [b.WIDE] if n_narrow == 0 else [b.NARROW, b.WIDE]
+    codes = synth.random_codes(N, o.row_bytes(K, ofmt, gf), rng)
+    alpha, beta = synth.cluster_params(N, rng)
+    if mode == 0:
+        scales = synth.scales_log_uniform_fp16(N, G, rng)
+        W = o.decode(K, N, ofmt, codes, scales, alpha, beta, gf)
+        w = b.Weight.from_canonical(K, N, bfmt, codes, scales, alpha, beta, gf, device=DEV)
+    else:
+        nb = o.sq_row_bytes(K, ofmt, gf)
+        sq = rng.integers(0, 256, size=(N, max(nb, 1)), dtype=np.uint8)[:, :nb]
+        ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(N, 1, rng).reshape(N)) * 0.1).astype(np.float16).view(np.uint16)
+        W = o.decode_cs(K, N, ofmt, codes, sq, ssup, alpha, beta, gf)
+        w = b.Weight.from_canonical_compressed(K, N, bfmt, codes, sq, ssup, alpha, beta, gf, device=DEV)
+    x = synth.activations_bf16(1, K, synth.rng(17, 900 + G))
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, W), f"one row, {what}, scale mode {mode}")
+    ks = np.concatenate([[0, 17, 59, 60, 61, 62, 63, 64, K - 64, K - 4, K - 1], synth.rng(17, 901).integers(0, K, 21)])
+    for k in ks:
+        got = _gemm_bits(w, synth.one_hot_bf16([int(k)], K))
+        assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, [int(k)]].T))), f"{what}: decoded weights differ at column {k}"
