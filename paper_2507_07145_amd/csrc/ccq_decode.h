@@ -54,4 +54,24 @@ __device__ __forceinline__ void decode16_narrow(uint32_t d, float al, float bem,
   }
 }
 
+constexpr uint32_t kDecMaskW2 = 0x00F000F0u;  // bits 4..7 of the mantissas of two fp16 numbers (a 4-bit state)
+
+// Six weights of one lane (two stored bytes a, b of a wide-format group: codes of (L=4,N=3,S=2), weights 3 code .. + 2)
+// to fp32, in k order.  `pp` holds the two bytes as {0, b, 0, a}.  Table 1's shift list [4, 2, 0] with mask 0xF: the
+// window at shift 4 already sits in bits 4..7 of its half, the other two are moved there with one shift each, and one
+// v_and_or per window puts both codes' state into the mantissas of two fp16 64.0 (64 + state, exact).  Then Alg. 2's
+// last line, d = (w_uint - zp) s, as one mixed-precision FMA per weight with c0 = -(64 + zp) s (exact in fp32: at
+// most 8 significant bits times at most 15).  11 vector instructions per 6 weights.
+__device__ __forceinline__ void decode6_wide(uint32_t pp, float s, float c0, uint32_t mask2, uint32_t base2, float (&w)[6]) {
+  const f16x2 f0 = __builtin_bit_cast(f16x2, dec_and_or(pp, mask2, base2));
+  const f16x2 f1 = __builtin_bit_cast(f16x2, dec_and_or(pp << 2, mask2, base2));
+  const f16x2 f2 = __builtin_bit_cast(f16x2, dec_and_or(pp << 4, mask2, base2));
+  w[0] = __builtin_fmaf((float)f0.x, s, c0);
+  w[1] = __builtin_fmaf((float)f1.x, s, c0);
+  w[2] = __builtin_fmaf((float)f2.x, s, c0);
+  w[3] = __builtin_fmaf((float)f0.y, s, c0);
+  w[4] = __builtin_fmaf((float)f1.y, s, c0);
+  w[5] = __builtin_fmaf((float)f2.y, s, c0);
+}
+
 }  // namespace ccq

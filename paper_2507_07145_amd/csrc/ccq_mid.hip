@@ -158,9 +158,9 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
   }
   const int64_t wide_code_off = (int64_t)a.tiles[kNarrow] * kNarrowTileBytes;
   const int64_t wide_scale_off = (int64_t)a.tiles[kNarrow] * kNarrowTileScaleHalfs;
-  uint32_t c43 = 0x43000000u, mask2 = kDecMask2, base2 = kDecBase2, mask_w = H16 ? 0x00070000u : 0x000F0000u;
+  uint32_t c43 = 0x43000000u, mask2 = kDecMask2, base2 = kDecBase2, mask_w = 0x00070000u, mask_w2 = kDecMaskW2;  // mask_w: the hybrid word's 3-bit states
   float magic = 8388608.f;
-  asm volatile("" : "+v"(c43), "+s"(mask2), "+v"(base2), "+s"(mask_w), "+v"(magic));
+  asm volatile("" : "+v"(c43), "+s"(mask2), "+v"(base2), "+s"(mask_w), "+s"(mask_w2), "+v"(magic));
 
   // code tiles in registers: the one being decoded and the next one of the same kind
   u32x4 cn[kMidRTW], cn_next[kMidRTW];
@@ -320,20 +320,16 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
         const uint32_t q3 = (uint32_t)__builtin_amdgcn_ds_bpermute((48 + nl) * 4, (int)own);
         s = (float)((q3 >> (16 * (j & 1) + 8)) & 0xFu) * ssup[i];
       }
-      const float c0 = -(128.f + a.zp[kWide]) * s;
+      const float c0 = -(kDecBase + a.zp[kWide]) * s;
       float w[18];
 #pragma unroll
       for (int t = 0; t < 3; ++t) {
         const uint32_t dd = dword_sel(cw[i][t], j >> 1);
-        const uint32_t h = (j & 1) ? (dd >> 16) : (dd & 0xFFFFu);  // two codes: low byte first
+        const uint32_t pp = __builtin_amdgcn_perm(0u, dd, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // two codes, low byte first: {0, b, 0, a}
+        float w6[6];
+        decode6_wide(pp, s, c0, mask_w2, base2, w6);
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const uint32_t c = (h >> (8 * b)) & 0xFFu;
-          // shift list [4,2,0], mask 0xF (Table 1), into bits 16..19
-          w[6 * t + 3 * b + 0] = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(c << 12, mask_w, c43)), s, c0);
-          w[6 * t + 3 * b + 1] = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(c << 14, mask_w, c43)), s, c0);
-          w[6 * t + 3 * b + 2] = __builtin_fmaf(__builtin_bit_cast(float, and_or_m(c << 16, mask_w, c43)), s, c0);
-        }
+        for (int e = 0; e < 6; ++e) w[6 * t + e] = w6[e];
       }
       uint32_t* p = reinterpret_cast<uint32_t*>(dst + ((wave * kMidRTW + i) * 16 + nl) * ROW + kq * 18);
 #pragma unroll
