@@ -656,6 +656,258 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
   }
 }
 
+// ---- two to sixteen activation rows on wide-format and mixed weights ------------------------------------------------
+// kernel16 for the (L=4,N=3,S=2) code and for per-group mixes: a workgroup is NW row tiles that share one staged slice
+// of the activations; the K shares (gridDim.y) are narrow shares of TPWN k-tiles first, then wide shares of TPWW k-tiles
+// of 8 groups.  A wide group is three MFMA 16x16x32 k-steps of 8 k-slots, 6 of them used (see kernel_nw); its
+// activation fragments are cut out of three 16-byte chunks per (group, row, quarter).
+struct Args16NW {
+  const uint8_t* codes;
+  const uint16_t* scales;
+  const float* alpha;
+  const float* beta;
+  const uint16_t* x;
+  uint16_t* y;
+  const uint16_t* scale_super;
+  const int32_t* meta;           // original group of every packed group (narrow first), or NULL: a single format
+  float* partial;                // fp32 [shares][M][N] when K is cut
+  int64_t ldx, ldy;
+  int64_t row_tile_bytes, row_tile_scale_halfs;
+  int32_t tiles_n, tiles_w, row_tiles, M, N;   // N: rows of the device layout, the stride of the partial tiles
+  int32_t shares_n;              // K shares that are narrow (the first ones)
+  int32_t meta_wide;             // entries of the group map that precede the wide groups
+  float cneg_n, cneg_w;
+  int32_t g_last, n_last;
+};
+
+template <int TPWN, int TPWW, int SM, int NW>
+__global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
+  constexpr int NGN = TPWN * 4, NGW = TPWW * 8;
+  extern __shared__ __align__(16) unsigned char smem[];
+  u32x4* lds_x = reinterpret_cast<u32x4*>(smem);
+  constexpr uint32_t nthreads = 64u * NW;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t n = lane & 15u, kq = lane >> 4;
+  const uint32_t rtile_raw = blockIdx.x * NW + wave;
+  const bool active = rtile_raw < (uint32_t)a.row_tiles;
+  const uint32_t rtile = active ? rtile_raw : (uint32_t)a.row_tiles - 1u;   // a ragged last block re-reads the last tile; nothing of it is stored
+  const uint32_t prow = min(rtile * 16u + n, (uint32_t)a.n_last);
+  const uint8_t* code_row = a.codes + (size_t)rtile * (size_t)a.row_tile_bytes;
+  const uint16_t* scale_row = a.scales + (size_t)rtile * (size_t)a.row_tile_scale_halfs;
+  uint32_t c4300 = 0x43004300u, mask_n = 0x003F003Fu, mask_w = 0x000F000Fu;
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(c4300), "+s"(mask_n), "+s"(mask_w), "+v"(magic));
+  typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  uint32_t ssup = 0;
+  if constexpr (SM == 1) ssup = a.scale_super[prow];
+  const uint32_t sn = TPWN > 0 ? (uint32_t)a.shares_n : 0u;
+
+  if (TPWN > 0 && blockIdx.y < sn) {
+    // ------------------------------------------------------------------ a narrow share (as in kernel16)
+    constexpr int NU = NGN * 4 * 16;
+    constexpr int SH = SM == 0 ? 64 : 16;
+    constexpr int NUT = NU > 0 ? (NU + (int)nthreads - 1) / (int)nthreads : 1;
+    float* lds_c = reinterpret_cast<float*>(smem + (size_t)NGN * 8 * 16 * 16);
+    const uint32_t t0 = blockIdx.y * TPWN;
+    u32x4 xv[NUT][2];
+#pragma unroll
+    for (int i = 0; i < NUT; ++i) {
+      uint32_t u = tid + (uint32_t)i * nthreads;
+      if (NU % nthreads != 0) u = min(u, (uint32_t)NU - 1u);
+      const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
+      const uint32_t row = min(m, (uint32_t)a.M - 1u);
+      const uint32_t pg = t0 * 4u + lg;
+      const uint32_t g = a.meta ? (uint32_t)a.meta[pg] : min(pg, (uint32_t)a.g_last);
+      const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + ((size_t)g * 64u + q * 16u);
+      xv[i][0] = *reinterpret_cast<const u32x4*>(p);
+      xv[i][1] = *reinterpret_cast<const u32x4*>(p + 8);
+    }
+    const float al = a.alpha[prow];
+    const float be_raw = a.beta[prow];
+    u32x4 cw[TPWN > 0 ? TPWN : 1];
+    uint32_t sw[TPWN > 0 ? TPWN : 1][SM == 0 ? 2 : 1];
+    const uint16_t* sb = scale_row + (size_t)t0 * SH;
+#pragma unroll
+    for (int i = 0; i < TPWN; ++i) {
+      if constexpr (SM == 0) {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+        sw[i][0] = v.x;
+        sw[i][1] = v.y;
+      } else {
+        sw[i][0] = sb[i * 16u + n];
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < TPWN; ++i) cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(code_row + (size_t)(t0 + i) * 1024u + lane * 16u));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NUT; ++i) {
+      const uint32_t u = tid + (uint32_t)i * nthreads;
+      float s = 0.f;
+      u32x4 o[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        o[t].x = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x05040100u);
+        o[t].y = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x07060302u);
+        o[t].z = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x05040100u);
+        o[t].w = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x07060302u);
+        s += frag_sum(o[t]);
+      }
+      s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+      s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+      if (NU % nthreads == 0 || u < (uint32_t)NU) {
+        const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
+        lds_x[((lg * 2u + 0u) * 4u + q) * 16u + m] = o[0];
+        lds_x[((lg * 2u + 1u) * 4u + q) * 16u + m] = o[1];
+        if (q == 0) lds_c[lg * 16u + m] = a.cneg_n * s;
+      }
+    }
+    __syncthreads();
+    const float be = be_raw + magic;
+#pragma unroll
+    for (int i = 0; i < TPWN; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int lg = i * 4 + j;
+        const u32x4 x0 = lds_x[((lg * 2 + 0) * 4 + kq) * 16 + n];
+        const u32x4 x1 = lds_x[((lg * 2 + 1) * 4 + kq) * 16 + n];
+        f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + lg * 16 + 4 * kq);
+        u32x4 w[2];
+        const uint32_t d = j == 0 ? cw[i].x : (j == 1 ? cw[i].y : (j == 2 ? cw[i].z : cw[i].w));
+        decode_dword(d, al, be, c4300, mask_n, w);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0), __builtin_bit_cast(bf16x8, w[0]), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1), __builtin_bit_cast(bf16x8, w[1]), p, 0, 0, 0);
+        float sc;
+        if constexpr (SM == 0) {
+          const uint32_t sd = sw[i][j >> 1];
+          sc = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else {
+          sc = (float)((sw[i][0] >> (4 * j)) & 0xFu);
+        }
+        acc[0] = __builtin_fmaf(sc, p[0], acc[0]);
+        acc[1] = __builtin_fmaf(sc, p[1], acc[1]);
+        acc[2] = __builtin_fmaf(sc, p[2], acc[2]);
+        acc[3] = __builtin_fmaf(sc, p[3], acc[3]);
+      }
+    }
+  } else {
+    // ------------------------------------------------------------------ a wide share
+    constexpr int NU = NGW * 4 * 16;                                   // staging units: (group, row, quarter)
+    constexpr int NUT = (NU + (int)nthreads - 1) / (int)nthreads;
+    float* lds_c = reinterpret_cast<float*>(smem + (size_t)NGW * 12 * 16 * 16);   // [group][row]
+    const uint32_t t0 = (blockIdx.y - sn) * TPWW;
+    u32x4 xv[NUT][3];
+#pragma unroll
+    for (int i = 0; i < NUT; ++i) {
+      uint32_t u = tid + (uint32_t)i * nthreads;
+      if (NU % nthreads != 0) u = min(u, (uint32_t)NU - 1u);
+      const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
+      const uint32_t row = min(m, (uint32_t)a.M - 1u);
+      const uint32_t pg = t0 * 8u + lg;
+      const uint32_t g = a.meta ? (uint32_t)a.meta[(uint32_t)a.meta_wide + pg] : min(pg, (uint32_t)a.g_last);
+      const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + (size_t)g * 64u;
+#pragma unroll
+      for (int t = 0; t < 3; ++t) xv[i][t] = load_chunk16(p + min(18u * q + 6u * t, 56u));
+    }
+    u32x4 cw[TPWW][3];
+    u32x4 sw[TPWW];
+    const uint16_t* sb = scale_row + (size_t)a.tiles_n * 64u + (size_t)t0 * 128u;   // fp16 scales only
+#pragma unroll
+    for (int i = 0; i < TPWW; ++i) {
+      if constexpr (SM == 0) sw[i] = *reinterpret_cast<const u32x4*>(sb + i * 128u + n * 8u);
+      else sw[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const uint8_t* cb = code_row + (size_t)a.tiles_n * 1024u + (size_t)t0 * 2816u;
+#pragma unroll
+    for (int i = 0; i < TPWW; ++i) {
+      const uint8_t* t = cb + i * 2816u + lane * 16u;
+      cw[i][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
+      cw[i][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
+      cw[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47u ? (lane - 47u) * 16u : 0u)));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NUT; ++i) {
+      const uint32_t u = tid + (uint32_t)i * nthreads;
+      const uint32_t uq = min(u, (uint32_t)NU - 1u) & 3u;
+      float s = 0.f;
+      u32x4 o[3];
+#pragma unroll
+      for (int t = 0; t < 3; ++t) {
+        o[t] = wide_frag(xv[i][t], uq, t);
+        s += frag_sum(o[t]);
+      }
+      s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));   // the four quarters of a (group, row): neighbouring lanes
+      s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, true));
+      if (NU % nthreads == 0 || u < (uint32_t)NU) {
+        const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
+#pragma unroll
+        for (int t = 0; t < 3; ++t) lds_x[((lg * 3u + t) * 4u + q) * 16u + m] = o[t];
+        if (q == 0) lds_c[lg * 16u + m] = a.cneg_w * s;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TPWW; ++i) {
+      uint32_t fields[4] = {0u, 0u, 0u, 0u};
+      if constexpr (SM == 1) {
+        const int src = (int)((48u + n) * 4u);
+        fields[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].x);
+        fields[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].y);
+        fields[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].z);
+        fields[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].w);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int lg = i * 8 + j;
+        f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + lg * 16 + 4 * kq);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+          const u32x4 xf = lds_x[((lg * 3 + t) * 4 + kq) * 16 + n];     // here n is the activation row of this lane's A fragment
+          const u32x4 seg = cw[i][t];
+          const uint32_t d = (j >> 1) == 0 ? seg.x : ((j >> 1) == 1 ? seg.y : ((j >> 1) == 2 ? seg.z : seg.w));
+          const uint32_t pp = __builtin_amdgcn_perm(0u, d, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // {0, b, 0, a}
+          u32x4 wv;
+          wv.x = and_or(pp >> 4, mask_w, c4300);   // Table 1: shifts [4, 2, 0], mask 0xF, both codes at once
+          wv.y = and_or(pp >> 2, mask_w, c4300);
+          wv.z = and_or(pp, mask_w, c4300);
+          wv.w = c4300;                            // unused k-slots: zero activations
+          p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xf), __builtin_bit_cast(bf16x8, wv), p, 0, 0, 0);
+        }
+        float sc;
+        if constexpr (SM == 0) {
+          const uint32_t sd = (j >> 1) == 0 ? sw[i].x : ((j >> 1) == 1 ? sw[i].y : ((j >> 1) == 2 ? sw[i].z : sw[i].w));
+          sc = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else {
+          sc = (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu);
+        }
+        acc[0] = __builtin_fmaf(sc, p[0], acc[0]);
+        acc[1] = __builtin_fmaf(sc, p[1], acc[1]);
+        acc[2] = __builtin_fmaf(sc, p[2], acc[2]);
+        acc[3] = __builtin_fmaf(sc, p[3], acc[3]);
+      }
+    }
+  }
+  if constexpr (SM == 1) acc *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
+
+  // ---- store: lane (n, kq) holds rows 4 kq .. 4 kq + 3 of column n -------------------------------------------------------
+  const uint32_t col = rtile * 16u + n;
+  if (active && col <= (uint32_t)a.n_last) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t m = 4u * kq + r;
+      if (m < (uint32_t)a.M) {
+        if (gridDim.y > 1) a.partial[((size_t)blockIdx.y * (uint32_t)a.M + m) * (uint32_t)a.N + col] = acc[r];
+        else a.y[(size_t)m * (size_t)a.ldy + col] = to_bf16_rne(acc[r]);
+      }
+    }
+  }
+}
+
 typedef void (*Kernel)(const Args);
 
 template <int SM>
@@ -808,6 +1060,111 @@ int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y,
     return CCQ_ERR_HIP;
   }
   hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * (wn + ww))), lds, static_cast<hipStream_t>(stream), a);
+  return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
+}
+
+// K shares of the 2..16-row kernel on wide-format and mixed weights: narrow shares of tpwn k-tiles, then wide shares of
+// tpww, at most min(max_shares, kMaxSplitsK) in all; the longest shares first (the least partial-tile traffic: at
+// N = 28672 a share's partial tile is as many bytes as 1/6 of a wide k-tile column block), shorter ones only when the
+// long ones leave compute units without a workgroup.  false: no wide k-tiles, the hybrid word, or no such split.
+bool gemv16_nw_shape(const Layout& L, int cus, int64_t max_shares, int* tpwn_out, int* tpww_out, int* sn_out, int* sw_out) {
+  if (L.h16 || L.tiles[kWide] < 1) return false;
+  const int tn = L.tiles[kNarrow], tw = L.tiles[kWide], nw = 8;
+  const int64_t row_blocks = (L.row_tiles + nw - 1) / nw;
+  const int64_t cap = std::min<int64_t>(max_shares, kMaxSplitsK);
+  static const int kPairs[][2] = {{4, 2}, {2, 1}, {2, 2}, {4, 1}, {1, 1}, {1, 2}};
+  static const int kWideOnly[] = {2, 1};
+  bool found = false;
+  auto take = [&](int pn, int pw) -> bool {
+    const int sn = pn > 0 ? tn / pn : 0, sw = tw / pw;
+    if (sn + sw > cap) return false;
+    if (found && (int64_t)(*sn_out + *sw_out) >= sn + sw) return false;   // only more shares than what is already held
+    *tpwn_out = pn; *tpww_out = pw; *sn_out = sn; *sw_out = sw;
+    found = true;
+    return row_blocks * (sn + sw) >= cus;   // enough workgroups: stop
+  };
+  if (tn == 0) {
+    for (int pw : kWideOnly) {
+      if (tw % pw != 0) continue;
+      if (take(0, pw)) break;
+    }
+  } else {
+    for (const auto& pr : kPairs) {
+      if (tn % pr[0] != 0 || tw % pr[1] != 0) continue;
+      if (take(pr[0], pr[1])) break;
+    }
+  }
+  return found;
+}
+
+int launch_gemv16_nw(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int tpwn,
+                     int tpww, int sn, int sw, void* stream) {
+  using namespace gemv;
+  constexpr int nw = 8;
+  if (M < 1 || M > 16 || L.h16 || sw < 1 || sn < 0 || sn * tpwn != L.tiles[kNarrow] || sw * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
+  const int S = sn + sw;
+  if (S > kMaxSplitsK || (S > 1 && !partial)) return CCQ_ERR_UNSUPPORTED;
+  if (L.row_tile_bytes * (int64_t)L.row_tiles >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  Args16NW a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
+  a.meta = L.has_map ? static_cast<const int32_t*>(w->meta) : nullptr;
+  a.partial = partial;
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.row_tile_bytes = L.row_tile_bytes;
+  a.row_tile_scale_halfs = L.row_tile_scale_halfs;
+  a.tiles_n = L.tiles[kNarrow];
+  a.tiles_w = L.tiles[kWide];
+  a.row_tiles = L.row_tiles;
+  a.M = M;
+  a.N = L.Npad;
+  a.shares_n = sn;
+  a.meta_wide = L.pgroups[kNarrow];
+  a.cneg_n = -(128.f + L.zp[kNarrow]);
+  a.cneg_w = -(128.f + L.zp[kWide]);
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
+  typedef void (*Kernel16NW)(const Args16NW);
+  Kernel16NW k = nullptr;
+  const int key = tpwn * 10 + tpww;
+  if (L.scale_mode == 0) {
+    switch (key) {
+      case 1: k = kernel16_nw<0, 1, 0, nw>; break;
+      case 2: k = kernel16_nw<0, 2, 0, nw>; break;
+      case 11: k = kernel16_nw<1, 1, 0, nw>; break;
+      case 12: k = kernel16_nw<1, 2, 0, nw>; break;
+      case 21: k = kernel16_nw<2, 1, 0, nw>; break;
+      case 22: k = kernel16_nw<2, 2, 0, nw>; break;
+      case 41: k = kernel16_nw<4, 1, 0, nw>; break;
+      case 42: k = kernel16_nw<4, 2, 0, nw>; break;
+    }
+  } else {
+    switch (key) {
+      case 1: k = kernel16_nw<0, 1, 1, nw>; break;
+      case 2: k = kernel16_nw<0, 2, 1, nw>; break;
+      case 11: k = kernel16_nw<1, 1, 1, nw>; break;
+      case 12: k = kernel16_nw<1, 2, 1, nw>; break;
+      case 21: k = kernel16_nw<2, 1, 1, nw>; break;
+      case 22: k = kernel16_nw<2, 2, 1, nw>; break;
+      case 41: k = kernel16_nw<4, 1, 1, nw>; break;
+      case 42: k = kernel16_nw<4, 2, 1, nw>; break;
+    }
+  }
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  const size_t lds_n = (size_t)(tpwn * 4) * (8 * 16 * 16 + 16 * 4), lds_w = (size_t)(tpww * 8) * (12 * 16 * 16 + 16 * 4);
+  const size_t lds = std::max(lds_n, lds_w);   // at most 16 groups x 3136 bytes = 49 KiB
+  if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  const dim3 grid((unsigned)((L.row_tiles + nw - 1) / nw), (unsigned)S);
+  hipLaunchKernelGGL(k, grid, dim3((unsigned)(64 * nw)), lds, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
 }
 

@@ -141,7 +141,7 @@ Decomp choose_decomp(const Layout& L, int M, int experts, int rows_total) {
 using namespace ccq;
 
 // Which kernel a dense call of M rows uses when no launch shape is given.
-enum DensePath { kPathGemv, kPathGemv16, kPathSkinny, kPathRows, kPathMid, kPathPrefill };
+enum DensePath { kPathGemv, kPathGemv16, kPathGemv16NW, kPathSkinny, kPathRows, kPathMid, kPathPrefill };
 static DensePath dense_path(const Layout& L, int M) {
   const bool narrow_only = L.tiles[kWide] == 0, wide_only = L.tiles[kNarrow] == 0;
   if (narrow_only && !L.has_map && M < kMidMinM) {
@@ -150,6 +150,11 @@ static DensePath dense_path(const Layout& L, int M) {
     int tpw = 0, nw = 0;
     if (M == 1 || (M <= kGemvMaxM && gemv_narrow_shares(L, M) > 0)) return kPathGemv;
     if (gemv16_shape(L, 256, kMaxSplitsK, &tpw, &nw)) return kPathGemv16;
+  }
+  // two to sixteen rows on wide-format and mixed weights: the 16-row kernel for those formats, where K splits its way
+  if (!narrow_only && !L.h16 && M >= 2 && M < kMidMinM) {
+    int tpwn = 0, tpww = 0, sn = 0, sw = 0;
+    if (gemv16_nw_shape(L, 256, kMaxSplitsK, &tpwn, &tpww, &sn, &sw)) return kPathGemv16NW;
   }
   // per-group activation tiles with the weights in registers: measured faster than its neighbours for 2-16 rows on the
   // wide and hybrid-word formats (whose whole-k-tile staging is the costliest) and for 17-32 rows on the narrow one
@@ -205,6 +210,11 @@ static int64_t dense_need(const Layout& L, int M) {
       if (!gemv16_shape(L, device_cus(), kMaxSplitsK, &tpw, &nw)) return skinny_need(L, M);
       const int S = L.tiles[kNarrow] / tpw;
       return S > 1 ? (int64_t)S * M * L.Npad * 4 : 0;
+    }
+    case kPathGemv16NW: {
+      int tpwn = 0, tpww = 0, sn = 0, sw = 0;
+      if (!gemv16_nw_shape(L, device_cus(), kMaxSplitsK, &tpwn, &tpww, &sn, &sw)) return skinny_need(L, M);
+      return sn + sw > 1 ? (int64_t)(sn + sw) * M * L.Npad * 4 : 0;
     }
     case kPathRows: {
       const int S = rows_splits(L, M);
@@ -458,7 +468,7 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
     if (rc != CCQ_OK) return rc;
     if (d.S > 1) need_passes = std::max(need_passes, (int64_t)d.S * mc * L.Npad * 4);
   }
-  if (!explicit_launch && dense_path(L, M) != kPathGemv16 && have < dense_need(L, M)) return CCQ_ERR_WORKSPACE;
+  if (!explicit_launch && dense_path(L, M) != kPathGemv16 && dense_path(L, M) != kPathGemv16NW && have < dense_need(L, M)) return CCQ_ERR_WORKSPACE;
 
   if (!explicit_launch) {
     const DensePath path = dense_path(L, M);
@@ -475,6 +485,18 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
         const int S = L.tiles[kNarrow] / tpw;
         float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
         rc = launch_gemv16(w, L, x, M, ldx, y, ldy, partial, tpw, nw, stream);
+        if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, L.Npad, S, stream);
+        if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+      }
+    }
+    if (path == kPathGemv16NW) {
+      // the same on wide-format and mixed weights
+      int tpwn = 0, tpww = 0, sn = 0, sw = 0;
+      const int64_t plane = (int64_t)M * L.Npad * 4;
+      if (gemv16_nw_shape(L, device_cus(), std::max<int64_t>(1, have / plane), &tpwn, &tpww, &sn, &sw)) {
+        const int S = sn + sw;
+        float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
+        rc = launch_gemv16_nw(w, L, x, M, ldx, y, ldy, partial, tpwn, tpww, sn, sw, stream);
         if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, L.Npad, S, stream);
         if (rc != CCQ_ERR_UNSUPPORTED) return rc;
       }

@@ -128,6 +128,9 @@ int device_cus();  // compute units of the current device (cached per device)
 // Two to sixteen rows on narrow-format weights (ccq_gemv.hip): K is cut into tiles / tpw shares across workgroups; with
 // more than one share the fp32 partial tiles go to `partial` ([shares][M][N]) and launch_reduce_splits adds them.
 bool gemv16_shape(const Layout& L, int cus, int64_t max_shares, int* tpw_out, int* nw_out);
+bool gemv16_nw_shape(const Layout& L, int cus, int64_t max_shares, int* tpwn_out, int* tpww_out, int* sn_out, int* sw_out);
+int launch_gemv16_nw(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int tpwn,
+                     int tpww, int sn, int sw, void* stream);
 int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int tpw,
                   int nw, void* stream);
 

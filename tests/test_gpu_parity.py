@@ -343,7 +343,7 @@ def test_grouped_all_experts_empty_and_errors():
 
 @pytest.mark.parametrize("kinds,K,N,M", [(["narrow"], 2048, 1024, 16), (["narrow"], 2048, 1024, 8), (["narrow"], 2048, 1024, 64),
                                          (["narrow"], 4096, 256, 24), (["wide"], 4096, 256, 12), (["wide"], 2048, 272, 70),
-                                         (["narrow", "wide"], 4096, 128, 40)])
+                                         (["narrow", "wide"], 4096, 128, 40), (["narrow", "wide"], 4096, 128, 9), (["wide"], 8192, 64, 16)])
 def test_workspace_guard_bands(kinds, K, N, M):
     """The K shares' fp32 partial tiles stay inside the workspace the library asked for: canaries on both sides of a
     workspace of exactly ccq_gemm_workspace_bytes are untouched, and the result does not depend on what the workspace held."""
@@ -364,14 +364,22 @@ def test_workspace_guard_bands(kinds, K, N, M):
     y2 = b.bf16_bits(b.gemm(w, xt, workspace=ws))
     torch.cuda.synchronize()
     assert np.array_equal(y1, y2)
-    if M > 16 or kinds != ["narrow"]:   # a smaller workspace is rejected (the 16-row narrow-format kernel only takes fewer, longer shares of K)
+    if M > 16:   # a smaller workspace is rejected
         with pytest.raises(b.CcqError) as ei:
             b.gemm(w, xt, workspace=buf[band:band + need - 16])
         assert ei.value.status == -5
     else:
-        y3 = b.bf16_bits(b.gemm(w, xt, workspace=buf[band:band + need // 2]))
-        torch.cuda.synchronize()
-        assert_gemm_close(y3, o.matmul(x, c.W()), f"half the workspace {kinds} M={M}")
+        # the 16-row kernels take fewer, longer shares of K when the workspace is smaller; where K does not split that
+        # way the call is either served by the general kernel or rejected, never wrong
+        buf.fill_(0xFF)
+        try:
+            y3 = b.bf16_bits(b.gemm(w, xt, workspace=buf[band:band + need // 2]))
+        except b.CcqError as e:
+            assert e.status == -5 and kinds != ["narrow"]
+        else:
+            torch.cuda.synchronize()
+            assert_gemm_close(y3, o.matmul(x, c.W()), f"half the workspace {kinds} M={M}")
+            assert bool((buf[:band] == 0xFF).all()) and bool((buf[band + need // 2:] == 0xFF).all()), "wrote outside the smaller workspace"
 
 
 @pytest.mark.parametrize("n_narrow,n_wide,what", [(0, 16, "wide, shares of two k-tiles"), (0, 8 * 5, "wide, five shares of one"), (96, 64, "(4,2)"),
@@ -406,3 +414,51 @@ def test_one_row_kernel_every_share_shape(n_narrow, n_wide, what, mode):
     for k in ks:
         got = _gemm_bits(w, synth.one_hot_bf16([int(k)], K))
         assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, [int(k)]].T))), f"{what}: decoded weights differ at column {k}"
+
+
+@pytest.mark.parametrize("n_narrow,n_wide,cap,what", [(0, 16, 32, "(0,1)"), (0, 16, 1, "(0,2): all of K in one share"), (0, 40, 32, "(0,1), five shares"),
+                                                      (64, 32, 32, "(1,1)"), (64, 32, 16, "(2,1)"), (64, 32, 10, "(2,2)"), (64, 32, 8, "(4,1)"),
+                                                      (64, 32, 6, "(4,2)"), (36, 80, 16, "(1,2)"), (100, 56, 32, "(1,1), 32 shares")])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("M", [2, 7, 16])
+def test_sixteen_row_kernel_wide_and_mixed(n_narrow, n_wide, cap, what, mode, M):
+    """Two to sixteen activation rows on wide-format and mixed weights: every (narrow share, wide share) pair of the
+    16-row kernel for those formats (the workspace is sized for `cap` shares, which decides the pair), both scale modes,
+    N not a multiple of the eight row tiles a workgroup holds; decoded weights bit-exact (one-hot rows) and the product
+    within tolerance; rows past M and columns past N untouched."""
+    G = n_narrow + n_wide
+    K, N = 64 * G, 16 * 11 + 5
+    rng = synth.rng(18, G + mode)
+    gf = synth.group_format_map(G, n_wide, rng) if n_narrow else None
+    ofmt = o.F275 if n_narrow == 0 else (o.F2, o.F275)
+    bfmt = [b.WIDE] if n_narrow == 0 else [b.NARROW, b.WIDE]
+    codes = synth.random_codes(N, o.row_bytes(K, ofmt, gf), rng)
+    alpha, beta = synth.cluster_params(N, rng)
+    if mode == 0:
+        scales = synth.scales_log_uniform_fp16(N, G, rng)
+        W = o.decode(K, N, ofmt, codes, scales, alpha, beta, gf)
+        w = b.Weight.from_canonical(K, N, bfmt, codes, scales, alpha, beta, gf, device=DEV)
+    else:
+        nb = o.sq_row_bytes(K, ofmt, gf)
+        sq = rng.integers(0, 256, size=(N, max(nb, 1)), dtype=np.uint8)[:, :nb]
+        ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(N, 1, rng).reshape(N)) * 0.1).astype(np.float16).view(np.uint16)
+        W = o.decode_cs(K, N, ofmt, codes, sq, ssup, alpha, beta, gf)
+        w = b.Weight.from_canonical_compressed(K, N, bfmt, codes, sq, ssup, alpha, beta, gf, device=DEV)
+    ws = torch.empty(cap * M * w.info.padded_N * 4, dtype=torch.uint8, device=DEV)
+
+    def run(x_bits):
+        ld = (N + 7) // 8 * 8 + 8
+        y = torch.full((M + 1, ld), 3.140625, dtype=torch.bfloat16, device=DEV)
+        b.gemm(w, b.bf16_tensor(x_bits, DEV), out=y[:M, :N], workspace=ws)
+        torch.cuda.synchronize()
+        bits = b.bf16_bits(y)
+        assert np.all(bits[:M, N:] == 0x4049) and np.all(bits[M] == 0x4049), "wrote past the output"
+        return bits[:M, :N]
+    x = synth.activations_bf16(M, K, synth.rng(18, 900 + G + M))
+    assert_gemm_close(run(x), o.matmul(x, W), f"{M} rows, {what}, scale mode {mode}")
+    ks = np.concatenate([[K - 1, 0, 59, 60, 61, 62, 63, 64, K - 64, K - 4, 17], synth.rng(18, 901).integers(0, K, 21)])
+    for i in range(0, len(ks), M):
+        kk = [int(k) for k in ks[i:i + M]]
+        kk += [kk[-1]] * (M - len(kk))
+        got = run(synth.one_hot_bf16(kk, K))
+        assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, kk].T))), f"{what}: decoded weights differ at columns {kk}"
