@@ -296,7 +296,67 @@ __device__ __forceinline__ u32x4 wide_frag(const u32x4 v, uint32_t kq, int t) {
   return o;
 }
 
-template <int TPWN, int TPWW, int SM>
+// The same for the hybrid 16-bit word of Sec. 3.2 (which takes the wide kind's place: 8 groups per k-tile, three k-steps
+// per group): word 4 t + kq of the group holds weights 7 word .. 7 word + 6 (word 9: weight 63 only), the chunk starts at
+// element min(7 word & ~1, 56), k-slots {0, 1, 3, 4, 5, 6, 2, -} (the order in which the decode pairs the states).
+__device__ __forceinline__ u32x4 h16_frag(const u32x4 v, uint32_t kq, int t) {
+  u32x4 o = {0u, 0u, 0u, 0u};
+  const uint32_t word = 4u * t + kq;
+  if (word == 9u) {
+    o.x = v.w >> 16;                                       // element 63 of the chunk that starts at 56
+  } else if (word < 9u) {
+    if (word & 1u) {                                       // the word starts at the chunk's second element
+      o.x = __builtin_amdgcn_perm(v.y, v.x, 0x05040302u);  // elements 1, 2
+      o.y = v.z;                                            // 4, 5
+      o.z = v.w;                                            // 6, 7
+      o.w = v.y >> 16;                                      // 3
+    } else {
+      o.x = v.x;                                            // 0, 1
+      o.y = __builtin_amdgcn_perm(v.z, v.y, 0x05040302u);  // 3, 4
+      o.z = __builtin_amdgcn_perm(v.w, v.z, 0x05040302u);  // 5, 6
+      o.w = v.y & 0xFFFFu;                                  // 2
+    }
+  }
+  return o;
+}
+// First element of the 16-byte chunk that holds the activations of (quarter kq, k-step t) of a group.
+template <bool H16>
+__device__ __forceinline__ uint32_t chunk_first(uint32_t kq, int t) {
+  if constexpr (H16) return min((7u * (4u * t + kq)) & ~1u, 56u);
+  else return min(18u * kq + 6u * t, 56u);
+}
+template <bool H16>
+__device__ __forceinline__ u32x4 kind_frag(const u32x4 v, uint32_t kq, int t) {
+  if constexpr (H16) return h16_frag(v, kq, t);
+  else return wide_frag(v, kq, t);
+}
+// Weight fragment (k-step t of group j of a k-tile held in `seg`): 8 bf16 integers 128 + state.
+//   wide: two 8-bit codes {0, b, 0, a}, windows [4, 2, 0] with mask 0xF of both at once, slots 6 and 7 unused;
+//   hybrid word w = (3,3,2) code | (3,4,2) code: seven 3-bit states at the shifts [13, 11, 9, 6, 4, 2, 0], mask 0x7
+//   (Table 1).  v = w | w << 18 puts a second copy of the word 18 bits up, so that the state at shift s - 2 of the copy
+//   lands 16 bits above the state at shift s: one shift and one and-or cut out two states.
+template <bool H16>
+__device__ __forceinline__ u32x4 kind_weights(const u32x4 seg, int j, uint32_t mask, uint32_t c4300) {
+  const uint32_t d = (j >> 1) == 0 ? seg.x : ((j >> 1) == 1 ? seg.y : ((j >> 1) == 2 ? seg.z : seg.w));
+  u32x4 wv;
+  if constexpr (H16) {
+    const uint32_t w = (j & 1) ? (d >> 16) : (d & 0xFFFFu);
+    const uint32_t v = w | (w << 18);
+    wv.x = and_or(v >> 13, mask, c4300);  // states 0, 1
+    wv.y = and_or(v >> 6, mask, c4300);   // states 3, 4
+    wv.z = and_or(v >> 2, mask, c4300);   // states 5, 6
+    wv.w = and_or(v >> 9, mask, c4300);   // state 2; the upper half is an unused k-slot (zero activation)
+  } else {
+    const uint32_t pp = __builtin_amdgcn_perm(0u, d, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // {0, b, 0, a}
+    wv.x = and_or(pp >> 4, mask, c4300);
+    wv.y = and_or(pp >> 2, mask, c4300);
+    wv.z = and_or(pp, mask, c4300);
+    wv.w = wv.z;                          // unused k-slots: zero activations
+  }
+  return wv;
+}
+
+template <int TPWN, int TPWW, int SM, bool H16 = false>
 __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
   constexpr int NGN = TPWN * 4, NGW = TPWW * 8;                 // groups per narrow / wide share
   constexpr int REGION_N = NGN * 8 * 16 + NGN * 4 * 16;         // private LDS bytes per wavefront: fragments, then start-value records
@@ -314,7 +374,7 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
   u32x4* lds_x = reinterpret_cast<u32x4*>(region);
   const uint8_t* code_row = a.codes + (size_t)rtile * (size_t)a.row_tile_bytes;
   const uint16_t* scale_row = a.scales + (size_t)rtile * (size_t)a.row_tile_scale_halfs;
-  uint32_t c4300 = 0x43004300u, mask_n = 0x003F003Fu, mask_w = 0x000F000Fu;
+  uint32_t c4300 = 0x43004300u, mask_n = 0x003F003Fu, mask_w = H16 ? 0x00070007u : 0x000F000Fu;
   float magic = 8388608.f;
   asm volatile("" : "+v"(c4300), "+s"(mask_n), "+s"(mask_w), "+v"(magic));   // register values, not literals: v_and_or_b32 gets selected
   uint32_t ssup = 0;
@@ -409,7 +469,7 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
     const uint32_t g = a.meta ? (uint32_t)a.meta[(uint32_t)a.meta_wide + pg] : min(pg, (uint32_t)a.g_last);
     u32x4 xc[3];
 #pragma unroll
-    for (int t = 0; t < 3; ++t) xc[t] = load_chunk16(a.x + (g << 6) + min(18u * skq + 6u * t, 56u));
+    for (int t = 0; t < 3; ++t) xc[t] = load_chunk16(a.x + (g << 6) + chunk_first<H16>(skq, t));
     if constexpr (SM == 1) ssup = a.scale_super[row];
     u32x4 cw[TPWW][3];
     u32x4 sw[TPWW];
@@ -420,15 +480,16 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
       else sw[i] = u32x4{0u, 0u, 0u, 0u};
     }
     __builtin_amdgcn_sched_barrier(0);
-    const uint8_t* cb = code_row + (size_t)a.tiles_n * 1024u + (size_t)t0 * 2816u;
+    constexpr uint32_t kTile = H16 ? 2560u : 2816u, kLast = H16 ? 31u : 47u;
+    const uint8_t* cb = code_row + (size_t)a.tiles_n * 1024u + (size_t)t0 * kTile;
 #pragma unroll
     for (int i = 0; i < TPWW; ++i) {
-      const uint8_t* t = cb + i * 2816u + lane * 16u;
+      const uint8_t* t = cb + i * kTile + lane * 16u;
       cw[i][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
       cw[i][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
-      // the third segment has entries for 48 lanes only; the lanes above re-read the last entry (their k-slots meet
-      // zero activations, and every bit pattern decodes to a finite value)
-      cw[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47u ? (lane - 47u) * 16u : 0u)));
+      // the third segment has entries for 48 lanes only (32 for the hybrid word); the lanes above re-read the last entry
+      // (their k-slots meet zero activations, and every bit pattern decodes to a finite value)
+      cw[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > kLast ? (lane - kLast) * 16u : 0u)));
     }
     __builtin_amdgcn_sched_barrier(0);
     float* lds_c = reinterpret_cast<float*>(region + NGW * 12 * 16);
@@ -436,7 +497,7 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
       float sum = 0.f;
 #pragma unroll
       for (int t = 0; t < 3; ++t) {
-        const u32x4 o = wide_frag(xc[t], skq, t);
+        const u32x4 o = kind_frag<H16>(xc[t], skq, t);
         sum += frag_sum(o);
         if (lane < (uint32_t)(4 * NGW)) lds_x[(slg * 3u + t) * 4u + skq] = o;
       }
@@ -447,11 +508,14 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
     for (int i = 0; i < TPWW; ++i) {
       uint32_t fields[4] = {0u, 0u, 0u, 0u};
       if constexpr (SM == 1) {
-        const int src = (int)((48u + n) * 4u);
-        fields[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].x);
-        fields[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].y);
-        fields[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].z);
-        fields[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].w);
+        // wide: byte 21 of the group, held by the row's quarter-3 lane in segment 1; hybrid word: word 9 of the group
+        // (scale mask 0x1FFF of Table 1), held by the row's quarter-1 lane in segment 2
+        const int src = (int)(((H16 ? 16u : 48u) + n) * 4u);
+        const u32x4 held = cw[i][H16 ? 2 : 1];
+        fields[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.x);
+        fields[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.y);
+        fields[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.z);
+        fields[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.w);
       }
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -460,21 +524,18 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
 #pragma unroll
         for (int t = 0; t < 3; ++t) {
           const u32x4 xf = lds_x[(lg * 3 + t) * 4 + kq];
-          const u32x4 seg = cw[i][t];
-          const uint32_t d = (j >> 1) == 0 ? seg.x : ((j >> 1) == 1 ? seg.y : ((j >> 1) == 2 ? seg.z : seg.w));
-          const uint32_t pp = __builtin_amdgcn_perm(0u, d, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // {0, b, 0, a}
-          const uint32_t w0 = and_or(pp >> 4, mask_w, c4300);   // Table 1: shifts [4, 2, 0], mask 0xF, both codes at once
-          const uint32_t w1 = and_or(pp >> 2, mask_w, c4300);
-          const uint32_t w2 = and_or(pp, mask_w, c4300);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.x, xf.y}), __builtin_bit_cast(bf16x4, u32x2{w0, w1}), p, 0, 0, 0);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.z, xf.w}), __builtin_bit_cast(bf16x4, u32x2{w2, w2}), p, 0, 0, 0);
+          const u32x4 wv = kind_weights<H16>(cw[i][t], j, mask_w, c4300);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.x, xf.y}), __builtin_bit_cast(bf16x4, u32x2{wv.x, wv.y}), p, 0, 0, 0);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.z, xf.w}), __builtin_bit_cast(bf16x4, u32x2{wv.z, wv.w}), p, 0, 0, 0);
         }
         float s;
         if constexpr (SM == 0) {
           const uint32_t sd = (j >> 1) == 0 ? sw[i].x : ((j >> 1) == 1 ? sw[i].y : ((j >> 1) == 2 ? sw[i].z : sw[i].w));
           s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else if constexpr (H16) {
+          s = (float)((fields[j >> 1] >> (16 * (j & 1))) & 0x1FFFu);    // the field alone; the row's super scale multiplies the sum once
         } else {
-          s = (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu);   // the field alone; the row's super scale multiplies the sum once
+          s = (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu);
         }
         acc = __builtin_fmaf(s, p[0], acc);
       }
@@ -680,7 +741,7 @@ struct Args16NW {
   int32_t g_last, n_last;
 };
 
-template <int TPWN, int TPWW, int SM, int NW>
+template <int TPWN, int TPWW, int SM, int NW, bool H16 = false>
 __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
   constexpr int NGN = TPWN * 4, NGW = TPWW * 8;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -695,7 +756,7 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
   const uint32_t prow = min(rtile * 16u + n, (uint32_t)a.n_last);
   const uint8_t* code_row = a.codes + (size_t)rtile * (size_t)a.row_tile_bytes;
   const uint16_t* scale_row = a.scales + (size_t)rtile * (size_t)a.row_tile_scale_halfs;
-  uint32_t c4300 = 0x43004300u, mask_n = 0x003F003Fu, mask_w = 0x000F000Fu;
+  uint32_t c4300 = 0x43004300u, mask_n = 0x003F003Fu, mask_w = H16 ? 0x00070007u : 0x000F000Fu;
   float magic = 8388608.f;
   asm volatile("" : "+v"(c4300), "+s"(mask_n), "+s"(mask_w), "+v"(magic));
   typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -810,7 +871,7 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
       const uint32_t g = a.meta ? (uint32_t)a.meta[(uint32_t)a.meta_wide + pg] : min(pg, (uint32_t)a.g_last);
       const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + (size_t)g * 64u;
 #pragma unroll
-      for (int t = 0; t < 3; ++t) xv[i][t] = load_chunk16(p + min(18u * q + 6u * t, 56u));
+      for (int t = 0; t < 3; ++t) xv[i][t] = load_chunk16(p + chunk_first<H16>(q, t));
     }
     u32x4 cw[TPWW][3];
     u32x4 sw[TPWW];
@@ -821,13 +882,14 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
       else sw[i] = u32x4{0u, 0u, 0u, 0u};
     }
     __builtin_amdgcn_sched_barrier(0);
-    const uint8_t* cb = code_row + (size_t)a.tiles_n * 1024u + (size_t)t0 * 2816u;
+    constexpr uint32_t kTile = H16 ? 2560u : 2816u, kLast = H16 ? 31u : 47u;
+    const uint8_t* cb = code_row + (size_t)a.tiles_n * 1024u + (size_t)t0 * kTile;
 #pragma unroll
     for (int i = 0; i < TPWW; ++i) {
-      const uint8_t* t = cb + i * 2816u + lane * 16u;
+      const uint8_t* t = cb + i * kTile + lane * 16u;
       cw[i][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t));
       cw[i][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024));
-      cw[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > 47u ? (lane - 47u) * 16u : 0u)));
+      cw[i][2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 2048 - (lane > kLast ? (lane - kLast) * 16u : 0u)));
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -838,7 +900,7 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
       u32x4 o[3];
 #pragma unroll
       for (int t = 0; t < 3; ++t) {
-        o[t] = wide_frag(xv[i][t], uq, t);
+        o[t] = kind_frag<H16>(xv[i][t], uq, t);
         s += frag_sum(o[t]);
       }
       s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));   // the four quarters of a (group, row): neighbouring lanes
@@ -855,11 +917,12 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
     for (int i = 0; i < TPWW; ++i) {
       uint32_t fields[4] = {0u, 0u, 0u, 0u};
       if constexpr (SM == 1) {
-        const int src = (int)((48u + n) * 4u);
-        fields[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].x);
-        fields[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].y);
-        fields[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].z);
-        fields[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)cw[i][1].w);
+        const int src = (int)(((H16 ? 16u : 48u) + n) * 4u);
+        const u32x4 held = cw[i][H16 ? 2 : 1];
+        fields[0] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.x);
+        fields[1] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.y);
+        fields[2] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.z);
+        fields[3] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)held.w);
       }
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -868,20 +931,15 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
 #pragma unroll
         for (int t = 0; t < 3; ++t) {
           const u32x4 xf = lds_x[((lg * 3 + t) * 4 + kq) * 16 + n];     // here n is the activation row of this lane's A fragment
-          const u32x4 seg = cw[i][t];
-          const uint32_t d = (j >> 1) == 0 ? seg.x : ((j >> 1) == 1 ? seg.y : ((j >> 1) == 2 ? seg.z : seg.w));
-          const uint32_t pp = __builtin_amdgcn_perm(0u, d, (j & 1) ? 0x0C030C02u : 0x0C010C00u);  // {0, b, 0, a}
-          u32x4 wv;
-          wv.x = and_or(pp >> 4, mask_w, c4300);   // Table 1: shifts [4, 2, 0], mask 0xF, both codes at once
-          wv.y = and_or(pp >> 2, mask_w, c4300);
-          wv.z = and_or(pp, mask_w, c4300);
-          wv.w = c4300;                            // unused k-slots: zero activations
+          const u32x4 wv = kind_weights<H16>(cw[i][t], j, mask_w, c4300);
           p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xf), __builtin_bit_cast(bf16x8, wv), p, 0, 0, 0);
         }
         float sc;
         if constexpr (SM == 0) {
           const uint32_t sd = (j >> 1) == 0 ? sw[i].x : ((j >> 1) == 1 ? sw[i].y : ((j >> 1) == 2 ? sw[i].z : sw[i].w));
           sc = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+        } else if constexpr (H16) {
+          sc = (float)((fields[j >> 1] >> (16 * (j & 1))) & 0x1FFFu);
         } else {
           sc = (float)((fields[j >> 1] >> (16 * (j & 1) + 8)) & 0xFu);
         }
@@ -984,10 +1042,14 @@ int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, v
 // (every lane of a wavefront then stages one (group, quarter) of the wide share's activations).  false: no wide
 // k-tiles, the hybrid word, or K does not split into at most 16 such shares (the caller uses the general kernel).
 bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out) {
-  if (L.h16 || L.tiles[kWide] < 1) return false;
+  if (L.tiles[kWide] < 1) return false;   // the hybrid word is a wide kind of its own (never mixed)
   const int tn = L.tiles[kNarrow], tw = L.tiles[kWide];
   if (tn == 0) {
-    for (int pw : {2, 1}) {   // config 3, all wide: 21.7 us with shares of two k-tiles, 23.3 us with shares of one
+    // shares of one k-tile (512 weights per row, as much as the two narrow k-tiles the narrow kernel prefers) while the
+    // chip holds all wavefronts at once (32 per CU); beyond that shares of two (config 3, all wide, 28672 wavefronts of
+    // one k-tile: 23.3 us against 21.7 us with shares of two)
+    const bool fits = (int64_t)L.row_tiles * tw <= (int64_t)32 * device_cus();
+    for (int pw : {fits ? 1 : 2, fits ? 2 : 1}) {
       if (tw % pw != 0 || tw / pw > 16) continue;
       *tpwn_out = 0; *tpww_out = pw; *wn_out = 0; *ww_out = tw / pw;
       return true;
@@ -1007,6 +1069,12 @@ bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, i
 
 namespace gemv {
 typedef void (*KernelNW)(const ArgsNW);
+template <int SM>
+static KernelNW pick_nw_h16(int tpww) {
+  if (tpww == 1) return kernel_nw<0, 1, SM, true>;
+  if (tpww == 2) return kernel_nw<0, 2, SM, true>;
+  return nullptr;
+}
 template <int SM>
 static KernelNW pick_nw(int tpwn, int tpww) {
   if (tpww == 1) {
@@ -1030,7 +1098,7 @@ static KernelNW pick_nw(int tpwn, int tpww) {
 
 int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww) {
   using namespace gemv;
-  if (L.h16 || ww < 1 || wn < 0 || wn + ww > 16 || wn * tpwn != L.tiles[kNarrow] || ww * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
+  if (ww < 1 || wn < 0 || (L.h16 && wn != 0) || wn + ww > 16 || wn * tpwn != L.tiles[kNarrow] || ww * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
   if (L.row_tile_bytes * (int64_t)L.row_tiles >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
   ArgsNW a;
   a.codes = static_cast<const uint8_t*>(w->codes);
@@ -1051,7 +1119,8 @@ int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y,
   a.cneg_w = -(128.f + L.zp[kWide]);
   a.g_last = L.G - 1;
   a.n_last = L.N - 1;
-  const KernelNW k = L.scale_mode == 0 ? pick_nw<0>(tpwn, tpww) : pick_nw<1>(tpwn, tpww);
+  const KernelNW k = L.h16 ? (L.scale_mode == 0 ? pick_nw_h16<0>(tpww) : pick_nw_h16<1>(tpww))
+                           : (L.scale_mode == 0 ? pick_nw<0>(tpwn, tpww) : pick_nw<1>(tpwn, tpww));
   if (!k) return CCQ_ERR_UNSUPPORTED;
   const size_t region_n = (size_t)tpwn * 4 * (8 * 16 + 4 * 16), region_w = (size_t)tpww * 8 * (12 * 16 + 4 * 16);
   const size_t lds = std::max<size_t>((size_t)wn * region_n + (size_t)ww * region_w, 1024);   // at most 16 * 4 KiB; the K reduction reuses the start
@@ -1068,7 +1137,7 @@ int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y,
 // N = 28672 a share's partial tile is as many bytes as 1/6 of a wide k-tile column block), shorter ones only when the
 // long ones leave compute units without a workgroup.  false: no wide k-tiles, the hybrid word, or no such split.
 bool gemv16_nw_shape(const Layout& L, int cus, int64_t max_shares, int* tpwn_out, int* tpww_out, int* sn_out, int* sw_out) {
-  if (L.h16 || L.tiles[kWide] < 1) return false;
+  if (L.tiles[kWide] < 1) return false;   // the hybrid word is a wide kind of its own (never mixed)
   const int tn = L.tiles[kNarrow], tw = L.tiles[kWide], nw = 8;
   const int64_t row_blocks = (L.row_tiles + nw - 1) / nw;
   const int64_t cap = std::min<int64_t>(max_shares, kMaxSplitsK);
@@ -1101,7 +1170,7 @@ int launch_gemv16_nw(const ccq_weight* w, const Layout& L, const void* x, int M,
                      int tpww, int sn, int sw, void* stream) {
   using namespace gemv;
   constexpr int nw = 8;
-  if (M < 1 || M > 16 || L.h16 || sw < 1 || sn < 0 || sn * tpwn != L.tiles[kNarrow] || sw * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
+  if (M < 1 || M > 16 || sw < 1 || sn < 0 || (L.h16 && sn != 0) || sn * tpwn != L.tiles[kNarrow] || sw * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
   const int S = sn + sw;
   if (S > kMaxSplitsK || (S > 1 && !partial)) return CCQ_ERR_UNSUPPORTED;
   if (L.row_tile_bytes * (int64_t)L.row_tiles >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
@@ -1133,7 +1202,10 @@ int launch_gemv16_nw(const ccq_weight* w, const Layout& L, const void* x, int M,
   typedef void (*Kernel16NW)(const Args16NW);
   Kernel16NW k = nullptr;
   const int key = tpwn * 10 + tpww;
-  if (L.scale_mode == 0) {
+  if (L.h16) {
+    if (L.scale_mode == 0) k = tpww == 1 ? kernel16_nw<0, 1, 0, nw, true> : (tpww == 2 ? kernel16_nw<0, 2, 0, nw, true> : nullptr);
+    else k = tpww == 1 ? kernel16_nw<0, 1, 1, nw, true> : (tpww == 2 ? kernel16_nw<0, 2, 1, nw, true> : nullptr);
+  } else if (L.scale_mode == 0) {
     switch (key) {
       case 1: k = kernel16_nw<0, 1, 0, nw>; break;
       case 2: k = kernel16_nw<0, 2, 0, nw>; break;

@@ -152,7 +152,7 @@ static DensePath dense_path(const Layout& L, int M) {
     if (gemv16_shape(L, 256, kMaxSplitsK, &tpw, &nw)) return kPathGemv16;
   }
   // two to sixteen rows on wide-format and mixed weights: the 16-row kernel for those formats, where K splits its way
-  if (!narrow_only && !L.h16 && M >= 2 && M < kMidMinM) {
+  if (!narrow_only && M >= 2 && M < kMidMinM) {
     int tpwn = 0, tpww = 0, sn = 0, sw = 0;
     if (gemv16_nw_shape(L, 256, kMaxSplitsK, &tpwn, &tpww, &sn, &sw)) return kPathGemv16NW;
   }

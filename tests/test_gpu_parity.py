@@ -462,3 +462,40 @@ def test_sixteen_row_kernel_wide_and_mixed(n_narrow, n_wide, cap, what, mode, M)
         kk += [kk[-1]] * (M - len(kk))
         got = run(synth.one_hot_bf16(kk, K))
         assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, kk].T))), f"{what}: decoded weights differ at columns {kk}"
+
+
+@pytest.mark.parametrize("kind", ["wide", "h16"])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_one_row_kernel_more_wavefronts_than_the_chip_holds(kind, mode):
+    """With more one-k-tile shares than the chip holds wavefronts (521 row tiles x 16 k-tiles > 32 x 256) the one-row
+    kernel takes shares of two wide k-tiles.  Sampled output channels against the oracle; one-hot rows bit-exact."""
+    K, N = 8192, 16 * 521
+    G = K // 64
+    rng = synth.rng(19, mode + (7 if kind == "h16" else 0))
+    rows = np.concatenate([np.arange(16), np.arange(4160, 4176), np.arange(N - 16, N)])
+    ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(N, 1, rng).reshape(N)) * (0.1 if kind == "wide" else 0.002)).astype(np.float16).view(np.uint16)
+    scales = synth.scales_log_uniform_fp16(N, G, rng)
+    if kind == "wide":
+        codes = synth.random_codes(N, G * 22, rng)
+        if mode == 0:
+            w = b.Weight.from_canonical(K, N, [b.WIDE], codes, scales, device=DEV)
+            W = o.decode(K, len(rows), o.F275, codes[rows], scales[rows])
+        else:
+            w = b.Weight.from_canonical_compressed(K, N, [b.WIDE], codes, np.zeros((N, 0), np.uint8), ssup, device=DEV)
+            W = o.decode_cs(K, len(rows), o.F275, codes[rows], np.zeros((len(rows), 0), np.uint8), ssup[rows])
+    else:
+        codes = synth.random_codes(N, o.h16_row_bytes(K), rng)
+        if mode == 0:
+            w = b.Weight.from_canonical(K, N, b.H16, codes, scales, device=DEV)
+            W = o.h16_decode(K, len(rows), codes[rows], scales[rows])
+        else:
+            w = b.Weight.from_canonical_compressed(K, N, b.H16, codes, None, ssup, device=DEV)
+            W = o.h16_decode_cs(K, len(rows), codes[rows], ssup[rows])
+    x = synth.activations_bf16(1, K, synth.rng(19, 50))
+    assert_gemm_close(_gemm_bits(w, x)[:, rows], o.matmul(x, W), f"one row, {kind}, scale mode {mode}, shares of two k-tiles")
+    for k in (0, 62, 63, 511, 512, K - 1):
+        got = _gemm_bits(w, synth.one_hot_bf16([k], K))[:, rows]
+        want = W[:, [k]].T
+        if kind == "h16" and mode == 1:
+            want = want.astype(np.float32).astype(np.float64)   # the kernel's single fp32 rounding of field x super scale x state
+        assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(want))), f"{kind} mode {mode}: decoded weights differ at column {k}"
