@@ -444,7 +444,7 @@ __global__ void __launch_bounds__(256) ccq_mid_kernel(const MidArgs a) {
       const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       const float val = acc[i][r];  // by value: bit-casting the element lvalue itself reads element 0
       if (m < Me && n <= a.n_last) {
-        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + row_off + m) * a.N + n] = val;
+        if (gridDim.y > 1) __builtin_nontemporal_store(val, &a.partial[((int64_t)split * a.M + row_off + m) * a.N + n]);
         else a.y[(int64_t)(row_off + m) * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
       }
     }
@@ -663,7 +663,7 @@ __global__ void __launch_bounds__(256) ccq_midr_narrow_kernel(const MidArgs a) {
       const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       const float val = acc[i][r];
       if (m < Me && n <= a.n_last) {
-        if (gridDim.y > 1) a.partial[((int64_t)split * a.M + row_off + m) * a.N + n] = val;
+        if (gridDim.y > 1) __builtin_nontemporal_store(val, &a.partial[((int64_t)split * a.M + row_off + m) * a.N + n]);
         else a.y[(int64_t)(row_off + m) * a.ldy + n] = (uint16_t)(pack_bf16_m(val, 0.f) & 0xFFFFu);
       }
     }

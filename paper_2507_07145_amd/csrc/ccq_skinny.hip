@@ -956,7 +956,7 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
             const int m = mt * 16 + 4 * kq + r;
             if (m < rows_valid && n <= a.n_last) {
               const int64_t prow = (int64_t)off0 + m0 + m;
-              if (a.S > 1) a.partial[((int64_t)split * a.M + prow) * a.N + n] = acc[rt][mt][r];
+              if (a.S > 1) __builtin_nontemporal_store(acc[rt][mt][r], &a.partial[((int64_t)split * a.M + prow) * a.N + n]);
               else a.y[prow * a.ldy + n] = f32_to_bf16_rne(acc[rt][mt][r]);
             }
           }
@@ -1240,7 +1240,7 @@ __global__ void __launch_bounds__(256) ccq_reduce_splits_kernel(const float* par
   if (n >= N) return;
   f32x4 v[SMAX];
 #pragma unroll
-  for (int s = 0; s < SMAX; ++s) v[s] = *reinterpret_cast<const f32x4*>(partial + (int64_t)min(s, S - 1) * total + i);
+  for (int s = 0; s < SMAX; ++s) v[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(partial + (int64_t)min(s, S - 1) * total + i));
   f32x4 sum = v[0];
 #pragma unroll
   for (int s = 1; s < SMAX; ++s)
@@ -1520,7 +1520,7 @@ __global__ void __launch_bounds__(64 * NW, 8 / NW) ccq_rows_kernel(const RowsArg
       for (int e = 0; e < 4; ++e) {
         const int m = m0 + mt * 16 + 4 * kq + e;
         if (m < a.M) {
-          if (gridDim.y > 1) a.partial[((int64_t)split * a.M + m) * a.N + n] = acc[mt][e];
+          if (gridDim.y > 1) __builtin_nontemporal_store(acc[mt][e], &a.partial[((int64_t)split * a.M + m) * a.N + n]);
           else a.y[(int64_t)m * a.ldy + n] = f32_to_bf16_rne(acc[mt][e]);
         }
       }
