@@ -73,3 +73,123 @@ def test_random_case(seed):
     got = b.bf16_bits(b.gemm(w, b.bf16_tensor(synth.one_hot_bf16(ks, K), DEV)))
     torch.cuda.synchronize()
     assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(c.W()[:, ks].T))), what + ": decoded weights differ"
+
+
+def _ragged_draw(rng):
+    family = ["narrow", "wide", "mixed", "h16"][int(rng.integers(0, 4))]
+    mode = int(rng.integers(0, 2))
+    G = int(rng.integers(2, 41))
+    n_wide = int(rng.integers(1, G)) if family == "mixed" else None
+    N = int(rng.integers(1, 600)) if rng.random() < 0.8 else int(rng.integers(600, 2600))
+    M = int(rng.choice([1, 1, 2, 3, 5, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200]))
+    return family, mode, 64 * G, N, M, n_wide
+
+
+def _ragged_arrays(family, mode, K, N, gf, rng):
+    """Canonical arrays of one random matrix in any format and scale mode, and its oracle-decoded weights."""
+    G = K // 64
+    a = {"scales": None, "sq": None, "ssup": None, "alpha": None, "beta": None}
+    if mode == 1:
+        a["ssup"] = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(N, 1, rng).reshape(N)) * 0.1).astype(np.float16).view(np.uint16)
+    else:
+        a["scales"] = synth.scales_log_uniform_fp16(N, G, rng)
+    if family == "h16":
+        a["codes"] = synth.random_codes(N, o.h16_row_bytes(K), rng)
+        a["W"] = o.h16_decode(K, N, a["codes"], a["scales"]) if mode == 0 else o.h16_decode_cs(K, N, a["codes"], a["ssup"])
+        return a
+    ofmt = {"narrow": o.F2, "wide": o.F275, "mixed": (o.F2, o.F275)}[family]
+    a["codes"] = synth.random_codes(N, o.row_bytes(K, ofmt, gf), rng)
+    if family != "wide":
+        a["alpha"], a["beta"] = synth.cluster_params(N, rng)
+    if mode == 0:
+        a["W"] = o.decode(K, N, ofmt, a["codes"], a["scales"], a["alpha"], a["beta"], gf)
+    else:
+        nb = o.sq_row_bytes(K, ofmt, gf)
+        a["sq"] = rng.integers(0, 256, size=(N, max(nb, 1)), dtype=np.uint8)[:, :nb]
+        a["W"] = o.decode_cs(K, N, ofmt, a["codes"], a["sq"], a["ssup"], a["alpha"], a["beta"], gf)
+    return a
+
+
+def _upload(family, mode, K, N, gf, parts):
+    """Device weight of one matrix (`parts` = one set of arrays) or of a stack of experts (a list of sets)."""
+    bfmt = {"narrow": [b.NARROW], "wide": [b.WIDE], "mixed": [b.NARROW, b.WIDE], "h16": b.H16}[family]
+    experts = len(parts) if isinstance(parts, list) else None
+
+    def get(key):
+        if experts is None:
+            return parts[key]
+        return None if parts[0][key] is None else np.stack([p[key] for p in parts])
+    if mode == 0:
+        return b.Weight.from_canonical(K, N, bfmt, get("codes"), get("scales"), get("alpha"), get("beta"), gf, device=DEV, experts=experts)
+    return b.Weight.from_canonical_compressed(K, N, bfmt, get("codes"), get("sq"), get("ssup"), get("alpha"), get("beta"), gf, device=DEV,
+                                              experts=experts)
+
+
+def _ragged_weight(family, mode, K, N, n_wide, seed):
+    rng = synth.rng(41, seed)
+    gf = synth.group_format_map(K // 64, n_wide, rng) if family == "mixed" else None
+    a = _ragged_arrays(family, mode, K, N, gf, rng)
+    return _upload(family, mode, K, N, gf, a), a["W"]
+
+
+@pytest.mark.parametrize("seed", range(160))
+def test_random_ragged_case(seed):
+    """Any K that is a multiple of the group size (Sec. 3.1), any N, any per-group format map (Sec. 3.3), the hybrid word
+    (Sec. 3.2) and both scale modes (Sec. 3.4), drawn at random: the product within tolerance, the decoded weights bit
+    for bit, and nothing written outside the M x N result."""
+    rng = np.random.default_rng(2000 + seed)
+    family, mode, K, N, M, n_wide = _ragged_draw(rng)
+    what = f"seed {seed}: {family} scale mode {mode} K={K} N={N} M={M} wide groups {n_wide}"
+    print(what, flush=True)
+    w, W = _ragged_weight(family, mode, K, N, n_wide, seed)
+    ld = (N + 7) // 8 * 8 + 8
+
+    def run(x_bits):
+        y = torch.full((M + 1, ld), 3.140625, dtype=torch.bfloat16, device=DEV)
+        b.gemm(w, b.bf16_tensor(x_bits, DEV), out=y[:M, :N])
+        torch.cuda.synchronize()
+        bits = b.bf16_bits(y)
+        assert np.all(bits[:M, N:] == 0x4049) and np.all(bits[M] == 0x4049), what + ": written outside the result"
+        return bits[:M, :N]
+
+    x = synth.activations_bf16(M, K, synth.rng(41, 1000 + seed))
+    assert_gemm_close(run(x), o.matmul(x, W), what, rounded=(x, W) if M > 16 else None)
+    ks = rng.integers(0, K, M)
+    ks[:min(M, 3)] = [K - 1, 0, K - 64][:min(M, 3)]
+    assert np.array_equal(canon_zero(run(synth.one_hot_bf16(ks, K))), canon_zero(o.to_bf16_bits(W[:, ks].T))), what + ": decoded weights differ"
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_ragged_grouped_case(seed):
+    """The same through the grouped entry point (Sec. 4.2, Table 5): a random number of experts with random row
+    counts, zero included, with and without the host copy of the offsets."""
+    from cases import grouped_rounded_weight_sigma
+    rng = np.random.default_rng(3000 + seed)
+    family = ["narrow", "wide", "mixed", "h16"][int(rng.integers(0, 4))]
+    mode = int(rng.integers(0, 2))
+    G = int(rng.integers(2, 25))
+    K, N, E, T = 64 * G, int(rng.integers(1, 300)), int(rng.integers(2, 9)), 50
+    most = int(rng.choice([1, 4, 16, 17, 40, 130]))
+    counts = [int(min(most, c)) for c in rng.choice([0, 0, 1, 1, 2, 5, 16, 17, 33, 40, 70, 130], size=E)]
+    if sum(counts) == 0:
+        counts[0] = 1
+    what = f"seed {seed}: grouped {family} scale mode {mode} K={K} N={N} rows per expert {counts}"
+    print(what, flush=True)
+    wrng = synth.rng(42, seed)
+    gf = synth.group_format_map(G, int(rng.integers(1, G)), wrng) if family == "mixed" else None
+    parts = [_ragged_arrays(family, mode, K, N, gf, wrng) for _ in range(E)]
+    w = _upload(family, mode, K, N, gf, parts)
+    x = synth.activations_bf16(T, K, synth.rng(42, 1000 + seed))
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    P = int(offs[-1])
+    rows = rng.integers(0, T, size=P).astype(np.int32)
+    ref = np.concatenate([o.matmul(x[rows[offs[e]:offs[e + 1]]], parts[e]["W"]) for e in range(E) if counts[e] > 0])
+    sigma = grouped_rounded_weight_sigma(x, rows, offs, lambda e: parts[e]["W"])
+    ld = (N + 7) // 8 * 8 + 8
+    for host_offsets in (offs, None):
+        y = torch.full((P + 1, ld), 3.140625, dtype=torch.bfloat16, device=DEV)
+        b.grouped_gemm(w, b.bf16_tensor(x, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), host_offsets, out=y[:P, :N])
+        torch.cuda.synchronize()
+        bits = b.bf16_bits(y)
+        assert np.all(bits[:P, N:] == 0x4049) and np.all(bits[P] == 0x4049), what + ": written outside the result"
+        assert_gemm_close(bits[:P, :N], ref, what + f", host offsets {'given' if host_offsets is not None else 'absent'}", rounded=sigma)
