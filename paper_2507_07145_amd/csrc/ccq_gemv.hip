@@ -245,6 +245,142 @@ __global__ void __launch_bounds__(1024) kernel(const Args a) {
   }
 }
 
+// ---- two to four activation rows on narrow-format weights -----------------------------------------------------------
+// The same kernel with MFMA 4x4x4 used as it is meant: lane l of a 4x4 block supplies the activation fragment of row
+// l % 4 (in `kernel` all four lanes supply the same one), so the block's product holds the results of four rows for
+// each of its columns.  The weights are streamed and decoded once for all rows; the cost is four times the activation
+// staging (LDS: 4 x the fragments) and three more scale multiplies per group.  Rows past M repeat row M - 1 and are
+// not stored.
+struct Args4 {
+  Args a;
+  int64_t ldx, ldy;
+  int32_t M;
+};
+
+template <int TPW, int SM>
+__global__ void __launch_bounds__(1024) kernel4(const Args4 aa) {
+  const Args& a = aa.a;
+  constexpr int NG = TPW * 4;                             // groups per wavefront
+  constexpr int NF = NG * 8 * 4 / 64;                     // staging units (fragment, row) per lane
+  constexpr int SH = SM == 0 ? 64 : 16;
+  constexpr int REGION = NG * 8 * 16 * 4 + NG * 4 * 16;   // private LDS bytes per wavefront: fragments of four rows, start values
+  extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t nwaves = blockDim.x >> 6;
+  const uint32_t n = lane & 15u, kq = lane >> 4;
+  const uint32_t t0 = wave * TPW;
+  const uint32_t rtile = blockIdx.x;
+  // ---- every request, before anything else ------------------------------------------------------------------
+  // unit u = lane + 64 i: bits 0-2 = the fragment's (quarter, k-step), bits 3-4 = activation row, the rest = group
+  u32x4 xv[NF];
+#pragma unroll
+  for (int i = 0; i < NF; ++i) {
+    const uint32_t u = lane + 64u * i;
+    const uint32_t f = (u & 7u) | ((u >> 5) << 3), r = min((u >> 3) & 3u, (uint32_t)aa.M - 1u);
+    const uint32_t g = min(t0 * 4u + (f >> 3), (uint32_t)a.g_last);
+    const uint32_t off = (g << 6) | ((f & 3u) << 4) | ((f & 4u) << 1);
+    xv[i] = *reinterpret_cast<const u32x4*>(a.x + (size_t)r * (size_t)aa.ldx + off);
+  }
+  const uint32_t row = min(rtile * 16u + n, (uint32_t)a.n_last);
+  const float al = a.alpha[row];
+  const float be_raw = a.beta[row];
+  uint32_t ssup = 0;
+  if constexpr (SM == 1) ssup = a.scale_super[row];
+  u32x4 cw[TPW];
+  uint32_t sw[TPW][SM == 0 ? 2 : 1];
+  const uint16_t* sb = a.scales + ((size_t)rtile * (uint32_t)a.tiles + t0) * SH;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    if constexpr (SM == 0) {
+      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+      sw[i][0] = v.x;
+      sw[i][1] = v.y;
+    } else {
+      sw[i][0] = sb[i * 16u + n];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  const uint8_t* cb = a.codes + ((size_t)rtile * (uint32_t)a.tiles + t0) * 1024u;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + i * 1024u + lane * 16u));
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- stage x: fragment f of row r at [f][r], start values -(128 + zp) sum x at [group][quarter][r] ---------------
+  unsigned char* region = smem + (size_t)wave * REGION;
+  u32x4* lds_x = reinterpret_cast<u32x4*>(region);
+  float* lds_c = reinterpret_cast<float*>(region + NG * 8 * 16 * 4);
+#pragma unroll
+  for (int i = 0; i < NF; ++i) {
+    const uint32_t u = lane + 64u * i;
+    const uint32_t f = (u & 7u) | ((u >> 5) << 3), r = (u >> 3) & 3u;
+    u32x4 o;
+    o.x = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x05040100u);
+    o.y = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x07060302u);
+    o.z = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x05040100u);
+    o.w = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x07060302u);
+    float s = frag_sum(o);
+    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x104, 0xF, 0xF, true));  // + the other k-step, 4 lanes up
+    lds_x[f * 4u + r] = o;
+    if ((f & 4u) == 0) lds_c[((f >> 3) * 4u + (f & 3u)) * 4u + r] = a.cneg * s;
+  }
+  __builtin_amdgcn_wave_barrier();
+  uint32_t c4300 = 0x43004300u, mask = 0x003F003Fu;
+  float magic = 8388608.f;
+  asm volatile("" : "+v"(c4300), "+s"(mask), "+v"(magic));   // register values, not literals: v_and_or_b32 gets selected
+  const float be = be_raw + magic;   // + 2^23: exact, beta is an integer below 2^15
+
+  // ---- contraction ------------------------------------------------------------------------------------------------
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  const uint32_t mr = lane & 3u;   // the activation row this lane supplies to its 4x4 block
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int lg = i * 4 + j;
+      const u32x4 x0 = lds_x[((lg * 2 + 0) * 4 + kq) * 4u + mr];
+      const u32x4 x1 = lds_x[((lg * 2 + 1) * 4 + kq) * 4u + mr];
+      f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+      u32x4 w[2];
+      const uint32_t d = j == 0 ? cw[i].x : (j == 1 ? cw[i].y : (j == 2 ? cw[i].z : cw[i].w));
+      decode_dword(d, al, be, c4300, mask, w);
+      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.x, x0.y}), __builtin_bit_cast(bf16x4, u32x2{w[0].x, w[0].y}), p, 0, 0, 0);
+      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.z, x0.w}), __builtin_bit_cast(bf16x4, u32x2{w[0].z, w[0].w}), p, 0, 0, 0);
+      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.x, x1.y}), __builtin_bit_cast(bf16x4, u32x2{w[1].x, w[1].y}), p, 0, 0, 0);
+      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.z, x1.w}), __builtin_bit_cast(bf16x4, u32x2{w[1].z, w[1].w}), p, 0, 0, 0);
+      float s;
+      if constexpr (SM == 0) {
+        const uint32_t sd = sw[i][j >> 1];
+        s = (float)__builtin_bit_cast(_Float16, (uint16_t)((j & 1) ? (sd >> 16) : (sd & 0xFFFFu)));
+      } else {
+        s = (float)((sw[i][0] >> (4 * j)) & 0xFu);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[r] = __builtin_fmaf(s, p[r], acc[r]);
+    }
+  }
+  // ---- per row: the four quarters, then the wavefronts of the workgroup (fixed order) ------------------------------
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    acc[r] += __shfl_xor(acc[r], 16);
+    acc[r] += __shfl_xor(acc[r], 32);
+  }
+  if (nwaves > 1) {
+    __syncthreads();
+    f32x4* red = reinterpret_cast<f32x4*>(smem);
+    if (wave > 0 && lane < 16u) red[(wave - 1) * 16u + lane] = acc;
+    __syncthreads();
+    if (wave == 0 && lane < 16u) {
+      for (uint32_t k = 1; k < nwaves; ++k) acc += red[(k - 1) * 16u + lane];
+    }
+  }
+  if (wave == 0 && lane < 16u && rtile * 16u + lane <= (uint32_t)a.n_last) {
+    if constexpr (SM == 1) acc *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (r < aa.M) a.y[(size_t)r * (size_t)aa.ldy + rtile * 16u + lane] = to_bf16_rne(acc[r]);
+  }
+}
+
 // ---- one activation row on wide-format and mixed-format weights ----------------------------------------------------
 // The same kernel shape for the (L=4,N=3,S=2) code of Table 1 (Alg. 2) and for a per-group mix of the two formats
 // (Sec. 3.3, "Hybrid Bits Mix"): a workgroup owns one row tile and all of K; its first WN wavefronts take shares of
@@ -1036,6 +1172,63 @@ int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, v
     return CCQ_ERR_HIP;
   }
   hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * waves)), lds, static_cast<hipStream_t>(stream), a);
+  return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
+}
+
+// Two to four rows: the same shares, as long as the four rows' fragments of all of K fit the LDS of a CU twice
+// (2304 bytes per k-tile) -- beyond that one workgroup per CU is left and the 16-row kernel is faster.
+bool gemv4_shape(const Layout& L, int cus, int* tpw_out, int* w_out) {
+  if (L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return false;
+  const int tiles = L.tiles[kNarrow];
+  if ((int64_t)tiles * 2304 > 80 * 1024) return false;
+  const int64_t waves2 = (int64_t)L.row_tiles * ((tiles + 1) / 2);
+  int want = 2;
+  if (waves2 > (int64_t)32 * cus) want = 4;
+  else if (2 * waves2 < (int64_t)3 * cus) want = 1;
+  int best = 0, best_dist = 1 << 30;
+  for (int tpw : {1, 2, 3, 4}) {   // the share lengths that are built
+    if (tiles % tpw != 0 || tiles / tpw > 16) continue;
+    const int dist = std::abs(tpw - want) * 2 + (tpw < want ? 1 : 0);
+    if (dist < best_dist) { best_dist = dist; best = tpw; }
+  }
+  if (best == 0) return false;
+  *tpw_out = best;
+  *w_out = tiles / best;
+  return true;
+}
+
+int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream, int tpw, int waves) {
+  using namespace gemv;
+  if (M < 1 || M > 4 || waves < 1 || waves > 16 || waves * tpw != L.tiles[kNarrow] || L.tiles[kWide] != 0 || L.has_map) return CCQ_ERR_UNSUPPORTED;
+  if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  Args4 a4;
+  Args& a = a4.a;
+  a.codes = static_cast<const uint8_t*>(w->codes);
+  a.scales = static_cast<const uint16_t*>(w->scales);
+  a.alpha = w->code_alpha;
+  a.beta = w->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
+  a.tiles = L.tiles[kNarrow];
+  a.cneg = -(128.f + L.zp[kNarrow]);
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
+  a4.ldx = ldx;
+  a4.ldy = ldy;
+  a4.M = M;
+  typedef void (*Kernel4)(const Args4);
+  Kernel4 k = nullptr;
+  if (L.scale_mode == 0) k = tpw == 1 ? kernel4<1, 0> : (tpw == 2 ? kernel4<2, 0> : (tpw == 3 ? kernel4<3, 0> : (tpw == 4 ? kernel4<4, 0> : nullptr)));
+  else k = tpw == 1 ? kernel4<1, 1> : (tpw == 2 ? kernel4<2, 1> : (tpw == 3 ? kernel4<3, 1> : (tpw == 4 ? kernel4<4, 1> : nullptr)));
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)waves * tpw * 2304;   // 576 bytes per group: 8 fragments of 4 rows, 16 start values
+  if (lds > 160 * 1024) return CCQ_ERR_UNSUPPORTED;
+  if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * waves)), lds, static_cast<hipStream_t>(stream), a4);
   return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
 }
 

@@ -148,7 +148,7 @@ static DensePath dense_path(const Layout& L, int M) {
     // one row: the GEMV kernel; two to four: its four-row variant where K splits into its shares; up to sixteen: the
     // 16-row kernel (each falls back to the per-row-tile kernel if K does not split its way)
     int tpw = 0, nw = 0;
-    if (M == 1 || (M <= kGemvMaxM && gemv_narrow_shares(L, M) > 0)) return kPathGemv;
+    if (M == 1 || (M <= kGemvMaxM && gemv4_shape(L, 256, &tpw, &nw))) return kPathGemv;
     if (gemv16_shape(L, 256, kMaxSplitsK, &tpw, &nw)) return kPathGemv16;
   }
   // two to sixteen rows on wide-format and mixed weights: the 16-row kernel for those formats, where K splits its way
@@ -202,8 +202,9 @@ static int64_t dense_need(const Layout& L, int M) {
   switch (dense_path(L, M)) {
     case kPathGemv: {
       int tpw = 0, waves = 0;
-      if (M == 1 && gemv1_shape(L, 256, &tpw, &waves)) return 0;   // whether K splits does not depend on the chip
-      return gemv_narrow_shares(L, M) > 0 ? 0 : skinny_need(L, M);
+      // whether K splits does not depend on the chip
+      if (M == 1 ? (gemv1_shape(L, 256, &tpw, &waves) || gemv_narrow_shares(L) > 0) : gemv4_shape(L, 256, &tpw, &waves)) return 0;
+      return skinny_need(L, M);
     }
     case kPathGemv16: {
       int tpw = 0, nw = 0;
@@ -523,8 +524,14 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
         rc = launch_gemv1(w, L, x, y, stream, tpw, waves);
         if (rc != CCQ_ERR_UNSUPPORTED) return rc;
       }
-      rc = launch_gemv_narrow(w, L, x, M, ldx, y, ldy, stream);
-      if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+      if (M > 1 && gemv4_shape(L, device_cus(), &tpw, &waves)) {
+        rc = launch_gemv4(w, L, x, M, ldx, y, ldy, stream, tpw, waves);
+        if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+      }
+      if (M == 1) {
+        rc = launch_gemv_narrow(w, L, x, y, stream);
+        if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+      }
     }
   }
 

@@ -115,8 +115,8 @@ int launch_skinny(const SkinnyCall& c);
 // not split into equal shares of at most 12 k-tiles (4 with more than one row) over at most 8 wavefronts (the
 // caller then uses launch_skinny).
 constexpr int kGemvMaxM = 4;
-int gemv_narrow_shares(const Layout& L, int M);  // wavefronts along K per workgroup; 0 = not applicable
-int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream);
+int gemv_narrow_shares(const Layout& L);  // one row: wavefronts along K per workgroup; 0 = not applicable
+int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream);
 
 // One activation row on narrow-format weights (ccq_gemv.hip): shape of the launch for a chip of `cus` compute units
 // (false when K does not split into at most 16 equal shares of a built length), and the launcher.
@@ -124,6 +124,8 @@ bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
 bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out);
 int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww);
 int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves);
+bool gemv4_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
+int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream, int tpw, int waves);
 int device_cus();  // compute units of the current device (cached per device)
 // Two to sixteen rows on narrow-format weights (ccq_gemv.hip): K is cut into tiles / tpw shares across workgroups; with
 // more than one share the fp32 partial tiles go to `partial` ([shares][M][N]) and launch_reduce_splits adds them.

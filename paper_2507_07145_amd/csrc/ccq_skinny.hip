@@ -967,38 +967,6 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
   }
 }
 
-// Private staging for up to four held rows (narrow format): fragment f = ((group * 2 + t) * 4 + kq) * 4 + m.
-constexpr int kPrivFrags4 = 8;  // 4 k-tiles x 32 fragments x 4 rows / 64 lanes
-__device__ __forceinline__ void stage_private4_request(uint4 (&v)[kPrivFrags4], const uint16_t* x, int64_t ldx, int M, int pg0, int ng, int g_last, int lane) {
-  const int nfrag = ng * 32;
-#pragma unroll
-  for (int i = 0; i < kPrivFrags4; ++i) {
-    if (64 * i >= nfrag) break;  // wavefront-uniform
-    const int f = min(lane + 64 * i, nfrag - 1);
-    const int m = min(f & 3, M - 1), kq = (f >> 2) & 3, t = (f >> 4) & 1, pg = min(pg0 + (f >> 5), g_last);  // rows past M repeat row M-1, never stored
-    v[i] = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + (int64_t)pg * kGroup + 16 * kq + 8 * t);
-  }
-}
-__device__ __forceinline__ void stage_private4_finish(const uint4 (&v)[kPrivFrags4], uint4* lds_x, float* lds_cneg, float cneg, int ng, int lane) {
-  const int nfrag = ng * 32;
-#pragma unroll
-  for (int i = 0; i < kPrivFrags4; ++i) {
-    if (64 * i >= nfrag) break;  // wavefront-uniform
-    const int f = lane + 64 * i;  // nfrag is a multiple of 64 here: every lane is active
-    uint4 o;
-    o.x = __builtin_amdgcn_perm(v[i].z, v[i].x, 0x05040100u);
-    o.y = __builtin_amdgcn_perm(v[i].z, v[i].x, 0x07060302u);
-    o.z = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x05040100u);
-    o.w = __builtin_amdgcn_perm(v[i].w, v[i].y, 0x07060302u);
-    lds_x[f] = o;
-    float sum = frag_sum(o);
-    const float other = __shfl_xor(sum, 16);  // the other k-step of the same (group, quarter, row) sits 16 lanes away
-    const float both = (f & 16) ? other + sum : sum + other;  // k-step 0 first on both sides: identical bits
-    if ((f & 16) == 0) lds_cneg[((f >> 5) * 4 + ((f >> 2) & 3)) * 4 + (f & 3)] = cneg * both;
-  }
-  __builtin_amdgcn_wave_barrier();
-}
-
 // ---- dense GEMV on narrow-format weights: the decode step of generation --------------------
 // Same arithmetic as the one-held-row path above (identical results), with everything that path
 // carries for the general case taken out: no experts, no row map, no format map, no K split over
@@ -1084,101 +1052,26 @@ __global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) 
   if (wave == 0 && lane < 16 && rtile * 16 + lane <= a.n_last) a.y[rtile * 16 + lane] = f32_to_bf16_rne(v);
 }
 
-// Two to four activation rows: the same kernel shape with MFMA 4x4x4 used as it is meant (lane l of a 4x4
-// block supplies row l % 4, the block's product holds the four rows' results of each of its columns), so
-// the weights are streamed and decoded once for all rows at the cost of three more scale multiplies per group.
-// Every wavefront owns at most 4 k-tiles.
-struct Gemv4Args {
-  GemvArgs g;
-  int64_t ldx, ldy;
-  int32_t M;
-};
-
-template <int SM>
-__global__ void __launch_bounds__(512) ccq_gemv4_narrow_kernel(const Gemv4Args aa) {
-  constexpr int KN = kNarrow | (SM << 1), NT = 4;
-  const GemvArgs& a = aa.g;
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nwaves = blockDim.x >> 6;
-  const int rtile = blockIdx.x, n = a.tpw;
-  const int t0 = wave * n;
-
-  uint4 xv[kPrivFrags4];
-  stage_private4_request(xv, a.x, aa.ldx, aa.M, t0 * kNarrowGroupsPerTile, n * kNarrowGroupsPerTile, a.g_last, lane);
-  float al[1], be[1];
-  const int prow = min(rtile * 16 + (lane & 15), a.n_last);
-  al[0] = a.alpha[prow];
-  const float be_raw = a.beta[prow];
-  const int frag_cap = n * kNarrowGroupsPerTile * 32, cneg_cap = n * kNarrowGroupsPerTile * 16;
-  uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
-  float* my_cneg = reinterpret_cast<float*>(my_x + frag_cap);
-  const uint8_t* codes = a.codes + (int64_t)rtile * a.row_tile_bytes + (int64_t)t0 * kNarrowTileBytes;
-  const uint16_t* scales = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + (int64_t)t0 * Traits<KN>::SCALE_HALFS;
-  TileRegs<KN> buf[NT][1];
-#pragma unroll
-  for (int i = 0; i < NT; ++i) load_tile<KN>(buf[i][0], codes, scales, min(i, n - 1), lane);
-  uint16_t ssup_bits = 0;
-  if constexpr (SM == 1) ssup_bits = a.scale_super[prow];
-  stage_private4_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
-  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
-  float magic = 8388608.f;
-  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+v"(magic));
-  dc.ssup[0] = (float)__builtin_bit_cast(_Float16, ssup_bits);
-  be[0] = be_raw + magic;  // + 2^23: exact, beta is an integer below 2^15
-
-  f32x4 acc[1][1] = {{f32x4{0.f, 0.f, 0.f, 0.f}}};
-#pragma unroll
-  for (int i = 0; i < NT; ++i) {
-    if (i < n) process_tile<KN, 1, 4, 1, 0, kNarrowGroupsPerTile>(buf[i], i * kNarrowGroupsPerTile, my_x, my_cneg, al, be, acc, lane, dc);
-  }
-
-  // per row: the four quarters, then the wavefronts of the workgroup (fixed order)
-  f32x4 v = acc[0][0];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    v[r] += __shfl_xor(v[r], 16);
-    v[r] += __shfl_xor(v[r], 32);
-  }
-  if (nwaves > 1) {
-    __syncthreads();
-    f32x4* red = reinterpret_cast<f32x4*>(smem);
-    if (wave > 0 && lane < 16) red[(wave - 1) * 16 + lane] = v;
-    __syncthreads();
-    if (wave == 0 && lane < 16) {
-      for (int k = 1; k < nwaves; ++k) v += red[(k - 1) * 16 + lane];
-    }
-  }
-  if constexpr (SM == 1) v *= dc.ssup[0];  // compressed scales: the row's super scale, once (see group_scale)
-  if (wave == 0 && lane < 16 && rtile * 16 + lane <= a.n_last) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (r < aa.M) a.y[(int64_t)r * aa.ldy + rtile * 16 + lane] = f32_to_bf16_rne(v[r]);
-  }
-}
-
-// Wavefronts per workgroup of the GEMV kernels = shares of K: a divisor of the k-tile count, at most 8.  Many short
+// Wavefronts per workgroup of this GEMV kernel = shares of K: a divisor of the k-tile count, at most 8.  Many short
 // wavefronts (4 k-tiles each) hide the latency chain of a call this small best; when that would be more wavefronts
-// than the chip holds at once (8 per SIMD), shares of 8 tiles are better.  With 2..4 rows a share is at most 4 tiles.
+// than the chip holds at once (8 per SIMD), shares of 8 tiles are better.
 // 0: K does not split that way (the caller uses the general kernel).
-int gemv_narrow_shares(const Layout& L, int M) {
-  if (M < 1 || M > kGemvMaxM || L.tiles[kWide] != 0 || L.has_map) return 0;
+int gemv_narrow_shares(const Layout& L) {
+  if (L.tiles[kWide] != 0 || L.has_map) return 0;
   if (L.row_tile_bytes >= ((int64_t)1 << 31) || L.row_tile_scale_halfs >= ((int64_t)1 << 31)) return 0;
   const int tiles = L.tiles[kNarrow];
-  const int max_share = M == 1 ? kGemvMaxTiles : 4;
-  const int target = (M > 1 || (int64_t)L.row_tiles * tiles / 4 <= 32 * (int64_t)device_cus()) ? 4 : 8;
+  const int target = (int64_t)L.row_tiles * tiles / 4 <= 32 * (int64_t)device_cus() ? 4 : 8;
   int wk = 0, best = 1 << 30;
   for (int c = 1; c <= 8; ++c) {
-    if (tiles % c != 0 || tiles / c > max_share) continue;
+    if (tiles % c != 0 || tiles / c > kGemvMaxTiles) continue;
     const int dist = std::abs(tiles / c - target);
     if (dist < best) { best = dist; wk = c; }
   }
   return wk;
 }
 
-int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream) {
-  const int wk = gemv_narrow_shares(L, M);
+int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream) {
+  const int wk = gemv_narrow_shares(L);
   if (wk == 0) return CCQ_ERR_UNSUPPORTED;  // the caller falls back to the general kernel
   const int tiles = L.tiles[kNarrow];
   GemvArgs a;
@@ -1197,32 +1090,15 @@ int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, int 
   a.n_last = L.N - 1;
   const dim3 grid((unsigned)L.row_tiles), block((unsigned)(64 * wk));
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (M == 1) {
-    const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 16);
-    if (L.scale_mode == 0) {
-      if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 0>), grid, block, lds, st, a);
-      else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 0>), grid, block, lds, st, a);
-      else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 0>), grid, block, lds, st, a);
-    } else {
-      if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 1>), grid, block, lds, st, a);
-      else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 1>), grid, block, lds, st, a);
-      else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 1>), grid, block, lds, st, a);
-    }
+  const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 16);
+  if (L.scale_mode == 0) {
+    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 0>), grid, block, lds, st, a);
+    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 0>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 0>), grid, block, lds, st, a);
   } else {
-    Gemv4Args a4;
-    a4.g = a;
-    a4.ldx = ldx;
-    a4.ldy = ldy;
-    a4.M = M;
-    const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (32 * 16 + 16 * 4);
-    typedef void (*Gemv4Kernel)(const Gemv4Args);
-    const Gemv4Kernel kern = L.scale_mode == 0 ? ccq_gemv4_narrow_kernel<0> : ccq_gemv4_narrow_kernel<1>;
-    if (lds > 48 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-      (void)hipGetLastError();
-      return CCQ_ERR_HIP;
-    }
-    hipLaunchKernelGGL(kern, grid, block, lds, st, a4);
+    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 1>), grid, block, lds, st, a);
+    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 1>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 1>), grid, block, lds, st, a);
   }
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;

@@ -416,6 +416,45 @@ def test_one_row_kernel_every_share_shape(n_narrow, n_wide, what, mode):
         assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, [int(k)]].T))), f"{what}: decoded weights differ at column {k}"
 
 
+@pytest.mark.parametrize("G,N,what", [(16, 100, "shares of one k-tile"), (15, 40, "shares of one, the last k-tile ragged"),
+                                      (128, 400, "16 shares of two"), (110, 1000, "14 shares of two, ragged K and N"),
+                                      (84, 72, "7 shares of three"), (128, 8208, "8 shares of four: more wavefronts than the chip holds"),
+                                      (132, 64, "33 k-tiles: 11 shares of three"), (144, 64, "36 k-tiles: the 16-row kernel")])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_four_row_kernel_every_share_shape(G, N, what, mode):
+    """Two to four activation rows on narrow-format weights (the GEMV operator of Table 4 with M = 4): every share length
+    the four-row kernel is built for, both scale modes, strided activations; the product within tolerance and the
+    decoded weights bit for bit (one-hot rows, a different column per row)."""
+    K = 64 * G
+    rng = synth.rng(19, G + mode)
+    codes = synth.random_codes(N, o.row_bytes(K, o.F2), rng)
+    alpha, beta = synth.cluster_params(N, rng)
+    if mode == 0:
+        scales = synth.scales_log_uniform_fp16(N, G, rng)
+        W = o.decode(K, N, o.F2, codes, scales, alpha, beta)
+        w = b.Weight.from_canonical(K, N, [b.NARROW], codes, scales, alpha, beta, device=DEV)
+    else:
+        nb = o.sq_row_bytes(K, o.F2)
+        sq = rng.integers(0, 256, size=(N, nb), dtype=np.uint8)
+        ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(N, 1, rng).reshape(N)) * 0.1).astype(np.float16).view(np.uint16)
+        W = o.decode_cs(K, N, o.F2, codes, sq, ssup, alpha, beta)
+        w = b.Weight.from_canonical_compressed(K, N, [b.NARROW], codes, sq, ssup, alpha, beta, device=DEV)
+    for M in (2, 3, 4):
+        x = synth.activations_bf16(M, K, synth.rng(19, 900 + G + M))
+        xs = torch.zeros((M, K + 24), dtype=torch.bfloat16, device=DEV)      # rows 24 elements apart from contiguous
+        xs[:, :K] = b.bf16_tensor(x, DEV)
+        y = torch.full((M + 1, (N + 7) // 8 * 8 + 8), 3.140625, dtype=torch.bfloat16, device=DEV)
+        b.gemm(w, xs[:, :K], out=y[:M, :N])
+        torch.cuda.synchronize()
+        bits = b.bf16_bits(y)
+        assert np.all(bits[:M, N:] == 0x4049) and np.all(bits[M] == 0x4049), f"{what} M={M}: written outside the result"
+        assert_gemm_close(bits[:M, :N], o.matmul(x, W), f"{M} rows, {what}, scale mode {mode}")
+    for k0 in (0, 59, K - 64, K - 4):
+        ks = [k0, min(k0 + 1, K - 1), K - 1 - k0, (k0 + 64) % K]
+        got = _gemm_bits(w, synth.one_hot_bf16(ks, K))
+        assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, ks].T))), f"{what}: decoded weights differ at columns {ks}"
+
+
 @pytest.mark.parametrize("n_narrow,n_wide,cap,what", [(0, 16, 32, "(0,1)"), (0, 16, 1, "(0,2): all of K in one share"), (0, 40, 32, "(0,1), five shares"),
                                                       (64, 32, 32, "(1,1)"), (64, 32, 16, "(2,1)"), (64, 32, 10, "(2,2)"), (64, 32, 8, "(4,1)"),
                                                       (64, 32, 6, "(4,2)"), (36, 80, 16, "(1,2)"), (100, 56, 32, "(1,1), 32 shares")])
