@@ -145,7 +145,7 @@ enum DensePath { kPathGemv, kPathGemv16, kPathGemv16NW, kPathSkinny, kPathRows, 
 static DensePath dense_path(const Layout& L, int M) {
   const bool narrow_only = L.tiles[kWide] == 0, wide_only = L.tiles[kNarrow] == 0;
   if (narrow_only && !L.has_map && M < kMidMinM) {
-    // one row: the GEMV kernel; two to four: its four-row variant where K splits into its shares; up to sixteen: the
+    // one row: the GEMV kernel; two to four: its four-row variant where K splits into its shares and fits its LDS; up to sixteen: the
     // 16-row kernel (each falls back to the per-row-tile kernel if K does not split its way)
     int tpw = 0, nw = 0;
     if (M == 1 || (M <= kGemvMaxM && gemv4_shape(L, 256, &tpw, &nw))) return kPathGemv;

@@ -111,21 +111,24 @@ struct SkinnyCall {
 };
 int launch_skinny(const SkinnyCall& c);
 
-// Dense product of one to four rows on narrow-format weights (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does
-// not split into equal shares of at most 12 k-tiles (4 with more than one row) over at most 8 wavefronts (the
-// caller then uses launch_skinny).
-constexpr int kGemvMaxM = 4;
-int gemv_narrow_shares(const Layout& L);  // one row: wavefronts along K per workgroup; 0 = not applicable
+// Dense product of one row on narrow-format weights for k-tile counts the kernel below is not built for
+// (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does not split into shares the kernel is built for (the caller then
+// uses launch_skinny).
+constexpr int kGemvMaxTiles = 16;  // k-tiles per wavefront (LDS for the private activation copies: 8 x 16 x 768 B = 96 KiB)
+constexpr int kGemvMaxM = 4;       // rows of the four-row kernel
+int gemv_narrow_shares(const Layout& L);  // wavefronts along K per workgroup; 0 = not applicable
 int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream);
 
 // One activation row on narrow-format weights (ccq_gemv.hip): shape of the launch for a chip of `cus` compute units
-// (false when K does not split into at most 16 equal shares of a built length), and the launcher.
+// (false when K does not split into at most 16 equal shares of a built length), and the launcher; the same for two
+// to four rows (gemv4: also false when the four rows' activation fragments of all of K do not fit the LDS twice),
+// and for one row on wide-format and mixed weights (gemv_nw).
 bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
-bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out);
-int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww);
 int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves);
 bool gemv4_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
 int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream, int tpw, int waves);
+bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out);
+int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww);
 int device_cus();  // compute units of the current device (cached per device)
 // Two to sixteen rows on narrow-format weights (ccq_gemv.hip): K is cut into tiles / tpw shares across workgroups; with
 // more than one share the fp32 partial tiles go to `partial` ([shares][M][N]) and launch_reduce_splits adds them.
