@@ -112,9 +112,8 @@ struct SkinnyCall {
 int launch_skinny(const SkinnyCall& c);
 
 // Dense product of one row on narrow-format weights for k-tile counts the kernel below is not built for
-// (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does not split into shares the kernel is built for (the caller then
-// uses launch_skinny).
-constexpr int kGemvMaxTiles = 16;  // k-tiles per wavefront (LDS for the private activation copies: 8 x 16 x 768 B = 96 KiB)
+// (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does not split into equal shares of at most 12 k-tiles over at most 8
+// wavefronts (the caller then uses launch_skinny).
 constexpr int kGemvMaxM = 4;       // rows of the four-row kernel
 int gemv_narrow_shares(const Layout& L);  // wavefronts along K per workgroup; 0 = not applicable
 int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream);
