@@ -24,6 +24,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cstddef>
 #include <cstdint>
 #include <cstdlib>
 
@@ -92,7 +93,7 @@ __device__ __forceinline__ void decode_dword(uint32_t d, float al, float be_magi
 }
 
 template <int RT, int TPW, int SM>
-__global__ void __launch_bounds__(1024) kernel(const Args a) {
+__device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0) {
   constexpr int NG = TPW * 4;                         // groups per wavefront
   constexpr int NF = (NG * 8 + 63) / 64;              // x fragments per lane while staging
   constexpr int SH = SM == 0 ? 64 : 16;               // scale halfwords per k-tile and row tile
@@ -103,7 +104,6 @@ __global__ void __launch_bounds__(1024) kernel(const Args a) {
   const uint32_t nwaves = blockDim.x >> 6;
   const uint32_t n = lane & 15u, kq = lane >> 4;
   const uint32_t t0 = wave * TPW;                     // first k-tile of this wavefront
-  const uint32_t rtile0 = blockIdx.x * RT;
   // ---- every request, before anything else ------------------------------------------------------------------
   // x: fragment f = (group * 2 + k-step) * 4 + quarter covers elements 64 group + 16 quarter + 8 k-step .. + 7
   u32x4 xv[NF];
@@ -245,6 +245,11 @@ __global__ void __launch_bounds__(1024) kernel(const Args a) {
   }
 }
 
+template <int RT, int TPW, int SM>
+__global__ void __launch_bounds__(1024) kernel(const Args a) {
+  rows1_body<RT, TPW, SM>(a, blockIdx.x * RT);
+}
+
 // ---- two to four activation rows on narrow-format weights -----------------------------------------------------------
 // The same kernel with MFMA 4x4x4 used as it is meant: lane l of a 4x4 block supplies the activation fragment of row
 // l % 4 (in `kernel` all four lanes supply the same one), so the block's product holds the results of four rows for
@@ -257,9 +262,9 @@ struct Args4 {
   int32_t M;
 };
 
+// `rows`: NULL (activation row r is row r of x) or the rows' indices in x (the grouped product gathers them).
 template <int TPW, int SM>
-__global__ void __launch_bounds__(1024) kernel4(const Args4 aa) {
-  const Args& a = aa.a;
+__device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, const int64_t ldy, const int32_t M, const int32_t* rows, const uint32_t rtile) {
   constexpr int NG = TPW * 4;                             // groups per wavefront
   constexpr int NF = NG * 8 * 4 / 64;                     // staging units (fragment, row) per lane
   constexpr int SH = SM == 0 ? 64 : 16;
@@ -270,17 +275,19 @@ __global__ void __launch_bounds__(1024) kernel4(const Args4 aa) {
   const uint32_t nwaves = blockDim.x >> 6;
   const uint32_t n = lane & 15u, kq = lane >> 4;
   const uint32_t t0 = wave * TPW;
-  const uint32_t rtile = blockIdx.x;
   // ---- every request, before anything else ------------------------------------------------------------------
-  // unit u = lane + 64 i: bits 0-2 = the fragment's (quarter, k-step), bits 3-4 = activation row, the rest = group
+  // unit u = lane + 64 i: bits 0-2 = the fragment's (quarter, k-step), bits 3-4 = activation row, the rest = group;
+  // a lane stages the same row in all of its units
+  const uint32_t sr = min((lane >> 3) & 3u, (uint32_t)M - 1u);
+  const size_t xrow = rows ? (size_t)rows[sr] : (size_t)sr;
   u32x4 xv[NF];
 #pragma unroll
   for (int i = 0; i < NF; ++i) {
     const uint32_t u = lane + 64u * i;
-    const uint32_t f = (u & 7u) | ((u >> 5) << 3), r = min((u >> 3) & 3u, (uint32_t)aa.M - 1u);
+    const uint32_t f = (u & 7u) | ((u >> 5) << 3);
     const uint32_t g = min(t0 * 4u + (f >> 3), (uint32_t)a.g_last);
     const uint32_t off = (g << 6) | ((f & 3u) << 4) | ((f & 4u) << 1);
-    xv[i] = *reinterpret_cast<const u32x4*>(a.x + (size_t)r * (size_t)aa.ldx + off);
+    xv[i] = *reinterpret_cast<const u32x4*>(a.x + xrow * (size_t)ldx + off);
   }
   const uint32_t row = min(rtile * 16u + n, (uint32_t)a.n_last);
   const float al = a.alpha[row];
@@ -377,7 +384,57 @@ __global__ void __launch_bounds__(1024) kernel4(const Args4 aa) {
     if constexpr (SM == 1) acc *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
-      if (r < aa.M) a.y[(size_t)r * (size_t)aa.ldy + rtile * 16u + lane] = to_bf16_rne(acc[r]);
+      if (r < M) a.y[(size_t)r * (size_t)ldy + rtile * 16u + lane] = to_bf16_rne(acc[r]);
+  }
+}
+
+template <int TPW, int SM>
+__global__ void __launch_bounds__(1024) kernel4(const Args4 aa) {
+  rows4_body<TPW, SM>(aa.a, aa.ldx, aa.ldy, aa.M, nullptr, blockIdx.x);
+}
+
+// ---- grouped product with at most four rows per expert (one or a few tokens' decode step of a mixture of experts:
+// the Grouped-GEMM operator of Table 5 with M = 1 and 4) ----------------------------------------------------------------
+// Every expert that has rows is a GEMV (or a four-row product) of its own: blockIdx.y picks the expert (from the list
+// of experts that have rows, when the host knows it; otherwise every expert, and those without rows leave at once),
+// blockIdx.x its row tile; the expert's rows of x are gathered through sorted_rows and its results are rows
+// offsets[e] .. offsets[e + 1] - 1 of y.
+struct ArgsG {
+  Args a;                        // expert 0's arrays; x and y of the whole call
+  int64_t ldx, ldy;
+  int64_t codes_stride, scales_stride, ab_stride;   // bytes from one expert's arrays to the next (scale_super: ab_stride / 2)
+  const int32_t* sorted_rows;
+  const int32_t* offsets;
+  int32_t n_active;              // > 0: gridDim.y experts are listed in active_ids
+  uint16_t active_ids[kMaxActiveList];
+};
+
+template <int TPW, int SM, bool FOUR>
+__global__ void __launch_bounds__(1024) kernel_grouped(const ArgsG g) {
+  uint32_t e = blockIdx.y;
+  if (g.n_active > 0) {
+    // read straight from the argument segment (a uniform scalar load): indexing the by-value copy with a run-time
+    // index would make the compiler keep the whole argument block in scratch memory
+    typedef const __attribute__((address_space(4))) uint16_t* KernargU16;
+    typedef const __attribute__((address_space(4))) char* KernargBytes;
+    KernargBytes args = (KernargBytes)__builtin_amdgcn_kernarg_segment_ptr();
+    e = ((KernargU16)(args + offsetof(ArgsG, active_ids)))[blockIdx.y];
+  }
+  const int32_t p0 = g.offsets[e], Me = g.offsets[e + 1] - p0;
+  if (Me <= 0) return;
+  Args a = g.a;
+  a.codes += (size_t)e * (size_t)g.codes_stride;
+  a.scales = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scales) + (size_t)e * (size_t)g.scales_stride);
+  a.alpha = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + (size_t)e * (size_t)g.ab_stride);
+  a.beta = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + (size_t)e * (size_t)g.ab_stride);
+  if constexpr (SM == 1)
+    a.scale_super = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + (size_t)e * (size_t)(g.ab_stride / 2));
+  a.y += (size_t)p0 * (size_t)g.ldy;
+  if (FOUR && Me > 1) {   // uniform over the workgroup; an expert with a single row takes the one-row path below
+    rows4_body<TPW, SM>(a, g.ldx, g.ldy, min(Me, 4), g.sorted_rows + p0, blockIdx.x);
+  } else {
+    a.x += (size_t)g.sorted_rows[p0] * (size_t)g.ldx;
+    rows1_body<1, TPW, SM>(a, blockIdx.x);
   }
 }
 
@@ -1229,6 +1286,89 @@ int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int
     return CCQ_ERR_HIP;
   }
   hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * waves)), lds, static_cast<hipStream_t>(stream), a4);
+  return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
+}
+
+// Grouped product with at most four rows per expert on narrow-format weights: the one-row or the four-row kernel per
+// expert that has rows.  Shares of one to four k-tiles, at most 16 per row tile, chosen as for the dense kernels with
+// `experts` (those that have rows, as far as the host knows) times as many row tiles.
+bool gemv_grouped_shape(const Layout& L, int cus, int experts, bool four, int* tpw_out, int* w_out) {
+  if (L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return false;
+  const int tiles = L.tiles[kNarrow];
+  if (four && (int64_t)tiles * 2304 > 80 * 1024) return false;
+  const int64_t waves2 = (int64_t)L.row_tiles * std::max(1, experts) * ((tiles + 1) / 2);
+  int want = 2;
+  if (waves2 > (int64_t)32 * cus) want = 4;
+  else if (2 * waves2 < (int64_t)3 * cus) want = 1;
+  int best = 0, best_dist = 1 << 30;
+  for (int tpw : {1, 2, 3, 4}) {
+    if (tiles % tpw != 0 || tiles / tpw > 16) continue;
+    const int dist = std::abs(tpw - want) * 2 + (tpw < want ? 1 : 0);
+    if (dist < best_dist) { best_dist = dist; best = tpw; }
+  }
+  if (best == 0) return false;
+  *tpw_out = best;
+  *w_out = tiles / best;
+  return true;
+}
+
+namespace gemv {
+typedef void (*KernelG)(const ArgsG);
+template <int SM, bool FOUR>
+static KernelG pick_grouped(int tpw) {
+  switch (tpw) {
+    case 1: return kernel_grouped<1, SM, FOUR>;
+    case 2: return kernel_grouped<2, SM, FOUR>;
+    case 3: return kernel_grouped<3, SM, FOUR>;
+    case 4: return kernel_grouped<4, SM, FOUR>;
+    default: return nullptr;
+  }
+}
+}  // namespace gemv
+
+int launch_gemv_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride, const void* x,
+                        int64_t ldx, const int32_t* sorted_rows, const int32_t* expert_offsets_dev, void* y, int64_t ldy, int most_rows,
+                        int n_active, const uint16_t* active_ids, void* stream) {
+  using namespace gemv;
+  if (most_rows < 1 || most_rows > 4 || E < 1 || E > 65535 || n_active < 0 || n_active > kMaxActiveList) return CCQ_ERR_UNSUPPORTED;
+  if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  const bool four = most_rows > 1;
+  int tpw = 0, waves = 0;
+  if (!gemv_grouped_shape(L, device_cus(), n_active > 0 ? n_active : E, four, &tpw, &waves)) return CCQ_ERR_UNSUPPORTED;
+  ArgsG g;
+  Args& a = g.a;
+  a.codes = static_cast<const uint8_t*>(w0->codes);
+  a.scales = static_cast<const uint16_t*>(w0->scales);
+  a.alpha = w0->code_alpha;
+  a.beta = w0->code_beta;
+  a.x = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.scale_super = static_cast<const uint16_t*>(w0->scale_super);
+  a.tiles = L.tiles[kNarrow];
+  a.cneg = -(128.f + L.zp[kNarrow]);
+  a.g_last = L.G - 1;
+  a.n_last = L.N - 1;
+  g.ldx = ldx;
+  g.ldy = ldy;
+  g.codes_stride = codes_stride;
+  g.scales_stride = scales_stride;
+  g.ab_stride = ab_stride;
+  g.sorted_rows = sorted_rows;
+  g.offsets = expert_offsets_dev;
+  g.n_active = n_active;
+  for (int i = 0; i < kMaxActiveList; ++i) g.active_ids[i] = i < n_active ? active_ids[i] : (uint16_t)0;
+  KernelG k = nullptr;
+  if (L.scale_mode == 0) k = four ? pick_grouped<0, true>(tpw) : pick_grouped<0, false>(tpw);
+  else k = four ? pick_grouped<1, true>(tpw) : pick_grouped<1, false>(tpw);
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  const size_t lds = four ? (size_t)waves * tpw * 2304 : (size_t)waves * (tpw * 4) * (8 * 16 + 4 * 16);
+  if (lds > 160 * 1024) return CCQ_ERR_UNSUPPORTED;
+  if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
+  hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles, (unsigned)(n_active > 0 ? n_active : E)), dim3((unsigned)(64 * waves)), lds,
+                     static_cast<hipStream_t>(stream), g);
   return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
 }
 

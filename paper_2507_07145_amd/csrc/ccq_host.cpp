@@ -676,8 +676,15 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
                             hip_stream);
     if (rc != CCQ_ERR_UNSUPPORTED) return rc;
   }
+  if (most_rows <= kGemvMaxM && (c.n_active > 0 || active == E || (int64_t)E * L.row_tiles <= 64 * (int64_t)device_cus())) {
+    // one or a few tokens' decode step: every expert that has rows is a GEMV (or a four-row product) of its own (not
+    // when the grid would have to span many experts without rows: dispatching their workgroups costs more than it saves)
+    rc = launch_gemv_grouped(w0, L, E, codes_stride, scales_stride, ab_stride, x, ldx, sorted_rows, expert_offsets_dev, y, ldy, most_rows,
+                             c.n_active, c.active_ids, hip_stream);
+    if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+  }
   if (most_rows == 1) {
-    // one token's decode step: no expert has more than one row, so every expert is a GEMV and takes the
+    // no expert has more than one row (on formats or shapes the kernel above is not built for): the
     // one-held-row kernel (wavefront-private staging, no 16-row activation tile)
     c.m_tile_hint = 1;
     c.d = choose_decomp(L, 1, std::max(1, active), P);

@@ -126,6 +126,12 @@ bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
 int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves);
 bool gemv4_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
 int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream, int tpw, int waves);
+// Grouped product with at most `most_rows` <= 4 rows per expert on narrow-format weights: one GEMV (or four-row
+// product) per expert; `active_ids` lists the n_active experts that have rows (n_active = 0: the grid covers all E).
+bool gemv_grouped_shape(const Layout& L, int cus, int experts, bool four, int* tpw_out, int* w_out);
+int launch_gemv_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride, const void* x,
+                        int64_t ldx, const int32_t* sorted_rows, const int32_t* expert_offsets_dev, void* y, int64_t ldy, int most_rows,
+                        int n_active, const uint16_t* active_ids, void* stream);
 bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out);
 int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww);
 int device_cus();  // compute units of the current device (cached per device)

@@ -193,3 +193,44 @@ def test_random_ragged_grouped_case(seed):
         bits = b.bf16_bits(y)
         assert np.all(bits[:P, N:] == 0x4049) and np.all(bits[P] == 0x4049), what + ": written outside the result"
         assert_gemm_close(bits[:P, :N], ref, what + f", host offsets {'given' if host_offsets is not None else 'absent'}", rounded=sigma)
+
+
+@pytest.mark.parametrize("G,N,counts,what", [(8, 7168, [1, 0, 0, 1, 1, 0, 1, 1, 1, 0, 1, 1], "one row per expert, shares of two k-tiles (Table 5, N x K = 7168 x 512)"),
+                                             (112, 1000, [0, 1, 1, 0, 1], "one row, 14 shares of two, ragged N"),
+                                             (15, 40, [1, 1, 1], "one row, every expert has rows, ragged K"),
+                                             (84, 72, [1, 0, 1], "one row, shares of three"),
+                                             (112, 1024, [1, 4, 0, 2, 3, 1, 0, 1], "up to four rows (Table 5, 1024 x 7168)"),
+                                             (8, 1000, [2, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 3], "up to four rows, most experts without rows"),
+                                             (132, 64, [4, 4], "four rows, 11 shares of three"),
+                                             (144, 64, [4, 1, 2], "36 k-tiles: four rows do not fit, the general kernel")])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_grouped_product_with_few_rows_per_expert(G, N, counts, what, mode):
+    """The Grouped-GEMM operator of Table 5 at one and four tokens: every expert that has rows is a GEMV or a four-row
+    product of its own.  With and without the host copy of the offsets (without it the library only knows the total),
+    both scale modes, gathered activation rows, experts without rows; products within tolerance and decoded weights
+    bit for bit through one-hot rows."""
+    K, E, T = 64 * G, len(counts), 9
+    wrng = synth.rng(43, G + N + mode)
+    parts = [_ragged_arrays("narrow", mode, K, N, None, wrng) for _ in range(E)]
+    w = _upload("narrow", mode, K, N, None, parts)
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    P = int(offs[-1])
+    rows = synth.rng(43, 7).integers(0, T, size=P).astype(np.int32)
+    ld = (N + 7) // 8 * 8 + 8
+    x = synth.activations_bf16(T, K, synth.rng(43, 8))
+    hot = synth.one_hot_bf16(synth.rng(43, 9).integers(0, K, T), K)
+    hot_cols = np.argmax(hot != 0, axis=1)
+    for xb, exact in ((x, False), (hot, True)):
+        for host_offsets in (offs, None):
+            y = torch.full((P + 1, ld), 3.140625, dtype=torch.bfloat16, device=DEV)
+            b.grouped_gemm(w, b.bf16_tensor(xb, DEV), torch.from_numpy(rows).to(DEV), torch.from_numpy(offs).to(DEV), host_offsets, out=y[:P, :N])
+            torch.cuda.synchronize()
+            bits = b.bf16_bits(y)
+            assert np.all(bits[:P, N:] == 0x4049) and np.all(bits[P] == 0x4049), what + ": written outside the result"
+            for e in range(E):
+                for p in range(offs[e], offs[e + 1]):
+                    if exact:
+                        want = o.to_bf16_bits(parts[e]["W"][:, hot_cols[rows[p]]])
+                        assert np.array_equal(canon_zero(bits[p, :N]), canon_zero(want)), f"{what}: decoded weights of expert {e} differ (row {p})"
+                    else:
+                        assert_gemm_close(bits[p:p + 1, :N], o.matmul(xb[rows[p]:rows[p] + 1], parts[e]["W"]), f"{what}, expert {e} row {p}")
