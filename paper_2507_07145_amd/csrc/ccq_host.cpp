@@ -676,9 +676,13 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
                             hip_stream);
     if (rc != CCQ_ERR_UNSUPPORTED) return rc;
   }
-  if (most_rows <= kGemvMaxM && (c.n_active > 0 || active == E || (int64_t)E * L.row_tiles <= 64 * (int64_t)device_cus())) {
-    // one or a few tokens' decode step: every expert that has rows is a GEMV (or a four-row product) of its own (not
-    // when the grid would have to span many experts without rows: dispatching their workgroups costs more than it saves)
+  if (most_rows <= kGemvMaxM &&
+      (c.n_active > 0 || (int64_t)(E - active) * L.row_tiles <= std::max<int64_t>(64 * (int64_t)device_cus(), (int64_t)active * L.row_tiles / 2))) {
+    // one or a few tokens' decode step: every expert that has rows is a GEMV (or a four-row product) of its own.  (Not
+    // when the grid would have to span many more experts without rows than with: dispatching their workgroups costs
+    // more than it saves.  Letting experts with more rows take one pass over their weights per four rows measured
+    // slower than the per-row-tile kernel once most experts need the four-row body: 181 against 150 us on 224 experts
+    // of 1024 x 7168 with 512 rows.)
     rc = launch_gemv_grouped(w0, L, E, codes_stride, scales_stride, ab_stride, x, ldx, sorted_rows, expert_offsets_dev, y, ldy, most_rows,
                              c.n_active, c.active_ids, hip_stream);
     if (rc != CCQ_ERR_UNSUPPORTED) return rc;

@@ -202,6 +202,7 @@ def test_random_ragged_grouped_case(seed):
                                              (112, 1024, [1, 4, 0, 2, 3, 1, 0, 1], "up to four rows (Table 5, 1024 x 7168)"),
                                              (8, 1000, [2, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 3], "up to four rows, most experts without rows"),
                                              (132, 64, [4, 4], "four rows, 11 shares of three"),
+                                             (16, 200, [1, 2, 9, 1, 0, 1, 3, 1, 2, 1, 1, 1], "one expert with nine rows: the general kernel"),
                                              (144, 64, [4, 1, 2], "36 k-tiles: four rows do not fit, the general kernel")])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_grouped_product_with_few_rows_per_expert(G, N, counts, what, mode):
