@@ -549,8 +549,8 @@ __device__ __forceinline__ u32x4 kind_weights(const u32x4 seg, int j, uint32_t m
   return wv;
 }
 
-template <int TPWN, int TPWW, int SM, bool H16 = false>
-__global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
+template <int TPWN, int TPWW, int SM, bool H16>
+__device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rtile) {
   constexpr int NGN = TPWN * 4, NGW = TPWW * 8;                 // groups per narrow / wide share
   constexpr int REGION_N = NGN * 8 * 16 + NGN * 4 * 16;         // private LDS bytes per wavefront: fragments, then start-value records
   constexpr int REGION_W = NGW * 12 * 16 + NGW * 4 * 16;
@@ -559,7 +559,6 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t nwaves = blockDim.x >> 6;
   const uint32_t n = lane & 15u, kq = lane >> 4;
-  const uint32_t rtile = blockIdx.x;
   const uint32_t row = min(rtile * 16u + n, (uint32_t)a.n_last);
   // private regions: the narrow shares' first, then the wide shares'
   const uint32_t wn = TPWN > 0 ? (uint32_t)a.waves_n : 0u;
@@ -751,6 +750,48 @@ __global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
     if constexpr (SM == 1) v *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
     if (rtile * 16u + lane <= (uint32_t)a.n_last) a.y[rtile * 16u + lane] = to_bf16_rne(v);
   }
+}
+
+template <int TPWN, int TPWW, int SM, bool H16 = false>
+__global__ void __launch_bounds__(1024) kernel_nw(const ArgsNW a) {
+  rows1_nw_body<TPWN, TPWW, SM, H16>(a, blockIdx.x);
+}
+
+// The grouped product with at most one row per expert on these formats: one such GEMV per expert that has a row (see
+// kernel_grouped).  The group map is the same for all experts.
+struct ArgsNWG {
+  ArgsNW a;                      // expert 0's arrays; x and y of the whole call
+  int64_t ldx, ldy;
+  int64_t codes_stride, scales_stride, ab_stride;
+  const int32_t* sorted_rows;
+  const int32_t* offsets;
+  int32_t n_active;
+  uint16_t active_ids[kMaxActiveList];
+};
+
+template <int TPWN, int TPWW, int SM, bool H16 = false>
+__global__ void __launch_bounds__(1024) kernel_nw_grouped(const ArgsNWG g) {
+  uint32_t e = blockIdx.y;
+  if (g.n_active > 0) {
+    typedef const __attribute__((address_space(4))) uint16_t* KernargU16;
+    typedef const __attribute__((address_space(4))) char* KernargBytes;
+    KernargBytes args = (KernargBytes)__builtin_amdgcn_kernarg_segment_ptr();
+    e = ((KernargU16)(args + offsetof(ArgsNWG, active_ids)))[blockIdx.y];
+  }
+  const int32_t p0 = g.offsets[e];
+  if (g.offsets[e + 1] <= p0) return;
+  ArgsNW a = g.a;
+  a.codes += (size_t)e * (size_t)g.codes_stride;
+  a.scales = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scales) + (size_t)e * (size_t)g.scales_stride);
+  if constexpr (TPWN > 0) {
+    a.alpha = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.alpha) + (size_t)e * (size_t)g.ab_stride);
+    a.beta = reinterpret_cast<const float*>(reinterpret_cast<const uint8_t*>(a.beta) + (size_t)e * (size_t)g.ab_stride);
+  }
+  if constexpr (SM == 1)
+    a.scale_super = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(a.scale_super) + (size_t)e * (size_t)(g.ab_stride / 2));
+  a.x += (size_t)g.sorted_rows[p0] * (size_t)g.ldx;
+  a.y += (size_t)p0 * (size_t)g.ldy;
+  rows1_nw_body<TPWN, TPWW, SM, H16>(a, blockIdx.x);
 }
 
 // ---- two to sixteen activation rows --------------------------------------------------------------------------------
@@ -1403,39 +1444,44 @@ bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, i
 }
 
 namespace gemv {
-typedef void (*KernelNW)(const ArgsNW);
-template <int SM>
-static KernelNW pick_nw_h16(int tpww) {
-  if (tpww == 1) return kernel_nw<0, 1, SM, true>;
-  if (tpww == 2) return kernel_nw<0, 2, SM, true>;
+// The dense kernel (GROUPED = false, one ArgsNW argument) or the grouped one (one ArgsNWG argument) of a share shape.
+template <int SM, bool GROUPED, int TPWN, int TPWW, bool H16 = false>
+static const void* nw_entry() {
+  if constexpr (GROUPED) return reinterpret_cast<const void*>(&kernel_nw_grouped<TPWN, TPWW, SM, H16>);
+  else return reinterpret_cast<const void*>(&kernel_nw<TPWN, TPWW, SM, H16>);
+}
+template <int SM, bool GROUPED>
+static const void* pick_nw_h16(int tpww) {
+  if (tpww == 1) return nw_entry<SM, GROUPED, 0, 1, true>();
+  if (tpww == 2) return nw_entry<SM, GROUPED, 0, 2, true>();
   return nullptr;
 }
-template <int SM>
-static KernelNW pick_nw(int tpwn, int tpww) {
+template <int SM, bool GROUPED>
+static const void* pick_nw(int tpwn, int tpww) {
   if (tpww == 1) {
     switch (tpwn) {
-      case 0: return kernel_nw<0, 1, SM>;
-      case 1: return kernel_nw<1, 1, SM>;
-      case 2: return kernel_nw<2, 1, SM>;
-      case 4: return kernel_nw<4, 1, SM>;
+      case 0: return nw_entry<SM, GROUPED, 0, 1>();
+      case 1: return nw_entry<SM, GROUPED, 1, 1>();
+      case 2: return nw_entry<SM, GROUPED, 2, 1>();
+      case 4: return nw_entry<SM, GROUPED, 4, 1>();
     }
   } else if (tpww == 2) {
     switch (tpwn) {
-      case 0: return kernel_nw<0, 2, SM>;
-      case 1: return kernel_nw<1, 2, SM>;
-      case 2: return kernel_nw<2, 2, SM>;
-      case 4: return kernel_nw<4, 2, SM>;
+      case 0: return nw_entry<SM, GROUPED, 0, 2>();
+      case 1: return nw_entry<SM, GROUPED, 1, 2>();
+      case 2: return nw_entry<SM, GROUPED, 2, 2>();
+      case 4: return nw_entry<SM, GROUPED, 4, 2>();
     }
   }
   return nullptr;
 }
-}  // namespace gemv
+template <bool GROUPED>
+static const void* pick_nw_kernel(const Layout& L, int tpwn, int tpww) {
+  if (L.h16) return L.scale_mode == 0 ? pick_nw_h16<0, GROUPED>(tpww) : pick_nw_h16<1, GROUPED>(tpww);
+  return L.scale_mode == 0 ? pick_nw<0, GROUPED>(tpwn, tpww) : pick_nw<1, GROUPED>(tpwn, tpww);
+}
 
-int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww) {
-  using namespace gemv;
-  if (ww < 1 || wn < 0 || (L.h16 && wn != 0) || wn + ww > 16 || wn * tpwn != L.tiles[kNarrow] || ww * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
-  if (L.row_tile_bytes * (int64_t)L.row_tiles >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
-  ArgsNW a;
+static void fill_args_nw(ArgsNW& a, const ccq_weight* w, const Layout& L, const void* x, void* y, int wn) {
   a.codes = static_cast<const uint8_t*>(w->codes);
   a.scales = static_cast<const uint16_t*>(w->scales);
   a.alpha = w->code_alpha;
@@ -1454,17 +1500,59 @@ int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y,
   a.cneg_w = -(128.f + L.zp[kWide]);
   a.g_last = L.G - 1;
   a.n_last = L.N - 1;
-  const KernelNW k = L.h16 ? (L.scale_mode == 0 ? pick_nw_h16<0>(tpww) : pick_nw_h16<1>(tpww))
-                           : (L.scale_mode == 0 ? pick_nw<0>(tpwn, tpww) : pick_nw<1>(tpwn, tpww));
-  if (!k) return CCQ_ERR_UNSUPPORTED;
+}
+
+// One launch of a kernel that takes a single by-value argument block.
+static int launch_nw(const void* k, void* arg_block, dim3 grid, int tpwn, int tpww, int wn, int ww, void* stream) {
   const size_t region_n = (size_t)tpwn * 4 * (8 * 16 + 4 * 16), region_w = (size_t)tpww * 8 * (12 * 16 + 4 * 16);
   const size_t lds = std::max<size_t>((size_t)wn * region_n + (size_t)ww * region_w, 1024);   // at most 16 * 4 KiB; the K reduction reuses the start
-  if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+  if (lds > 48 * 1024 && hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return CCQ_ERR_HIP;
   }
-  hipLaunchKernelGGL(k, dim3((unsigned)L.row_tiles), dim3((unsigned)(64 * (wn + ww))), lds, static_cast<hipStream_t>(stream), a);
+  void* params[] = {arg_block};
+  if (hipLaunchKernel(k, grid, dim3((unsigned)(64 * (wn + ww))), params, lds, static_cast<hipStream_t>(stream)) != hipSuccess) {
+    (void)hipGetLastError();
+    return CCQ_ERR_HIP;
+  }
   return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
+}
+}  // namespace gemv
+
+int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww) {
+  using namespace gemv;
+  if (ww < 1 || wn < 0 || (L.h16 && wn != 0) || wn + ww > 16 || wn * tpwn != L.tiles[kNarrow] || ww * tpww != L.tiles[kWide]) return CCQ_ERR_UNSUPPORTED;
+  if (L.row_tile_bytes * (int64_t)L.row_tiles >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  ArgsNW a;
+  fill_args_nw(a, w, L, x, y, wn);
+  const void* k = pick_nw_kernel<false>(L, tpwn, tpww);
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  return launch_nw(k, &a, dim3((unsigned)L.row_tiles), tpwn, tpww, wn, ww, stream);
+}
+
+// The grouped product with at most one row per expert on wide-format, mixed and hybrid-word weights: one such GEMV per
+// expert that has a row; `active_ids` lists the n_active experts that have one (n_active = 0: the grid covers all E).
+int launch_gemv_nw_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride,
+                           const void* x, int64_t ldx, const int32_t* sorted_rows, const int32_t* expert_offsets_dev, void* y, int64_t ldy,
+                           int n_active, const uint16_t* active_ids, void* stream) {
+  using namespace gemv;
+  int tpwn = 0, tpww = 0, wn = 0, ww = 0;
+  if (E < 1 || E > 65535 || n_active < 0 || n_active > kMaxActiveList || !gemv_nw_shape(L, &tpwn, &tpww, &wn, &ww)) return CCQ_ERR_UNSUPPORTED;
+  if (L.row_tile_bytes * (int64_t)L.row_tiles >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  ArgsNWG g;
+  fill_args_nw(g.a, w0, L, x, y, wn);
+  g.ldx = ldx;
+  g.ldy = ldy;
+  g.codes_stride = codes_stride;
+  g.scales_stride = scales_stride;
+  g.ab_stride = ab_stride;
+  g.sorted_rows = sorted_rows;
+  g.offsets = expert_offsets_dev;
+  g.n_active = n_active;
+  for (int i = 0; i < kMaxActiveList; ++i) g.active_ids[i] = i < n_active ? active_ids[i] : (uint16_t)0;
+  const void* k = pick_nw_kernel<true>(L, tpwn, tpww);
+  if (!k) return CCQ_ERR_UNSUPPORTED;
+  return launch_nw(k, &g, dim3((unsigned)L.row_tiles, (unsigned)(n_active > 0 ? n_active : E)), tpwn, tpww, wn, ww, stream);
 }
 
 // K shares of the 2..16-row kernel on wide-format and mixed weights: narrow shares of tpwn k-tiles, then wide shares of

@@ -686,6 +686,11 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
     rc = launch_gemv_grouped(w0, L, E, codes_stride, scales_stride, ab_stride, x, ldx, sorted_rows, expert_offsets_dev, y, ldy, most_rows,
                              c.n_active, c.active_ids, hip_stream);
     if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    if (most_rows == 1) {   // the same on the wide, mixed and hybrid-word formats, one row per expert only
+      rc = launch_gemv_nw_grouped(w0, L, E, codes_stride, scales_stride, ab_stride, x, ldx, sorted_rows, expert_offsets_dev, y, ldy, c.n_active,
+                                  c.active_ids, hip_stream);
+      if (rc != CCQ_ERR_UNSUPPORTED) return rc;
+    }
   }
   if (most_rows == 1) {
     // no expert has more than one row (on formats or shapes the kernel above is not built for): the

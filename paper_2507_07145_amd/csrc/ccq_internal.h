@@ -134,6 +134,9 @@ int launch_gemv_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t co
                         int n_active, const uint16_t* active_ids, void* stream);
 bool gemv_nw_shape(const Layout& L, int* tpwn_out, int* tpww_out, int* wn_out, int* ww_out);
 int launch_gemv_nw(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpwn, int tpww, int wn, int ww);
+int launch_gemv_nw_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t codes_stride, int64_t scales_stride, int64_t ab_stride,
+                           const void* x, int64_t ldx, const int32_t* sorted_rows, const int32_t* expert_offsets_dev, void* y, int64_t ldy,
+                           int n_active, const uint16_t* active_ids, void* stream);
 int device_cus();  // compute units of the current device (cached per device)
 // Two to sixteen rows on narrow-format weights (ccq_gemv.hip): K is cut into tiles / tpw shares across workgroups; with
 // more than one share the fp32 partial tiles go to `partial` ([shares][M][N]) and launch_reduce_splits adds them.

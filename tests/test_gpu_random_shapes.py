@@ -195,25 +195,33 @@ def test_random_ragged_grouped_case(seed):
         assert_gemm_close(bits[:P, :N], ref, what + f", host offsets {'given' if host_offsets is not None else 'absent'}", rounded=sigma)
 
 
-@pytest.mark.parametrize("G,N,counts,what", [(8, 7168, [1, 0, 0, 1, 1, 0, 1, 1, 1, 0, 1, 1], "one row per expert, shares of two k-tiles (Table 5, N x K = 7168 x 512)"),
-                                             (112, 1000, [0, 1, 1, 0, 1], "one row, 14 shares of two, ragged N"),
-                                             (15, 40, [1, 1, 1], "one row, every expert has rows, ragged K"),
-                                             (84, 72, [1, 0, 1], "one row, shares of three"),
-                                             (112, 1024, [1, 4, 0, 2, 3, 1, 0, 1], "up to four rows (Table 5, 1024 x 7168)"),
-                                             (8, 1000, [2, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 3], "up to four rows, most experts without rows"),
-                                             (132, 64, [4, 4], "four rows, 11 shares of three"),
-                                             (16, 200, [1, 2, 9, 1, 0, 1, 3, 1, 2, 1, 1, 1], "one expert with nine rows: the general kernel"),
-                                             (144, 64, [4, 1, 2], "36 k-tiles: four rows do not fit, the general kernel")])
+@pytest.mark.parametrize("family,G,N,counts,what", [("narrow", 8, 7168, [1, 0, 0, 1, 1, 0, 1, 1, 1, 0, 1, 1], "one row per expert, shares of two k-tiles (Table 5, N x K = 7168 x 512)"),
+                                             ("narrow", 112, 1000, [0, 1, 1, 0, 1], "one row, 14 shares of two, ragged N"),
+                                             ("narrow", 15, 40, [1, 1, 1], "one row, every expert has rows, ragged K"),
+                                             ("narrow", 84, 72, [1, 0, 1], "one row, shares of three"),
+                                             ("narrow", 112, 1024, [1, 4, 0, 2, 3, 1, 0, 1], "up to four rows (Table 5, 1024 x 7168)"),
+                                             ("narrow", 8, 1000, [2, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 3], "up to four rows, most experts without rows"),
+                                             ("narrow", 132, 64, [4, 4], "four rows, 11 shares of three"),
+                                             ("narrow", 16, 200, [1, 2, 9, 1, 0, 1, 3, 1, 2, 1, 1, 1], "one expert with nine rows: the general kernel"),
+                                             ("narrow", 144, 64, [4, 1, 2], "36 k-tiles: four rows do not fit, the general kernel"),
+                                             ("wide", 16, 1000, [1, 0, 1, 1, 0, 0, 1], "wide format, one row per expert, shares of two k-tiles"),
+                                             ("wide", 13, 40, [1, 1], "wide format, ragged last k-tile, every expert has a row"),
+                                             ("mixed", 24, 200, [0, 1, 1, 0, 1], "per-group mix, one row per expert"),
+                                             ("mixed", 112, 72, [1, 0, 0, 1], "per-group mix, 14 k-tiles"),
+                                             ("h16", 16, 300, [1, 0, 1, 1], "hybrid word, one row per expert"),
+                                             ("h16", 17, 40, [1, 1, 0], "hybrid word, ragged last k-tile"),
+                                             ("wide", 16, 200, [1, 2, 0, 1], "wide format, two rows on one expert: the general kernel")])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_grouped_product_with_few_rows_per_expert(G, N, counts, what, mode):
+def test_grouped_product_with_few_rows_per_expert(family, G, N, counts, what, mode):
     """The Grouped-GEMM operator of Table 5 at one and four tokens: every expert that has rows is a GEMV or a four-row
     product of its own.  With and without the host copy of the offsets (without it the library only knows the total),
     both scale modes, gathered activation rows, experts without rows; products within tolerance and decoded weights
     bit for bit through one-hot rows."""
     K, E, T = 64 * G, len(counts), 9
     wrng = synth.rng(43, G + N + mode)
-    parts = [_ragged_arrays("narrow", mode, K, N, None, wrng) for _ in range(E)]
-    w = _upload("narrow", mode, K, N, None, parts)
+    gf = synth.group_format_map(G, max(1, G // 3), wrng) if family == "mixed" else None
+    parts = [_ragged_arrays(family, mode, K, N, gf, wrng) for _ in range(E)]
+    w = _upload(family, mode, K, N, gf, parts)
     offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
     P = int(offs[-1])
     rows = synth.rng(43, 7).integers(0, T, size=P).astype(np.int32)
