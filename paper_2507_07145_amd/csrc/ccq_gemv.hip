@@ -820,14 +820,15 @@ struct Args16 {
   int32_t g_last, n_last;           // last real group of K, last real output row (see Args)
 };
 
-template <int TPW, int SM, int NW>
-__global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
+template <int TPW, int SM, int NW, int MT>
+__device__ __forceinline__ void rows16_body(const Args16& a) {
+  constexpr int MR = 16 * MT;                  // activation rows held: MT tiles of 16 (MT = 2 serves 17..32 rows)
   constexpr int NG = TPW * 4;                  // groups per share
-  constexpr int NU = NG * 4 * 16;              // staging units: (group, row, quarter) = 16 consecutive activations
+  constexpr int NU = NG * 4 * MR;              // staging units: (group, row, quarter) = 16 consecutive activations
   constexpr int SH = SM == 0 ? 64 : 16;
   extern __shared__ __align__(16) unsigned char smem[];
   u32x4* lds_x = reinterpret_cast<u32x4*>(smem);                       // [group][k-step][quarter][row]
-  float* lds_c = reinterpret_cast<float*>(smem + (size_t)NG * 8 * 16 * 16);  // [group][row]
+  float* lds_c = reinterpret_cast<float*>(smem + (size_t)NG * 8 * 16 * MR);  // [group][row]
   constexpr uint32_t nthreads = 64u * NW;
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -840,17 +841,23 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
   // ---- every request, before anything else --------------------------------------------------------------------
   // unit u = (group * 16 + row) * 4 + quarter: the quarters of a (group, row) sit in neighbouring lanes
   constexpr int NUT = (NU + (int)nthreads - 1) / (int)nthreads;   // units per thread
-  u32x4 xv[NUT][2];
+  // (two 16-row tiles: the units go in two rounds through the same registers; the second round's requests wait behind
+  // the code tiles', which take longer than anything here)
+  constexpr int NUA = MT == 1 ? NUT : (NUT + 1) / 2;                // units per thread and round
+  u32x4 xv[NUA][2];
+  auto request = [&](int i0) {
 #pragma unroll
-  for (int i = 0; i < NUT; ++i) {
-    uint32_t u = tid + (uint32_t)i * nthreads;
-    if (NU % nthreads != 0) u = min(u, (uint32_t)NU - 1u);             // clamped: the request is unconditional
-    const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
-    const uint32_t row = min(m, (uint32_t)a.M - 1u);                    // rows past M repeat the last one; never stored
-    const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + ((size_t)min(t0 * 4u + lg, (uint32_t)a.g_last) * 64u + q * 16u);
-    xv[i][0] = *reinterpret_cast<const u32x4*>(p);
-    xv[i][1] = *reinterpret_cast<const u32x4*>(p + 8);
-  }
+    for (int i = 0; i < NUA; ++i) {
+      uint32_t u = tid + (uint32_t)(i0 + i) * nthreads;
+      if (NU % nthreads != 0 || NUT % NUA != 0) u = min(u, (uint32_t)NU - 1u);   // clamped: the request is unconditional
+      const uint32_t q = u & 3u, m = (u >> 2) & (uint32_t)(MR - 1), lg = u / (uint32_t)(4 * MR);
+      const uint32_t row = min(m, (uint32_t)a.M - 1u);                  // rows past M repeat the last one; never stored
+      const uint16_t* p = a.x + (size_t)row * (size_t)a.ldx + ((size_t)min(t0 * 4u + lg, (uint32_t)a.g_last) * 64u + q * 16u);
+      xv[i][0] = *reinterpret_cast<const u32x4*>(p);
+      xv[i][1] = *reinterpret_cast<const u32x4*>(p + 8);
+    }
+  };
+  request(0);
   const uint32_t prow = min(rtile * 16u + n, (uint32_t)a.n_last);
   const float al = a.alpha[prow];
   const float be_raw = a.beta[prow];
@@ -876,28 +883,35 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- stage the activations: fragments in k-slot order {0,4,1,5,2,6,3,7} and the start values ----------------------
+  auto finish = [&](int i0) {
 #pragma unroll
-  for (int i = 0; i < NUT; ++i) {
-    const uint32_t u = tid + (uint32_t)i * nthreads;
-    float s = 0.f;
-    u32x4 o[2];
+    for (int i = 0; i < NUA; ++i) {
+      const uint32_t u = tid + (uint32_t)(i0 + i) * nthreads;
+      float s = 0.f;
+      u32x4 o[2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      o[t].x = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x05040100u);
-      o[t].y = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x07060302u);
-      o[t].z = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x05040100u);
-      o[t].w = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x07060302u);
-      s += frag_sum(o[t]);
+      for (int t = 0; t < 2; ++t) {
+        o[t].x = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x05040100u);
+        o[t].y = __builtin_amdgcn_perm(xv[i][t].z, xv[i][t].x, 0x07060302u);
+        o[t].z = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x05040100u);
+        o[t].w = __builtin_amdgcn_perm(xv[i][t].w, xv[i][t].y, 0x07060302u);
+        s += frag_sum(o[t]);
+      }
+      // the four quarters of a (group, row): neighbouring lanes
+      s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+      s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+      if ((NU % nthreads == 0 && NUT % NUA == 0) || u < (uint32_t)NU) {
+        const uint32_t q = u & 3u, m = (u >> 2) & (uint32_t)(MR - 1), lg = u / (uint32_t)(4 * MR);
+        lds_x[((lg * 2u + 0u) * 4u + q) * (uint32_t)MR + m] = o[0];
+        lds_x[((lg * 2u + 1u) * 4u + q) * (uint32_t)MR + m] = o[1];
+        if (q == 0) lds_c[lg * (uint32_t)MR + m] = a.cneg * s;
+      }
     }
-    // the four quarters of a (group, row): neighbouring lanes
-    s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-    s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-    if (NU % nthreads == 0 || u < (uint32_t)NU) {
-      const uint32_t q = u & 3u, m = (u >> 2) & 15u, lg = u >> 6;
-      lds_x[((lg * 2u + 0u) * 4u + q) * 16u + m] = o[0];
-      lds_x[((lg * 2u + 1u) * 4u + q) * 16u + m] = o[1];
-      if (q == 0) lds_c[lg * 16u + m] = a.cneg * s;
-    }
+  };
+  finish(0);
+  if constexpr (NUA < NUT) {
+    request(NUA);
+    finish(NUA);
   }
   __syncthreads();
 
@@ -908,20 +922,17 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
 
   // ---- contraction ------------------------------------------------------------------------------------------------
   typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  f32x4 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int lg = i * 4 + j;
-      const u32x4 x0 = lds_x[((lg * 2 + 0) * 4 + kq) * 16 + n];        // here n is the activation row of this lane's A fragment
-      const u32x4 x1 = lds_x[((lg * 2 + 1) * 4 + kq) * 16 + n];
-      f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + lg * 16 + 4 * kq);
       u32x4 w[2];
       const uint32_t d = j == 0 ? cw[i].x : (j == 1 ? cw[i].y : (j == 2 ? cw[i].z : cw[i].w));
       decode_dword(d, al, be, c4300, mask, w);
-      p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0), __builtin_bit_cast(bf16x8, w[0]), p, 0, 0, 0);
-      p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1), __builtin_bit_cast(bf16x8, w[1]), p, 0, 0, 0);
       float sc;
       if constexpr (SM == 0) {
         const uint32_t sd = sw[i][j >> 1];
@@ -929,28 +940,56 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
       } else {
         sc = (float)((sw[i][0] >> (4 * j)) & 0xFu);
       }
-      acc[0] = __builtin_fmaf(sc, p[0], acc[0]);
-      acc[1] = __builtin_fmaf(sc, p[1], acc[1]);
-      acc[2] = __builtin_fmaf(sc, p[2], acc[2]);
-      acc[3] = __builtin_fmaf(sc, p[3], acc[3]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const u32x4 x0 = lds_x[((lg * 2 + 0) * 4 + kq) * MR + mt * 16 + n];   // here n is the activation row of this lane's A fragment
+        const u32x4 x1 = lds_x[((lg * 2 + 1) * 4 + kq) * MR + mt * 16 + n];
+        f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + lg * MR + mt * 16 + 4 * kq);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0), __builtin_bit_cast(bf16x8, w[0]), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1), __builtin_bit_cast(bf16x8, w[1]), p, 0, 0, 0);
+        acc[mt][0] = __builtin_fmaf(sc, p[0], acc[mt][0]);
+        acc[mt][1] = __builtin_fmaf(sc, p[1], acc[mt][1]);
+        acc[mt][2] = __builtin_fmaf(sc, p[2], acc[mt][2]);
+        acc[mt][3] = __builtin_fmaf(sc, p[3], acc[mt][3]);
+      }
+      // two tiles: keep the scheduler from pulling the fragment reads of later groups ahead (it would need more
+      // registers than four wavefronts per SIMD leave)
+      if constexpr (MT > 1) __builtin_amdgcn_sched_barrier(0);
     }
   }
-  if constexpr (SM == 1) acc *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
+  if constexpr (SM == 1) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
+  }
 
-  // ---- store: lane (n, kq) holds rows 4 kq .. 4 kq + 3 of column n -------------------------------------------------------
+  // ---- store: lane (n, kq) holds rows 4 kq .. 4 kq + 3 of column n (of every 16-row tile) ---------------------------------
   const uint32_t col = rtile * 16u + n;
   if (active && col <= (uint32_t)a.n_last) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const uint32_t m = 4u * kq + r;
-      if (m < (uint32_t)a.M) {
-        // (nontemporal: the partial tiles are read once, by another kernel; kept out of the L2 they need no write-back
-        // when this kernel ends: config 2 at M = 16 12.9 -> 12.1 us)
-        if (gridDim.y > 1) __builtin_nontemporal_store(acc[r], &a.partial[((size_t)blockIdx.y * (uint32_t)a.M + m) * (uint32_t)a.N + col]);
-        else a.y[(size_t)m * (size_t)a.ldy + col] = to_bf16_rne(acc[r]);
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t m = 16u * mt + 4u * kq + r;
+        if (m < (uint32_t)a.M) {
+          // (nontemporal: the partial tiles are read once, by another kernel; kept out of the L2 they need no write-back
+          // when this kernel ends: config 2 at M = 16 12.9 -> 12.1 us)
+          if (gridDim.y > 1) __builtin_nontemporal_store(acc[mt][r], &a.partial[((size_t)blockIdx.y * (uint32_t)a.M + m) * (uint32_t)a.N + col]);
+          else a.y[(size_t)m * (size_t)a.ldy + col] = to_bf16_rne(acc[mt][r]);
+        }
       }
     }
   }
+}
+
+template <int TPW, int SM, int NW>
+__global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
+  rows16_body<TPW, SM, NW, 1>(a);
+}
+// 17..32 rows: two 16-row tiles of activations per workgroup (twice the LDS, two workgroups of eight wavefronts per CU:
+// the register budget of four wavefronts per SIMD)
+template <int TPW, int SM, int NW>
+__global__ void __launch_bounds__(64 * NW, 3) kernel32(const Args16 a) {
+  rows16_body<TPW, SM, NW, 2>(a);
 }
 
 // ---- two to sixteen activation rows on wide-format and mixed weights ------------------------------------------------
@@ -1683,14 +1722,15 @@ bool gemv16_shape(const Layout& L, int cus, int64_t max_shares, int* tpw_out, in
   return true;
 }
 
-// Two to sixteen rows, narrow format, dense.  nw = 8 or 16 wavefronts (row tiles) per workgroup share one staged slice of the
+// Two to 32 rows (beyond 16: two 16-row tiles of activations per workgroup, nw = 8), narrow format, dense.  nw = 8 or 16 wavefronts (row tiles) per workgroup share one staged slice of the
 // activations; S = tiles / tpw <= 32 shares of K across workgroups (S > 1 needs `partial`, fp32 [S][M][N], and a pass of
 // launch_reduce_splits afterwards).
 int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, float* partial, int tpw,
                   int nw, void* stream) {
   using namespace gemv;
-  if (M < 1 || M > 16 || L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return CCQ_ERR_UNSUPPORTED;
+  if (M < 1 || M > 32 || L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return CCQ_ERR_UNSUPPORTED;
   if (tpw < 1 || L.tiles[kNarrow] % tpw != 0 || nw < 1 || nw > 16) return CCQ_ERR_UNSUPPORTED;
+  const int mt = M > 16 ? 2 : 1;   // 16-row tiles of activations held by a workgroup
   const int S = L.tiles[kNarrow] / tpw;
   if (S > kMaxSplitsK || (S > 1 && !partial)) return CCQ_ERR_UNSUPPORTED;
   if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
@@ -1714,9 +1754,12 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
   a.n_last = L.N - 1;
   typedef void (*Kernel16)(const Args16);
   Kernel16 k = nullptr;
-  const int key = tpw * 100 + nw;
+  const int key = (mt - 1) * 1000 + tpw * 100 + nw;
   if (L.scale_mode == 0) {
     switch (key) {
+      case 1108: k = kernel32<1, 0, 8>; break;
+      case 1208: k = kernel32<2, 0, 8>; break;
+      case 1408: k = kernel32<4, 0, 8>; break;
       case 108: k = kernel16<1, 0, 8>; break;
       case 116: k = kernel16<1, 0, 16>; break;
       case 208: k = kernel16<2, 0, 8>; break;
@@ -1726,6 +1769,9 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
     }
   } else {
     switch (key) {
+      case 1108: k = kernel32<1, 1, 8>; break;
+      case 1208: k = kernel32<2, 1, 8>; break;
+      case 1408: k = kernel32<4, 1, 8>; break;
       case 108: k = kernel16<1, 1, 8>; break;
       case 116: k = kernel16<1, 1, 16>; break;
       case 208: k = kernel16<2, 1, 8>; break;
@@ -1735,7 +1781,7 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
     }
   }
   if (!k) return CCQ_ERR_UNSUPPORTED;
-  const size_t lds = (size_t)(tpw * 4) * (8 * 16 * 16 + 16 * 4);
+  const size_t lds = (size_t)(tpw * 4) * (8 * 16 * 16 + 16 * 4) * mt;
   if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
     (void)hipGetLastError();
     return CCQ_ERR_HIP;

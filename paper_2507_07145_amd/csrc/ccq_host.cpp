@@ -160,7 +160,12 @@ static DensePath dense_path(const Layout& L, int M) {
   // wide and hybrid-word formats (whose whole-k-tile staging is the costliest) and for 17-32 rows on the narrow one
   if (wide_only && M >= 2 && M < kMidMinM) return kPathRows;
   if (M < kMidMinM) return kPathSkinny;
-  if (narrow_only && M <= 32) return kPathRows;
+  if (narrow_only && M <= 32) {
+    // 17..32 rows: the 16-row kernel holding two 16-row tiles of activations, where K splits its way
+    int tpw = 0, nw = 0;
+    if (!L.has_map && gemv16_shape(L, 256, kMaxSplitsK, &tpw, &nw)) return kPathGemv16;
+    return kPathRows;
+  }
   if (narrow_only && M > 128) {
     // 256-row tiles pay off once they fill enough of the chip.  Both kernels are bound by the same two things (matrix
     // core time, and the vector work of decoding a weight tile once per row block of the output), so their times

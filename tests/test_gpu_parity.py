@@ -364,12 +364,12 @@ def test_workspace_guard_bands(kinds, K, N, M):
     y2 = b.bf16_bits(b.gemm(w, xt, workspace=ws))
     torch.cuda.synchronize()
     assert np.array_equal(y1, y2)
-    if M > 16:   # a smaller workspace is rejected
+    if M > 32 or (M > 16 and kinds != ["narrow"]):   # a smaller workspace is rejected
         with pytest.raises(b.CcqError) as ei:
             b.gemm(w, xt, workspace=buf[band:band + need - 16])
         assert ei.value.status == -5
     else:
-        # the 16-row kernels take fewer, longer shares of K when the workspace is smaller; where K does not split that
+        # the 16-row kernels (32 rows on the narrow format) take fewer, longer shares of K when the workspace is smaller; where K does not split that
         # way the call is either served by the general kernel or rejected, never wrong
         buf.fill_(0xFF)
         try:
@@ -496,6 +496,48 @@ def test_sixteen_row_kernel_wide_and_mixed(n_narrow, n_wide, cap, what, mode, M)
     x = synth.activations_bf16(M, K, synth.rng(18, 900 + G + M))
     assert_gemm_close(run(x), o.matmul(x, W), f"{M} rows, {what}, scale mode {mode}")
     ks = np.concatenate([[K - 1, 0, 59, 60, 61, 62, 63, 64, K - 64, K - 4, 17], synth.rng(18, 901).integers(0, K, 21)])
+    for i in range(0, len(ks), M):
+        kk = [int(k) for k in ks[i:i + M]]
+        kk += [kk[-1]] * (M - len(kk))
+        got = run(synth.one_hot_bf16(kk, K))
+        assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, kk].T))), f"{what}: decoded weights differ at columns {kk}"
+
+
+@pytest.mark.parametrize("G,cap,what", [(64, 32, "shares of one k-tile"), (64, 8, "shares of two"), (64, 4, "shares of four"),
+                                        (62, 4, "shares of four, the last k-tile ragged"), (16, 1, "all of K in one share: no partial tiles")])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("M", [5, 16, 17, 25, 32])
+def test_sixteen_and_32_row_kernel_narrow(G, cap, what, mode, M):
+    """Five to 32 activation rows on narrow-format weights: every share length of the 16-row kernel and of its variant
+    that holds two 16-row tiles of activations (17..32 rows); the workspace is sized for `cap` shares, which decides
+    the share length; both scale modes, N not a multiple of the eight row tiles a workgroup holds; decoded weights
+    bit-exact (one-hot rows), the product within tolerance, rows past M and columns past N untouched."""
+    K, N = 64 * G, 16 * 11 + 5
+    rng = synth.rng(20, G + mode)
+    codes = synth.random_codes(N, o.row_bytes(K, o.F2), rng)
+    alpha, beta = synth.cluster_params(N, rng)
+    if mode == 0:
+        scales = synth.scales_log_uniform_fp16(N, G, rng)
+        W = o.decode(K, N, o.F2, codes, scales, alpha, beta)
+        w = b.Weight.from_canonical(K, N, [b.NARROW], codes, scales, alpha, beta, device=DEV)
+    else:
+        sq = rng.integers(0, 256, size=(N, o.sq_row_bytes(K, o.F2)), dtype=np.uint8)
+        ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(N, 1, rng).reshape(N)) * 0.1).astype(np.float16).view(np.uint16)
+        W = o.decode_cs(K, N, o.F2, codes, sq, ssup, alpha, beta)
+        w = b.Weight.from_canonical_compressed(K, N, [b.NARROW], codes, sq, ssup, alpha, beta, device=DEV)
+    ws = torch.full((max(cap * M * w.info.padded_N * 4, 16),), 0xFF, dtype=torch.uint8, device=DEV)
+
+    def run(x_bits):
+        ld = (N + 7) // 8 * 8 + 8
+        y = torch.full((M + 1, ld), 3.140625, dtype=torch.bfloat16, device=DEV)
+        b.gemm(w, b.bf16_tensor(x_bits, DEV), out=y[:M, :N], workspace=ws)
+        torch.cuda.synchronize()
+        bits = b.bf16_bits(y)
+        assert np.all(bits[:M, N:] == 0x4049) and np.all(bits[M] == 0x4049), "wrote past the output"
+        return bits[:M, :N]
+    x = synth.activations_bf16(M, K, synth.rng(20, 900 + G + M))
+    assert_gemm_close(run(x), o.matmul(x, W), f"{M} rows, {what}, scale mode {mode}")
+    ks = np.concatenate([[K - 1, 0, 63, 64, K - 64, K - 4, 17], synth.rng(20, 901).integers(0, K, 2 * M - 7)])
     for i in range(0, len(ks), M):
         kk = [int(k) for k in ks[i:i + M]]
         kk += [kk[-1]] * (M - len(kk))
