@@ -952,9 +952,15 @@ __device__ __forceinline__ void rows16_body(const Args16& a) {
         acc[mt][2] = __builtin_fmaf(sc, p[2], acc[mt][2]);
         acc[mt][3] = __builtin_fmaf(sc, p[3], acc[mt][3]);
       }
-      // two tiles: keep the scheduler from pulling the fragment reads of later groups ahead (it would need more
-      // registers than four wavefronts per SIMD leave)
-      if constexpr (MT > 1) __builtin_amdgcn_sched_barrier(0);
+    }
+    // two tiles: the sums are pinned after every k-tile.  Left alone the compiler moves all scale multiplies to the end
+    // of the kernel (behind the wait for the scale loads) and keeps every group's MFMA result live until then: 128
+    // registers for those alone, 160 in all and three wavefronts per SIMD.  Pinned per k-tile: 76 registers; per group:
+    // 61, but small calls lose the overlap between groups.  With one tile the same pin costs time (config 2 at
+    // M = 8 / 16: 11.3 / 11.7 -> 12.3 / 12.9 us): its 100 registers already let every wavefront of such a call be resident
+    if constexpr (MT > 1) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) asm volatile("" : "+v"(acc[mt][0]), "+v"(acc[mt][1]), "+v"(acc[mt][2]), "+v"(acc[mt][3]));
     }
   }
   if constexpr (SM == 1) {
@@ -988,7 +994,7 @@ __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
 // 17..32 rows: two 16-row tiles of activations per workgroup (twice the LDS, two workgroups of eight wavefronts per CU:
 // the register budget of four wavefronts per SIMD)
 template <int TPW, int SM, int NW>
-__global__ void __launch_bounds__(64 * NW, 3) kernel32(const Args16 a) {
+__global__ void __launch_bounds__(64 * NW, 4) kernel32(const Args16 a) {
   rows16_body<TPW, SM, NW, 2>(a);
 }
 
@@ -1223,6 +1229,9 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
         acc[2] = __builtin_fmaf(sc, p[2], acc[2]);
         acc[3] = __builtin_fmaf(sc, p[3], acc[3]);
       }
+      // shares of two k-tiles: the sums are pinned after each (see rows16_body; 106 -> 74 registers, four -> six wavefronts
+      // per SIMD: all-wide 8192 x 28672 at M = 2 / 8 / 16 30.2 / 32.1 / 35.4 -> 27.7 / 30.0 / 32.2 us, smaller calls unchanged)
+      if constexpr (TPWW > 1) asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
     }
   }
   if constexpr (SM == 1) acc *= (float)__builtin_bit_cast(_Float16, (uint16_t)ssup);
