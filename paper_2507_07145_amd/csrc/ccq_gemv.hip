@@ -92,7 +92,9 @@ __device__ __forceinline__ void decode_dword(uint32_t d, float al, float be_magi
   }
 }
 
-template <int RT, int TPW, int SM>
+// RAGGED: the k-tile count is not a multiple of TPW; the last wavefront's share is shorter.  Its requests past the
+// last k-tile re-read that tile (a request never sits under a condition) and its loop skips them.
+template <int RT, int TPW, int SM, bool RAGGED = false>
 __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0) {
   constexpr int NG = TPW * 4;                         // groups per wavefront
   constexpr int NF = (NG * 8 + 63) / 64;              // x fragments per lane while staging
@@ -104,6 +106,7 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
   const uint32_t nwaves = blockDim.x >> 6;
   const uint32_t n = lane & 15u, kq = lane >> 4;
   const uint32_t t0 = wave * TPW;                     // first k-tile of this wavefront
+  const uint32_t t_last = (uint32_t)a.tiles - 1u;
   // ---- every request, before anything else ------------------------------------------------------------------
   // x: fragment f = (group * 2 + k-step) * 4 + quarter covers elements 64 group + 16 quarter + 8 k-step .. + 7
   u32x4 xv[NF];
@@ -132,13 +135,14 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
   for (int i = 0; i < TPW; ++i) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
+      const uint32_t ti = RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i;
       const uint16_t* sb = a.scales + ((size_t)(rtile0 + rt) * (uint32_t)a.tiles + t0) * SH;
       if constexpr (SM == 0) {
-        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u);
         sw[rt][i][0] = v.x;
         sw[rt][i][1] = v.y;
       } else {
-        sw[rt][i][0] = sb[i * 16u + n];   // the tile's four 4-bit fields of this row (first line of Alg. 3)
+        sw[rt][i][0] = sb[ti * 16u + n];   // the tile's four 4-bit fields of this row (first line of Alg. 3)
       }
     }
   }
@@ -147,8 +151,9 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
   for (int i = 0; i < TPW; ++i) {
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
+      const uint32_t ti = RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i;
       const uint8_t* cb = a.codes + ((size_t)(rtile0 + rt) * (uint32_t)a.tiles + t0) * 1024u;
-      cw[rt][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + i * 1024u + lane * 16u));
+      cw[rt][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + ti * 1024u + lane * 16u));
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -187,6 +192,7 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
   for (int rt = 0; rt < RT; ++rt) acc[rt] = 0.f;
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
+    if (RAGGED && t0 + i > t_last) break;   // uniform over the wavefront
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int lg = i * 4 + j;
@@ -245,9 +251,9 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
   }
 }
 
-template <int RT, int TPW, int SM>
+template <int RT, int TPW, int SM, bool RAGGED = false>
 __global__ void __launch_bounds__(1024) kernel(const Args a) {
-  rows1_body<RT, TPW, SM>(a, blockIdx.x * RT);
+  rows1_body<RT, TPW, SM, RAGGED>(a, blockIdx.x * RT);
 }
 
 // ---- two to four activation rows on narrow-format weights -----------------------------------------------------------
@@ -820,7 +826,7 @@ struct Args16 {
   int32_t g_last, n_last;           // last real group of K, last real output row (see Args)
 };
 
-template <int TPW, int SM, int NW, int MT>
+template <int TPW, int SM, int NW, int MT, bool RAGGED>
 __device__ __forceinline__ void rows16_body(const Args16& a) {
   constexpr int MR = 16 * MT;                  // activation rows held: MT tiles of 16 (MT = 2 serves 17..32 rows)
   constexpr int NG = TPW * 4;                  // groups per share
@@ -834,6 +840,7 @@ __device__ __forceinline__ void rows16_body(const Args16& a) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t n = lane & 15u, kq = lane >> 4;
   const uint32_t t0 = blockIdx.y * TPW;
+  const uint32_t t_last = (uint32_t)a.tiles - 1u;   // RAGGED: the last share is shorter; its requests past this tile re-read it
   const uint32_t rtile_raw = blockIdx.x * NW + wave;
   const bool active = rtile_raw < (uint32_t)a.row_tiles;
   const uint32_t rtile = active ? rtile_raw : (uint32_t)a.row_tiles - 1u;   // a ragged last block re-reads the last tile; nothing of it is stored
@@ -868,18 +875,20 @@ __device__ __forceinline__ void rows16_body(const Args16& a) {
   const uint16_t* sb = a.scales + ((size_t)rtile * (uint32_t)a.tiles + t0) * SH;
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
+    const uint32_t ti = RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i;
     if constexpr (SM == 0) {
-      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u);
       sw[i][0] = v.x;
       sw[i][1] = v.y;
     } else {
-      sw[i][0] = sb[i * 16u + n];
+      sw[i][0] = sb[ti * 16u + n];
     }
   }
   __builtin_amdgcn_sched_barrier(0);
   const uint8_t* cb = a.codes + ((size_t)rtile * (uint32_t)a.tiles + t0) * 1024u;
 #pragma unroll
-  for (int i = 0; i < TPW; ++i) cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + i * 1024u + lane * 16u));
+  for (int i = 0; i < TPW; ++i)
+    cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + (RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i) * 1024u + lane * 16u));
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- stage the activations: fragments in k-slot order {0,4,1,5,2,6,3,7} and the start values ----------------------
@@ -927,6 +936,7 @@ __device__ __forceinline__ void rows16_body(const Args16& a) {
   for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
+    if (RAGGED && t0 + i > t_last) break;   // uniform over the workgroup
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int lg = i * 4 + j;
@@ -987,15 +997,15 @@ __device__ __forceinline__ void rows16_body(const Args16& a) {
   }
 }
 
-template <int TPW, int SM, int NW>
+template <int TPW, int SM, int NW, bool RAGGED = false>
 __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
-  rows16_body<TPW, SM, NW, 1>(a);
+  rows16_body<TPW, SM, NW, 1, RAGGED>(a);
 }
 // 17..32 rows: two 16-row tiles of activations per workgroup (twice the LDS, two workgroups of eight wavefronts per CU:
 // the register budget of four wavefronts per SIMD)
-template <int TPW, int SM, int NW>
+template <int TPW, int SM, int NW, bool RAGGED = false>
 __global__ void __launch_bounds__(64 * NW, 4) kernel32(const Args16 a) {
-  rows16_body<TPW, SM, NW, 2>(a);
+  rows16_body<TPW, SM, NW, 2, RAGGED>(a);
 }
 
 // ---- two to sixteen activation rows on wide-format and mixed weights ------------------------------------------------
@@ -1252,16 +1262,16 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
 
 typedef void (*Kernel)(const Args);
 
-template <int SM>
+template <int SM, bool RAGGED>
 static Kernel pick_tpw(int tpw) {
   switch (tpw) {
-    case 1: return kernel<1, 1, SM>;
-    case 2: return kernel<1, 2, SM>;
-    case 3: return kernel<1, 3, SM>;
-    case 4: return kernel<1, 4, SM>;
-    case 6: return kernel<1, 6, SM>;
-    case 7: return kernel<1, 7, SM>;
-    case 8: return kernel<1, 8, SM>;
+    case 1: return RAGGED ? nullptr : kernel<1, 1, SM>;
+    case 2: return kernel<1, 2, SM, RAGGED>;
+    case 3: return kernel<1, 3, SM, RAGGED>;
+    case 4: return kernel<1, 4, SM, RAGGED>;
+    case 6: return kernel<1, 6, SM, RAGGED>;
+    case 7: return kernel<1, 7, SM, RAGGED>;
+    case 8: return kernel<1, 8, SM, RAGGED>;
     default: return nullptr;
   }
 }
@@ -1288,16 +1298,24 @@ bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out) {
     const int dist = std::abs(tpw - want) * 2 + (tpw < want ? 1 : 0);   // nearest; of two equally near the longer share
     if (dist < best_dist) { best_dist = dist; best = tpw; }
   }
-  if (best == 0) return false;
+  if (best == 0) {
+    // no equal split (43 k-tiles for K = 11008): the shortest built share that needs at most 16 wavefronts, the last
+    // of which gets what is left
+    for (int tpw : kBuilt) {
+      if (tpw >= 2 && (tiles + tpw - 1) / tpw <= 16) { best = tpw; break; }
+    }
+    if (best == 0) return false;
+  }
   *tpw_out = best;
-  *w_out = tiles / best;
+  *w_out = (tiles + best - 1) / best;
   return true;
 }
 
 int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves) {
   using namespace gemv;
-  if (tpw < 1 || waves < 1 || waves > 16 || waves * tpw != L.tiles[kNarrow] || L.tiles[kWide] != 0 || L.has_map) return CCQ_ERR_UNSUPPORTED;
+  if (tpw < 1 || waves < 1 || waves > 16 || waves != (L.tiles[kNarrow] + tpw - 1) / tpw || L.tiles[kWide] != 0 || L.has_map) return CCQ_ERR_UNSUPPORTED;
   if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
+  const bool ragged = waves * tpw != L.tiles[kNarrow];
   Args a;
   a.codes = static_cast<const uint8_t*>(w->codes);
   a.scales = static_cast<const uint16_t*>(w->scales);
@@ -1310,7 +1328,7 @@ int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, v
   a.cneg = -(128.f + L.zp[kNarrow]);
   a.g_last = L.G - 1;
   a.n_last = L.N - 1;
-  const Kernel k = L.scale_mode == 0 ? pick_tpw<0>(tpw) : pick_tpw<1>(tpw);
+  const Kernel k = L.scale_mode == 0 ? (ragged ? pick_tpw<0, true>(tpw) : pick_tpw<0, false>(tpw)) : (ragged ? pick_tpw<1, true>(tpw) : pick_tpw<1, false>(tpw));
   if (!k) return CCQ_ERR_UNSUPPORTED;
   const size_t lds = (size_t)waves * (tpw * 4) * (8 * 16 + 4 * 16);   // at most 16 * 32 * 192 bytes = 96 KiB
   if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -1725,6 +1743,18 @@ bool gemv16_shape(const Layout& L, int cus, int64_t max_shares, int* tpw_out, in
     pick = tpw;                                   // the shortest share that qualifies, unless a longer one fills the chip
     if (row_blocks * (tiles / tpw) >= cus) break;
   }
+  if (pick == 0 || tiles / pick > 16) {
+    // no equal split, or only one into many short shares (43 k-tiles for K = 11008): unequal shares, the last one
+    // shorter -- fewer partial tiles than 43 shares of one k-tile would write
+    int unequal = 0;
+    for (int tpw : {4, 2}) {
+      const int shares = (tiles + tpw - 1) / tpw;
+      if (shares > cap) continue;
+      unequal = tpw;
+      if (row_blocks * shares >= cus) break;
+    }
+    if (unequal != 0) pick = unequal;
+  }
   if (pick == 0) return false;
   *tpw_out = pick;
   *nw_out = nw;
@@ -1738,9 +1768,10 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
                   int nw, void* stream) {
   using namespace gemv;
   if (M < 1 || M > 32 || L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return CCQ_ERR_UNSUPPORTED;
-  if (tpw < 1 || L.tiles[kNarrow] % tpw != 0 || nw < 1 || nw > 16) return CCQ_ERR_UNSUPPORTED;
+  if (tpw < 1 || nw < 1 || nw > 16) return CCQ_ERR_UNSUPPORTED;
   const int mt = M > 16 ? 2 : 1;   // 16-row tiles of activations held by a workgroup
-  const int S = L.tiles[kNarrow] / tpw;
+  const int S = (L.tiles[kNarrow] + tpw - 1) / tpw;
+  const bool ragged = L.tiles[kNarrow] % tpw != 0;   // the last share is shorter
   if (S > kMaxSplitsK || (S > 1 && !partial)) return CCQ_ERR_UNSUPPORTED;
   if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
   Args16 a;
@@ -1763,9 +1794,13 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
   a.n_last = L.N - 1;
   typedef void (*Kernel16)(const Args16);
   Kernel16 k = nullptr;
-  const int key = (mt - 1) * 1000 + tpw * 100 + nw;
+  const int key = (ragged ? 10000 : 0) + (mt - 1) * 1000 + tpw * 100 + nw;
   if (L.scale_mode == 0) {
     switch (key) {
+      case 11208: k = kernel32<2, 0, 8, true>; break;
+      case 11408: k = kernel32<4, 0, 8, true>; break;
+      case 10208: k = kernel16<2, 0, 8, true>; break;
+      case 10408: k = kernel16<4, 0, 8, true>; break;
       case 1108: k = kernel32<1, 0, 8>; break;
       case 1208: k = kernel32<2, 0, 8>; break;
       case 1408: k = kernel32<4, 0, 8>; break;
@@ -1778,6 +1813,10 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
     }
   } else {
     switch (key) {
+      case 11208: k = kernel32<2, 1, 8, true>; break;
+      case 11408: k = kernel32<4, 1, 8, true>; break;
+      case 10208: k = kernel16<2, 1, 8, true>; break;
+      case 10408: k = kernel16<4, 1, 8, true>; break;
       case 1108: k = kernel32<1, 1, 8>; break;
       case 1208: k = kernel32<2, 1, 8>; break;
       case 1408: k = kernel32<4, 1, 8>; break;

@@ -208,13 +208,13 @@ static int64_t dense_need(const Layout& L, int M) {
     case kPathGemv: {
       int tpw = 0, waves = 0;
       // whether K splits does not depend on the chip
-      if (M == 1 ? (gemv1_shape(L, 256, &tpw, &waves) || gemv_narrow_shares(L) > 0) : gemv4_shape(L, 256, &tpw, &waves)) return 0;
+      if (M == 1 ? gemv1_shape(L, 256, &tpw, &waves) : gemv4_shape(L, 256, &tpw, &waves)) return 0;
       return skinny_need(L, M);
     }
     case kPathGemv16: {
       int tpw = 0, nw = 0;
       if (!gemv16_shape(L, device_cus(), kMaxSplitsK, &tpw, &nw)) return skinny_need(L, M);
-      const int S = L.tiles[kNarrow] / tpw;
+      const int S = (L.tiles[kNarrow] + tpw - 1) / tpw;
       return S > 1 ? (int64_t)S * M * L.Npad * 4 : 0;
     }
     case kPathGemv16NW: {
@@ -488,7 +488,7 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
       int tpw = 0, nw = 0;
       const int64_t plane = (int64_t)M * L.Npad * 4;
       if (gemv16_shape(L, device_cus(), std::max<int64_t>(1, have / plane), &tpw, &nw)) {
-        const int S = L.tiles[kNarrow] / tpw;
+        const int S = (L.tiles[kNarrow] + tpw - 1) / tpw;
         float* partial = S > 1 ? static_cast<float*>(workspace) : nullptr;
         rc = launch_gemv16(w, L, x, M, ldx, y, ldy, partial, tpw, nw, stream);
         if (rc == CCQ_OK && S > 1) rc = launch_reduce_splits(partial, y, ldy, M, L.N, L.Npad, S, stream);
@@ -531,10 +531,6 @@ int gemm_dispatch(const ccq_weight* w, const void* x, int32_t M, int64_t ldx, vo
       }
       if (M > 1 && gemv4_shape(L, device_cus(), &tpw, &waves)) {
         rc = launch_gemv4(w, L, x, M, ldx, y, ldy, stream, tpw, waves);
-        if (rc != CCQ_ERR_UNSUPPORTED) return rc;
-      }
-      if (M == 1) {
-        rc = launch_gemv_narrow(w, L, x, y, stream);
         if (rc != CCQ_ERR_UNSUPPORTED) return rc;
       }
     }

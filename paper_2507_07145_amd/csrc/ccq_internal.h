@@ -111,17 +111,12 @@ struct SkinnyCall {
 };
 int launch_skinny(const SkinnyCall& c);
 
-// Dense product of one row on narrow-format weights for k-tile counts the kernel below is not built for
-// (ccq_skinny.hip); CCQ_ERR_UNSUPPORTED when K does not split into equal shares of at most 12 k-tiles over at most 8
-// wavefronts (the caller then uses launch_skinny).
 constexpr int kGemvMaxM = 4;       // rows of the four-row kernel
-int gemv_narrow_shares(const Layout& L);  // wavefronts along K per workgroup; 0 = not applicable
-int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream);
 
 // One activation row on narrow-format weights (ccq_gemv.hip): shape of the launch for a chip of `cus` compute units
-// (false when K does not split into at most 16 equal shares of a built length), and the launcher; the same for two
-// to four rows (gemv4: also false when the four rows' activation fragments of all of K do not fit the LDS twice),
-// and for one row on wide-format and mixed weights (gemv_nw).
+// (false when K does not split into at most 16 shares of a built length, the last one possibly shorter), and the
+// launcher; the same for two to four rows (gemv4: equal shares only, and false when the four rows' activation fragments
+// of all of K do not fit the LDS twice), and for one row on wide-format and mixed weights (gemv_nw).
 bool gemv1_shape(const Layout& L, int cus, int* tpw_out, int* w_out);
 int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream, int tpw, int waves);
 bool gemv4_shape(const Layout& L, int cus, int* tpw_out, int* w_out);

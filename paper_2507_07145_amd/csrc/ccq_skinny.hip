@@ -967,143 +967,6 @@ __global__ void __launch_bounds__(skinny_max_threads(MT, MR, FM, SM)) ccq_skinny
   }
 }
 
-// ---- dense GEMV on narrow-format weights: the decode step of generation --------------------
-// Same arithmetic as the one-held-row path above (identical results), with everything that path
-// carries for the general case taken out: no experts, no row map, no format map, no K split over
-// workgroups, every wavefront owns the same number TPW <= kGemvMaxTiles of k-tiles and requests all
-// of them, and its activations, before it does anything else.  A call of this size lasts a few
-// microseconds, of which the argument fetch is a visible part: the arguments fit one 64-byte scalar
-// load.
-constexpr int kGemvMaxTiles = 12;
-struct GemvArgs {
-  const uint8_t* codes;
-  const uint16_t* scales;
-  const float* alpha;
-  const float* beta;
-  const uint16_t* x;
-  uint16_t* y;
-  int32_t row_tile_bytes;        // bytes of one row tile's code stream
-  int32_t row_tile_scale_halfs;
-  int32_t tpw;                   // k-tiles per wavefront; the workgroup's blockDim.x / 64 wavefronts cover K
-  float cneg;                    // -(128 + zp)
-  const uint16_t* scale_super;   // fp16 [N], compressed scales only (a second, 8-byte scalar load)
-  int32_t g_last, n_last;        // last real group of K and last real output row (see SkinnyArgs)
-};
-
-// NT = register sets for k-tiles (4, 8 or 12); the wavefront owns tpw <= NT tiles.  SM = scale mode.
-template <int NT, int SM>
-__global__ void __launch_bounds__(512) ccq_gemv_narrow_kernel(const GemvArgs a) {
-  constexpr int KN = kNarrow | (SM << 1);
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nwaves = blockDim.x >> 6;
-  const int rtile = blockIdx.x, n = a.tpw;
-  const int t0 = wave * n;  // first k-tile of this wavefront
-
-  // all requests go out before anything else: activations first (they are needed first), then every code
-  // tile of this wavefront, then the per-row parameters
-  uint4 xv[kPrivFrags];
-  stage_private_request<false>(xv, nullptr, a.x, t0 * kNarrowGroupsPerTile, n * kNarrowGroupsPerTile, a.g_last, lane);
-  float al[1], be[1];
-  const int prow = min(rtile * 16 + (lane & 15), a.n_last);
-  al[0] = a.alpha[prow];
-  const float be_raw = a.beta[prow];
-  // private staging region of this wavefront: fragments, then start values
-  const int frag_cap = n * kNarrowGroupsPerTile * 8, cneg_cap = n * kNarrowGroupsPerTile * 16;
-  uint4* my_x = reinterpret_cast<uint4*>(smem) + (size_t)wave * (frag_cap + cneg_cap / 4);
-  float* my_cneg = reinterpret_cast<float*>(my_x + frag_cap);
-  const uint8_t* codes = a.codes + (int64_t)rtile * a.row_tile_bytes + (int64_t)t0 * kNarrowTileBytes;
-  const uint16_t* scales = a.scales + (int64_t)rtile * a.row_tile_scale_halfs + (int64_t)t0 * Traits<KN>::SCALE_HALFS;
-  // unconditional requests (a request under a condition would make the first use wait for all of them);
-  // sets beyond tpw re-request the last tile and are not used
-  TileRegs<KN> buf[NT][1];
-#pragma unroll
-  for (int i = 0; i < NT; ++i) load_tile<KN>(buf[i][0], codes, scales, min(i, n - 1), lane);
-  uint16_t ssup_bits = 0;
-  if constexpr (SM == 1) ssup_bits = a.scale_super[prow];
-  stage_private_finish(xv, my_x, my_cneg, a.cneg, n * kNarrowGroupsPerTile, lane);
-  DecodeConsts dc = {0x43004300u, {0x003F003Fu, 0x000F000Fu, 0x00070007u}, {0.f, 0.f}};
-  float magic = 8388608.f;
-  asm volatile("" : "+v"(dc.c4300), "+s"(dc.mask[0]), "+s"(dc.mask[1]), "+v"(magic));
-  dc.ssup[0] = (float)__builtin_bit_cast(_Float16, ssup_bits);
-  be[0] = be_raw + magic;  // + 2^23: exact, beta is an integer below 2^15
-
-  f32x4 acc[1][1] = {{f32x4{0.f, 0.f, 0.f, 0.f}}};
-#pragma unroll
-  for (int i = 0; i < NT; ++i) {
-    if (i < n) process_tile<KN, 1, 1, 1, 0, kNarrowGroupsPerTile>(buf[i], i * kNarrowGroupsPerTile, my_x, my_cneg, al, be, acc, lane, dc);
-  }
-
-  // the four quarters of a row, then the wavefronts of the workgroup (fixed order)
-  float v = acc[0][0][0];
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
-  if (nwaves > 1) {
-    __syncthreads();
-    float* red = reinterpret_cast<float*>(smem);
-    if (wave > 0 && lane < 16) red[(wave - 1) * 16 + lane] = v;
-    __syncthreads();
-    if (wave == 0 && lane < 16) {
-      for (int k = 1; k < nwaves; ++k) v += red[(k - 1) * 16 + lane];
-    }
-  }
-  if constexpr (SM == 1) v *= dc.ssup[0];  // compressed scales: the row's super scale, once (see group_scale)
-  if (wave == 0 && lane < 16 && rtile * 16 + lane <= a.n_last) a.y[rtile * 16 + lane] = f32_to_bf16_rne(v);
-}
-
-// Wavefronts per workgroup of this GEMV kernel = shares of K: a divisor of the k-tile count, at most 8.  Many short
-// wavefronts (4 k-tiles each) hide the latency chain of a call this small best; when that would be more wavefronts
-// than the chip holds at once (8 per SIMD), shares of 8 tiles are better.
-// 0: K does not split that way (the caller uses the general kernel).
-int gemv_narrow_shares(const Layout& L) {
-  if (L.tiles[kWide] != 0 || L.has_map) return 0;
-  if (L.row_tile_bytes >= ((int64_t)1 << 31) || L.row_tile_scale_halfs >= ((int64_t)1 << 31)) return 0;
-  const int tiles = L.tiles[kNarrow];
-  const int target = (int64_t)L.row_tiles * tiles / 4 <= 32 * (int64_t)device_cus() ? 4 : 8;
-  int wk = 0, best = 1 << 30;
-  for (int c = 1; c <= 8; ++c) {
-    if (tiles % c != 0 || tiles / c > kGemvMaxTiles) continue;
-    const int dist = std::abs(tiles / c - target);
-    if (dist < best) { best = dist; wk = c; }
-  }
-  return wk;
-}
-
-int launch_gemv_narrow(const ccq_weight* w, const Layout& L, const void* x, void* y, void* stream) {
-  const int wk = gemv_narrow_shares(L);
-  if (wk == 0) return CCQ_ERR_UNSUPPORTED;  // the caller falls back to the general kernel
-  const int tiles = L.tiles[kNarrow];
-  GemvArgs a;
-  a.codes = static_cast<const uint8_t*>(w->codes);
-  a.scales = static_cast<const uint16_t*>(w->scales);
-  a.alpha = w->code_alpha;
-  a.beta = w->code_beta;
-  a.x = static_cast<const uint16_t*>(x);
-  a.y = static_cast<uint16_t*>(y);
-  a.row_tile_bytes = (int32_t)L.row_tile_bytes;
-  a.row_tile_scale_halfs = (int32_t)L.row_tile_scale_halfs;
-  a.tpw = tiles / wk;
-  a.cneg = -(128.f + L.zp[kNarrow]);
-  a.scale_super = static_cast<const uint16_t*>(w->scale_super);
-  a.g_last = L.G - 1;
-  a.n_last = L.N - 1;
-  const dim3 grid((unsigned)L.row_tiles), block((unsigned)(64 * wk));
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const size_t lds = (size_t)wk * a.tpw * kNarrowGroupsPerTile * (8 * 16 + 4 * 16);
-  if (L.scale_mode == 0) {
-    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 0>), grid, block, lds, st, a);
-    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 0>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 0>), grid, block, lds, st, a);
-  } else {
-    if (a.tpw <= 4) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<4, 1>), grid, block, lds, st, a);
-    else if (a.tpw <= 8) hipLaunchKernelGGL((ccq_gemv_narrow_kernel<8, 1>), grid, block, lds, st, a);
-    else hipLaunchKernelGGL((ccq_gemv_narrow_kernel<kGemvMaxTiles, 1>), grid, block, lds, st, a);
-  }
-  if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
-  return CCQ_OK;
-}
-
 // y[p][n] = bf16( sum_s partial[s][p][n] ), splits added in index order.  `partial` rows hold Npad (a multiple of 16)
 // floats of which the first N are results.  Four consecutive columns per thread (partial and y rows are 16-byte
 // aligned); all S requests of a thread go out before the first add.

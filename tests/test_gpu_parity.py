@@ -416,6 +416,40 @@ def test_one_row_kernel_every_share_shape(n_narrow, n_wide, what, mode):
         assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, [int(k)]].T))), f"{what}: decoded weights differ at column {k}"
 
 
+@pytest.mark.parametrize("G,N,what", [(172, 96, "43 k-tiles (K = 11008): 15 shares of three, the last of one"),
+                                      (68, 40, "17 k-tiles: nine shares of two, the last of one"),
+                                      (170, 200, "43 k-tiles, the last one ragged too"),
+                                      (296, 64, "74 k-tiles (K = 18944): 13 shares of six, the last of two"),
+                                      (344, 32, "86 k-tiles (K = 22016): 15 shares of six, the last of two"),
+                                      (432, 32, "108 k-tiles (K = 27648): 16 shares of seven, the last of three"),
+                                      (462, 16, "116 k-tiles (K = 29568): 15 shares of eight, the last of four")])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_one_row_kernel_unequal_shares(G, N, what, mode):
+    """One activation row on narrow-format weights whose k-tile count has no split into at most 16 equal shares (the
+    K of several common models): the last wavefront's share is shorter.  Product within tolerance, decoded weights bit
+    for bit at the ends of K, around the last share and at random columns."""
+    K = 64 * G
+    rng = synth.rng(21, G + mode)
+    codes = synth.random_codes(N, o.row_bytes(K, o.F2), rng)
+    alpha, beta = synth.cluster_params(N, rng)
+    if mode == 0:
+        scales = synth.scales_log_uniform_fp16(N, G, rng)
+        W = o.decode(K, N, o.F2, codes, scales, alpha, beta)
+        w = b.Weight.from_canonical(K, N, [b.NARROW], codes, scales, alpha, beta, device=DEV)
+    else:
+        sq = rng.integers(0, 256, size=(N, o.sq_row_bytes(K, o.F2)), dtype=np.uint8)
+        ssup = (o.fp16_bits_to_f64(synth.scales_log_uniform_fp16(N, 1, rng).reshape(N)) * 0.1).astype(np.float16).view(np.uint16)
+        W = o.decode_cs(K, N, o.F2, codes, sq, ssup, alpha, beta)
+        w = b.Weight.from_canonical_compressed(K, N, [b.NARROW], codes, sq, ssup, alpha, beta, device=DEV)
+    x = synth.activations_bf16(1, K, synth.rng(21, 900 + G))
+    assert_gemm_close(_gemm_bits(w, x), o.matmul(x, W), f"one row, {what}, scale mode {mode}")
+    ks = np.concatenate([[0, 63, 64, K - 1, K - 64, K - 65, K - 256, K - 257, K - 512, K - 1024, K - 2048], synth.rng(21, 901).integers(0, K, 13)])
+    for k in ks:
+        k = int(max(k, 0))
+        got = _gemm_bits(w, synth.one_hot_bf16([k], K))
+        assert np.array_equal(canon_zero(got), canon_zero(o.to_bf16_bits(W[:, [k]].T))), f"{what}: decoded weights differ at column {k}"
+
+
 @pytest.mark.parametrize("G,N,what", [(16, 100, "shares of one k-tile"), (15, 40, "shares of one, the last k-tile ragged"),
                                       (128, 400, "16 shares of two"), (110, 1000, "14 shares of two, ragged K and N"),
                                       (84, 72, "7 shares of three"), (128, 8208, "8 shares of four: more wavefronts than the chip holds"),
@@ -504,7 +538,9 @@ def test_sixteen_row_kernel_wide_and_mixed(n_narrow, n_wide, cap, what, mode, M)
 
 
 @pytest.mark.parametrize("G,cap,what", [(64, 32, "shares of one k-tile"), (64, 8, "shares of two"), (64, 4, "shares of four"),
-                                        (62, 4, "shares of four, the last k-tile ragged"), (16, 1, "all of K in one share: no partial tiles")])
+                                        (62, 4, "shares of four, the last k-tile ragged"), (16, 1, "all of K in one share: no partial tiles"),
+                                        (172, 32, "43 k-tiles (K = 11008): unequal shares, ten of four and one of three"),
+                                        (172, 24, "43 k-tiles: 22 shares of two, the last of one"), (68, 32, "17 k-tiles: unequal shares")])
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("M", [5, 16, 17, 25, 32])
 def test_sixteen_and_32_row_kernel_narrow(G, cap, what, mode, M):
