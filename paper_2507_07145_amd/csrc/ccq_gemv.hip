@@ -269,7 +269,7 @@ struct Args4 {
 };
 
 // `rows`: NULL (activation row r is row r of x) or the rows' indices in x (the grouped product gathers them).
-template <int TPW, int SM>
+template <int TPW, int SM, bool RAGGED = false>
 __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, const int64_t ldy, const int32_t M, const int32_t* rows, const uint32_t rtile) {
   constexpr int NG = TPW * 4;                             // groups per wavefront
   constexpr int NF = NG * 8 * 4 / 64;                     // staging units (fragment, row) per lane
@@ -281,6 +281,7 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
   const uint32_t nwaves = blockDim.x >> 6;
   const uint32_t n = lane & 15u, kq = lane >> 4;
   const uint32_t t0 = wave * TPW;
+  const uint32_t t_last = (uint32_t)a.tiles - 1u;   // RAGGED: see rows1_body
   // ---- every request, before anything else ------------------------------------------------------------------
   // unit u = lane + 64 i: bits 0-2 = the fragment's (quarter, k-step), bits 3-4 = activation row, the rest = group;
   // a lane stages the same row in all of its units
@@ -305,18 +306,20 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
   const uint16_t* sb = a.scales + ((size_t)rtile * (uint32_t)a.tiles + t0) * SH;
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
+    const uint32_t ti = RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i;
     if constexpr (SM == 0) {
-      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u);
       sw[i][0] = v.x;
       sw[i][1] = v.y;
     } else {
-      sw[i][0] = sb[i * 16u + n];
+      sw[i][0] = sb[ti * 16u + n];
     }
   }
   __builtin_amdgcn_sched_barrier(0);
   const uint8_t* cb = a.codes + ((size_t)rtile * (uint32_t)a.tiles + t0) * 1024u;
 #pragma unroll
-  for (int i = 0; i < TPW; ++i) cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + i * 1024u + lane * 16u));
+  for (int i = 0; i < TPW; ++i)
+    cw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + (RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i) * 1024u + lane * 16u));
   __builtin_amdgcn_sched_barrier(0);
   // ---- stage x: fragment f of row r at [f][r], start values -(128 + zp) sum x at [group][quarter][r] ---------------
   unsigned char* region = smem + (size_t)wave * REGION;
@@ -347,6 +350,7 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
   const uint32_t mr = lane & 3u;   // the activation row this lane supplies to its 4x4 block
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
+    if (RAGGED && t0 + i > t_last) break;   // uniform over the wavefront
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int lg = i * 4 + j;
@@ -394,9 +398,9 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
   }
 }
 
-template <int TPW, int SM>
+template <int TPW, int SM, bool RAGGED = false>
 __global__ void __launch_bounds__(1024) kernel4(const Args4 aa) {
-  rows4_body<TPW, SM>(aa.a, aa.ldx, aa.ldy, aa.M, nullptr, blockIdx.x);
+  rows4_body<TPW, SM, RAGGED>(aa.a, aa.ldx, aa.ldy, aa.M, nullptr, blockIdx.x);
 }
 
 // ---- grouped product with at most four rows per expert (one or a few tokens' decode step of a mixture of experts:
@@ -1339,12 +1343,13 @@ int launch_gemv1(const ccq_weight* w, const Layout& L, const void* x, void* y, v
   return hipGetLastError() == hipSuccess ? CCQ_OK : CCQ_ERR_HIP;
 }
 
-// Two to four rows: the same shares, as long as the four rows' fragments of all of K fit the LDS of a CU twice
-// (2304 bytes per k-tile) -- beyond that one workgroup per CU is left and the 16-row kernel is faster.
+// Two to four rows: the same shares (of one to four k-tiles), as long as the four rows' fragments of all of K fit the LDS
+// of a CU (2304 bytes per k-tile: K <= 16384).  Beyond 35 k-tiles only one workgroup fits a CU and the kernel still
+// beats the 16-row one with its second launch (12288 x 4096 at M = 4: 7.8 against 13.1 us; 16384 x 4096: 9.3 against 13.7).
 bool gemv4_shape(const Layout& L, int cus, int* tpw_out, int* w_out) {
   if (L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return false;
   const int tiles = L.tiles[kNarrow];
-  if ((int64_t)tiles * 2304 > 80 * 1024) return false;
+  if ((int64_t)tiles * 2304 > 150 * 1024) return false;
   const int64_t waves2 = (int64_t)L.row_tiles * ((tiles + 1) / 2);
   int want = 2;
   if (waves2 > (int64_t)32 * cus) want = 4;
@@ -1355,15 +1360,21 @@ bool gemv4_shape(const Layout& L, int cus, int* tpw_out, int* w_out) {
     const int dist = std::abs(tpw - want) * 2 + (tpw < want ? 1 : 0);
     if (dist < best_dist) { best_dist = dist; best = tpw; }
   }
-  if (best == 0) return false;
+  if (best == 0) {   // no equal split: unequal shares, the last one shorter (see gemv1_shape)
+    for (int tpw : {2, 3, 4}) {
+      if ((tiles + tpw - 1) / tpw <= 16) { best = tpw; break; }
+    }
+    if (best == 0) return false;
+  }
   *tpw_out = best;
-  *w_out = tiles / best;
+  *w_out = (tiles + best - 1) / best;
   return true;
 }
 
 int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int64_t ldx, void* y, int64_t ldy, void* stream, int tpw, int waves) {
   using namespace gemv;
-  if (M < 1 || M > 4 || waves < 1 || waves > 16 || waves * tpw != L.tiles[kNarrow] || L.tiles[kWide] != 0 || L.has_map) return CCQ_ERR_UNSUPPORTED;
+  if (M < 1 || M > 4 || tpw < 1 || waves < 1 || waves > 16 || waves != (L.tiles[kNarrow] + tpw - 1) / tpw || L.tiles[kWide] != 0 || L.has_map) return CCQ_ERR_UNSUPPORTED;
+  const bool ragged = waves * tpw != L.tiles[kNarrow];
   if ((int64_t)L.row_tiles * L.tiles[kNarrow] * 1024 >= ((int64_t)1 << 40)) return CCQ_ERR_UNSUPPORTED;
   Args4 a4;
   Args& a = a4.a;
@@ -1383,8 +1394,14 @@ int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int
   a4.M = M;
   typedef void (*Kernel4)(const Args4);
   Kernel4 k = nullptr;
-  if (L.scale_mode == 0) k = tpw == 1 ? kernel4<1, 0> : (tpw == 2 ? kernel4<2, 0> : (tpw == 3 ? kernel4<3, 0> : (tpw == 4 ? kernel4<4, 0> : nullptr)));
-  else k = tpw == 1 ? kernel4<1, 1> : (tpw == 2 ? kernel4<2, 1> : (tpw == 3 ? kernel4<3, 1> : (tpw == 4 ? kernel4<4, 1> : nullptr)));
+  if (ragged) {
+    if (L.scale_mode == 0) k = tpw == 2 ? kernel4<2, 0, true> : (tpw == 3 ? kernel4<3, 0, true> : (tpw == 4 ? kernel4<4, 0, true> : nullptr));
+    else k = tpw == 2 ? kernel4<2, 1, true> : (tpw == 3 ? kernel4<3, 1, true> : (tpw == 4 ? kernel4<4, 1, true> : nullptr));
+  } else if (L.scale_mode == 0) {
+    k = tpw == 1 ? kernel4<1, 0> : (tpw == 2 ? kernel4<2, 0> : (tpw == 3 ? kernel4<3, 0> : (tpw == 4 ? kernel4<4, 0> : nullptr)));
+  } else {
+    k = tpw == 1 ? kernel4<1, 1> : (tpw == 2 ? kernel4<2, 1> : (tpw == 3 ? kernel4<3, 1> : (tpw == 4 ? kernel4<4, 1> : nullptr)));
+  }
   if (!k) return CCQ_ERR_UNSUPPORTED;
   const size_t lds = (size_t)waves * tpw * 2304;   // 576 bytes per group: 8 fragments of 4 rows, 16 start values
   if (lds > 160 * 1024) return CCQ_ERR_UNSUPPORTED;
@@ -1402,7 +1419,7 @@ int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int
 bool gemv_grouped_shape(const Layout& L, int cus, int experts, bool four, int* tpw_out, int* w_out) {
   if (L.tiles[kWide] != 0 || L.has_map || L.tiles[kNarrow] < 1) return false;
   const int tiles = L.tiles[kNarrow];
-  if (four && (int64_t)tiles * 2304 > 80 * 1024) return false;
+  if (four && (int64_t)tiles * 2304 > 150 * 1024) return false;
   const int64_t waves2 = (int64_t)L.row_tiles * std::max(1, experts) * ((tiles + 1) / 2);
   int want = 2;
   if (waves2 > (int64_t)32 * cus) want = 4;   // also with four rows: shares of two measured 14-30 % slower on 100-224 experts of 1024 x 7168

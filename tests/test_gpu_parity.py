@@ -453,7 +453,10 @@ def test_one_row_kernel_unequal_shares(G, N, what, mode):
 @pytest.mark.parametrize("G,N,what", [(16, 100, "shares of one k-tile"), (15, 40, "shares of one, the last k-tile ragged"),
                                       (128, 400, "16 shares of two"), (110, 1000, "14 shares of two, ragged K and N"),
                                       (84, 72, "7 shares of three"), (128, 8208, "8 shares of four: more wavefronts than the chip holds"),
-                                      (132, 64, "33 k-tiles: 11 shares of three"), (144, 64, "36 k-tiles: the 16-row kernel")])
+                                      (132, 64, "33 k-tiles: 11 shares of three"), (144, 64, "36 k-tiles: one workgroup per CU"),
+                                      (172, 40, "43 k-tiles (K = 11008): unequal shares, 14 of three and one of one"),
+                                      (256, 32, "64 k-tiles: 16 shares of four, 144 KiB of LDS"),
+                                      (260, 32, "65 k-tiles: no split into 16 shares, the 16-row kernel")])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_four_row_kernel_every_share_shape(G, N, what, mode):
     """Two to four activation rows on narrow-format weights (the GEMV operator of Table 4 with M = 4): every share length

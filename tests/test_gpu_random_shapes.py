@@ -203,7 +203,8 @@ def test_random_ragged_grouped_case(seed):
                                              ("narrow", 8, 1000, [2, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 3], "up to four rows, most experts without rows"),
                                              ("narrow", 132, 64, [4, 4], "four rows, 11 shares of three"),
                                              ("narrow", 16, 200, [1, 2, 9, 1, 0, 1, 3, 1, 2, 1, 1, 1], "one expert with nine rows: the general kernel"),
-                                             ("narrow", 144, 64, [4, 1, 2], "36 k-tiles: four rows do not fit, the general kernel"),
+                                             ("narrow", 144, 64, [4, 1, 2], "36 k-tiles: one workgroup per CU"),
+                                             ("narrow", 268, 32, [3, 1], "67 k-tiles: four rows do not fit the LDS, the general kernel"),
                                              ("wide", 16, 1000, [1, 0, 1, 1, 0, 0, 1], "wide format, one row per expert, shares of two k-tiles"),
                                              ("wide", 13, 40, [1, 1], "wide format, ragged last k-tile, every expert has a row"),
                                              ("mixed", 24, 200, [0, 1, 1, 0, 1], "per-group mix, one row per expert"),
