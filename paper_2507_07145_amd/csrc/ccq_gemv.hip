@@ -251,9 +251,13 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
   }
 }
 
-template <int RT, int TPW, int SM, bool RAGGED = false>
+template <int RT, int TPW, int SM>
 __global__ void __launch_bounds__(1024) kernel(const Args a) {
-  rows1_body<RT, TPW, SM, RAGGED>(a, blockIdx.x * RT);
+  rows1_body<RT, TPW, SM, false>(a, blockIdx.x * RT);
+}
+template <int TPW, int SM>
+__global__ void __launch_bounds__(1024) kernel_unequal(const Args a) {   // the last wavefront's share of K is shorter
+  rows1_body<1, TPW, SM, true>(a, blockIdx.x);
 }
 
 // ---- two to four activation rows on narrow-format weights -----------------------------------------------------------
@@ -398,9 +402,13 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
   }
 }
 
-template <int TPW, int SM, bool RAGGED = false>
+template <int TPW, int SM>
 __global__ void __launch_bounds__(1024) kernel4(const Args4 aa) {
-  rows4_body<TPW, SM, RAGGED>(aa.a, aa.ldx, aa.ldy, aa.M, nullptr, blockIdx.x);
+  rows4_body<TPW, SM, false>(aa.a, aa.ldx, aa.ldy, aa.M, nullptr, blockIdx.x);
+}
+template <int TPW, int SM>
+__global__ void __launch_bounds__(1024) kernel4_unequal(const Args4 aa) {
+  rows4_body<TPW, SM, true>(aa.a, aa.ldx, aa.ldy, aa.M, nullptr, blockIdx.x);
 }
 
 // ---- grouped product with at most four rows per expert (one or a few tokens' decode step of a mixture of experts:
@@ -1001,15 +1009,23 @@ __device__ __forceinline__ void rows16_body(const Args16& a) {
   }
 }
 
-template <int TPW, int SM, int NW, bool RAGGED = false>
+template <int TPW, int SM, int NW>
 __global__ void __launch_bounds__(64 * NW) kernel16(const Args16 a) {
-  rows16_body<TPW, SM, NW, 1, RAGGED>(a);
+  rows16_body<TPW, SM, NW, 1, false>(a);
+}
+template <int TPW, int SM, int NW>
+__global__ void __launch_bounds__(64 * NW) kernel16_unequal(const Args16 a) {   // the last share of K is shorter
+  rows16_body<TPW, SM, NW, 1, true>(a);
 }
 // 17..32 rows: two 16-row tiles of activations per workgroup (twice the LDS, two workgroups of eight wavefronts per CU:
 // the register budget of four wavefronts per SIMD)
-template <int TPW, int SM, int NW, bool RAGGED = false>
+template <int TPW, int SM, int NW>
 __global__ void __launch_bounds__(64 * NW, 4) kernel32(const Args16 a) {
-  rows16_body<TPW, SM, NW, 2, RAGGED>(a);
+  rows16_body<TPW, SM, NW, 2, false>(a);
+}
+template <int TPW, int SM, int NW>
+__global__ void __launch_bounds__(64 * NW, 4) kernel32_unequal(const Args16 a) {
+  rows16_body<TPW, SM, NW, 2, true>(a);
 }
 
 // ---- two to sixteen activation rows on wide-format and mixed weights ------------------------------------------------
@@ -1268,15 +1284,27 @@ typedef void (*Kernel)(const Args);
 
 template <int SM, bool RAGGED>
 static Kernel pick_tpw(int tpw) {
-  switch (tpw) {
-    case 1: return RAGGED ? nullptr : kernel<1, 1, SM>;
-    case 2: return kernel<1, 2, SM, RAGGED>;
-    case 3: return kernel<1, 3, SM, RAGGED>;
-    case 4: return kernel<1, 4, SM, RAGGED>;
-    case 6: return kernel<1, 6, SM, RAGGED>;
-    case 7: return kernel<1, 7, SM, RAGGED>;
-    case 8: return kernel<1, 8, SM, RAGGED>;
-    default: return nullptr;
+  if constexpr (RAGGED) {
+    switch (tpw) {
+      case 2: return kernel_unequal<2, SM>;
+      case 3: return kernel_unequal<3, SM>;
+      case 4: return kernel_unequal<4, SM>;
+      case 6: return kernel_unequal<6, SM>;
+      case 7: return kernel_unequal<7, SM>;
+      case 8: return kernel_unequal<8, SM>;
+      default: return nullptr;
+    }
+  } else {
+    switch (tpw) {
+      case 1: return kernel<1, 1, SM>;
+      case 2: return kernel<1, 2, SM>;
+      case 3: return kernel<1, 3, SM>;
+      case 4: return kernel<1, 4, SM>;
+      case 6: return kernel<1, 6, SM>;
+      case 7: return kernel<1, 7, SM>;
+      case 8: return kernel<1, 8, SM>;
+      default: return nullptr;
+    }
   }
 }
 
@@ -1395,8 +1423,8 @@ int launch_gemv4(const ccq_weight* w, const Layout& L, const void* x, int M, int
   typedef void (*Kernel4)(const Args4);
   Kernel4 k = nullptr;
   if (ragged) {
-    if (L.scale_mode == 0) k = tpw == 2 ? kernel4<2, 0, true> : (tpw == 3 ? kernel4<3, 0, true> : (tpw == 4 ? kernel4<4, 0, true> : nullptr));
-    else k = tpw == 2 ? kernel4<2, 1, true> : (tpw == 3 ? kernel4<3, 1, true> : (tpw == 4 ? kernel4<4, 1, true> : nullptr));
+    if (L.scale_mode == 0) k = tpw == 2 ? kernel4_unequal<2, 0> : (tpw == 3 ? kernel4_unequal<3, 0> : (tpw == 4 ? kernel4_unequal<4, 0> : nullptr));
+    else k = tpw == 2 ? kernel4_unequal<2, 1> : (tpw == 3 ? kernel4_unequal<3, 1> : (tpw == 4 ? kernel4_unequal<4, 1> : nullptr));
   } else if (L.scale_mode == 0) {
     k = tpw == 1 ? kernel4<1, 0> : (tpw == 2 ? kernel4<2, 0> : (tpw == 3 ? kernel4<3, 0> : (tpw == 4 ? kernel4<4, 0> : nullptr)));
   } else {
@@ -1814,10 +1842,10 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
   const int key = (ragged ? 10000 : 0) + (mt - 1) * 1000 + tpw * 100 + nw;
   if (L.scale_mode == 0) {
     switch (key) {
-      case 11208: k = kernel32<2, 0, 8, true>; break;
-      case 11408: k = kernel32<4, 0, 8, true>; break;
-      case 10208: k = kernel16<2, 0, 8, true>; break;
-      case 10408: k = kernel16<4, 0, 8, true>; break;
+      case 11208: k = kernel32_unequal<2, 0, 8>; break;
+      case 11408: k = kernel32_unequal<4, 0, 8>; break;
+      case 10208: k = kernel16_unequal<2, 0, 8>; break;
+      case 10408: k = kernel16_unequal<4, 0, 8>; break;
       case 1108: k = kernel32<1, 0, 8>; break;
       case 1208: k = kernel32<2, 0, 8>; break;
       case 1408: k = kernel32<4, 0, 8>; break;
@@ -1830,10 +1858,10 @@ int launch_gemv16(const ccq_weight* w, const Layout& L, const void* x, int M, in
     }
   } else {
     switch (key) {
-      case 11208: k = kernel32<2, 1, 8, true>; break;
-      case 11408: k = kernel32<4, 1, 8, true>; break;
-      case 10208: k = kernel16<2, 1, 8, true>; break;
-      case 10408: k = kernel16<4, 1, 8, true>; break;
+      case 11208: k = kernel32_unequal<2, 1, 8>; break;
+      case 11408: k = kernel32_unequal<4, 1, 8>; break;
+      case 10208: k = kernel16_unequal<2, 1, 8>; break;
+      case 10408: k = kernel16_unequal<4, 1, 8>; break;
       case 1108: k = kernel32<1, 1, 8>; break;
       case 1208: k = kernel32<2, 1, 8>; break;
       case 1408: k = kernel32<4, 1, 8>; break;

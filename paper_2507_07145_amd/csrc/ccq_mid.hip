@@ -81,13 +81,15 @@ __device__ __forceinline__ uint32_t dword_sel(const u32x4& v, int j) { return j 
 // scales; 1 the compressed scales of Sec. 3.4: group scale = 4-bit field * per-row super scale, first line of
 // Alg. 2 / Alg. 3; the field of a narrow group comes from the packed scale array, that of a wide group from the
 // spare low nibble of the group's last code byte).
-// NWV: wavefronts per workgroup.  4: each decodes two of the block's eight 16-row weight tiles and multiplies all 64
-// activation rows with its 32 columns.  8 (what is launched): each decodes one weight tile and multiplies 32 activation
-// rows with 32 columns (wavefronts 0-3 the first 32 rows, 4-7 the others): half the work per wavefront, twice the
-// wavefronts per SIMD, 100-119 registers instead of 150-178.  Measured against 4 on the same box, 8192 x 8192 at
-// M = 64: wide 28.1 -> 24.9 us, a 3:1 mix 46.1 -> 35.2, hybrid word 35.0 -> 31.2; 8192 x 28672: 2-6 % less; M = 2048: 2-4 % less.
-template <int FM, int SM, bool GROUPED, int NWV = 8>
-__global__ void __launch_bounds__(64 * NWV) ccq_mid_kernel(const MidArgs a) {
+// Wavefronts per workgroup (kMidWaves): eight; each decodes one of the block's eight 16-row weight tiles and multiplies 32
+// activation rows with 32 columns (wavefronts 0-3 the first 32 rows, 4-7 the others).  With four (two weight tiles and a
+// 64 x 32 wave tile each: twice the work per wavefront, half the wavefronts per SIMD, 150-178 registers instead of
+// 100-119) the same code measured slower on the same box: 8192 x 8192 at M = 64 wide 28.1 -> 24.9 us, a 3:1 mix
+// 46.1 -> 35.2, hybrid word 35.0 -> 31.2; 8192 x 28672: 2-6 % less; M = 2048: 2-4 % less.
+constexpr int kMidWaves = 8;
+template <int FM, int SM, bool GROUPED>
+__global__ void __launch_bounds__(64 * kMidWaves) ccq_mid_kernel(const MidArgs a) {
+  constexpr int NWV = kMidWaves;
   constexpr int kMidRTW = 8 / NWV;   // 16-row weight tiles per wavefront
   constexpr int NT = 64 * NWV;       // threads
   constexpr int AI = 8 / NWV;        // 32-row accumulator tiles per wavefront
@@ -751,7 +753,7 @@ int launch_mid(const ccq_weight* w, const Layout& L, const void* x, int M, int64
     (void)hipGetLastError();
     return CCQ_ERR_HIP;
   }
-  dim3 grid((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block(512);   // eight wavefronts
+  dim3 grid((unsigned)(a.m_blocks * n_blocks), (unsigned)S), block(64 * kMidWaves);
   hipLaunchKernelGGL(kern, grid, block, lds, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
@@ -818,7 +820,7 @@ int launch_mid_grouped(const ccq_weight* w0, const Layout& L, int E, int64_t cod
     (void)hipGetLastError();
     return CCQ_ERR_HIP;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(512), lds, static_cast<hipStream_t>(stream), a);   // eight wavefronts
+  hipLaunchKernelGGL(kern, grid, dim3(64 * kMidWaves), lds, static_cast<hipStream_t>(stream), a);
   if (hipGetLastError() != hipSuccess) return CCQ_ERR_HIP;
   return CCQ_OK;
 }
