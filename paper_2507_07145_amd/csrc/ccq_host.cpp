@@ -677,8 +677,9 @@ extern "C" int ccq_grouped_gemm(const ccq_weight* w0, int32_t E, int64_t codes_s
                             hip_stream);
     if (rc != CCQ_ERR_UNSUPPORTED) return rc;
   }
+  const int with_rows = expert_offsets_host ? active : std::min(E, P);   // experts that have rows (without the host copy: at most P)
   if (most_rows <= kGemvMaxM &&
-      (c.n_active > 0 || (int64_t)(E - active) * L.row_tiles <= std::max<int64_t>(64 * (int64_t)device_cus(), (int64_t)active * L.row_tiles / 2))) {
+      (c.n_active > 0 || (int64_t)(E - with_rows) * L.row_tiles <= std::max<int64_t>(64 * (int64_t)device_cus(), (int64_t)with_rows * L.row_tiles / 2))) {
     // one or a few tokens' decode step: every expert that has rows is a GEMV (or a four-row product) of its own.  (Not
     // when the grid would have to span many more experts without rows than with: dispatching their workgroups costs
     // more than it saves.  Letting experts with more rows take one pass over their weights per four rows measured
