@@ -35,6 +35,7 @@ def test_static_entry_matches_gemm_on_two_calls_in_a_row():
     _both(big, wb, 64, 1)      # 64-row kernel, K cut into shares: 1 MiB of partial tiles in the array
     _both(big, wb, 16, 2)      # per-row-tile kernel, smaller input, same array
     _both(small, wsm, 8, 3)    # another matrix and format, smaller again
+    _both(big, wb, 24, 4)      # the 32-row variant of the per-row-tile kernel
     _both(big, wb, 64, 1)      # and the first call again, after the others have left their partials behind
 
 
