@@ -705,13 +705,25 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
     float* lds_c = reinterpret_cast<float*>(region + NGW * 12 * 16);
     {
       float sum = 0.f;
+      u32x4 o[3];
 #pragma unroll
       for (int t = 0; t < 3; ++t) {
-        const u32x4 o = kind_frag<H16>(xc[t], skq, t);
-        sum += frag_sum(o);
-        if (lane < (uint32_t)(4 * NGW)) lds_x[(slg * 3u + t) * 4u + skq] = o;
+        o[t] = kind_frag<H16>(xc[t], skq, t);
+        sum += frag_sum(o[t]);
       }
-      if (lane < (uint32_t)(4 * NGW)) lds_c[(slg * 4u + skq) * 4u] = a.cneg_w * sum;
+      if (lane < (uint32_t)(4 * NGW)) {
+        if constexpr (H16) {
+#pragma unroll
+          for (int t = 0; t < 3; ++t) lds_x[(slg * 3u + t) * 4u + skq] = o[t];
+        } else {
+          // the wide format fills three of the four registers of a k-step: the nine registers of a (group, quarter) are
+          // stored back to back, so that the contraction is five MFMA 4x4x4 (the last with one empty register) instead of six
+          lds_x[(slg * 3u + 0u) * 4u + skq] = u32x4{o[0].x, o[0].y, o[0].z, o[1].x};
+          lds_x[(slg * 3u + 1u) * 4u + skq] = u32x4{o[1].y, o[1].z, o[2].x, o[2].y};
+          *reinterpret_cast<u32x2*>(&lds_x[(slg * 3u + 2u) * 4u + skq]) = u32x2{o[2].z, 0u};
+        }
+        lds_c[(slg * 4u + skq) * 4u] = a.cneg_w * sum;
+      }
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -731,12 +743,26 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
       for (int j = 0; j < 8; ++j) {
         const int lg = i * 8 + j;
         f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+        if constexpr (H16) {
 #pragma unroll
-        for (int t = 0; t < 3; ++t) {
-          const u32x4 xf = lds_x[(lg * 3 + t) * 4 + kq];
-          const u32x4 wv = kind_weights<H16>(cw[i][t], j, mask_w, c4300);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.x, xf.y}), __builtin_bit_cast(bf16x4, u32x2{wv.x, wv.y}), p, 0, 0, 0);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.z, xf.w}), __builtin_bit_cast(bf16x4, u32x2{wv.z, wv.w}), p, 0, 0, 0);
+          for (int t = 0; t < 3; ++t) {
+            const u32x4 xf = lds_x[(lg * 3 + t) * 4 + kq];
+            const u32x4 wv = kind_weights<H16>(cw[i][t], j, mask_w, c4300);
+            p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.x, xf.y}), __builtin_bit_cast(bf16x4, u32x2{wv.x, wv.y}), p, 0, 0, 0);
+            p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.z, xf.w}), __builtin_bit_cast(bf16x4, u32x2{wv.z, wv.w}), p, 0, 0, 0);
+          }
+        } else {
+          const u32x4 xa = lds_x[(lg * 3 + 0) * 4 + kq];
+          const u32x4 xb = lds_x[(lg * 3 + 1) * 4 + kq];
+          const u32x2 xc2 = *reinterpret_cast<const u32x2*>(&lds_x[(lg * 3 + 2) * 4 + kq]);
+          const u32x4 w0 = kind_weights<H16>(cw[i][0], j, mask_w, c4300);
+          const u32x4 w1 = kind_weights<H16>(cw[i][1], j, mask_w, c4300);
+          const u32x4 w2 = kind_weights<H16>(cw[i][2], j, mask_w, c4300);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xa.x, xa.y}), __builtin_bit_cast(bf16x4, u32x2{w0.x, w0.y}), p, 0, 0, 0);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xa.z, xa.w}), __builtin_bit_cast(bf16x4, u32x2{w0.z, w1.x}), p, 0, 0, 0);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xb.x, xb.y}), __builtin_bit_cast(bf16x4, u32x2{w1.y, w1.z}), p, 0, 0, 0);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xb.z, xb.w}), __builtin_bit_cast(bf16x4, u32x2{w2.x, w2.y}), p, 0, 0, 0);
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, xc2), __builtin_bit_cast(bf16x4, u32x2{w2.z, w2.z}), p, 0, 0, 0);   // second register: zero activations
         }
         float s;
         if constexpr (SM == 0) {
