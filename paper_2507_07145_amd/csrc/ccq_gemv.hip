@@ -562,7 +562,7 @@ __device__ __forceinline__ u32x4 kind_weights(const u32x4 seg, int j, uint32_t m
     wv.x = and_or(pp >> 4, mask, c4300);
     wv.y = and_or(pp >> 2, mask, c4300);
     wv.z = and_or(pp, mask, c4300);
-    wv.w = wv.z;                          // unused k-slots: zero activations
+    wv.w = pp;                            // unused k-slots (zero activations): any finite value; pp's halves are bf16 numbers below 2^-126, and it is already in a register
   }
   return wv;
 }
@@ -762,7 +762,7 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
           p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xa.z, xa.w}), __builtin_bit_cast(bf16x4, u32x2{w0.z, w1.x}), p, 0, 0, 0);
           p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xb.x, xb.y}), __builtin_bit_cast(bf16x4, u32x2{w1.y, w1.z}), p, 0, 0, 0);
           p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xb.z, xb.w}), __builtin_bit_cast(bf16x4, u32x2{w2.x, w2.y}), p, 0, 0, 0);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, xc2), __builtin_bit_cast(bf16x4, u32x2{w2.z, w2.z}), p, 0, 0, 0);   // second register: zero activations
+          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, xc2), __builtin_bit_cast(bf16x4, u32x2{w2.z, w2.w}), p, 0, 0, 0);   // second register: zero activations
         }
         float s;
         if constexpr (SM == 0) {
