@@ -263,6 +263,19 @@ def ceilings_leg(dev, nbytes_config2):
                       "frac_of_hbm_peak": round(n / us / 1e3 / HBM_PEAK_GBS, 4)})
     best = min(reads, key=lambda r: r["us_per_launch"])
     del bufs
+    # the same read over the bytes of one launch of config 3 (all wide, M = 1) and of config 4 (one projection)
+    larger = []
+    for label, nb in (("config3_all_wide_bytes", 88154112), ("config4_up_projection_bytes", 268304384)):
+        nb = nb // 16 * 16
+        copies = 8 if nb < (128 << 20) else 3
+        bl = [torch.randint(0, 256, (nb,), dtype=torch.uint8, device=dev) for _ in range(copies)]
+        fns = [(lambda s=s: b.probe_stream_read(s, sink, 2, 256)) for s in bl]
+        steps = copies * 40
+        t = time_steps(fns, steps, copies, dev, target_launches=steps)
+        us = t["event_s"] / steps * 1e6
+        larger.append({"what": label, "bytes_per_launch": nb, "loads_per_thread": 2, "block_threads": 256, "us_per_launch": round(us, 2),
+                       "GBps": round(nb / us / 1e3, 1), "frac_of_hbm_peak": round(nb / us / 1e3 / HBM_PEAK_GBS, 4)})
+        del bl
     big = [torch.randint(0, 256, (1 << 30,), dtype=torch.uint8, device=dev) for _ in range(2)]
     fns = [(lambda s=s: b.probe_stream_read(s, sink, 8, 256)) for s in big]
     t = time_steps(fns, 40, 2, dev, target_launches=40)
@@ -281,6 +294,7 @@ def ceilings_leg(dev, nbytes_config2):
         mf.append({"workgroups": wgs, "wavefronts_per_simd": wgs // 256, "ms_per_launch": round(sec * 1e3, 4), "TFLOPs": round(flop / sec / 1e12, 1),
                    "frac_of_mfma_peak": round(flop / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)})
     return {"stream_read_config2_bytes": {"bytes_per_launch": n, "variants": reads, "best": best},
+            "stream_read_larger_launches": larger,
             "stream_read_1GiB": {"us_per_launch": round(us_big, 1), "GBps": round((1 << 30) / us_big / 1e3, 1),
                                  "frac_of_hbm_peak": round((1 << 30) / us_big / 1e3 / HBM_PEAK_GBS, 4)},
             "mfma_bf16_32x32x16_loop": mf}
