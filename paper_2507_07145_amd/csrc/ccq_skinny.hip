@@ -284,7 +284,7 @@ __device__ __forceinline__ bf16x8 decode_frag(const TileRegs<KIND>& r, int j, in
     o.x = and_or(p >> 4, mask, c4300);
     o.y = and_or(p >> 2, mask, c4300);
     o.z = and_or(p, mask, c4300);
-    o.w = c4300;  // unused k-slots (their activations are staged as zero)
+    o.w = p;      // unused k-slots (their activations are staged as zero): any finite pair; p is already in a register (bf16 values below 2^-126)
   }
   return __builtin_bit_cast(bf16x8, o);
 }
