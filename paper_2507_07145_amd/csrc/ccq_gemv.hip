@@ -16,10 +16,14 @@
 //     the rounding of Eq. 1 and the code sits in the low mantissa bits); two codes are put side by side in one register
 //     and each of the four windows of Table 1 (shifts 9, 6, 3, 0, mask 0x3F) is cut out of both with one shift and one
 //     and-or into the mantissa of bf16 128.0: the operand is the bf16 integer 128 + state, exactly;
-//   * contraction: MFMA 4x4x4 bf16 (lane l feeds its own 4 weights as one column of its 4x4 block, the activations are
-//     the same fragment for the whole block); the accumulator of a (group, quarter) starts at -(128 + zp) sum x, so the
-//     group's result is sum (state - zp) x, which is multiplied by the group scale afterwards: the linear map
-//     (w_uint - zp) * s of Alg. 3 applied after the contraction.
+//   * contraction: MFMA 16x16x32 bf16, two per group: lane l = (row n, quarter kq) feeds the eight weights of its quarter
+//     as column n of the B operand, and every one of the sixteen rows of the A operand is the one activation row (lane
+//     (m, kq) supplies the fragment of quarter kq whatever m is: an LDS broadcast), so every lane receives the whole
+//     group's product for its column, the four quarters already added; the accumulator of a group starts at
+//     -(128 + zp) sum x, so the group's result is sum (state - zp) x, which is multiplied by the group scale afterwards:
+//     the linear map (w_uint - zp) * s of Alg. 3 applied after the contraction.  (The first version used four MFMA
+//     4x4x4 per group, each lane multiplying its own 16 weights, and two cross-lane adds at the end: twice the matrix
+//     instructions; 8192 x 8192: 6.86 -> 6.65 us, 7.56 -> 7.10 us on a slower box.)
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -38,6 +42,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
 struct Args {          // 72 bytes: two scalar loads, issued together
   const uint8_t* codes;
@@ -70,6 +75,14 @@ __device__ __forceinline__ float frag_sum(const u32x4 o) {
   s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, o1), ones, s, false);
   s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, o2), ones, s, false);
   s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, o3), ones, s, false);
+  return s;
+}
+
+// Sum over eight neighbouring lanes (an aligned group of eight), the same in all of them.
+__device__ __forceinline__ float group_sum8(float s) {
+  s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  s += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s), 0x141, 0xF, 0xF, true));  // row_half_mirror: lane 7 - l of its eight
   return s;
 }
 
@@ -171,11 +184,13 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
     o.y = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x07060302u);
     o.z = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x05040100u);
     o.w = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x07060302u);
-    float s = frag_sum(o);
-    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x104, 0xF, 0xF, true));  // + the other k-step, 4 lanes up
+    const float s = group_sum8(frag_sum(o));   // the eight fragments of a group sit in eight neighbouring lanes
     if (NG * 8 % 64 == 0 || f < (uint32_t)(NG * 8)) {
       lds_x[f] = o;
-      if ((f & 4u) == 0) lds_c[((f >> 3) * 4u + (f & 3u)) * 4u] = a.cneg * s;
+      if ((f & 7u) == 0) {
+        const float c = a.cneg * s;
+        *reinterpret_cast<f32x4*>(lds_c + (f >> 3) * 4u) = f32x4{c, c, c, c};
+      }
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -198,17 +213,15 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
       const int lg = i * 4 + j;
       const u32x4 x0 = lds_x[(lg * 2 + 0) * 4 + kq];
       const u32x4 x1 = lds_x[(lg * 2 + 1) * 4 + kq];
-      const f32x4 cin = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+      const f32x4 cin = *reinterpret_cast<const f32x4*>(lds_c + lg * 4);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         u32x4 w[2];
         const uint32_t d = j == 0 ? cw[rt][i].x : (j == 1 ? cw[rt][i].y : (j == 2 ? cw[rt][i].z : cw[rt][i].w));
         decode_dword(d, al[rt], be[rt], c4300, mask, w);
         f32x4 p = cin;
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.x, x0.y}), __builtin_bit_cast(bf16x4, u32x2{w[0].x, w[0].y}), p, 0, 0, 0);
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.z, x0.w}), __builtin_bit_cast(bf16x4, u32x2{w[0].z, w[0].w}), p, 0, 0, 0);
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.x, x1.y}), __builtin_bit_cast(bf16x4, u32x2{w[1].x, w[1].y}), p, 0, 0, 0);
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.z, x1.w}), __builtin_bit_cast(bf16x4, u32x2{w[1].z, w[1].w}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0), __builtin_bit_cast(bf16x8, w[0]), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1), __builtin_bit_cast(bf16x8, w[1]), p, 0, 0, 0);
         float s;
         if constexpr (SM == 0) {
           const uint32_t sd = sw[rt][i][j >> 1];
@@ -220,12 +233,7 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
       }
     }
   }
-  // ---- the four quarters of a row, then the wavefronts of the workgroup (fixed order) ------------------------------
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    acc[rt] += __shfl_xor(acc[rt], 16);
-    acc[rt] += __shfl_xor(acc[rt], 32);
-  }
+  // ---- the wavefronts of the workgroup (fixed order); the matrix core has added the four quarters of a row ---------
   if (nwaves > 1) {
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem);
@@ -261,11 +269,11 @@ __global__ void __launch_bounds__(1024) kernel_unequal(const Args a) {   // the 
 }
 
 // ---- two to four activation rows on narrow-format weights -----------------------------------------------------------
-// The same kernel with MFMA 4x4x4 used as it is meant: lane l of a 4x4 block supplies the activation fragment of row
-// l % 4 (in `kernel` all four lanes supply the same one), so the block's product holds the results of four rows for
-// each of its columns.  The weights are streamed and decoded once for all rows; the cost is four times the activation
-// staging (LDS: 4 x the fragments) and three more scale multiplies per group.  Rows past M repeat row M - 1 and are
-// not stored.
+// The same kernel with four different rows in the A operand: lane (m, kq) supplies the fragment of row m % 4 (in
+// `kernel` all sixteen rows are the same one), so the four accumulator registers of a lane, rows 4 kq .. 4 kq + 3 of its
+// column, are the results of rows 0 .. 3.  The weights are streamed and decoded once for all rows; the cost is four
+// times the activation staging (LDS: 4 x the fragments) and three more scale multiplies per group.  Rows past M
+// repeat row M - 1 and are not stored.
 struct Args4 {
   Args a;
   int64_t ldx, ldy;
@@ -338,10 +346,9 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
     o.y = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x07060302u);
     o.z = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x05040100u);
     o.w = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x07060302u);
-    float s = frag_sum(o);
-    s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x104, 0xF, 0xF, true));  // + the other k-step, 4 lanes up
+    const float s = group_sum8(frag_sum(o));   // the eight fragments of a (group, row) sit in eight neighbouring lanes
     lds_x[f * 4u + r] = o;
-    if ((f & 4u) == 0) lds_c[((f >> 3) * 4u + (f & 3u)) * 4u + r] = a.cneg * s;
+    if ((f & 7u) == 0) lds_c[(f >> 3) * 4u + r] = a.cneg * s;
   }
   __builtin_amdgcn_wave_barrier();
   uint32_t c4300 = 0x43004300u, mask = 0x003F003Fu;
@@ -351,7 +358,7 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
 
   // ---- contraction ------------------------------------------------------------------------------------------------
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  const uint32_t mr = lane & 3u;   // the activation row this lane supplies to its 4x4 block
+  const uint32_t mr = lane & 3u;   // the activation row this lane supplies: rows 4, 5, ... of the 16-row operand repeat rows 0-3
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
     if (RAGGED && t0 + i > t_last) break;   // uniform over the wavefront
@@ -360,14 +367,12 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
       const int lg = i * 4 + j;
       const u32x4 x0 = lds_x[((lg * 2 + 0) * 4 + kq) * 4u + mr];
       const u32x4 x1 = lds_x[((lg * 2 + 1) * 4 + kq) * 4u + mr];
-      f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+      f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + lg * 4);
       u32x4 w[2];
       const uint32_t d = j == 0 ? cw[i].x : (j == 1 ? cw[i].y : (j == 2 ? cw[i].z : cw[i].w));
       decode_dword(d, al, be, c4300, mask, w);
-      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.x, x0.y}), __builtin_bit_cast(bf16x4, u32x2{w[0].x, w[0].y}), p, 0, 0, 0);
-      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.z, x0.w}), __builtin_bit_cast(bf16x4, u32x2{w[0].z, w[0].w}), p, 0, 0, 0);
-      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.x, x1.y}), __builtin_bit_cast(bf16x4, u32x2{w[1].x, w[1].y}), p, 0, 0, 0);
-      p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.z, x1.w}), __builtin_bit_cast(bf16x4, u32x2{w[1].z, w[1].w}), p, 0, 0, 0);
+      p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0), __builtin_bit_cast(bf16x8, w[0]), p, 0, 0, 0);
+      p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1), __builtin_bit_cast(bf16x8, w[1]), p, 0, 0, 0);
       float s;
       if constexpr (SM == 0) {
         const uint32_t sd = sw[i][j >> 1];
@@ -379,12 +384,7 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
       for (int r = 0; r < 4; ++r) acc[r] = __builtin_fmaf(s, p[r], acc[r]);
     }
   }
-  // ---- per row: the four quarters, then the wavefronts of the workgroup (fixed order) ------------------------------
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    acc[r] += __shfl_xor(acc[r], 16);
-    acc[r] += __shfl_xor(acc[r], 32);
-  }
+  // ---- the wavefronts of the workgroup (fixed order); the matrix core has added the four quarters of a row ---------
   if (nwaves > 1) {
     __syncthreads();
     f32x4* red = reinterpret_cast<f32x4*>(smem);
@@ -634,11 +634,13 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
       o.y = __builtin_amdgcn_perm(xv[i].z, xv[i].x, 0x07060302u);
       o.z = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x05040100u);
       o.w = __builtin_amdgcn_perm(xv[i].w, xv[i].y, 0x07060302u);
-      float s = frag_sum(o);
-      s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x104, 0xF, 0xF, true));  // + the other k-step, 4 lanes up
+      const float s = group_sum8(frag_sum(o));
       if (NGN * 8 % 64 == 0 || f < (uint32_t)(NGN * 8)) {
         lds_x[f] = o;
-        if ((f & 4u) == 0) lds_c[((f >> 3) * 4u + (f & 3u)) * 4u] = a.cneg_n * s;
+        if ((f & 7u) == 0) {
+          const float c = a.cneg_n * s;
+          *reinterpret_cast<f32x4*>(lds_c + (f >> 3) * 4u) = f32x4{c, c, c, c};
+        }
       }
     }
     __builtin_amdgcn_wave_barrier();
@@ -650,15 +652,13 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
         const int lg = i * 4 + j;
         const u32x4 x0 = lds_x[(lg * 2 + 0) * 4 + kq];
         const u32x4 x1 = lds_x[(lg * 2 + 1) * 4 + kq];
-        const f32x4 cin = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
+        const f32x4 cin = *reinterpret_cast<const f32x4*>(lds_c + lg * 4);
         u32x4 w[2];
         const uint32_t d = j == 0 ? cw[i].x : (j == 1 ? cw[i].y : (j == 2 ? cw[i].z : cw[i].w));
         decode_dword(d, al, be, c4300, mask_n, w);
         f32x4 p = cin;
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.x, x0.y}), __builtin_bit_cast(bf16x4, u32x2{w[0].x, w[0].y}), p, 0, 0, 0);
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x0.z, x0.w}), __builtin_bit_cast(bf16x4, u32x2{w[0].z, w[0].w}), p, 0, 0, 0);
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.x, x1.y}), __builtin_bit_cast(bf16x4, u32x2{w[1].x, w[1].y}), p, 0, 0, 0);
-        p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{x1.z, x1.w}), __builtin_bit_cast(bf16x4, u32x2{w[1].z, w[1].w}), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x0), __builtin_bit_cast(bf16x8, w[0]), p, 0, 0, 0);
+        p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x1), __builtin_bit_cast(bf16x8, w[1]), p, 0, 0, 0);
         float s;
         if constexpr (SM == 0) {
           const uint32_t sd = sw[i][j >> 1];
@@ -711,18 +711,16 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
         o[t] = kind_frag<H16>(xc[t], skq, t);
         sum += frag_sum(o[t]);
       }
+      // the four quarters of a group: neighbouring lanes
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, sum), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, sum), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
       if (lane < (uint32_t)(4 * NGW)) {
-        if constexpr (H16) {
 #pragma unroll
-          for (int t = 0; t < 3; ++t) lds_x[(slg * 3u + t) * 4u + skq] = o[t];
-        } else {
-          // the wide format fills three of the four registers of a k-step: the nine registers of a (group, quarter) are
-          // stored back to back, so that the contraction is five MFMA 4x4x4 (the last with one empty register) instead of six
-          lds_x[(slg * 3u + 0u) * 4u + skq] = u32x4{o[0].x, o[0].y, o[0].z, o[1].x};
-          lds_x[(slg * 3u + 1u) * 4u + skq] = u32x4{o[1].y, o[1].z, o[2].x, o[2].y};
-          *reinterpret_cast<u32x2*>(&lds_x[(slg * 3u + 2u) * 4u + skq]) = u32x2{o[2].z, 0u};
+        for (int t = 0; t < 3; ++t) lds_x[(slg * 3u + t) * 4u + skq] = o[t];
+        if (skq == 0) {
+          const float c = a.cneg_w * sum;
+          *reinterpret_cast<f32x4*>(lds_c + slg * 4u) = f32x4{c, c, c, c};
         }
-        lds_c[(slg * 4u + skq) * 4u] = a.cneg_w * sum;
       }
     }
     __builtin_amdgcn_wave_barrier();
@@ -742,27 +740,12 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int lg = i * 8 + j;
-        f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + (lg * 4 + kq) * 4);
-        if constexpr (H16) {
+        f32x4 p = *reinterpret_cast<const f32x4*>(lds_c + lg * 4);
 #pragma unroll
-          for (int t = 0; t < 3; ++t) {
-            const u32x4 xf = lds_x[(lg * 3 + t) * 4 + kq];
-            const u32x4 wv = kind_weights<H16>(cw[i][t], j, mask_w, c4300);
-            p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.x, xf.y}), __builtin_bit_cast(bf16x4, u32x2{wv.x, wv.y}), p, 0, 0, 0);
-            p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xf.z, xf.w}), __builtin_bit_cast(bf16x4, u32x2{wv.z, wv.w}), p, 0, 0, 0);
-          }
-        } else {
-          const u32x4 xa = lds_x[(lg * 3 + 0) * 4 + kq];
-          const u32x4 xb = lds_x[(lg * 3 + 1) * 4 + kq];
-          const u32x2 xc2 = *reinterpret_cast<const u32x2*>(&lds_x[(lg * 3 + 2) * 4 + kq]);
-          const u32x4 w0 = kind_weights<H16>(cw[i][0], j, mask_w, c4300);
-          const u32x4 w1 = kind_weights<H16>(cw[i][1], j, mask_w, c4300);
-          const u32x4 w2 = kind_weights<H16>(cw[i][2], j, mask_w, c4300);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xa.x, xa.y}), __builtin_bit_cast(bf16x4, u32x2{w0.x, w0.y}), p, 0, 0, 0);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xa.z, xa.w}), __builtin_bit_cast(bf16x4, u32x2{w0.z, w1.x}), p, 0, 0, 0);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xb.x, xb.y}), __builtin_bit_cast(bf16x4, u32x2{w1.y, w1.z}), p, 0, 0, 0);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, u32x2{xb.z, xb.w}), __builtin_bit_cast(bf16x4, u32x2{w2.x, w2.y}), p, 0, 0, 0);
-          p = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(bf16x4, xc2), __builtin_bit_cast(bf16x4, u32x2{w2.z, w2.w}), p, 0, 0, 0);   // second register: zero activations
+        for (int t = 0; t < 3; ++t) {
+          const u32x4 xf = lds_x[(lg * 3 + t) * 4 + kq];
+          const u32x4 wv = kind_weights<H16>(cw[i][t], j, mask_w, c4300);
+          p = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xf), __builtin_bit_cast(bf16x8, wv), p, 0, 0, 0);
         }
         float s;
         if constexpr (SM == 0) {
@@ -777,9 +760,7 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
       }
     }
   }
-  // ---- the four quarters of a row, then the wavefronts of the workgroup (fixed order) ------------------------------
-  acc += __shfl_xor(acc, 16);
-  acc += __shfl_xor(acc, 32);
+  // ---- the wavefronts of the workgroup (fixed order); the matrix core has added the four quarters of a row ---------
   if (nwaves > 1) {
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem);
