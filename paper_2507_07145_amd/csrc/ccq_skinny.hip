@@ -975,11 +975,21 @@ __global__ void __launch_bounds__(256) ccq_reduce_splits_kernel(const float* par
   const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   const int64_t total = (int64_t)rows * Npad;
   if (i >= total) return;
-  const int64_t p = i / Npad, n = i % Npad;
-  if (n >= N) return;
+  // the requests first (every quad below `total` exists, padded columns included); the row and column of the quad are
+  // worked out while they are on their way
   f32x4 v[SMAX];
 #pragma unroll
   for (int s = 0; s < SMAX; ++s) v[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(partial + (int64_t)min(s, S - 1) * total + i));
+  __builtin_amdgcn_sched_barrier(0);
+  int64_t p, n;
+  if (total < ((int64_t)1 << 31)) {
+    p = (uint32_t)i / (uint32_t)Npad;
+    n = (uint32_t)i % (uint32_t)Npad;
+  } else {
+    p = i / Npad;
+    n = i % Npad;
+  }
+  if (n >= N) return;
   f32x4 sum = v[0];
 #pragma unroll
   for (int s = 1; s < SMAX; ++s)
