@@ -151,11 +151,11 @@ __device__ __forceinline__ void rows1_body(const Args& a, const uint32_t rtile0)
       const uint32_t ti = RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i;
       const uint16_t* sb = a.scales + ((size_t)(rtile0 + rt) * (uint32_t)a.tiles + t0) * SH;
       if constexpr (SM == 0) {
-        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u);
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u));
         sw[rt][i][0] = v.x;
         sw[rt][i][1] = v.y;
       } else {
-        sw[rt][i][0] = sb[ti * 16u + n];   // the tile's four 4-bit fields of this row (first line of Alg. 3)
+        sw[rt][i][0] = __builtin_nontemporal_load(sb + ti * 16u + n);   // the tile's four 4-bit fields of this row (first line of Alg. 3)
       }
     }
   }
@@ -320,11 +320,11 @@ __device__ __forceinline__ void rows4_body(const Args& a, const int64_t ldx, con
   for (int i = 0; i < TPW; ++i) {
     const uint32_t ti = RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i;
     if constexpr (SM == 0) {
-      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u);
+      const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u));
       sw[i][0] = v.x;
       sw[i][1] = v.y;
     } else {
-      sw[i][0] = sb[ti * 16u + n];
+      sw[i][0] = __builtin_nontemporal_load(sb + ti * 16u + n);
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -614,11 +614,11 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
     for (int i = 0; i < TPWN; ++i) {
       const uint16_t* sb = scale_row + (size_t)t0 * SH;
       if constexpr (SM == 0) {
-        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u));
         sw[i][0] = v.x;
         sw[i][1] = v.y;
       } else {
-        sw[i][0] = sb[i * 16u + n];
+        sw[i][0] = __builtin_nontemporal_load(sb + i * 16u + n);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -686,7 +686,7 @@ __device__ __forceinline__ void rows1_nw_body(const ArgsNW& a, const uint32_t rt
     const uint16_t* sb = scale_row + (size_t)a.tiles_n * 64u + (size_t)t0 * 128u;   // fp16 scales only: [narrow tiles][wide tiles]
 #pragma unroll
     for (int i = 0; i < TPWW; ++i) {
-      if constexpr (SM == 0) sw[i] = *reinterpret_cast<const u32x4*>(sb + i * 128u + n * 8u);
+      if constexpr (SM == 0) sw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(sb + i * 128u + n * 8u));
       else sw[i] = u32x4{0u, 0u, 0u, 0u};
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -896,11 +896,11 @@ __device__ __forceinline__ void rows16_body(const Args16& a) {
   for (int i = 0; i < TPW; ++i) {
     const uint32_t ti = RAGGED ? min(t0 + i, t_last) - t0 : (uint32_t)i;
     if constexpr (SM == 0) {
-      const u32x2 v = *reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u);
+      const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(sb + ti * 64u + n * 4u));
       sw[i][0] = v.x;
       sw[i][1] = v.y;
     } else {
-      sw[i][0] = sb[ti * 16u + n];
+      sw[i][0] = __builtin_nontemporal_load(sb + ti * 16u + n);
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -1111,11 +1111,11 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
 #pragma unroll
     for (int i = 0; i < TPWN; ++i) {
       if constexpr (SM == 0) {
-        const u32x2 v = *reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u);
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(sb + i * 64u + n * 4u));
         sw[i][0] = v.x;
         sw[i][1] = v.y;
       } else {
-        sw[i][0] = sb[i * 16u + n];
+        sw[i][0] = __builtin_nontemporal_load(sb + i * 16u + n);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -1196,7 +1196,7 @@ __global__ void __launch_bounds__(64 * NW) kernel16_nw(const Args16NW a) {
     const uint16_t* sb = scale_row + (size_t)a.tiles_n * 64u + (size_t)t0 * 128u;   // fp16 scales only
 #pragma unroll
     for (int i = 0; i < TPWW; ++i) {
-      if constexpr (SM == 0) sw[i] = *reinterpret_cast<const u32x4*>(sb + i * 128u + n * 8u);
+      if constexpr (SM == 0) sw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(sb + i * 128u + n * 8u));
       else sw[i] = u32x4{0u, 0u, 0u, 0u};
     }
     __builtin_amdgcn_sched_barrier(0);
